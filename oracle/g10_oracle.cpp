@@ -1,0 +1,490 @@
+// CPU oracle for G10's tensor vitality analysis and smart tensor eviction.
+//
+// TEST INFRASTRUCTURE ONLY.  This file is the slow, single-threaded reference
+// that the GPU library is checked against.  Nothing in the product path may
+// include, link or call it; it shares no code with the GPU library.
+//
+// What it follows (G10, MICRO'23):
+//   * Section 3: a tensor is active while the executing kernel uses it;
+//     an inactive period is an interval in which it is unused but will be
+//     used again.
+//   * Section 4.2 (tensor vitality analysis): global tensors live for the
+//     whole iteration and their last inactive period runs into the next
+//     iteration; intermediate tensors are born at their first use and dead
+//     after their last; period lengths come from profiled kernel times;
+//     eviction / prefetch overheads are size / bandwidth.
+//   * Section 4.3 and Algorithm 1 (smart tensor eviction): repeat { stop if
+//     the pressure never exceeds the capacity; rank all remaining inactive
+//     periods by the over-capacity pressure they would remove; take the best
+//     if its benefit is positive; send it to flash unless the flash channel
+//     is full during the transfer, in which case send it to host memory if
+//     host memory has room; update pressure and traffic }.
+//   * Section 4.4: Algorithm 1 assumes each prefetch starts at the latest
+//     time that still completes before the next use.
+//
+// The paper leaves the discretisation open.  The readings taken here:
+//   * the timeline is divided into kernel slots (instructions can only be
+//     inserted between kernels, Figure 6); two iterations are laid end to end
+//     ("doubled coordinates") so that a weight's period can run into the next;
+//   * an eviction is issued at the start of the period, a prefetch ends at the
+//     next use; memory counts as freed only from the first slot boundary after
+//     the eviction ends to the last slot boundary before the prefetch starts;
+//   * "traffic is full during the transfer" = the channel time not yet
+//     reserved inside the slot-rounded transfer window cannot carry the
+//     transfer; tested for the eviction and for the prefetch;
+//   * benefit = size x time spent over capacity inside the absent window;
+//     ranking by benefit alone, ties to the lowest period index;
+//   * flash full and host memory without room: the candidate is dropped.
+//
+// Two evaluation modes compute the same values:
+//   mode 0 ("direct"):  every sum / max / search is the literal loop of its
+//                       definition over kernel slots.  O(window) per query.
+//   mode 1 ("prefix"):  range sums come from prefix arrays rebuilt from
+//                       scratch at the top of every iteration, window ends
+//                       from binary search, the pressure timeline from a
+//                       difference array.  Same integers, usable on large
+//                       traces.  Tests tie mode 1 to mode 0.
+//
+// All times are integer nanoseconds, sizes integer bytes, bandwidths bytes
+// per microsecond; benefits are 128-bit byte-nanoseconds.
+//
+// Parity status of the readings that the paper does not fix numerically
+// (benefit clipping, benefit-only ranking key, prefetch-side channel test,
+// slot rounding, dropping on flash-full + host-full): parity unpinned — the
+// paper prints no value that separates the alternatives.  Everything else is
+// pinned by the tests under tests/ (worked examples, closed forms,
+// invariants, brute force).
+
+#include <algorithm>
+#include <cstdint>
+#include <cstring>
+#include <new>
+#include <vector>
+
+typedef unsigned __int128 u128;
+typedef uint64_t u64;
+typedef uint32_t u32;
+
+extern "C" {
+
+struct g10o_trace {
+  u32 K, N;
+  u64 P;
+  const u64* dur_ns;      // [K]
+  const u64* size_bytes;  // [N]
+  const uint8_t* is_global;  // [N]
+  const u32* use_kernel;  // [P]
+  const u32* use_tensor;  // [P]
+  u32 no_wrap;            // 1: ignore cross-iteration periods of global tensors
+};
+
+struct g10o_params {
+  u64 gpu_cap, host_cap;
+  u64 bw_out[2], bw_in[2];  // [0] flash, [1] host; bytes per microsecond
+};
+
+struct g10o_record {  // one committed migration, in commit order
+  u32 cand, tensor, evict_after, absent_first, absent_last, next_use;
+  u32 dest, wraps;
+  u64 size, t_out, t_in, benefit_lo, benefit_hi;
+};
+
+struct g10o_summary {
+  int32_t status;  // 0 fits, 1 residual, 2 stopped by max_iters
+  u64 n_migrations, n_iterations, n_null, n_cand_evals;
+  u64 peak_before, peak_after, overtime_before, overtime_after;
+};
+
+}  // extern "C"
+
+namespace {
+
+enum { FLASH = 0, HOST = 1, OUT = 0, IN = 1 };
+
+struct Dest {
+  bool valid;
+  u32 a, b;        // absent slots [a, b], doubled coordinates
+  u64 tau_o, tau_i;
+};
+
+struct Cand {
+  u32 t, L, R;     // tensor, last use before, next use (R may be >= K)
+  u64 s;
+  Dest d[2];
+};
+
+struct Oracle {
+  // trace
+  u32 K = 0, N = 0;
+  std::vector<u64> dur, size;
+  std::vector<uint8_t> glob;
+  // vitality
+  std::vector<u64> use_off;          // [N+1]
+  std::vector<u32> use_k;            // distinct uses, tensor-major
+  std::vector<u32> birth, death;     // [N], meaningful where the tensor is used
+  std::vector<u32> per_t, per_L, per_R;
+  std::vector<u64> start;            // [K+1]
+  std::vector<u64> pressure0;        // [K]
+  u64 peak = 0, T = 0;
+  // plan output
+  std::vector<g10o_record> records;
+  std::vector<u32> null_cands;
+  std::vector<u64> null_iters;       // rank pass (0-based) in which each was dropped
+  std::vector<u64> pressure_after;
+  std::vector<u64> busy_after[2][2];
+  std::vector<u64> host_after;
+};
+
+inline u64 ceil_div(u128 x, u64 y) { return (u64)((x + y - 1) / y); }
+
+// start time of slot j on the doubled timeline, j in [0, 2K]   (two
+// back-to-back iterations that follow the same plan)
+inline u64 start2(const Oracle& o, u64 j) {
+  return j < o.K ? o.start[j] : o.start[j - o.K] + o.T;
+}
+
+// ---------------------------------------------------------------- vitality
+int vitality(Oracle& o, const g10o_trace& tr, int mode) {
+  if (!tr.K || !tr.N || tr.K >= (1u << 31)) return -1;
+  if (!tr.dur_ns || !tr.size_bytes || !tr.is_global) return -1;
+  if (tr.P && (!tr.use_kernel || !tr.use_tensor)) return -1;
+  o.K = tr.K;
+  o.N = tr.N;
+  o.dur.assign(tr.dur_ns, tr.dur_ns + tr.K);
+  o.size.assign(tr.size_bytes, tr.size_bytes + tr.N);
+  o.glob.assign(tr.is_global, tr.is_global + tr.N);
+  for (u64 d : o.dur) if (!d) return -1;
+  for (u64 s : o.size) if (!s) return -1;
+  for (u64 s : o.size) if (((u128)s * 1000) >> 64) return -2;
+  for (u64 p = 0; p < tr.P; ++p)
+    if (tr.use_kernel[p] >= tr.K || tr.use_tensor[p] >= tr.N) return -1;
+
+  // slot start times (Section 4.2: kernel times give the period lengths)
+  o.start.assign(o.K + 1, 0);
+  u128 tt = 0;
+  for (u32 k = 0; k < o.K; ++k) {
+    tt += o.dur[k];
+    if (tt >> 62) return -2;
+    o.start[k + 1] = (u64)tt;
+  }
+  o.T = o.start[o.K];
+
+  // use lists: the distinct kernels touching each tensor, ascending
+  std::vector<std::vector<u32>> uses(o.N);
+  for (u64 p = 0; p < tr.P; ++p) uses[tr.use_tensor[p]].push_back(tr.use_kernel[p]);
+  o.use_off.assign(o.N + 1, 0);
+  o.use_k.clear();
+  o.birth.assign(o.N, 0);
+  o.death.assign(o.N, 0);
+  for (u32 t = 0; t < o.N; ++t) {
+    std::vector<u32>& u = uses[t];
+    std::sort(u.begin(), u.end());
+    u.erase(std::unique(u.begin(), u.end()), u.end());
+    o.use_off[t] = o.use_k.size();
+    o.use_k.insert(o.use_k.end(), u.begin(), u.end());
+    if (!u.empty()) { o.birth[t] = u.front(); o.death[t] = u.back(); }
+  }
+  o.use_off[o.N] = o.use_k.size();
+
+  // inactive periods: gaps of at least one whole kernel between two uses;
+  // for a global tensor also the gap from its last use to its first use in
+  // the next iteration.  Order: tensor, then period start; wrap period last.
+  o.per_t.clear(); o.per_L.clear(); o.per_R.clear();
+  for (u32 t = 0; t < o.N; ++t) {
+    const std::vector<u32>& u = uses[t];
+    for (size_t i = 0; i + 1 < u.size(); ++i)
+      if (u[i + 1] - u[i] >= 2) { o.per_t.push_back(t); o.per_L.push_back(u[i]); o.per_R.push_back(u[i + 1]); }
+    if (o.glob[t] && !tr.no_wrap && !u.empty()) {
+      u64 R = (u64)u.front() + o.K;
+      if (R - u.back() >= 2) { o.per_t.push_back(t); o.per_L.push_back(u.back()); o.per_R.push_back((u32)R); }
+    }
+  }
+
+  // memory pressure: bytes resident in each kernel slot with nothing evicted
+  o.pressure0.assign(o.K, 0);
+  u128 total = 0;
+  for (u32 t = 0; t < o.N; ++t) if (!uses[t].empty()) total += o.size[t];
+  if (total >> 64) return -2;
+  if (mode == 0) {
+    for (u32 t = 0; t < o.N; ++t) {
+      if (uses[t].empty()) continue;
+      u32 lo = o.glob[t] ? 0 : o.birth[t], hi = o.glob[t] ? o.K - 1 : o.death[t];
+      for (u32 k = lo; k <= hi; ++k) o.pressure0[k] += o.size[t];
+    }
+  } else {
+    std::vector<u64> diff(o.K + 1, 0);
+    for (u32 t = 0; t < o.N; ++t) {
+      if (uses[t].empty()) continue;
+      u32 lo = o.glob[t] ? 0 : o.birth[t], hi = o.glob[t] ? o.K - 1 : o.death[t];
+      diff[lo] += o.size[t];
+      diff[hi + 1] -= o.size[t];
+    }
+    u64 run = 0;
+    for (u32 k = 0; k < o.K; ++k) { run += diff[k]; o.pressure0[k] = run; }
+  }
+  o.peak = 0;
+  for (u64 p : o.pressure0) o.peak = std::max(o.peak, p);
+  return 0;
+}
+
+// ---------------------------------------------------------------- planning
+struct Planner {
+  const Oracle& o;
+  const g10o_params& pr;
+  int mode;
+  u32 K;
+  std::vector<Cand> cand;
+  std::vector<uint8_t> live;
+  u64 n_live = 0;
+  std::vector<u64> pressure, host_used;
+  std::vector<u64> busy[2][2];
+  // mode 1 only: prefix arrays, rebuilt at the top of every iteration
+  std::vector<u64> OT;           // over-capacity time before slot k
+  std::vector<u64> FP[2][2];     // free channel time before slot k
+
+  Planner(const Oracle& o_, const g10o_params& p_, int m) : o(o_), pr(p_), mode(m), K(o_.K) {}
+
+  // -- per candidate and destination: transfer times and the absent window
+  void prepare() {
+    size_t C = o.per_t.size();
+    cand.resize(C);
+    for (size_t c = 0; c < C; ++c) {
+      Cand& x = cand[c];
+      x.t = o.per_t[c]; x.L = o.per_L[c]; x.R = o.per_R[c]; x.s = o.size[x.t];
+      for (int d = 0; d < 2; ++d) {
+        Dest& D = x.d[d];
+        D.tau_o = ceil_div((u128)x.s * 1000, pr.bw_out[d]);
+        D.tau_i = ceil_div((u128)x.s * 1000, pr.bw_in[d]);
+        u64 t_r = start2(o, (u64)x.L + 1);           // eviction issued at the period start
+        u64 t_use = start2(o, x.R);                  // tensor needed again here
+        bool has_a = false, has_b = false;
+        u64 a = 0, b = 0;
+        if (mode == 0) {
+          for (u64 j = (u64)x.L + 1; j <= x.R; ++j)
+            if ((u128)start2(o, j) >= (u128)t_r + D.tau_o) { a = j; has_a = true; break; }
+          if (D.tau_i <= t_use)
+            for (u64 j = x.R; j-- > x.L;)              // j = R-1 ... L
+              if (start2(o, j + 1) <= t_use - D.tau_i) { b = j; has_b = true; break; }
+        } else {
+          if ((u128)t_use >= (u128)t_r + D.tau_o) {   // first slot boundary at/after eviction end
+            u64 lo = (u64)x.L + 1, hi = x.R;
+            while (lo < hi) { u64 mid = (lo + hi) / 2; if (start2(o, mid) >= t_r + D.tau_o) hi = mid; else lo = mid + 1; }
+            a = lo; has_a = true;
+          }
+          if (D.tau_i <= t_use && start2(o, (u64)x.L + 1) <= t_use - D.tau_i) {
+            u64 lo = x.L, hi = (u64)x.R - 1;          // last slot whose end is at/before prefetch start
+            while (lo < hi) { u64 mid = (lo + hi + 1) / 2; if (start2(o, mid + 1) <= t_use - D.tau_i) lo = mid; else hi = mid - 1; }
+            b = lo; has_b = true;
+          }
+        }
+        D.valid = has_a && has_b && a <= b;
+        D.a = (u32)a; D.b = (u32)b;
+      }
+    }
+    live.assign(C, 1);
+    n_live = C;
+    pressure = o.pressure0;
+    host_used.assign(K, 0);
+    for (int d = 0; d < 2; ++d) for (int r = 0; r < 2; ++r) busy[d][r].assign(K, 0);
+  }
+
+  bool over(u32 k) const { return pressure[k] > pr.gpu_cap; }
+
+  void rebuild_prefix() {
+    OT.assign(K + 1, 0);
+    for (u32 k = 0; k < K; ++k) OT[k + 1] = OT[k] + (over(k) ? o.dur[k] : 0);
+    for (int d = 0; d < 2; ++d) for (int r = 0; r < 2; ++r) {
+      FP[d][r].assign(K + 1, 0);
+      for (u32 k = 0; k < K; ++k) FP[d][r][k + 1] = FP[d][r][k] + (o.dur[k] - busy[d][r][k]);
+    }
+  }
+  static u64 pref2(const std::vector<u64>& P, u32 K, u64 j) { return j <= K ? P[j] : P[j - K] + P[K]; }
+
+  // sums over doubled-coordinate slot ranges [x, y] (empty if x > y)
+  u64 free_time(int d, int r, u64 x, u64 y) const {
+    if (x > y) return 0;
+    if (mode == 1) return pref2(FP[d][r], K, y + 1) - pref2(FP[d][r], K, x);
+    u64 s = 0;
+    for (u64 j = x; j <= y; ++j) s += o.dur[j % K] - busy[d][r][j % K];
+    return s;
+  }
+  u64 over_time(u64 x, u64 y) const {
+    if (x > y) return 0;
+    if (mode == 1) return pref2(OT, K, y + 1) - pref2(OT, K, x);
+    u64 s = 0;
+    for (u64 j = x; j <= y; ++j) if (over((u32)(j % K))) s += o.dur[j % K];
+    return s;
+  }
+
+  // "is the channel full during the transfer": can the unreserved channel
+  // time inside the slot-rounded transfer windows still carry this tensor
+  bool feasible(const Cand& x, int d) const {
+    const Dest& D = x.d[d];
+    return free_time(d, OUT, (u64)x.L + 1, (u64)D.a - 1) >= D.tau_o &&
+           free_time(d, IN, (u64)D.b + 1, (u64)x.R - 1) >= D.tau_i;
+  }
+
+  // flash first; host only if flash cannot take it; benefit of that choice
+  void score(const Cand& x, int& dest, u128& B) const {
+    dest = -1; B = 0;
+    for (int d = 0; d < 2; ++d) {
+      if (!x.d[d].valid || !feasible(x, d)) continue;
+      dest = d;
+      B = (u128)x.s * over_time(x.d[d].a, x.d[d].b);
+      return;
+    }
+  }
+
+  bool host_has_room(const Cand& x) const {
+    u64 mx = 0;
+    for (u64 j = (u64)x.L + 1; j + 1 <= x.R; ++j) mx = std::max(mx, host_used[j % K]);
+    return x.s <= pr.host_cap && mx <= pr.host_cap - x.s;
+  }
+
+  void commit(const Cand& x, int d) {
+    const Dest& D = x.d[d];
+    for (u64 j = D.a; j <= D.b; ++j) pressure[j % K] -= x.s;
+    u64 rem = D.tau_o;                                  // eviction: earliest free channel time first
+    for (u64 j = (u64)x.L + 1; j < D.a && rem; ++j) {
+      u64 k = j % K, f = o.dur[k] - busy[d][OUT][k], take = std::min(f, rem);
+      busy[d][OUT][k] += take; rem -= take;
+    }
+    rem = D.tau_i;                                      // prefetch: latest free channel time first
+    for (u64 j = x.R; j-- > (u64)D.b + 1 && rem;) {
+      u64 k = j % K, f = o.dur[k] - busy[d][IN][k], take = std::min(f, rem);
+      busy[d][IN][k] += take; rem -= take;
+    }
+    if (d == HOST)
+      for (u64 j = (u64)x.L + 1; j + 1 <= x.R; ++j) host_used[j % K] += x.s;
+  }
+
+  u64 max_pressure() const { u64 m = 0; for (u64 p : pressure) m = std::max(m, p); return m; }
+  u64 total_over_time() const { u64 s = 0; for (u32 k = 0; k < K; ++k) if (over(k)) s += o.dur[k]; return s; }
+};
+
+int plan(Oracle& o, const g10o_params& pr, int mode, u64 max_iters, g10o_summary& S) {
+  std::memset(&S, 0, sizeof S);
+  for (int d = 0; d < 2; ++d) if (!pr.bw_out[d] || !pr.bw_in[d]) return -1;
+  Planner P(o, pr, mode);
+  P.prepare();
+  o.records.clear();
+  o.null_cands.clear();
+  o.null_iters.clear();
+  S.peak_before = P.max_pressure();
+  S.overtime_before = P.total_over_time();
+  const size_t C = P.cand.size();
+  for (;;) {
+    if (P.max_pressure() <= pr.gpu_cap) { S.status = 0; break; }       // fits
+    if (S.n_iterations >= max_iters) { S.status = 2; break; }
+    ++S.n_iterations;
+    S.n_cand_evals += P.n_live;
+    if (mode == 1) P.rebuild_prefix();
+    size_t w = C; int wd = -1; u128 wB = 0;
+    for (size_t c = 0; c < C; ++c) {                                    // rank: best benefit, lowest index
+      if (!P.live[c]) continue;
+      int d; u128 B;
+      P.score(P.cand[c], d, B);
+      if (B > wB) { wB = B; w = c; wd = d; }
+    }
+    if (wB == 0) { S.status = 1; break; }                               // nothing beneficial is left
+    const Cand& x = P.cand[w];
+    P.live[w] = 0; --P.n_live;
+    if (wd == HOST && !P.host_has_room(x)) {
+      ++S.n_null; o.null_cands.push_back((u32)w); o.null_iters.push_back(S.n_iterations - 1);
+      continue;
+    }
+    g10o_record r;
+    std::memset(&r, 0, sizeof r);
+    const Dest& D = x.d[wd];
+    r.cand = (u32)w; r.tensor = x.t; r.evict_after = x.L;
+    r.absent_first = D.a % P.K; r.absent_last = D.b % P.K; r.next_use = x.R % P.K;
+    r.dest = (u32)wd; r.wraps = x.R >= P.K;
+    r.size = x.s; r.t_out = D.tau_o; r.t_in = D.tau_i;
+    r.benefit_lo = (u64)wB; r.benefit_hi = (u64)(wB >> 64);
+    o.records.push_back(r);
+    P.commit(x, wd);
+  }
+  S.n_migrations = o.records.size();
+  S.peak_after = P.max_pressure();
+  S.overtime_after = P.total_over_time();
+  o.pressure_after = P.pressure;
+  o.host_after = P.host_used;
+  for (int d = 0; d < 2; ++d) for (int r = 0; r < 2; ++r) o.busy_after[d][r] = P.busy[d][r];
+  return 0;
+}
+
+template <class T>
+void copy_out(const std::vector<T>& v, void* dst) { if (!v.empty()) std::memcpy(dst, v.data(), v.size() * sizeof(T)); }
+
+}  // namespace
+
+extern "C" {
+
+int g10o_vitality(const g10o_trace* tr, int mode, void** handle) {
+  if (!tr || !handle) return -1;
+  Oracle* o = new (std::nothrow) Oracle();
+  if (!o) return -3;
+  int rc = vitality(*o, *tr, mode);
+  if (rc) { delete o; return rc; }
+  *handle = o;
+  return 0;
+}
+
+// out[0..4] = distinct uses, periods, peak bytes, iteration time, plan records
+void g10o_counts(void* h, u64* out) {
+  Oracle* o = (Oracle*)h;
+  out[0] = o->use_k.size(); out[1] = o->per_t.size(); out[2] = o->peak; out[3] = o->T;
+  out[4] = o->records.size(); out[5] = o->null_cands.size();
+}
+
+// which: 0 use_off 1 use_k 2 birth 3 death 4 per_t 5 per_L 6 per_R 7 start
+//        8 pressure0 9 records 10 pressure_after 11 null_cands 12 host_after
+//        13 null_iters
+//        16 + 2*d + r : busy_after[d][r]
+int g10o_copy(void* h, int which, void* dst) {
+  Oracle* o = (Oracle*)h;
+  switch (which) {
+    case 0: copy_out(o->use_off, dst); break;
+    case 1: copy_out(o->use_k, dst); break;
+    case 2: copy_out(o->birth, dst); break;
+    case 3: copy_out(o->death, dst); break;
+    case 4: copy_out(o->per_t, dst); break;
+    case 5: copy_out(o->per_L, dst); break;
+    case 6: copy_out(o->per_R, dst); break;
+    case 7: copy_out(o->start, dst); break;
+    case 8: copy_out(o->pressure0, dst); break;
+    case 9: copy_out(o->records, dst); break;
+    case 10: copy_out(o->pressure_after, dst); break;
+    case 11: copy_out(o->null_cands, dst); break;
+    case 12: copy_out(o->host_after, dst); break;
+    case 13: copy_out(o->null_iters, dst); break;
+    case 16: case 17: case 18: case 19:
+      copy_out(o->busy_after[(which - 16) / 2][(which - 16) % 2], dst); break;
+    default: return -1;
+  }
+  return 0;
+}
+
+int g10o_plan(void* h, const g10o_params* pr, int mode, u64 max_iters, g10o_summary* out) {
+  if (!h || !pr || !out) return -1;
+  return plan(*(Oracle*)h, *pr, mode, max_iters, *out);
+}
+
+// per candidate and destination: validity and absent window, for window tests
+// out arrays have length C: valid (u8), a, b (u32, doubled coords), tau_o, tau_i
+int g10o_windows(void* h, const g10o_params* pr, int mode, int dest,
+                 uint8_t* valid, u32* a, u32* b, u64* tau_o, u64* tau_i) {
+  if (!h || !pr || dest < 0 || dest > 1) return -1;
+  Oracle& o = *(Oracle*)h;
+  Planner P(o, *pr, mode);
+  P.prepare();
+  for (size_t c = 0; c < P.cand.size(); ++c) {
+    const Dest& D = P.cand[c].d[dest];
+    valid[c] = D.valid; a[c] = D.a; b[c] = D.b; tau_o[c] = D.tau_o; tau_i[c] = D.tau_i;
+  }
+  return 0;
+}
+
+void g10o_free(void* h) { delete (Oracle*)h; }
+
+}  // extern "C"
