@@ -1,0 +1,172 @@
+/* g10.h - C ABI of the MI355X (gfx950) implementation of G10's compile-time
+ * hot path: tensor vitality analysis and smart tensor eviction planning
+ * (G10, MICRO'23, Sections 4.2-4.4 and Algorithm 1).
+ *
+ * A DNN training step's kernel trace goes in; an eviction / prefetch schedule
+ * over GPU memory, host memory and flash comes out.  All work runs in HIP
+ * kernels on the device of the caller's stream; the library never falls back
+ * to the CPU.  Times are integer nanoseconds, sizes integer bytes, bandwidths
+ * bytes per microsecond (6 GB/s = 6000).
+ *
+ * Conventions
+ *   - plain C, no exceptions, no global state; every call returns an int:
+ *     G10_OK or a negative error.  On error output arguments are left
+ *     untouched (handles) or zeroed (result structs).
+ *   - pointers inside g10_trace are DEVICE pointers owned by the caller; the
+ *     library copies what it needs, so they may be freed once g10_vitality
+ *     returns.  Everything a result struct points to is HOST memory owned by
+ *     the handle, valid until the next g10_plan on that handle or
+ *     g10_plan_free.
+ *   - a handle is bound to the device and stream given to g10_vitality and is
+ *     not thread-safe; distinct handles are independent.
+ */
+#ifndef G10_H
+#define G10_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  G10_OK = 0,
+  G10_EINVAL = -1,    /* NULL argument, K = 0, N = 0, K >= 2^31, an index out of range,
+                         a zero duration / size / bandwidth                            */
+  G10_EOVERFLOW = -2, /* sum of durations >= 2^62, sum of used sizes >= 2^64,
+                         or a size * 1000 >= 2^64                                      */
+  G10_ENOMEM = -3,    /* host or device allocation failed                              */
+  G10_EDEVICE = -4    /* a HIP call failed                                             */
+};
+
+enum { G10_FLASH = 0, G10_HOST = 1 };          /* migration destinations               */
+enum { G10_FITS = 0, G10_RESIDUAL = 1, G10_TRUNCATED = 2 };
+
+#define G10_NO_WRAP 1u  /* g10_trace.flags: ignore the cross-iteration inactive
+                           period of global tensors                                    */
+
+/* One training iteration as profiled offline (Section 4.2): kernels in
+ * execution order with their durations, the tensors each kernel touches, tensor
+ * sizes, and which tensors are global (weights: alive across iterations) rather
+ * than intermediate (born at first use, dead after last use).  The (kernel,
+ * tensor) pairs are a COO list in any order; duplicates are legal (Figure 6
+ * passes one tensor twice to a kernel) and collapse. */
+typedef struct {
+  uint32_t K, N;               /* kernels, tensors                                     */
+  uint64_t P;                  /* use pairs (may be 0)                                 */
+  const uint64_t *dur_ns;      /* device [K], each > 0                                 */
+  const uint64_t *size_bytes;  /* device [N], each > 0                                 */
+  const uint8_t *is_global;    /* device [N], 1 = global                               */
+  const uint32_t *use_kernel;  /* device [P], each < K                                 */
+  const uint32_t *use_tensor;  /* device [P], each < N                                 */
+  uint32_t flags;              /* G10_NO_WRAP or 0                                     */
+} g10_trace;
+
+typedef struct {
+  uint64_t n_uses;      /* distinct (tensor, kernel) pairs                             */
+  uint64_t n_periods;   /* inactive periods = eviction candidates                      */
+  uint64_t peak_bytes;  /* maximum of the memory-pressure timeline                     */
+  uint64_t iter_ns;     /* duration of the iteration                                   */
+} g10_vitality_stats;
+
+/* Inputs of Algorithm 1 beyond the periods: the GPU memory capacity, the host
+ * memory that may hold evicted tensors, and the bandwidths from which eviction
+ * and prefetch times are estimated (Section 4.2; Table 2 has asymmetric flash
+ * read / write bandwidth, hence separate directions). */
+typedef struct {
+  uint64_t gpu_cap_bytes;
+  uint64_t host_cap_bytes;
+  uint64_t bw_out_Bpus[2];   /* GPU -> [G10_FLASH, G10_HOST], bytes per microsecond    */
+  uint64_t bw_in_Bpus[2];    /* [G10_FLASH, G10_HOST] -> GPU                           */
+  uint64_t max_iterations;   /* stop after this many ranking passes; 0 = no limit      */
+  uint32_t profile;          /* 1: time every scoring launch with events (slower)      */
+  uint32_t reserved;
+} g10_params;
+
+/* One migration, i.e. one g10_pre_evict / g10_prefetch pair of Section 4.4's
+ * instruction set: evict `tensor` to `dest` right after kernel `evict_after`
+ * finished; its memory is free during kernels absent_first..absent_last
+ * (cyclically when `wraps`); the prefetch must have completed before kernel
+ * `next_use` starts (of the next iteration when `wraps`). */
+typedef struct {
+  uint32_t cand;          /* index of the inactive period (tensor-major, by start)     */
+  uint32_t tensor;
+  uint32_t evict_after;   /* last kernel using the tensor before the period            */
+  uint32_t absent_first;  /* first kernel slot in which the memory is free             */
+  uint32_t absent_last;   /* last such slot; the prefetch is issued after it           */
+  uint32_t next_use;      /* first kernel using the tensor after the period            */
+  uint32_t dest;          /* G10_FLASH or G10_HOST                                     */
+  uint32_t wraps;         /* 1: the period runs into the next iteration                */
+  uint64_t size_bytes;
+  uint64_t t_out_ns;      /* eviction time  = ceil(size * 1000 / bw_out[dest])         */
+  uint64_t t_in_ns;       /* prefetch time  = ceil(size * 1000 / bw_in[dest])          */
+  uint64_t benefit_lo;    /* size x over-capacity time removed, byte*ns, 128 bit       */
+  uint64_t benefit_hi;
+} g10_migration;
+
+/* A candidate that won a ranking pass but was dropped: flash could not carry
+ * it and host memory had no room during its period. */
+typedef struct {
+  uint64_t iteration;     /* 0-based ranking pass                                      */
+  uint32_t cand;
+  uint32_t reserved;
+} g10_dropped;
+
+typedef struct {
+  int32_t status;         /* G10_FITS: pressure <= capacity everywhere; G10_RESIDUAL:
+                             no beneficial candidate left; G10_TRUNCATED: max_iterations */
+  uint64_t n_migrations, n_iterations, n_dropped;
+  uint64_t n_cand_evals;  /* sum over ranking passes of the live candidates            */
+  uint64_t peak_before, peak_after;          /* bytes                                  */
+  uint64_t overtime_before_ns, overtime_after_ns; /* time spent over capacity          */
+  const g10_migration *migrations;           /* host [n_migrations], commit order      */
+  const g10_dropped *dropped;                /* host [n_dropped]                       */
+  const uint64_t *pressure_after;            /* host [K]                               */
+  /* filled when params.profile = 1: the scoring kernel, summed over launches */
+  uint64_t score_launches, score_cands_streamed;
+  double score_ms;
+  double plan_ms;         /* device time of the whole call, events on the stream       */
+} g10_result;
+
+typedef struct g10_plan_s g10_plan_t;   /* opaque: device copy of the analysis + workspaces */
+
+/* Tensor vitality analysis (Section 4.2): per-tensor use lists (sorted,
+ * duplicates dropped), birth / death, inactive periods (gaps of at least one
+ * whole kernel between consecutive uses, plus the cross-iteration gap of
+ * global tensors), and the memory-pressure timeline (bytes resident per
+ * kernel slot) with its peak.  Enqueues on `hip_stream` (a hipStream_t, NULL =
+ * default stream) and synchronises it before returning.
+ * Errors: G10_EINVAL / G10_EOVERFLOW as listed above (array contents are
+ * validated on the device before any other work), G10_ENOMEM, G10_EDEVICE. */
+int g10_vitality(const g10_trace *trace, void *hip_stream, g10_plan_t **out_handle);
+
+/* Counts and peak of a finished analysis. */
+int g10_vitality_info(const g10_plan_t *handle, g10_vitality_stats *out);
+
+/* Copies one analysis array to HOST memory `dst` of `bytes` bytes (must match
+ * the array's size exactly, else G10_EINVAL).  `which`:
+ *   0 use_off  u64[N+1]   CSR offsets into use_k
+ *   1 use_k    u32[n_uses]
+ *   2 per_tensor u32[n_periods]   3 per_L u32[n_periods]   4 per_R u32[n_periods]
+ *     (L = last use before the period, R = next use; R >= K for the
+ *      cross-iteration period: R - K is the kernel of the next iteration)
+ *   5 start    u64[K+1]  start time of every kernel slot
+ *   6 pressure u64[K] */
+int g10_vitality_read(const g10_plan_t *handle, int which, void *dst, uint64_t bytes);
+
+/* Smart tensor eviction (Algorithm 1, Section 4.3) on an analysed trace: the
+ * whole greedy loop - scoring of every live candidate against the pressure
+ * and channel timelines, arg-max with lowest-index tie-break, commit and range
+ * updates - runs on the device.  May be called repeatedly with different
+ * parameters; the analysis is never modified.  Synchronises the stream.
+ * Errors: G10_EINVAL (NULL, zero bandwidth), G10_ENOMEM, G10_EDEVICE.  Not
+ * getting under capacity is not an error: status = G10_RESIDUAL. */
+int g10_plan(g10_plan_t *handle, const g10_params *params, g10_result *out);
+
+/* Frees everything the library allocated for the handle.  NULL is allowed. */
+void g10_plan_free(g10_plan_t *handle);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* G10_H */

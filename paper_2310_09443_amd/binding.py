@@ -1,0 +1,198 @@
+"""Thin ctypes binding over the C ABI of include/g10.h (argument marshalling only).
+
+Every step of the analysis and of the planning loop runs in the HIP library
+`libg10.so`; this module allocates nothing but the small argument structs and
+uses torch only for device buffers and the current stream.  If the library has
+not been built the import of the library fails loudly: there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libg10.so")
+
+OK, EINVAL, EOVERFLOW, ENOMEM, EDEVICE = 0, -1, -2, -3, -4
+FLASH, HOST = 0, 1
+FITS, RESIDUAL, TRUNCATED = 0, 1, 2
+NO_WRAP = 1
+
+EXPORTS = ["g10_vitality", "g10_vitality_info", "g10_vitality_read", "g10_plan", "g10_plan_free"]
+
+MIGRATION = np.dtype([("cand", "<u4"), ("tensor", "<u4"), ("evict_after", "<u4"),
+                      ("absent_first", "<u4"), ("absent_last", "<u4"), ("next_use", "<u4"),
+                      ("dest", "<u4"), ("wraps", "<u4"), ("size", "<u8"), ("t_out", "<u8"),
+                      ("t_in", "<u8"), ("benefit_lo", "<u8"), ("benefit_hi", "<u8")])
+DROPPED = np.dtype([("iteration", "<u8"), ("cand", "<u4"), ("reserved", "<u4")])
+assert MIGRATION.itemsize == 72 and DROPPED.itemsize == 16
+
+
+class G10Error(RuntimeError):
+    def __init__(self, code, what):
+        super().__init__(f"{what} failed with code {code}")
+        self.code = code
+
+
+class _Trace(C.Structure):
+    _fields_ = [("K", C.c_uint32), ("N", C.c_uint32), ("P", C.c_uint64),
+                ("dur_ns", C.c_void_p), ("size_bytes", C.c_void_p), ("is_global", C.c_void_p),
+                ("use_kernel", C.c_void_p), ("use_tensor", C.c_void_p), ("flags", C.c_uint32)]
+
+
+class _Stats(C.Structure):
+    _fields_ = [("n_uses", C.c_uint64), ("n_periods", C.c_uint64), ("peak_bytes", C.c_uint64),
+                ("iter_ns", C.c_uint64)]
+
+
+class _Params(C.Structure):
+    _fields_ = [("gpu_cap_bytes", C.c_uint64), ("host_cap_bytes", C.c_uint64),
+                ("bw_out_Bpus", C.c_uint64 * 2), ("bw_in_Bpus", C.c_uint64 * 2),
+                ("max_iterations", C.c_uint64), ("profile", C.c_uint32), ("reserved", C.c_uint32)]
+
+
+class _Result(C.Structure):
+    _fields_ = [("status", C.c_int32),
+                ("n_migrations", C.c_uint64), ("n_iterations", C.c_uint64), ("n_dropped", C.c_uint64),
+                ("n_cand_evals", C.c_uint64), ("peak_before", C.c_uint64), ("peak_after", C.c_uint64),
+                ("overtime_before_ns", C.c_uint64), ("overtime_after_ns", C.c_uint64),
+                ("migrations", C.c_void_p), ("dropped", C.c_void_p), ("pressure_after", C.c_void_p),
+                ("score_launches", C.c_uint64), ("score_cands_streamed", C.c_uint64),
+                ("score_ms", C.c_double), ("plan_ms", C.c_double)]
+
+
+_lib = None
+
+
+def load():
+    """Loads libg10.so; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2310_09443_amd.build` "
+                              "(hipcc, gfx950); there is no CPU fallback")
+        lib = C.CDLL(LIB_PATH)
+        lib.g10_vitality.argtypes = [C.POINTER(_Trace), C.c_void_p, C.POINTER(C.c_void_p)]
+        lib.g10_vitality_info.argtypes = [C.c_void_p, C.POINTER(_Stats)]
+        lib.g10_vitality_read.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_uint64]
+        lib.g10_plan.argtypes = [C.c_void_p, C.POINTER(_Params), C.POINTER(_Result)]
+        lib.g10_plan_free.argtypes = [C.c_void_p]
+        lib.g10_plan_free.restype = None
+        _lib = lib
+    return _lib
+
+
+class DeviceTrace:
+    """A trace resident in HBM (torch tensors own the memory)."""
+
+    def __init__(self, trace, device="cuda:0"):
+        import torch
+        self.K, self.N, self.P = trace.K, trace.N, trace.P
+        dev = torch.device(device)
+        # torch has no uint64 arithmetic, but these are only buffers: ship the bits as int64 / int32
+        self.dur = torch.from_numpy(trace.dur_ns.view(np.int64)).to(dev)
+        self.size = torch.from_numpy(trace.size_bytes.view(np.int64)).to(dev)
+        self.glob = torch.from_numpy(np.ascontiguousarray(trace.is_global, np.uint8)).to(dev)
+        self.uk = torch.from_numpy(trace.use_kernel.view(np.int32)).to(dev)
+        self.ut = torch.from_numpy(trace.use_tensor.view(np.int32)).to(dev)
+        self.device = dev
+
+
+class Result:
+    def __init__(self, r: _Result, K: int):
+        for f, _ in _Result._fields_:
+            if f not in ("migrations", "dropped", "pressure_after"):
+                setattr(self, f, getattr(r, f))
+        self.records = self._copy(r.migrations, int(r.n_migrations), MIGRATION)
+        self.dropped = self._copy(r.dropped, int(r.n_dropped), DROPPED)
+        self.pressure_after = self._copy(r.pressure_after, K, np.dtype("<u8"))
+        self.null_iters = self.dropped["iteration"].copy()
+        self.null_cands = self.dropped["cand"].copy()
+
+    @staticmethod
+    def _copy(ptr, n, dtype):
+        if not n or not ptr:
+            return np.zeros(0, dtype)
+        buf = (C.c_char * (n * dtype.itemsize)).from_address(ptr)
+        return np.frombuffer(buf, dtype=dtype, count=n).copy()
+
+
+class Handle:
+    """g10_vitality on construction; g10_plan via .plan(); g10_plan_free on close."""
+
+    def __init__(self, dtrace: DeviceTrace, no_wrap: bool = False, stream=None):
+        import torch
+        lib = load()
+        self._h = C.c_void_p()
+        self.K, self.N = dtrace.K, dtrace.N
+        if stream is None:
+            stream = torch.cuda.current_stream(dtrace.device).cuda_stream
+        t = _Trace(dtrace.K, dtrace.N, dtrace.P, dtrace.dur.data_ptr(), dtrace.size.data_ptr(),
+                   dtrace.glob.data_ptr(), dtrace.uk.data_ptr() if dtrace.P else None,
+                   dtrace.ut.data_ptr() if dtrace.P else None, NO_WRAP if no_wrap else 0)
+        with torch.cuda.device(dtrace.device):
+            rc = lib.g10_vitality(C.byref(t), C.c_void_p(stream), C.byref(self._h))
+        if rc:
+            self._h = None
+            raise G10Error(rc, "g10_vitality")
+        s = _Stats()
+        lib.g10_vitality_info(self._h, C.byref(s))
+        self.n_uses, self.C, self.peak, self.T = int(s.n_uses), int(s.n_periods), int(s.peak_bytes), int(s.iter_ns)
+        self._dev = dtrace.device
+
+    def read(self, which: int):
+        n, dt = {0: (self.N + 1, np.uint64), 1: (self.n_uses, np.uint32), 2: (self.C, np.uint32),
+                 3: (self.C, np.uint32), 4: (self.C, np.uint32), 5: (self.K + 1, np.uint64),
+                 6: (self.K, np.uint64)}[which]
+        a = np.zeros(n, dt)
+        rc = load().g10_vitality_read(self._h, which, a.ctypes.data, a.nbytes)
+        if rc:
+            raise G10Error(rc, "g10_vitality_read")
+        return a
+
+    use_off = property(lambda self: self.read(0))
+    use_k = property(lambda self: self.read(1))
+    per_tensor = property(lambda self: self.read(2))
+    per_L = property(lambda self: self.read(3))
+    per_R = property(lambda self: self.read(4))
+    start = property(lambda self: self.read(5))
+    pressure = property(lambda self: self.read(6))
+
+    def plan(self, gpu_cap, host_cap, bw_out, bw_in, max_iters=0, profile=False) -> Result:
+        import torch
+        p = _Params()
+        p.gpu_cap_bytes, p.host_cap_bytes = int(gpu_cap), int(host_cap)
+        p.bw_out_Bpus[0], p.bw_out_Bpus[1] = int(bw_out[0]), int(bw_out[1])
+        p.bw_in_Bpus[0], p.bw_in_Bpus[1] = int(bw_in[0]), int(bw_in[1])
+        p.max_iterations, p.profile = int(max_iters), int(bool(profile))
+        r = _Result()
+        with torch.cuda.device(self._dev):
+            rc = load().g10_plan(self._h, C.byref(p), C.byref(r))
+        if rc:
+            raise G10Error(rc, "g10_plan")
+        return Result(r, self.K)
+
+    def close(self):
+        if self._h:
+            load().g10_plan_free(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def g10_vitality(dtrace: DeviceTrace, no_wrap: bool = False, stream=None) -> Handle:
+    return Handle(dtrace, no_wrap, stream)
+
+
+def g10_plan(handle: Handle, gpu_cap, host_cap, bw_out, bw_in, max_iters=0, profile=False) -> Result:
+    return handle.plan(gpu_cap, host_cap, bw_out, bw_in, max_iters, profile)
+
+
+def g10_plan_free(handle: Handle) -> None:
+    handle.close()

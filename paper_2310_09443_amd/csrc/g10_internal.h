@@ -1,0 +1,141 @@
+// Internal declarations shared by the library's translation units (gfx950).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "g10.h"
+
+typedef uint64_t u64;
+typedef uint32_t u32;
+
+#define G10_WAVE 64
+#define G10_BLOCK 256               // 4 wavefronts per workgroup everywhere
+#define G10_WAVES (G10_BLOCK / G10_WAVE)
+
+#define G10_HIP(call)                                   \
+  do {                                                  \
+    hipError_t e_ = (call);                             \
+    if (e_ != hipSuccess) return g10_hip_fail(e_, __FILE__, __LINE__); \
+  } while (0)
+
+int g10_hip_fail(hipError_t e, const char* file, int line);
+
+// ---------------------------------------------------------------------------
+// wavefront / workgroup primitives (64-wide)
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ u32 lane_id() { return threadIdx.x & (G10_WAVE - 1); }
+__device__ __forceinline__ u32 wave_id() { return threadIdx.x / G10_WAVE; }
+
+template <class T>
+__device__ __forceinline__ T wave_sum(T v) {
+#pragma unroll
+  for (int o = G10_WAVE / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, G10_WAVE);
+  return v;
+}
+
+template <class T>
+__device__ __forceinline__ T wave_max(T v) {
+#pragma unroll
+  for (int o = G10_WAVE / 2; o > 0; o >>= 1) {
+    T w = __shfl_xor(v, o, G10_WAVE);
+    v = w > v ? w : v;
+  }
+  return v;
+}
+
+// inclusive scan inside a wavefront
+template <class T>
+__device__ __forceinline__ T wave_scan_incl(T v) {
+  const u32 l = lane_id();
+#pragma unroll
+  for (int o = 1; o < G10_WAVE; o <<= 1) {
+    T w = __shfl_up(v, o, G10_WAVE);
+    if (l >= (u32)o) v += w;
+  }
+  return v;
+}
+
+// Exclusive scan over the workgroup; `total` receives the sum on every thread.
+// `tmp` is LDS of G10_WAVES + 1 elements.  Contains two barriers.
+template <class T>
+__device__ __forceinline__ T block_scan_excl(T v, T* tmp, T& total) {
+  T inc = wave_scan_incl(v);
+  if (lane_id() == G10_WAVE - 1) tmp[wave_id()] = inc;
+  __syncthreads();
+  T base = 0, tot = 0;
+#pragma unroll
+  for (u32 w = 0; w < G10_WAVES; ++w) {
+    T x = tmp[w];
+    if (w < wave_id()) base += x;
+    tot += x;
+  }
+  __syncthreads();
+  total = tot;
+  return base + inc - v;
+}
+
+template <class T>
+__device__ __forceinline__ T block_sum(T v, T* tmp) {
+  v = wave_sum(v);
+  if (lane_id() == 0) tmp[wave_id()] = v;
+  __syncthreads();
+  T tot = 0;
+#pragma unroll
+  for (u32 w = 0; w < G10_WAVES; ++w) tot += tmp[w];
+  __syncthreads();
+  return tot;
+}
+
+template <class T>
+__device__ __forceinline__ T block_max(T v, T* tmp) {
+  v = wave_max(v);
+  if (lane_id() == 0) tmp[wave_id()] = v;
+  __syncthreads();
+  T m = tmp[0];
+#pragma unroll
+  for (u32 w = 1; w < G10_WAVES; ++w) m = tmp[w] > m ? tmp[w] : m;
+  __syncthreads();
+  return m;
+}
+
+// ---------------------------------------------------------------------------
+// device-wide exclusive scan: out[i] = sum of in[0..i), i in [0, n]; out has
+// n + 1 elements (out[n] = total).  in == out is allowed.  `scratch` must
+// hold scan_scratch_elems(n) elements of T.
+// ---------------------------------------------------------------------------
+size_t scan_scratch_elems(u64 n);
+int scan_excl_u32(const u32* in, u32* out, u64 n, u32* scratch, hipStream_t s);
+int scan_excl_u64(const u64* in, u64* out, u64 n, u64* scratch, hipStream_t s);
+
+// ---------------------------------------------------------------------------
+// handle
+// ---------------------------------------------------------------------------
+struct PlanWork;   // planning workspaces, defined in g10_plan.hip
+
+struct g10_plan_s {
+  int device = 0;
+  hipStream_t stream = nullptr;
+  u32 K = 0, N = 0, flags = 0;
+  u64 P = 0;
+  u32 kbits = 0;                 // bits of the kernel index inside a sort key
+  // counts known after the analysis
+  u64 n_uses = 0, n_periods = 0, peak = 0, T = 0;
+  // device arrays (owned)
+  u64* dur = nullptr;            // [K]
+  u64* size = nullptr;           // [N]
+  uint8_t* glob = nullptr;       // [N]
+  u64* start = nullptr;          // [K+1]
+  u64* ukeys = nullptr;          // [n_uses] sorted distinct (tensor << kbits | kernel)
+  u64* use_off = nullptr;        // [N+1]
+  u32* use_k = nullptr;          // [n_uses]
+  u32* per_t = nullptr;          // [n_periods]
+  u32* per_L = nullptr;
+  u32* per_R = nullptr;
+  u64* pressure_buf = nullptr;   // [K+1]; pressure = pressure_buf + 1
+  PlanWork* work = nullptr;
+};
+
+int vitality_run(g10_plan_s* h, const g10_trace* tr);
+int plan_run(g10_plan_s* h, const g10_params* p, g10_result* out);
+void plan_work_free(PlanWork* w);

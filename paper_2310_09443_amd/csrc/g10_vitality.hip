@@ -1,0 +1,510 @@
+// Tensor vitality analysis on the device (G10, Section 4.2).
+//
+//   pairs (kernel, tensor)  --pack-->  64-bit keys (tensor << kbits | kernel)
+//     --LSD radix sort, 8-bit digits, only the significant digits-->
+//     --adjacent compare + scan-->  distinct keys = per-tensor use lists
+//     --adjacent difference-->      inactive periods (gap of >= 1 whole kernel),
+//                                   plus the cross-iteration period of globals
+//   lifetimes --interval add into a difference array + scan--> pressure[K]
+//     --wavefront-shuffle max--> peak
+//
+// Everything is integer work bound by memory traffic; no matrix cores.
+
+#include "g10_internal.h"
+
+#include <stdio.h>
+#include <stdlib.h>
+
+namespace {
+
+constexpr int ITEMS = 8;                        // elements per thread in tiled kernels
+constexpr int TILE = G10_BLOCK * ITEMS;         // 2048
+
+// ===========================================================================
+// device-wide exclusive scan
+// ===========================================================================
+template <class T>
+__global__ __launch_bounds__(G10_BLOCK) void k_scan_tiles(const T* __restrict__ in, T* out, u64 n, T* sums) {
+  __shared__ T tmp[G10_WAVES + 1];
+  const u64 base = (u64)blockIdx.x * TILE + (u64)threadIdx.x * ITEMS;
+  T v[ITEMS];
+  T acc = 0;
+#pragma unroll
+  for (int i = 0; i < ITEMS; ++i) {
+    v[i] = base + i < n ? in[base + i] : (T)0;
+    acc += v[i];
+  }
+  T total;
+  T run = block_scan_excl(acc, tmp, total);
+#pragma unroll
+  for (int i = 0; i < ITEMS; ++i) {
+    if (base + i < n) out[base + i] = run;
+    run += v[i];
+  }
+  if (threadIdx.x == 0) {
+    if (sums) sums[blockIdx.x] = total;
+    else out[n] = total;                        // single tile: finished
+  }
+}
+
+template <class T>
+__global__ __launch_bounds__(G10_BLOCK) void k_scan_add(T* out, u64 n, const T* __restrict__ sums, u32 nb) {
+  const T add = sums[blockIdx.x];
+  const u64 base = (u64)blockIdx.x * TILE + (u64)threadIdx.x * ITEMS;
+#pragma unroll
+  for (int i = 0; i < ITEMS; ++i)
+    if (base + i < n) out[base + i] += add;
+  if (blockIdx.x == 0 && threadIdx.x == 0) out[n] = sums[nb];
+}
+
+template <class T>
+int scan_excl(const T* in, T* out, u64 n, T* scratch, hipStream_t s) {
+  if (n == 0) {                                  // out[0] = 0
+    G10_HIP(hipMemsetAsync(out, 0, sizeof(T), s));
+    return G10_OK;
+  }
+  const u64 nb = (n + TILE - 1) / TILE;
+  if (nb == 1) {
+    hipLaunchKernelGGL(k_scan_tiles<T>, dim3(1), dim3(G10_BLOCK), 0, s, in, out, n, (T*)nullptr);
+    G10_HIP(hipGetLastError());
+    return G10_OK;
+  }
+  hipLaunchKernelGGL(k_scan_tiles<T>, dim3((u32)nb), dim3(G10_BLOCK), 0, s, in, out, n, scratch);
+  G10_HIP(hipGetLastError());
+  int rc = scan_excl<T>(scratch, scratch, nb, scratch + nb + 1, s);
+  if (rc) return rc;
+  hipLaunchKernelGGL(k_scan_add<T>, dim3((u32)nb), dim3(G10_BLOCK), 0, s, out, n, scratch, (u32)nb);
+  G10_HIP(hipGetLastError());
+  return G10_OK;
+}
+
+// ===========================================================================
+// validation of array contents (one pass each, flags + wide sums)
+// ===========================================================================
+struct VitStats {
+  u32 bad_index, zero_dur, zero_size, size_overflow;
+  u64 dur_lo, dur_hi;        // sum of low / high 32-bit halves of the durations
+  u64 used_lo, used_hi;      // same for the sizes of used tensors
+  u64 n_uses, n_periods, peak;
+};
+
+__global__ __launch_bounds__(G10_BLOCK) void k_check_pairs(const u32* __restrict__ uk, const u32* __restrict__ ut,
+                                                          u64 P, u32 K, u32 N, VitStats* st) {
+  u32 bad = 0;
+  for (u64 i = (u64)blockIdx.x * G10_BLOCK + threadIdx.x; i < P; i += (u64)gridDim.x * G10_BLOCK)
+    bad |= (uk[i] >= K) | (ut[i] >= N);
+  if (__any(bad) && lane_id() == 0) atomicOr(&st->bad_index, 1u);
+}
+
+__global__ __launch_bounds__(G10_BLOCK) void k_check_dur(const u64* __restrict__ dur, u32 K, VitStats* st) {
+  __shared__ u64 tmp[G10_WAVES + 1];
+  u64 lo = 0, hi = 0;
+  u32 zero = 0;
+  for (u64 i = (u64)blockIdx.x * G10_BLOCK + threadIdx.x; i < K; i += (u64)gridDim.x * G10_BLOCK) {
+    u64 d = dur[i];
+    zero |= d == 0;
+    lo += d & 0xffffffffull;
+    hi += d >> 32;
+  }
+  lo = block_sum(lo, tmp);
+  hi = block_sum(hi, tmp);
+  if (__any(zero) && lane_id() == 0) atomicOr(&st->zero_dur, 1u);
+  if (threadIdx.x == 0) {
+    atomicAdd((unsigned long long*)&st->dur_lo, (unsigned long long)lo);
+    atomicAdd((unsigned long long*)&st->dur_hi, (unsigned long long)hi);
+  }
+}
+
+__global__ __launch_bounds__(G10_BLOCK) void k_check_size(const u64* __restrict__ size, u32 N, VitStats* st) {
+  u32 zero = 0, ovf = 0;
+  for (u64 i = (u64)blockIdx.x * G10_BLOCK + threadIdx.x; i < N; i += (u64)gridDim.x * G10_BLOCK) {
+    u64 s = size[i];
+    zero |= s == 0;
+    ovf |= s > 0xffffffffffffffffull / 1000ull;
+  }
+  if (__any(zero) && lane_id() == 0) atomicOr(&st->zero_size, 1u);
+  if (__any(ovf) && lane_id() == 0) atomicOr(&st->size_overflow, 1u);
+}
+
+// ===========================================================================
+// use lists: key pack, radix sort, distinct
+// ===========================================================================
+__global__ __launch_bounds__(G10_BLOCK) void k_pack(const u32* __restrict__ uk, const u32* __restrict__ ut, u64 P,
+                                                   u32 kbits, u64* __restrict__ keys) {
+  for (u64 i = (u64)blockIdx.x * G10_BLOCK + threadIdx.x; i < P; i += (u64)gridDim.x * G10_BLOCK)
+    keys[i] = ((u64)ut[i] << kbits) | uk[i];
+}
+
+// Tile layout of the sort kernels: wavefront w of a workgroup owns the
+// contiguous keys [tile + w*512, tile + (w+1)*512); in round r lane l holds key
+// tile + w*512 + r*64 + l.  Key order = (wavefront, round, lane): that is what
+// makes the per-digit ranks stable.
+__device__ __forceinline__ u64 tile_index(u32 r) {
+  return (u64)blockIdx.x * TILE + (u64)wave_id() * (G10_WAVE * ITEMS) + (u64)r * G10_WAVE + lane_id();
+}
+
+__global__ __launch_bounds__(G10_BLOCK) void k_radix_hist(const u64* __restrict__ keys, u64 P, u32 shift,
+                                                         u32* __restrict__ hist, u32 nblocks) {
+  __shared__ u32 cnt[256];
+  cnt[threadIdx.x] = 0;
+  __syncthreads();
+#pragma unroll
+  for (u32 r = 0; r < ITEMS; ++r) {
+    u64 i = tile_index(r);
+    if (i < P) atomicAdd(&cnt[(keys[i] >> shift) & 255u], 1u);
+  }
+  __syncthreads();
+  hist[(u64)threadIdx.x * nblocks + blockIdx.x] = cnt[threadIdx.x];     // digit-major
+}
+
+__global__ __launch_bounds__(G10_BLOCK) void k_radix_scatter(const u64* __restrict__ keys, u64* __restrict__ out,
+                                                            u64 P, u32 shift, const u32* __restrict__ offs,
+                                                            u32 nblocks) {
+  __shared__ u32 cnt[G10_WAVES][256];        // per wavefront: running count per digit
+  __shared__ u32 gbase[256];
+  for (u32 i = threadIdx.x; i < G10_WAVES * 256; i += G10_BLOCK) (&cnt[0][0])[i] = 0;
+  __syncthreads();
+  const u32 w = wave_id(), l = lane_id();
+  const u64 lt = (1ull << l) - 1ull;
+  u64 key[ITEMS];
+  u32 rank[ITEMS];
+#pragma unroll
+  for (u32 r = 0; r < ITEMS; ++r) {
+    const u64 i = tile_index(r);
+    const bool ok = i < P;
+    key[r] = ok ? keys[i] : 0;
+    const u32 dig = (u32)(key[r] >> shift) & 255u;
+    u64 peers = __ballot(ok);
+#pragma unroll
+    for (u32 b = 0; b < 8; ++b) {
+      const u64 m = __ballot((dig >> b) & 1u);
+      peers &= ((dig >> b) & 1u) ? m : ~m;
+    }
+    const u32 before = cnt[w][dig];          // all peers read, then the first one adds
+    rank[r] = before + __popcll(peers & lt);
+    __builtin_amdgcn_wave_barrier();
+    if (ok && (peers & lt) == 0) cnt[w][dig] = before + __popcll(peers);
+    __builtin_amdgcn_wave_barrier();
+  }
+  __syncthreads();
+  {                                           // one thread per digit: offsets of the wavefronts
+    const u32 d = threadIdx.x;
+    u32 run = 0;
+#pragma unroll
+    for (u32 ww = 0; ww < G10_WAVES; ++ww) {
+      u32 c = cnt[ww][d];
+      cnt[ww][d] = run;
+      run += c;
+    }
+    gbase[d] = offs[(u64)d * nblocks + blockIdx.x];
+  }
+  __syncthreads();
+#pragma unroll
+  for (u32 r = 0; r < ITEMS; ++r) {
+    const u64 i = tile_index(r);
+    if (i < P) {
+      const u32 dig = (u32)(key[r] >> shift) & 255u;
+      out[(u64)gbase[dig] + cnt[w][dig] + rank[r]] = key[r];
+    }
+  }
+}
+
+__global__ __launch_bounds__(G10_BLOCK) void k_flag_distinct(const u64* __restrict__ keys, u64 P, u32* __restrict__ flag) {
+  for (u64 i = (u64)blockIdx.x * G10_BLOCK + threadIdx.x; i < P; i += (u64)gridDim.x * G10_BLOCK)
+    flag[i] = (i == 0 || keys[i] != keys[i - 1]) ? 1u : 0u;
+}
+
+__global__ __launch_bounds__(G10_BLOCK) void k_compact_distinct(const u64* __restrict__ keys, u64 P,
+                                                               const u32* __restrict__ pos, u64* __restrict__ ukeys,
+                                                               u32* __restrict__ use_k, u32 kbits) {
+  for (u64 i = (u64)blockIdx.x * G10_BLOCK + threadIdx.x; i < P; i += (u64)gridDim.x * G10_BLOCK)
+    if (pos[i + 1] != pos[i]) {
+      ukeys[pos[i]] = keys[i];
+      use_k[pos[i]] = (u32)(keys[i] & ((1ull << kbits) - 1ull));
+    }
+}
+
+// use_off[t] = first position whose key has tensor >= t  (t in [0, N])
+__global__ __launch_bounds__(G10_BLOCK) void k_use_off(const u64* __restrict__ ukeys, const u32* __restrict__ n_uses_p,
+                                                      u32 N, u32 kbits, u64* __restrict__ use_off) {
+  const u64 n = *n_uses_p;
+  for (u64 t = (u64)blockIdx.x * G10_BLOCK + threadIdx.x; t <= N; t += (u64)gridDim.x * G10_BLOCK) {
+    const u64 want = t << kbits;
+    u64 lo = 0, hi = n;
+    while (lo < hi) {
+      u64 mid = (lo + hi) >> 1;
+      if (ukeys[mid] >= want) hi = mid; else lo = mid + 1;
+    }
+    use_off[t] = lo;
+  }
+}
+
+// ===========================================================================
+// inactive periods: adjacent difference inside each tensor's use list
+// ===========================================================================
+// Position i of the distinct keys ends an in-iteration period when its
+// predecessor is the same tensor at least two kernels earlier; the last use of
+// a global tensor additionally starts the cross-iteration period.
+__device__ __forceinline__ void period_at(const u64* ukeys, const u64* use_off, const uint8_t* glob, u64 i, u32 K,
+                                          u32 kbits, u32 no_wrap, bool& inner, bool& wrap, u32& t, u32& k, u32& kprev,
+                                          u32& kfirst) {
+  const u64 key = ukeys[i];
+  const u64 kmask = (1ull << kbits) - 1ull;
+  t = (u32)(key >> kbits);
+  k = (u32)(key & kmask);
+  const u64 b = use_off[t], e = use_off[t + 1];
+  inner = false;
+  wrap = false;
+  kprev = 0;
+  kfirst = 0;
+  if (i > b) {
+    kprev = (u32)(ukeys[i - 1] & kmask);
+    inner = k - kprev >= 2;
+  }
+  if (i + 1 == e && glob[t] && !no_wrap) {
+    kfirst = (u32)(ukeys[b] & kmask);
+    wrap = (u64)kfirst + K - k >= 2;
+  }
+}
+
+__global__ __launch_bounds__(G10_BLOCK) void k_period_count(const u64* __restrict__ ukeys, const u64* __restrict__ use_off,
+                                                           const uint8_t* __restrict__ glob, const u32* __restrict__ n_uses_p,
+                                                           u32 K, u32 kbits, u32 no_wrap, u32* __restrict__ cnt) {
+  const u64 n = *n_uses_p;
+  for (u64 i = (u64)blockIdx.x * G10_BLOCK + threadIdx.x; i < n; i += (u64)gridDim.x * G10_BLOCK) {
+    bool inner, wrap;
+    u32 t, k, kp, kf;
+    period_at(ukeys, use_off, glob, i, K, kbits, no_wrap, inner, wrap, t, k, kp, kf);
+    cnt[i] = (u32)inner + (u32)wrap;
+  }
+}
+
+__global__ __launch_bounds__(G10_BLOCK) void k_period_write(const u64* __restrict__ ukeys, const u64* __restrict__ use_off,
+                                                           const uint8_t* __restrict__ glob, const u32* __restrict__ n_uses_p,
+                                                           u32 K, u32 kbits, u32 no_wrap, const u32* __restrict__ pos,
+                                                           u32* __restrict__ per_t, u32* __restrict__ per_L,
+                                                           u32* __restrict__ per_R) {
+  const u64 n = *n_uses_p;
+  for (u64 i = (u64)blockIdx.x * G10_BLOCK + threadIdx.x; i < n; i += (u64)gridDim.x * G10_BLOCK) {
+    bool inner, wrap;
+    u32 t, k, kp, kf;
+    period_at(ukeys, use_off, glob, i, K, kbits, no_wrap, inner, wrap, t, k, kp, kf);
+    u32 o = pos[i];
+    if (inner) { per_t[o] = t; per_L[o] = kp; per_R[o] = k; ++o; }
+    if (wrap) { per_t[o] = t; per_L[o] = k; per_R[o] = kf + K; }
+  }
+}
+
+// ===========================================================================
+// memory pressure: interval adds into a difference array, scan, max
+// ===========================================================================
+__global__ __launch_bounds__(G10_BLOCK) void k_fill_u64(u64* p, u64 n, u64 v) {
+  for (u64 i = (u64)blockIdx.x * G10_BLOCK + threadIdx.x; i < n; i += (u64)gridDim.x * G10_BLOCK) p[i] = v;
+}
+
+__global__ __launch_bounds__(G10_BLOCK) void k_lifetime_adds(const u64* __restrict__ ukeys, const u64* __restrict__ use_off,
+                                                            const u64* __restrict__ size, const uint8_t* __restrict__ glob,
+                                                            u32 N, u32 K, u32 kbits, u64* diff, VitStats* st) {
+  __shared__ u64 tmp[G10_WAVES + 1];
+  const u64 kmask = (1ull << kbits) - 1ull;
+  u64 gsum = 0, lo32 = 0, hi32 = 0;
+  for (u64 t = (u64)blockIdx.x * G10_BLOCK + threadIdx.x; t < N; t += (u64)gridDim.x * G10_BLOCK) {
+    const u64 b = use_off[t], e = use_off[t + 1];
+    if (b == e) continue;                       // never used: ignored everywhere
+    const u64 s = size[t];
+    lo32 += s & 0xffffffffull;
+    hi32 += s >> 32;
+    if (glob[t]) {
+      gsum += s;                                // resident in every slot
+    } else {
+      const u32 birth = (u32)(ukeys[b] & kmask), death = (u32)(ukeys[e - 1] & kmask);
+      atomicAdd((unsigned long long*)&diff[birth], (unsigned long long)s);
+      atomicAdd((unsigned long long*)&diff[death + 1], (unsigned long long)(0ull - s));
+    }
+  }
+  gsum = block_sum(gsum, tmp);
+  lo32 = block_sum(lo32, tmp);
+  hi32 = block_sum(hi32, tmp);
+  if (threadIdx.x == 0) {
+    if (gsum) {
+      atomicAdd((unsigned long long*)&diff[0], (unsigned long long)gsum);
+      atomicAdd((unsigned long long*)&diff[K], (unsigned long long)(0ull - gsum));
+    }
+    atomicAdd((unsigned long long*)&st->used_lo, (unsigned long long)lo32);
+    atomicAdd((unsigned long long*)&st->used_hi, (unsigned long long)hi32);
+  }
+}
+
+__global__ __launch_bounds__(G10_BLOCK) void k_max_u64(const u64* __restrict__ v, u64 n, u64* out) {
+  __shared__ u64 tmp[G10_WAVES + 1];
+  u64 m = 0;
+  for (u64 i = (u64)blockIdx.x * G10_BLOCK + threadIdx.x; i < n; i += (u64)gridDim.x * G10_BLOCK) m = v[i] > m ? v[i] : m;
+  m = block_max(m, tmp);                        // wavefront shuffles, then 4 partials
+  if (threadIdx.x == 0) atomicMax((unsigned long long*)out, (unsigned long long)m);
+}
+
+__global__ void k_store_counts(const u32* n_uses_p, const u32* n_per_p, VitStats* st) {
+  st->n_uses = *n_uses_p;
+  st->n_periods = *n_per_p;
+}
+
+inline u32 grid_for(u64 n, u32 cap = 4096) {
+  u64 g = (n + G10_BLOCK - 1) / G10_BLOCK;
+  return (u32)(g < 1 ? 1 : (g > cap ? cap : g));
+}
+
+inline u32 bits_for(u64 max_value) {            // bits needed to hold values 0..max_value, at least 1
+  u32 b = 1;
+  while (b < 64 && (max_value >> b)) ++b;
+  return b;
+}
+
+struct Tmp {                                    // device temporaries released when the analysis ends
+  void* p[16] = {};
+  int n = 0;
+  ~Tmp() { for (int i = 0; i < n; ++i) (void)hipFree(p[i]); }
+  template <class T>
+  int alloc(T** out, u64 elems) {
+    void* q = nullptr;
+    if (hipMalloc(&q, (elems ? elems : 1) * sizeof(T)) != hipSuccess) { (void)hipGetLastError(); return G10_ENOMEM; }
+    p[n++] = q;
+    *out = (T*)q;
+    return G10_OK;
+  }
+};
+
+template <class T>
+int dev_alloc(T** out, u64 elems) {
+  void* q = nullptr;
+  if (hipMalloc(&q, (elems ? elems : 1) * sizeof(T)) != hipSuccess) { (void)hipGetLastError(); return G10_ENOMEM; }
+  *out = (T*)q;
+  return G10_OK;
+}
+
+}  // namespace
+
+size_t scan_scratch_elems(u64 n) {
+  size_t tot = 0;
+  while (n > (u64)TILE) {
+    n = (n + TILE - 1) / TILE;
+    tot += n + 1;
+  }
+  return tot + 2;
+}
+int scan_excl_u32(const u32* in, u32* out, u64 n, u32* scratch, hipStream_t s) { return scan_excl<u32>(in, out, n, scratch, s); }
+int scan_excl_u64(const u64* in, u64* out, u64 n, u64* scratch, hipStream_t s) { return scan_excl<u64>(in, out, n, scratch, s); }
+
+int g10_hip_fail(hipError_t e, const char* file, int line) {
+  if (getenv("G10_LOG")) fprintf(stderr, "g10: HIP error %d (%s) at %s:%d\n", (int)e, hipGetErrorString(e), file, line);
+  (void)hipGetLastError();
+  return e == hipErrorOutOfMemory ? G10_ENOMEM : G10_EDEVICE;
+}
+
+#define G10_TRY(x) do { int rc_ = (x); if (rc_) return rc_; } while (0)
+
+int vitality_run(g10_plan_s* h, const g10_trace* tr) {
+  hipStream_t s = h->stream;
+  const u32 K = h->K, N = h->N;
+  const u64 P = h->P;
+  if (P >= (1ull << 32)) return G10_EINVAL;      // positions and counts are 32-bit on the device
+  Tmp tmp;
+
+  VitStats* st = nullptr;
+  G10_TRY(tmp.alloc(&st, 1));
+  G10_HIP(hipMemsetAsync(st, 0, sizeof(VitStats), s));
+
+  // own copies of what planning needs later
+  G10_TRY(dev_alloc(&h->dur, K));
+  G10_TRY(dev_alloc(&h->size, N));
+  G10_TRY(dev_alloc(&h->glob, N));
+  G10_HIP(hipMemcpyAsync(h->dur, tr->dur_ns, (u64)K * 8, hipMemcpyDeviceToDevice, s));
+  G10_HIP(hipMemcpyAsync(h->size, tr->size_bytes, (u64)N * 8, hipMemcpyDeviceToDevice, s));
+  G10_HIP(hipMemcpyAsync(h->glob, tr->is_global, (u64)N, hipMemcpyDeviceToDevice, s));
+
+  // ---- validation --------------------------------------------------------
+  if (P) hipLaunchKernelGGL(k_check_pairs, dim3(grid_for(P)), dim3(G10_BLOCK), 0, s, tr->use_kernel, tr->use_tensor, P, K, N, st);
+  hipLaunchKernelGGL(k_check_dur, dim3(grid_for(K)), dim3(G10_BLOCK), 0, s, h->dur, K, st);
+  hipLaunchKernelGGL(k_check_size, dim3(grid_for(N)), dim3(G10_BLOCK), 0, s, h->size, N, st);
+  G10_HIP(hipGetLastError());
+  VitStats hs;
+  G10_HIP(hipMemcpyAsync(&hs, st, sizeof hs, hipMemcpyDeviceToHost, s));
+  G10_HIP(hipStreamSynchronize(s));
+  if (hs.bad_index || hs.zero_dur || hs.zero_size) return G10_EINVAL;
+  if (hs.size_overflow) return G10_EOVERFLOW;
+  {
+    unsigned __int128 T = ((unsigned __int128)hs.dur_hi << 32) + hs.dur_lo;
+    if (T >> 62) return G10_EOVERFLOW;
+    h->T = (u64)T;
+  }
+
+  // ---- slot start times ----------------------------------------------------
+  u64* scratch64 = nullptr;
+  G10_TRY(tmp.alloc(&scratch64, scan_scratch_elems(K > N ? K : N)));
+  G10_TRY(dev_alloc(&h->start, (u64)K + 1));
+  G10_TRY(scan_excl_u64(h->dur, h->start, K, scratch64, s));
+
+  // ---- use lists -------------------------------------------------------------
+  h->kbits = bits_for(K - 1);
+  const u32 tbits = bits_for(N - 1);
+  u64 *keys = nullptr, *alt = nullptr;
+  u32 *flag = nullptr, *scratch32 = nullptr, *hist = nullptr;
+  const u32 nb = (u32)((P + TILE - 1) / TILE);
+  G10_TRY(tmp.alloc(&keys, P));
+  G10_TRY(tmp.alloc(&alt, P));
+  G10_TRY(tmp.alloc(&flag, P + 1));
+  G10_TRY(tmp.alloc(&hist, (u64)256 * (nb ? nb : 1) + 1));
+  G10_TRY(tmp.alloc(&scratch32, scan_scratch_elems((u64)256 * (nb ? nb : 1) > P ? (u64)256 * (nb ? nb : 1) : P)));
+  if (P) {
+    hipLaunchKernelGGL(k_pack, dim3(grid_for(P)), dim3(G10_BLOCK), 0, s, tr->use_kernel, tr->use_tensor, P, h->kbits, keys);
+    for (u32 shift = 0; shift < h->kbits + tbits; shift += 8) {
+      hipLaunchKernelGGL(k_radix_hist, dim3(nb), dim3(G10_BLOCK), 0, s, keys, P, shift, hist, nb);
+      G10_TRY(scan_excl_u32(hist, hist, (u64)256 * nb, scratch32, s));
+      hipLaunchKernelGGL(k_radix_scatter, dim3(nb), dim3(G10_BLOCK), 0, s, keys, alt, P, shift, hist, nb);
+      u64* t = keys; keys = alt; alt = t;
+    }
+    hipLaunchKernelGGL(k_flag_distinct, dim3(grid_for(P)), dim3(G10_BLOCK), 0, s, keys, P, flag);
+    G10_HIP(hipGetLastError());
+  }
+  G10_TRY(scan_excl_u32(flag, flag, P, scratch32, s));           // flag[i] = position, flag[P] = n_uses
+  const u32* n_uses_p = flag + P;
+  G10_TRY(dev_alloc(&h->ukeys, P));                               // upper bounds: no host round trip here
+  G10_TRY(dev_alloc(&h->use_k, P));
+  G10_TRY(dev_alloc(&h->use_off, (u64)N + 1));
+  if (P) hipLaunchKernelGGL(k_compact_distinct, dim3(grid_for(P)), dim3(G10_BLOCK), 0, s, keys, P, flag, h->ukeys, h->use_k, h->kbits);
+  hipLaunchKernelGGL(k_use_off, dim3(grid_for((u64)N + 1)), dim3(G10_BLOCK), 0, s, h->ukeys, n_uses_p, N, h->kbits, h->use_off);
+  G10_HIP(hipGetLastError());
+
+  // ---- inactive periods --------------------------------------------------------
+  u32* pcnt = nullptr;
+  G10_TRY(tmp.alloc(&pcnt, P + 1));
+  const u32 no_wrap = (h->flags & G10_NO_WRAP) ? 1u : 0u;
+  G10_HIP(hipMemsetAsync(pcnt, 0, (P + 1) * sizeof(u32), s));
+  if (P) hipLaunchKernelGGL(k_period_count, dim3(grid_for(P)), dim3(G10_BLOCK), 0, s, h->ukeys, h->use_off, h->glob, n_uses_p, K, h->kbits, no_wrap, pcnt);
+  G10_TRY(scan_excl_u32(pcnt, pcnt, P, scratch32, s));           // pcnt[P] = n_periods (entries past n_uses are 0)
+  G10_TRY(dev_alloc(&h->per_t, P));
+  G10_TRY(dev_alloc(&h->per_L, P));
+  G10_TRY(dev_alloc(&h->per_R, P));
+  if (P) hipLaunchKernelGGL(k_period_write, dim3(grid_for(P)), dim3(G10_BLOCK), 0, s, h->ukeys, h->use_off, h->glob, n_uses_p, K, h->kbits, no_wrap, pcnt, h->per_t, h->per_L, h->per_R);
+  G10_HIP(hipGetLastError());
+
+  // ---- memory pressure -----------------------------------------------------------
+  G10_TRY(dev_alloc(&h->pressure_buf, (u64)K + 2));
+  hipLaunchKernelGGL(k_fill_u64, dim3(grid_for((u64)K + 2)), dim3(G10_BLOCK), 0, s, h->pressure_buf, (u64)K + 2, 0ull);
+  hipLaunchKernelGGL(k_lifetime_adds, dim3(grid_for(N)), dim3(G10_BLOCK), 0, s, h->ukeys, h->use_off, h->size, h->glob, N, K, h->kbits, h->pressure_buf, st);
+  G10_HIP(hipGetLastError());
+  // exclusive scan of diff[0..K] in place: buf[k + 1] = sum diff[0..k] = pressure[k]
+  G10_TRY(scan_excl_u64(h->pressure_buf, h->pressure_buf, (u64)K, scratch64, s));
+  hipLaunchKernelGGL(k_max_u64, dim3(grid_for(K, 1024)), dim3(G10_BLOCK), 0, s, h->pressure_buf + 1, (u64)K, &st->peak);
+  hipLaunchKernelGGL(k_store_counts, dim3(1), dim3(1), 0, s, n_uses_p, pcnt + P, st);
+  G10_HIP(hipGetLastError());
+  G10_HIP(hipMemcpyAsync(&hs, st, sizeof hs, hipMemcpyDeviceToHost, s));
+  G10_HIP(hipStreamSynchronize(s));
+  {
+    unsigned __int128 used = ((unsigned __int128)hs.used_hi << 32) + hs.used_lo;
+    if (used >> 64) return G10_EOVERFLOW;
+  }
+  h->n_uses = hs.n_uses;
+  h->n_periods = hs.n_periods;
+  h->peak = hs.peak;
+  return G10_OK;
+}

@@ -1,0 +1,49 @@
+"""The C-ABI library loads without a GPU and exports every call the header declares."""
+import ctypes
+import os
+import re
+
+from paper_2310_09443_amd import binding, build
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "g10.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return re.findall(r"^\s*(?:int|void)\s+(g10_\w+)\s*\(", text, flags=re.M)
+
+
+def test_header_declares_the_documented_calls():
+    assert sorted(declared_functions()) == sorted(binding.EXPORTS)
+    for name in ("g10_vitality", "g10_plan", "g10_plan_free"):
+        assert name in declared_functions()
+
+
+def test_library_exports_every_declared_symbol():
+    if not os.path.exists(build.LIB):
+        build.build()
+    lib = ctypes.CDLL(build.LIB)
+    for name in declared_functions():
+        assert hasattr(lib, name), name
+
+
+def test_struct_layouts_match_the_header():
+    # sizes follow from the field lists in the header (natural alignment)
+    assert ctypes.sizeof(binding._Trace) == 64
+    assert ctypes.sizeof(binding._Params) == 64
+    assert ctypes.sizeof(binding._Stats) == 32
+    assert ctypes.sizeof(binding._Result) == 8 + 8 * 8 + 3 * 8 + 2 * 8 + 2 * 8
+    assert binding.MIGRATION.itemsize == 72 and binding.DROPPED.itemsize == 16
+
+
+def test_null_arguments_are_rejected_without_a_gpu():
+    lib = binding.load()
+    assert lib.g10_vitality(None, None, None) == binding.EINVAL
+    assert lib.g10_plan(None, None, None) == binding.EINVAL
+    assert lib.g10_vitality_info(None, None) == binding.EINVAL
+    lib.g10_plan_free(None)
+    t = binding._Trace()                        # K = 0
+    h = ctypes.c_void_p()
+    assert lib.g10_vitality(ctypes.byref(t), None, ctypes.byref(h)) == binding.EINVAL
+    assert not h.value
