@@ -108,6 +108,10 @@ size_t scan_scratch_elems(u64 n);
 int scan_excl_u32(const u32* in, u32* out, u64 n, u32* scratch, hipStream_t s);
 int scan_excl_u64(const u64* in, u64* out, u64 n, u64* scratch, hipStream_t s);
 
+// stable LSD radix sort of the low `bits` bits of 64-bit keys (see g10_vitality.hip)
+size_t radix_hist_elems(u64 n);
+int radix_sort_u64(u64** keys, u64** alt, u64 n, u32 bits, u32* hist, u32* scratch, hipStream_t s);
+
 // ---------------------------------------------------------------------------
 // handle
 // ---------------------------------------------------------------------------

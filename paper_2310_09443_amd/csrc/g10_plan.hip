@@ -1,6 +1,6 @@
 // Smart tensor eviction on the device (G10, Section 4.3, Algorithm 1).
 //
-// State on the device (all u64 unless noted, K = kernel slots):
+// State on the device (u64 unless noted, K = kernel slots):
 //   pressure[K]                 bytes resident per slot
 //   busy[4][K]                  channel time already reserved per slot;
 //                               channel = 2 * direction + destination
@@ -10,18 +10,26 @@
 //   change after every commit:
 //     array 0        over-capacity time   dur[k] * [pressure[k] > cap]
 //     array 1 + ch   free channel time    dur[k] - busy[ch][k]
-//   level 0 = exclusive prefix inside a chunk of CH slots (inch[5][K]),
-//   level 1 = exclusive prefix of the chunk totals (bases[5][nch + 1]); a
-//   prefix up to slot j is bases[j / CH] + inch[j].  Level 1 is small enough to
-//   sit in LDS while candidates are scored.
+//   level 0 = exclusive prefix inside a chunk of CH slots, interleaved per
+//             slot (px[K][8], one 64-byte record per slot, so that the words a
+//             candidate needs at one slot share a cache line);
+//   level 1 = exclusive prefix of the chunk totals (bases[5][nch + 1]), small
+//             enough to sit in LDS while candidates are scored.
+//   A prefix up to slot j is bases[j / CH] + px[j].
+//
+// Candidates (inactive periods with at least one valid window) are kept as
+// packed 16-byte vectors, sorted by period start so that neighbouring lanes
+// gather neighbouring timeline records, and are compacted between batches of
+// passes: a candidate whose both destinations are invalid, can no longer be
+// carried, or remove no over-capacity time can never score again (pressure
+// only falls, reservations only grow), so dropping it changes nothing.
 //
 // One ranking pass = two launches:
-//   k_score   streams the candidate SoA (36 B per candidate), gathers the few
-//             prefix words each candidate needs, reduces to the best
-//             (benefit, lowest index) per workgroup; the last workgroup to
-//             finish reduces the partials, decides (stop / drop / commit),
-//             appends the migration record.
-//   k_commit  one workgroup per chunk applies the range updates of the winner
+//   k_score   streams the candidate vectors (32 B per candidate), gathers the
+//             prefix words, reduces to the best (benefit, lowest index) per
+//             workgroup; the last workgroup to finish reduces the partials,
+//             decides (stop / drop / commit) and appends the migration record.
+//   k_commit  one workgroup per chunk applies the winner's range updates
 //             (pressure, channel reservations, host memory) to its slots and
 //             rebuilds its chunk's prefixes; the last workgroup rebuilds
 //             level 1 and tests the "fits" stop rule.
@@ -35,7 +43,7 @@
 
 namespace {
 
-enum { A_OT = 0, A_FO = 1, A_FI = 3, N_ARR = 5 };   // FO + dest, FI + dest
+enum { A_OT = 0, A_FO = 1, A_FI = 3, N_ARR = 5, PX = 8 };   // FO + dest, FI + dest; PX = words per slot record
 enum { ACT_NONE = 0, ACT_COMMIT = 1, ACT_DROP = 2 };
 
 struct Ctl {
@@ -60,9 +68,10 @@ struct Partial {
   u32 cand, pos, dest, pad;
 };
 
-struct Cands {                // active candidates, SoA
-  u32 *idx, *L1, *R, *a0, *b0, *a1, *b1;
-  u64* s;
+struct Cands {                // live candidates, sorted by L1
+  uint4* A;                   // {L1, R, a0, b0}     a > b: no valid window for that destination
+  uint4* B;                   // {a1, b1, size lo, size hi}
+  u32* idx;                   // index of the period in the analysis order (the tie-break)
 };
 
 struct Timelines {
@@ -70,34 +79,85 @@ struct Timelines {
   u64* pressure;
   u64* busy;                  // [4][K]
   u64* host_used;
-  u64* inch;                  // [5][K]
+  u64* px;                    // [K][PX]
   u64* tot;                   // [5][nch]
   u64* bases;                 // [5][nch + 1]
   u64* hostmax;               // [nch]
-  u32 K, nch, spt;            // chunk = 256 * spt slots
+  u32 K, nch, spt, shift_ch;  // chunk = 256 * spt = 1 << shift_ch slots
 };
 
 // ---------------------------------------------------------------------------
 // prefix queries on the doubled timeline (two iterations end to end)
 // ---------------------------------------------------------------------------
-struct PrefixView {
-  const u64* inch;            // global, [K]
-  const u64* base;            // LDS or global, [nch + 1]
-  u32 K, nch, shift_ch;       // chunk = 1 << shift_ch slots
-  __device__ __forceinline__ u64 total() const { return base[nch]; }
-  // sum over slots [0, j) of the doubled timeline, j in [0, 2K]
-  __device__ __forceinline__ u64 at(u32 j) const {
-    u64 add = 0;
-    if (j >= K) { j -= K; add = base[nch]; }
-    if (j == K) return add + base[nch];
-    return add + base[j >> shift_ch] + inch[j];
+struct Slot {                 // a doubled coordinate j in [0, 2K) resolved once
+  const u64* rec;             // its 64-byte record
+  u32 chunk;
+  bool second;                // j >= K: add one whole iteration
+};
+
+struct Prefix {
+  const u64* px;
+  const u64* base;            // [5][nb1], LDS in k_score
+  u32 K, nb1, shift_ch;
+  __device__ __forceinline__ Slot slot(u32 j) const {
+    Slot s;
+    s.second = j >= K;
+    const u32 jj = s.second ? j - K : j;
+    s.rec = px + (u64)jj * PX;
+    s.chunk = jj >> shift_ch;
+    return s;
+  }
+  // sum of array `arr` over the slots before the slot
+  __device__ __forceinline__ u64 at(u32 arr, const Slot& s) const {
+    const u64* b = base + arr * nb1;
+    return (s.second ? b[nb1 - 1] : 0ull) + b[s.chunk] + s.rec[arr];
   }
 };
 
 __device__ __forceinline__ bool carries(u64 free_ns, u64 bw, u64 bytes_x1000) {
   // free_ns >= ceil(bytes_x1000 / bw)  <=>  free_ns * bw >= bytes_x1000
-  const u64 hi = __umul64hi(free_ns, bw);
-  return hi != 0 || free_ns * bw >= bytes_x1000;
+  return __umul64hi(free_ns, bw) != 0 || free_ns * bw >= bytes_x1000;
+}
+
+struct Machine { u64 bwo[2], bwi[2]; };
+
+// Policy destination and over-capacity time of one candidate: flash unless
+// flash has no valid window or cannot carry the transfer, then host.
+// Returns false if no destination can take it now.
+__device__ __forceinline__ bool policy(const Prefix& pf, const Machine& m, const uint4 A, const uint4 B, u64 s,
+                                       u32& dest, u64& ot) {
+  const u64 x1000 = s * 1000ull;
+  const Slot sL = pf.slot(A.x), sR = pf.slot(A.y);
+#pragma unroll
+  for (u32 d = 0; d < 2; ++d) {
+    const u32 a = d ? B.x : A.z, b = d ? B.y : A.w;
+    if (a > b) continue;
+    const Slot sa = pf.slot(a);
+    if (!carries(pf.at(A_FO + d, sa) - pf.at(A_FO + d, sL), m.bwo[d], x1000)) continue;   // eviction in [L1, a-1]
+    const Slot sb = pf.slot(b + 1);
+    if (!carries(pf.at(A_FI + d, sR) - pf.at(A_FI + d, sb), m.bwi[d], x1000)) continue;   // prefetch in [b+1, R-1]
+    ot = pf.at(A_OT, sb) - pf.at(A_OT, sa);                                               // over capacity while absent
+    dest = d;
+    return true;
+  }
+  return false;
+}
+
+// Can the candidate ever score again?  (either destination still possible and useful)
+__device__ __forceinline__ bool alive(const Prefix& pf, const Machine& m, const uint4 A, const uint4 B, u64 s) {
+  const u64 x1000 = s * 1000ull;
+  const Slot sL = pf.slot(A.x), sR = pf.slot(A.y);
+#pragma unroll
+  for (u32 d = 0; d < 2; ++d) {
+    const u32 a = d ? B.x : A.z, b = d ? B.y : A.w;
+    if (a > b) continue;
+    const Slot sa = pf.slot(a), sb = pf.slot(b + 1);
+    if (pf.at(A_OT, sb) == pf.at(A_OT, sa)) continue;
+    if (!carries(pf.at(A_FO + d, sa) - pf.at(A_FO + d, sL), m.bwo[d], x1000)) continue;
+    if (!carries(pf.at(A_FI + d, sR) - pf.at(A_FI + d, sb), m.bwi[d], x1000)) continue;
+    return true;
+  }
+  return false;
 }
 
 __device__ __forceinline__ bool better(u64 hi, u64 lo, u32 cand, u64 bhi, u64 blo, u32 bcand) {
@@ -119,14 +179,14 @@ __device__ __forceinline__ u64 ceil_div_x1000(u64 s, u64 bw) {
 __global__ __launch_bounds__(G10_BLOCK) void k_prep(const u32* __restrict__ per_t, const u32* __restrict__ per_L,
                                                    const u32* __restrict__ per_R, const u64* __restrict__ size,
                                                    const u64* __restrict__ start, u32 K, u64 T, u32 C, const Ctl* ctl,
-                                                   u32* __restrict__ a0, u32* __restrict__ b0, u32* __restrict__ a1,
-                                                   u32* __restrict__ b1, u32* __restrict__ keep) {
+                                                   uint4* __restrict__ win, u32* __restrict__ keep) {
   const u32 c = blockIdx.x * G10_BLOCK + threadIdx.x;
   if (c >= C) return;
   const u32 L = per_L[c], R = per_R[c];
   const u64 s = size[per_t[c]];
   const u64 t_r = start2(start, K, T, L + 1), t_use = start2(start, K, T, R), len = t_use - t_r;
   u32 any = 0;
+  u32 w[4];
 #pragma unroll
   for (int d = 0; d < 2; ++d) {
     const u64 tau_o = ceil_div_x1000(s, ctl->bw_out[d]), tau_i = ceil_div_x1000(s, ctl->bw_in[d]);
@@ -141,32 +201,38 @@ __global__ __launch_bounds__(G10_BLOCK) void k_prep(const u32* __restrict__ per_
       while (lo < hi) { u32 mid = lo + ((hi - lo + 1) >> 1); if (start2(start, K, T, mid + 1) <= lim) lo = mid; else hi = mid - 1; }
       if (aa <= lo) { a = aa; b = lo; any = 1; }
     }
-    if (d == 0) { a0[c] = a; b0[c] = b; } else { a1[c] = a; b1[c] = b; }
+    w[2 * d] = a; w[2 * d + 1] = b;
   }
+  win[c] = make_uint4(w[0], w[1], w[2], w[3]);
   keep[c] = any;
 }
 
-__global__ __launch_bounds__(G10_BLOCK) void k_gather_active(const u32* __restrict__ per_t, const u32* __restrict__ per_L,
-                                                            const u32* __restrict__ per_R, const u64* __restrict__ size,
-                                                            const u32* __restrict__ a0, const u32* __restrict__ b0,
-                                                            const u32* __restrict__ a1, const u32* __restrict__ b1,
-                                                            const u32* __restrict__ pos, u32 C, Cands out) {
+// sort keys of the kept candidates: (L + 1) in the high bits, period index below
+__global__ __launch_bounds__(G10_BLOCK) void k_sort_keys(const u32* __restrict__ per_L, const u32* __restrict__ pos, u32 C,
+                                                        u32 cbits, u64* __restrict__ keys) {
   const u32 c = blockIdx.x * G10_BLOCK + threadIdx.x;
   if (c >= C || pos[c + 1] == pos[c]) return;
-  const u32 o = pos[c];
+  keys[pos[c]] = ((u64)(per_L[c] + 1) << cbits) | c;
+}
+
+__global__ __launch_bounds__(G10_BLOCK) void k_gather_sorted(const u64* __restrict__ keys, u32 n, u32 cbits,
+                                                            const u32* __restrict__ per_t, const u32* __restrict__ per_R,
+                                                            const u64* __restrict__ size, const uint4* __restrict__ win,
+                                                            Cands out) {
+  const u32 o = blockIdx.x * G10_BLOCK + threadIdx.x;
+  if (o >= n) return;
+  const u64 key = keys[o];
+  const u32 c = (u32)(key & ((1ull << cbits) - 1ull));
+  const uint4 w = win[c];
+  const u64 s = size[per_t[c]];
+  out.A[o] = make_uint4((u32)(key >> cbits), per_R[c], w.x, w.y);
+  out.B[o] = make_uint4(w.z, w.w, (u32)s, (u32)(s >> 32));
   out.idx[o] = c;
-  out.L1[o] = per_L[c] + 1;
-  out.R[o] = per_R[c];
-  out.a0[o] = a0[c]; out.b0[o] = b0[c];
-  out.a1[o] = a1[c]; out.b1[o] = b1[c];
-  out.s[o] = size[per_t[c]];
 }
 
 // ---------------------------------------------------------------------------
 // chunk-local rebuild of the prefix arrays (also used to initialise them)
 // ---------------------------------------------------------------------------
-// Rebuilds array `arr` for the calling workgroup's chunk from per-slot values
-// supplied by `val(slot)`.
 template <class F>
 __device__ __forceinline__ void rebuild_chunk(const Timelines& tl, u32 arr, u64* lds_tmp, F val) {
   const u32 chunk = blockIdx.x, ch = G10_BLOCK * tl.spt;
@@ -175,10 +241,9 @@ __device__ __forceinline__ void rebuild_chunk(const Timelines& tl, u32 arr, u64*
   for (u32 i = 0; i < tl.spt; ++i) { const u32 j = j0 + i; if (j < tl.K) acc += val(j); }
   u64 total;
   u64 run = block_scan_excl(acc, lds_tmp, total);
-  u64* inch = tl.inch + (u64)arr * tl.K;
   for (u32 i = 0; i < tl.spt; ++i) {
     const u32 j = j0 + i;
-    if (j < tl.K) { inch[j] = run; run += val(j); }
+    if (j < tl.K) { tl.px[(u64)j * PX + arr] = run; run += val(j); }
   }
   if (threadIdx.x == 0) tl.tot[(u64)arr * tl.nch + chunk] = total;
 }
@@ -288,48 +353,48 @@ __device__ __forceinline__ u64 host_max_segment(const Timelines& tl, u32 x, u32 
   return m;
 }
 
-__global__ __launch_bounds__(G10_BLOCK) void k_score(Cands cd, u32 n_act, Timelines tl, Ctl* ctl, Partial* partials,
-                                                    const u32* __restrict__ per_t, g10_migration* records,
-                                                    g10_dropped* dropped) {
+// Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous
+// run of candidate blocks so that its L2 sees one region of the timeline.
+__device__ __forceinline__ u32 logical_block() {
+  const u32 g = gridDim.x;
+  return (g & 7u) ? blockIdx.x : (blockIdx.x & 7u) * (g >> 3) + (blockIdx.x >> 3);
+}
+
+__device__ __forceinline__ void load_bases(const Timelines& tl, u64* lds_base) {
+  const u32 nb1 = tl.nch + 1;
+  for (u32 i = threadIdx.x; i < N_ARR * nb1; i += G10_BLOCK) lds_base[i] = tl.bases[i];
+  __syncthreads();
+}
+
+__global__ __launch_bounds__(G10_BLOCK) void k_score(Cands cd, u32 n_act, u32 per_block, Timelines tl, Ctl* ctl,
+                                                    Partial* partials, const u32* __restrict__ per_t,
+                                                    g10_migration* records, g10_dropped* dropped) {
   extern __shared__ u64 lds_base[];            // [5][nch + 1]
   __shared__ Best lds_best[G10_WAVES];
   __shared__ u64 lds_tmp[G10_WAVES + 1];
   __shared__ u32 lds_flag;
   if (ctl->done) return;
-
-  const u32 nb1 = tl.nch + 1;
-  for (u32 i = threadIdx.x; i < N_ARR * nb1; i += G10_BLOCK) lds_base[i] = tl.bases[i];
-  __syncthreads();
-  u32 shift_ch = 0;
-  while ((1u << shift_ch) < G10_BLOCK * tl.spt) ++shift_ch;
-  PrefixView pv[N_ARR];
-#pragma unroll
-  for (u32 arr = 0; arr < N_ARR; ++arr) {
-    pv[arr].inch = tl.inch + (u64)arr * tl.K;
-    pv[arr].base = lds_base + arr * nb1;
-    pv[arr].K = tl.K; pv[arr].nch = tl.nch; pv[arr].shift_ch = shift_ch;
-  }
-  const u64 bwo0 = ctl->bw_out[0], bwo1 = ctl->bw_out[1], bwi0 = ctl->bw_in[0], bwi1 = ctl->bw_in[1];
+  load_bases(tl, lds_base);
+  Prefix pf;
+  pf.px = tl.px; pf.base = lds_base; pf.K = tl.K; pf.nb1 = tl.nch + 1; pf.shift_ch = tl.shift_ch;
+  Machine m;
+  m.bwo[0] = ctl->bw_out[0]; m.bwo[1] = ctl->bw_out[1]; m.bwi[0] = ctl->bw_in[0]; m.bwi[1] = ctl->bw_in[1];
 
   Best best;
   best.hi = 0; best.lo = 0; best.cand = 0xffffffffu; best.pos = 0; best.dest = 0;
-  for (u32 p = blockIdx.x * G10_BLOCK + threadIdx.x; p < n_act; p += gridDim.x * G10_BLOCK) {
-    const u32 L1 = cd.L1[p], R = cd.R[p];
-    const u64 s = cd.s[p];
-    const u64 x1000 = s * 1000ull;
-#pragma unroll
-    for (u32 d = 0; d < 2; ++d) {
-      const u32 a = d ? cd.a1[p] : cd.a0[p], b = d ? cd.b1[p] : cd.b0[p];
-      if (a > b) continue;                                            // no valid window for this destination
-      const PrefixView& fo = pv[A_FO + d];
-      if (!carries(fo.at(a) - fo.at(L1), d ? bwo1 : bwo0, x1000)) continue;      // eviction: slots [L1, a-1]
-      const PrefixView& fi = pv[A_FI + d];
-      if (!carries(fi.at(R) - fi.at(b + 1), d ? bwi1 : bwi0, x1000)) continue;   // prefetch: slots [b+1, R-1]
-      const u64 ot = pv[A_OT].at(b + 1) - pv[A_OT].at(a);                        // over-capacity time while absent
-      Best me;
-      me.hi = __umul64hi(s, ot); me.lo = s * ot; me.cand = cd.idx[p]; me.pos = p; me.dest = d;
-      if ((me.hi | me.lo) != 0) best_merge(best, me);
-      break;                                                          // flash first: host only if flash cannot
+  const u32 p0 = logical_block() * per_block;
+  const u32 p1 = p0 + per_block < n_act ? p0 + per_block : n_act;
+  for (u32 p = p0 + threadIdx.x; p < p1; p += G10_BLOCK) {
+    const uint4 A = cd.A[p], B = cd.B[p];
+    const u64 s = ((u64)B.w << 32) | B.z;
+    u32 d;
+    u64 ot;
+    if (!policy(pf, m, A, B, s, d, ot)) continue;
+    const u64 hi = __umul64hi(s, ot), lo = s * ot;
+    if ((hi | lo) == 0) continue;
+    if (hi > best.hi || (hi == best.hi && lo >= best.lo)) {           // the index is needed on ties only
+      const u32 c = cd.idx[p];
+      if (better(hi, lo, c, best.hi, best.lo, best.cand)) { best.hi = hi; best.lo = lo; best.cand = c; best.pos = p; best.dest = d; }
     }
   }
   best = block_best(best, lds_best);
@@ -363,27 +428,30 @@ __global__ __launch_bounds__(G10_BLOCK) void k_score(Cands cd, u32 n_act, Timeli
     return;
   }
   const u32 p = best.pos, d = best.dest;
-  const u32 L1 = cd.L1[p], R = cd.R[p];
-  const u64 s = cd.s[p];
+  const uint4 A = cd.A[p], B = cd.B[p];
+  const u32 L1 = A.x, R = A.y;
+  const u64 s = ((u64)B.w << 32) | B.z;
   bool room = true;
   if (d == G10_HOST) {                          // host memory must hold it during the whole period
-    u64 m = 0;
+    u64 mx = 0;
     const u32 x = L1, y = R - 1;                // doubled coordinates, y - x < K
-    if (y < tl.K) m = host_max_segment(tl, x, y);
-    else if (x >= tl.K) m = host_max_segment(tl, x - tl.K, y - tl.K);
+    if (y < tl.K) mx = host_max_segment(tl, x, y);
+    else if (x >= tl.K) mx = host_max_segment(tl, x - tl.K, y - tl.K);
     else {
       const u64 m1 = host_max_segment(tl, x, tl.K - 1), m2 = host_max_segment(tl, 0, y - tl.K);
-      m = m1 > m2 ? m1 : m2;
+      mx = m1 > m2 ? m1 : m2;
     }
-    m = block_max(m, lds_tmp);
-    room = s <= ctl->host_cap && m <= ctl->host_cap - s;
+    mx = block_max(mx, lds_tmp);
+    room = s <= ctl->host_cap && mx <= ctl->host_cap - s;
   }
+  __syncthreads();                              // every thread has read the candidate before it is retired
   if (threadIdx.x == 0) {
-    const u32 a = d ? cd.a1[p] : cd.a0[p], b = d ? cd.b1[p] : cd.b0[p];
+    const u32 a = d ? B.x : A.z, b = d ? B.y : A.w;
     const u64 it = ctl->n_iter;
     ctl->n_iter = it + 1;
     ctl->n_evals += ctl->C - ctl->n_mig - ctl->n_drop;
-    cd.a0[p] = 1; cd.b0[p] = 0; cd.a1[p] = 1; cd.b1[p] = 0;        // the candidate leaves the live set
+    cd.A[p] = make_uint4(L1, R, 1u, 0u);                             // the candidate leaves the live set
+    cd.B[p] = make_uint4(1u, 0u, B.z, B.w);
     if (!room) {
       g10_dropped dr; dr.iteration = it; dr.cand = best.cand; dr.reserved = 0;
       dropped[ctl->n_drop] = dr;
@@ -391,22 +459,47 @@ __global__ __launch_bounds__(G10_BLOCK) void k_score(Cands cd, u32 n_act, Timeli
       ctl->action = ACT_DROP;
     } else {
       const u64 tau_o = ceil_div_x1000(s, ctl->bw_out[d]), tau_i = ceil_div_x1000(s, ctl->bw_in[d]);
-      g10_migration m;
-      m.cand = best.cand; m.tensor = per_t[best.cand];
-      m.evict_after = L1 - 1; m.absent_first = a % tl.K; m.absent_last = b % tl.K; m.next_use = R % tl.K;
-      m.dest = d; m.wraps = R >= tl.K ? 1u : 0u;
-      m.size_bytes = s; m.t_out_ns = tau_o; m.t_in_ns = tau_i; m.benefit_lo = best.lo; m.benefit_hi = best.hi;
-      records[ctl->n_mig] = m;
+      g10_migration mg;
+      mg.cand = best.cand; mg.tensor = per_t[best.cand];
+      mg.evict_after = L1 - 1; mg.absent_first = a % tl.K; mg.absent_last = b % tl.K; mg.next_use = R % tl.K;
+      mg.dest = d; mg.wraps = R >= tl.K ? 1u : 0u;
+      mg.size_bytes = s; mg.t_out_ns = tau_o; mg.t_in_ns = tau_i; mg.benefit_lo = best.lo; mg.benefit_hi = best.hi;
+      records[ctl->n_mig] = mg;
       ctl->n_mig += 1;
       ctl->action = ACT_COMMIT;
       ctl->dest = d; ctl->pos = p; ctl->cand = best.cand;
       ctl->L1 = L1; ctl->R = R; ctl->a = a; ctl->b = b;
       ctl->s = s; ctl->tau_o = tau_o; ctl->tau_i = tau_i;
-      ctl->fo_base = pv[A_FO + d].at(L1);
-      ctl->fi_end = pv[A_FI + d].at(R);
+      ctl->fo_base = pf.at(A_FO + d, pf.slot(L1));
+      ctl->fi_end = pf.at(A_FI + d, pf.slot(R));
     }
     ctl->score_done = 0;
   }
+}
+
+// ---------------------------------------------------------------------------
+// compaction of candidates that can never score again
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(G10_BLOCK) void k_alive(Cands cd, u32 n_act, Timelines tl, const Ctl* ctl, u32* __restrict__ flag) {
+  extern __shared__ u64 lds_base[];
+  load_bases(tl, lds_base);
+  Prefix pf;
+  pf.px = tl.px; pf.base = lds_base; pf.K = tl.K; pf.nb1 = tl.nch + 1; pf.shift_ch = tl.shift_ch;
+  Machine m;
+  m.bwo[0] = ctl->bw_out[0]; m.bwo[1] = ctl->bw_out[1]; m.bwi[0] = ctl->bw_in[0]; m.bwi[1] = ctl->bw_in[1];
+  for (u32 p = blockIdx.x * G10_BLOCK + threadIdx.x; p < n_act; p += gridDim.x * G10_BLOCK) {
+    const uint4 A = cd.A[p], B = cd.B[p];
+    flag[p] = alive(pf, m, A, B, ((u64)B.w << 32) | B.z) ? 1u : 0u;
+  }
+}
+
+__global__ __launch_bounds__(G10_BLOCK) void k_compact(Cands src, Cands dst, const u32* __restrict__ pos, u32 n_act) {
+  const u32 p = blockIdx.x * G10_BLOCK + threadIdx.x;
+  if (p >= n_act || pos[p + 1] == pos[p]) return;
+  const u32 o = pos[p];
+  dst.A[o] = src.A[p];
+  dst.B[o] = src.B[p];
+  dst.idx[o] = src.idx[p];
 }
 
 // ---------------------------------------------------------------------------
@@ -437,8 +530,6 @@ __global__ __launch_bounds__(G10_BLOCK) void k_commit(Timelines tl, Ctl* ctl) {
   if (touched) {
     u64* busy_o = tl.busy + (u64)(0 + d) * K;
     u64* busy_i = tl.busy + (u64)(2 + d) * K;
-    const u64* inch_o = tl.inch + (u64)(A_FO + d) * K;
-    const u64* inch_i = tl.inch + (u64)(A_FI + d) * K;
     const u64* base_o = tl.bases + (u64)(A_FO + d) * (tl.nch + 1);
     const u64* base_i = tl.bases + (u64)(A_FI + d) * (tl.nch + 1);
     const u64 bo = base_o[chunk], bi = base_i[chunk], tot_o = base_o[tl.nch], tot_i = base_i[tl.nch];
@@ -450,7 +541,7 @@ __global__ __launch_bounds__(G10_BLOCK) void k_commit(Timelines tl, Ctl* ctl) {
       u32 jj = in_doubled(j, K, L1, a - 1);                 // eviction window: earliest free time first
       if (jj != 0xffffffffu) {
         const u64 fr = tl.dur[j] - busy_o[j];
-        const u64 before = (jj >= K ? tot_o : 0) + bo + inch_o[j] - fo_base;
+        const u64 before = (jj >= K ? tot_o : 0) + bo + tl.px[(u64)j * PX + A_FO + d] - fo_base;
         const u64 used = before < tau_o ? before : tau_o;
         const u64 take = fr < tau_o - used ? fr : tau_o - used;
         busy_o[j] += take;
@@ -458,7 +549,7 @@ __global__ __launch_bounds__(G10_BLOCK) void k_commit(Timelines tl, Ctl* ctl) {
       jj = in_doubled(j, K, b + 1, R - 1);                  // prefetch window: latest free time first
       if (jj != 0xffffffffu) {
         const u64 fr = tl.dur[j] - busy_i[j];
-        const u64 upto = (jj >= K ? tot_i : 0) + bi + inch_i[j] + fr;   // free time before slot jj + 1
+        const u64 upto = (jj >= K ? tot_i : 0) + bi + tl.px[(u64)j * PX + A_FI + d] + fr;   // free time before slot jj + 1
         const u64 after = fi_end - upto;
         const u64 used = after < tau_i ? after : tau_i;
         const u64 take = fr < tau_i - used ? fr : tau_i - used;
@@ -507,17 +598,24 @@ int dalloc(T** out, u64 elems) {
   return G10_OK;
 }
 
+inline u32 bits_for(u64 max_value) {
+  u32 b = 1;
+  while (b < 64 && (max_value >> b)) ++b;
+  return b;
+}
+
 }  // namespace
 
 #define G10_TRY(x) do { int rc_ = (x); if (rc_) return rc_; } while (0)
 
 struct PlanWork {
-  // sized by the trace
-  u32 K = 0, nch = 0, spt = 1;
+  u32 K = 0, nch = 0, spt = 1, shift_ch = 8;
   u64 C = 0;
-  u32 *a0 = nullptr, *b0 = nullptr, *a1 = nullptr, *b1 = nullptr, *keep = nullptr, *scratch32 = nullptr;
-  Cands cd = {};
-  u64 *pressure = nullptr, *busy = nullptr, *host_used = nullptr, *inch = nullptr, *tot = nullptr, *bases = nullptr,
+  uint4* win = nullptr;
+  u32 *keep = nullptr, *scratch32 = nullptr, *hist = nullptr;
+  u64 *keys = nullptr, *keys_alt = nullptr;
+  Cands cd[2] = {};
+  u64 *pressure = nullptr, *busy = nullptr, *host_used = nullptr, *px = nullptr, *tot = nullptr, *bases = nullptr,
       *hostmax = nullptr, *peak_after = nullptr;
   Ctl* ctl = nullptr;
   Partial* partials = nullptr;
@@ -534,9 +632,9 @@ struct PlanWork {
 
 void plan_work_free(PlanWork* w) {
   if (!w) return;
-  void* dev[] = {w->a0, w->b0, w->a1, w->b1, w->keep, w->scratch32, w->cd.idx, w->cd.L1, w->cd.R, w->cd.a0, w->cd.b0,
-                 w->cd.a1, w->cd.b1, w->cd.s, w->pressure, w->busy, w->host_used, w->inch, w->tot, w->bases, w->hostmax,
-                 w->peak_after, w->ctl, w->partials, w->records, w->dropped};
+  void* dev[] = {w->win, w->keep, w->scratch32, w->hist, w->keys, w->keys_alt, w->cd[0].A, w->cd[0].B, w->cd[0].idx,
+                 w->cd[1].A, w->cd[1].B, w->cd[1].idx, w->pressure, w->busy, w->host_used, w->px, w->tot, w->bases,
+                 w->hostmax, w->peak_after, w->ctl, w->partials, w->records, w->dropped};
   for (void* p : dev) if (p) (void)hipFree(p);
   free(w->h_records);
   free(w->h_dropped);
@@ -548,7 +646,7 @@ void plan_work_free(PlanWork* w) {
 }
 
 static const u32 MAX_SCORE_BLOCKS = 2048;
-static const u32 BATCH = 64;                     // ranking passes enqueued between two polls of the done flag
+static const u32 BATCH = 32;                     // ranking passes enqueued between two polls of the done flag
 
 static int work_alloc(g10_plan_s* h) {
   PlanWork* w = new (std::nothrow) PlanWork();
@@ -557,18 +655,21 @@ static int work_alloc(g10_plan_s* h) {
   const u32 K = h->K;
   const u64 C = h->n_periods;
   w->K = K; w->C = C;
-  w->spt = 1;
-  while ((u64)G10_BLOCK * w->spt * 1024 < K) w->spt *= 2;      // at most 1024 chunks; chunk size a power of two
+  w->spt = 1; w->shift_ch = 8;
+  while ((u64)G10_BLOCK * w->spt * 1024 < K) { w->spt *= 2; w->shift_ch += 1; }   // at most 1024 chunks
   const u32 ch = G10_BLOCK * w->spt;
   w->nch = (K + ch - 1) / ch;
-  G10_TRY(dalloc(&w->a0, C)); G10_TRY(dalloc(&w->b0, C)); G10_TRY(dalloc(&w->a1, C)); G10_TRY(dalloc(&w->b1, C));
+  G10_TRY(dalloc(&w->win, C));
   G10_TRY(dalloc(&w->keep, C + 1));
-  G10_TRY(dalloc(&w->scratch32, scan_scratch_elems(C)));
-  G10_TRY(dalloc(&w->cd.idx, C)); G10_TRY(dalloc(&w->cd.L1, C)); G10_TRY(dalloc(&w->cd.R, C));
-  G10_TRY(dalloc(&w->cd.a0, C)); G10_TRY(dalloc(&w->cd.b0, C)); G10_TRY(dalloc(&w->cd.a1, C)); G10_TRY(dalloc(&w->cd.b1, C));
-  G10_TRY(dalloc(&w->cd.s, C));
+  const u64 he = radix_hist_elems(C);
+  G10_TRY(dalloc(&w->hist, he));
+  G10_TRY(dalloc(&w->scratch32, scan_scratch_elems(he > C ? he : C)));
+  G10_TRY(dalloc(&w->keys, C)); G10_TRY(dalloc(&w->keys_alt, C));
+  for (int i = 0; i < 2; ++i) {
+    G10_TRY(dalloc(&w->cd[i].A, C)); G10_TRY(dalloc(&w->cd[i].B, C)); G10_TRY(dalloc(&w->cd[i].idx, C));
+  }
   G10_TRY(dalloc(&w->pressure, K)); G10_TRY(dalloc(&w->busy, (u64)4 * K)); G10_TRY(dalloc(&w->host_used, K));
-  G10_TRY(dalloc(&w->inch, (u64)N_ARR * K));
+  G10_TRY(dalloc(&w->px, (u64)PX * K));
   G10_TRY(dalloc(&w->tot, (u64)N_ARR * w->nch));
   G10_TRY(dalloc(&w->bases, (u64)N_ARR * (w->nch + 1)));
   G10_TRY(dalloc(&w->hostmax, w->nch));
@@ -583,6 +684,17 @@ static int work_alloc(g10_plan_s* h) {
   if (!w->h_records || !w->h_dropped || !w->h_pressure) return G10_ENOMEM;
   for (int i = 0; i < 2; ++i) G10_HIP(hipEventCreate(&w->ev[i]));
   return G10_OK;
+}
+
+// launch shape of the scoring pass for n live candidates
+static void score_shape(u32 n, u32& grid, u32& per_block) {
+  grid = (n + 2 * G10_BLOCK - 1) / (2 * G10_BLOCK);            // about two candidates per thread
+  if (grid < 1) grid = 1;
+  if (grid >= 8) grid = (grid + 7u) & ~7u;                     // a multiple of the XCD count
+  if (grid > MAX_SCORE_BLOCKS) grid = MAX_SCORE_BLOCKS;
+  per_block = (n + grid - 1) / grid;
+  per_block = (per_block + G10_BLOCK - 1) / G10_BLOCK * G10_BLOCK;
+  if (per_block < G10_BLOCK) per_block = G10_BLOCK;
 }
 
 int plan_run(g10_plan_s* h, const g10_params* p, g10_result* out) {
@@ -610,8 +722,9 @@ int plan_run(g10_plan_s* h, const g10_params* p, g10_result* out) {
   G10_HIP(hipMemcpyAsync(w->ctl, &hc, sizeof hc, hipMemcpyHostToDevice, s));
 
   Timelines tl;
-  tl.dur = h->dur; tl.pressure = w->pressure; tl.busy = w->busy; tl.host_used = w->host_used; tl.inch = w->inch;
+  tl.dur = h->dur; tl.pressure = w->pressure; tl.busy = w->busy; tl.host_used = w->host_used; tl.px = w->px;
   tl.tot = w->tot; tl.bases = w->bases; tl.hostmax = w->hostmax; tl.K = K; tl.nch = w->nch; tl.spt = w->spt;
+  tl.shift_ch = w->shift_ch;
 
   G10_HIP(hipMemcpyAsync(w->pressure, h->pressure_buf + 1, (u64)K * 8, hipMemcpyDeviceToDevice, s));
   G10_HIP(hipMemsetAsync(w->busy, 0, (u64)4 * K * 8, s));
@@ -620,40 +733,56 @@ int plan_run(g10_plan_s* h, const g10_params* p, g10_result* out) {
   hipLaunchKernelGGL(k_init_timelines, dim3(w->nch), dim3(G10_BLOCK), 0, s, tl, w->ctl);
   G10_HIP(hipGetLastError());
 
-  // candidates: windows per destination, then keep those with at least one valid window
+  // candidates: windows per destination; keep those with at least one valid window; sort by period start
   u32 n_act = 0;
+  const u32 cbits = bits_for(C ? C - 1 : 0);
+  const u32 gC = (C + G10_BLOCK - 1) / G10_BLOCK;
   if (C) {
-    const u32 g = (C + G10_BLOCK - 1) / G10_BLOCK;
-    hipLaunchKernelGGL(k_prep, dim3(g), dim3(G10_BLOCK), 0, s, h->per_t, h->per_L, h->per_R, h->size, h->start, K, h->T, C,
-                       w->ctl, w->a0, w->b0, w->a1, w->b1, w->keep);
+    hipLaunchKernelGGL(k_prep, dim3(gC), dim3(G10_BLOCK), 0, s, h->per_t, h->per_L, h->per_R, h->size, h->start, K, h->T, C,
+                       w->ctl, w->win, w->keep);
     G10_HIP(hipGetLastError());
     G10_TRY(scan_excl_u32(w->keep, w->keep, C, w->scratch32, s));
-    hipLaunchKernelGGL(k_gather_active, dim3(g), dim3(G10_BLOCK), 0, s, h->per_t, h->per_L, h->per_R, h->size, w->a0, w->b0,
-                       w->a1, w->b1, w->keep, C, w->cd);
-    G10_HIP(hipGetLastError());
     G10_HIP(hipMemcpyAsync(&n_act, w->keep + C, sizeof(u32), hipMemcpyDeviceToHost, s));
   }
   G10_HIP(hipMemcpyAsync(&hc, w->ctl, sizeof hc, hipMemcpyDeviceToHost, s));
   G10_HIP(hipStreamSynchronize(s));
   const u64 overtime_before = hc.overtime_before;
+  int cur = 0;
+  if (n_act && !hc.done) {
+    hipLaunchKernelGGL(k_sort_keys, dim3(gC), dim3(G10_BLOCK), 0, s, h->per_L, w->keep, C, cbits, w->keys);
+    u64 *keys = w->keys, *alt = w->keys_alt;
+    G10_TRY(radix_sort_u64(&keys, &alt, n_act, cbits + bits_for(2ull * K), w->hist, w->scratch32, s));
+    hipLaunchKernelGGL(k_gather_sorted, dim3((n_act + G10_BLOCK - 1) / G10_BLOCK), dim3(G10_BLOCK), 0, s, keys, n_act, cbits,
+                       h->per_t, h->per_R, h->size, w->win, w->cd[cur]);
+    G10_HIP(hipGetLastError());
+  }
 
   // the greedy loop
-  u32 grid = (n_act + G10_BLOCK - 1) / G10_BLOCK;
-  if (grid < 1) grid = 1;
-  if (grid > MAX_SCORE_BLOCKS) grid = MAX_SCORE_BLOCKS;
   const size_t lds = (size_t)N_ARR * (w->nch + 1) * sizeof(u64);
-  u64 launches = 0;
+  u64 launches = 0, streamed = 0, enqueued = 0;
   double score_ms = 0.0;
-  u64 enqueued = 0;
+  const u64 max_passes = (u64)n_act + 2;
   while (!hc.done) {
-    if (enqueued > (u64)n_act + 2) return G10_EDEVICE;      // every pass removes a candidate or stops: cannot happen
+    if (enqueued > max_passes) return G10_EDEVICE;           // every pass removes a candidate or stops: cannot happen
     enqueued += BATCH;
+    u32 grid, per_block;
+    score_shape(n_act, grid, per_block);
     for (u32 i = 0; i < BATCH; ++i) {
       if (p->profile) G10_HIP(hipEventRecord(w->prof[2 * i], s));
-      hipLaunchKernelGGL(k_score, dim3(grid), dim3(G10_BLOCK), lds, s, w->cd, n_act, tl, w->ctl, w->partials, h->per_t,
-                         w->records, w->dropped);
+      hipLaunchKernelGGL(k_score, dim3(grid), dim3(G10_BLOCK), lds, s, w->cd[cur], n_act, per_block, tl, w->ctl, w->partials,
+                         h->per_t, w->records, w->dropped);
       if (p->profile) G10_HIP(hipEventRecord(w->prof[2 * i + 1], s));
       hipLaunchKernelGGL(k_commit, dim3(w->nch), dim3(G10_BLOCK), 0, s, tl, w->ctl);
+    }
+    // which candidates can still score?  (flags + positions; compacted below if it pays)
+    u32 n_alive = n_act;
+    const bool sweep = n_act > 4096;
+    if (sweep) {
+      u32 ga = (n_act + G10_BLOCK - 1) / G10_BLOCK;
+      if (ga > MAX_SCORE_BLOCKS) ga = MAX_SCORE_BLOCKS;
+      hipLaunchKernelGGL(k_alive, dim3(ga), dim3(G10_BLOCK), lds, s, w->cd[cur], n_act, tl, w->ctl, w->keep);
+      G10_TRY(scan_excl_u32(w->keep, w->keep, n_act, w->scratch32, s));
+      G10_HIP(hipMemcpyAsync(&n_alive, w->keep + n_act, sizeof(u32), hipMemcpyDeviceToHost, s));
     }
     G10_HIP(hipGetLastError());
     G10_HIP(hipMemcpyAsync(&hc, w->ctl, sizeof hc, hipMemcpyDeviceToHost, s));
@@ -668,6 +797,14 @@ int plan_run(g10_plan_s* h, const g10_params* p, g10_result* out) {
         score_ms += ms;
       }
     launches += cnt;
+    streamed += (u64)cnt * n_act;
+    if (!hc.done && sweep && (u64)n_alive * 8 < (u64)n_act * 7) {
+      hipLaunchKernelGGL(k_compact, dim3((n_act + G10_BLOCK - 1) / G10_BLOCK), dim3(G10_BLOCK), 0, s, w->cd[cur], w->cd[cur ^ 1],
+                         w->keep, n_act);
+      G10_HIP(hipGetLastError());
+      cur ^= 1;
+      n_act = n_alive;
+    }
   }
 
   hipLaunchKernelGGL(k_max_u64p, dim3(K / G10_BLOCK / 4 + 1), dim3(G10_BLOCK), 0, s, w->pressure, (u64)K, w->peak_after);
@@ -689,7 +826,7 @@ int plan_run(g10_plan_s* h, const g10_params* p, g10_result* out) {
   out->peak_before = h->peak; out->peak_after = peak_after;
   out->overtime_before_ns = overtime_before; out->overtime_after_ns = overtime_after;
   out->migrations = w->h_records; out->dropped = w->h_dropped; out->pressure_after = w->h_pressure;
-  out->score_launches = launches; out->score_cands_streamed = launches * (u64)n_act;
+  out->score_launches = launches; out->score_cands_streamed = streamed;
   out->score_ms = score_ms; out->plan_ms = ms;
   return G10_OK;
 }

@@ -402,6 +402,24 @@ int g10_hip_fail(hipError_t e, const char* file, int line) {
 
 #define G10_TRY(x) do { int rc_ = (x); if (rc_) return rc_; } while (0)
 
+size_t radix_hist_elems(u64 n) { return (size_t)256 * ((n + TILE - 1) / TILE ? (n + TILE - 1) / TILE : 1) + 1; }
+
+// LSD radix sort of the low `bits` bits of 64-bit keys, 8 bits per pass, stable.
+// On return *keys points at the sorted data and *alt at the other buffer.
+// hist: radix_hist_elems(n) words; scratch: scan_scratch_elems(radix_hist_elems(n)) words.
+int radix_sort_u64(u64** keys, u64** alt, u64 n, u32 bits, u32* hist, u32* scratch, hipStream_t s) {
+  if (n == 0) return G10_OK;
+  const u32 nb = (u32)((n + TILE - 1) / TILE);
+  for (u32 shift = 0; shift < bits; shift += 8) {
+    hipLaunchKernelGGL(k_radix_hist, dim3(nb), dim3(G10_BLOCK), 0, s, *keys, n, shift, hist, nb);
+    G10_TRY(scan_excl_u32(hist, hist, (u64)256 * nb, scratch, s));
+    hipLaunchKernelGGL(k_radix_scatter, dim3(nb), dim3(G10_BLOCK), 0, s, *keys, *alt, n, shift, hist, nb);
+    u64* t = *keys; *keys = *alt; *alt = t;
+  }
+  G10_HIP(hipGetLastError());
+  return G10_OK;
+}
+
 int vitality_run(g10_plan_s* h, const g10_trace* tr) {
   hipStream_t s = h->stream;
   const u32 K = h->K, N = h->N;
@@ -448,20 +466,14 @@ int vitality_run(g10_plan_s* h, const g10_trace* tr) {
   const u32 tbits = bits_for(N - 1);
   u64 *keys = nullptr, *alt = nullptr;
   u32 *flag = nullptr, *scratch32 = nullptr, *hist = nullptr;
-  const u32 nb = (u32)((P + TILE - 1) / TILE);
   G10_TRY(tmp.alloc(&keys, P));
   G10_TRY(tmp.alloc(&alt, P));
   G10_TRY(tmp.alloc(&flag, P + 1));
-  G10_TRY(tmp.alloc(&hist, (u64)256 * (nb ? nb : 1) + 1));
-  G10_TRY(tmp.alloc(&scratch32, scan_scratch_elems((u64)256 * (nb ? nb : 1) > P ? (u64)256 * (nb ? nb : 1) : P)));
+  G10_TRY(tmp.alloc(&hist, radix_hist_elems(P)));
+  G10_TRY(tmp.alloc(&scratch32, scan_scratch_elems(radix_hist_elems(P) > P ? radix_hist_elems(P) : P)));
   if (P) {
     hipLaunchKernelGGL(k_pack, dim3(grid_for(P)), dim3(G10_BLOCK), 0, s, tr->use_kernel, tr->use_tensor, P, h->kbits, keys);
-    for (u32 shift = 0; shift < h->kbits + tbits; shift += 8) {
-      hipLaunchKernelGGL(k_radix_hist, dim3(nb), dim3(G10_BLOCK), 0, s, keys, P, shift, hist, nb);
-      G10_TRY(scan_excl_u32(hist, hist, (u64)256 * nb, scratch32, s));
-      hipLaunchKernelGGL(k_radix_scatter, dim3(nb), dim3(G10_BLOCK), 0, s, keys, alt, P, shift, hist, nb);
-      u64* t = keys; keys = alt; alt = t;
-    }
+    G10_TRY(radix_sort_u64(&keys, &alt, P, h->kbits + tbits, hist, scratch32, s));
     hipLaunchKernelGGL(k_flag_distinct, dim3(grid_for(P)), dim3(G10_BLOCK), 0, s, keys, P, flag);
     G10_HIP(hipGetLastError());
   }

@@ -1,0 +1,54 @@
+"""Writes tests/golden/config5_plan_digest.txt: digests of the oracle's complete
+plan for the stress workload (config 5).  Calls only the trace generator and
+oracle/.  Takes about five minutes of one CPU core.
+
+    python tests/golden/make_config5_digest.py
+"""
+import hashlib
+import os
+import sys
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, os.path.dirname(os.path.dirname(HERE)))
+
+from oracle import oracle as O                      # noqa: E402
+from paper_2310_09443_amd import traces             # noqa: E402
+
+FIELDS = ["cand", "tensor", "evict_after", "absent_first", "absent_last", "next_use", "dest", "wraps",
+          "size", "t_out", "t_in", "benefit_lo", "benefit_hi"]
+
+
+def trace_digest(tr):
+    h = hashlib.sha256()
+    for a in (tr.dur_ns, tr.size_bytes, tr.is_global, tr.use_kernel, tr.use_tensor):
+        h.update(np.ascontiguousarray(a).tobytes())
+    return h.hexdigest()
+
+
+def records_digest(rec):
+    h = hashlib.sha256()
+    for f in FIELDS:
+        h.update(np.ascontiguousarray(rec[f]).astype("<u8").tobytes())
+    return h.hexdigest()
+
+
+def main():
+    w = traces.config(5)
+    v = O.Vitality(w.trace, O.PREFIX)
+    cap, hcap = traces.resolve_caps(w, v.peak)
+    p = v.plan(cap, hcap, w.bw_out_Bpus, w.bw_in_Bpus)
+    with open(os.path.join(HERE, "config5_plan_digest.txt"), "w") as f:
+        f.write("# Complete plan of the CPU oracle for the stress workload (config 5), as digests.\n")
+        f.write("# Written by tests/golden/make_config5_digest.py, which calls only oracle/.\n")
+        f.write(f"trace_sha256 {trace_digest(w.trace)}\n")
+        f.write(f"records_sha256 {records_digest(p.records)}\n")
+        f.write(f"pressure_after_sha256 {hashlib.sha256(p.pressure_after.astype('<u8').tobytes()).hexdigest()}\n")
+        f.write(f"status {p.status}\npasses {p.n_iterations}\nmigrations {p.n_migrations}\n"
+                f"dropped {p.n_null}\ncand_evals {p.n_cand_evals}\n")
+    print("written")
+
+
+if __name__ == "__main__":
+    main()
