@@ -126,6 +126,10 @@ typedef struct {
   uint64_t score_launches, score_cands_streamed;
   double score_ms;
   double plan_ms;         /* device time of the whole call, events on the stream       */
+  /* profile = 1: the scoring launches made over the complete candidate list
+   * (before the first compaction): how many, candidates each, total time */
+  uint64_t full_launches, full_cands;
+  double full_ms;
 } g10_result;
 
 typedef struct g10_plan_s g10_plan_t;   /* opaque: device copy of the analysis + workspaces */

@@ -60,7 +60,8 @@ class _Result(C.Structure):
                 ("overtime_before_ns", C.c_uint64), ("overtime_after_ns", C.c_uint64),
                 ("migrations", C.c_void_p), ("dropped", C.c_void_p), ("pressure_after", C.c_void_p),
                 ("score_launches", C.c_uint64), ("score_cands_streamed", C.c_uint64),
-                ("score_ms", C.c_double), ("plan_ms", C.c_double)]
+                ("score_ms", C.c_double), ("plan_ms", C.c_double),
+                ("full_launches", C.c_uint64), ("full_cands", C.c_uint64), ("full_ms", C.c_double)]
 
 
 _lib = None

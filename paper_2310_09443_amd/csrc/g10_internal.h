@@ -75,6 +75,32 @@ __device__ __forceinline__ T block_scan_excl(T v, T* tmp, T& total) {
   return base + inc - v;
 }
 
+// The same for N values at once (two barriers in total).  tmp: LDS of N * G10_WAVES.
+template <int N>
+__device__ __forceinline__ void block_scan_excl_n(u64 (&v)[N], u64* tmp, u64 (&total)[N]) {
+  u64 inc[N];
+#pragma unroll
+  for (int n = 0; n < N; ++n) inc[n] = wave_scan_incl(v[n]);
+  if (lane_id() == G10_WAVE - 1) {
+#pragma unroll
+    for (int n = 0; n < N; ++n) tmp[n * G10_WAVES + wave_id()] = inc[n];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int n = 0; n < N; ++n) {
+    u64 base = 0, tot = 0;
+#pragma unroll
+    for (u32 w = 0; w < G10_WAVES; ++w) {
+      const u64 x = tmp[n * G10_WAVES + w];
+      if (w < wave_id()) base += x;
+      tot += x;
+    }
+    v[n] = base + inc[n] - v[n];
+    total[n] = tot;
+  }
+  __syncthreads();
+}
+
 template <class T>
 __device__ __forceinline__ T block_sum(T v, T* tmp) {
   v = wave_sum(v);

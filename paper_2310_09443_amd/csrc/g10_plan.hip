@@ -38,6 +38,7 @@
 #include "g10_internal.h"
 
 #include <new>
+#include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
 
@@ -263,17 +264,20 @@ __device__ __forceinline__ void rebuild_bases(const Timelines& tl, u32 arr, u64*
 }
 
 // true on exactly the last workgroup to arrive; makes the other workgroups'
-// global writes visible to it
+// global writes visible to it.  One release per workgroup (thread 0, after the
+// barrier has ordered the other threads' writes before it) and one acquire in
+// the last workgroup only: agent-scope fences write back / invalidate L2 on
+// this multi-die part, so they are kept off the other waves.
 __device__ __forceinline__ bool last_workgroup(u32* counter, u32* lds_flag) {
-  __threadfence();
   __syncthreads();
   if (threadIdx.x == 0) {
-    const u32 t = atomicAdd(counter, 1u);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+    const u32 t = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     *lds_flag = (t == gridDim.x - 1);
   }
   __syncthreads();
   const bool last = *lds_flag != 0;
-  if (last) __threadfence();
+  if (last) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
   return last;
 }
 
@@ -691,7 +695,9 @@ static void score_shape(u32 n, u32& grid, u32& per_block) {
   grid = (n + 2 * G10_BLOCK - 1) / (2 * G10_BLOCK);            // about two candidates per thread
   if (grid < 1) grid = 1;
   if (grid >= 8) grid = (grid + 7u) & ~7u;                     // a multiple of the XCD count
-  if (grid > MAX_SCORE_BLOCKS) grid = MAX_SCORE_BLOCKS;
+  u32 cap = 512;                                               // two workgroups per CU: more only adds fences
+  if (const char* e = getenv("G10_SCORE_BLOCKS")) { u32 v = (u32)atoi(e); if (v >= 8 && v <= MAX_SCORE_BLOCKS) cap = v & ~7u; }
+  if (grid > cap) grid = cap;
   per_block = (n + grid - 1) / grid;
   per_block = (per_block + G10_BLOCK - 1) / G10_BLOCK * G10_BLOCK;
   if (per_block < G10_BLOCK) per_block = G10_BLOCK;
@@ -760,7 +766,9 @@ int plan_run(g10_plan_s* h, const g10_params* p, g10_result* out) {
   // the greedy loop
   const size_t lds = (size_t)N_ARR * (w->nch + 1) * sizeof(u64);
   u64 launches = 0, streamed = 0, enqueued = 0;
-  double score_ms = 0.0;
+  double score_ms = 0.0, full_ms = 0.0;
+  u64 full_launches = 0;
+  const u32 n_full = n_act;
   const u64 max_passes = (u64)n_act + 2;
   while (!hc.done) {
     if (enqueued > max_passes) return G10_EDEVICE;           // every pass removes a candidate or stops: cannot happen
@@ -798,6 +806,20 @@ int plan_run(g10_plan_s* h, const g10_params* p, g10_result* out) {
       }
     launches += cnt;
     streamed += (u64)cnt * n_act;
+    if (p->profile && n_act == n_full) {                    // launches over the full candidate list
+      full_launches += cnt;
+      for (u32 i = 0; i < cnt; ++i) {
+        float ms = 0.f;
+        G10_HIP(hipEventElapsedTime(&ms, w->prof[2 * i], w->prof[2 * i + 1]));
+        full_ms += ms;
+      }
+    }
+    if (p->profile && getenv("G10_LOG") && cnt) {
+      double b = 0.0;
+      for (u32 i = 0; i < cnt; ++i) { float ms = 0.f; (void)hipEventElapsedTime(&ms, w->prof[2 * i], w->prof[2 * i + 1]); b += ms; }
+      fprintf(stderr, "g10: passes %llu..%llu  live %u  score %.2f us/launch\n", (unsigned long long)(launches - cnt),
+              (unsigned long long)launches, n_act, 1e3 * b / cnt);
+    }
     if (!hc.done && sweep && (u64)n_alive * 8 < (u64)n_act * 7) {
       hipLaunchKernelGGL(k_compact, dim3((n_act + G10_BLOCK - 1) / G10_BLOCK), dim3(G10_BLOCK), 0, s, w->cd[cur], w->cd[cur ^ 1],
                          w->keep, n_act);
@@ -828,5 +850,6 @@ int plan_run(g10_plan_s* h, const g10_params* p, g10_result* out) {
   out->migrations = w->h_records; out->dropped = w->h_dropped; out->pressure_after = w->h_pressure;
   out->score_launches = launches; out->score_cands_streamed = streamed;
   out->score_ms = score_ms; out->plan_ms = ms;
+  out->full_launches = full_launches; out->full_cands = n_full; out->full_ms = full_ms;
   return G10_OK;
 }
