@@ -79,8 +79,7 @@ typedef struct {
   uint64_t bw_out_Bpus[2];   /* GPU -> [G10_FLASH, G10_HOST], bytes per microsecond    */
   uint64_t bw_in_Bpus[2];    /* [G10_FLASH, G10_HOST] -> GPU                           */
   uint64_t max_iterations;   /* stop after this many ranking passes; 0 = no limit      */
-  uint32_t profile;          /* 1: time every scoring launch with events (slower)      */
-  uint32_t reserved;
+  uint32_t reserved[2];      /* 0                                                      */
 } g10_params;
 
 /* One migration, i.e. one g10_pre_evict / g10_prefetch pair of Section 4.4's
@@ -122,14 +121,15 @@ typedef struct {
   const g10_migration *migrations;           /* host [n_migrations], commit order      */
   const g10_dropped *dropped;                /* host [n_dropped]                       */
   const uint64_t *pressure_after;            /* host [K]                               */
-  /* filled when params.profile = 1: the scoring kernel, summed over launches */
-  uint64_t score_launches, score_cands_streamed;
-  double score_ms;
-  double plan_ms;         /* device time of the whole call, events on the stream       */
-  /* profile = 1: the scoring launches made over the complete candidate list
-   * (before the first compaction): how many, candidates each, total time */
-  uint64_t full_launches, full_cands;
-  double full_ms;
+  /* device times (events on the stream) and work counters of this call */
+  double plan_ms;              /* the whole call                                       */
+  double score_full_ms;        /* the one streaming scoring pass over all candidates   */
+  uint64_t score_full_cands;   /* candidates it streamed (those with a valid window)   */
+  double loop_ms;              /* the greedy loop                                      */
+  uint64_t loop_launches;      /* launches of the loop kernel                          */
+  uint64_t loop_cands_scored;  /* candidates re-scored inside the loop (tiles * 256)   */
+  uint64_t loop_second_rounds; /* passes that needed a second scoring round            */
+  uint64_t loop_chunk_jobs;    /* timeline chunks rewritten slot by slot               */
 } g10_result;
 
 typedef struct g10_plan_s g10_plan_t;   /* opaque: device copy of the analysis + workspaces */
@@ -159,8 +159,8 @@ int g10_vitality_info(const g10_plan_t *handle, g10_vitality_stats *out);
 int g10_vitality_read(const g10_plan_t *handle, int which, void *dst, uint64_t bytes);
 
 /* Smart tensor eviction (Algorithm 1, Section 4.3) on an analysed trace: the
- * whole greedy loop - scoring of every live candidate against the pressure
- * and channel timelines, arg-max with lowest-index tie-break, commit and range
+ * whole greedy loop - scoring of the live candidates against the pressure and
+ * channel timelines, arg-max with lowest-index tie-break, commit and range
  * updates - runs on the device.  May be called repeatedly with different
  * parameters; the analysis is never modified.  Synchronises the stream.
  * Errors: G10_EINVAL (NULL, zero bandwidth), G10_ENOMEM, G10_EDEVICE.  Not

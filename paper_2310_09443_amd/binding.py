@@ -50,7 +50,7 @@ class _Stats(C.Structure):
 class _Params(C.Structure):
     _fields_ = [("gpu_cap_bytes", C.c_uint64), ("host_cap_bytes", C.c_uint64),
                 ("bw_out_Bpus", C.c_uint64 * 2), ("bw_in_Bpus", C.c_uint64 * 2),
-                ("max_iterations", C.c_uint64), ("profile", C.c_uint32), ("reserved", C.c_uint32)]
+                ("max_iterations", C.c_uint64), ("reserved", C.c_uint32 * 2)]
 
 
 class _Result(C.Structure):
@@ -59,9 +59,9 @@ class _Result(C.Structure):
                 ("n_cand_evals", C.c_uint64), ("peak_before", C.c_uint64), ("peak_after", C.c_uint64),
                 ("overtime_before_ns", C.c_uint64), ("overtime_after_ns", C.c_uint64),
                 ("migrations", C.c_void_p), ("dropped", C.c_void_p), ("pressure_after", C.c_void_p),
-                ("score_launches", C.c_uint64), ("score_cands_streamed", C.c_uint64),
-                ("score_ms", C.c_double), ("plan_ms", C.c_double),
-                ("full_launches", C.c_uint64), ("full_cands", C.c_uint64), ("full_ms", C.c_double)]
+                ("plan_ms", C.c_double), ("score_full_ms", C.c_double), ("score_full_cands", C.c_uint64),
+                ("loop_ms", C.c_double), ("loop_launches", C.c_uint64), ("loop_cands_scored", C.c_uint64),
+                ("loop_second_rounds", C.c_uint64), ("loop_chunk_jobs", C.c_uint64)]
 
 
 _lib = None
@@ -161,13 +161,13 @@ class Handle:
     start = property(lambda self: self.read(5))
     pressure = property(lambda self: self.read(6))
 
-    def plan(self, gpu_cap, host_cap, bw_out, bw_in, max_iters=0, profile=False) -> Result:
+    def plan(self, gpu_cap, host_cap, bw_out, bw_in, max_iters=0) -> Result:
         import torch
         p = _Params()
         p.gpu_cap_bytes, p.host_cap_bytes = int(gpu_cap), int(host_cap)
         p.bw_out_Bpus[0], p.bw_out_Bpus[1] = int(bw_out[0]), int(bw_out[1])
         p.bw_in_Bpus[0], p.bw_in_Bpus[1] = int(bw_in[0]), int(bw_in[1])
-        p.max_iterations, p.profile = int(max_iters), int(bool(profile))
+        p.max_iterations = int(max_iters)
         r = _Result()
         with torch.cuda.device(self._dev):
             rc = load().g10_plan(self._h, C.byref(p), C.byref(r))
@@ -191,8 +191,8 @@ def g10_vitality(dtrace: DeviceTrace, no_wrap: bool = False, stream=None) -> Han
     return Handle(dtrace, no_wrap, stream)
 
 
-def g10_plan(handle: Handle, gpu_cap, host_cap, bw_out, bw_in, max_iters=0, profile=False) -> Result:
-    return handle.plan(gpu_cap, host_cap, bw_out, bw_in, max_iters, profile)
+def g10_plan(handle: Handle, gpu_cap, host_cap, bw_out, bw_in, max_iters=0) -> Result:
+    return handle.plan(gpu_cap, host_cap, bw_out, bw_in, max_iters)
 
 
 def g10_plan_free(handle: Handle) -> None:
