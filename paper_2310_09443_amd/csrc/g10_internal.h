@@ -27,34 +27,67 @@ int g10_hip_fail(hipError_t e, const char* file, int line);
 __device__ __forceinline__ u32 lane_id() { return threadIdx.x & (G10_WAVE - 1); }
 __device__ __forceinline__ u32 wave_id() { return threadIdx.x / G10_WAVE; }
 
-template <class T>
-__device__ __forceinline__ T wave_sum(T v) {
-#pragma unroll
-  for (int o = G10_WAVE / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, G10_WAVE);
+// Cross-lane steps run on the DPP path of the vector ALU (row shifts inside
+// rows of 16 lanes, then the row broadcasts 15 and 31 of the 64-wide wavefront)
+// instead of ds_bpermute: a few cycles per step, no LDS crossbar.  Lanes a step
+// does not write take the operation's identity.
+template <int CTRL, int ROW_MASK, int BANK_MASK>
+__device__ __forceinline__ u32 dpp_move32(u32 identity, u32 v) {
+  return (u32)__builtin_amdgcn_update_dpp((int)identity, (int)v, CTRL, ROW_MASK, BANK_MASK, false);
+}
+template <int CTRL, int ROW_MASK, int BANK_MASK, class T>
+__device__ __forceinline__ T dpp_move(T identity, T v) {
+  static_assert(sizeof(T) == 4 || sizeof(T) == 8, "32- or 64-bit integers");
+  if constexpr (sizeof(T) == 4) {
+    return (T)dpp_move32<CTRL, ROW_MASK, BANK_MASK>((u32)identity, (u32)v);
+  } else {
+    const u32 lo = dpp_move32<CTRL, ROW_MASK, BANK_MASK>((u32)identity, (u32)v);
+    const u32 hi = dpp_move32<CTRL, ROW_MASK, BANK_MASK>((u32)((u64)identity >> 32), (u32)((u64)v >> 32));
+    return (T)(((u64)hi << 32) | lo);
+  }
+}
+
+struct OpAdd { template <class T> static __device__ __forceinline__ T f(T a, T b) { return a + b; } };
+struct OpMax { template <class T> static __device__ __forceinline__ T f(T a, T b) { return a > b ? a : b; } };
+struct OpMin { template <class T> static __device__ __forceinline__ T f(T a, T b) { return a < b ? a : b; } };
+
+// inclusive scan inside a wavefront (all 64 lanes must be active); lane 63 ends with the total
+template <class Op, class T>
+__device__ __forceinline__ T wave_scan_dpp(T x, T identity) {
+  T v = x;
+  v = Op::f(v, dpp_move<0x111, 0xf, 0xf>(identity, x));      // row_shr:1
+  v = Op::f(v, dpp_move<0x112, 0xf, 0xf>(identity, x));      // row_shr:2
+  v = Op::f(v, dpp_move<0x113, 0xf, 0xf>(identity, x));      // row_shr:3
+  v = Op::f(v, dpp_move<0x114, 0xf, 0xe>(identity, v));      // row_shr:4, lanes 4..15 of a row
+  v = Op::f(v, dpp_move<0x118, 0xf, 0xc>(identity, v));      // row_shr:8, lanes 8..15 of a row
+  v = Op::f(v, dpp_move<0x142, 0xa, 0xf>(identity, v));      // lane 15 of rows 0 and 2 into rows 1 and 3
+  v = Op::f(v, dpp_move<0x143, 0xc, 0xf>(identity, v));      // lane 31 into rows 2 and 3
   return v;
 }
 
 template <class T>
-__device__ __forceinline__ T wave_max(T v) {
-#pragma unroll
-  for (int o = G10_WAVE / 2; o > 0; o >>= 1) {
-    T w = __shfl_xor(v, o, G10_WAVE);
-    v = w > v ? w : v;
+__device__ __forceinline__ T wave_last(T v) {                 // the value of lane 63, in every lane
+  if constexpr (sizeof(T) == 4) {
+    return (T)__builtin_amdgcn_readlane((int)v, G10_WAVE - 1);
+  } else {
+    const u32 lo = (u32)__builtin_amdgcn_readlane((int)(u32)v, G10_WAVE - 1);
+    const u32 hi = (u32)__builtin_amdgcn_readlane((int)(u32)((u64)v >> 32), G10_WAVE - 1);
+    return (T)(((u64)hi << 32) | lo);
   }
-  return v;
 }
+
+template <class T>
+__device__ __forceinline__ T wave_sum(T v) { return wave_last(wave_scan_dpp<OpAdd>(v, (T)0)); }
+
+template <class T>
+__device__ __forceinline__ T wave_max(T v) { return wave_last(wave_scan_dpp<OpMax>(v, (T)0)); }
+
+template <class T>
+__device__ __forceinline__ T wave_min(T v) { return wave_last(wave_scan_dpp<OpMin>(v, (T)~(T)0)); }
 
 // inclusive scan inside a wavefront
 template <class T>
-__device__ __forceinline__ T wave_scan_incl(T v) {
-  const u32 l = lane_id();
-#pragma unroll
-  for (int o = 1; o < G10_WAVE; o <<= 1) {
-    T w = __shfl_up(v, o, G10_WAVE);
-    if (l >= (u32)o) v += w;
-  }
-  return v;
-}
+__device__ __forceinline__ T wave_scan_incl(T v) { return wave_scan_dpp<OpAdd>(v, (T)0); }
 
 // Exclusive scan over the workgroup; `total` receives the sum on every thread.
 // `tmp` is LDS of G10_WAVES + 1 elements.  Contains two barriers.

@@ -55,12 +55,18 @@ namespace {
 enum { A_OT = 0, A_FO = 1, A_FI = 3, N_ARR = 5, PX = 8 };
 enum { J_FO = 0, J_FI = 1, J_P_PART = 2, J_P_FULL = 3, J_H = 4, J_HQ = 5 };
 
-constexpr u32 LB = 1024;               // threads of the loop workgroup
+#ifndef G10_LOOP_THREADS
+#define G10_LOOP_THREADS 512
+#endif
+constexpr u32 LB = G10_LOOP_THREADS;   // threads of the loop workgroup (at least NCH_MAX)
 constexpr u32 LW = LB / G10_WAVE;      // its wavefronts
 constexpr u32 UNIT = 256;              // candidates scored by four wavefronts at a time
 constexpr u32 NCH_MAX = 512;           // chunks (level-1 arrays live in LDS)
 constexpr u32 NT_MAX = 8192;           // tiles  (their bounds live in LDS)
-constexpr u32 GUESS_SHIFT = 5;         // first threshold of a pass: last benefit * (1 - 2^-5)
+#ifndef G10_GUESS_SHIFT
+#define G10_GUESS_SHIFT 7
+#endif
+constexpr u32 GUESS_SHIFT = G10_GUESS_SHIFT;   // first threshold of a pass: last benefit * (1 - 2^-shift)
 constexpr u64 NONE64 = ~0ull;
 constexpr u32 NONE32 = 0xffffffffu;
 
@@ -78,6 +84,7 @@ struct Ctl {
   u32 thr_key, pad0;          // first threshold of the next pass (0: use the largest tile bound)
   // statistics
   u64 units_scored, second_rounds, jobs_run, launches;
+  u64 phase[12];              // wall-clock ticks per phase of the loop (only with G10_PHASE_TIMERS)
 };
 
 struct Cands {
@@ -223,9 +230,7 @@ __global__ __launch_bounds__(G10_BLOCK) void k_init_timelines(Timelines tl, cons
     if (pressure0[j] > cap) run_o += d;
   }
   // smallest pressure above the capacity
-  u64 m = mn;
-#pragma unroll
-  for (int o = G10_WAVE / 2; o > 0; o >>= 1) { const u64 w = __shfl_xor(m, o, G10_WAVE); m = w < m ? w : m; }
+  u64 m = wave_min(mn);
   if (lane_id() == 0) mins[wave_id()] = m;
   __syncthreads();
   if (threadIdx.x == 0) {
@@ -335,17 +340,28 @@ __device__ __forceinline__ bool better(u64 hi, u64 lo, u32 cand, u64 bhi, u64 bl
   return cand < bcand;
 }
 
-struct Shared {               // small per-pass state of the loop workgroup
-  u64 whi, wlo;               // winner: benefit
-  u64 s, tau_o, tau_i, fo_base, fi_end;
+#ifdef G10_PHASE_TIMERS
+#define PHASE(i) do { if (tid == 0) { const u64 now_ = wall_clock64(); S->phase[i] += now_ - S->t_last; S->t_last = now_; } } while (0)
+#else
+#define PHASE(i) do { } while (0)
+#endif
+
+struct Winner {               // what a commit needs of the winning candidate
+  u64 hi, lo;                 // benefit
+  u64 s, fo_base, fi_end;     // size; free out-channel time before L1; free in-channel time before R
   u32 cand, tensor, pos, dest, L1, R, a, b;
+};
+
+struct Shared {               // small per-pass state of the loop workgroup
+  Winner win;                 // winner of the pass (hi = lo = 0: none)
+  Winner wave_win[LW];        // best of every wavefront
+  u64 tau_o, tau_i;
   u64 hq;                     // host-capacity query: maximum over the period
   u32 ntl, restmax, njobs, ot_changed;
-  u64 wave_hi[LW], wave_lo[LW];
-  u32 wave_cand[LW];
   // progress (mirrors Ctl)
   u64 n_iter, n_mig, n_drop, n_evals, units, second, jobs;
-  u32 thr_key, status, done, room;
+  u32 thr_key, status, done, pad;
+  u64 phase[12], t_last;
 };
 
 // covered slots of chunk c by the doubled range [x, y] (x <= y, y - x < K)
@@ -373,93 +389,128 @@ __device__ __forceinline__ u32 in_doubled(u32 j, u32 K, u32 x, u32 y) {
   return NONE32;
 }
 
-__device__ __forceinline__ u64 wave_min64(u64 v) {
-#pragma unroll
-  for (int o = G10_WAVE / 2; o > 0; o >>= 1) { const u64 w = __shfl_xor(v, o, G10_WAVE); v = w < v ? w : v; }
-  return v;
+__device__ __forceinline__ ulonglong2 ld2(const u64* p) { return *reinterpret_cast<const ulonglong2*>(p); }
+
+// The lane of the wavefront holding the best (benefit, lowest index), or NONE32
+// if every benefit is 0.  The 31-bit key decides unless several lanes share the
+// largest key; those few are compared in full one by one.
+__device__ __forceinline__ u32 wave_best_lane(u64 hi, u64 lo, u32 cand) {
+  const u32 k = upkey(hi, lo);
+  const u32 kmax = wave_max(k);
+  if (kmax == 0) return NONE32;
+  u64 m = __ballot(k == kmax);
+  u32 best = (u32)__builtin_ctzll(m);
+  m &= m - 1;
+  if (m) {
+    u64 bh = ((u64)__builtin_amdgcn_readlane((int)(hi >> 32), best) << 32) | (u32)__builtin_amdgcn_readlane((int)hi, best);
+    u64 bl = ((u64)__builtin_amdgcn_readlane((int)(lo >> 32), best) << 32) | (u32)__builtin_amdgcn_readlane((int)lo, best);
+    u32 bc = (u32)__builtin_amdgcn_readlane((int)cand, best);
+    while (m) {
+      const u32 l = (u32)__builtin_ctzll(m);
+      m &= m - 1;
+      const u64 yh = ((u64)__builtin_amdgcn_readlane((int)(hi >> 32), l) << 32) | (u32)__builtin_amdgcn_readlane((int)hi, l);
+      const u64 yl = ((u64)__builtin_amdgcn_readlane((int)(lo >> 32), l) << 32) | (u32)__builtin_amdgcn_readlane((int)lo, l);
+      const u32 yc = (u32)__builtin_amdgcn_readlane((int)cand, l);
+      if (better(yh, yl, yc, bh, bl, bc)) { bh = yh; bl = yl; bc = yc; best = l; }
+    }
+  }
+  return best;
 }
 
 __global__ __launch_bounds__(LB) void k_loop(LoopArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
   const Timelines tl = a.tl;
-  const u32 nch = tl.nch, nb1 = nch + 1, K = tl.K, CH = 1u << tl.shift_ch, nt = a.nt;
+  const u32 nch = tl.nch, nb1 = nch + 1, K = tl.K, CH = 1u << tl.shift_ch, nt = a.nt, ns = (nt + 63) / 64;
   u64* base = (u64*)smem;                               // [5][nch + 1]
   u64* tot = base + (u64)N_ARR * nb1;                   // [5][nch]
   u64* lazyP = tot + (u64)N_ARR * nch;
   u64* minOver = lazyP + nch;
   u64* lazyH = minOver + nch;
   u64* hmax = lazyH + nch;
-  u64* scr = hmax + nch;                                // [3 * LW]
-  Shared* S = (Shared*)(scr + 3 * LW);
-  u32* keys = (u32*)(S + 1);                            // [nt]
-  u32* jobs = keys + nt;                                // [4 * nch + 8]
-  u32* mark = jobs + 4 * nch + 8;                       // [(nt + 31) / 32]
-  unsigned short* tlist = (unsigned short*)(mark + (nt + 31) / 32);   // [nt]
+  u64* smark = hmax + nch;                              // [ns] tiles of a group of 64 scored in this pass
+  u64* scr = smark + ns;                                // [4 * LW]
+  Shared* S = (Shared*)(scr + 4 * LW);
+  u32* keys = (u32*)(S + 1);                            // [nt]  bound of every tile
+  u32* skeys = keys + nt;                               // [ns]  largest bound of every group of 64 tiles
+  u32* jobs = skeys + ns;                               // [4 * nch + 8]
+  unsigned short* tlist = (unsigned short*)(jobs + 4 * nch + 8);   // [nt]
 
   const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
   Ctl* ctl = a.ctl;
   const u64 cap = ctl->gpu_cap, host_cap = ctl->host_cap, max_iter = ctl->max_iter, C = ctl->C;
-  const u64 bwo[2] = {ctl->bw_out[0], ctl->bw_out[1]}, bwi[2] = {ctl->bw_in[0], ctl->bw_in[1]};
+  const u64 bwo0 = ctl->bw_out[0], bwo1 = ctl->bw_out[1], bwi0 = ctl->bw_in[0], bwi1 = ctl->bw_in[1];
 
   // ---- state in ----------------------------------------------------------------------
   for (u32 i = tid; i < N_ARR * nch; i += LB) tot[i] = a.g_tot[i];
   for (u32 i = tid; i < nch; i += LB) { lazyP[i] = a.g_lazyP[i]; minOver[i] = a.g_minOver[i]; lazyH[i] = a.g_lazyH[i]; hmax[i] = a.g_hmax[i]; }
   for (u32 i = tid; i < nt; i += LB) keys[i] = a.g_keys[i];
-  for (u32 i = tid; i < (nt + 31) / 32; i += LB) mark[i] = 0;
+  for (u32 i = tid; i < ns; i += LB) smark[i] = 0;
   if (tid == 0) {
     S->n_iter = ctl->n_iter; S->n_mig = ctl->n_mig; S->n_drop = ctl->n_drop; S->n_evals = ctl->n_evals;
     S->units = 0; S->second = 0; S->jobs = 0;
     S->thr_key = ctl->thr_key; S->status = ctl->status; S->done = ctl->done;
+    for (u32 i = 0; i < 12; ++i) S->phase[i] = 0;
+    S->t_last = wall_clock64();
   }
   __syncthreads();
+  for (u32 g = wave; g < ns; g += LW) {                 // group bounds
+    const u32 t = g * 64 + lane;
+    const u32 k = wave_max(t < nt ? keys[t] : 0u);
+    if (lane == 0) skeys[g] = k;
+  }
 
-  // exclusive scan of the chunk totals of NA arrays into base
-  auto scan_bases = [&](const u32* arrs, u32 na) {
-    u64 v[3], inc[3];
-    for (u32 q = 0; q < na; ++q) {
-      v[q] = tid < nch ? tot[(u64)arrs[q] * nch + tid] : 0ull;
-      inc[q] = wave_scan_incl(v[q]);
-      if (lane == G10_WAVE - 1) scr[q * LW + wave] = inc[q];
+  // exclusive scan of the chunk totals of `na` arrays into base (three barriers)
+  auto scan_bases = [&](u32 arr0, u32 arr1, u32 arr2, u32 na) {
+    const u32 arrs[3] = {arr0, arr1, arr2};
+    const bool act = tid < ((nch + 63u) & ~63u);
+    u64 v[3] = {0, 0, 0}, inc[3] = {0, 0, 0};
+    if (act) {
+      for (u32 q = 0; q < na; ++q) {
+        v[q] = tid < nch ? tot[(u64)arrs[q] * nch + tid] : 0ull;
+        inc[q] = wave_scan_incl(v[q]);
+        if (lane == G10_WAVE - 1) scr[q * LW + wave] = inc[q];
+      }
     }
     __syncthreads();
-    for (u32 q = 0; q < na; ++q) {
-      u64 b = 0, t = 0;
-      for (u32 w = 0; w < LW; ++w) { const u64 x = scr[q * LW + w]; if (w < wave) b += x; t += x; }
-      if (tid < nch) base[(u64)arrs[q] * nb1 + tid] = b + inc[q] - v[q];
-      if (tid == 0) base[(u64)arrs[q] * nb1 + nch] = t;
+    if (wave == 0) {                                    // the wavefront totals: one small scan
+      const u32 nw = (nch + 63) / 64;
+      for (u32 q = 0; q < na; ++q) {
+        const u64 x = lane < nw ? scr[q * LW + lane] : 0ull;
+        const u64 xi = wave_scan_incl(x);
+        if (lane < nw) scr[q * LW + lane] = xi - x;
+        if (lane == G10_WAVE - 1) base[(u64)arrs[q] * nb1 + nch] = xi;
+      }
     }
     __syncthreads();
+    if (act && tid < nch)
+      for (u32 q = 0; q < na; ++q) base[(u64)arrs[q] * nb1 + tid] = scr[q * LW + wave] + inc[q] - v[q];
+    __syncthreads();
   };
-  { const u32 a3[3] = {0, 1, 2}; scan_bases(a3, 3); const u32 a2[2] = {3, 4}; scan_bases(a2, 2); }
-
-  // full prefix of record word `w` (array arr) before doubled slot j
-  auto pref = [&](u32 arr, u32 w, u32 j) -> u64 {
-    const bool second = j >= K;
-    const u32 jj = second ? j - K : j;
-    const u64* b = base + (u64)arr * nb1;
-    return (second ? b[nch] : 0ull) + b[jj >> tl.shift_ch] + tl.px[(u64)jj * PX + w];
-  };
+  scan_bases(0, 1, 2, 3);
+  scan_bases(3, 4, 0, 2);
 
   // tiles whose bound reaches `thr` and that were not scored in this pass -> tlist;
-  // the largest bound among the tiles left out -> restmax
+  // an upper bound of the bounds of the tiles left out -> restmax
   auto build_list = [&](u32 thr) {
     if (tid == 0) { S->ntl = 0; S->restmax = 0; }
     __syncthreads();
     u32 rm = 0;
-    for (u32 t0 = 0; t0 < nt; t0 += LB) {
-      const u32 t = t0 + tid;
+    for (u32 g = wave; g < ns; g += LW) {
+      const u32 sk = skeys[g];
+      if (sk == 0 || sk < thr) { rm = sk > rm ? sk : rm; continue; }
+      const u32 t = g * 64 + lane;
       const u32 k = t < nt ? keys[t] : 0u;
-      const bool marked = t < nt && ((mark[t >> 5] >> (t & 31u)) & 1u);
+      const u64 mk = smark[g];
+      const bool marked = (mk >> lane) & 1ull;
       const bool sel = k != 0 && k >= thr && !marked;
       if (!sel && !marked && k > rm) rm = k;
       const u64 m = __ballot(sel);
       if (m) {
         u32 off = 0;
-        if (lane == 0) off = atomicAdd(&S->ntl, (u32)__popcll(m));
-        off = __shfl(off, 0, G10_WAVE);
+        if (lane == 0) { off = atomicAdd(&S->ntl, (u32)__popcll(m)); smark[g] = mk | m; }
+        off = (u32)__builtin_amdgcn_readfirstlane((int)off);
         if (sel) {
           tlist[off + __popcll(m & ((1ull << lane) - 1ull))] = (unsigned short)t;
-          atomicOr(&mark[t >> 5], 1u << (t & 31u));
           keys[t] = 0;                           // rebuilt by the scoring below
         }
       }
@@ -469,108 +520,201 @@ __global__ __launch_bounds__(LB) void k_loop(LoopArgs a) {
     __syncthreads();
   };
 
-  // this thread's best candidate of the pass, with what a commit needs
-  u64 m_hi = 0, m_lo = 0, m_s = 0, m_fo = 0, m_fi = 0;
-  u32 m_cand = NONE32, m_tensor = 0, m_pos = 0, m_dest = 0, m_L1 = 0, m_R = 0, m_a = 0, m_b = 0;
+  // this thread's best candidate of the pass
+  Winner mine;
+  mine.hi = 0; mine.lo = 0; mine.cand = NONE32;
 
+  struct CandV { uint4 A, B; uint2 id; u32 p, t; };
+  auto load_cand = [&](u32 u) -> CandV {
+    CandV c;
+    c.t = tlist[u >> a.tshift];
+    c.p = (((c.t << a.tshift) + (u & ((1u << a.tshift) - 1u))) << 8) + (tid & 255u);
+    c.A = a.cd.A[c.p]; c.B = a.cd.B[c.p]; c.id = a.cd.id[c.p];
+    return c;
+  };
+
+  // Scores the listed tiles: four wavefronts per 256 candidates, the next
+  // candidate's record already in flight.  One workgroup has one texture
+  // unit, about one cache line per clock: lanes whose candidate is dead load
+  // nothing, a destination that can never be used again (its channel cannot
+  // carry the transfer any more; for host also: no over-capacity time left in
+  // its window) is struck from the record so that later passes skip it.
   auto score_list = [&]() {
     const u32 nunits = S->ntl << a.tshift;
-    for (u32 u = tid >> 8; u < nunits; u += LB / UNIT) {
-      const u32 t = tlist[u >> a.tshift], sub = u & ((1u << a.tshift) - 1u);
-      const u32 p = (((t << a.tshift) + sub) << 8) + (tid & 255u);
-      const uint4 A = a.cd.A[p], B = a.cd.B[p];
-      const uint2 id = a.cd.id[p];
+    const u64 allOT = base[(u64)A_OT * nb1 + nch];
+    const u64 allFO0 = base[(u64)(A_FO + 0) * nb1 + nch], allFO1 = base[(u64)(A_FO + 1) * nb1 + nch];
+    const u64 allFI0 = base[(u64)(A_FI + 0) * nb1 + nch], allFI1 = base[(u64)(A_FI + 1) * nb1 + nch];
+    const u64 *bOT = base + (u64)A_OT * nb1, *bFO0 = base + (u64)(A_FO + 0) * nb1, *bFO1 = base + (u64)(A_FO + 1) * nb1,
+              *bFI0 = base + (u64)(A_FI + 0) * nb1, *bFI1 = base + (u64)(A_FI + 1) * nb1;
+    u32 u = tid >> 8;
+    CandV cur;
+    if (u < nunits) cur = load_cand(u);
+    while (u < nunits) {
+      const u32 un = u + LB / UNIT;
+      CandV nxt;
+      if (un < nunits) nxt = load_cand(un);
+      const uint4 A = cur.A, B = cur.B;
       const u64 s = ((u64)B.w << 32) | B.z, x1000 = s * 1000ull;
       const u32 L1 = A.x, R = A.y;
-      u64 uhi = 0, ulo = 0;
-      bool have = false;                        // the policy's destination found
-#pragma unroll
-      for (u32 d = 0; d < 2; ++d) {
-        const u32 wa = d ? B.x : A.z, wb = d ? B.y : A.w;
-        if (wa > wb) continue;
-        const u64 fo_L = pref(A_FO + d, w_fo(d), L1), fo_a = pref(A_FO + d, w_fo(d), wa);
-        const u64 fi_R = pref(A_FI + d, w_fi(d), R), fi_b = pref(A_FI + d, w_fi(d), wb + 1);
-        const u64 ot = pref(A_OT, w_fi(d) + 1, wb + 1) - pref(A_OT, w_fo(d) + 1, wa);
-        if (!carries(fo_a - fo_L, bwo[d], x1000) || !carries(fi_R - fi_b, bwi[d], x1000)) continue;
-        const u64 hi = __umul64hi(s, ot), lo = s * ot;
-        if (gt128(hi, lo, uhi, ulo)) { uhi = hi; ulo = lo; }
-        if (!have) {                            // flash first; host only if flash cannot take it
-          have = true;
-          if ((hi | lo) != 0 && better(hi, lo, id.x, m_hi, m_lo, m_cand)) {
-            m_hi = hi; m_lo = lo; m_cand = id.x; m_tensor = id.y; m_pos = p; m_dest = d;
-            m_L1 = L1; m_R = R; m_a = wa; m_b = wb; m_s = s; m_fo = fo_L; m_fi = fi_R;
+      const bool v0 = A.z <= A.w, v1 = B.x <= B.y;
+      u64 h0 = 0, l0 = 0, h1 = 0, l1 = 0, fo_L = 0, fi_R = 0;
+      bool ok0 = false, ok1 = false;
+      if (v0 || v1) {
+        const bool sL = L1 >= K, sR = R >= K;
+        const u32 jL = sL ? L1 - K : L1, jR = sR ? R - K : R;
+        const u32 cL = jL >> tl.shift_ch, cR = jR >> tl.shift_ch;
+        ulonglong2 qL, qR, qa, qb;
+        u64 fo0_L = 0, fi0_R = 0, fo1_L = 0, fi1_R = 0;
+        // flash
+        bool sa0 = false, sb0 = false; u32 ca0 = 0, cb0 = 0;
+        ulonglong2 qa0 = {0, 0}, qb0 = {0, 0}, qL0 = {0, 0}, qR0 = {0, 0};
+        if (v0) {
+          sa0 = A.z >= K; sb0 = A.w + 1 >= K;
+          const u32 ja = sa0 ? A.z - K : A.z, jb = sb0 ? A.w + 1 - K : A.w + 1;
+          ca0 = ja >> tl.shift_ch; cb0 = jb >> tl.shift_ch;
+          qL0 = ld2(tl.px + (u64)jL * PX + 0); qR0 = ld2(tl.px + (u64)jR * PX + 4);
+          qa0 = ld2(tl.px + (u64)ja * PX + 0); qb0 = ld2(tl.px + (u64)jb * PX + 4);
+        }
+        bool sa1 = false, sb1 = false; u32 ca1 = 0, cb1 = 0;
+        ulonglong2 qa1 = {0, 0}, qb1 = {0, 0}, qL1 = {0, 0}, qR1 = {0, 0};
+        if (v1) {
+          sa1 = B.x >= K; sb1 = B.y + 1 >= K;
+          const u32 ja = sa1 ? B.x - K : B.x, jb = sb1 ? B.y + 1 - K : B.y + 1;
+          ca1 = ja >> tl.shift_ch; cb1 = jb >> tl.shift_ch;
+          qL1 = ld2(tl.px + (u64)jL * PX + 2); qR1 = ld2(tl.px + (u64)jR * PX + 6);
+          qa1 = ld2(tl.px + (u64)ja * PX + 2); qb1 = ld2(tl.px + (u64)jb * PX + 6);
+        }
+        (void)qL; (void)qR; (void)qa; (void)qb;
+        bool f0 = false, f1 = false;                     // the channel can still carry it
+        if (v0) {
+          fo0_L = (sL ? allFO0 : 0ull) + bFO0[cL] + qL0.x; fi0_R = (sR ? allFI0 : 0ull) + bFI0[cR] + qR0.x;
+          const u64 fo_a = (sa0 ? allFO0 : 0ull) + bFO0[ca0] + qa0.x, fi_b = (sb0 ? allFI0 : 0ull) + bFI0[cb0] + qb0.x;
+          f0 = carries(fo_a - fo0_L, bwo0, x1000) && carries(fi0_R - fi_b, bwi0, x1000);
+          if (f0) {
+            const u64 ot = ((sb0 ? allOT : 0ull) + bOT[cb0] + qb0.y) - ((sa0 ? allOT : 0ull) + bOT[ca0] + qa0.y);
+            h0 = __umul64hi(s, ot); l0 = s * ot;
           }
         }
+        if (v1) {
+          fo1_L = (sL ? allFO1 : 0ull) + bFO1[cL] + qL1.x; fi1_R = (sR ? allFI1 : 0ull) + bFI1[cR] + qR1.x;
+          const u64 fo_a = (sa1 ? allFO1 : 0ull) + bFO1[ca1] + qa1.x, fi_b = (sb1 ? allFI1 : 0ull) + bFI1[cb1] + qb1.x;
+          f1 = carries(fo_a - fo1_L, bwo1, x1000) && carries(fi1_R - fi_b, bwi1, x1000);
+          if (f1) {
+            const u64 ot = ((sb1 ? allOT : 0ull) + bOT[cb1] + qb1.y) - ((sa1 ? allOT : 0ull) + bOT[ca1] + qa1.y);
+            h1 = __umul64hi(s, ot); l1 = s * ot;
+          }
+        }
+        ok0 = f0; ok1 = f1;
+        // strike what can never count again
+        const bool keep1 = f1 && (h1 | l1) != 0;
+        const bool keep0 = f0 && (keep1 || (h0 | l0) != 0);
+        if (v0 && !keep0) a.cd.A[cur.p] = make_uint4(L1, R, 1u, 0u);
+        if (v1 && !keep1) a.cd.B[cur.p] = make_uint4(1u, 0u, B.z, B.w);
+        fo_L = ok0 ? fo0_L : fo1_L; fi_R = ok0 ? fi0_R : fi1_R;
       }
-      const u32 k = wave_max(upkey(uhi, ulo));
-      if (lane == 0 && k) atomicMax(&keys[t], k);
+      const bool one = gt128(h1, l1, h0, l0);
+      const u32 k = wave_max(upkey(one ? h1 : h0, one ? l1 : l0));
+      if (lane == 0 && k) atomicMax(&keys[cur.t], k);
+      if (ok0 || ok1) {                          // flash first; host only if flash cannot take it
+        const u32 d = ok0 ? 0u : 1u;
+        const u64 hi = d ? h1 : h0, lo = d ? l1 : l0;
+        if ((hi | lo) != 0 && better(hi, lo, cur.id.x, mine.hi, mine.lo, mine.cand)) {
+          mine.hi = hi; mine.lo = lo; mine.cand = cur.id.x; mine.tensor = cur.id.y; mine.pos = cur.p; mine.dest = d;
+          mine.L1 = L1; mine.R = R; mine.a = d ? B.x : A.z; mine.b = d ? B.y : A.w; mine.s = s;
+          mine.fo_base = fo_L; mine.fi_end = fi_R;
+        }
+      }
+      u = un;
+      cur = nxt;
     }
     if (tid == 0) S->units += nunits;
   };
 
-  // block-wide arg-max of the threads' best; the owner publishes the winner
+  // block-wide arg-max of the threads' best (two barriers); refreshes the group bounds in between
   auto reduce_best = [&]() {
-    Best x; x.hi = m_hi; x.lo = m_lo; x.cand = m_cand;
-#pragma unroll
-    for (int o = G10_WAVE / 2; o > 0; o >>= 1) {
-      const u64 yh = __shfl_xor(x.hi, o, G10_WAVE), yl = __shfl_xor(x.lo, o, G10_WAVE);
-      const u32 yc = __shfl_xor(x.cand, o, G10_WAVE);
-      if (better(yh, yl, yc, x.hi, x.lo, x.cand)) { x.hi = yh; x.lo = yl; x.cand = yc; }
+    const u32 bl = wave_best_lane(mine.hi, mine.lo, mine.cand);
+    if (bl == NONE32) { if (lane == 0) { S->wave_win[wave].hi = 0; S->wave_win[wave].lo = 0; S->wave_win[wave].cand = NONE32; } }
+    else if (lane == bl) S->wave_win[wave] = mine;
+    __syncthreads();                               // all tile bounds and wavefront winners are in LDS
+    const u32 ntl = S->ntl;
+    for (u32 i = wave; i < ntl; i += LW) {          // bounds of the groups that hold re-scored tiles
+      const u32 g = tlist[i] >> 6, t = g * 64 + lane;
+      const u32 k = wave_max(t < nt ? keys[t] : 0u);
+      if (lane == 0) skeys[g] = k;
     }
-    if (lane == 0) { S->wave_hi[wave] = x.hi; S->wave_lo[wave] = x.lo; S->wave_cand[wave] = x.cand; }
-    __syncthreads();
-    x.hi = S->wave_hi[0]; x.lo = S->wave_lo[0]; x.cand = S->wave_cand[0];
-    for (u32 w = 1; w < LW; ++w)
-      if (better(S->wave_hi[w], S->wave_lo[w], S->wave_cand[w], x.hi, x.lo, x.cand)) { x.hi = S->wave_hi[w]; x.lo = S->wave_lo[w]; x.cand = S->wave_cand[w]; }
-    if ((x.hi | x.lo) != 0 && m_cand == x.cand && m_hi == x.hi && m_lo == x.lo) {
-      S->whi = m_hi; S->wlo = m_lo; S->cand = m_cand; S->tensor = m_tensor; S->pos = m_pos; S->dest = m_dest;
-      S->L1 = m_L1; S->R = m_R; S->a = m_a; S->b = m_b; S->s = m_s; S->fo_base = m_fo; S->fi_end = m_fi;
-      S->tau_o = ceil_div_x1000(m_s, m_dest ? bwo[1] : bwo[0]); S->tau_i = ceil_div_x1000(m_s, m_dest ? bwi[1] : bwi[0]);
+    if (wave == 0) {
+      u64 h = 0, l = 0;
+      u32 c = NONE32;
+      if (lane < LW) { h = S->wave_win[lane].hi; l = S->wave_win[lane].lo; c = S->wave_win[lane].cand; }
+      const u32 w = wave_best_lane(h, l, c);
+      if (w == NONE32) { if (lane == 0) { S->win.hi = 0; S->win.lo = 0; } }
+      else {
+        if (lane == 0) {
+          S->win = S->wave_win[w];
+          S->tau_o = ceil_div_x1000(S->wave_win[w].s, S->wave_win[w].dest ? bwo1 : bwo0);
+        }
+        if (lane == 1) S->tau_i = ceil_div_x1000(S->wave_win[w].s, S->wave_win[w].dest ? bwi1 : bwi0);
+      }
     }
-    if (tid == 0 && (x.hi | x.lo) == 0) { S->whi = 0; S->wlo = 0; }
     __syncthreads();
   };
 
   // ---- chunk jobs: one wavefront rewrites one chunk of one array ------------------------
   auto run_jobs = [&]() {
     const u32 nj = S->njobs;
-    const u32 d = S->dest, L1 = S->L1, R = S->R, wa = S->a, wb = S->b;
-    const u64 s = S->s, tau_o = S->tau_o, tau_i = S->tau_i, fo_base = S->fo_base, fi_end = S->fi_end;
+    const u32 d = S->win.dest, L1 = S->win.L1, R = S->win.R, wa = S->win.a, wb = S->win.b;
+    const u64 s = S->win.s, tau_o = S->tau_o, tau_i = S->tau_i, fo_base = S->win.fo_base, fi_end = S->win.fi_end;
     for (u32 jb = wave; jb < nj; jb += LW) {
       const u32 type = jobs[jb] >> 16, c = jobs[jb] & 0xffffu;
       const u32 s0 = c * CH;
       if (type == J_FO || type == J_FI) {
+        // channel time of the window is taken from this chunk's slots; the free-time prefix
+        // of the slots after the first window slot is rewritten (scans of the old and new values)
         const bool out = type == J_FO;
         const u32 arr = (out ? A_FO : A_FI) + d, w = out ? w_fo(d) : w_fi(d);
         u64* fr = tl.fre + (u64)((out ? 0u : 2u) + d) * tl.Kp;
         const u64 bc = base[(u64)arr * nb1 + c], ball = base[(u64)arr * nb1 + nch];
         const u32 x = out ? L1 : wb + 1, y = out ? wa - 1 : R - 1;
-        u64 carry = 0;
+        u64 carry_old = 0, carry = 0;
+        u32 first = NONE32;                              // first window slot of the chunk seen so far
         for (u32 st = 0; st < tl.spt; ++st) {
           const u32 j0 = s0 + st * 256u + lane * 4u;
           u64 f[4];
-          u64 lsum = 0;
+          u32 jj[4];
+          u64 osum = 0;
+          u32 myfirst = NONE32;
 #pragma unroll
           for (u32 i = 0; i < 4; ++i) {
             const u32 j = j0 + i;
-            f[i] = 0;
-            if (j < K) {
-              f[i] = fr[j];
-              const u32 jj = in_doubled(j, K, x, y);
-              if (jj != NONE32) {
-                const u64 before_slot = (jj >= K ? ball : 0ull) + bc + tl.px[(u64)j * PX + w];   // free time before slot jj
-                u64 take;
-                if (out) {                         // eviction: earliest free time of the window first
-                  const u64 before = before_slot - fo_base;
-                  const u64 used = before < tau_o ? before : tau_o;
-                  take = f[i] < tau_o - used ? f[i] : tau_o - used;
-                } else {                           // prefetch: latest free time first
-                  const u64 after = fi_end - (before_slot + f[i]);
-                  const u64 used = after < tau_i ? after : tau_i;
-                  take = f[i] < tau_i - used ? f[i] : tau_i - used;
-                }
-                if (take) { f[i] -= take; fr[j] = f[i]; }
+            f[i] = j < K ? fr[j] : 0ull;
+            jj[i] = j < K ? in_doubled(j, K, x, y) : NONE32;
+            if (jj[i] != NONE32 && myfirst == NONE32) myfirst = j;
+            osum += f[i];
+          }
+          const u64 oinc = wave_scan_incl(osum);
+          u64 orun = carry_old + oinc - osum;            // old free time of the chunk before this lane's slots
+          carry_old += wave_last(oinc);
+          const u32 stfirst = wave_min(myfirst);
+          if (first == NONE32) first = stfirst;
+          u64 lsum = 0;
+#pragma unroll
+          for (u32 i = 0; i < 4; ++i) {
+            if (jj[i] != NONE32) {
+              const u64 before_slot = (jj[i] >= K ? ball : 0ull) + bc + orun;    // free time before slot jj
+              u64 take;
+              if (out) {                           // eviction: earliest free time of the window first
+                const u64 before = before_slot - fo_base;
+                const u64 used = before < tau_o ? before : tau_o;
+                take = f[i] < tau_o - used ? f[i] : tau_o - used;
+              } else {                             // prefetch: latest free time first
+                const u64 after = fi_end - (before_slot + f[i]);
+                const u64 used = after < tau_i ? after : tau_i;
+                take = f[i] < tau_i - used ? f[i] : tau_i - used;
               }
+              orun += f[i];
+              if (take) { f[i] -= take; fr[j0 + i] = f[i]; }
+            } else {
+              orun += f[i];
             }
             lsum += f[i];
           }
@@ -579,45 +723,67 @@ __global__ __launch_bounds__(LB) void k_loop(LoopArgs a) {
 #pragma unroll
           for (u32 i = 0; i < 4; ++i) {
             const u32 j = j0 + i;
-            if (j < K) { tl.px[(u64)j * PX + w] = run; run += f[i]; }
+            if (j < K && first != NONE32 && j > first) tl.px[(u64)j * PX + w] = run;
+            run += f[i];
           }
-          carry += __shfl(inc, G10_WAVE - 1, G10_WAVE);
+          carry += wave_last(inc);
         }
         if (lane == 0) tot[(u64)arr * nch + c] = carry;
       } else if (type == J_P_PART || type == J_P_FULL) {
+        // pressure of the chunk's slots; where a slot drops under the capacity the
+        // over-capacity prefix after it is rewritten
         const u64 lz = lazyP[c];
-        u64 carry = 0, mn = NONE64;
+        u64 mn = NONE64;
+        u32 first = NONE32;                              // first slot that dropped under the capacity
         for (u32 st = 0; st < tl.spt; ++st) {
           const u32 j0 = s0 + st * 256u + lane * 4u;
-          u64 v[4];
-          u64 lsum = 0;
+          u32 myfirst = NONE32;
 #pragma unroll
           for (u32 i = 0; i < 4; ++i) {
             const u32 j = j0 + i;
-            v[i] = 0;
             if (j < K) {
               u64 p = tl.P[j];
-              if (type == J_P_PART && in_doubled(j, K, wa, wb) != NONE32) { p -= s; tl.P[j] = p; }
+              const bool hit = type == J_P_PART && in_doubled(j, K, wa, wb) != NONE32;
+              const u64 before = p - lz + (type == J_P_FULL ? s : 0ull);     // pressure before this eviction
+              if (hit) { p -= s; tl.P[j] = p; }
               const u64 act = p - lz;
-              if (act > cap) { v[i] = tl.dur[j]; mn = act < mn ? act : mn; }
+              if (act > cap) mn = act < mn ? act : mn;
+              else if (before > cap && myfirst == NONE32) myfirst = j;
             }
-            lsum += v[i];
           }
-          const u64 inc = wave_scan_incl(lsum);
-          u64 run = carry + inc - lsum;
+          const u32 stfirst = wave_min(myfirst);
+          if (first == NONE32) first = stfirst;
+        }
+        mn = wave_min(mn);
+        if (lane == 0) minOver[c] = mn;
+        if (first != NONE32) {                           // rewrite the prefix of the slots after it
+          u64 carry = 0;
+          for (u32 st = 0; st < tl.spt; ++st) {
+            const u32 j0 = s0 + st * 256u + lane * 4u;
+            u64 v[4];
+            u64 lsum = 0;
 #pragma unroll
-          for (u32 i = 0; i < 4; ++i) {
-            const u32 j = j0 + i;
-            if (j < K) {
-              u64* rec = tl.px + (u64)j * PX;
-              rec[1] = run; rec[3] = run; rec[5] = run; rec[7] = run;
+            for (u32 i = 0; i < 4; ++i) {
+              const u32 j = j0 + i;
+              v[i] = 0;
+              if (j < K && tl.P[j] - lz > cap) v[i] = tl.dur[j];
+              lsum += v[i];
+            }
+            const u64 inc = wave_scan_incl(lsum);
+            u64 run = carry + inc - lsum;
+#pragma unroll
+            for (u32 i = 0; i < 4; ++i) {
+              const u32 j = j0 + i;
+              if (j < K && j > first) {
+                ulonglong2* rec = reinterpret_cast<ulonglong2*>(tl.px + (u64)j * PX);
+                rec[0].y = run; rec[1].y = run; rec[2].y = run; rec[3].y = run;   // the four copies of OT
+              }
               run += v[i];
             }
+            carry += wave_last(inc);
           }
-          carry += __shfl(inc, G10_WAVE - 1, G10_WAVE);
+          if (lane == 0) { tot[(u64)A_OT * nch + c] = carry; S->ot_changed = 1; }
         }
-        mn = wave_min64(mn);
-        if (lane == 0) { tot[(u64)A_OT * nch + c] = carry; minOver[c] = mn; S->ot_changed = 1; }
       } else {                                     // J_H: add the tensor; J_HQ: only ask for the maximum
         const u64 lz = lazyH[c];
         u64 m_all = 0, m_cov = 0;
@@ -643,6 +809,7 @@ __global__ __launch_bounds__(LB) void k_loop(LoopArgs a) {
     if (tid == 0) S->jobs += nj;
   };
 
+  __syncthreads();
   // ---- passes ------------------------------------------------------------------------
   u32 passes = 0;
   while (true) {
@@ -651,93 +818,114 @@ __global__ __launch_bounds__(LB) void k_loop(LoopArgs a) {
     if (max_iter && S->n_iter >= max_iter) { if (tid == 0) { S->done = 1; S->status = G10_TRUNCATED; } break; }
     if (passes >= a.pass_budget) break;
     ++passes;
-    m_hi = 0; m_lo = 0; m_cand = NONE32;
+    mine.hi = 0; mine.lo = 0; mine.cand = NONE32;
 
-    // rank: tiles that can hold the winner, first against a guess, then against the best found
-    u32 thr = S->thr_key;
-    __syncthreads();                               // everyone has read the loop conditions and thr
-    build_list(thr ? thr : 1u);
-    if (S->ntl == 0 && S->restmax != 0) {          // the guess was too high: start from the largest bound
-      thr = S->restmax;
-      __syncthreads();
+    // rank: score the tiles whose bound reaches a threshold, lower the threshold to the best
+    // benefit found, repeat until no tile left out could hold an equal or better candidate
+    u32 thr = S->thr_key ? S->thr_key : NONE32;
+    u32 rounds = 0;
+    __syncthreads();                               // the loop conditions and thr are read
+    while (true) {
       build_list(thr);
-    }
-    const u32 n1 = S->ntl;
-    score_list();
-    reduce_best();
-    {
-      const u32 kb = upkey(S->whi, S->wlo);
-      const u32 need = kb ? kb : 1u;
-      if (S->restmax >= need) {                    // a tile left out may hold an equal or better one
+      const u32 ntl = S->ntl, rest = S->restmax;
+      const u32 found = upkey(S->win.hi, S->win.lo);     // meaningful after the first scoring round of the pass
+      if (ntl == 0) {
+        if ((rounds && found) || rest == 0) break;       // nothing left that could win
+        thr = rest;                                      // strictly lower than before: start from the largest bound left
         __syncthreads();
-        build_list(need);
-        if (tid == 0) S->second += 1;
-        score_list();
-        reduce_best();
+        continue;
       }
+      PHASE(0);
+      score_list();
+      PHASE(1);
+      reduce_best();
+      PHASE(2);
+      ++rounds;
+      const u32 kb = upkey(S->win.hi, S->win.lo);
+      const u32 need = kb ? kb : 1u;
+      if (rest < need) break;                            // every tile left out is below the best found
+      // a tile left out may hold an equal or better one; with nothing found yet, step down by about 2^-4
+      thr = kb ? kb : (rest > (1u << 19) ? rest - (1u << 19) : 1u);
+      if (tid == 0) S->second += 1;
+      __syncthreads();
     }
-    // forget which tiles were scored in this pass
-    for (u32 i = tid; i < (nt + 31) / 32; i += LB) mark[i] = 0;
-    (void)n1;
+    if (rounds == 0 && tid == 0) { S->win.hi = 0; S->win.lo = 0; }
+    for (u32 i = tid; i < ns; i += LB) smark[i] = 0;     // forget which tiles were scored in this pass
+    __syncthreads();
+    PHASE(3);
 
-    const bool none = (S->whi | S->wlo) == 0;
+    const bool none = (S->win.hi | S->win.lo) == 0;
+    const u32 d = S->win.dest, L1 = S->win.L1, R = S->win.R, wa = S->win.a, wb = S->win.b;
+    const u64 s = S->win.s;
     if (tid == 0) { S->n_iter += 1; S->n_evals += C - S->n_mig - S->n_drop; S->hq = 0; S->njobs = 0; S->ot_changed = 0; }
     __syncthreads();
     if (none) { if (tid == 0) { S->done = 1; S->status = G10_RESIDUAL; } break; }
 
-    const u32 d = S->dest, L1 = S->L1, R = S->R, wa = S->a, wb = S->b;
-    const u64 s = S->s;
+    // which chunks the period, its absent window and its transfer windows cover
+    u32 cvE = 0, cvW = 0, cvA = 0, cvP = 0, len = 0;
+    if (tid < nch) {
+      cvE = cover(tid, CH, K, L1, wa - 1, len);
+      cvW = cover(tid, CH, K, wb + 1, R - 1, len);
+      cvA = cover(tid, CH, K, wa, wb, len);
+      cvP = cvE + cvA + cvW;                             // the period interior [L1, R - 1]
+    }
     // host memory must hold the tensor during the whole period
     bool room = true;
     if (d == G10_HOST) {
-      if (tid < nch) {
-        u32 len;
-        const u32 cv = cover(tid, CH, K, L1, R - 1, len);
-        if (cv == len) atomicMax((unsigned long long*)&S->hq, (unsigned long long)hmax[tid]);
-        else if (cv) jobs[atomicAdd(&S->njobs, 1u)] = ((u32)J_HQ << 16) | tid;
+      if (tid < ((nch + 63u) & ~63u)) {                  // bound: the maxima of all chunks the period touches
+        const u64 m = wave_max(cvP ? hmax[tid] : 0ull);
+        if (lane == 0 && m) atomicMax((unsigned long long*)&S->hq, (unsigned long long)m);
       }
       __syncthreads();
-      run_jobs();
-      __syncthreads();
       room = s <= host_cap && S->hq <= host_cap - s;
-      __syncthreads();
-      if (tid == 0) S->njobs = 0;
+      if (!room) {                                       // exact: chunks cut by the period ends slot by slot
+        __syncthreads();
+        if (tid == 0) S->hq = 0;
+        __syncthreads();
+        if (cvP == len && cvP) atomicMax((unsigned long long*)&S->hq, (unsigned long long)hmax[tid]);
+        else if (cvP) jobs[atomicAdd(&S->njobs, 1u)] = ((u32)J_HQ << 16) | tid;
+        __syncthreads();
+        run_jobs();
+        __syncthreads();
+        room = s <= host_cap && S->hq <= host_cap - s;
+        __syncthreads();
+        if (tid == 0) S->njobs = 0;
+        __syncthreads();
+      }
     }
+    PHASE(4);
     if (tid == 0) {
-      const u32 p = S->pos;
-      a.cd.A[p] = make_uint4(L1, R, 1u, 0u);       // the candidate leaves the live set
+      const u32 p = S->win.pos;
+      a.cd.A[p] = make_uint4(L1, R, 1u, 0u);             // the candidate leaves the live set
       a.cd.B[p] = make_uint4(1u, 0u, (u32)s, (u32)(s >> 32));
       // first threshold of the next pass: a little under this benefit
-      u64 ghi = S->whi, glo = S->wlo;
+      u64 ghi = S->win.hi, glo = S->win.lo;
       const u64 dlo = (glo >> GUESS_SHIFT) | (ghi << (64 - GUESS_SHIFT)), dhi = ghi >> GUESS_SHIFT;
       const u64 nlo = glo - dlo;
       ghi = ghi - dhi - (glo < dlo ? 1ull : 0ull);
       S->thr_key = upkey(ghi, nlo);
       if (!room) {
-        g10_dropped dr; dr.iteration = S->n_iter - 1; dr.cand = S->cand; dr.reserved = 0;
+        g10_dropped dr; dr.iteration = S->n_iter - 1; dr.cand = S->win.cand; dr.reserved = 0;
         a.dropped[S->n_drop] = dr;
         S->n_drop += 1;
       } else {
         g10_migration mg;
-        mg.cand = S->cand; mg.tensor = S->tensor;
+        mg.cand = S->win.cand; mg.tensor = S->win.tensor;
         mg.evict_after = L1 - 1; mg.absent_first = wa % K; mg.absent_last = wb % K; mg.next_use = R % K;
         mg.dest = d; mg.wraps = R >= K ? 1u : 0u;
-        mg.size_bytes = s; mg.t_out_ns = S->tau_o; mg.t_in_ns = S->tau_i; mg.benefit_lo = S->wlo; mg.benefit_hi = S->whi;
+        mg.size_bytes = s; mg.t_out_ns = S->tau_o; mg.t_in_ns = S->tau_i; mg.benefit_lo = S->win.lo; mg.benefit_hi = S->win.hi;
         a.records[S->n_mig] = mg;
         S->n_mig += 1;
       }
     }
-    __syncthreads();
-    if (!room) continue;
+    if (!room) { __syncthreads(); continue; }
 
-    // commit: which chunks change, and how
+    // commit: whole chunks take a lazy add, the others a job
     if (tid < nch) {
       const u32 c = tid;
-      u32 len;
-      if (cover(c, CH, K, L1, wa - 1, len)) jobs[atomicAdd(&S->njobs, 1u)] = ((u32)J_FO << 16) | c;
-      if (cover(c, CH, K, wb + 1, R - 1, len)) jobs[atomicAdd(&S->njobs, 1u)] = ((u32)J_FI << 16) | c;
-      u32 cv = cover(c, CH, K, wa, wb, len);
-      if (cv == len) {                             // the whole chunk loses the tensor
+      if (cvE) jobs[atomicAdd(&S->njobs, 1u)] = ((u32)J_FO << 16) | c;
+      if (cvW) jobs[atomicAdd(&S->njobs, 1u)] = ((u32)J_FI << 16) | c;
+      if (cvA == len) {                                  // the whole chunk loses the tensor
         lazyP[c] += s;
         u64 mo = minOver[c];
         if (mo != NONE64) {
@@ -745,20 +933,37 @@ __global__ __launch_bounds__(LB) void k_loop(LoopArgs a) {
           minOver[c] = mo;
           if (mo <= cap) jobs[atomicAdd(&S->njobs, 1u)] = ((u32)J_P_FULL << 16) | c;   // a slot drops under the capacity
         }
-      } else if (cv) {
+      } else if (cvA) {
         jobs[atomicAdd(&S->njobs, 1u)] = ((u32)J_P_PART << 16) | c;
       }
       if (d == G10_HOST) {
-        cv = cover(c, CH, K, L1, R - 1, len);
-        if (cv == len) { lazyH[c] += s; hmax[c] += s; }
-        else if (cv) jobs[atomicAdd(&S->njobs, 1u)] = ((u32)J_H << 16) | c;
+        if (cvP == len) { lazyH[c] += s; hmax[c] += s; }
+        else if (cvP) jobs[atomicAdd(&S->njobs, 1u)] = ((u32)J_H << 16) | c;
       }
     }
     __syncthreads();
+    PHASE(6);
     run_jobs();
     __syncthreads();
-    if (S->ot_changed) { const u32 a3[3] = {A_OT, A_FO + d, A_FI + d}; scan_bases(a3, 3); }
-    else { const u32 a2[2] = {A_FO + d, A_FI + d}; scan_bases(a2, 2); }
+    PHASE(7);
+    // level 1: a transfer window inside one chunk lowers every later chunk's base by the
+    // transfer time; otherwise (and for the over-capacity time, if it changed) scan again
+    {
+      const u32 eA = (L1 >= K ? L1 - K : L1) >> tl.shift_ch, eB = (wa - 1 >= K ? wa - 1 - K : wa - 1) >> tl.shift_ch;
+      const u32 pA = (wb + 1 >= K ? wb + 1 - K : wb + 1) >> tl.shift_ch, pB = (R - 1 >= K ? R - 1 - K : R - 1) >> tl.shift_ch;
+      const bool oneE = eA == eB && !(L1 < K && wa - 1 >= K), oneP = pA == pB && !(wb + 1 < K && R - 1 >= K);
+      const bool ot = S->ot_changed != 0;
+      if (oneE && oneP && !ot) {
+        if (tid < nch) {
+          if (tid > eA) base[(u64)(A_FO + d) * nb1 + tid] -= S->tau_o;
+          if (tid > pA) base[(u64)(A_FI + d) * nb1 + tid] -= S->tau_i;
+        }
+        if (tid == 0) { base[(u64)(A_FO + d) * nb1 + nch] -= S->tau_o; base[(u64)(A_FI + d) * nb1 + nch] -= S->tau_i; }
+        __syncthreads();
+      } else if (ot) scan_bases(A_OT, A_FO + d, A_FI + d, 3);
+      else scan_bases(A_FO + d, A_FI + d, 0, 2);
+    }
+    PHASE(8);
   }
   __syncthreads();
 
@@ -770,6 +975,7 @@ __global__ __launch_bounds__(LB) void k_loop(LoopArgs a) {
     ctl->n_iter = S->n_iter; ctl->n_mig = S->n_mig; ctl->n_drop = S->n_drop; ctl->n_evals = S->n_evals;
     ctl->thr_key = S->thr_key; ctl->status = S->status; ctl->done = S->done;
     ctl->overtime_after = base[(u64)A_OT * nb1 + nch];
+    for (u32 i = 0; i < 12; ++i) ctl->phase[i] += S->phase[i];
     ctl->units_scored += S->units; ctl->second_rounds += S->second; ctl->jobs_run += S->jobs; ctl->launches += 1;
   }
 }
@@ -896,10 +1102,11 @@ static int work_alloc(g10_plan_s* h) {
 }
 
 static size_t loop_lds_bytes(u32 nch, u32 nt) {
+  const size_t ns = (nt + 63) / 64;
   size_t b = 0;
-  b += (size_t)N_ARR * (nch + 1) * 8 + (size_t)N_ARR * nch * 8 + (size_t)4 * nch * 8 + (size_t)3 * LW * 8;
+  b += ((size_t)N_ARR * (nch + 1) + (size_t)N_ARR * nch + (size_t)4 * nch + ns + (size_t)4 * LW) * 8;
   b += sizeof(Shared);
-  b += (size_t)nt * 4 + ((size_t)4 * nch + 8) * 4 + (size_t)((nt + 31) / 32) * 4 + (size_t)nt * 2;
+  b += ((size_t)nt + ns + (size_t)4 * nch + 8) * 4 + (size_t)nt * 2;
   return (b + 15) & ~(size_t)15;
 }
 
@@ -1009,6 +1216,13 @@ int plan_run(g10_plan_s* h, const g10_params* p, g10_result* out) {
   if (timed_full) G10_HIP(hipEventElapsedTime(&full_ms, w->ev[2], w->ev[3]));
   if (timed_loop) G10_HIP(hipEventElapsedTime(&loop_ms, w->ev[4], w->ev[5]));
 
+#ifdef G10_PHASE_TIMERS
+  if (getenv("G10_LOG")) {
+    fprintf(stderr, "g10: loop phases (us per pass):");
+    for (int i = 0; i < 9; ++i) fprintf(stderr, " %d:%.2f", i, hc.phase[i] / 100.0 / (double)(hc.n_iter ? hc.n_iter : 1));
+    fprintf(stderr, "\n");
+  }
+#endif
   memset(out, 0, sizeof *out);
   out->status = (int32_t)hc.status;
   out->n_migrations = hc.n_mig; out->n_iterations = hc.n_iter; out->n_dropped = hc.n_drop; out->n_cand_evals = hc.n_evals;
