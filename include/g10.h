@@ -127,6 +127,7 @@ typedef struct {
   uint64_t score_full_cands;   /* candidates it streamed (those with a valid window)   */
   double loop_ms;              /* the greedy loop                                      */
   uint64_t loop_launches;      /* launches of the loop kernel                          */
+  uint64_t loop_retiles;       /* times the candidate list was put back into score order */
   uint64_t loop_cands_scored;  /* candidates re-scored inside the loop (tiles * 256)   */
   uint64_t loop_second_rounds; /* passes that needed a second scoring round            */
   uint64_t loop_chunk_jobs;    /* timeline chunks rewritten slot by slot               */

@@ -60,7 +60,8 @@ class _Result(C.Structure):
                 ("overtime_before_ns", C.c_uint64), ("overtime_after_ns", C.c_uint64),
                 ("migrations", C.c_void_p), ("dropped", C.c_void_p), ("pressure_after", C.c_void_p),
                 ("plan_ms", C.c_double), ("score_full_ms", C.c_double), ("score_full_cands", C.c_uint64),
-                ("loop_ms", C.c_double), ("loop_launches", C.c_uint64), ("loop_cands_scored", C.c_uint64),
+                ("loop_ms", C.c_double), ("loop_launches", C.c_uint64), ("loop_retiles", C.c_uint64),
+                ("loop_cands_scored", C.c_uint64),
                 ("loop_second_rounds", C.c_uint64), ("loop_chunk_jobs", C.c_uint64)]
 
 

@@ -81,7 +81,8 @@ struct Ctl {
   u32 done, status;
   u64 n_iter, n_mig, n_drop, n_evals;
   u64 overtime_before, overtime_after;
-  u32 thr_key, pad0;          // first threshold of the next pass (0: use the largest tile bound)
+  u32 thr_key;                // first threshold of the next pass (0: use the largest tile bound)
+  u32 n_live;                 // candidates that could still score at the last re-scoring
   // statistics
   u64 units_scored, second_rounds, jobs_run, launches;
   u64 phase[12];              // wall-clock ticks per phase of the loop (only with G10_PHASE_TIMERS)
@@ -292,6 +293,92 @@ __global__ __launch_bounds__(G10_BLOCK) void k_score_full(Cands cd, u32 n, const
   sortkeys[p] = ((u64)(0x7fffffu - (k >> 8)) << posbits) | p;      // descending score, then analysis order
 }
 
+// ---------------------------------------------------------------------------
+// score of one candidate against the current timelines
+// ---------------------------------------------------------------------------
+struct Machine { u64 bwo0, bwo1, bwi0, bwi1; };
+
+struct PrefixView {           // slot records in HBM / L2, level 1 in LDS
+  const u64* px;
+  const u64* base;            // [5][nch + 1]
+  u32 K, nch, shift_ch;
+};
+
+struct Score {
+  u64 h0, l0, h1, l1;         // benefit per destination (0 if it cannot be used now)
+  u64 fo_L, fi_R;             // of the policy's destination: free out-channel time before L1, in-channel before R
+  bool ok0, ok1;              // the destination's channels can carry the transfer now
+  bool strike0, strike1;      // the destination can never count again
+};
+
+__device__ __forceinline__ ulonglong2 ld2(const u64* p) { return *reinterpret_cast<const ulonglong2*>(p); }
+
+// Both destinations' record pairs are gathered before anything is used.  A
+// destination is struck when its channel cannot carry the transfer any more
+// (reservations only grow); host also when no over-capacity time is left in
+// its window (pressure only falls), flash then too if host is gone: while
+// host could still score, a feasible flash window keeps the policy on flash.
+__device__ __forceinline__ Score score_candidate(const PrefixView& pv, const Machine& mc, const uint4 A, const uint4 B) {
+  Score r;
+  r.h0 = r.l0 = r.h1 = r.l1 = r.fo_L = r.fi_R = 0;
+  r.ok0 = r.ok1 = r.strike0 = r.strike1 = false;
+  const bool v0 = A.z <= A.w, v1 = B.x <= B.y;
+  if (!(v0 || v1)) return r;
+  const u32 K = pv.K, nb1 = pv.nch + 1;
+  const u64 s = ((u64)B.w << 32) | B.z, x1000 = s * 1000ull;
+  const u32 L1 = A.x, R = A.y;
+  const bool sL = L1 >= K, sR = R >= K;
+  const u32 jL = sL ? L1 - K : L1, jR = sR ? R - K : R;
+  const u32 cL = jL >> pv.shift_ch, cR = jR >> pv.shift_ch;
+  const u64* bOT = pv.base + (u64)A_OT * nb1;
+  bool sa0 = false, sb0 = false, sa1 = false, sb1 = false;
+  u32 ca0 = 0, cb0 = 0, ca1 = 0, cb1 = 0;
+  ulonglong2 qa0 = {0, 0}, qb0 = {0, 0}, qL0 = {0, 0}, qR0 = {0, 0}, qa1 = {0, 0}, qb1 = {0, 0}, qL1 = {0, 0}, qR1 = {0, 0};
+  if (v0) {
+    sa0 = A.z >= K; sb0 = A.w + 1 >= K;
+    const u32 ja = sa0 ? A.z - K : A.z, jb = sb0 ? A.w + 1 - K : A.w + 1;
+    ca0 = ja >> pv.shift_ch; cb0 = jb >> pv.shift_ch;
+    qL0 = ld2(pv.px + (u64)jL * PX + 0); qR0 = ld2(pv.px + (u64)jR * PX + 4);      // {FO0, OT} {FI0, OT}
+    qa0 = ld2(pv.px + (u64)ja * PX + 0); qb0 = ld2(pv.px + (u64)jb * PX + 4);
+  }
+  if (v1) {
+    sa1 = B.x >= K; sb1 = B.y + 1 >= K;
+    const u32 ja = sa1 ? B.x - K : B.x, jb = sb1 ? B.y + 1 - K : B.y + 1;
+    ca1 = ja >> pv.shift_ch; cb1 = jb >> pv.shift_ch;
+    qL1 = ld2(pv.px + (u64)jL * PX + 2); qR1 = ld2(pv.px + (u64)jR * PX + 6);      // {FO1, OT} {FI1, OT}
+    qa1 = ld2(pv.px + (u64)ja * PX + 2); qb1 = ld2(pv.px + (u64)jb * PX + 6);
+  }
+  u64 fo0_L = 0, fi0_R = 0, fo1_L = 0, fi1_R = 0;
+  if (v0) {
+    const u64 *bFO = pv.base + (u64)(A_FO + 0) * nb1, *bFI = pv.base + (u64)(A_FI + 0) * nb1;
+    const u64 allFO = bFO[pv.nch], allFI = bFI[pv.nch], allOT = bOT[pv.nch];
+    fo0_L = (sL ? allFO : 0ull) + bFO[cL] + qL0.x; fi0_R = (sR ? allFI : 0ull) + bFI[cR] + qR0.x;
+    const u64 fo_a = (sa0 ? allFO : 0ull) + bFO[ca0] + qa0.x, fi_b = (sb0 ? allFI : 0ull) + bFI[cb0] + qb0.x;
+    r.ok0 = carries(fo_a - fo0_L, mc.bwo0, x1000) && carries(fi0_R - fi_b, mc.bwi0, x1000);
+    if (r.ok0) {
+      const u64 ot = ((sb0 ? allOT : 0ull) + bOT[cb0] + qb0.y) - ((sa0 ? allOT : 0ull) + bOT[ca0] + qa0.y);
+      r.h0 = __umul64hi(s, ot); r.l0 = s * ot;
+    }
+  }
+  if (v1) {
+    const u64 *bFO = pv.base + (u64)(A_FO + 1) * nb1, *bFI = pv.base + (u64)(A_FI + 1) * nb1;
+    const u64 allFO = bFO[pv.nch], allFI = bFI[pv.nch], allOT = bOT[pv.nch];
+    fo1_L = (sL ? allFO : 0ull) + bFO[cL] + qL1.x; fi1_R = (sR ? allFI : 0ull) + bFI[cR] + qR1.x;
+    const u64 fo_a = (sa1 ? allFO : 0ull) + bFO[ca1] + qa1.x, fi_b = (sb1 ? allFI : 0ull) + bFI[cb1] + qb1.x;
+    r.ok1 = carries(fo_a - fo1_L, mc.bwo1, x1000) && carries(fi1_R - fi_b, mc.bwi1, x1000);
+    if (r.ok1) {
+      const u64 ot = ((sb1 ? allOT : 0ull) + bOT[cb1] + qb1.y) - ((sa1 ? allOT : 0ull) + bOT[ca1] + qa1.y);
+      r.h1 = __umul64hi(s, ot); r.l1 = s * ot;
+    }
+  }
+  const bool keep1 = r.ok1 && (r.h1 | r.l1) != 0;
+  const bool keep0 = r.ok0 && (keep1 || (r.h0 | r.l0) != 0);
+  r.strike0 = v0 && !keep0;
+  r.strike1 = v1 && !keep1;
+  r.fo_L = r.ok0 ? fo0_L : fo1_L; r.fi_R = r.ok0 ? fi0_R : fi1_R;
+  return r;
+}
+
 // candidates into score order; the tile bound is the largest key of its members
 __global__ __launch_bounds__(G10_BLOCK) void k_tile_gather(const u64* __restrict__ sorted, u32 n, u32 n_pad, u32 posbits,
                                                           Cands src, const u32* __restrict__ key32, Cands dst,
@@ -314,6 +401,35 @@ __global__ __launch_bounds__(G10_BLOCK) void k_tile_gather(const u64* __restrict
   if (lane_id() == 0 && k) atomicMax(&tkeys[r >> tile_shift], k);
 }
 
+// Re-scores every candidate of the list against the current timelines (all
+// workgroups of the chip; used between launches of the loop kernel to put the
+// candidates back into score order).  Writes the 4-byte key and the sort key;
+// strikes dead destinations; counts the candidates that can still score.
+__global__ __launch_bounds__(G10_BLOCK) void k_rescore(Cands cd, u32 n, const u64* __restrict__ px, const u64* __restrict__ g_base,
+                                                      u32 K, u32 nch, u32 shift_ch, const Ctl* ctl, u32 posbits,
+                                                      u32* __restrict__ key32, u64* __restrict__ sortkeys, u32* __restrict__ n_live) {
+  extern __shared__ u64 lb[];                  // [5][nch + 1]
+  for (u32 i = threadIdx.x; i < N_ARR * (nch + 1); i += G10_BLOCK) lb[i] = g_base[i];
+  __syncthreads();
+  PrefixView pv; pv.px = px; pv.base = lb; pv.K = K; pv.nch = nch; pv.shift_ch = shift_ch;
+  Machine mc; mc.bwo0 = ctl->bw_out[0]; mc.bwo1 = ctl->bw_out[1]; mc.bwi0 = ctl->bw_in[0]; mc.bwi1 = ctl->bw_in[1];
+  u32 live = 0;
+  for (u32 p = blockIdx.x * G10_BLOCK + threadIdx.x; p < n; p += gridDim.x * G10_BLOCK) {
+    const uint4 A = cd.A[p], B = cd.B[p];
+    const Score r = score_candidate(pv, mc, A, B);
+    if (r.strike0) cd.A[p] = make_uint4(A.x, A.y, 1u, 0u);
+    if (r.strike1) cd.B[p] = make_uint4(1u, 0u, B.z, B.w);
+    const bool one = gt128(r.h1, r.l1, r.h0, r.l0);
+    const u32 k = upkey(one ? r.h1 : r.h0, one ? r.l1 : r.l0);
+    key32[p] = k;
+    sortkeys[p] = ((u64)(0x7fffffu - (k >> 8)) << posbits) | p;
+    live += k != 0;
+  }
+  __shared__ u32 tmp[G10_WAVES + 1];
+  live = block_sum(live, tmp);
+  if (threadIdx.x == 0 && live) atomicAdd(n_live, live);
+}
+
 // ---------------------------------------------------------------------------
 // the greedy loop
 // ---------------------------------------------------------------------------
@@ -321,7 +437,7 @@ struct LoopArgs {
   Cands cd;
   u32 n_pad, nt, tshift;      // tile = UNIT << tshift candidates
   Timelines tl;
-  u64 *g_tot, *g_lazyP, *g_minOver, *g_lazyH, *g_hmax;
+  u64 *g_tot, *g_lazyP, *g_minOver, *g_lazyH, *g_hmax, *g_base;
   u32* g_keys;
   Ctl* ctl;
   g10_migration* records;
@@ -388,8 +504,6 @@ __device__ __forceinline__ u32 in_doubled(u32 j, u32 K, u32 x, u32 y) {
   if (jj >= x && jj <= y) return jj;
   return NONE32;
 }
-
-__device__ __forceinline__ ulonglong2 ld2(const u64* p) { return *reinterpret_cast<const ulonglong2*>(p); }
 
 // The lane of the wavefront holding the best (benefit, lowest index), or NONE32
 // if every benefit is 0.  The 31-bit key decides unless several lanes share the
@@ -536,16 +650,11 @@ __global__ __launch_bounds__(LB) void k_loop(LoopArgs a) {
   // Scores the listed tiles: four wavefronts per 256 candidates, the next
   // candidate's record already in flight.  One workgroup has one texture
   // unit, about one cache line per clock: lanes whose candidate is dead load
-  // nothing, a destination that can never be used again (its channel cannot
-  // carry the transfer any more; for host also: no over-capacity time left in
-  // its window) is struck from the record so that later passes skip it.
+  // nothing, and struck destinations are written back so later passes skip them.
   auto score_list = [&]() {
     const u32 nunits = S->ntl << a.tshift;
-    const u64 allOT = base[(u64)A_OT * nb1 + nch];
-    const u64 allFO0 = base[(u64)(A_FO + 0) * nb1 + nch], allFO1 = base[(u64)(A_FO + 1) * nb1 + nch];
-    const u64 allFI0 = base[(u64)(A_FI + 0) * nb1 + nch], allFI1 = base[(u64)(A_FI + 1) * nb1 + nch];
-    const u64 *bOT = base + (u64)A_OT * nb1, *bFO0 = base + (u64)(A_FO + 0) * nb1, *bFO1 = base + (u64)(A_FO + 1) * nb1,
-              *bFI0 = base + (u64)(A_FI + 0) * nb1, *bFI1 = base + (u64)(A_FI + 1) * nb1;
+    PrefixView pv; pv.px = tl.px; pv.base = base; pv.K = K; pv.nch = nch; pv.shift_ch = tl.shift_ch;
+    Machine mc; mc.bwo0 = bwo0; mc.bwo1 = bwo1; mc.bwi0 = bwi0; mc.bwi1 = bwi1;
     u32 u = tid >> 8;
     CandV cur;
     if (u < nunits) cur = load_cand(u);
@@ -554,74 +663,26 @@ __global__ __launch_bounds__(LB) void k_loop(LoopArgs a) {
       CandV nxt;
       if (un < nunits) nxt = load_cand(un);
       const uint4 A = cur.A, B = cur.B;
-      const u64 s = ((u64)B.w << 32) | B.z, x1000 = s * 1000ull;
-      const u32 L1 = A.x, R = A.y;
-      const bool v0 = A.z <= A.w, v1 = B.x <= B.y;
-      u64 h0 = 0, l0 = 0, h1 = 0, l1 = 0, fo_L = 0, fi_R = 0;
-      bool ok0 = false, ok1 = false;
-      if (v0 || v1) {
-        const bool sL = L1 >= K, sR = R >= K;
-        const u32 jL = sL ? L1 - K : L1, jR = sR ? R - K : R;
-        const u32 cL = jL >> tl.shift_ch, cR = jR >> tl.shift_ch;
-        ulonglong2 qL, qR, qa, qb;
-        u64 fo0_L = 0, fi0_R = 0, fo1_L = 0, fi1_R = 0;
-        // flash
-        bool sa0 = false, sb0 = false; u32 ca0 = 0, cb0 = 0;
-        ulonglong2 qa0 = {0, 0}, qb0 = {0, 0}, qL0 = {0, 0}, qR0 = {0, 0};
-        if (v0) {
-          sa0 = A.z >= K; sb0 = A.w + 1 >= K;
-          const u32 ja = sa0 ? A.z - K : A.z, jb = sb0 ? A.w + 1 - K : A.w + 1;
-          ca0 = ja >> tl.shift_ch; cb0 = jb >> tl.shift_ch;
-          qL0 = ld2(tl.px + (u64)jL * PX + 0); qR0 = ld2(tl.px + (u64)jR * PX + 4);
-          qa0 = ld2(tl.px + (u64)ja * PX + 0); qb0 = ld2(tl.px + (u64)jb * PX + 4);
-        }
-        bool sa1 = false, sb1 = false; u32 ca1 = 0, cb1 = 0;
-        ulonglong2 qa1 = {0, 0}, qb1 = {0, 0}, qL1 = {0, 0}, qR1 = {0, 0};
-        if (v1) {
-          sa1 = B.x >= K; sb1 = B.y + 1 >= K;
-          const u32 ja = sa1 ? B.x - K : B.x, jb = sb1 ? B.y + 1 - K : B.y + 1;
-          ca1 = ja >> tl.shift_ch; cb1 = jb >> tl.shift_ch;
-          qL1 = ld2(tl.px + (u64)jL * PX + 2); qR1 = ld2(tl.px + (u64)jR * PX + 6);
-          qa1 = ld2(tl.px + (u64)ja * PX + 2); qb1 = ld2(tl.px + (u64)jb * PX + 6);
-        }
-        (void)qL; (void)qR; (void)qa; (void)qb;
-        bool f0 = false, f1 = false;                     // the channel can still carry it
-        if (v0) {
-          fo0_L = (sL ? allFO0 : 0ull) + bFO0[cL] + qL0.x; fi0_R = (sR ? allFI0 : 0ull) + bFI0[cR] + qR0.x;
-          const u64 fo_a = (sa0 ? allFO0 : 0ull) + bFO0[ca0] + qa0.x, fi_b = (sb0 ? allFI0 : 0ull) + bFI0[cb0] + qb0.x;
-          f0 = carries(fo_a - fo0_L, bwo0, x1000) && carries(fi0_R - fi_b, bwi0, x1000);
-          if (f0) {
-            const u64 ot = ((sb0 ? allOT : 0ull) + bOT[cb0] + qb0.y) - ((sa0 ? allOT : 0ull) + bOT[ca0] + qa0.y);
-            h0 = __umul64hi(s, ot); l0 = s * ot;
-          }
-        }
-        if (v1) {
-          fo1_L = (sL ? allFO1 : 0ull) + bFO1[cL] + qL1.x; fi1_R = (sR ? allFI1 : 0ull) + bFI1[cR] + qR1.x;
-          const u64 fo_a = (sa1 ? allFO1 : 0ull) + bFO1[ca1] + qa1.x, fi_b = (sb1 ? allFI1 : 0ull) + bFI1[cb1] + qb1.x;
-          f1 = carries(fo_a - fo1_L, bwo1, x1000) && carries(fi1_R - fi_b, bwi1, x1000);
-          if (f1) {
-            const u64 ot = ((sb1 ? allOT : 0ull) + bOT[cb1] + qb1.y) - ((sa1 ? allOT : 0ull) + bOT[ca1] + qa1.y);
-            h1 = __umul64hi(s, ot); l1 = s * ot;
-          }
-        }
-        ok0 = f0; ok1 = f1;
-        // strike what can never count again
-        const bool keep1 = f1 && (h1 | l1) != 0;
-        const bool keep0 = f0 && (keep1 || (h0 | l0) != 0);
-        if (v0 && !keep0) a.cd.A[cur.p] = make_uint4(L1, R, 1u, 0u);
-        if (v1 && !keep1) a.cd.B[cur.p] = make_uint4(1u, 0u, B.z, B.w);
-        fo_L = ok0 ? fo0_L : fo1_L; fi_R = ok0 ? fi0_R : fi1_R;
+      const Score r = score_candidate(pv, mc, A, B);
+      if (r.strike0) a.cd.A[cur.p] = make_uint4(A.x, A.y, 1u, 0u);
+      if (r.strike1) a.cd.B[cur.p] = make_uint4(1u, 0u, B.z, B.w);
+#ifdef G10_PHASE_TIMERS
+      {                                          // live candidates and destinations looked at
+        const bool v0 = A.z <= A.w, v1 = B.x <= B.y;
+        const u32 nl = (u32)__popcll(__ballot(v0 || v1)), nd = (u32)(__popcll(__ballot(v0)) + __popcll(__ballot(v1)));
+        if (lane == 0) { atomicAdd((unsigned long long*)&S->phase[9], (unsigned long long)nl); atomicAdd((unsigned long long*)&S->phase[10], (unsigned long long)nd); }
       }
-      const bool one = gt128(h1, l1, h0, l0);
-      const u32 k = wave_max(upkey(one ? h1 : h0, one ? l1 : l0));
+#endif
+      const bool one = gt128(r.h1, r.l1, r.h0, r.l0);
+      const u32 k = wave_max(upkey(one ? r.h1 : r.h0, one ? r.l1 : r.l0));
       if (lane == 0 && k) atomicMax(&keys[cur.t], k);
-      if (ok0 || ok1) {                          // flash first; host only if flash cannot take it
-        const u32 d = ok0 ? 0u : 1u;
-        const u64 hi = d ? h1 : h0, lo = d ? l1 : l0;
+      if (r.ok0 || r.ok1) {                      // flash first; host only if flash cannot take it
+        const u32 d = r.ok0 ? 0u : 1u;
+        const u64 hi = d ? r.h1 : r.h0, lo = d ? r.l1 : r.l0;
         if ((hi | lo) != 0 && better(hi, lo, cur.id.x, mine.hi, mine.lo, mine.cand)) {
           mine.hi = hi; mine.lo = lo; mine.cand = cur.id.x; mine.tensor = cur.id.y; mine.pos = cur.p; mine.dest = d;
-          mine.L1 = L1; mine.R = R; mine.a = d ? B.x : A.z; mine.b = d ? B.y : A.w; mine.s = s;
-          mine.fo_base = fo_L; mine.fi_end = fi_R;
+          mine.L1 = A.x; mine.R = A.y; mine.a = d ? B.x : A.z; mine.b = d ? B.y : A.w; mine.s = ((u64)B.w << 32) | B.z;
+          mine.fo_base = r.fo_L; mine.fi_end = r.fi_R;
         }
       }
       u = un;
@@ -971,6 +1032,7 @@ __global__ __launch_bounds__(LB) void k_loop(LoopArgs a) {
   for (u32 i = tid; i < N_ARR * nch; i += LB) a.g_tot[i] = tot[i];
   for (u32 i = tid; i < nch; i += LB) { a.g_lazyP[i] = lazyP[i]; a.g_minOver[i] = minOver[i]; a.g_lazyH[i] = lazyH[i]; a.g_hmax[i] = hmax[i]; }
   for (u32 i = tid; i < nt; i += LB) a.g_keys[i] = keys[i];
+  for (u32 i = tid; i < N_ARR * nb1; i += LB) a.g_base[i] = base[i];
   if (tid == 0) {
     ctl->n_iter = S->n_iter; ctl->n_mig = S->n_mig; ctl->n_drop = S->n_drop; ctl->n_evals = S->n_evals;
     ctl->thr_key = S->thr_key; ctl->status = S->status; ctl->done = S->done;
@@ -1020,7 +1082,8 @@ struct PlanWork {
   u64 *keys = nullptr, *keys_alt = nullptr;
   Cands cd[2] = {};
   u64 *P = nullptr, *fre = nullptr, *H = nullptr, *px = nullptr, *otc = nullptr, *base0 = nullptr, *g_tot = nullptr,
-      *g_lazyP = nullptr, *g_minOver = nullptr, *g_lazyH = nullptr, *g_hmax = nullptr, *pressure_after = nullptr,
+      *g_lazyP = nullptr, *g_minOver = nullptr, *g_lazyH = nullptr, *g_hmax = nullptr, *g_base = nullptr,
+      *pressure_after = nullptr,
       *peak_after = nullptr;
   Ctl* ctl = nullptr;
   g10_migration* records = nullptr;
@@ -1037,7 +1100,7 @@ void plan_work_free(PlanWork* w) {
   if (!w) return;
   void* dev[] = {w->win, w->keep, w->scratch32, w->hist, w->key32, w->tkeys, w->keys, w->keys_alt, w->cd[0].A, w->cd[0].B,
                  w->cd[0].id, w->cd[1].A, w->cd[1].B, w->cd[1].id, w->P, w->fre, w->H, w->px, w->otc, w->base0, w->g_tot,
-                 w->g_lazyP, w->g_minOver, w->g_lazyH, w->g_hmax, w->pressure_after, w->peak_after, w->ctl, w->records,
+                 w->g_lazyP, w->g_minOver, w->g_lazyH, w->g_hmax, w->g_base, w->pressure_after, w->peak_after, w->ctl, w->records,
                  w->dropped};
   for (void* p : dev) if (p) (void)hipFree(p);
   free(w->h_records);
@@ -1048,6 +1111,11 @@ void plan_work_free(PlanWork* w) {
 }
 
 static const u32 PASS_BUDGET = 4096;             // ranking passes per launch of the loop kernel
+#ifndef G10_RETILE_PASSES
+#define G10_RETILE_PASSES 512
+#endif
+static const u32 RETILE_PASSES = G10_RETILE_PASSES;   // ... between two re-tilings of a long candidate list
+static const u32 RETILE_MIN_CANDS = 8192;        // shorter lists are never re-tiled
 
 static u32 tile_shift_for(u64 n) {               // smallest tile (256 << shift) with at most NT_MAX tiles
   u32 sh = 0;
@@ -1079,12 +1147,13 @@ static int work_alloc(g10_plan_s* h) {
   G10_TRY(dalloc(&w->key32, C));
   G10_TRY(dalloc(&w->tkeys, (u64)NT_MAX));
   for (int i = 0; i < 2; ++i) {
-    const u64 n = i ? w->cap_pad : C;
+    const u64 n = w->cap_pad;
     G10_TRY(dalloc(&w->cd[i].A, n)); G10_TRY(dalloc(&w->cd[i].B, n)); G10_TRY(dalloc(&w->cd[i].id, n));
   }
   G10_TRY(dalloc(&w->P, K)); G10_TRY(dalloc(&w->fre, (u64)4 * w->Kp)); G10_TRY(dalloc(&w->H, K));
   G10_TRY(dalloc(&w->px, (u64)PX * K)); G10_TRY(dalloc(&w->otc, K));
   G10_TRY(dalloc(&w->base0, (u64)w->nch + 1));
+  G10_TRY(dalloc(&w->g_base, (u64)N_ARR * (w->nch + 1)));
   G10_TRY(dalloc(&w->g_tot, (u64)N_ARR * w->nch));
   G10_TRY(dalloc(&w->g_lazyP, w->nch)); G10_TRY(dalloc(&w->g_minOver, w->nch));
   G10_TRY(dalloc(&w->g_lazyH, w->nch)); G10_TRY(dalloc(&w->g_hmax, w->nch));
@@ -1153,49 +1222,81 @@ int plan_run(g10_plan_s* h, const g10_params* p, g10_result* out) {
   G10_HIP(hipStreamSynchronize(s));
   const u64 overtime_before = hc.overtime_before;
 
-  const u32 tsh = tile_shift_for(n);
-  const u32 tile = UNIT << tsh;
-  const u32 nt = (u32)(((u64)n + tile - 1) / tile);
-  const u32 n_pad = nt * tile;
   float full_ms = 0.f, loop_ms = 0.f;
   bool timed_full = false, timed_loop = false;
+  u64 retiles = 0;
   if (!hc.done) {
-    if (n) {
+    // candidates into score order, in tiles; `cur` is the buffer the loop reads
+    int cur = 0;
+    u32 tsh = 0, nt = 0, n_pad = 0;
+    auto retile = [&](bool first) -> int {
+      tsh = tile_shift_for(n);
+      const u32 tile = UNIT << tsh;
+      nt = (u32)(((u64)n + tile - 1) / tile);
+      n_pad = nt * tile;
+      if (!n) return G10_OK;
       const u32 posbits = bits_for(n - 1);
-      const u32 gn = (n + G10_BLOCK - 1) / G10_BLOCK;
-      hipLaunchKernelGGL(k_pack, dim3(gC), dim3(G10_BLOCK), 0, s, h->per_t, h->per_L, h->per_R, h->size, (const uint4*)w->win,
-                         (const u32*)w->keep, C, w->cd[0]);
-      G10_HIP(hipEventRecord(w->ev[2], s));
-      hipLaunchKernelGGL(k_score_full, dim3(gn), dim3(G10_BLOCK), (size_t)(w->nch + 1) * 8, s, w->cd[0], n, (const u64*)w->otc,
-                         (const u64*)w->base0, K, w->nch, w->shift_ch, posbits, w->key32, w->keys);
-      G10_HIP(hipEventRecord(w->ev[3], s));
-      timed_full = true;
+      if (first) {
+        const u32 gn = (n + G10_BLOCK - 1) / G10_BLOCK;
+        G10_HIP(hipEventRecord(w->ev[2], s));
+        hipLaunchKernelGGL(k_score_full, dim3(gn), dim3(G10_BLOCK), (size_t)(w->nch + 1) * 8, s, w->cd[cur], n, (const u64*)w->otc,
+                           (const u64*)w->base0, K, w->nch, w->shift_ch, posbits, w->key32, w->keys);
+        G10_HIP(hipEventRecord(w->ev[3], s));
+        timed_full = true;
+      } else {
+        u32 gn = (n + G10_BLOCK - 1) / G10_BLOCK;
+        if (gn > 2048) gn = 2048;
+        G10_HIP(hipMemsetAsync(&w->ctl->n_live, 0, sizeof(u32), s));
+        hipLaunchKernelGGL(k_rescore, dim3(gn), dim3(G10_BLOCK), (size_t)N_ARR * (w->nch + 1) * 8, s, w->cd[cur], n,
+                           (const u64*)w->px, (const u64*)w->g_base, K, w->nch, w->shift_ch, (const Ctl*)w->ctl, posbits,
+                           w->key32, w->keys, &w->ctl->n_live);
+      }
       G10_HIP(hipGetLastError());
       u64 *keys = w->keys, *alt = w->keys_alt;
       G10_TRY(radix_sort_u64(&keys, &alt, n, posbits + 23, w->hist, w->scratch32, s));
       G10_HIP(hipMemsetAsync(w->tkeys, 0, (u64)NT_MAX * 4, s));
       hipLaunchKernelGGL(k_tile_gather, dim3(n_pad / G10_BLOCK), dim3(G10_BLOCK), 0, s, (const u64*)keys, n, n_pad, posbits,
-                         w->cd[0], (const u32*)w->key32, w->cd[1], 8 + tsh, w->tkeys);
+                         w->cd[cur], (const u32*)w->key32, w->cd[cur ^ 1], 8 + tsh, w->tkeys);
+      G10_HIP(hipGetLastError());
+      cur ^= 1;
+      return G10_OK;
+    };
+    if (n) {
+      hipLaunchKernelGGL(k_pack, dim3(gC), dim3(G10_BLOCK), 0, s, h->per_t, h->per_L, h->per_R, h->size, (const uint4*)w->win,
+                         (const u32*)w->keep, C, w->cd[cur]);
       G10_HIP(hipGetLastError());
     }
+    G10_TRY(retile(true));
     LoopArgs la;
-    la.cd = w->cd[1]; la.n_pad = n_pad; la.nt = nt; la.tshift = tsh; la.tl = tl;
+    la.tl = tl;
     la.g_tot = w->g_tot; la.g_lazyP = w->g_lazyP; la.g_minOver = w->g_minOver; la.g_lazyH = w->g_lazyH; la.g_hmax = w->g_hmax;
-    la.g_keys = w->tkeys; la.ctl = w->ctl; la.records = w->records; la.dropped = w->dropped; la.pass_budget = PASS_BUDGET;
-    const size_t lds = loop_lds_bytes(w->nch, nt);
-    if (lds > 64 * 1024 && !w->lds_opt_in) {
+    la.g_base = w->g_base;
+    la.g_keys = w->tkeys; la.ctl = w->ctl; la.records = w->records; la.dropped = w->dropped;
+    if (!w->lds_opt_in && loop_lds_bytes(w->nch, nt) > 64 * 1024) {
       G10_HIP(hipFuncSetAttribute((const void*)k_loop, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
       w->lds_opt_in = true;
     }
     G10_HIP(hipEventRecord(w->ev[4], s));
-    const u64 max_launches = (u64)n / PASS_BUDGET + 3;          // every pass removes a candidate or stops
+    // Every pass removes a candidate or stops, so the launches are bounded.  Long lists are
+    // put back into score order every RETILE_PASSES passes: the tiles the loop looks at are
+    // dense with live candidates again, and the list is cut to those that can still score.
+    const u64 max_launches = (u64)n / RETILE_PASSES + 3;
     u64 launches = 0;
+    bool counted = false;                                   // hc.n_live holds a count of the current list
     while (!hc.done) {
       if (launches++ > max_launches) return G10_EDEVICE;
-      hipLaunchKernelGGL(k_loop, dim3(1), dim3(LB), lds, s, la);
+      la.cd = w->cd[cur]; la.n_pad = n_pad; la.nt = nt; la.tshift = tsh;
+      la.pass_budget = n > RETILE_MIN_CANDS ? RETILE_PASSES : PASS_BUDGET;
+      hipLaunchKernelGGL(k_loop, dim3(1), dim3(LB), loop_lds_bytes(w->nch, nt), s, la);
       G10_HIP(hipGetLastError());
       G10_HIP(hipMemcpyAsync(&hc, w->ctl, sizeof hc, hipMemcpyDeviceToHost, s));
       G10_HIP(hipStreamSynchronize(s));
+      if (!hc.done && n > RETILE_MIN_CANDS) {
+        if (counted && hc.n_live < n) n = hc.n_live;        // live candidates come first in the list
+        G10_TRY(retile(false));
+        counted = true;
+        ++retiles;
+      }
     }
     G10_HIP(hipEventRecord(w->ev[5], s));
     timed_loop = true;
@@ -1220,7 +1321,7 @@ int plan_run(g10_plan_s* h, const g10_params* p, g10_result* out) {
   if (getenv("G10_LOG")) {
     fprintf(stderr, "g10: loop phases (us per pass):");
     for (int i = 0; i < 9; ++i) fprintf(stderr, " %d:%.2f", i, hc.phase[i] / 100.0 / (double)(hc.n_iter ? hc.n_iter : 1));
-    fprintf(stderr, "\n");
+    fprintf(stderr, "  live/pass %.1f dests/pass %.1f\n", hc.phase[9] / (double)(hc.n_iter ? hc.n_iter : 1), hc.phase[10] / (double)(hc.n_iter ? hc.n_iter : 1));
   }
 #endif
   memset(out, 0, sizeof *out);
@@ -1231,7 +1332,7 @@ int plan_run(g10_plan_s* h, const g10_params* p, g10_result* out) {
   out->migrations = w->h_records; out->dropped = w->h_dropped; out->pressure_after = w->h_pressure;
   out->plan_ms = ms;
   out->score_full_ms = full_ms; out->score_full_cands = n;
-  out->loop_ms = loop_ms; out->loop_launches = hc.launches;
+  out->loop_ms = loop_ms; out->loop_launches = hc.launches; out->loop_retiles = retiles;
   out->loop_cands_scored = hc.units_scored * UNIT; out->loop_second_rounds = hc.second_rounds; out->loop_chunk_jobs = hc.jobs_run;
   return G10_OK;
 }
