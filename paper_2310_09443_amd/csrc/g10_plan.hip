@@ -76,6 +76,7 @@ __device__ __forceinline__ u32 w_fi(u32 d) { return 4 + 2 * d; }      // word of
 struct Ctl {
   // parameters
   u64 gpu_cap, host_cap, bw_out[2], bw_in[2], max_iter;
+  u64 inv_out[2], inv_in[2];  // floor(2^64 / bandwidth), 0 for bandwidth 1
   u64 C;                      // all inactive periods (live before any removal)
   // progress
   u32 done, status;
@@ -136,9 +137,14 @@ __device__ __forceinline__ bool carries(u64 free_ns, u64 bw, u64 bytes_x1000) {
   return __umul64hi(free_ns, bw) != 0 || free_ns * bw >= bytes_x1000;
 }
 
-__device__ __forceinline__ u64 ceil_div_x1000(u64 s, u64 bw) {
+// ceil(s * 1000 / bw) with the reciprocal inv = floor(2^64 / bw) (bw >= 2; inv = 0 stands for
+// bw = 1): the high half of x * inv is the quotient or up to 2 below it.
+__device__ __forceinline__ u64 ceil_div_x1000(u64 s, u64 bw, u64 inv) {
   const u64 x = s * 1000ull;              // validated: no overflow
-  return x / bw + (x % bw != 0);
+  if (inv == 0) return x;
+  u64 q = __umul64hi(x, inv), r = x - q * bw;
+  while (r >= bw) { r -= bw; ++q; }
+  return q + (r != 0);
 }
 
 // ---------------------------------------------------------------------------
@@ -159,7 +165,7 @@ __global__ __launch_bounds__(G10_BLOCK) void k_prep(const u32* __restrict__ per_
   u32 w[4];
 #pragma unroll
   for (int d = 0; d < 2; ++d) {
-    const u64 tau_o = ceil_div_x1000(s, ctl->bw_out[d]), tau_i = ceil_div_x1000(s, ctl->bw_in[d]);
+    const u64 tau_o = ceil_div_x1000(s, ctl->bw_out[d], ctl->inv_out[d]), tau_i = ceil_div_x1000(s, ctl->bw_in[d], ctl->inv_in[d]);
     u32 a = 1, b = 0;
     if (tau_o <= len && tau_i <= len) {
       u32 lo = L + 1, hi = R;               // first slot boundary at or after the end of the eviction
@@ -497,6 +503,20 @@ __device__ __forceinline__ u32 cover(u32 c, u32 ch, u32 K, u32 x, u32 y, u32& le
   return cnt;
 }
 
+// first plain slot of [s0, s1] inside the doubled range [x, y] (y - x < K), or NONE32
+__device__ __forceinline__ u32 first_covered(u32 s0, u32 s1, u32 K, u32 x, u32 y) {
+  u32 first = NONE32;
+  if (y >= K) {                                   // the part in the second iteration: plain [max(x, K) - K, y - K]
+    const u32 x2 = x >= K ? x - K : 0u, lo = s0 > x2 ? s0 : x2, hi = s1 < y - K ? s1 : y - K;
+    if (lo <= hi) first = lo;
+  }
+  if (x < K) {                                    // the part in the first iteration: plain [x, min(y, K - 1)]
+    const u32 y1 = y < K - 1 ? y : K - 1, lo = s0 > x ? s0 : x, hi = s1 < y1 ? s1 : y1;
+    if (lo <= hi && lo < first) first = lo;
+  }
+  return first;
+}
+
 // position of plain slot j inside the doubled range [x, y] (y - x < K), or NONE32
 __device__ __forceinline__ u32 in_doubled(u32 j, u32 K, u32 x, u32 y) {
   if (j >= x && j <= y) return j;
@@ -553,6 +573,7 @@ __global__ __launch_bounds__(LB) void k_loop(LoopArgs a) {
   Ctl* ctl = a.ctl;
   const u64 cap = ctl->gpu_cap, host_cap = ctl->host_cap, max_iter = ctl->max_iter, C = ctl->C;
   const u64 bwo0 = ctl->bw_out[0], bwo1 = ctl->bw_out[1], bwi0 = ctl->bw_in[0], bwi1 = ctl->bw_in[1];
+  const u64 ivo0 = ctl->inv_out[0], ivo1 = ctl->inv_out[1], ivi0 = ctl->inv_in[0], ivi1 = ctl->inv_in[1];
 
   // ---- state in ----------------------------------------------------------------------
   for (u32 i = tid; i < N_ARR * nch; i += LB) tot[i] = a.g_tot[i];
@@ -609,23 +630,30 @@ __global__ __launch_bounds__(LB) void k_loop(LoopArgs a) {
     if (tid == 0) { S->ntl = 0; S->restmax = 0; }
     __syncthreads();
     u32 rm = 0;
-    for (u32 g = wave; g < ns; g += LW) {
-      const u32 sk = skeys[g];
-      if (sk == 0 || sk < thr) { rm = sk > rm ? sk : rm; continue; }
-      const u32 t = g * 64 + lane;
-      const u32 k = t < nt ? keys[t] : 0u;
-      const u64 mk = smark[g];
-      const bool marked = (mk >> lane) & 1ull;
-      const bool sel = k != 0 && k >= thr && !marked;
-      if (!sel && !marked && k > rm) rm = k;
-      const u64 m = __ballot(sel);
-      if (m) {
-        u32 off = 0;
-        if (lane == 0) { off = atomicAdd(&S->ntl, (u32)__popcll(m)); smark[g] = mk | m; }
-        off = (u32)__builtin_amdgcn_readfirstlane((int)off);
-        if (sel) {
-          tlist[off + __popcll(m & ((1ull << lane) - 1ull))] = (unsigned short)t;
-          keys[t] = 0;                           // rebuilt by the scoring below
+    for (u32 g0 = 0; g0 < ns; g0 += 64) {          // 64 groups at a time, one per lane, in every wavefront alike
+      const u32 sk = g0 + lane < ns ? skeys[g0 + lane] : 0u;
+      const bool q = sk != 0 && sk >= thr;
+      if (!q && sk > rm) rm = sk;
+      u64 qm = __ballot(q);
+      for (u32 turn = 0; qm; ++turn) {             // the wavefronts share the groups that qualify
+        const u32 g = g0 + (u32)__builtin_ctzll(qm);
+        qm &= qm - 1;
+        if (turn % LW != wave) continue;
+        const u32 t = g * 64 + lane;
+        const u32 k = t < nt ? keys[t] : 0u;
+        const u64 mk = smark[g];
+        const bool marked = (mk >> lane) & 1ull;
+        const bool sel = k != 0 && k >= thr && !marked;
+        if (!sel && !marked && k > rm) rm = k;
+        const u64 m = __ballot(sel);
+        if (m) {
+          u32 off = 0;
+          if (lane == 0) { off = atomicAdd(&S->ntl, (u32)__popcll(m)); smark[g] = mk | m; }
+          off = (u32)__builtin_amdgcn_readfirstlane((int)off);
+          if (sel) {
+            tlist[off + __popcll(m & ((1ull << lane) - 1ull))] = (unsigned short)t;
+            keys[t] = 0;                           // rebuilt by the scoring below
+          }
         }
       }
     }
@@ -698,7 +726,7 @@ __global__ __launch_bounds__(LB) void k_loop(LoopArgs a) {
     else if (lane == bl) S->wave_win[wave] = mine;
     __syncthreads();                               // all tile bounds and wavefront winners are in LDS
     const u32 ntl = S->ntl;
-    for (u32 i = wave; i < ntl; i += LW) {          // bounds of the groups that hold re-scored tiles
+    for (u32 i = wave - 1; wave && i < ntl; i += LW - 1) {   // bounds of the groups that hold re-scored tiles
       const u32 g = tlist[i] >> 6, t = g * 64 + lane;
       const u32 k = wave_max(t < nt ? keys[t] : 0u);
       if (lane == 0) skeys[g] = k;
@@ -712,9 +740,9 @@ __global__ __launch_bounds__(LB) void k_loop(LoopArgs a) {
       else {
         if (lane == 0) {
           S->win = S->wave_win[w];
-          S->tau_o = ceil_div_x1000(S->wave_win[w].s, S->wave_win[w].dest ? bwo1 : bwo0);
+          S->tau_o = ceil_div_x1000(S->wave_win[w].s, S->wave_win[w].dest ? bwo1 : bwo0, S->wave_win[w].dest ? ivo1 : ivo0);
         }
-        if (lane == 1) S->tau_i = ceil_div_x1000(S->wave_win[w].s, S->wave_win[w].dest ? bwi1 : bwi0);
+        if (lane == 1) S->tau_i = ceil_div_x1000(S->wave_win[w].s, S->wave_win[w].dest ? bwi1 : bwi0, S->wave_win[w].dest ? ivi1 : ivi0);
       }
     }
     __syncthreads();
@@ -730,38 +758,30 @@ __global__ __launch_bounds__(LB) void k_loop(LoopArgs a) {
       const u32 s0 = c * CH;
       if (type == J_FO || type == J_FI) {
         // channel time of the window is taken from this chunk's slots; the free-time prefix
-        // of the slots after the first window slot is rewritten (scans of the old and new values)
+        // of the slots after the first window slot is rewritten from a scan of the new values
         const bool out = type == J_FO;
         const u32 arr = (out ? A_FO : A_FI) + d, w = out ? w_fo(d) : w_fi(d);
         u64* fr = tl.fre + (u64)((out ? 0u : 2u) + d) * tl.Kp;
         const u64 bc = base[(u64)arr * nb1 + c], ball = base[(u64)arr * nb1 + nch];
         const u32 x = out ? L1 : wb + 1, y = out ? wa - 1 : R - 1;
-        u64 carry_old = 0, carry = 0;
-        u32 first = NONE32;                              // first window slot of the chunk seen so far
+        const u32 first = first_covered(s0, (s0 + CH - 1 < K - 1) ? s0 + CH - 1 : K - 1, K, x, y);
+        u64 carry = 0;
         for (u32 st = 0; st < tl.spt; ++st) {
           const u32 j0 = s0 + st * 256u + lane * 4u;
-          u64 f[4];
+          u64 f[4], old[4];
           u32 jj[4];
-          u64 osum = 0;
-          u32 myfirst = NONE32;
 #pragma unroll
           for (u32 i = 0; i < 4; ++i) {
             const u32 j = j0 + i;
             f[i] = j < K ? fr[j] : 0ull;
             jj[i] = j < K ? in_doubled(j, K, x, y) : NONE32;
-            if (jj[i] != NONE32 && myfirst == NONE32) myfirst = j;
-            osum += f[i];
+            old[i] = jj[i] != NONE32 ? tl.px[(u64)j * PX + w] : 0ull;       // free time of the chunk before the slot
           }
-          const u64 oinc = wave_scan_incl(osum);
-          u64 orun = carry_old + oinc - osum;            // old free time of the chunk before this lane's slots
-          carry_old += wave_last(oinc);
-          const u32 stfirst = wave_min(myfirst);
-          if (first == NONE32) first = stfirst;
           u64 lsum = 0;
 #pragma unroll
           for (u32 i = 0; i < 4; ++i) {
             if (jj[i] != NONE32) {
-              const u64 before_slot = (jj[i] >= K ? ball : 0ull) + bc + orun;    // free time before slot jj
+              const u64 before_slot = (jj[i] >= K ? ball : 0ull) + bc + old[i];  // free time before slot jj
               u64 take;
               if (out) {                           // eviction: earliest free time of the window first
                 const u64 before = before_slot - fo_base;
@@ -772,10 +792,7 @@ __global__ __launch_bounds__(LB) void k_loop(LoopArgs a) {
                 const u64 used = after < tau_i ? after : tau_i;
                 take = f[i] < tau_i - used ? f[i] : tau_i - used;
               }
-              orun += f[i];
               if (take) { f[i] -= take; fr[j0 + i] = f[i]; }
-            } else {
-              orun += f[i];
             }
             lsum += f[i];
           }
@@ -784,7 +801,7 @@ __global__ __launch_bounds__(LB) void k_loop(LoopArgs a) {
 #pragma unroll
           for (u32 i = 0; i < 4; ++i) {
             const u32 j = j0 + i;
-            if (j < K && first != NONE32 && j > first) tl.px[(u64)j * PX + w] = run;
+            if (j < K && j > first) tl.px[(u64)j * PX + w] = run;
             run += f[i];
           }
           carry += wave_last(inc);
@@ -1112,7 +1129,7 @@ void plan_work_free(PlanWork* w) {
 
 static const u32 PASS_BUDGET = 4096;             // ranking passes per launch of the loop kernel
 #ifndef G10_RETILE_PASSES
-#define G10_RETILE_PASSES 512
+#define G10_RETILE_PASSES 256
 #endif
 static const u32 RETILE_PASSES = G10_RETILE_PASSES;   // ... between two re-tilings of a long candidate list
 static const u32 RETILE_MIN_CANDS = 8192;        // shorter lists are never re-tiled
@@ -1193,7 +1210,11 @@ int plan_run(g10_plan_s* h, const g10_params* p, g10_result* out) {
   Ctl hc;
   memset(&hc, 0, sizeof hc);
   hc.gpu_cap = p->gpu_cap_bytes; hc.host_cap = p->host_cap_bytes;
-  for (int d = 0; d < 2; ++d) { hc.bw_out[d] = p->bw_out_Bpus[d]; hc.bw_in[d] = p->bw_in_Bpus[d]; }
+  for (int d = 0; d < 2; ++d) {
+    hc.bw_out[d] = p->bw_out_Bpus[d]; hc.bw_in[d] = p->bw_in_Bpus[d];
+    hc.inv_out[d] = hc.bw_out[d] > 1 ? (u64)((((unsigned __int128)1) << 64) / hc.bw_out[d]) : 0;
+    hc.inv_in[d] = hc.bw_in[d] > 1 ? (u64)((((unsigned __int128)1) << 64) / hc.bw_in[d]) : 0;
+  }
   hc.max_iter = p->max_iterations;
   hc.C = C;
   G10_HIP(hipMemcpyAsync(w->ctl, &hc, sizeof hc, hipMemcpyHostToDevice, s));
