@@ -101,7 +101,7 @@ struct Timelines {
   u64* fre;                   // [4][Kp]
   u64* H;
   u64* px;                    // [K][PX]
-  u64* otc;                   // [K] chunk-local prefix of the over-capacity time before any eviction
+  u64* otc;                   // [K + 1] over-capacity time before every slot, before any eviction
   u32 K, Kp, nch, spt, shift_ch;   // chunk = 256 * spt = 1 << shift_ch slots
 };
 
@@ -268,35 +268,46 @@ __global__ __launch_bounds__(LB) void k_level1_init(const u64* __restrict__ g_to
   }
 }
 
+// over-capacity time before every slot, before any eviction: ot[j] for j in [0, K], chunk-local
+// prefix + chunk base, in place
+__global__ __launch_bounds__(G10_BLOCK) void k_ot_full(u64* __restrict__ ot, const u64* __restrict__ base0, u32 K, u32 nch,
+                                                      u32 shift_ch) {
+  const u32 j = blockIdx.x * G10_BLOCK + threadIdx.x;
+  if (j < K) ot[j] += base0[j >> shift_ch];
+  else if (j == K) ot[K] = base0[nch];
+}
+
 // ---------------------------------------------------------------------------
 // the streaming scoring pass over every candidate, before any eviction: all
 // channels are still free, so every valid window can be carried and
 // U = size * (largest over-capacity time of the valid windows).  Reads the 32
-// bytes of the candidate, gathers four prefix words from a table that fits
-// L2, writes the 4-byte key and the sort key.
+// bytes of the candidate, gathers four words of a prefix table that fits L2
+// (8 bytes per slot), writes the 8-byte sort key: the 31-bit score key rounded
+// up to its top 23 bits (descending), then the position.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(G10_BLOCK) void k_score_full(Cands cd, u32 n, const u64* __restrict__ otc,
-                                                         const u64* __restrict__ base0, u32 K, u32 nch, u32 shift_ch,
-                                                         u32 posbits, u32* __restrict__ key32, u64* __restrict__ sortkeys) {
-  extern __shared__ u64 lb[];                  // [nch + 1]
-  for (u32 i = threadIdx.x; i <= nch; i += G10_BLOCK) lb[i] = base0[i];
-  __syncthreads();
+__device__ __forceinline__ u64 sort_key(u32 key31, u32 posbits, u32 p) {
+  return ((u64)(0x7fffffu - ((key31 + 255u) >> 8)) << posbits) | p;
+}
+// the bound a sort key stands for: at least the score key it was made from, 0 only for 0
+__device__ __forceinline__ u32 bound_of_sort_key(u64 sk, u32 posbits) { return (0x7fffffu - (u32)(sk >> posbits)) << 8; }
+
+__global__ __launch_bounds__(G10_BLOCK) void k_score_full(const uint4* __restrict__ cA, const uint4* __restrict__ cB, u32 n,
+                                                         const u64* __restrict__ ot, u32 K, u32 posbits,
+                                                         u64* __restrict__ sortkeys) {
   const u32 p = blockIdx.x * G10_BLOCK + threadIdx.x;
   if (p >= n) return;
-  const uint4 A = cd.A[p], B = cd.B[p];
+  const uint4 A = cA[p], B = cB[p];
   const u64 s = ((u64)B.w << 32) | B.z;
-  const u64 total = lb[nch];
-  auto ot2 = [&](u32 j) -> u64 {               // over-capacity time before doubled slot j
-    const bool second = j >= K;
-    const u32 jj = second ? j - K : j;
-    return (second ? total : 0ull) + lb[jj >> shift_ch] + otc[jj];
-  };
-  u64 ot = 0;
-  if (A.z <= A.w) ot = ot2(A.w + 1) - ot2(A.z);
-  if (B.x <= B.y) { const u64 o1 = ot2(B.y + 1) - ot2(B.x); ot = o1 > ot ? o1 : ot; }
-  const u32 k = upkey(__umul64hi(s, ot), s * ot);
-  key32[p] = k;
-  sortkeys[p] = ((u64)(0x7fffffu - (k >> 8)) << posbits) | p;      // descending score, then analysis order
+  const u64 total = ot[K];
+  const bool v0 = A.z <= A.w, v1 = B.x <= B.y;
+  // an invalid window reads slot 0 twice: difference 0
+  const u32 a0 = v0 ? A.z : 0u, b0 = v0 ? A.w + 1 : 0u, a1 = v1 ? B.x : 0u, b1 = v1 ? B.y + 1 : 0u;
+  const u64 oa0 = ot[a0 >= K ? a0 - K : a0], ob0 = ot[b0 >= K ? b0 - K : b0];
+  const u64 oa1 = ot[a1 >= K ? a1 - K : a1], ob1 = ot[b1 >= K ? b1 - K : b1];
+  const u64 t0 = (ob0 + (b0 >= K ? total : 0ull)) - (oa0 + (a0 >= K ? total : 0ull));
+  const u64 t1 = (ob1 + (b1 >= K ? total : 0ull)) - (oa1 + (a1 >= K ? total : 0ull));
+  const u64 t = t1 > t0 ? t1 : t0;
+  sortkeys[p] = sort_key(upkey(__umul64hi(s, t), s * t), posbits, p);
 }
 
 // ---------------------------------------------------------------------------
@@ -385,19 +396,19 @@ __device__ __forceinline__ Score score_candidate(const PrefixView& pv, const Mac
   return r;
 }
 
-// candidates into score order; the tile bound is the largest key of its members
+// candidates into score order; the tile bound is the largest bound of its members
 __global__ __launch_bounds__(G10_BLOCK) void k_tile_gather(const u64* __restrict__ sorted, u32 n, u32 n_pad, u32 posbits,
-                                                          Cands src, const u32* __restrict__ key32, Cands dst,
-                                                          u32 tile_shift, u32* __restrict__ tkeys) {
+                                                          Cands src, Cands dst, u32 tile_shift, u32* __restrict__ tkeys) {
   const u32 r = blockIdx.x * G10_BLOCK + threadIdx.x;
   if (r >= n_pad) return;
   u32 k = 0;
   if (r < n) {
-    const u32 p = (u32)(sorted[r] & ((1ull << posbits) - 1ull));
+    const u64 sk = sorted[r];
+    const u32 p = (u32)(sk & ((1ull << posbits) - 1ull));
     dst.A[r] = src.A[p];
     dst.B[r] = src.B[p];
     dst.id[r] = src.id[p];
-    k = key32[p];
+    k = bound_of_sort_key(sk, posbits);
   } else {                                       // padding of the last tile: no valid window
     dst.A[r] = make_uint4(0u, 0u, 1u, 0u);
     dst.B[r] = make_uint4(1u, 0u, 0u, 0u);
@@ -409,11 +420,11 @@ __global__ __launch_bounds__(G10_BLOCK) void k_tile_gather(const u64* __restrict
 
 // Re-scores every candidate of the list against the current timelines (all
 // workgroups of the chip; used between launches of the loop kernel to put the
-// candidates back into score order).  Writes the 4-byte key and the sort key;
+// candidates back into score order).  Writes the sort key;
 // strikes dead destinations; counts the candidates that can still score.
 __global__ __launch_bounds__(G10_BLOCK) void k_rescore(Cands cd, u32 n, const u64* __restrict__ px, const u64* __restrict__ g_base,
                                                       u32 K, u32 nch, u32 shift_ch, const Ctl* ctl, u32 posbits,
-                                                      u32* __restrict__ key32, u64* __restrict__ sortkeys, u32* __restrict__ n_live) {
+                                                      u64* __restrict__ sortkeys, u32* __restrict__ n_live) {
   extern __shared__ u64 lb[];                  // [5][nch + 1]
   for (u32 i = threadIdx.x; i < N_ARR * (nch + 1); i += G10_BLOCK) lb[i] = g_base[i];
   __syncthreads();
@@ -427,8 +438,7 @@ __global__ __launch_bounds__(G10_BLOCK) void k_rescore(Cands cd, u32 n, const u6
     if (r.strike1) cd.B[p] = make_uint4(1u, 0u, B.z, B.w);
     const bool one = gt128(r.h1, r.l1, r.h0, r.l0);
     const u32 k = upkey(one ? r.h1 : r.h0, one ? r.l1 : r.l0);
-    key32[p] = k;
-    sortkeys[p] = ((u64)(0x7fffffu - (k >> 8)) << posbits) | p;
+    sortkeys[p] = sort_key(k, posbits, p);
     live += k != 0;
   }
   __shared__ u32 tmp[G10_WAVES + 1];
@@ -1095,7 +1105,7 @@ struct PlanWork {
   u32 K = 0, Kp = 0, nch = 0, spt = 1, shift_ch = 8;
   u64 C = 0, cap_pad = 0;
   uint4* win = nullptr;
-  u32 *keep = nullptr, *scratch32 = nullptr, *hist = nullptr, *key32 = nullptr, *tkeys = nullptr;
+  u32 *keep = nullptr, *scratch32 = nullptr, *hist = nullptr, *tkeys = nullptr;
   u64 *keys = nullptr, *keys_alt = nullptr;
   Cands cd[2] = {};
   u64 *P = nullptr, *fre = nullptr, *H = nullptr, *px = nullptr, *otc = nullptr, *base0 = nullptr, *g_tot = nullptr,
@@ -1115,7 +1125,7 @@ struct PlanWork {
 
 void plan_work_free(PlanWork* w) {
   if (!w) return;
-  void* dev[] = {w->win, w->keep, w->scratch32, w->hist, w->key32, w->tkeys, w->keys, w->keys_alt, w->cd[0].A, w->cd[0].B,
+  void* dev[] = {w->win, w->keep, w->scratch32, w->hist, w->tkeys, w->keys, w->keys_alt, w->cd[0].A, w->cd[0].B,
                  w->cd[0].id, w->cd[1].A, w->cd[1].B, w->cd[1].id, w->P, w->fre, w->H, w->px, w->otc, w->base0, w->g_tot,
                  w->g_lazyP, w->g_minOver, w->g_lazyH, w->g_hmax, w->g_base, w->pressure_after, w->peak_after, w->ctl, w->records,
                  w->dropped};
@@ -1161,14 +1171,13 @@ static int work_alloc(g10_plan_s* h) {
   G10_TRY(dalloc(&w->hist, he));
   G10_TRY(dalloc(&w->scratch32, scan_scratch_elems(he > C ? he : C)));
   G10_TRY(dalloc(&w->keys, C)); G10_TRY(dalloc(&w->keys_alt, C));
-  G10_TRY(dalloc(&w->key32, C));
   G10_TRY(dalloc(&w->tkeys, (u64)NT_MAX));
   for (int i = 0; i < 2; ++i) {
     const u64 n = w->cap_pad;
     G10_TRY(dalloc(&w->cd[i].A, n)); G10_TRY(dalloc(&w->cd[i].B, n)); G10_TRY(dalloc(&w->cd[i].id, n));
   }
   G10_TRY(dalloc(&w->P, K)); G10_TRY(dalloc(&w->fre, (u64)4 * w->Kp)); G10_TRY(dalloc(&w->H, K));
-  G10_TRY(dalloc(&w->px, (u64)PX * K)); G10_TRY(dalloc(&w->otc, K));
+  G10_TRY(dalloc(&w->px, (u64)PX * K)); G10_TRY(dalloc(&w->otc, (u64)K + 1));
   G10_TRY(dalloc(&w->base0, (u64)w->nch + 1));
   G10_TRY(dalloc(&w->g_base, (u64)N_ARR * (w->nch + 1)));
   G10_TRY(dalloc(&w->g_tot, (u64)N_ARR * w->nch));
@@ -1227,6 +1236,7 @@ int plan_run(g10_plan_s* h, const g10_params* p, g10_result* out) {
   hipLaunchKernelGGL(k_init_timelines, dim3(w->nch), dim3(G10_BLOCK), 0, s, tl, (const u64*)(h->pressure_buf + 1),
                      (const Ctl*)w->ctl, w->g_tot, w->g_lazyP, w->g_minOver, w->g_lazyH, w->g_hmax);
   hipLaunchKernelGGL(k_level1_init, dim3(1), dim3(LB), 0, s, (const u64*)w->g_tot, w->nch, w->base0, w->ctl);
+  hipLaunchKernelGGL(k_ot_full, dim3(K / G10_BLOCK + 1), dim3(G10_BLOCK), 0, s, w->otc, (const u64*)w->base0, K, w->nch, w->shift_ch);
   G10_HIP(hipGetLastError());
 
   // candidates: windows per destination; keep those with at least one valid window
@@ -1260,8 +1270,8 @@ int plan_run(g10_plan_s* h, const g10_params* p, g10_result* out) {
       if (first) {
         const u32 gn = (n + G10_BLOCK - 1) / G10_BLOCK;
         G10_HIP(hipEventRecord(w->ev[2], s));
-        hipLaunchKernelGGL(k_score_full, dim3(gn), dim3(G10_BLOCK), (size_t)(w->nch + 1) * 8, s, w->cd[cur], n, (const u64*)w->otc,
-                           (const u64*)w->base0, K, w->nch, w->shift_ch, posbits, w->key32, w->keys);
+        hipLaunchKernelGGL(k_score_full, dim3(gn), dim3(G10_BLOCK), 0, s, (const uint4*)w->cd[cur].A, (const uint4*)w->cd[cur].B, n,
+                           (const u64*)w->otc, K, posbits, w->keys);
         G10_HIP(hipEventRecord(w->ev[3], s));
         timed_full = true;
       } else {
@@ -1270,14 +1280,14 @@ int plan_run(g10_plan_s* h, const g10_params* p, g10_result* out) {
         G10_HIP(hipMemsetAsync(&w->ctl->n_live, 0, sizeof(u32), s));
         hipLaunchKernelGGL(k_rescore, dim3(gn), dim3(G10_BLOCK), (size_t)N_ARR * (w->nch + 1) * 8, s, w->cd[cur], n,
                            (const u64*)w->px, (const u64*)w->g_base, K, w->nch, w->shift_ch, (const Ctl*)w->ctl, posbits,
-                           w->key32, w->keys, &w->ctl->n_live);
+                           w->keys, &w->ctl->n_live);
       }
       G10_HIP(hipGetLastError());
       u64 *keys = w->keys, *alt = w->keys_alt;
       G10_TRY(radix_sort_u64(&keys, &alt, n, posbits + 23, w->hist, w->scratch32, s));
       G10_HIP(hipMemsetAsync(w->tkeys, 0, (u64)NT_MAX * 4, s));
       hipLaunchKernelGGL(k_tile_gather, dim3(n_pad / G10_BLOCK), dim3(G10_BLOCK), 0, s, (const u64*)keys, n, n_pad, posbits,
-                         w->cd[cur], (const u32*)w->key32, w->cd[cur ^ 1], 8 + tsh, w->tkeys);
+                         w->cd[cur], w->cd[cur ^ 1], 8 + tsh, w->tkeys);
       G10_HIP(hipGetLastError());
       cur ^= 1;
       return G10_OK;
