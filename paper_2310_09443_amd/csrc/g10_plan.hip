@@ -134,6 +134,7 @@ __device__ __forceinline__ u32 upkey(u64 hi, u64 lo) {
 
 __device__ __forceinline__ bool carries(u64 free_ns, u64 bw, u64 bytes_x1000) {
   // free_ns >= ceil(bytes_x1000 / bw)  <=>  free_ns * bw >= bytes_x1000
+  if (((free_ns | bw) >> 32) == 0) return (u64)(u32)free_ns * (u32)bw >= bytes_x1000;   // the usual case: one 32 x 32 multiply
   return __umul64hi(free_ns, bw) != 0 || free_ns * bw >= bytes_x1000;
 }
 
@@ -489,28 +490,26 @@ struct Shared {               // small per-pass state of the loop workgroup
   Winner wave_win[LW];        // best of every wavefront
   u64 tau_o, tau_i;
   u64 hq;                     // host-capacity query: maximum over the period
-  u32 ntl, restmax, njobs, ot_changed;
+  u32 nl, restL;              // hot list: length; bound of the tiles outside it
+  u32 ntl, filt;              // current round: tiles to score; bound of the hot tiles left out
+  u32 njobs, ot_changed, stale_hot, pad1;
   // progress (mirrors Ctl)
   u64 n_iter, n_mig, n_drop, n_evals, units, second, jobs;
   u32 thr_key, status, done, pad;
   u64 phase[12], t_last;
 };
 
-// covered slots of chunk c by the doubled range [x, y] (x <= y, y - x < K)
+// covered slots of chunk c by the doubled range [x, y] (x <= y, y - x < K): the chunk's slots
+// appear at [s0, s1] and at [s0 + K, s1 + K] in doubled coordinates
 __device__ __forceinline__ u32 cover(u32 c, u32 ch, u32 K, u32 x, u32 y, u32& len) {
-  const u32 s0 = c * ch, s1 = (s0 + ch - 1 < K - 1) ? s0 + ch - 1 : K - 1;
-  len = s1 - s0 + 1;
-  u32 cnt = 0;
-  if (x < K) {
-    const u32 lo = s0 > x ? s0 : x, hi0 = y < K - 1 ? y : K - 1, hi = s1 < hi0 ? s1 : hi0;
-    if (lo <= hi) cnt += hi - lo + 1;
-  }
-  if (y >= K) {
-    const u32 x2 = x >= K ? x - K : 0u, y2 = y - K;
-    const u32 lo = s0 > x2 ? s0 : x2, hi = s1 < y2 ? s1 : y2;
-    if (lo <= hi) cnt += hi - lo + 1;
-  }
-  return cnt;
+  const long long s0 = (long long)c * ch, s1 = (s0 + ch - 1 < (long long)K - 1) ? s0 + ch - 1 : (long long)K - 1;
+  len = (u32)(s1 - s0 + 1);
+  const long long X = x, Y = y;
+  long long n1 = (s1 < Y ? s1 : Y) - (s0 > X ? s0 : X) + 1;
+  long long n2 = (s1 + K < Y ? s1 + K : Y) - (s0 + K > X ? s0 + K : X) + 1;
+  if (n1 < 0) n1 = 0;
+  if (n2 < 0) n2 = 0;
+  return (u32)(n1 + n2);
 }
 
 // first plain slot of [s0, s1] inside the doubled range [x, y] (y - x < K), or NONE32
@@ -577,7 +576,8 @@ __global__ __launch_bounds__(LB) void k_loop(LoopArgs a) {
   u32* keys = (u32*)(S + 1);                            // [nt]  bound of every tile
   u32* skeys = keys + nt;                               // [ns]  largest bound of every group of 64 tiles
   u32* jobs = skeys + ns;                               // [4 * nch + 8]
-  unsigned short* tlist = (unsigned short*)(jobs + 4 * nch + 8);   // [nt]
+  unsigned short* tlist = (unsigned short*)(jobs + 4 * nch + 8);   // [nt]  the hot list
+  unsigned short* alist = tlist + nt;                            // [nt]  tiles scored in the current round
 
   const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
   Ctl* ctl = a.ctl;
@@ -594,6 +594,8 @@ __global__ __launch_bounds__(LB) void k_loop(LoopArgs a) {
     S->n_iter = ctl->n_iter; S->n_mig = ctl->n_mig; S->n_drop = ctl->n_drop; S->n_evals = ctl->n_evals;
     S->units = 0; S->second = 0; S->jobs = 0;
     S->thr_key = ctl->thr_key; S->status = ctl->status; S->done = ctl->done;
+    S->nl = 0; S->restL = NONE32; S->stale_hot = 0;
+    S->win.hi = 0; S->win.lo = 0;
     for (u32 i = 0; i < 12; ++i) S->phase[i] = 0;
     S->t_last = wall_clock64();
   }
@@ -634,10 +636,11 @@ __global__ __launch_bounds__(LB) void k_loop(LoopArgs a) {
   scan_bases(0, 1, 2, 3);
   scan_bases(3, 4, 0, 2);
 
-  // tiles whose bound reaches `thr` and that were not scored in this pass -> tlist;
-  // an upper bound of the bounds of the tiles left out -> restmax
-  auto build_list = [&](u32 thr) {
-    if (tid == 0) { S->ntl = 0; S->restmax = 0; }
+  // The hot list: every tile not scored in this pass whose bound reaches `thr`; restL bounds
+  // the tiles left out.  Bounds only fall and only scored tiles change, so the list stays
+  // complete for any later threshold above restL and is kept across passes.
+  auto build_hot = [&](u32 thr) {
+    if (tid == 0) { S->nl = 0; S->restL = 0; }
     __syncthreads();
     u32 rm = 0;
     for (u32 g0 = 0; g0 < ns; g0 += 64) {          // 64 groups at a time, one per lane, in every wavefront alike
@@ -651,24 +654,52 @@ __global__ __launch_bounds__(LB) void k_loop(LoopArgs a) {
         if (turn % LW != wave) continue;
         const u32 t = g * 64 + lane;
         const u32 k = t < nt ? keys[t] : 0u;
-        const u64 mk = smark[g];
-        const bool marked = (mk >> lane) & 1ull;
+        const bool marked = (smark[g] >> lane) & 1ull;
         const bool sel = k != 0 && k >= thr && !marked;
         if (!sel && !marked && k > rm) rm = k;
         const u64 m = __ballot(sel);
         if (m) {
           u32 off = 0;
-          if (lane == 0) { off = atomicAdd(&S->ntl, (u32)__popcll(m)); smark[g] = mk | m; }
+          if (lane == 0) off = atomicAdd(&S->nl, (u32)__popcll(m));
           off = (u32)__builtin_amdgcn_readfirstlane((int)off);
-          if (sel) {
-            tlist[off + __popcll(m & ((1ull << lane) - 1ull))] = (unsigned short)t;
-            keys[t] = 0;                           // rebuilt by the scoring below
-          }
+          if (sel) tlist[off + __popcll(m & ((1ull << lane) - 1ull))] = (unsigned short)t;
         }
       }
     }
     rm = wave_max(rm);
-    if (lane == 0 && rm) atomicMax(&S->restmax, rm);
+    if (lane == 0 && rm) atomicMax(&S->restL, rm);
+    __syncthreads();
+  };
+
+  // The tiles of the hot list whose bound reaches `thr` and that were not scored in this pass
+  // -> alist (marked, bound cleared: the scoring rebuilds it); filt bounds the others.
+  auto activate = [&](u32 thr) {
+    if (tid == 0) { S->ntl = 0; S->filt = 0; }
+    __syncthreads();
+    const u32 nl = S->nl;
+    u32 fm = 0;
+    for (u32 i0 = 0; i0 < nl; i0 += LB) {
+      const u32 i = i0 + tid;
+      const u32 t = i < nl ? tlist[i] : 0u;
+      const u32 k = i < nl ? keys[t] : 0u;
+      const bool marked = i < nl && ((smark[t >> 6] >> (t & 63u)) & 1ull);
+      const bool sel = k != 0 && k >= thr && !marked;
+      if (!sel && !marked && k > fm) fm = k;
+      const u64 m = __ballot(sel);
+      if (m) {
+        u32 off = 0;
+        if (lane == 0) off = atomicAdd(&S->ntl, (u32)__popcll(m));
+        off = (u32)__builtin_amdgcn_readfirstlane((int)off);
+        if (sel) {
+          alist[off + __popcll(m & ((1ull << lane) - 1ull))] = (unsigned short)t;
+          keys[t] = 0;
+          atomicOr((unsigned long long*)&smark[t >> 6], 1ull << (t & 63u));
+        }
+      }
+      if (i0 + LB >= nl) break;
+    }
+    fm = wave_max(fm);
+    if (lane == 0 && fm) atomicMax(&S->filt, fm);
     __syncthreads();
   };
 
@@ -679,7 +710,7 @@ __global__ __launch_bounds__(LB) void k_loop(LoopArgs a) {
   struct CandV { uint4 A, B; uint2 id; u32 p, t; };
   auto load_cand = [&](u32 u) -> CandV {
     CandV c;
-    c.t = tlist[u >> a.tshift];
+    c.t = alist[u >> a.tshift];
     c.p = (((c.t << a.tshift) + (u & ((1u << a.tshift) - 1u))) << 8) + (tid & 255u);
     c.A = a.cd.A[c.p]; c.B = a.cd.B[c.p]; c.id = a.cd.id[c.p];
     return c;
@@ -737,7 +768,7 @@ __global__ __launch_bounds__(LB) void k_loop(LoopArgs a) {
     __syncthreads();                               // all tile bounds and wavefront winners are in LDS
     const u32 ntl = S->ntl;
     for (u32 i = wave - 1; wave && i < ntl; i += LW - 1) {   // bounds of the groups that hold re-scored tiles
-      const u32 g = tlist[i] >> 6, t = g * 64 + lane;
+      const u32 g = alist[i] >> 6, t = g * 64 + lane;
       const u32 k = wave_max(t < nt ? keys[t] : 0u);
       if (lane == 0) skeys[g] = k;
     }
@@ -907,18 +938,32 @@ __global__ __launch_bounds__(LB) void k_loop(LoopArgs a) {
     if (passes >= a.pass_budget) break;
     ++passes;
     mine.hi = 0; mine.lo = 0; mine.cand = NONE32;
-
-    // rank: score the tiles whose bound reaches a threshold, lower the threshold to the best
-    // benefit found, repeat until no tile left out could hold an equal or better candidate
     u32 thr = S->thr_key ? S->thr_key : NONE32;
-    u32 rounds = 0;
     __syncthreads();                               // the loop conditions and thr are read
+    for (u32 i = tid; i < ns; i += LB) smark[i] = 0;     // no tile scored in this pass yet
+    if (tid == 0) {
+      S->n_iter += 1; S->n_evals += C - S->n_mig - S->n_drop;
+      S->hq = 0; S->njobs = 0; S->ot_changed = 0;
+      S->win.hi = 0; S->win.lo = 0;
+      if (S->stale_hot) { S->restL = NONE32; S->stale_hot = 0; }
+    }
+    __syncthreads();
+
+    // rank: score the hot tiles whose bound reaches a threshold (first a guess a little under
+    // the last benefit), lower the threshold to the best benefit found, repeat until no tile
+    // left out could hold an equal or better candidate
+    u32 rounds = 0;
     while (true) {
-      build_list(thr);
-      const u32 ntl = S->ntl, rest = S->restmax;
-      const u32 found = upkey(S->win.hi, S->win.lo);     // meaningful after the first scoring round of the pass
+      if (S->restL >= thr) {                       // the hot list may miss a tile that reaches thr: build it anew,
+        const u32 low = thr == NONE32 ? thr : (thr > (1u << 19) ? thr - (1u << 19) : 1u);   // a few percent lower to last a while
+        __syncthreads();
+        build_hot(low);
+        if (rounds && tid == 0) S->stale_hot = 1;  // built without the tiles already scored: not kept for the next pass
+      }
+      activate(thr);
+      const u32 ntl = S->ntl, rest = S->restL > S->filt ? S->restL : S->filt;
       if (ntl == 0) {
-        if ((rounds && found) || rest == 0) break;       // nothing left that could win
+        if ((rounds && (S->win.hi | S->win.lo) != 0) || rest == 0) break;      // nothing left that could win
         thr = rest;                                      // strictly lower than before: start from the largest bound left
         __syncthreads();
         continue;
@@ -932,22 +977,17 @@ __global__ __launch_bounds__(LB) void k_loop(LoopArgs a) {
       const u32 kb = upkey(S->win.hi, S->win.lo);
       const u32 need = kb ? kb : 1u;
       if (rest < need) break;                            // every tile left out is below the best found
-      // a tile left out may hold an equal or better one; with nothing found yet, step down by about 2^-4
+      // a tile left out may hold an equal or better one; with nothing found yet, step down a few percent
       thr = kb ? kb : (rest > (1u << 19) ? rest - (1u << 19) : 1u);
       if (tid == 0) S->second += 1;
       __syncthreads();
     }
-    if (rounds == 0 && tid == 0) { S->win.hi = 0; S->win.lo = 0; }
-    for (u32 i = tid; i < ns; i += LB) smark[i] = 0;     // forget which tiles were scored in this pass
-    __syncthreads();
     PHASE(3);
 
     const bool none = (S->win.hi | S->win.lo) == 0;
     const u32 d = S->win.dest, L1 = S->win.L1, R = S->win.R, wa = S->win.a, wb = S->win.b;
     const u64 s = S->win.s;
-    if (tid == 0) { S->n_iter += 1; S->n_evals += C - S->n_mig - S->n_drop; S->hq = 0; S->njobs = 0; S->ot_changed = 0; }
-    __syncthreads();
-    if (none) { if (tid == 0) { S->done = 1; S->status = G10_RESIDUAL; } break; }
+    if (none) { __syncthreads(); if (tid == 0) { S->done = 1; S->status = G10_RESIDUAL; } break; }
 
     // which chunks the period, its absent window and its transfer windows cover
     u32 cvE = 0, cvW = 0, cvA = 0, cvP = 0, len = 0;
@@ -999,7 +1039,8 @@ __global__ __launch_bounds__(LB) void k_loop(LoopArgs a) {
       } else {
         g10_migration mg;
         mg.cand = S->win.cand; mg.tensor = S->win.tensor;
-        mg.evict_after = L1 - 1; mg.absent_first = wa % K; mg.absent_last = wb % K; mg.next_use = R % K;
+        mg.evict_after = L1 - 1; mg.absent_first = wa >= K ? wa - K : wa; mg.absent_last = wb >= K ? wb - K : wb;
+        mg.next_use = R >= K ? R - K : R;
         mg.dest = d; mg.wraps = R >= K ? 1u : 0u;
         mg.size_bytes = s; mg.t_out_ns = S->tau_o; mg.t_in_ns = S->tau_i; mg.benefit_lo = S->win.lo; mg.benefit_hi = S->win.hi;
         a.records[S->n_mig] = mg;
@@ -1083,14 +1124,6 @@ __global__ __launch_bounds__(G10_BLOCK) void k_finish(Timelines tl, const u64* _
   if (threadIdx.x == 0) atomicMax((unsigned long long*)peak, (unsigned long long)m);
 }
 
-template <class T>
-int dalloc(T** out, u64 elems) {
-  void* q = nullptr;
-  if (hipMalloc(&q, (elems ? elems : 1) * sizeof(T)) != hipSuccess) { (void)hipGetLastError(); return G10_ENOMEM; }
-  *out = (T*)q;
-  return G10_OK;
-}
-
 inline u32 bits_for(u64 max_value) {
   u32 b = 1;
   while (b < 64 && (max_value >> b)) ++b;
@@ -1121,15 +1154,12 @@ struct PlanWork {
   u64* h_pressure = nullptr;
   hipEvent_t ev[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
   bool lds_opt_in = false;
+  void* arena = nullptr;        // the one device allocation all pointers above point into
 };
 
 void plan_work_free(PlanWork* w) {
   if (!w) return;
-  void* dev[] = {w->win, w->keep, w->scratch32, w->hist, w->tkeys, w->keys, w->keys_alt, w->cd[0].A, w->cd[0].B,
-                 w->cd[0].id, w->cd[1].A, w->cd[1].B, w->cd[1].id, w->P, w->fre, w->H, w->px, w->otc, w->base0, w->g_tot,
-                 w->g_lazyP, w->g_minOver, w->g_lazyH, w->g_hmax, w->g_base, w->pressure_after, w->peak_after, w->ctl, w->records,
-                 w->dropped};
-  for (void* p : dev) if (p) (void)hipFree(p);
+  if (w->arena) (void)hipFree(w->arena);
   free(w->h_records);
   free(w->h_dropped);
   free(w->h_pressure);
@@ -1150,6 +1180,44 @@ static u32 tile_shift_for(u64 n) {               // smallest tile (256 << shift)
   return sh;
 }
 
+// One device allocation for all planning workspaces (a handle is often short-lived; every
+// hipMalloc / hipFree costs about 0.1 ms): the layout is walked twice, first to measure.
+struct Arena {
+  char* base = nullptr;
+  size_t off = 0;
+  template <class T>
+  void take(T** out, u64 elems) {
+    off = (off + 255) & ~(size_t)255;
+    if (base) *out = (T*)(base + off);
+    off += (size_t)(elems ? elems : 1) * sizeof(T);
+  }
+};
+
+static void work_layout(PlanWork* w, Arena& ar) {
+  const u32 K = w->K;
+  const u64 C = w->C;
+  ar.take(&w->win, C);
+  ar.take(&w->keep, C + 1);
+  const u64 he = radix_hist_elems(C);
+  ar.take(&w->hist, he);
+  ar.take(&w->scratch32, scan_scratch_elems(he > C ? he : C));
+  ar.take(&w->keys, C); ar.take(&w->keys_alt, C);
+  ar.take(&w->tkeys, (u64)NT_MAX);
+  for (int i = 0; i < 2; ++i) { ar.take(&w->cd[i].A, w->cap_pad); ar.take(&w->cd[i].B, w->cap_pad); ar.take(&w->cd[i].id, w->cap_pad); }
+  ar.take(&w->P, K); ar.take(&w->fre, (u64)4 * w->Kp); ar.take(&w->H, K);
+  ar.take(&w->px, (u64)PX * K); ar.take(&w->otc, (u64)K + 1);
+  ar.take(&w->base0, (u64)w->nch + 1);
+  ar.take(&w->g_base, (u64)N_ARR * (w->nch + 1));
+  ar.take(&w->g_tot, (u64)N_ARR * w->nch);
+  ar.take(&w->g_lazyP, w->nch); ar.take(&w->g_minOver, w->nch);
+  ar.take(&w->g_lazyH, w->nch); ar.take(&w->g_hmax, w->nch);
+  ar.take(&w->pressure_after, K);
+  ar.take(&w->peak_after, 1);
+  ar.take(&w->ctl, 1);
+  ar.take(&w->records, C);
+  ar.take(&w->dropped, C);
+}
+
 static int work_alloc(g10_plan_s* h) {
   PlanWork* w = new (std::nothrow) PlanWork();
   if (!w) return G10_ENOMEM;
@@ -1165,29 +1233,14 @@ static int work_alloc(g10_plan_s* h) {
   const u32 tsh = tile_shift_for(C);
   w->cap_pad = ((C + ((u64)UNIT << tsh) - 1) >> (8 + tsh)) << (8 + tsh);
   if (!w->cap_pad) w->cap_pad = UNIT;
-  G10_TRY(dalloc(&w->win, C));
-  G10_TRY(dalloc(&w->keep, C + 1));
-  const u64 he = radix_hist_elems(C);
-  G10_TRY(dalloc(&w->hist, he));
-  G10_TRY(dalloc(&w->scratch32, scan_scratch_elems(he > C ? he : C)));
-  G10_TRY(dalloc(&w->keys, C)); G10_TRY(dalloc(&w->keys_alt, C));
-  G10_TRY(dalloc(&w->tkeys, (u64)NT_MAX));
-  for (int i = 0; i < 2; ++i) {
-    const u64 n = w->cap_pad;
-    G10_TRY(dalloc(&w->cd[i].A, n)); G10_TRY(dalloc(&w->cd[i].B, n)); G10_TRY(dalloc(&w->cd[i].id, n));
-  }
-  G10_TRY(dalloc(&w->P, K)); G10_TRY(dalloc(&w->fre, (u64)4 * w->Kp)); G10_TRY(dalloc(&w->H, K));
-  G10_TRY(dalloc(&w->px, (u64)PX * K)); G10_TRY(dalloc(&w->otc, (u64)K + 1));
-  G10_TRY(dalloc(&w->base0, (u64)w->nch + 1));
-  G10_TRY(dalloc(&w->g_base, (u64)N_ARR * (w->nch + 1)));
-  G10_TRY(dalloc(&w->g_tot, (u64)N_ARR * w->nch));
-  G10_TRY(dalloc(&w->g_lazyP, w->nch)); G10_TRY(dalloc(&w->g_minOver, w->nch));
-  G10_TRY(dalloc(&w->g_lazyH, w->nch)); G10_TRY(dalloc(&w->g_hmax, w->nch));
-  G10_TRY(dalloc(&w->pressure_after, K));
-  G10_TRY(dalloc(&w->peak_after, 1));
-  G10_TRY(dalloc(&w->ctl, 1));
-  G10_TRY(dalloc(&w->records, C));
-  G10_TRY(dalloc(&w->dropped, C));
+  Arena measure;
+  work_layout(w, measure);
+  void* q = nullptr;
+  if (hipMalloc(&q, measure.off + 256) != hipSuccess) { (void)hipGetLastError(); return G10_ENOMEM; }
+  w->arena = q;
+  Arena carve;
+  carve.base = (char*)q;
+  work_layout(w, carve);
   w->h_records = (g10_migration*)malloc((C ? C : 1) * sizeof(g10_migration));
   w->h_dropped = (g10_dropped*)malloc((C ? C : 1) * sizeof(g10_dropped));
   w->h_pressure = (u64*)malloc((u64)K * sizeof(u64));
@@ -1201,7 +1254,7 @@ static size_t loop_lds_bytes(u32 nch, u32 nt) {
   size_t b = 0;
   b += ((size_t)N_ARR * (nch + 1) + (size_t)N_ARR * nch + (size_t)4 * nch + ns + (size_t)4 * LW) * 8;
   b += sizeof(Shared);
-  b += ((size_t)nt + ns + (size_t)4 * nch + 8) * 4 + (size_t)nt * 2;
+  b += ((size_t)nt + ns + (size_t)4 * nch + 8) * 4 + (size_t)nt * 4;
   return (b + 15) & ~(size_t)15;
 }
 
@@ -1252,6 +1305,7 @@ int plan_run(g10_plan_s* h, const g10_params* p, g10_result* out) {
   G10_HIP(hipMemcpyAsync(&hc, w->ctl, sizeof hc, hipMemcpyDeviceToHost, s));
   G10_HIP(hipStreamSynchronize(s));
   const u64 overtime_before = hc.overtime_before;
+  const u32 n_valid = n;                                  // candidates with a valid window
 
   float full_ms = 0.f, loop_ms = 0.f;
   bool timed_full = false, timed_loop = false;
@@ -1362,7 +1416,7 @@ int plan_run(g10_plan_s* h, const g10_params* p, g10_result* out) {
   out->overtime_before_ns = overtime_before; out->overtime_after_ns = hc.overtime_after;
   out->migrations = w->h_records; out->dropped = w->h_dropped; out->pressure_after = w->h_pressure;
   out->plan_ms = ms;
-  out->score_full_ms = full_ms; out->score_full_cands = n;
+  out->score_full_ms = full_ms; out->score_full_cands = n_valid;
   out->loop_ms = loop_ms; out->loop_launches = hc.launches; out->loop_retiles = retiles;
   out->loop_cands_scored = hc.units_scored * UNIT; out->loop_second_rounds = hc.second_rounds; out->loop_chunk_jobs = hc.jobs_run;
   return G10_OK;
