@@ -79,7 +79,13 @@ typedef struct {
   uint64_t bw_out_Bpus[2];   /* GPU -> [G10_FLASH, G10_HOST], bytes per microsecond    */
   uint64_t bw_in_Bpus[2];    /* [G10_FLASH, G10_HOST] -> GPU                           */
   uint64_t max_iterations;   /* stop after this many ranking passes; 0 = no limit      */
-  uint32_t reserved[2];      /* 0                                                      */
+  uint32_t max_tiles;        /* 0 = library default.  Candidates are ranked in tiles of 256 << k, k the
+                                smallest with at most this many tiles (default and maximum 8192)        */
+  uint32_t max_chunks;       /* 0 = library default.  The kernel timeline is split into chunks of
+                                256 << k slots, k the smallest with at most this many chunks (default and
+                                maximum 512).  Both limits only trade speed against on-chip memory; the
+                                plan does not depend on them.  Tests lower them to reach the code paths of
+                                very long traces with small ones.                                        */
 } g10_params;
 
 /* One migration, i.e. one g10_pre_evict / g10_prefetch pair of Section 4.4's

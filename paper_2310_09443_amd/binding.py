@@ -50,7 +50,7 @@ class _Stats(C.Structure):
 class _Params(C.Structure):
     _fields_ = [("gpu_cap_bytes", C.c_uint64), ("host_cap_bytes", C.c_uint64),
                 ("bw_out_Bpus", C.c_uint64 * 2), ("bw_in_Bpus", C.c_uint64 * 2),
-                ("max_iterations", C.c_uint64), ("reserved", C.c_uint32 * 2)]
+                ("max_iterations", C.c_uint64), ("max_tiles", C.c_uint32), ("max_chunks", C.c_uint32)]
 
 
 class _Result(C.Structure):
@@ -162,13 +162,14 @@ class Handle:
     start = property(lambda self: self.read(5))
     pressure = property(lambda self: self.read(6))
 
-    def plan(self, gpu_cap, host_cap, bw_out, bw_in, max_iters=0) -> Result:
+    def plan(self, gpu_cap, host_cap, bw_out, bw_in, max_iters=0, max_tiles=0, max_chunks=0) -> Result:
         import torch
         p = _Params()
         p.gpu_cap_bytes, p.host_cap_bytes = int(gpu_cap), int(host_cap)
         p.bw_out_Bpus[0], p.bw_out_Bpus[1] = int(bw_out[0]), int(bw_out[1])
         p.bw_in_Bpus[0], p.bw_in_Bpus[1] = int(bw_in[0]), int(bw_in[1])
         p.max_iterations = int(max_iters)
+        p.max_tiles, p.max_chunks = int(max_tiles), int(max_chunks)
         r = _Result()
         with torch.cuda.device(self._dev):
             rc = load().g10_plan(self._h, C.byref(p), C.byref(r))
@@ -192,8 +193,8 @@ def g10_vitality(dtrace: DeviceTrace, no_wrap: bool = False, stream=None) -> Han
     return Handle(dtrace, no_wrap, stream)
 
 
-def g10_plan(handle: Handle, gpu_cap, host_cap, bw_out, bw_in, max_iters=0) -> Result:
-    return handle.plan(gpu_cap, host_cap, bw_out, bw_in, max_iters)
+def g10_plan(handle: Handle, gpu_cap, host_cap, bw_out, bw_in, max_iters=0, max_tiles=0, max_chunks=0) -> Result:
+    return handle.plan(gpu_cap, host_cap, bw_out, bw_in, max_iters, max_tiles, max_chunks)
 
 
 def g10_plan_free(handle: Handle) -> None:

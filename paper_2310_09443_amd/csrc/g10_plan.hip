@@ -1155,6 +1155,7 @@ struct PlanWork {
   hipEvent_t ev[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
   bool lds_opt_in = false;
   void* arena = nullptr;        // the one device allocation all pointers above point into
+  u32 max_chunks = 0;           // the chunk limit the timelines were laid out for
 };
 
 void plan_work_free(PlanWork* w) {
@@ -1174,11 +1175,13 @@ static const u32 PASS_BUDGET = 4096;             // ranking passes per launch of
 static const u32 RETILE_PASSES = G10_RETILE_PASSES;   // ... between two re-tilings of a long candidate list
 static const u32 RETILE_MIN_CANDS = 8192;        // shorter lists are never re-tiled
 
-static u32 tile_shift_for(u64 n) {               // smallest tile (256 << shift) with at most NT_MAX tiles
+static u32 tile_shift_for(u64 n, u32 max_tiles) { // smallest tile (256 << shift) with at most max_tiles tiles
   u32 sh = 0;
-  while ((((n + UNIT - 1) / UNIT) + (1ull << sh) - 1) >> sh > NT_MAX) ++sh;
+  while ((((n + UNIT - 1) / UNIT) + (1ull << sh) - 1) >> sh > max_tiles) ++sh;
   return sh;
 }
+
+static u32 clamp_limit(u32 asked, u32 lib_max) { return asked == 0 || asked > lib_max ? lib_max : asked; }
 
 // One device allocation for all planning workspaces (a handle is often short-lived; every
 // hipMalloc / hipFree costs about 0.1 ms): the layout is walked twice, first to measure.
@@ -1218,7 +1221,7 @@ static void work_layout(PlanWork* w, Arena& ar) {
   ar.take(&w->dropped, C);
 }
 
-static int work_alloc(g10_plan_s* h) {
+static int work_alloc(g10_plan_s* h, u32 max_chunks) {
   PlanWork* w = new (std::nothrow) PlanWork();
   if (!w) return G10_ENOMEM;
   h->work = w;
@@ -1227,12 +1230,12 @@ static int work_alloc(g10_plan_s* h) {
   w->K = K; w->C = C;
   w->Kp = (K + 3u) & ~3u;
   w->spt = 1; w->shift_ch = 8;
-  while ((u64)G10_BLOCK * w->spt * NCH_MAX < K) { w->spt *= 2; w->shift_ch += 1; }
+  w->max_chunks = max_chunks;
+  while ((u64)G10_BLOCK * w->spt * max_chunks < K) { w->spt *= 2; w->shift_ch += 1; }
   const u32 ch = G10_BLOCK * w->spt;
   w->nch = (K + ch - 1) / ch;
-  const u32 tsh = tile_shift_for(C);
-  w->cap_pad = ((C + ((u64)UNIT << tsh) - 1) >> (8 + tsh)) << (8 + tsh);
-  if (!w->cap_pad) w->cap_pad = UNIT;
+  // room for the padding of the last tile at any tile size: tiles hold at most max(256, C) candidates
+  w->cap_pad = 2 * (C > UNIT ? C : UNIT) + UNIT;
   Arena measure;
   work_layout(w, measure);
   void* q = nullptr;
@@ -1259,8 +1262,14 @@ static size_t loop_lds_bytes(u32 nch, u32 nt) {
 }
 
 int plan_run(g10_plan_s* h, const g10_params* p, g10_result* out) {
+  const u32 max_chunks = clamp_limit(p->max_chunks, NCH_MAX), max_tiles = clamp_limit(p->max_tiles, NT_MAX);
+  if (h->work && h->work->max_chunks != max_chunks) {      // another chunk size: lay the workspaces out again
+    G10_HIP(hipStreamSynchronize(h->stream));
+    plan_work_free(h->work);
+    h->work = nullptr;
+  }
   if (!h->work) {
-    int rc = work_alloc(h);
+    int rc = work_alloc(h, max_chunks);
     if (rc) { plan_work_free(h->work); h->work = nullptr; return rc; }
   }
   PlanWork* w = h->work;
@@ -1315,7 +1324,7 @@ int plan_run(g10_plan_s* h, const g10_params* p, g10_result* out) {
     int cur = 0;
     u32 tsh = 0, nt = 0, n_pad = 0;
     auto retile = [&](bool first) -> int {
-      tsh = tile_shift_for(n);
+      tsh = tile_shift_for(n, max_tiles);
       const u32 tile = UNIT << tsh;
       nt = (u32)(((u64)n + tile - 1) / tile);
       n_pad = nt * tile;

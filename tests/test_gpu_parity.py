@@ -114,6 +114,46 @@ def test_stress_scaled(g10, K, N, seed):
     h.close()
 
 
+@pytest.mark.parametrize("max_tiles,max_chunks", [(1, 1), (3, 2), (16, 5), (0, 3), (2, 0)])
+def test_tile_and_chunk_limits(g10, max_tiles, max_chunks):
+    """Large tiles (several scoring units per tile) and long chunks (several strips per
+    chunk job), reached with a small trace by lowering the limits; the plan does not
+    depend on them.  The same handle is laid out again when the chunk limit changes."""
+    w = traces.stress(K=2048, N=20000, seed=2)
+    h, v, args = run_both(g10, w)
+    p = v.plan(**args)
+    assert_plan_equal(h.plan(max_tiles=max_tiles, max_chunks=max_chunks, **args), p)
+    assert_plan_equal(h.plan(**args), p)
+    args2 = dict(args, gpu_cap=int(v.peak * 0.97), host_cap=2 ** 62)
+    assert_plan_equal(h.plan(max_tiles=max_tiles, max_chunks=max_chunks, **args2), v.plan(**args2))
+    h.close()
+
+
+@pytest.mark.parametrize("frac", [0.002, 0.004, 0.1])
+def test_tight_host_memory(g10, frac):
+    """Host memory fills up: winners are dropped, the exact per-slot host check runs."""
+    w = traces.stress(K=3000, N=30000, seed=7)
+    h, v, args = run_both(g10, w)
+    args = dict(args, host_cap=int(v.peak * frac), bw_out=(50, 25000), bw_in=(50, 25000))   # flash too slow for most
+    p = v.plan(**args)
+    r = h.plan(**args)
+    assert_plan_equal(r, p)
+    assert (r.records["dest"] == 1).any() and (r.n_dropped > 0 or frac > 0.05)
+    h.close()
+
+
+def test_long_timeline(g10):
+    """More kernels than 512 chunks of 256 slots hold: two strips per chunk job by default."""
+    w = traces.stress(K=140000, N=6000, seed=11)
+    h, v, args = run_both(g10, w)
+    p = v.plan(max_iters=600, **args)
+    r = h.plan(max_iters=600, **args)
+    assert r.status == g10.TRUNCATED == p.status and r.n_iterations == 600
+    assert_plan_equal(r, p, prefix=True)
+    assert (r.pressure_after == p.pressure_after).all()
+    h.close()
+
+
 def test_iteration_limit(g10):
     w = traces.resnet152()
     h, v, args = run_both(g10, w)
