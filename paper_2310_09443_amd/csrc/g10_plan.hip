@@ -45,6 +45,7 @@
 
 #include "g10_internal.h"
 
+#include <hip/hip_ext.h>
 #include <new>
 #include <stdio.h>
 #include <stdlib.h>
@@ -282,9 +283,10 @@ __global__ __launch_bounds__(G10_BLOCK) void k_ot_full(u64* __restrict__ ot, con
 // the streaming scoring pass over every candidate, before any eviction: all
 // channels are still free, so every valid window can be carried and
 // U = size * (largest over-capacity time of the valid windows).  Reads the 32
-// bytes of the candidate, gathers four words of a prefix table that fits L2
-// (8 bytes per slot), writes the 8-byte sort key: the 31-bit score key rounded
-// up to its top 23 bits (descending), then the position.
+// bytes of the candidate, gathers two words per window of a prefix table that
+// fits L2 (8 bytes per slot; a window inside the other one is skipped), writes
+// the 8-byte sort key: the 31-bit score key rounded up to its top 23 bits
+// (descending), then the position.
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ u64 sort_key(u32 key31, u32 posbits, u32 p) {
   return ((u64)(0x7fffffu - ((key31 + 255u) >> 8)) << posbits) | p;
@@ -300,13 +302,23 @@ __global__ __launch_bounds__(G10_BLOCK) void k_score_full(const uint4* __restric
   const uint4 A = cA[p], B = cB[p];
   const u64 s = ((u64)B.w << 32) | B.z;
   const u64 total = ot[K];
-  const bool v0 = A.z <= A.w, v1 = B.x <= B.y;
-  // an invalid window reads slot 0 twice: difference 0
-  const u32 a0 = v0 ? A.z : 0u, b0 = v0 ? A.w + 1 : 0u, a1 = v1 ? B.x : 0u, b1 = v1 ? B.y + 1 : 0u;
-  const u64 oa0 = ot[a0 >= K ? a0 - K : a0], ob0 = ot[b0 >= K ? b0 - K : b0];
-  const u64 oa1 = ot[a1 >= K ? a1 - K : a1], ob1 = ot[b1 >= K ? b1 - K : b1];
-  const u64 t0 = (ob0 + (b0 >= K ? total : 0ull)) - (oa0 + (a0 >= K ? total : 0ull));
-  const u64 t1 = (ob1 + (b1 >= K ? total : 0ull)) - (oa1 + (a1 >= K ? total : 0ull));
+  bool v0 = A.z <= A.w, v1 = B.x <= B.y;
+  // the prefix is monotone: a window inside the other one cannot hold more over-capacity time
+  if (v0 && v1) {
+    if (B.x <= A.z && B.y >= A.w) v0 = false;
+    else if (A.z <= B.x && A.w >= B.y) v1 = false;
+  }
+  u64 t0 = 0, t1 = 0;
+  if (v0) {
+    const u32 a = A.z, b = A.w + 1;
+    const u64 oa = ot[a >= K ? a - K : a], ob = ot[b >= K ? b - K : b];
+    t0 = (ob + (b >= K ? total : 0ull)) - (oa + (a >= K ? total : 0ull));
+  }
+  if (v1) {
+    const u32 a = B.x, b = B.y + 1;
+    const u64 oa = ot[a >= K ? a - K : a], ob = ot[b >= K ? b - K : b];
+    t1 = (ob + (b >= K ? total : 0ull)) - (oa + (a >= K ? total : 0ull));
+  }
   const u64 t = t1 > t0 ? t1 : t0;
   sortkeys[p] = sort_key(upkey(__umul64hi(s, t), s * t), posbits, p);
 }
@@ -1332,10 +1344,9 @@ int plan_run(g10_plan_s* h, const g10_params* p, g10_result* out) {
       const u32 posbits = bits_for(n - 1);
       if (first) {
         const u32 gn = (n + G10_BLOCK - 1) / G10_BLOCK;
-        G10_HIP(hipEventRecord(w->ev[2], s));
-        hipLaunchKernelGGL(k_score_full, dim3(gn), dim3(G10_BLOCK), 0, s, (const uint4*)w->cd[cur].A, (const uint4*)w->cd[cur].B, n,
-                           (const u64*)w->otc, K, posbits, w->keys);
-        G10_HIP(hipEventRecord(w->ev[3], s));
+        // the two events take the kernel's own begin and end time stamps
+        hipExtLaunchKernelGGL(k_score_full, dim3(gn), dim3(G10_BLOCK), 0, s, w->ev[2], w->ev[3], 0, (const uint4*)w->cd[cur].A,
+                              (const uint4*)w->cd[cur].B, n, (const u64*)w->otc, K, posbits, w->keys);
         timed_full = true;
       } else {
         u32 gn = (n + G10_BLOCK - 1) / G10_BLOCK;
