@@ -20,7 +20,11 @@
 //     is full during the transfer, in which case send it to host memory if
 //     host memory has room; update pressure and traffic }.
 //   * Section 4.4: Algorithm 1 assumes each prefetch starts at the latest
-//     time that still completes before the next use.
+//     time that still completes before the next use (the latest safe prefetch
+//     time).  Smart prefetching then takes the evicted periods in the order of
+//     that time and moves each prefetch back to the earliest time from which
+//     the GPU can hold the whole tensor without exceeding its capacity,
+//     raising the pressure curve in between.
 //
 // The paper leaves the discretisation open.  The readings taken here:
 //   * the timeline is divided into kernel slots (instructions can only be
@@ -34,7 +38,12 @@
 //     transfer; tested for the eviction and for the prefetch;
 //   * benefit = size x time spent over capacity inside the absent window;
 //     ranking by benefit alone, ties to the lowest period index;
-//   * flash full and host memory without room: the candidate is dropped.
+//   * flash full and host memory without room: the candidate is dropped;
+//   * smart prefetching: the prefetch moves back in whole kernel slots, at most
+//     to the slot boundary at which the eviction has ended; a slot can take
+//     the tensor if its pressure plus the tensor's size stays within the
+//     capacity; equal prefetch times keep the plan's order; only the pressure
+//     curve is updated (the paper says nothing of the channels here).
 //
 // Two evaluation modes compute the same values:
 //   mode 0 ("direct"):  every sum / max / search is the literal loop of its
@@ -50,7 +59,9 @@
 //
 // Parity status of the readings that the paper does not fix numerically
 // (benefit clipping, benefit-only ranking key, prefetch-side channel test,
-// slot rounding, dropping on flash-full + host-full): parity unpinned — the
+// slot rounding, dropping on flash-full + host-full, and in smart prefetching
+// the slot granularity, the lower limit and leaving the channels alone):
+// parity unpinned — the
 // paper prints no value that separates the alternatives.  Everything else is
 // pinned by the tests under tests/ (worked examples, closed forms,
 // invariants, brute force).
@@ -133,6 +144,12 @@ struct Oracle {
   std::vector<u64> pressure_after;
   std::vector<u64> busy_after[2][2];
   std::vector<u64> host_after;
+  std::vector<u32> rec_a, rec_b, rec_R;  // per record: absent slots [a, b] and next use, doubled coordinates
+  u64 plan_cap = 0;                  // GPU capacity the plan was made for
+  // smart prefetching output
+  std::vector<u32> pf_order;         // records in the order they were visited
+  std::vector<u32> pf_gained;        // per record: kernel slots by which its prefetch moved back
+  std::vector<u64> pressure_eager;   // pressure with the earlier prefetches
 };
 
 inline u64 ceil_div(u128 x, u64 y) { return (u64)((x + y - 1) / y); }
@@ -370,6 +387,8 @@ int plan(Oracle& o, const g10o_params& pr, int mode, u64 max_iters, g10o_summary
   o.records.clear();
   o.null_cands.clear();
   o.null_iters.clear();
+  o.rec_a.clear(); o.rec_b.clear(); o.rec_R.clear();
+  o.plan_cap = pr.gpu_cap;
   S.peak_before = P.max_pressure();
   S.overtime_before = P.total_over_time();
   const size_t C = P.cand.size();
@@ -402,6 +421,7 @@ int plan(Oracle& o, const g10o_params& pr, int mode, u64 max_iters, g10o_summary
     r.size = x.s; r.t_out = D.tau_o; r.t_in = D.tau_i;
     r.benefit_lo = (u64)wB; r.benefit_hi = (u64)(wB >> 64);
     o.records.push_back(r);
+    o.rec_a.push_back(D.a); o.rec_b.push_back(D.b); o.rec_R.push_back(x.R);
     P.commit(x, wd);
   }
   S.n_migrations = o.records.size();
@@ -410,6 +430,45 @@ int plan(Oracle& o, const g10o_params& pr, int mode, u64 max_iters, g10o_summary
   o.pressure_after = P.pressure;
   o.host_after = P.host_used;
   for (int d = 0; d < 2; ++d) for (int r = 0; r < 2; ++r) o.busy_after[d][r] = P.busy[d][r];
+  return 0;
+}
+
+// ------------------------------------------------------- smart prefetching
+// Section 4.4.  The evicted periods are visited in the order of their latest
+// safe prefetch time t_i = (start of the next use) - (prefetch time); equal
+// times in plan order.  From the slot before the prefetch the search goes back
+// while the slot can hold the tensor (pressure + size <= capacity), not past
+// the first absent slot; the prefetch is issued before the earliest such slot
+// and the pressure of the slots gained rises by the tensor's size.
+//   mode 0: the backward search as stated.
+//   mode 1: one forward sweep over the absent window that remembers the last
+//           slot that cannot hold the tensor.
+int prefetch(Oracle& o, int mode) {
+  const size_t n = o.records.size();
+  const u32 K = o.K;
+  const u64 cap = o.plan_cap;
+  o.pf_order.resize(n);
+  for (size_t i = 0; i < n; ++i) o.pf_order[i] = (u32)i;
+  std::vector<u64> t_safe(n);
+  for (size_t i = 0; i < n; ++i) t_safe[i] = start2(o, o.rec_R[i]) - o.records[i].t_in;
+  std::stable_sort(o.pf_order.begin(), o.pf_order.end(), [&](u32 x, u32 y) { return t_safe[x] < t_safe[y]; });
+  o.pressure_eager = o.pressure_after;
+  o.pf_gained.assign(n, 0);
+  std::vector<u64>& pr = o.pressure_eager;
+  for (u32 i : o.pf_order) {
+    const u64 s = o.records[i].size;
+    const u64 a = o.rec_a[i], b = o.rec_b[i];
+    auto holds = [&](u64 j) { const u64 x = pr[j % K]; return x <= cap && s <= cap - x; };
+    u64 p = b + 1;                                   // first slot the tensor is back in
+    if (mode == 0) {
+      while (p > a && holds(p - 1)) --p;
+    } else {
+      p = a;
+      for (u64 j = a; j <= b; ++j) if (!holds(j)) p = j + 1;
+    }
+    for (u64 j = p; j <= b; ++j) pr[j % K] += s;
+    o.pf_gained[i] = (u32)(b + 1 - p);
+  }
   return 0;
 }
 
@@ -440,6 +499,8 @@ void g10o_counts(void* h, u64* out) {
 // which: 0 use_off 1 use_k 2 birth 3 death 4 per_t 5 per_L 6 per_R 7 start
 //        8 pressure0 9 records 10 pressure_after 11 null_cands 12 host_after
 //        13 null_iters
+//        20 prefetch order 21 slots gained 22 pressure with the earlier prefetches
+//        23 / 24 absent window of every record in doubled coordinates
 //        16 + 2*d + r : busy_after[d][r]
 int g10o_copy(void* h, int which, void* dst) {
   Oracle* o = (Oracle*)h;
@@ -458,6 +519,11 @@ int g10o_copy(void* h, int which, void* dst) {
     case 11: copy_out(o->null_cands, dst); break;
     case 12: copy_out(o->host_after, dst); break;
     case 13: copy_out(o->null_iters, dst); break;
+    case 20: copy_out(o->pf_order, dst); break;
+    case 21: copy_out(o->pf_gained, dst); break;
+    case 22: copy_out(o->pressure_eager, dst); break;
+    case 23: copy_out(o->rec_a, dst); break;
+    case 24: copy_out(o->rec_b, dst); break;
     case 16: case 17: case 18: case 19:
       copy_out(o->busy_after[(which - 16) / 2][(which - 16) % 2], dst); break;
     default: return -1;
@@ -483,6 +549,12 @@ int g10o_windows(void* h, const g10o_params* pr, int mode, int dest,
     valid[c] = D.valid; a[c] = D.a; b[c] = D.b; tau_o[c] = D.tau_o; tau_i[c] = D.tau_i;
   }
   return 0;
+}
+
+// smart prefetching on the plan made last (g10o_plan must have run)
+int g10o_prefetch(void* h, int mode) {
+  if (!h) return -1;
+  return prefetch(*(Oracle*)h, mode);
 }
 
 void g10o_free(void* h) { delete (Oracle*)h; }

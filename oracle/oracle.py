@@ -54,6 +54,7 @@ def lib():
         _lib.g10o_plan.argtypes = [C.c_void_p, C.POINTER(_Params), C.c_int, C.c_uint64,
                                    C.POINTER(_Summary)]
         _lib.g10o_windows.argtypes = [C.c_void_p, C.POINTER(_Params), C.c_int, C.c_int] + [C.c_void_p] * 5
+        _lib.g10o_prefetch.argtypes = [C.c_void_p, C.c_int]
         _lib.g10o_free.argtypes = [C.c_void_p]
         _lib.g10o_free.restype = None
     return _lib
@@ -153,8 +154,36 @@ class Vitality:
             pass
 
 
+class Prefetch:
+    """Smart prefetching (Section 4.4) applied to a plan: per record the kernel
+    slots by which its prefetch moved back, the last absent slot that is left
+    (mod K; one before the first absent slot if none is left), the visiting
+    order and the pressure curve with the earlier prefetches."""
+
+    def __init__(self, plan: "Plan", mode: int):
+        v = plan._v
+        rc = lib().g10o_prefetch(v._h, mode)
+        if rc:
+            raise OracleError(rc)
+        n = len(plan.records)
+        self.order = v._get(20, n, np.uint32)
+        self.gained = v._get(21, n, np.uint32)
+        self.pressure = v._get(22, v.K, np.uint64)
+        self.absent_last = ((plan.b2.astype(np.int64) - self.gained) % v.K).astype(np.uint32)
+        self.n_moved = int((self.gained > 0).sum())
+        self.slots_gained = int(self.gained.astype(np.uint64).sum())
+        self.peak = int(self.pressure.max()) if v.K else 0
+
+
 class Plan:
+    def prefetch(self, mode=None) -> "Prefetch":
+        """Must be called before the handle plans again."""
+        return Prefetch(self, self._v.mode if mode is None else mode)
+
     def __init__(self, v: Vitality, s: _Summary, n_rec: int, n_null: int):
+        self._v = v
+        self.a2 = v._get(23, n_rec, np.uint32)      # absent window in doubled coordinates
+        self.b2 = v._get(24, n_rec, np.uint32)
         for f, _ in _Summary._fields_:
             setattr(self, f, int(getattr(s, f)))
         self.records = v._get(9, n_rec, RECORD)
