@@ -174,6 +174,33 @@ int g10_vitality_read(const g10_plan_t *handle, int which, void *dst, uint64_t b
  * getting under capacity is not an error: status = G10_RESIDUAL. */
 int g10_plan(g10_plan_t *handle, const g10_params *params, g10_result *out);
 
+/* Result of g10_prefetch; the arrays are host memory owned by the handle, valid until the
+ * next g10_plan / g10_prefetch on it or g10_plan_free. */
+typedef struct {
+  uint64_t n_migrations;        /* records of the plan                                  */
+  uint64_t n_moved;             /* prefetches that moved back                           */
+  uint64_t slots_gained;        /* kernel slots gained, summed over the records         */
+  uint64_t peak_bytes;          /* maximum of the pressure with the earlier prefetches  */
+  const uint32_t *order;        /* [n_migrations] records in the order they were visited */
+  const uint32_t *gained;       /* [n_migrations] slots by which each prefetch moved back */
+  const uint32_t *absent_last;  /* [n_migrations] last kernel slot in which the memory is still free
+                                   (the prefetch is issued after it); one before absent_first if
+                                   none is left                                          */
+  const uint64_t *pressure;     /* [K] bytes resident per kernel slot                   */
+  double ms;                    /* device time of the call                              */
+} g10_prefetch_result;
+
+/* Smart tensor prefetching (Section 4.4) on the plan the last g10_plan made on this handle.
+ * Algorithm 1 assumes every prefetch at its latest safe time (so that it ends exactly when
+ * the tensor is used again).  Here the evicted periods are visited in the order of that
+ * time (equal times in plan order); each prefetch is moved back, in whole kernel slots and
+ * not past the first slot in which the memory was free, as far as every slot up to the old
+ * prefetch can hold the whole tensor within the capacity the plan was made for, and the
+ * pressure of the slots gained rises by the tensor's size.  The channel reservations are
+ * left as the plan made them.  Runs on the handle's stream and synchronises it.
+ * Errors: G10_EINVAL (NULL, no plan on the handle), G10_ENOMEM, G10_EDEVICE. */
+int g10_prefetch(g10_plan_t *handle, g10_prefetch_result *out);
+
 /* Frees everything the library allocated for the handle.  NULL is allowed. */
 void g10_plan_free(g10_plan_t *handle);
 

@@ -20,7 +20,7 @@ FLASH, HOST = 0, 1
 FITS, RESIDUAL, TRUNCATED = 0, 1, 2
 NO_WRAP = 1
 
-EXPORTS = ["g10_vitality", "g10_vitality_info", "g10_vitality_read", "g10_plan", "g10_plan_free"]
+EXPORTS = ["g10_vitality", "g10_vitality_info", "g10_vitality_read", "g10_plan", "g10_prefetch", "g10_plan_free"]
 
 MIGRATION = np.dtype([("cand", "<u4"), ("tensor", "<u4"), ("evict_after", "<u4"),
                       ("absent_first", "<u4"), ("absent_last", "<u4"), ("next_use", "<u4"),
@@ -65,6 +65,12 @@ class _Result(C.Structure):
                 ("loop_second_rounds", C.c_uint64), ("loop_chunk_jobs", C.c_uint64)]
 
 
+class _PrefetchResult(C.Structure):
+    _fields_ = [("n_migrations", C.c_uint64), ("n_moved", C.c_uint64), ("slots_gained", C.c_uint64),
+                ("peak_bytes", C.c_uint64), ("order", C.c_void_p), ("gained", C.c_void_p),
+                ("absent_last", C.c_void_p), ("pressure", C.c_void_p), ("ms", C.c_double)]
+
+
 _lib = None
 
 
@@ -80,6 +86,7 @@ def load():
         lib.g10_vitality_info.argtypes = [C.c_void_p, C.POINTER(_Stats)]
         lib.g10_vitality_read.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_uint64]
         lib.g10_plan.argtypes = [C.c_void_p, C.POINTER(_Params), C.POINTER(_Result)]
+        lib.g10_prefetch.argtypes = [C.c_void_p, C.POINTER(_PrefetchResult)]
         lib.g10_plan_free.argtypes = [C.c_void_p]
         lib.g10_plan_free.restype = None
         _lib = lib
@@ -121,8 +128,20 @@ class Result:
         return np.frombuffer(buf, dtype=dtype, count=n).copy()
 
 
+class PrefetchResult:
+    def __init__(self, r: _PrefetchResult, K: int):
+        n = int(r.n_migrations)
+        self.n_migrations, self.n_moved, self.slots_gained = n, int(r.n_moved), int(r.slots_gained)
+        self.peak, self.ms = int(r.peak_bytes), float(r.ms)
+        self.order = Result._copy(r.order, n, np.dtype("<u4"))
+        self.gained = Result._copy(r.gained, n, np.dtype("<u4"))
+        self.absent_last = Result._copy(r.absent_last, n, np.dtype("<u4"))
+        self.pressure = Result._copy(r.pressure, K, np.dtype("<u8"))
+
+
 class Handle:
-    """g10_vitality on construction; g10_plan via .plan(); g10_plan_free on close."""
+    """g10_vitality on construction; g10_plan via .plan(); g10_prefetch via .prefetch();
+    g10_plan_free on close."""
 
     def __init__(self, dtrace: DeviceTrace, no_wrap: bool = False, stream=None):
         import torch
@@ -177,6 +196,15 @@ class Handle:
             raise G10Error(rc, "g10_plan")
         return Result(r, self.K)
 
+    def prefetch(self) -> PrefetchResult:
+        import torch
+        r = _PrefetchResult()
+        with torch.cuda.device(self._dev):
+            rc = load().g10_prefetch(self._h, C.byref(r))
+        if rc:
+            raise G10Error(rc, "g10_prefetch")
+        return PrefetchResult(r, self.K)
+
     def close(self):
         if self._h:
             load().g10_plan_free(self._h)
@@ -195,6 +223,10 @@ def g10_vitality(dtrace: DeviceTrace, no_wrap: bool = False, stream=None) -> Han
 
 def g10_plan(handle: Handle, gpu_cap, host_cap, bw_out, bw_in, max_iters=0, max_tiles=0, max_chunks=0) -> Result:
     return handle.plan(gpu_cap, host_cap, bw_out, bw_in, max_iters, max_tiles, max_chunks)
+
+
+def g10_prefetch(handle: Handle) -> PrefetchResult:
+    return handle.prefetch()
 
 
 def g10_plan_free(handle: Handle) -> None:

@@ -73,4 +73,15 @@ extern "C" int g10_plan(g10_plan_t* h, const g10_params* p, g10_result* out) {
   return rc;
 }
 
+extern "C" int g10_prefetch(g10_plan_t* h, g10_prefetch_result* out) {
+  if (out) memset(out, 0, sizeof *out);
+  if (!h || !out) return G10_EINVAL;
+  const int rc = prefetch_run(h, out);
+  if (rc) {
+    (void)hipStreamSynchronize(h->stream);
+    memset(out, 0, sizeof *out);
+  }
+  return rc;
+}
+
 extern "C" void g10_plan_free(g10_plan_t* h) { handle_free(h); }

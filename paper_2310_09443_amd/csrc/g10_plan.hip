@@ -470,6 +470,7 @@ struct LoopArgs {
   u32* g_keys;
   Ctl* ctl;
   g10_migration* records;
+  uint2* rec_ab;              // absent window [a, b] of every migration in doubled coordinates
   g10_dropped* dropped;
   u32 pass_budget;
 };
@@ -1056,6 +1057,7 @@ __global__ __launch_bounds__(LB) void k_loop(LoopArgs a) {
         mg.dest = d; mg.wraps = R >= K ? 1u : 0u;
         mg.size_bytes = s; mg.t_out_ns = S->tau_o; mg.t_in_ns = S->tau_i; mg.benefit_lo = S->win.lo; mg.benefit_hi = S->win.hi;
         a.records[S->n_mig] = mg;
+        a.rec_ab[S->n_mig] = make_uint2(wa, wb);
         S->n_mig += 1;
       }
     }
@@ -1159,7 +1161,15 @@ struct PlanWork {
       *peak_after = nullptr;
   Ctl* ctl = nullptr;
   g10_migration* records = nullptr;
+  uint2* rec_ab = nullptr;
   g10_dropped* dropped = nullptr;
+  // smart prefetching
+  u64 *pf_keys = nullptr, *pf_keys_alt = nullptr, *pf_pressure = nullptr, *pf_stats = nullptr;
+  u32 *pf_order = nullptr, *pf_order_alt = nullptr, *pf_gained = nullptr, *pf_last = nullptr;
+  u32 *h_pf_order = nullptr, *h_pf_gained = nullptr, *h_pf_last = nullptr;
+  u64* h_pf_pressure = nullptr;
+  bool planned = false;         // a plan is stored in the handle
+  u64 plan_cap = 0, plan_n_mig = 0;
   // host copies handed out through g10_result
   g10_migration* h_records = nullptr;
   g10_dropped* h_dropped = nullptr;
@@ -1176,6 +1186,7 @@ void plan_work_free(PlanWork* w) {
   free(w->h_records);
   free(w->h_dropped);
   free(w->h_pressure);
+  free(w->h_pf_order); free(w->h_pf_gained); free(w->h_pf_last); free(w->h_pf_pressure);
   for (hipEvent_t e : w->ev) if (e) (void)hipEventDestroy(e);
   delete w;
 }
@@ -1230,7 +1241,13 @@ static void work_layout(PlanWork* w, Arena& ar) {
   ar.take(&w->peak_after, 1);
   ar.take(&w->ctl, 1);
   ar.take(&w->records, C);
+  ar.take(&w->rec_ab, C);
   ar.take(&w->dropped, C);
+  ar.take(&w->pf_keys, C); ar.take(&w->pf_keys_alt, C);
+  ar.take(&w->pf_order, C); ar.take(&w->pf_order_alt, C);
+  ar.take(&w->pf_gained, C); ar.take(&w->pf_last, C);
+  ar.take(&w->pf_pressure, K);
+  ar.take(&w->pf_stats, 4);
 }
 
 static int work_alloc(g10_plan_s* h, u32 max_chunks) {
@@ -1288,6 +1305,7 @@ int plan_run(g10_plan_s* h, const g10_params* p, g10_result* out) {
   hipStream_t s = h->stream;
   const u32 K = h->K;
   const u32 C = (u32)h->n_periods;
+  w->planned = false;
 
   G10_HIP(hipEventRecord(w->ev[0], s));
   Ctl hc;
@@ -1376,7 +1394,7 @@ int plan_run(g10_plan_s* h, const g10_params* p, g10_result* out) {
     la.tl = tl;
     la.g_tot = w->g_tot; la.g_lazyP = w->g_lazyP; la.g_minOver = w->g_minOver; la.g_lazyH = w->g_lazyH; la.g_hmax = w->g_hmax;
     la.g_base = w->g_base;
-    la.g_keys = w->tkeys; la.ctl = w->ctl; la.records = w->records; la.dropped = w->dropped;
+    la.g_keys = w->tkeys; la.ctl = w->ctl; la.records = w->records; la.rec_ab = w->rec_ab; la.dropped = w->dropped;
     if (!w->lds_opt_in && loop_lds_bytes(w->nch, nt) > 64 * 1024) {
       G10_HIP(hipFuncSetAttribute((const void*)k_loop, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
       w->lds_opt_in = true;
@@ -1429,6 +1447,7 @@ int plan_run(g10_plan_s* h, const g10_params* p, g10_result* out) {
     fprintf(stderr, "  live/pass %.1f dests/pass %.1f\n", hc.phase[9] / (double)(hc.n_iter ? hc.n_iter : 1), hc.phase[10] / (double)(hc.n_iter ? hc.n_iter : 1));
   }
 #endif
+  w->planned = true; w->plan_cap = p->gpu_cap_bytes; w->plan_n_mig = hc.n_mig;
   memset(out, 0, sizeof *out);
   out->status = (int32_t)hc.status;
   out->n_migrations = hc.n_mig; out->n_iterations = hc.n_iter; out->n_dropped = hc.n_drop; out->n_cand_evals = hc.n_evals;
@@ -1439,5 +1458,203 @@ int plan_run(g10_plan_s* h, const g10_params* p, g10_result* out) {
   out->score_full_ms = full_ms; out->score_full_cands = n_valid;
   out->loop_ms = loop_ms; out->loop_launches = hc.launches; out->loop_retiles = retiles;
   out->loop_cands_scored = hc.units_scored * UNIT; out->loop_second_rounds = hc.second_rounds; out->loop_chunk_jobs = hc.jobs_run;
+  return G10_OK;
+}
+
+
+// ===========================================================================
+// Smart prefetching (Section 4.4) on a finished plan
+// ===========================================================================
+// The evicted periods are visited in the order of their latest safe prefetch
+// time; each prefetch moves back, in whole kernel slots and not past the first
+// absent slot, to the earliest slot from which every slot up to the old
+// prefetch can hold the tensor (pressure + size <= capacity); the pressure of
+// the slots gained rises by the tensor's size.  Every step depends on the
+// pressure the earlier ones left, so this is a serial chain like the eviction
+// loop and runs in one workgroup: the pressure in HBM / L2, per chunk a lazy
+// add and the chunk maximum in LDS.  The search asks the chunk maxima which
+// chunk can hold the last slot that cannot take the tensor and scans only that
+// chunk; the update adds lazily to whole chunks and slot by slot at the ends.
+namespace {
+
+__global__ __launch_bounds__(G10_BLOCK) void k_pf_keys(const g10_migration* __restrict__ rec, u32 n, const u64* __restrict__ start,
+                                                      u32 K, u64 T, u64* __restrict__ keys, u32* __restrict__ order) {
+  const u32 i = blockIdx.x * G10_BLOCK + threadIdx.x;
+  if (i >= n) return;
+  const u64 t_use = start[rec[i].next_use] + (rec[i].wraps ? T : 0ull);
+  keys[i] = t_use - rec[i].t_in_ns;              // latest safe prefetch time
+  order[i] = i;
+}
+
+struct PfShared {
+  unsigned long long cand;    // (upper end << 32 | lower end) of the chunk piece that may hold the last refusing slot
+  u32 found, q;               // a refusing slot was found; its doubled coordinate
+  u32 njobs, pad;
+  u64 n_moved, slots;
+};
+
+__global__ __launch_bounds__(LB) void k_eager(const g10_migration* __restrict__ rec, const uint2* __restrict__ rec_ab,
+                                             const u32* __restrict__ order, u32 n, u64* __restrict__ E, u32 K, u32 nch,
+                                             u32 spt, u32 shift_ch, u64 cap, u32* __restrict__ gained,
+                                             u32* __restrict__ last, u64* __restrict__ stats) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  u64* cmax = (u64*)smem;                          // [nch] largest pressure of the chunk (lazy add included)
+  u64* ladd = cmax + nch;                          // [nch] added to every slot of the chunk, not yet in E
+  PfShared* S = (PfShared*)(ladd + nch);
+  u32* jobs = (u32*)(S + 1);                       // [nch] chunks to rewrite slot by slot
+  const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6, CH = 1u << shift_ch;
+
+  for (u32 c = wave; c < nch; c += LW) {           // chunk maxima
+    u64 m = 0;
+    for (u32 st = 0; st < spt; ++st) {
+      const u32 j0 = c * CH + st * 256u + lane * 4u;
+#pragma unroll
+      for (u32 i = 0; i < 4; ++i) if (j0 + i < K) { const u64 x = E[j0 + i]; m = x > m ? x : m; }
+    }
+    m = wave_max(m);
+    if (lane == 0) { cmax[c] = m; ladd[c] = 0; }
+  }
+  if (tid == 0) { S->n_moved = 0; S->slots = 0; }
+  __syncthreads();
+
+  for (u32 it = 0; it < n; ++it) {
+    const u32 r = order[it];
+    const u64 s = rec[r].size_bytes;
+    const u32 a = rec_ab[r].x, b = rec_ab[r].y;
+    u32 p = b + 1;                                 // first slot the tensor is back in
+    if (s <= cap) {
+      const u64 lim = cap - s;                     // a slot holds the tensor iff its pressure <= lim
+      u32 upper = b;                               // the search is still open over [a, upper]
+      p = a;
+      while (true) {
+        if (tid == 0) { S->cand = 0ull; S->found = 0; }
+        __syncthreads();
+        if (tid < nch && cmax[tid] > lim) {        // the two places of the chunk on the doubled timeline
+          const u64 s0 = (u64)tid * CH, s1 = (s0 + CH - 1 < (u64)K - 1) ? s0 + CH - 1 : (u64)K - 1;
+#pragma unroll
+          for (u32 rep = 0; rep < 2; ++rep) {
+            const u64 o = rep ? K : 0u;
+            const u64 plo = s0 + o > a ? s0 + o : a, phi = s1 + o < upper ? s1 + o : upper;
+            if (plo <= phi) atomicMax(&S->cand, (unsigned long long)(((phi + 1) << 32) | plo));
+          }
+        }
+        __syncthreads();
+        const unsigned long long cd = S->cand;
+        if (cd == 0ull) break;                     // no chunk holds a refusing slot inside [a, upper]
+        const u32 hi = (u32)(cd >> 32) - 1u, lo = (u32)cd;
+        if (wave == 0) {                           // the last refusing slot of the piece, if any
+          u32 best = 0;                            // doubled coordinate + 1
+          for (u32 j0 = lo; j0 <= hi; j0 += 64) {
+            const u32 j = j0 + lane;
+            if (j <= hi) {
+              const u32 jj = j >= K ? j - K : j;
+              if (E[jj] + ladd[jj >> shift_ch] > lim) best = j + 1;      // ascending: the last one stays
+            }
+          }
+          best = wave_max(best);
+          if (lane == 0 && best) { S->found = 1; S->q = best - 1; }
+        }
+        __syncthreads();
+        if (S->found) { p = S->q + 1; break; }
+        if (lo == a) break;                        // nothing refuses in [a, upper]
+        upper = lo - 1;
+        __syncthreads();
+      }
+    }
+    __syncthreads();
+    const u32 g = b + 1 - p;
+    if (tid == 0) {
+      gained[r] = g;
+      const u32 nl = b - g;                        // last absent slot left (one before a if none)
+      last[r] = nl >= K ? nl - K : nl;
+      if (g) { S->n_moved += 1; S->slots += g; }
+      S->njobs = 0;
+    }
+    __syncthreads();
+    if (g) {                                       // the slots gained take the tensor
+      if (tid < nch) {
+        u32 len;
+        const u32 cv = cover(tid, CH, K, p, b, len);
+        if (cv == len) { ladd[tid] += s; cmax[tid] += s; }
+        else if (cv) jobs[atomicAdd(&S->njobs, 1u)] = tid;
+      }
+      __syncthreads();
+      const u32 nj = S->njobs;
+      for (u32 jb = wave; jb < nj; jb += LW) {
+        const u32 c = jobs[jb];
+        const u64 lz = ladd[c];
+        u64 m = 0;
+        for (u32 st = 0; st < spt; ++st) {
+          const u32 j0 = c * CH + st * 256u + lane * 4u;
+#pragma unroll
+          for (u32 i = 0; i < 4; ++i) {
+            const u32 j = j0 + i;
+            if (j < K) {
+              u64 x = E[j];
+              if (in_doubled(j, K, p, b) != NONE32) { x += s; E[j] = x; }
+              x += lz;
+              m = x > m ? x : m;
+            }
+          }
+        }
+        m = wave_max(m);
+        if (lane == 0) cmax[c] = m;
+      }
+      __syncthreads();
+    }
+  }
+  // the lazy adds into the slots; the peak
+  u64 m = 0;
+  for (u32 j = tid; j < K; j += LB) { const u64 x = E[j] + ladd[j >> shift_ch]; E[j] = x; m = x > m ? x : m; }
+  m = wave_max(m);
+  if (lane == 0) atomicMax((unsigned long long*)&stats[2], (unsigned long long)m);
+  if (tid == 0) { stats[0] = S->n_moved; stats[1] = S->slots; }
+}
+
+}  // namespace
+
+int prefetch_run(g10_plan_s* h, g10_prefetch_result* out) {
+  PlanWork* w = h->work;
+  if (!w || !w->planned) return G10_EINVAL;
+  hipStream_t s = h->stream;
+  const u32 K = h->K, n = (u32)w->plan_n_mig;
+  if (!w->h_pf_order) {
+    const u64 C = w->C ? w->C : 1;
+    w->h_pf_order = (u32*)malloc(C * 4); w->h_pf_gained = (u32*)malloc(C * 4); w->h_pf_last = (u32*)malloc(C * 4);
+    w->h_pf_pressure = (u64*)malloc((u64)K * 8);
+    if (!w->h_pf_order || !w->h_pf_gained || !w->h_pf_last || !w->h_pf_pressure) return G10_ENOMEM;
+  }
+  G10_HIP(hipEventRecord(w->ev[0], s));
+  G10_HIP(hipMemcpyAsync(w->pf_pressure, w->pressure_after, (u64)K * 8, hipMemcpyDeviceToDevice, s));
+  G10_HIP(hipMemsetAsync(w->pf_stats, 0, 4 * 8, s));
+  u64* keys = w->pf_keys; u64* alt = w->pf_keys_alt;
+  u32* ord = w->pf_order; u32* oalt = w->pf_order_alt;
+  if (n) {
+    hipLaunchKernelGGL(k_pf_keys, dim3((n + G10_BLOCK - 1) / G10_BLOCK), dim3(G10_BLOCK), 0, s, (const g10_migration*)w->records, n,
+                       (const u64*)h->start, K, h->T, keys, ord);
+    G10_HIP(hipGetLastError());
+    G10_TRY(radix_sort_u64_pairs(&keys, &alt, &ord, &oalt, n, bits_for(2 * h->T), w->hist, w->scratch32, s));
+  }
+  const size_t lds = ((size_t)2 * w->nch * 8 + sizeof(PfShared) + (size_t)w->nch * 4 + 15) & ~(size_t)15;
+  hipLaunchKernelGGL(k_eager, dim3(1), dim3(LB), lds, s, (const g10_migration*)w->records, (const uint2*)w->rec_ab,
+                     (const u32*)ord, n, w->pf_pressure, K, w->nch, w->spt, w->shift_ch, w->plan_cap, w->pf_gained, w->pf_last,
+                     w->pf_stats);
+  G10_HIP(hipGetLastError());
+  u64 st[4] = {0, 0, 0, 0};
+  G10_HIP(hipMemcpyAsync(st, w->pf_stats, sizeof st, hipMemcpyDeviceToHost, s));
+  if (n) {
+    G10_HIP(hipMemcpyAsync(w->h_pf_order, ord, (u64)n * 4, hipMemcpyDeviceToHost, s));
+    G10_HIP(hipMemcpyAsync(w->h_pf_gained, w->pf_gained, (u64)n * 4, hipMemcpyDeviceToHost, s));
+    G10_HIP(hipMemcpyAsync(w->h_pf_last, w->pf_last, (u64)n * 4, hipMemcpyDeviceToHost, s));
+  }
+  G10_HIP(hipMemcpyAsync(w->h_pf_pressure, w->pf_pressure, (u64)K * 8, hipMemcpyDeviceToHost, s));
+  G10_HIP(hipEventRecord(w->ev[1], s));
+  G10_HIP(hipStreamSynchronize(s));
+  float ms = 0.f;
+  G10_HIP(hipEventElapsedTime(&ms, w->ev[0], w->ev[1]));
+  memset(out, 0, sizeof *out);
+  out->n_migrations = n; out->n_moved = st[0]; out->slots_gained = st[1]; out->peak_bytes = st[2];
+  out->order = w->h_pf_order; out->gained = w->h_pf_gained; out->absent_last = w->h_pf_last; out->pressure = w->h_pf_pressure;
+  out->ms = ms;
   return G10_OK;
 }

@@ -157,7 +157,9 @@ __global__ __launch_bounds__(G10_BLOCK) void k_radix_hist(const u64* __restrict_
   hist[(u64)threadIdx.x * nblocks + blockIdx.x] = cnt[threadIdx.x];     // digit-major
 }
 
+template <bool PAIRS>
 __global__ __launch_bounds__(G10_BLOCK) void k_radix_scatter(const u64* __restrict__ keys, u64* __restrict__ out,
+                                                            const u32* __restrict__ vals, u32* __restrict__ vout,
                                                             u64 P, u32 shift, const u32* __restrict__ offs,
                                                             u32 nblocks) {
   __shared__ u32 cnt[G10_WAVES][256];        // per wavefront: running count per digit
@@ -167,12 +169,13 @@ __global__ __launch_bounds__(G10_BLOCK) void k_radix_scatter(const u64* __restri
   const u32 w = wave_id(), l = lane_id();
   const u64 lt = (1ull << l) - 1ull;
   u64 key[ITEMS];
-  u32 rank[ITEMS];
+  u32 rank[ITEMS], val[ITEMS];
 #pragma unroll
   for (u32 r = 0; r < ITEMS; ++r) {
     const u64 i = tile_index(r);
     const bool ok = i < P;
     key[r] = ok ? keys[i] : 0;
+    val[r] = PAIRS && ok ? vals[i] : 0u;
     const u32 dig = (u32)(key[r] >> shift) & 255u;
     u64 peers = __ballot(ok);
 #pragma unroll
@@ -204,7 +207,9 @@ __global__ __launch_bounds__(G10_BLOCK) void k_radix_scatter(const u64* __restri
     const u64 i = tile_index(r);
     if (i < P) {
       const u32 dig = (u32)(key[r] >> shift) & 255u;
-      out[(u64)gbase[dig] + cnt[w][dig] + rank[r]] = key[r];
+      const u64 pos = (u64)gbase[dig] + cnt[w][dig] + rank[r];
+      out[pos] = key[r];
+      if (PAIRS) vout[pos] = val[r];
     }
   }
 }
@@ -413,8 +418,26 @@ int radix_sort_u64(u64** keys, u64** alt, u64 n, u32 bits, u32* hist, u32* scrat
   for (u32 shift = 0; shift < bits; shift += 8) {
     hipLaunchKernelGGL(k_radix_hist, dim3(nb), dim3(G10_BLOCK), 0, s, *keys, n, shift, hist, nb);
     G10_TRY(scan_excl_u32(hist, hist, (u64)256 * nb, scratch, s));
-    hipLaunchKernelGGL(k_radix_scatter, dim3(nb), dim3(G10_BLOCK), 0, s, *keys, *alt, n, shift, hist, nb);
+    hipLaunchKernelGGL(k_radix_scatter<false>, dim3(nb), dim3(G10_BLOCK), 0, s, *keys, *alt, (const u32*)nullptr, (u32*)nullptr, n,
+                       shift, hist, nb);
     u64* t = *keys; *keys = *alt; *alt = t;
+  }
+  G10_HIP(hipGetLastError());
+  return G10_OK;
+}
+
+// The same with a 32-bit value carried along with every key; *vals / *valt swap like the keys.
+int radix_sort_u64_pairs(u64** keys, u64** alt, u32** vals, u32** valt, u64 n, u32 bits, u32* hist, u32* scratch,
+                         hipStream_t s) {
+  if (n == 0) return G10_OK;
+  const u32 nb = (u32)((n + TILE - 1) / TILE);
+  for (u32 shift = 0; shift < bits; shift += 8) {
+    hipLaunchKernelGGL(k_radix_hist, dim3(nb), dim3(G10_BLOCK), 0, s, *keys, n, shift, hist, nb);
+    G10_TRY(scan_excl_u32(hist, hist, (u64)256 * nb, scratch, s));
+    hipLaunchKernelGGL(k_radix_scatter<true>, dim3(nb), dim3(G10_BLOCK), 0, s, *keys, *alt, (const u32*)*vals, *valt, n, shift,
+                       hist, nb);
+    u64* t = *keys; *keys = *alt; *alt = t;
+    u32* v = *vals; *vals = *valt; *valt = v;
   }
   G10_HIP(hipGetLastError());
   return G10_OK;

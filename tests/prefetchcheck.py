@@ -45,3 +45,27 @@ def doubled_windows(K, records):
         a2.append(a)
         b2.append(b)
     return np.array(a2, np.uint32), np.array(b2, np.uint32)
+
+
+def replay_numpy(K, start, gpu_cap, records, a2, b2, pressure_after):
+    """The same replay with the backward walk done on numpy slices (for long plans)."""
+    T = int(start[K])
+    st2 = np.concatenate([np.asarray(start[:K], np.uint64), np.asarray(start[:K], np.uint64) + np.uint64(T)])
+    n = len(records)
+    R2 = records["next_use"].astype(np.int64) + np.where(records["wraps"] > 0, K, 0)
+    t_safe = st2[R2].astype(np.int64) - records["t_in"].astype(np.int64)
+    order = np.lexsort((np.arange(n), t_safe))
+    pr = np.asarray(pressure_after, np.uint64).copy()
+    gained = np.zeros(n, np.uint32)
+    cap = np.uint64(gpu_cap)
+    for i in order:
+        s, a, b = np.uint64(records["size"][i]), int(a2[i]), int(b2[i])
+        if s > cap:
+            continue
+        idx = np.arange(a, b + 1) % K
+        bad = np.flatnonzero(pr[idx] > cap - s)
+        p = a + (int(bad[-1]) + 1 if len(bad) else 0)
+        if p <= b:
+            pr[idx[p - a:]] += s
+            gained[i] = b + 1 - p
+    return order.astype(np.uint32), gained, pr

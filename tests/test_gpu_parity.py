@@ -5,6 +5,7 @@ import numpy as np
 import pytest
 
 import plancheck
+import prefetchcheck
 from goldenio import Golden
 from oracle import oracle as O
 from paper_2310_09443_amd import traces
@@ -52,6 +53,15 @@ def assert_plan_equal(r, p, prefix=False):
         assert (r.records[f][:n] == p.records[f]).all(), f
 
 
+def assert_prefetch_equal(f, fo):
+    """g10_prefetch against the oracle's smart prefetching on the same plan."""
+    assert (f.n_migrations, f.n_moved, f.slots_gained) == (len(fo.gained), fo.n_moved, fo.slots_gained)
+    assert (f.order == fo.order).all()
+    assert (f.gained == fo.gained).all()
+    assert (f.absent_last == fo.absent_last).all()
+    assert (f.pressure == fo.pressure).all() and f.peak == fo.peak
+
+
 def run_both(g10, w, no_wrap=False, **over):
     tr = w.trace
     v = O.Vitality(tr, O.PREFIX, no_wrap=no_wrap)
@@ -63,7 +73,7 @@ def run_both(g10, w, no_wrap=False, **over):
     return h, v, args
 
 
-@pytest.mark.parametrize("name", ["fig6_listing.txt", "hand_plan_a.txt", "hand_plan_b.txt"])
+@pytest.mark.parametrize("name", ["fig6_listing.txt", "hand_plan_a.txt", "hand_plan_b.txt", "hand_prefetch.txt"])
 def test_worked_examples(g10, name):
     g = Golden(name)
     v = O.Vitality(g.trace, O.DIRECT)
@@ -75,6 +85,12 @@ def test_worked_examples(g10, name):
         fields = FIELDS[:-2]
         got = [[int(x[f]) for f in fields] + [int(x["benefit_lo"]) + (int(x["benefit_hi"]) << 64)] for x in r.records]
         assert got == g.expect["record"]            # the values derived by hand, directly
+        f = h.prefetch()
+        assert_prefetch_equal(f, v.plan(**g.plan_args()).prefetch())
+        if "gained" in g.expect:
+            assert f.order.tolist() == g.expect["prefetch_order"][0] and f.gained.tolist() == g.expect["gained"][0]
+            assert f.absent_last.tolist() == g.expect["absent_last_eager"][0]
+            assert f.pressure.tolist() == g.expect["pressure_eager"][0]
     h.close()
 
 
@@ -83,7 +99,13 @@ def test_random_small(g10, seed):
     w = traces.random_small(5000 + seed, K=6 + seed % 20, N=4 + seed % 13, max_uses=5)
     no_wrap = seed % 4 == 0
     h, v, args = run_both(g10, w, no_wrap=no_wrap)
-    assert_plan_equal(h.plan(**args), v.plan(mode=O.DIRECT, **args))
+    p = v.plan(mode=O.DIRECT, **args)
+    assert_plan_equal(h.plan(**args), p)
+    assert_prefetch_equal(h.prefetch(), p.prefetch(O.DIRECT))
+    args2 = dict(args, gpu_cap=int(args["gpu_cap"] * 1.3))      # more room: prefetches do move
+    p = v.plan(mode=O.DIRECT, **args2)
+    assert_plan_equal(h.plan(**args2), p)
+    assert_prefetch_equal(h.prefetch(), p.prefetch(O.DIRECT))
     h.close()
 
 
@@ -94,6 +116,7 @@ def test_configs(g10, cfg):
     p = v.plan(**args)
     r = h.plan(**args)
     assert_plan_equal(r, p)
+    assert_prefetch_equal(h.prefetch(), p.prefetch())
     # same handle, different machine: the analysis is not modified by planning
     args2 = dict(args, gpu_cap=int(v.peak * 0.9), host_cap=0)
     assert_plan_equal(h.plan(**args2), v.plan(**args2))
@@ -111,6 +134,9 @@ def test_stress_scaled(g10, K, N, seed):
     args2 = dict(args, gpu_cap=int(v.peak * 0.97), host_cap=2 ** 62)
     p2 = v.plan(**args2)
     assert_plan_equal(h.plan(**args2), p2)
+    f2 = h.prefetch()
+    assert_prefetch_equal(f2, p2.prefetch())
+    assert f2.n_moved > 0
     h.close()
 
 
@@ -125,7 +151,9 @@ def test_tile_and_chunk_limits(g10, max_tiles, max_chunks):
     assert_plan_equal(h.plan(max_tiles=max_tiles, max_chunks=max_chunks, **args), p)
     assert_plan_equal(h.plan(**args), p)
     args2 = dict(args, gpu_cap=int(v.peak * 0.97), host_cap=2 ** 62)
-    assert_plan_equal(h.plan(max_tiles=max_tiles, max_chunks=max_chunks, **args2), v.plan(**args2))
+    p2 = v.plan(**args2)
+    assert_plan_equal(h.plan(max_tiles=max_tiles, max_chunks=max_chunks, **args2), p2)
+    assert_prefetch_equal(h.prefetch(), p2.prefetch())        # chunks of the same length as the plan's
     h.close()
 
 
@@ -233,6 +261,9 @@ def test_errors(g10):
     with pytest.raises(g10.G10Error) as e:
         h.plan(gpu_cap=1, host_cap=1, bw_out=(0, 1), bw_in=(1, 1))
     assert e.value.code == g10.EINVAL
+    with pytest.raises(g10.G10Error) as e:
+        h.prefetch()                                  # no plan on the handle yet
+    assert e.value.code == g10.EINVAL
     h.close()
 
 
@@ -258,6 +289,12 @@ def test_stress_full_size_prefix_and_properties(g10):
     # determinism: a second run returns the same bytes
     r2 = h.plan(**args)
     assert r2.records.tobytes() == r.records.tobytes()
+    # smart prefetching on the full plan, against the independent replay of the definitions
+    f = h.prefetch()
+    a2, b2 = prefetchcheck.doubled_windows(tr.K, r.records)
+    o, g, pr = prefetchcheck.replay_numpy(tr.K, v.start, args["gpu_cap"], r.records, a2, b2, r.pressure_after)
+    assert (f.order == o).all() and (f.gained == g).all() and (f.pressure == pr).all()
+    assert (f.n_moved, f.slots_gained, f.peak) == (int((g > 0).sum()), int(g.astype(np.uint64).sum()), int(pr.max()))
     h.close()
     # the oracle's complete plan, stored as digests (tests/golden/make_config5_digest.py)
     import hashlib

@@ -150,3 +150,5 @@ def test_configs_invariants(cfg):
     _invariants(v, p, f, cap)
     o, g, pr = prefetchcheck.replay(v.K, v.start, cap, p.records, p.a2, p.b2, p.pressure_after)
     assert (f.order == o).all() and (f.gained == g).all() and (f.pressure == pr).all()
+    o, g, pr = prefetchcheck.replay_numpy(v.K, v.start, cap, p.records, p.a2, p.b2, p.pressure_after)
+    assert (f.order == o).all() and (f.gained == g).all() and (f.pressure == pr).all()
