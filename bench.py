@@ -140,6 +140,15 @@ def main():
                             / (loop_ms * 1e-3) / 1e9 if loop_ms > 0 else 0.0},
     }
 
+    # smart prefetching (Section 4.4) on the finished plan: a further row of the path, timed on its own
+    hp = binding.g10_vitality(dt)
+    cap, hcap = traces.resolve_caps(w, hp.peak)
+    hp.plan(cap, hcap, w.bw_out_Bpus, w.bw_in_Bpus)
+    pf = [hp.prefetch() for _ in range(3)][-1]
+    hp.close()
+    out["smart_prefetch"] = {"kernel": "k_eager", "ms": pf.ms, "migrations": pf.n_migrations, "moved": pf.n_moved,
+                             "slots_gained": pf.slots_gained, "us_per_migration": 1e3 * pf.ms / max(pf.n_migrations, 1)}
+
     if not a.no_cpu:
         from oracle import oracle as O
         t0 = time.perf_counter()

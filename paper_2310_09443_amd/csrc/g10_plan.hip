@@ -1517,12 +1517,19 @@ __global__ __launch_bounds__(LB) void k_eager(const g10_migration* __restrict__ 
   if (tid == 0) { S->n_moved = 0; S->slots = 0; }
   __syncthreads();
 
+  // the next record is fetched while the current one is worked on
+  u32 r_next = n ? order[0] : 0u;
+  u64 s_next = n ? rec[r_next].size_bytes : 0ull;
+  uint2 ab_next = n ? rec_ab[r_next] : make_uint2(0u, 0u);
   for (u32 it = 0; it < n; ++it) {
-    const u32 r = order[it];
-    const u64 s = rec[r].size_bytes;
-    const u32 a = rec_ab[r].x, b = rec_ab[r].y;
+    const u32 r = r_next;
+    const u64 s = s_next;
+    const u32 a = ab_next.x, b = ab_next.y;
+    if (it + 1 < n) { r_next = order[it + 1]; s_next = rec[r_next].size_bytes; ab_next = rec_ab[r_next]; }
     u32 p = b + 1;                                 // first slot the tensor is back in
-    if (s <= cap) {
+    // the slot just before the prefetch decides most cases: if it cannot take the tensor, nothing moves
+    const u32 bb = b >= K ? b - K : b;
+    if (s <= cap && E[bb] + ladd[bb >> shift_ch] <= cap - s) {
       const u64 lim = cap - s;                     // a slot holds the tensor iff its pressure <= lim
       u32 upper = b;                               // the search is still open over [a, upper]
       p = a;

@@ -34,6 +34,7 @@ def test_struct_layouts_match_the_header():
     assert ctypes.sizeof(binding._Params) == 64
     assert ctypes.sizeof(binding._Stats) == 32
     assert ctypes.sizeof(binding._Result) == 8 + 8 * 8 + 3 * 8 + 9 * 8
+    assert ctypes.sizeof(binding._PrefetchResult) == 4 * 8 + 4 * 8 + 8
     assert binding.MIGRATION.itemsize == 72 and binding.DROPPED.itemsize == 16
 
 
@@ -42,6 +43,7 @@ def test_null_arguments_are_rejected_without_a_gpu():
     assert lib.g10_vitality(None, None, None) == binding.EINVAL
     assert lib.g10_plan(None, None, None) == binding.EINVAL
     assert lib.g10_vitality_info(None, None) == binding.EINVAL
+    assert lib.g10_prefetch(None, None) == binding.EINVAL
     lib.g10_plan_free(None)
     t = binding._Trace()                        # K = 0
     h = ctypes.c_void_p()
