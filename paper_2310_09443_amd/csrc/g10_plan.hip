@@ -549,28 +549,23 @@ __device__ __forceinline__ u32 in_doubled(u32 j, u32 K, u32 x, u32 y) {
 
 // The lane of the wavefront holding the best (benefit, lowest index), or NONE32
 // if every benefit is 0.  The 31-bit key decides unless several lanes share the
-// largest key; those few are compared in full one by one.
+// largest key (equal or nearly equal benefits: common where a model repeats one
+// layer); those are settled by three more reductions: high word, low word, index.
 __device__ __forceinline__ u32 wave_best_lane(u64 hi, u64 lo, u32 cand) {
   const u32 k = upkey(hi, lo);
   const u32 kmax = wave_max(k);
   if (kmax == 0) return NONE32;
   u64 m = __ballot(k == kmax);
-  u32 best = (u32)__builtin_ctzll(m);
-  m &= m - 1;
-  if (m) {
-    u64 bh = ((u64)__builtin_amdgcn_readlane((int)(hi >> 32), best) << 32) | (u32)__builtin_amdgcn_readlane((int)hi, best);
-    u64 bl = ((u64)__builtin_amdgcn_readlane((int)(lo >> 32), best) << 32) | (u32)__builtin_amdgcn_readlane((int)lo, best);
-    u32 bc = (u32)__builtin_amdgcn_readlane((int)cand, best);
-    while (m) {
-      const u32 l = (u32)__builtin_ctzll(m);
-      m &= m - 1;
-      const u64 yh = ((u64)__builtin_amdgcn_readlane((int)(hi >> 32), l) << 32) | (u32)__builtin_amdgcn_readlane((int)hi, l);
-      const u64 yl = ((u64)__builtin_amdgcn_readlane((int)(lo >> 32), l) << 32) | (u32)__builtin_amdgcn_readlane((int)lo, l);
-      const u32 yc = (u32)__builtin_amdgcn_readlane((int)cand, l);
-      if (better(yh, yl, yc, bh, bl, bc)) { bh = yh; bl = yl; bc = yc; best = l; }
-    }
+  if (m & (m - 1)) {
+    const bool in1 = k == kmax;
+    const u64 hmax = wave_max(in1 ? hi : 0ull);
+    const bool in2 = in1 && hi == hmax;
+    const u64 lmax = wave_max(in2 ? lo : 0ull);
+    const bool in3 = in2 && lo == lmax;
+    const u32 cmin = wave_min(in3 ? cand : NONE32);
+    m = __ballot(in3 && cand == cmin);
   }
-  return best;
+  return (u32)__builtin_ctzll(m);
 }
 
 __global__ __launch_bounds__(LB) void k_loop(LoopArgs a) {
