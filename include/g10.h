@@ -174,6 +174,17 @@ int g10_vitality_read(const g10_plan_t *handle, int which, void *dst, uint64_t b
  * getting under capacity is not an error: status = G10_RESIDUAL. */
 int g10_plan(g10_plan_t *handle, const g10_params *params, g10_result *out);
 
+/* `count` plans on one analysed trace in one call (capacity, host-memory or bandwidth
+ * sweeps): outs[i] is what g10_plan(handle, &params[i], &outs[i]) would return, bit for bit.
+ * The greedy loop of a plan is a serial chain that occupies one workgroup; a batch runs the
+ * loops of all its plans side by side (one workgroup each), so up to a few hundred plans take
+ * about as long as the slowest one plus their streaming passes.  Every plan keeps its own
+ * workspaces in the handle (about 350 bytes per inactive period): the result arrays of all
+ * `count` plans stay valid until the next planning call on the handle.  plan_ms and loop_ms of
+ * every result are those of the whole batch.  g10_prefetch afterwards refers to params[0]'s plan.
+ * Errors: as g10_plan; also G10_EINVAL for count = 0 or count > 4096. */
+int g10_plan_batch(g10_plan_t *handle, const g10_params *params, uint32_t count, g10_result *outs);
+
 /* Result of g10_prefetch; the arrays are host memory owned by the handle, valid until the
  * next g10_plan / g10_prefetch on it or g10_plan_free. */
 typedef struct {

@@ -20,7 +20,7 @@ FLASH, HOST = 0, 1
 FITS, RESIDUAL, TRUNCATED = 0, 1, 2
 NO_WRAP = 1
 
-EXPORTS = ["g10_vitality", "g10_vitality_info", "g10_vitality_read", "g10_plan", "g10_prefetch", "g10_plan_free"]
+EXPORTS = ["g10_vitality", "g10_vitality_info", "g10_vitality_read", "g10_plan", "g10_plan_batch", "g10_prefetch", "g10_plan_free"]
 
 MIGRATION = np.dtype([("cand", "<u4"), ("tensor", "<u4"), ("evict_after", "<u4"),
                       ("absent_first", "<u4"), ("absent_last", "<u4"), ("next_use", "<u4"),
@@ -86,6 +86,7 @@ def load():
         lib.g10_vitality_info.argtypes = [C.c_void_p, C.POINTER(_Stats)]
         lib.g10_vitality_read.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_uint64]
         lib.g10_plan.argtypes = [C.c_void_p, C.POINTER(_Params), C.POINTER(_Result)]
+        lib.g10_plan_batch.argtypes = [C.c_void_p, C.POINTER(_Params), C.c_uint32, C.POINTER(_Result)]
         lib.g10_prefetch.argtypes = [C.c_void_p, C.POINTER(_PrefetchResult)]
         lib.g10_plan_free.argtypes = [C.c_void_p]
         lib.g10_plan_free.restype = None
@@ -181,14 +182,32 @@ class Handle:
     start = property(lambda self: self.read(5))
     pressure = property(lambda self: self.read(6))
 
-    def plan(self, gpu_cap, host_cap, bw_out, bw_in, max_iters=0, max_tiles=0, max_chunks=0) -> Result:
-        import torch
-        p = _Params()
+    @staticmethod
+    def _fill(p, gpu_cap, host_cap, bw_out, bw_in, max_iters=0, max_tiles=0, max_chunks=0):
         p.gpu_cap_bytes, p.host_cap_bytes = int(gpu_cap), int(host_cap)
         p.bw_out_Bpus[0], p.bw_out_Bpus[1] = int(bw_out[0]), int(bw_out[1])
         p.bw_in_Bpus[0], p.bw_in_Bpus[1] = int(bw_in[0]), int(bw_in[1])
         p.max_iterations = int(max_iters)
         p.max_tiles, p.max_chunks = int(max_tiles), int(max_chunks)
+
+    def plan_batch(self, param_dicts):
+        """g10_plan_batch: one plan per dict of plan() keyword arguments."""
+        import torch
+        n = len(param_dicts)
+        ps = (_Params * n)()
+        for p, d in zip(ps, param_dicts):
+            self._fill(p, **d)
+        rs = (_Result * n)()
+        with torch.cuda.device(self._dev):
+            rc = load().g10_plan_batch(self._h, ps, n, rs)
+        if rc:
+            raise G10Error(rc, "g10_plan_batch")
+        return [Result(r, self.K) for r in rs]
+
+    def plan(self, gpu_cap, host_cap, bw_out, bw_in, max_iters=0, max_tiles=0, max_chunks=0) -> Result:
+        import torch
+        p = _Params()
+        self._fill(p, gpu_cap, host_cap, bw_out, bw_in, max_iters, max_tiles, max_chunks)
         r = _Result()
         with torch.cuda.device(self._dev):
             rc = load().g10_plan(self._h, C.byref(p), C.byref(r))
@@ -223,6 +242,10 @@ def g10_vitality(dtrace: DeviceTrace, no_wrap: bool = False, stream=None) -> Han
 
 def g10_plan(handle: Handle, gpu_cap, host_cap, bw_out, bw_in, max_iters=0, max_tiles=0, max_chunks=0) -> Result:
     return handle.plan(gpu_cap, host_cap, bw_out, bw_in, max_iters, max_tiles, max_chunks)
+
+
+def g10_plan_batch(handle: Handle, param_dicts):
+    return handle.plan_batch(param_dicts)
 
 
 def g10_prefetch(handle: Handle) -> PrefetchResult:

@@ -2,11 +2,15 @@
 #include "g10_internal.h"
 
 #include <new>
+#include <stdlib.h>
 #include <string.h>
 
 static void handle_free(g10_plan_s* h) {
   if (!h) return;
   plan_work_free(h->work);
+  for (u32 i = 0; i < h->n_more; ++i) plan_work_free(h->more[i]);
+  free(h->more);
+  if (h->loop_args) (void)hipFree(h->loop_args);
   void* dev[] = {h->dur, h->size, h->glob, h->start, h->ukeys, h->use_off, h->use_k, h->per_t, h->per_L, h->per_R,
                  h->pressure_buf};
   for (void* p : dev) if (p) (void)hipFree(p);
@@ -69,6 +73,20 @@ extern "C" int g10_plan(g10_plan_t* h, const g10_params* p, g10_result* out) {
   if (rc) {
     (void)hipStreamSynchronize(h->stream);
     memset(out, 0, sizeof *out);
+  }
+  return rc;
+}
+
+extern "C" int g10_plan_batch(g10_plan_t* h, const g10_params* params, uint32_t count, g10_result* outs) {
+  if (outs && count) memset(outs, 0, sizeof(g10_result) * (size_t)count);
+  if (!h || !params || !outs || !count || count > 4096) return G10_EINVAL;
+  for (uint32_t i = 0; i < count; ++i)
+    for (int d = 0; d < 2; ++d)
+      if (!params[i].bw_out_Bpus[d] || !params[i].bw_in_Bpus[d]) return G10_EINVAL;
+  const int rc = plan_batch_run(h, params, count, outs);
+  if (rc) {
+    (void)hipStreamSynchronize(h->stream);
+    memset(outs, 0, sizeof(g10_result) * (size_t)count);
   }
   return rc;
 }

@@ -198,10 +198,16 @@ struct g10_plan_s {
   u32* per_L = nullptr;
   u32* per_R = nullptr;
   u64* pressure_buf = nullptr;   // [K+1]; pressure = pressure_buf + 1
-  PlanWork* work = nullptr;
+  PlanWork* work = nullptr;      // workspaces of the first plan of a batch (the only one of g10_plan)
+  PlanWork** more = nullptr;     // ... of the further plans of a batch
+  u32 n_more = 0;
+  void* loop_args = nullptr;     // device array of per-plan arguments of the loop kernel
+  u32 loop_args_cap = 0;
+  bool lds_opt_in = false;       // the loop kernel was allowed more than 64 KB of LDS
 };
 
 int vitality_run(g10_plan_s* h, const g10_trace* tr);
 int plan_run(g10_plan_s* h, const g10_params* p, g10_result* out);
+int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_result* outs);
 int prefetch_run(g10_plan_s* h, g10_prefetch_result* out);
 void plan_work_free(PlanWork* w);

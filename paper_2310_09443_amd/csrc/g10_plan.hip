@@ -568,8 +568,9 @@ __device__ __forceinline__ u32 wave_best_lane(u64 hi, u64 lo, u32 cand) {
   return (u32)__builtin_ctzll(m);
 }
 
-__global__ __launch_bounds__(LB) void k_loop(LoopArgs a) {
+__global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans) {
   extern __shared__ __align__(16) unsigned char smem[];
+  const LoopArgs a = plans[blockIdx.x];        // one workgroup per plan
   const Timelines tl = a.tl;
   const u32 nch = tl.nch, nb1 = nch + 1, K = tl.K, CH = 1u << tl.shift_ch, nt = a.nt, ns = (nt + 63) / 64;
   u64* base = (u64*)smem;                               // [5][nch + 1]
@@ -1170,7 +1171,6 @@ struct PlanWork {
   g10_dropped* h_dropped = nullptr;
   u64* h_pressure = nullptr;
   hipEvent_t ev[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
-  bool lds_opt_in = false;
   void* arena = nullptr;        // the one device allocation all pointers above point into
   u32 max_chunks = 0;           // the chunk limit the timelines were laid out for
 };
@@ -1245,10 +1245,10 @@ static void work_layout(PlanWork* w, Arena& ar) {
   ar.take(&w->pf_stats, 4);
 }
 
-static int work_alloc(g10_plan_s* h, u32 max_chunks) {
+static int work_alloc(g10_plan_s* h, u32 max_chunks, PlanWork** slot) {
   PlanWork* w = new (std::nothrow) PlanWork();
   if (!w) return G10_ENOMEM;
-  h->work = w;
+  *slot = w;
   const u32 K = h->K;
   const u64 C = h->n_periods;
   w->K = K; w->C = C;
@@ -1285,177 +1285,254 @@ static size_t loop_lds_bytes(u32 nch, u32 nt) {
   return (b + 15) & ~(size_t)15;
 }
 
-int plan_run(g10_plan_s* h, const g10_params* p, g10_result* out) {
-  const u32 max_chunks = clamp_limit(p->max_chunks, NCH_MAX), max_tiles = clamp_limit(p->max_tiles, NT_MAX);
-  if (h->work && h->work->max_chunks != max_chunks) {      // another chunk size: lay the workspaces out again
-    G10_HIP(hipStreamSynchronize(h->stream));
-    plan_work_free(h->work);
-    h->work = nullptr;
-  }
-  if (!h->work) {
-    int rc = work_alloc(h, max_chunks);
-    if (rc) { plan_work_free(h->work); h->work = nullptr; return rc; }
-  }
-  PlanWork* w = h->work;
+// One plan of a batch, host side.
+struct Inst {
+  PlanWork* w = nullptr;
+  const g10_params* p = nullptr;
+  Ctl hc;
+  Timelines tl;
+  u32 n = 0, n_valid = 0, max_tiles = 0;
+  u32 tsh = 0, nt = 0, n_pad = 0;
+  int cur = 0;                 // the candidate buffer the loop reads
+  u64 retiles = 0, launches = 0, max_launches = 0, overtime_before = 0;
+  bool counted = false;        // hc.n_live holds a count of the current list
+  bool timed_full = false;
+};
+
+static PlanWork** work_slot(g10_plan_s* h, u32 i) { return i == 0 ? &h->work : &h->more[i - 1]; }
+
+// `count` plans on one analysed trace.  The streaming kernels of the plans run one after the
+// other (each fills the chip); the greedy loops run side by side, one workgroup per plan, in
+// one launch per round; between rounds the long candidate lists are put back into score order.
+int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_result* outs) {
   hipStream_t s = h->stream;
   const u32 K = h->K;
   const u32 C = (u32)h->n_periods;
-  w->planned = false;
-
-  G10_HIP(hipEventRecord(w->ev[0], s));
-  Ctl hc;
-  memset(&hc, 0, sizeof hc);
-  hc.gpu_cap = p->gpu_cap_bytes; hc.host_cap = p->host_cap_bytes;
-  for (int d = 0; d < 2; ++d) {
-    hc.bw_out[d] = p->bw_out_Bpus[d]; hc.bw_in[d] = p->bw_in_Bpus[d];
-    hc.inv_out[d] = hc.bw_out[d] > 1 ? (u64)((((unsigned __int128)1) << 64) / hc.bw_out[d]) : 0;
-    hc.inv_in[d] = hc.bw_in[d] > 1 ? (u64)((((unsigned __int128)1) << 64) / hc.bw_in[d]) : 0;
-  }
-  hc.max_iter = p->max_iterations;
-  hc.C = C;
-  G10_HIP(hipMemcpyAsync(w->ctl, &hc, sizeof hc, hipMemcpyHostToDevice, s));
-
-  Timelines tl;
-  tl.dur = h->dur; tl.P = w->P; tl.fre = w->fre; tl.H = w->H; tl.px = w->px; tl.otc = w->otc;
-  tl.K = K; tl.Kp = w->Kp; tl.nch = w->nch; tl.spt = w->spt; tl.shift_ch = w->shift_ch;
-
-  G10_HIP(hipMemsetAsync(w->peak_after, 0, 8, s));
-  hipLaunchKernelGGL(k_init_timelines, dim3(w->nch), dim3(G10_BLOCK), 0, s, tl, (const u64*)(h->pressure_buf + 1),
-                     (const Ctl*)w->ctl, w->g_tot, w->g_lazyP, w->g_minOver, w->g_lazyH, w->g_hmax);
-  hipLaunchKernelGGL(k_level1_init, dim3(1), dim3(LB), 0, s, (const u64*)w->g_tot, w->nch, w->base0, w->ctl);
-  hipLaunchKernelGGL(k_ot_full, dim3(K / G10_BLOCK + 1), dim3(G10_BLOCK), 0, s, w->otc, (const u64*)w->base0, K, w->nch, w->shift_ch);
-  G10_HIP(hipGetLastError());
-
-  // candidates: windows per destination; keep those with at least one valid window
-  u32 n = 0;
   const u32 gC = (C + G10_BLOCK - 1) / G10_BLOCK;
-  if (C) {
-    hipLaunchKernelGGL(k_prep, dim3(gC), dim3(G10_BLOCK), 0, s, h->per_t, h->per_L, h->per_R, h->size, h->start, K, h->T, C,
-                       (const Ctl*)w->ctl, w->win, w->keep);
-    G10_HIP(hipGetLastError());
-    G10_TRY(scan_excl_u32(w->keep, w->keep, C, w->scratch32, s));
-    G10_HIP(hipMemcpyAsync(&n, w->keep + C, sizeof(u32), hipMemcpyDeviceToHost, s));
+  if (count > 1 + h->n_more) {                             // more workspace slots
+    PlanWork** m = (PlanWork**)realloc(h->more, (size_t)(count - 1) * sizeof(PlanWork*));
+    if (!m) return G10_ENOMEM;
+    for (u32 i = h->n_more; i < count - 1; ++i) m[i] = nullptr;
+    h->more = m; h->n_more = count - 1;
   }
-  G10_HIP(hipMemcpyAsync(&hc, w->ctl, sizeof hc, hipMemcpyDeviceToHost, s));
-  G10_HIP(hipStreamSynchronize(s));
-  const u64 overtime_before = hc.overtime_before;
-  const u32 n_valid = n;                                  // candidates with a valid window
+  if (count > h->loop_args_cap) {
+    if (h->loop_args) { G10_HIP(hipStreamSynchronize(s)); (void)hipFree(h->loop_args); h->loop_args = nullptr; h->loop_args_cap = 0; }
+    void* q = nullptr;
+    if (hipMalloc(&q, (size_t)count * sizeof(LoopArgs)) != hipSuccess) { (void)hipGetLastError(); return G10_ENOMEM; }
+    h->loop_args = q; h->loop_args_cap = count;
+  }
+  Inst* I = new (std::nothrow) Inst[count];
+  LoopArgs* hargs = (LoopArgs*)malloc((size_t)count * sizeof(LoopArgs));
+  struct Guard { Inst* i; LoopArgs* a; ~Guard() { delete[] i; free(a); } } guard{I, hargs};
+  if (!I || !hargs) return G10_ENOMEM;
 
-  float full_ms = 0.f, loop_ms = 0.f;
-  bool timed_full = false, timed_loop = false;
-  u64 retiles = 0;
-  if (!hc.done) {
-    // candidates into score order, in tiles; `cur` is the buffer the loop reads
-    int cur = 0;
-    u32 tsh = 0, nt = 0, n_pad = 0;
-    auto retile = [&](bool first) -> int {
-      tsh = tile_shift_for(n, max_tiles);
-      const u32 tile = UNIT << tsh;
-      nt = (u32)(((u64)n + tile - 1) / tile);
-      n_pad = nt * tile;
-      if (!n) return G10_OK;
-      const u32 posbits = bits_for(n - 1);
-      if (first) {
-        const u32 gn = (n + G10_BLOCK - 1) / G10_BLOCK;
-        // the two events take the kernel's own begin and end time stamps
-        hipExtLaunchKernelGGL(k_score_full, dim3(gn), dim3(G10_BLOCK), 0, s, w->ev[2], w->ev[3], 0, (const uint4*)w->cd[cur].A,
-                              (const uint4*)w->cd[cur].B, n, (const u64*)w->otc, K, posbits, w->keys);
-        timed_full = true;
-      } else {
-        u32 gn = (n + G10_BLOCK - 1) / G10_BLOCK;
-        if (gn > 2048) gn = 2048;
-        G10_HIP(hipMemsetAsync(&w->ctl->n_live, 0, sizeof(u32), s));
-        hipLaunchKernelGGL(k_rescore, dim3(gn), dim3(G10_BLOCK), (size_t)N_ARR * (w->nch + 1) * 8, s, w->cd[cur], n,
-                           (const u64*)w->px, (const u64*)w->g_base, K, w->nch, w->shift_ch, (const Ctl*)w->ctl, posbits,
-                           w->keys, &w->ctl->n_live);
-      }
-      G10_HIP(hipGetLastError());
-      u64 *keys = w->keys, *alt = w->keys_alt;
-      G10_TRY(radix_sort_u64(&keys, &alt, n, posbits + 23, w->hist, w->scratch32, s));
-      G10_HIP(hipMemsetAsync(w->tkeys, 0, (u64)NT_MAX * 4, s));
-      hipLaunchKernelGGL(k_tile_gather, dim3(n_pad / G10_BLOCK), dim3(G10_BLOCK), 0, s, (const u64*)keys, n, n_pad, posbits,
-                         w->cd[cur], w->cd[cur ^ 1], 8 + tsh, w->tkeys);
-      G10_HIP(hipGetLastError());
-      cur ^= 1;
-      return G10_OK;
-    };
-    if (n) {
-      hipLaunchKernelGGL(k_pack, dim3(gC), dim3(G10_BLOCK), 0, s, h->per_t, h->per_L, h->per_R, h->size, (const uint4*)w->win,
-                         (const u32*)w->keep, C, w->cd[cur]);
-      G10_HIP(hipGetLastError());
-    }
-    G10_TRY(retile(true));
-    LoopArgs la;
-    la.tl = tl;
-    la.g_tot = w->g_tot; la.g_lazyP = w->g_lazyP; la.g_minOver = w->g_minOver; la.g_lazyH = w->g_lazyH; la.g_hmax = w->g_hmax;
-    la.g_base = w->g_base;
-    la.g_keys = w->tkeys; la.ctl = w->ctl; la.records = w->records; la.rec_ab = w->rec_ab; la.dropped = w->dropped;
-    if (!w->lds_opt_in && loop_lds_bytes(w->nch, nt) > 64 * 1024) {
-      G10_HIP(hipFuncSetAttribute((const void*)k_loop, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-      w->lds_opt_in = true;
-    }
-    G10_HIP(hipEventRecord(w->ev[4], s));
-    // Every pass removes a candidate or stops, so the launches are bounded.  Long lists are
-    // put back into score order every RETILE_PASSES passes: the tiles the loop looks at are
-    // dense with live candidates again, and the list is cut to those that can still score.
-    const u64 max_launches = (u64)n / RETILE_PASSES + 3;
-    u64 launches = 0;
-    bool counted = false;                                   // hc.n_live holds a count of the current list
-    while (!hc.done) {
-      if (launches++ > max_launches) return G10_EDEVICE;
-      la.cd = w->cd[cur]; la.n_pad = n_pad; la.nt = nt; la.tshift = tsh;
-      la.pass_budget = n > RETILE_MIN_CANDS ? RETILE_PASSES : PASS_BUDGET;
-      hipLaunchKernelGGL(k_loop, dim3(1), dim3(LB), loop_lds_bytes(w->nch, nt), s, la);
-      G10_HIP(hipGetLastError());
-      G10_HIP(hipMemcpyAsync(&hc, w->ctl, sizeof hc, hipMemcpyDeviceToHost, s));
+  for (u32 i = 0; i < count; ++i) {
+    const g10_params* p = params + i;
+    const u32 max_chunks = clamp_limit(p->max_chunks, NCH_MAX);
+    PlanWork** slot = work_slot(h, i);
+    if (*slot && (*slot)->max_chunks != max_chunks) {      // another chunk size: lay the workspaces out again
       G10_HIP(hipStreamSynchronize(s));
-      if (!hc.done && n > RETILE_MIN_CANDS) {
-        if (counted && hc.n_live < n) n = hc.n_live;        // live candidates come first in the list
-        G10_TRY(retile(false));
-        counted = true;
-        ++retiles;
+      plan_work_free(*slot);
+      *slot = nullptr;
+    }
+    if (!*slot) {
+      int rc = work_alloc(h, max_chunks, slot);
+      if (rc) { plan_work_free(*slot); *slot = nullptr; return rc; }
+    }
+    I[i].w = *slot; I[i].p = p; I[i].max_tiles = clamp_limit(p->max_tiles, NT_MAX);
+    (*slot)->planned = false;
+  }
+
+  // ---- timelines before any eviction, candidate windows --------------------------------
+  G10_HIP(hipEventRecord(I[0].w->ev[0], s));
+  for (u32 i = 0; i < count; ++i) {
+    Inst& x = I[i];
+    PlanWork* w = x.w;
+    const g10_params* p = x.p;
+    Ctl& hc = x.hc;
+    memset(&hc, 0, sizeof hc);
+    hc.gpu_cap = p->gpu_cap_bytes; hc.host_cap = p->host_cap_bytes;
+    for (int d = 0; d < 2; ++d) {
+      hc.bw_out[d] = p->bw_out_Bpus[d]; hc.bw_in[d] = p->bw_in_Bpus[d];
+      hc.inv_out[d] = hc.bw_out[d] > 1 ? (u64)((((unsigned __int128)1) << 64) / hc.bw_out[d]) : 0;
+      hc.inv_in[d] = hc.bw_in[d] > 1 ? (u64)((((unsigned __int128)1) << 64) / hc.bw_in[d]) : 0;
+    }
+    hc.max_iter = p->max_iterations;
+    hc.C = C;
+    G10_HIP(hipMemcpyAsync(w->ctl, &hc, sizeof hc, hipMemcpyHostToDevice, s));
+    Timelines& tl = x.tl;
+    tl.dur = h->dur; tl.P = w->P; tl.fre = w->fre; tl.H = w->H; tl.px = w->px; tl.otc = w->otc;
+    tl.K = K; tl.Kp = w->Kp; tl.nch = w->nch; tl.spt = w->spt; tl.shift_ch = w->shift_ch;
+    G10_HIP(hipMemsetAsync(w->peak_after, 0, 8, s));
+    hipLaunchKernelGGL(k_init_timelines, dim3(w->nch), dim3(G10_BLOCK), 0, s, tl, (const u64*)(h->pressure_buf + 1),
+                       (const Ctl*)w->ctl, w->g_tot, w->g_lazyP, w->g_minOver, w->g_lazyH, w->g_hmax);
+    hipLaunchKernelGGL(k_level1_init, dim3(1), dim3(LB), 0, s, (const u64*)w->g_tot, w->nch, w->base0, w->ctl);
+    hipLaunchKernelGGL(k_ot_full, dim3(K / G10_BLOCK + 1), dim3(G10_BLOCK), 0, s, w->otc, (const u64*)w->base0, K, w->nch, w->shift_ch);
+    G10_HIP(hipGetLastError());
+    if (C) {      // windows per destination; keep the candidates with at least one valid window
+      hipLaunchKernelGGL(k_prep, dim3(gC), dim3(G10_BLOCK), 0, s, h->per_t, h->per_L, h->per_R, h->size, h->start, K, h->T, C,
+                         (const Ctl*)w->ctl, w->win, w->keep);
+      G10_HIP(hipGetLastError());
+      G10_TRY(scan_excl_u32(w->keep, w->keep, C, w->scratch32, s));
+      G10_HIP(hipMemcpyAsync(&x.n, w->keep + C, sizeof(u32), hipMemcpyDeviceToHost, s));
+    }
+    G10_HIP(hipMemcpyAsync(&hc, w->ctl, sizeof hc, hipMemcpyDeviceToHost, s));
+  }
+  G10_HIP(hipStreamSynchronize(s));
+
+  // candidates of plan x into score order, in tiles
+  auto retile = [&](Inst& x, bool first) -> int {
+    PlanWork* w = x.w;
+    x.tsh = tile_shift_for(x.n, x.max_tiles);
+    const u32 tile = UNIT << x.tsh;
+    x.nt = (u32)(((u64)x.n + tile - 1) / tile);
+    x.n_pad = x.nt * tile;
+    if (!x.n) return G10_OK;
+    const u32 n = x.n, posbits = bits_for(n - 1);
+    if (first) {
+      const u32 gn = (n + G10_BLOCK - 1) / G10_BLOCK;
+      // the two events take the kernel's own begin and end time stamps
+      hipExtLaunchKernelGGL(k_score_full, dim3(gn), dim3(G10_BLOCK), 0, s, w->ev[2], w->ev[3], 0, (const uint4*)w->cd[x.cur].A,
+                            (const uint4*)w->cd[x.cur].B, n, (const u64*)w->otc, K, posbits, w->keys);
+      x.timed_full = true;
+    } else {
+      u32 gn = (n + G10_BLOCK - 1) / G10_BLOCK;
+      if (gn > 2048) gn = 2048;
+      G10_HIP(hipMemsetAsync(&w->ctl->n_live, 0, sizeof(u32), s));
+      hipLaunchKernelGGL(k_rescore, dim3(gn), dim3(G10_BLOCK), (size_t)N_ARR * (w->nch + 1) * 8, s, w->cd[x.cur], n,
+                         (const u64*)w->px, (const u64*)w->g_base, K, w->nch, w->shift_ch, (const Ctl*)w->ctl, posbits,
+                         w->keys, &w->ctl->n_live);
+    }
+    G10_HIP(hipGetLastError());
+    u64 *keys = w->keys, *alt = w->keys_alt;
+    G10_TRY(radix_sort_u64(&keys, &alt, n, posbits + 23, w->hist, w->scratch32, s));
+    G10_HIP(hipMemsetAsync(w->tkeys, 0, (u64)NT_MAX * 4, s));
+    hipLaunchKernelGGL(k_tile_gather, dim3(x.n_pad / G10_BLOCK), dim3(G10_BLOCK), 0, s, (const u64*)keys, n, x.n_pad, posbits,
+                       w->cd[x.cur], w->cd[x.cur ^ 1], 8 + x.tsh, w->tkeys);
+    G10_HIP(hipGetLastError());
+    x.cur ^= 1;
+    return G10_OK;
+  };
+
+  u32 n_active = 0;
+  size_t lds_max = 0;
+  for (u32 i = 0; i < count; ++i) {
+    Inst& x = I[i];
+    x.overtime_before = x.hc.overtime_before;
+    x.n_valid = x.n;
+    // every pass removes a candidate or stops, so the launches are bounded
+    x.max_launches = (u64)x.n / RETILE_PASSES + 3;
+    if (x.hc.done) continue;
+    ++n_active;
+    if (x.n) {
+      hipLaunchKernelGGL(k_pack, dim3(gC), dim3(G10_BLOCK), 0, s, h->per_t, h->per_L, h->per_R, h->size, (const uint4*)x.w->win,
+                         (const u32*)x.w->keep, C, x.w->cd[x.cur]);
+      G10_HIP(hipGetLastError());
+    }
+    G10_TRY(retile(x, true));
+    const size_t lds = loop_lds_bytes(x.w->nch, x.nt);
+    if (lds > lds_max) lds_max = lds;
+  }
+  if (!h->lds_opt_in && lds_max > 64 * 1024) {
+    G10_HIP(hipFuncSetAttribute((const void*)k_loop, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+    h->lds_opt_in = true;
+  }
+
+  // ---- the greedy loops: one workgroup per plan, side by side ------------------------------
+  // Long lists are put back into score order every RETILE_PASSES passes: the tiles the loop
+  // looks at are dense with live candidates again, and the list is cut to those that can
+  // still score.
+  const bool timed_loop = n_active != 0;
+  if (timed_loop) G10_HIP(hipEventRecord(I[0].w->ev[4], s));
+  while (n_active) {
+    u32 na = 0;
+    size_t lds = 0;
+    for (u32 i = 0; i < count; ++i) {
+      Inst& x = I[i];
+      if (x.hc.done) continue;
+      if (x.launches++ > x.max_launches) return G10_EDEVICE;
+      PlanWork* w = x.w;
+      LoopArgs& la = hargs[na++];
+      la.tl = x.tl;
+      la.g_tot = w->g_tot; la.g_lazyP = w->g_lazyP; la.g_minOver = w->g_minOver; la.g_lazyH = w->g_lazyH; la.g_hmax = w->g_hmax;
+      la.g_base = w->g_base;
+      la.g_keys = w->tkeys; la.ctl = w->ctl; la.records = w->records; la.rec_ab = w->rec_ab; la.dropped = w->dropped;
+      la.cd = w->cd[x.cur]; la.n_pad = x.n_pad; la.nt = x.nt; la.tshift = x.tsh;
+      la.pass_budget = x.n > RETILE_MIN_CANDS ? RETILE_PASSES : PASS_BUDGET;
+      const size_t l = loop_lds_bytes(w->nch, x.nt);
+      if (l > lds) lds = l;
+    }
+    G10_HIP(hipMemcpyAsync(h->loop_args, hargs, (size_t)na * sizeof(LoopArgs), hipMemcpyHostToDevice, s));
+    hipLaunchKernelGGL(k_loop, dim3(na), dim3(LB), lds, s, (const LoopArgs*)h->loop_args);
+    G10_HIP(hipGetLastError());
+    for (u32 i = 0; i < count; ++i)
+      if (!I[i].hc.done) G10_HIP(hipMemcpyAsync(&I[i].hc, I[i].w->ctl, sizeof(Ctl), hipMemcpyDeviceToHost, s));
+    G10_HIP(hipStreamSynchronize(s));
+    n_active = 0;
+    for (u32 i = 0; i < count; ++i) {
+      Inst& x = I[i];
+      if (x.hc.done) continue;
+      ++n_active;
+      if (x.n > RETILE_MIN_CANDS) {
+        if (x.counted && x.hc.n_live < x.n) x.n = x.hc.n_live;   // live candidates come first in the list
+        G10_TRY(retile(x, false));
+        x.counted = true;
+        ++x.retiles;
       }
     }
-    G10_HIP(hipEventRecord(w->ev[5], s));
-    timed_loop = true;
   }
+  if (timed_loop) G10_HIP(hipEventRecord(I[0].w->ev[5], s));
 
-  hipLaunchKernelGGL(k_finish, dim3(K / G10_BLOCK / 4 + 1), dim3(G10_BLOCK), 0, s, tl, (const u64*)w->g_lazyP, w->pressure_after,
-                     w->peak_after);
-  G10_HIP(hipGetLastError());
-  u64 peak_after = 0;
-  G10_HIP(hipMemcpyAsync(&peak_after, w->peak_after, 8, hipMemcpyDeviceToHost, s));
-  if (hc.n_mig) G10_HIP(hipMemcpyAsync(w->h_records, w->records, hc.n_mig * sizeof(g10_migration), hipMemcpyDeviceToHost, s));
-  if (hc.n_drop) G10_HIP(hipMemcpyAsync(w->h_dropped, w->dropped, hc.n_drop * sizeof(g10_dropped), hipMemcpyDeviceToHost, s));
-  G10_HIP(hipMemcpyAsync(w->h_pressure, w->pressure_after, (u64)K * 8, hipMemcpyDeviceToHost, s));
-  G10_HIP(hipEventRecord(w->ev[1], s));
+  // ---- results ---------------------------------------------------------------------------
+  u64* peaks = (u64*)hargs;                                // reuse as a small host buffer (count <= its size / 8)
+  for (u32 i = 0; i < count; ++i) {
+    Inst& x = I[i];
+    PlanWork* w = x.w;
+    const Ctl& hc = x.hc;
+    hipLaunchKernelGGL(k_finish, dim3(K / G10_BLOCK / 4 + 1), dim3(G10_BLOCK), 0, s, x.tl, (const u64*)w->g_lazyP, w->pressure_after,
+                       w->peak_after);
+    G10_HIP(hipGetLastError());
+    G10_HIP(hipMemcpyAsync(&peaks[i], w->peak_after, 8, hipMemcpyDeviceToHost, s));
+    if (hc.n_mig) G10_HIP(hipMemcpyAsync(w->h_records, w->records, hc.n_mig * sizeof(g10_migration), hipMemcpyDeviceToHost, s));
+    if (hc.n_drop) G10_HIP(hipMemcpyAsync(w->h_dropped, w->dropped, hc.n_drop * sizeof(g10_dropped), hipMemcpyDeviceToHost, s));
+    G10_HIP(hipMemcpyAsync(w->h_pressure, w->pressure_after, (u64)K * 8, hipMemcpyDeviceToHost, s));
+  }
+  G10_HIP(hipEventRecord(I[0].w->ev[1], s));
   G10_HIP(hipStreamSynchronize(s));
-  float ms = 0.f;
-  G10_HIP(hipEventElapsedTime(&ms, w->ev[0], w->ev[1]));
-  if (timed_full) G10_HIP(hipEventElapsedTime(&full_ms, w->ev[2], w->ev[3]));
-  if (timed_loop) G10_HIP(hipEventElapsedTime(&loop_ms, w->ev[4], w->ev[5]));
+  float ms = 0.f, loop_ms = 0.f;
+  G10_HIP(hipEventElapsedTime(&ms, I[0].w->ev[0], I[0].w->ev[1]));
+  if (timed_loop) G10_HIP(hipEventElapsedTime(&loop_ms, I[0].w->ev[4], I[0].w->ev[5]));
 
+  for (u32 i = 0; i < count; ++i) {
+    Inst& x = I[i];
+    PlanWork* w = x.w;
+    const Ctl& hc = x.hc;
+    float full_ms = 0.f;
+    if (x.timed_full) G10_HIP(hipEventElapsedTime(&full_ms, w->ev[2], w->ev[3]));
 #ifdef G10_PHASE_TIMERS
-  if (getenv("G10_LOG")) {
-    fprintf(stderr, "g10: loop phases (us per pass):");
-    for (int i = 0; i < 9; ++i) fprintf(stderr, " %d:%.2f", i, hc.phase[i] / 100.0 / (double)(hc.n_iter ? hc.n_iter : 1));
-    fprintf(stderr, "  live/pass %.1f dests/pass %.1f\n", hc.phase[9] / (double)(hc.n_iter ? hc.n_iter : 1), hc.phase[10] / (double)(hc.n_iter ? hc.n_iter : 1));
-  }
+    if (getenv("G10_LOG")) {
+      fprintf(stderr, "g10: loop phases (us per pass):");
+      for (int q = 0; q < 9; ++q) fprintf(stderr, " %d:%.2f", q, hc.phase[q] / 100.0 / (double)(hc.n_iter ? hc.n_iter : 1));
+      fprintf(stderr, "  live/pass %.1f dests/pass %.1f\n", hc.phase[9] / (double)(hc.n_iter ? hc.n_iter : 1), hc.phase[10] / (double)(hc.n_iter ? hc.n_iter : 1));
+    }
 #endif
-  w->planned = true; w->plan_cap = p->gpu_cap_bytes; w->plan_n_mig = hc.n_mig;
-  memset(out, 0, sizeof *out);
-  out->status = (int32_t)hc.status;
-  out->n_migrations = hc.n_mig; out->n_iterations = hc.n_iter; out->n_dropped = hc.n_drop; out->n_cand_evals = hc.n_evals;
-  out->peak_before = h->peak; out->peak_after = peak_after;
-  out->overtime_before_ns = overtime_before; out->overtime_after_ns = hc.overtime_after;
-  out->migrations = w->h_records; out->dropped = w->h_dropped; out->pressure_after = w->h_pressure;
-  out->plan_ms = ms;
-  out->score_full_ms = full_ms; out->score_full_cands = n_valid;
-  out->loop_ms = loop_ms; out->loop_launches = hc.launches; out->loop_retiles = retiles;
-  out->loop_cands_scored = hc.units_scored * UNIT; out->loop_second_rounds = hc.second_rounds; out->loop_chunk_jobs = hc.jobs_run;
+    w->planned = true; w->plan_cap = x.p->gpu_cap_bytes; w->plan_n_mig = hc.n_mig;
+    g10_result* out = outs + i;
+    memset(out, 0, sizeof *out);
+    out->status = (int32_t)hc.status;
+    out->n_migrations = hc.n_mig; out->n_iterations = hc.n_iter; out->n_dropped = hc.n_drop; out->n_cand_evals = hc.n_evals;
+    out->peak_before = h->peak; out->peak_after = peaks[i];
+    out->overtime_before_ns = x.overtime_before; out->overtime_after_ns = hc.overtime_after;
+    out->migrations = w->h_records; out->dropped = w->h_dropped; out->pressure_after = w->h_pressure;
+    out->plan_ms = ms;
+    out->score_full_ms = full_ms; out->score_full_cands = x.n_valid;
+    out->loop_ms = loop_ms; out->loop_launches = hc.launches; out->loop_retiles = x.retiles;
+    out->loop_cands_scored = hc.units_scored * UNIT; out->loop_second_rounds = hc.second_rounds; out->loop_chunk_jobs = hc.jobs_run;
+  }
   return G10_OK;
 }
 
+int plan_run(g10_plan_s* h, const g10_params* p, g10_result* out) { return plan_batch_run(h, p, 1, out); }
 
 // ===========================================================================
 // Smart prefetching (Section 4.4) on a finished plan

@@ -182,6 +182,35 @@ def test_long_timeline(g10):
     h.close()
 
 
+def test_plan_batch(g10):
+    """A sweep in one call: every plan of the batch equals the plan made alone (and the oracle's)."""
+    w = traces.stress(K=2048, N=20000, seed=2)
+    h, v, args = run_both(g10, w)
+    sweep = []
+    for cap_frac in (0.25, 0.5, 0.9, 1.0):
+        for hfrac, bw in ((0.25, (6000, 25000)), (0.0, (12000, 25000)), (0.01, (50, 25000))):
+            sweep.append(dict(gpu_cap=int(v.peak * cap_frac), host_cap=int(v.peak * hfrac), bw_out=bw, bw_in=bw))
+    sweep.append(dict(sweep[0], max_iters=37))
+    sweep.append(dict(sweep[1], max_tiles=2, max_chunks=3))
+    rs = h.plan_batch(sweep)
+    assert len(rs) == len(sweep)
+    for d, r in zip(sweep, rs):
+        oa = {k: x for k, x in d.items() if k not in ("max_tiles", "max_chunks")}
+        p = v.plan(**oa) if "max_iters" in oa else v.plan(**oa)
+        if "max_iters" in d:
+            assert r.status == g10.TRUNCATED == p.status and r.n_iterations == 37
+            assert_plan_equal(r, p, prefix=True)
+        else:
+            assert_plan_equal(r, p)
+    # the prefetch pass refers to the first plan of the batch
+    assert_prefetch_equal(h.prefetch(), v.plan(**sweep[0]).prefetch())
+    # a smaller batch and a single plan on the same handle afterwards
+    rs2 = h.plan_batch(sweep[3:5])
+    assert rs2[0].records.tobytes() == rs[3].records.tobytes() and rs2[1].records.tobytes() == rs[4].records.tobytes()
+    assert_plan_equal(h.plan(**args), v.plan(**args))
+    h.close()
+
+
 def test_iteration_limit(g10):
     w = traces.resnet152()
     h, v, args = run_both(g10, w)
