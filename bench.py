@@ -49,6 +49,8 @@ def main():
     ap.add_argument("--cpu-passes", type=int, default=0,
                     help="ranking passes of the CPU oracle to time (0 = sized to roughly 15 s)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--batch", type=int, default=32,
+                    help="plans of the extra capacity-sweep measurement with g10_plan_batch (0 or 1: skip)")
     ap.add_argument("--probe", action="store_true",
                     help="counter probe: one 256 MiB device copy (calibration), one analysis and a plan cut after 8 passes")
     a = ap.parse_args()
@@ -148,6 +150,23 @@ def main():
     hp.close()
     out["smart_prefetch"] = {"kernel": "k_eager", "ms": pf.ms, "migrations": pf.n_migrations, "moved": pf.n_moved,
                              "slots_gained": pf.slots_gained, "us_per_migration": 1e3 * pf.ms / max(pf.n_migrations, 1)}
+
+    # a capacity sweep planned in one call (g10_plan_batch): the loops of the plans run side by side
+    nb = a.batch
+    if nb > 1:
+        hb = binding.g10_vitality(dt)
+        base = dict(gpu_cap=cap, host_cap=hcap, bw_out=w.bw_out_Bpus, bw_in=w.bw_in_Bpus)
+        sweep = [dict(base, gpu_cap=int(hb.peak * (0.20 + 0.15 * i / (nb - 1)))) for i in range(nb)]
+        hb.plan_batch(sweep)                                    # warm-up (allocates the workspaces)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        rs = hb.plan_batch(sweep)
+        tb = time.perf_counter() - t0
+        hb.close()
+        out["batch"] = {"plans": nb, "sweep": "gpu_cap 20..35 % of the peak footprint", "ms": tb * 1e3,
+                        "ms_per_plan": tb * 1e3 / nb, "passes": int(sum(x.n_iterations for x in rs)),
+                        "candidates_per_s": sum(x.n_cand_evals for x in rs) / tb,
+                        "speedup_over_one_by_one": (r.plan_ms * 1e-3 * nb) / tb}
 
     if not a.no_cpu:
         from oracle import oracle as O
