@@ -472,7 +472,8 @@ struct LoopArgs {
   g10_migration* records;
   uint2* rec_ab;              // absent window [a, b] of every migration in doubled coordinates
   g10_dropped* dropped;
-  u32 pass_budget;
+  u32 pass_budget;            // the launch ends after this many passes,
+  u64 tick_budget;            // or (if not 0) after this many ticks of the 100 MHz wall clock
 };
 
 struct Best {
@@ -508,7 +509,8 @@ struct Shared {               // small per-pass state of the loop workgroup
   u32 njobs, ot_changed, stale_hot, pad1;
   // progress (mirrors Ctl)
   u64 n_iter, n_mig, n_drop, n_evals, units, second, jobs;
-  u32 thr_key, status, done, pad;
+  u32 thr_key, status, done, stop;
+  u64 t_start;
   u64 phase[12], t_last;
 };
 
@@ -604,6 +606,7 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
     S->units = 0; S->second = 0; S->jobs = 0;
     S->thr_key = ctl->thr_key; S->status = ctl->status; S->done = ctl->done;
     S->nl = 0; S->restL = NONE32; S->stale_hot = 0;
+    S->stop = 0; S->t_start = wall_clock64();
     S->win.hi = 0; S->win.lo = 0;
     for (u32 i = 0; i < 12; ++i) S->phase[i] = 0;
     S->t_last = wall_clock64();
@@ -944,7 +947,7 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
     if (S->done) break;
     if (base[(u64)A_OT * nb1 + nch] == 0) { if (tid == 0) { S->done = 1; S->status = G10_FITS; } break; }
     if (max_iter && S->n_iter >= max_iter) { if (tid == 0) { S->done = 1; S->status = G10_TRUNCATED; } break; }
-    if (passes >= a.pass_budget) break;
+    if (passes >= a.pass_budget || S->stop) break;
     ++passes;
     mine.hi = 0; mine.lo = 0; mine.cand = NONE32;
     u32 thr = S->thr_key ? S->thr_key : NONE32;
@@ -955,6 +958,7 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
       S->hq = 0; S->njobs = 0; S->ot_changed = 0;
       S->win.hi = 0; S->win.lo = 0;
       if (S->stale_hot) { S->restL = NONE32; S->stale_hot = 0; }
+      if (a.tick_budget && wall_clock64() - S->t_start > a.tick_budget) S->stop = 1;
     }
     __syncthreads();
 
@@ -1192,6 +1196,7 @@ static const u32 PASS_BUDGET = 4096;             // ranking passes per launch of
 #endif
 static const u32 RETILE_PASSES = G10_RETILE_PASSES;   // ... between two re-tilings of a long candidate list
 static const u32 RETILE_MIN_CANDS = 8192;        // shorter lists are never re-tiled
+static const u64 BATCH_LAUNCH_TICKS = 250000;    // a launch of a batch ends after 2.5 ms (100 MHz clock)
 
 static u32 tile_shift_for(u64 n, u32 max_tiles) { // smallest tile (256 << shift) with at most max_tiles tiles
   u32 sh = 0;
@@ -1297,6 +1302,7 @@ struct Inst {
   u64 retiles = 0, launches = 0, max_launches = 0, overtime_before = 0;
   bool counted = false;        // hc.n_live holds a count of the current list
   bool timed_full = false;
+  u64 seen_iter = 0;           // passes done at the last re-tiling
 };
 
 static PlanWork** work_slot(g10_plan_s* h, u32 i) { return i == 0 ? &h->work : &h->more[i - 1]; }
@@ -1421,7 +1427,7 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     x.overtime_before = x.hc.overtime_before;
     x.n_valid = x.n;
     // every pass removes a candidate or stops, so the launches are bounded
-    x.max_launches = (u64)x.n / RETILE_PASSES + 3;
+    x.max_launches = count == 1 ? (u64)x.n / RETILE_PASSES + 3 : (u64)x.n + 3;   // (a launch by the clock makes a pass at least)
     if (x.hc.done) continue;
     ++n_active;
     if (x.n) {
@@ -1439,9 +1445,10 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
   }
 
   // ---- the greedy loops: one workgroup per plan, side by side ------------------------------
-  // Long lists are put back into score order every RETILE_PASSES passes: the tiles the loop
-  // looks at are dense with live candidates again, and the list is cut to those that can
-  // still score.
+  // Long lists are put back into score order every RETILE_PASSES passes or more: the tiles the
+  // loop looks at are dense with live candidates again, and the list is cut to those that can
+  // still score.  A batch ends its launches by the clock instead, so that no plan waits long for
+  // the slowest one.
   const bool timed_loop = n_active != 0;
   if (timed_loop) G10_HIP(hipEventRecord(I[0].w->ev[4], s));
   while (n_active) {
@@ -1458,7 +1465,8 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
       la.g_base = w->g_base;
       la.g_keys = w->tkeys; la.ctl = w->ctl; la.records = w->records; la.rec_ab = w->rec_ab; la.dropped = w->dropped;
       la.cd = w->cd[x.cur]; la.n_pad = x.n_pad; la.nt = x.nt; la.tshift = x.tsh;
-      la.pass_budget = x.n > RETILE_MIN_CANDS ? RETILE_PASSES : PASS_BUDGET;
+      la.pass_budget = x.n > RETILE_MIN_CANDS && count == 1 ? RETILE_PASSES : PASS_BUDGET;
+      la.tick_budget = count > 1 ? BATCH_LAUNCH_TICKS : 0;
       const size_t l = loop_lds_bytes(w->nch, x.nt);
       if (l > lds) lds = l;
     }
@@ -1473,7 +1481,8 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
       Inst& x = I[i];
       if (x.hc.done) continue;
       ++n_active;
-      if (x.n > RETILE_MIN_CANDS) {
+      if (x.n > RETILE_MIN_CANDS && x.hc.n_iter - x.seen_iter >= RETILE_PASSES) {
+        x.seen_iter = x.hc.n_iter;
         if (x.counted && x.hc.n_live < x.n) x.n = x.hc.n_live;   // live candidates come first in the list
         G10_TRY(retile(x, false));
         x.counted = true;
