@@ -197,6 +197,8 @@ struct g10_plan_s {
   u32* per_t = nullptr;          // [n_periods]
   u32* per_L = nullptr;
   u32* per_R = nullptr;
+  uint4* per_by_start = nullptr; // [n_periods] {L, R, tensor, period index}, ordered by L (then index)
+  u64* per_size = nullptr;       // [n_periods] size of the period's tensor, same order
   u64* pressure_buf = nullptr;   // [K+1]; pressure = pressure_buf + 1
   PlanWork* work = nullptr;      // workspaces of the first plan of a batch (the only one of g10_plan)
   PlanWork** more = nullptr;     // ... of the further plans of a batch

@@ -154,14 +154,16 @@ __device__ __forceinline__ u64 ceil_div_x1000(u64 s, u64 bw, u64 inv) {
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ u64 start2(const u64* start, u32 K, u64 T, u32 j) { return j < K ? start[j] : start[j - K] + T; }
 
-__global__ __launch_bounds__(G10_BLOCK) void k_prep(const u32* __restrict__ per_t, const u32* __restrict__ per_L,
-                                                   const u32* __restrict__ per_R, const u64* __restrict__ size,
+// (one thread per period, the periods in the order of their start: neighbouring threads search
+// neighbouring parts of the start-time array)
+__global__ __launch_bounds__(G10_BLOCK) void k_prep(const uint4* __restrict__ per, const u64* __restrict__ size,
                                                    const u64* __restrict__ start, u32 K, u64 T, u32 C, const Ctl* ctl,
                                                    uint4* __restrict__ win, u32* __restrict__ keep) {
   const u32 c = blockIdx.x * G10_BLOCK + threadIdx.x;
   if (c >= C) return;
-  const u32 L = per_L[c], R = per_R[c];
-  const u64 s = size[per_t[c]];
+  const uint4 pd = per[c];                  // {L, R, tensor, period index}
+  const u32 L = pd.x, R = pd.y;
+  const u64 s = size[c];                    // sizes in the same order
   const u64 t_r = start2(start, K, T, L + 1), t_use = start2(start, K, T, R), len = t_use - t_r;
   u32 any = 0;
   u32 w[4];
@@ -185,19 +187,19 @@ __global__ __launch_bounds__(G10_BLOCK) void k_prep(const u32* __restrict__ per_
   keep[c] = any;
 }
 
-// candidates with at least one valid window, packed in the analysis order
-__global__ __launch_bounds__(G10_BLOCK) void k_pack(const u32* __restrict__ per_t, const u32* __restrict__ per_L,
-                                                   const u32* __restrict__ per_R, const u64* __restrict__ size,
+// candidates with at least one valid window, packed in the order of their start
+__global__ __launch_bounds__(G10_BLOCK) void k_pack(const uint4* __restrict__ per, const u64* __restrict__ size,
                                                    const uint4* __restrict__ win, const u32* __restrict__ pos, u32 C,
                                                    Cands out) {
   const u32 c = blockIdx.x * G10_BLOCK + threadIdx.x;
   if (c >= C || pos[c + 1] == pos[c]) return;
-  const u32 o = pos[c], t = per_t[c];
+  const uint4 pd = per[c];                  // {L, R, tensor, period index}
+  const u32 o = pos[c];
   const uint4 w = win[c];
-  const u64 s = size[t];
-  out.A[o] = make_uint4(per_L[c] + 1, per_R[c], w.x, w.y);
+  const u64 s = size[c];                    // sizes in the same order
+  out.A[o] = make_uint4(pd.x + 1, pd.y, w.x, w.y);
   out.B[o] = make_uint4(w.z, w.w, (u32)s, (u32)(s >> 32));
-  out.id[o] = make_uint2(c, t);
+  out.id[o] = make_uint2(pd.w, pd.z);
 }
 
 // ---------------------------------------------------------------------------
@@ -1376,7 +1378,7 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     hipLaunchKernelGGL(k_ot_full, dim3(K / G10_BLOCK + 1), dim3(G10_BLOCK), 0, s, w->otc, (const u64*)w->base0, K, w->nch, w->shift_ch);
     G10_HIP(hipGetLastError());
     if (C) {      // windows per destination; keep the candidates with at least one valid window
-      hipLaunchKernelGGL(k_prep, dim3(gC), dim3(G10_BLOCK), 0, s, h->per_t, h->per_L, h->per_R, h->size, h->start, K, h->T, C,
+      hipLaunchKernelGGL(k_prep, dim3(gC), dim3(G10_BLOCK), 0, s, (const uint4*)h->per_by_start, (const u64*)h->per_size, h->start, K, h->T, C,
                          (const Ctl*)w->ctl, w->win, w->keep);
       G10_HIP(hipGetLastError());
       G10_TRY(scan_excl_u32(w->keep, w->keep, C, w->scratch32, s));
@@ -1431,7 +1433,7 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     if (x.hc.done) continue;
     ++n_active;
     if (x.n) {
-      hipLaunchKernelGGL(k_pack, dim3(gC), dim3(G10_BLOCK), 0, s, h->per_t, h->per_L, h->per_R, h->size, (const uint4*)x.w->win,
+      hipLaunchKernelGGL(k_pack, dim3(gC), dim3(G10_BLOCK), 0, s, (const uint4*)h->per_by_start, (const u64*)h->per_size, (const uint4*)x.w->win,
                          (const u32*)x.w->keep, C, x.w->cd[x.cur]);
       G10_HIP(hipGetLastError());
     }

@@ -300,6 +300,24 @@ __global__ __launch_bounds__(G10_BLOCK) void k_period_write(const u64* __restric
   }
 }
 
+// sort keys (period start, period index) and the periods gathered in that order as {L, R, tensor, index}
+__global__ __launch_bounds__(G10_BLOCK) void k_start_keys(const u32* __restrict__ per_L, u64 C, u32 cbits, u64* __restrict__ keys) {
+  for (u64 c = (u64)blockIdx.x * G10_BLOCK + threadIdx.x; c < C; c += (u64)gridDim.x * G10_BLOCK)
+    keys[c] = ((u64)per_L[c] << cbits) | c;
+}
+
+__global__ __launch_bounds__(G10_BLOCK) void k_gather_periods(const u64* __restrict__ keys, u64 C, u32 cbits,
+                                                             const u32* __restrict__ per_t, const u32* __restrict__ per_L,
+                                                             const u32* __restrict__ per_R, const u64* __restrict__ size,
+                                                             uint4* __restrict__ out, u64* __restrict__ out_size) {
+  for (u64 i = (u64)blockIdx.x * G10_BLOCK + threadIdx.x; i < C; i += (u64)gridDim.x * G10_BLOCK) {
+    const u32 c = (u32)(keys[i] & ((1ull << cbits) - 1ull));
+    const u32 t = per_t[c];
+    out[i] = make_uint4(per_L[c], per_R[c], t, c);
+    out_size[i] = size[t];
+  }
+}
+
 // ===========================================================================
 // memory pressure: interval adds into a difference array, scan, max
 // ===========================================================================
@@ -541,5 +559,21 @@ int vitality_run(g10_plan_s* h, const g10_trace* tr) {
   h->n_uses = hs.n_uses;
   h->n_periods = hs.n_periods;
   h->peak = hs.peak;
+
+  // ---- the periods once more, ordered by their start --------------------------------------
+  // Planning walks the periods with one thread each and looks up the timeline around their
+  // start and end; in this order neighbouring threads look at neighbouring slots.
+  const u64 C = h->n_periods;
+  G10_TRY(dev_alloc(&h->per_by_start, C));
+  G10_TRY(dev_alloc(&h->per_size, C));
+  if (C) {
+    const u32 cbits = bits_for(C - 1);
+    hipLaunchKernelGGL(k_start_keys, dim3(grid_for(C)), dim3(G10_BLOCK), 0, s, h->per_L, C, cbits, keys);
+    G10_TRY(radix_sort_u64(&keys, &alt, C, cbits + h->kbits, hist, scratch32, s));
+    hipLaunchKernelGGL(k_gather_periods, dim3(grid_for(C)), dim3(G10_BLOCK), 0, s, keys, C, cbits, h->per_t, h->per_L, h->per_R,
+                       h->size, h->per_by_start, h->per_size);
+    G10_HIP(hipGetLastError());
+    G10_HIP(hipStreamSynchronize(s));               // the temporaries go away with this function
+  }
   return G10_OK;
 }
