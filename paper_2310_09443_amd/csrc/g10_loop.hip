@@ -1,0 +1,634 @@
+// The greedy loop of smart tensor eviction (G10, Section 4.3, Algorithm 1) as one persistent
+// workgroup per plan: rank (tile bounds, score, arg-max), decide, commit (lazy chunk adds and
+// chunk jobs), level-1 update.  See g10_plan.hip for the data structures and why the plan is
+// the one Algorithm 1 makes.
+
+#include "g10_plan_defs.h"
+
+using namespace g10;
+
+namespace {
+
+#ifdef G10_PHASE_TIMERS
+#define PHASE(i) do { if (tid == 0) { const u64 now_ = wall_clock64(); S->phase[i] += now_ - S->t_last; S->t_last = now_; } } while (0)
+#else
+#define PHASE(i) do { } while (0)
+#endif
+
+struct Winner {               // what a commit needs of the winning candidate
+  u64 hi, lo;                 // benefit
+  u64 s, fo_base, fi_end;     // size; free out-channel time before L1; free in-channel time before R
+  u32 cand, tensor, pos, dest, L1, R, a, b;
+};
+
+struct Shared {               // small per-pass state of the loop workgroup
+  Winner win;                 // winner of the pass (hi = lo = 0: none)
+  Winner wave_win[LW];        // best of every wavefront
+  u64 tau_o, tau_i;
+  u64 hq;                     // host-capacity query: maximum over the period
+  u32 nl, restL;              // hot list: length; bound of the tiles outside it
+  u32 ntl, filt;              // current round: tiles to score; bound of the hot tiles left out
+  u32 njobs, ot_changed, stale_hot, pad1;
+  // progress (mirrors Ctl)
+  u64 n_iter, n_mig, n_drop, n_evals, units, second, jobs;
+  u32 thr_key, status, done, stop;
+  u64 t_start;
+  u64 phase[12], t_last;
+};
+
+// The lane of the wavefront holding the best (benefit, lowest index), or NONE32
+// if every benefit is 0.  The 31-bit key decides unless several lanes share the
+// largest key (equal or nearly equal benefits: common where a model repeats one
+// layer); those are settled by three more reductions: high word, low word, index.
+__device__ __forceinline__ u32 wave_best_lane(u64 hi, u64 lo, u32 cand) {
+  const u32 k = upkey(hi, lo);
+  const u32 kmax = wave_max(k);
+  if (kmax == 0) return NONE32;
+  u64 m = __ballot(k == kmax);
+  if (m & (m - 1)) {
+    const bool in1 = k == kmax;
+    const u64 hmax = wave_max(in1 ? hi : 0ull);
+    const bool in2 = in1 && hi == hmax;
+    const u64 lmax = wave_max(in2 ? lo : 0ull);
+    const bool in3 = in2 && lo == lmax;
+    const u32 cmin = wave_min(in3 ? cand : NONE32);
+    m = __ballot(in3 && cand == cmin);
+  }
+  return (u32)__builtin_ctzll(m);
+}
+
+__global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const LoopArgs a = plans[blockIdx.x];        // one workgroup per plan
+  const Timelines tl = a.tl;
+  const u32 nch = tl.nch, nb1 = nch + 1, K = tl.K, CH = 1u << tl.shift_ch, nt = a.nt, ns = (nt + 63) / 64;
+  u64* base = (u64*)smem;                               // [5][nch + 1]
+  u64* tot = base + (u64)N_ARR * nb1;                   // [5][nch]
+  u64* lazyP = tot + (u64)N_ARR * nch;
+  u64* minOver = lazyP + nch;
+  u64* lazyH = minOver + nch;
+  u64* hmax = lazyH + nch;
+  u64* smark = hmax + nch;                              // [ns] tiles of a group of 64 scored in this pass
+  u64* scr = smark + ns;                                // [4 * LW]
+  Shared* S = (Shared*)(scr + 4 * LW);
+  u32* keys = (u32*)(S + 1);                            // [nt]  bound of every tile
+  u32* skeys = keys + nt;                               // [ns]  largest bound of every group of 64 tiles
+  u32* jobs = skeys + ns;                               // [4 * nch + 8]
+  unsigned short* tlist = (unsigned short*)(jobs + 4 * nch + 8);   // [nt]  the hot list
+  unsigned short* alist = tlist + nt;                            // [nt]  tiles scored in the current round
+
+  const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+  Ctl* ctl = a.ctl;
+  const u64 cap = ctl->gpu_cap, host_cap = ctl->host_cap, max_iter = ctl->max_iter, C = ctl->C;
+  const u64 bwo0 = ctl->bw_out[0], bwo1 = ctl->bw_out[1], bwi0 = ctl->bw_in[0], bwi1 = ctl->bw_in[1];
+  const u64 ivo0 = ctl->inv_out[0], ivo1 = ctl->inv_out[1], ivi0 = ctl->inv_in[0], ivi1 = ctl->inv_in[1];
+
+  // ---- state in ----------------------------------------------------------------------
+  for (u32 i = tid; i < N_ARR * nch; i += LB) tot[i] = a.g_tot[i];
+  for (u32 i = tid; i < nch; i += LB) { lazyP[i] = a.g_lazyP[i]; minOver[i] = a.g_minOver[i]; lazyH[i] = a.g_lazyH[i]; hmax[i] = a.g_hmax[i]; }
+  for (u32 i = tid; i < nt; i += LB) keys[i] = a.g_keys[i];
+  for (u32 i = tid; i < ns; i += LB) smark[i] = 0;
+  if (tid == 0) {
+    S->n_iter = ctl->n_iter; S->n_mig = ctl->n_mig; S->n_drop = ctl->n_drop; S->n_evals = ctl->n_evals;
+    S->units = 0; S->second = 0; S->jobs = 0;
+    S->thr_key = ctl->thr_key; S->status = ctl->status; S->done = ctl->done;
+    S->nl = 0; S->restL = NONE32; S->stale_hot = 0;
+    S->stop = 0; S->t_start = wall_clock64();
+    S->win.hi = 0; S->win.lo = 0;
+    for (u32 i = 0; i < 12; ++i) S->phase[i] = 0;
+    S->t_last = wall_clock64();
+  }
+  __syncthreads();
+  for (u32 g = wave; g < ns; g += LW) {                 // group bounds
+    const u32 t = g * 64 + lane;
+    const u32 k = wave_max(t < nt ? keys[t] : 0u);
+    if (lane == 0) skeys[g] = k;
+  }
+
+  // exclusive scan of the chunk totals of `na` arrays into base (three barriers)
+  auto scan_bases = [&](u32 arr0, u32 arr1, u32 arr2, u32 na) {
+    const u32 arrs[3] = {arr0, arr1, arr2};
+    const bool act = tid < ((nch + 63u) & ~63u);
+    u64 v[3] = {0, 0, 0}, inc[3] = {0, 0, 0};
+    if (act) {
+      for (u32 q = 0; q < na; ++q) {
+        v[q] = tid < nch ? tot[(u64)arrs[q] * nch + tid] : 0ull;
+        inc[q] = wave_scan_incl(v[q]);
+        if (lane == G10_WAVE - 1) scr[q * LW + wave] = inc[q];
+      }
+    }
+    __syncthreads();
+    if (wave == 0) {                                    // the wavefront totals: one small scan
+      const u32 nw = (nch + 63) / 64;
+      for (u32 q = 0; q < na; ++q) {
+        const u64 x = lane < nw ? scr[q * LW + lane] : 0ull;
+        const u64 xi = wave_scan_incl(x);
+        if (lane < nw) scr[q * LW + lane] = xi - x;
+        if (lane == G10_WAVE - 1) base[(u64)arrs[q] * nb1 + nch] = xi;
+      }
+    }
+    __syncthreads();
+    if (act && tid < nch)
+      for (u32 q = 0; q < na; ++q) base[(u64)arrs[q] * nb1 + tid] = scr[q * LW + wave] + inc[q] - v[q];
+    __syncthreads();
+  };
+  scan_bases(0, 1, 2, 3);
+  scan_bases(3, 4, 0, 2);
+
+  // The hot list: every tile not scored in this pass whose bound reaches `thr`; restL bounds
+  // the tiles left out.  Bounds only fall and only scored tiles change, so the list stays
+  // complete for any later threshold above restL and is kept across passes.
+  auto build_hot = [&](u32 thr) {
+    if (tid == 0) { S->nl = 0; S->restL = 0; }
+    __syncthreads();
+    u32 rm = 0;
+    for (u32 g0 = 0; g0 < ns; g0 += 64) {          // 64 groups at a time, one per lane, in every wavefront alike
+      const u32 sk = g0 + lane < ns ? skeys[g0 + lane] : 0u;
+      const bool q = sk != 0 && sk >= thr;
+      if (!q && sk > rm) rm = sk;
+      u64 qm = __ballot(q);
+      for (u32 turn = 0; qm; ++turn) {             // the wavefronts share the groups that qualify
+        const u32 g = g0 + (u32)__builtin_ctzll(qm);
+        qm &= qm - 1;
+        if (turn % LW != wave) continue;
+        const u32 t = g * 64 + lane;
+        const u32 k = t < nt ? keys[t] : 0u;
+        const bool marked = (smark[g] >> lane) & 1ull;
+        const bool sel = k != 0 && k >= thr && !marked;
+        if (!sel && !marked && k > rm) rm = k;
+        const u64 m = __ballot(sel);
+        if (m) {
+          u32 off = 0;
+          if (lane == 0) off = atomicAdd(&S->nl, (u32)__popcll(m));
+          off = (u32)__builtin_amdgcn_readfirstlane((int)off);
+          if (sel) tlist[off + __popcll(m & ((1ull << lane) - 1ull))] = (unsigned short)t;
+        }
+      }
+    }
+    rm = wave_max(rm);
+    if (lane == 0 && rm) atomicMax(&S->restL, rm);
+    __syncthreads();
+  };
+
+  // The tiles of the hot list whose bound reaches `thr` and that were not scored in this pass
+  // -> alist (marked, bound cleared: the scoring rebuilds it); filt bounds the others.
+  auto activate = [&](u32 thr) {
+    if (tid == 0) { S->ntl = 0; S->filt = 0; }
+    __syncthreads();
+    const u32 nl = S->nl;
+    u32 fm = 0;
+    for (u32 i0 = 0; i0 < nl; i0 += LB) {
+      const u32 i = i0 + tid;
+      const u32 t = i < nl ? tlist[i] : 0u;
+      const u32 k = i < nl ? keys[t] : 0u;
+      const bool marked = i < nl && ((smark[t >> 6] >> (t & 63u)) & 1ull);
+      const bool sel = k != 0 && k >= thr && !marked;
+      if (!sel && !marked && k > fm) fm = k;
+      const u64 m = __ballot(sel);
+      if (m) {
+        u32 off = 0;
+        if (lane == 0) off = atomicAdd(&S->ntl, (u32)__popcll(m));
+        off = (u32)__builtin_amdgcn_readfirstlane((int)off);
+        if (sel) {
+          alist[off + __popcll(m & ((1ull << lane) - 1ull))] = (unsigned short)t;
+          keys[t] = 0;
+          atomicOr((unsigned long long*)&smark[t >> 6], 1ull << (t & 63u));
+        }
+      }
+      if (i0 + LB >= nl) break;
+    }
+    fm = wave_max(fm);
+    if (lane == 0 && fm) atomicMax(&S->filt, fm);
+    __syncthreads();
+  };
+
+  // this thread's best candidate of the pass
+  Winner mine;
+  mine.hi = 0; mine.lo = 0; mine.cand = NONE32;
+
+  struct CandV { uint4 A, B; uint2 id; u32 p, t; };
+  auto load_cand = [&](u32 u) -> CandV {
+    CandV c;
+    c.t = alist[u >> a.tshift];
+    c.p = (((c.t << a.tshift) + (u & ((1u << a.tshift) - 1u))) << 8) + (tid & 255u);
+    c.A = a.cd.A[c.p]; c.B = a.cd.B[c.p]; c.id = a.cd.id[c.p];
+    return c;
+  };
+
+  // Scores the listed tiles: four wavefronts per 256 candidates, the next
+  // candidate's record already in flight.  One workgroup has one texture
+  // unit, about one cache line per clock: lanes whose candidate is dead load
+  // nothing, and struck destinations are written back so later passes skip them.
+  auto score_list = [&]() {
+    const u32 nunits = S->ntl << a.tshift;
+    PrefixView pv; pv.px = tl.px; pv.base = base; pv.K = K; pv.nch = nch; pv.shift_ch = tl.shift_ch;
+    Machine mc; mc.bwo0 = bwo0; mc.bwo1 = bwo1; mc.bwi0 = bwi0; mc.bwi1 = bwi1;
+    u32 u = tid >> 8;
+    CandV cur;
+    if (u < nunits) cur = load_cand(u);
+    while (u < nunits) {
+      const u32 un = u + LB / UNIT;
+      CandV nxt;
+      if (un < nunits) nxt = load_cand(un);
+      const uint4 A = cur.A, B = cur.B;
+      const Score r = score_candidate(pv, mc, A, B);
+      if (r.strike0) a.cd.A[cur.p] = make_uint4(A.x, A.y, 1u, 0u);
+      if (r.strike1) a.cd.B[cur.p] = make_uint4(1u, 0u, B.z, B.w);
+#ifdef G10_PHASE_TIMERS
+      {                                          // live candidates and destinations looked at
+        const bool v0 = A.z <= A.w, v1 = B.x <= B.y;
+        const u32 nl = (u32)__popcll(__ballot(v0 || v1)), nd = (u32)(__popcll(__ballot(v0)) + __popcll(__ballot(v1)));
+        if (lane == 0) { atomicAdd((unsigned long long*)&S->phase[9], (unsigned long long)nl); atomicAdd((unsigned long long*)&S->phase[10], (unsigned long long)nd); }
+      }
+#endif
+      const bool one = gt128(r.h1, r.l1, r.h0, r.l0);
+      const u32 k = wave_max(upkey(one ? r.h1 : r.h0, one ? r.l1 : r.l0));
+      if (lane == 0 && k) atomicMax(&keys[cur.t], k);
+      if (r.ok0 || r.ok1) {                      // flash first; host only if flash cannot take it
+        const u32 d = r.ok0 ? 0u : 1u;
+        const u64 hi = d ? r.h1 : r.h0, lo = d ? r.l1 : r.l0;
+        if ((hi | lo) != 0 && better(hi, lo, cur.id.x, mine.hi, mine.lo, mine.cand)) {
+          mine.hi = hi; mine.lo = lo; mine.cand = cur.id.x; mine.tensor = cur.id.y; mine.pos = cur.p; mine.dest = d;
+          mine.L1 = A.x; mine.R = A.y; mine.a = d ? B.x : A.z; mine.b = d ? B.y : A.w; mine.s = ((u64)B.w << 32) | B.z;
+          mine.fo_base = r.fo_L; mine.fi_end = r.fi_R;
+        }
+      }
+      u = un;
+      cur = nxt;
+    }
+    if (tid == 0) S->units += nunits;
+  };
+
+  // block-wide arg-max of the threads' best (two barriers); refreshes the group bounds in between
+  auto reduce_best = [&]() {
+    const u32 bl = wave_best_lane(mine.hi, mine.lo, mine.cand);
+    if (bl == NONE32) { if (lane == 0) { S->wave_win[wave].hi = 0; S->wave_win[wave].lo = 0; S->wave_win[wave].cand = NONE32; } }
+    else if (lane == bl) S->wave_win[wave] = mine;
+    __syncthreads();                               // all tile bounds and wavefront winners are in LDS
+    const u32 ntl = S->ntl;
+    for (u32 i = wave - 1; wave && i < ntl; i += LW - 1) {   // bounds of the groups that hold re-scored tiles
+      const u32 g = alist[i] >> 6, t = g * 64 + lane;
+      const u32 k = wave_max(t < nt ? keys[t] : 0u);
+      if (lane == 0) skeys[g] = k;
+    }
+    if (wave == 0) {
+      u64 h = 0, l = 0;
+      u32 c = NONE32;
+      if (lane < LW) { h = S->wave_win[lane].hi; l = S->wave_win[lane].lo; c = S->wave_win[lane].cand; }
+      const u32 w = wave_best_lane(h, l, c);
+      if (w == NONE32) { if (lane == 0) { S->win.hi = 0; S->win.lo = 0; } }
+      else {
+        if (lane == 0) {
+          S->win = S->wave_win[w];
+          S->tau_o = ceil_div_x1000(S->wave_win[w].s, S->wave_win[w].dest ? bwo1 : bwo0, S->wave_win[w].dest ? ivo1 : ivo0);
+        }
+        if (lane == 1) S->tau_i = ceil_div_x1000(S->wave_win[w].s, S->wave_win[w].dest ? bwi1 : bwi0, S->wave_win[w].dest ? ivi1 : ivi0);
+      }
+    }
+    __syncthreads();
+  };
+
+  // ---- chunk jobs: one wavefront rewrites one chunk of one array ------------------------
+  auto run_jobs = [&]() {
+    const u32 nj = S->njobs;
+    const u32 d = S->win.dest, L1 = S->win.L1, R = S->win.R, wa = S->win.a, wb = S->win.b;
+    const u64 s = S->win.s, tau_o = S->tau_o, tau_i = S->tau_i, fo_base = S->win.fo_base, fi_end = S->win.fi_end;
+    for (u32 jb = wave; jb < nj; jb += LW) {
+      const u32 type = jobs[jb] >> 16, c = jobs[jb] & 0xffffu;
+      const u32 s0 = c * CH;
+      if (type == J_FO || type == J_FI) {
+        // channel time of the window is taken from this chunk's slots; the free-time prefix
+        // of the slots after the first window slot is rewritten from a scan of the new values
+        const bool out = type == J_FO;
+        const u32 arr = (out ? A_FO : A_FI) + d, w = out ? w_fo(d) : w_fi(d);
+        u64* fr = tl.fre + (u64)((out ? 0u : 2u) + d) * tl.Kp;
+        const u64 bc = base[(u64)arr * nb1 + c], ball = base[(u64)arr * nb1 + nch];
+        const u32 x = out ? L1 : wb + 1, y = out ? wa - 1 : R - 1;
+        const u32 first = first_covered(s0, (s0 + CH - 1 < K - 1) ? s0 + CH - 1 : K - 1, K, x, y);
+        u64 carry = 0;
+        for (u32 st = 0; st < tl.spt; ++st) {
+          const u32 j0 = s0 + st * 256u + lane * 4u;
+          u64 f[4], old[4];
+          u32 jj[4];
+#pragma unroll
+          for (u32 i = 0; i < 4; ++i) {
+            const u32 j = j0 + i;
+            f[i] = j < K ? fr[j] : 0ull;
+            jj[i] = j < K ? in_doubled(j, K, x, y) : NONE32;
+            old[i] = jj[i] != NONE32 ? tl.px[(u64)j * PX + w] : 0ull;       // free time of the chunk before the slot
+          }
+          u64 lsum = 0;
+#pragma unroll
+          for (u32 i = 0; i < 4; ++i) {
+            if (jj[i] != NONE32) {
+              const u64 before_slot = (jj[i] >= K ? ball : 0ull) + bc + old[i];  // free time before slot jj
+              u64 take;
+              if (out) {                           // eviction: earliest free time of the window first
+                const u64 before = before_slot - fo_base;
+                const u64 used = before < tau_o ? before : tau_o;
+                take = f[i] < tau_o - used ? f[i] : tau_o - used;
+              } else {                             // prefetch: latest free time first
+                const u64 after = fi_end - (before_slot + f[i]);
+                const u64 used = after < tau_i ? after : tau_i;
+                take = f[i] < tau_i - used ? f[i] : tau_i - used;
+              }
+              if (take) { f[i] -= take; fr[j0 + i] = f[i]; }
+            }
+            lsum += f[i];
+          }
+          const u64 inc = wave_scan_incl(lsum);
+          u64 run = carry + inc - lsum;
+#pragma unroll
+          for (u32 i = 0; i < 4; ++i) {
+            const u32 j = j0 + i;
+            if (j < K && j > first) tl.px[(u64)j * PX + w] = run;
+            run += f[i];
+          }
+          carry += wave_last(inc);
+        }
+        if (lane == 0) tot[(u64)arr * nch + c] = carry;
+      } else if (type == J_P_PART || type == J_P_FULL) {
+        // pressure of the chunk's slots; where a slot drops under the capacity the
+        // over-capacity prefix after it is rewritten
+        const u64 lz = lazyP[c];
+        u64 mn = NONE64;
+        u32 first = NONE32;                              // first slot that dropped under the capacity
+        for (u32 st = 0; st < tl.spt; ++st) {
+          const u32 j0 = s0 + st * 256u + lane * 4u;
+          u32 myfirst = NONE32;
+#pragma unroll
+          for (u32 i = 0; i < 4; ++i) {
+            const u32 j = j0 + i;
+            if (j < K) {
+              u64 p = tl.P[j];
+              const bool hit = type == J_P_PART && in_doubled(j, K, wa, wb) != NONE32;
+              const u64 before = p - lz + (type == J_P_FULL ? s : 0ull);     // pressure before this eviction
+              if (hit) { p -= s; tl.P[j] = p; }
+              const u64 act = p - lz;
+              if (act > cap) mn = act < mn ? act : mn;
+              else if (before > cap && myfirst == NONE32) myfirst = j;
+            }
+          }
+          const u32 stfirst = wave_min(myfirst);
+          if (first == NONE32) first = stfirst;
+        }
+        mn = wave_min(mn);
+        if (lane == 0) minOver[c] = mn;
+        if (first != NONE32) {                           // rewrite the prefix of the slots after it
+          u64 carry = 0;
+          for (u32 st = 0; st < tl.spt; ++st) {
+            const u32 j0 = s0 + st * 256u + lane * 4u;
+            u64 v[4];
+            u64 lsum = 0;
+#pragma unroll
+            for (u32 i = 0; i < 4; ++i) {
+              const u32 j = j0 + i;
+              v[i] = 0;
+              if (j < K && tl.P[j] - lz > cap) v[i] = tl.dur[j];
+              lsum += v[i];
+            }
+            const u64 inc = wave_scan_incl(lsum);
+            u64 run = carry + inc - lsum;
+#pragma unroll
+            for (u32 i = 0; i < 4; ++i) {
+              const u32 j = j0 + i;
+              if (j < K && j > first) {
+                ulonglong2* rec = reinterpret_cast<ulonglong2*>(tl.px + (u64)j * PX);
+                rec[0].y = run; rec[1].y = run; rec[2].y = run; rec[3].y = run;   // the four copies of OT
+              }
+              run += v[i];
+            }
+            carry += wave_last(inc);
+          }
+          if (lane == 0) { tot[(u64)A_OT * nch + c] = carry; S->ot_changed = 1; }
+        }
+      } else {                                     // J_H: add the tensor; J_HQ: only ask for the maximum
+        const u64 lz = lazyH[c];
+        u64 m_all = 0, m_cov = 0;
+        for (u32 st = 0; st < tl.spt; ++st) {
+          const u32 j0 = s0 + st * 256u + lane * 4u;
+#pragma unroll
+          for (u32 i = 0; i < 4; ++i) {
+            const u32 j = j0 + i;
+            if (j < K) {
+              u64 h = tl.H[j];
+              const bool cov = in_doubled(j, K, L1, R - 1) != NONE32;
+              if (type == J_H && cov) { h += s; tl.H[j] = h; }
+              const u64 act = h + lz;
+              m_all = act > m_all ? act : m_all;
+              if (cov) m_cov = act > m_cov ? act : m_cov;
+            }
+          }
+        }
+        if (type == J_H) { m_all = wave_max(m_all); if (lane == 0) hmax[c] = m_all; }
+        else { m_cov = wave_max(m_cov); if (lane == 0) atomicMax((unsigned long long*)&S->hq, (unsigned long long)m_cov); }
+      }
+    }
+    if (tid == 0) S->jobs += nj;
+  };
+
+  __syncthreads();
+  // ---- passes ------------------------------------------------------------------------
+  u32 passes = 0;
+  while (true) {
+    if (S->done) break;
+    if (base[(u64)A_OT * nb1 + nch] == 0) { if (tid == 0) { S->done = 1; S->status = G10_FITS; } break; }
+    if (max_iter && S->n_iter >= max_iter) { if (tid == 0) { S->done = 1; S->status = G10_TRUNCATED; } break; }
+    if (passes >= a.pass_budget || S->stop) break;
+    ++passes;
+    mine.hi = 0; mine.lo = 0; mine.cand = NONE32;
+    u32 thr = S->thr_key ? S->thr_key : NONE32;
+    __syncthreads();                               // the loop conditions and thr are read
+    for (u32 i = tid; i < ns; i += LB) smark[i] = 0;     // no tile scored in this pass yet
+    if (tid == 0) {
+      S->n_iter += 1; S->n_evals += C - S->n_mig - S->n_drop;
+      S->hq = 0; S->njobs = 0; S->ot_changed = 0;
+      S->win.hi = 0; S->win.lo = 0;
+      if (S->stale_hot) { S->restL = NONE32; S->stale_hot = 0; }
+      if (a.tick_budget && wall_clock64() - S->t_start > a.tick_budget) S->stop = 1;
+    }
+    __syncthreads();
+
+    // rank: score the hot tiles whose bound reaches a threshold (first a guess a little under
+    // the last benefit), lower the threshold to the best benefit found, repeat until no tile
+    // left out could hold an equal or better candidate
+    u32 rounds = 0;
+    while (true) {
+      if (S->restL >= thr) {                       // the hot list may miss a tile that reaches thr: build it anew,
+        const u32 low = thr == NONE32 ? thr : (thr > (1u << 19) ? thr - (1u << 19) : 1u);   // a few percent lower to last a while
+        __syncthreads();
+        build_hot(low);
+        if (rounds && tid == 0) S->stale_hot = 1;  // built without the tiles already scored: not kept for the next pass
+      }
+      activate(thr);
+      const u32 ntl = S->ntl, rest = S->restL > S->filt ? S->restL : S->filt;
+      if (ntl == 0) {
+        if ((rounds && (S->win.hi | S->win.lo) != 0) || rest == 0) break;      // nothing left that could win
+        thr = rest;                                      // strictly lower than before: start from the largest bound left
+        __syncthreads();
+        continue;
+      }
+      PHASE(0);
+      score_list();
+      PHASE(1);
+      reduce_best();
+      PHASE(2);
+      ++rounds;
+      const u32 kb = upkey(S->win.hi, S->win.lo);
+      const u32 need = kb ? kb : 1u;
+      if (rest < need) break;                            // every tile left out is below the best found
+      // a tile left out may hold an equal or better one; with nothing found yet, step down a few percent
+      thr = kb ? kb : (rest > (1u << 19) ? rest - (1u << 19) : 1u);
+      if (tid == 0) S->second += 1;
+      __syncthreads();
+    }
+    PHASE(3);
+
+    const bool none = (S->win.hi | S->win.lo) == 0;
+    const u32 d = S->win.dest, L1 = S->win.L1, R = S->win.R, wa = S->win.a, wb = S->win.b;
+    const u64 s = S->win.s;
+    if (none) { __syncthreads(); if (tid == 0) { S->done = 1; S->status = G10_RESIDUAL; } break; }
+
+    // which chunks the period, its absent window and its transfer windows cover
+    u32 cvE = 0, cvW = 0, cvA = 0, cvP = 0, len = 0;
+    if (tid < nch) {
+      cvE = cover(tid, CH, K, L1, wa - 1, len);
+      cvW = cover(tid, CH, K, wb + 1, R - 1, len);
+      cvA = cover(tid, CH, K, wa, wb, len);
+      cvP = cvE + cvA + cvW;                             // the period interior [L1, R - 1]
+    }
+    // host memory must hold the tensor during the whole period
+    bool room = true;
+    if (d == G10_HOST) {
+      if (tid < ((nch + 63u) & ~63u)) {                  // bound: the maxima of all chunks the period touches
+        const u64 m = wave_max(cvP ? hmax[tid] : 0ull);
+        if (lane == 0 && m) atomicMax((unsigned long long*)&S->hq, (unsigned long long)m);
+      }
+      __syncthreads();
+      room = s <= host_cap && S->hq <= host_cap - s;
+      if (!room) {                                       // exact: chunks cut by the period ends slot by slot
+        __syncthreads();
+        if (tid == 0) S->hq = 0;
+        __syncthreads();
+        if (cvP == len && cvP) atomicMax((unsigned long long*)&S->hq, (unsigned long long)hmax[tid]);
+        else if (cvP) jobs[atomicAdd(&S->njobs, 1u)] = ((u32)J_HQ << 16) | tid;
+        __syncthreads();
+        run_jobs();
+        __syncthreads();
+        room = s <= host_cap && S->hq <= host_cap - s;
+        __syncthreads();
+        if (tid == 0) S->njobs = 0;
+        __syncthreads();
+      }
+    }
+    PHASE(4);
+    if (tid == 0) {
+      const u32 p = S->win.pos;
+      a.cd.A[p] = make_uint4(L1, R, 1u, 0u);             // the candidate leaves the live set
+      a.cd.B[p] = make_uint4(1u, 0u, (u32)s, (u32)(s >> 32));
+      // first threshold of the next pass: a little under this benefit
+      u64 ghi = S->win.hi, glo = S->win.lo;
+      const u64 dlo = (glo >> GUESS_SHIFT) | (ghi << (64 - GUESS_SHIFT)), dhi = ghi >> GUESS_SHIFT;
+      const u64 nlo = glo - dlo;
+      ghi = ghi - dhi - (glo < dlo ? 1ull : 0ull);
+      S->thr_key = upkey(ghi, nlo);
+      if (!room) {
+        g10_dropped dr; dr.iteration = S->n_iter - 1; dr.cand = S->win.cand; dr.reserved = 0;
+        a.dropped[S->n_drop] = dr;
+        S->n_drop += 1;
+      } else {
+        g10_migration mg;
+        mg.cand = S->win.cand; mg.tensor = S->win.tensor;
+        mg.evict_after = L1 - 1; mg.absent_first = wa >= K ? wa - K : wa; mg.absent_last = wb >= K ? wb - K : wb;
+        mg.next_use = R >= K ? R - K : R;
+        mg.dest = d; mg.wraps = R >= K ? 1u : 0u;
+        mg.size_bytes = s; mg.t_out_ns = S->tau_o; mg.t_in_ns = S->tau_i; mg.benefit_lo = S->win.lo; mg.benefit_hi = S->win.hi;
+        a.records[S->n_mig] = mg;
+        a.rec_ab[S->n_mig] = make_uint2(wa, wb);
+        S->n_mig += 1;
+      }
+    }
+    if (!room) { __syncthreads(); continue; }
+
+    // commit: whole chunks take a lazy add, the others a job
+    if (tid < nch) {
+      const u32 c = tid;
+      if (cvE) jobs[atomicAdd(&S->njobs, 1u)] = ((u32)J_FO << 16) | c;
+      if (cvW) jobs[atomicAdd(&S->njobs, 1u)] = ((u32)J_FI << 16) | c;
+      if (cvA == len) {                                  // the whole chunk loses the tensor
+        lazyP[c] += s;
+        u64 mo = minOver[c];
+        if (mo != NONE64) {
+          mo -= s;
+          minOver[c] = mo;
+          if (mo <= cap) jobs[atomicAdd(&S->njobs, 1u)] = ((u32)J_P_FULL << 16) | c;   // a slot drops under the capacity
+        }
+      } else if (cvA) {
+        jobs[atomicAdd(&S->njobs, 1u)] = ((u32)J_P_PART << 16) | c;
+      }
+      if (d == G10_HOST) {
+        if (cvP == len) { lazyH[c] += s; hmax[c] += s; }
+        else if (cvP) jobs[atomicAdd(&S->njobs, 1u)] = ((u32)J_H << 16) | c;
+      }
+    }
+    __syncthreads();
+    PHASE(6);
+    run_jobs();
+    __syncthreads();
+    PHASE(7);
+    // level 1: a transfer window inside one chunk lowers every later chunk's base by the
+    // transfer time; otherwise (and for the over-capacity time, if it changed) scan again
+    {
+      const u32 eA = (L1 >= K ? L1 - K : L1) >> tl.shift_ch, eB = (wa - 1 >= K ? wa - 1 - K : wa - 1) >> tl.shift_ch;
+      const u32 pA = (wb + 1 >= K ? wb + 1 - K : wb + 1) >> tl.shift_ch, pB = (R - 1 >= K ? R - 1 - K : R - 1) >> tl.shift_ch;
+      const bool oneE = eA == eB && !(L1 < K && wa - 1 >= K), oneP = pA == pB && !(wb + 1 < K && R - 1 >= K);
+      const bool ot = S->ot_changed != 0;
+      if (oneE && oneP && !ot) {
+        if (tid < nch) {
+          if (tid > eA) base[(u64)(A_FO + d) * nb1 + tid] -= S->tau_o;
+          if (tid > pA) base[(u64)(A_FI + d) * nb1 + tid] -= S->tau_i;
+        }
+        if (tid == 0) { base[(u64)(A_FO + d) * nb1 + nch] -= S->tau_o; base[(u64)(A_FI + d) * nb1 + nch] -= S->tau_i; }
+        __syncthreads();
+      } else if (ot) scan_bases(A_OT, A_FO + d, A_FI + d, 3);
+      else scan_bases(A_FO + d, A_FI + d, 0, 2);
+    }
+    PHASE(8);
+  }
+  __syncthreads();
+
+  // ---- state out ---------------------------------------------------------------------
+  for (u32 i = tid; i < N_ARR * nch; i += LB) a.g_tot[i] = tot[i];
+  for (u32 i = tid; i < nch; i += LB) { a.g_lazyP[i] = lazyP[i]; a.g_minOver[i] = minOver[i]; a.g_lazyH[i] = lazyH[i]; a.g_hmax[i] = hmax[i]; }
+  for (u32 i = tid; i < nt; i += LB) a.g_keys[i] = keys[i];
+  for (u32 i = tid; i < N_ARR * nb1; i += LB) a.g_base[i] = base[i];
+  if (tid == 0) {
+    ctl->n_iter = S->n_iter; ctl->n_mig = S->n_mig; ctl->n_drop = S->n_drop; ctl->n_evals = S->n_evals;
+    ctl->thr_key = S->thr_key; ctl->status = S->status; ctl->done = S->done;
+    ctl->overtime_after = base[(u64)A_OT * nb1 + nch];
+    for (u32 i = 0; i < 12; ++i) ctl->phase[i] += S->phase[i];
+    ctl->units_scored += S->units; ctl->second_rounds += S->second; ctl->jobs_run += S->jobs; ctl->launches += 1;
+  }
+}
+
+}  // namespace
+
+size_t loop_lds_bytes(u32 nch, u32 nt) {
+  const size_t ns = (nt + 63) / 64;
+  size_t b = 0;
+  b += ((size_t)N_ARR * (nch + 1) + (size_t)N_ARR * nch + (size_t)4 * nch + ns + (size_t)4 * LW) * 8;
+  b += sizeof(Shared);
+  b += ((size_t)nt + ns + (size_t)4 * nch + 8) * 4 + (size_t)nt * 4;
+  return (b + 15) & ~(size_t)15;
+}
+
+int loop_allow_large_lds() {
+  G10_HIP(hipFuncSetAttribute((const void*)k_loop, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+  return G10_OK;
+}
+
+int loop_launch(const LoopArgs* plans, u32 n_plans, size_t lds, hipStream_t s) {
+  hipLaunchKernelGGL(k_loop, dim3(n_plans), dim3(LB), lds, s, plans);
+  G10_HIP(hipGetLastError());
+  return G10_OK;
+}

@@ -1,0 +1,301 @@
+// Definitions shared by the planning translation units (gfx950): constants, the control
+// block, candidate and timeline views, the 128-bit helpers, the score of one candidate, and
+// the per-plan workspaces.  Device functions are inline; kernels live in the .hip files.
+#pragma once
+
+#include "g10_internal.h"
+
+#include <hip/hip_runtime.h>
+
+#define G10_TRY(x) do { int rc_ = (x); if (rc_) return rc_; } while (0)
+
+namespace g10 {
+
+enum { A_OT = 0, A_FO = 1, A_FI = 3, N_ARR = 5, PX = 8 };
+enum { J_FO = 0, J_FI = 1, J_P_PART = 2, J_P_FULL = 3, J_H = 4, J_HQ = 5 };
+
+#ifndef G10_LOOP_THREADS
+#define G10_LOOP_THREADS 512
+#endif
+constexpr u32 LB = G10_LOOP_THREADS;   // threads of the loop workgroup (at least NCH_MAX)
+constexpr u32 LW = LB / G10_WAVE;      // its wavefronts
+constexpr u32 UNIT = 256;              // candidates scored by four wavefronts at a time
+constexpr u32 NCH_MAX = 512;           // chunks (level-1 arrays live in LDS)
+constexpr u32 NT_MAX = 8192;           // tiles  (their bounds live in LDS)
+#ifndef G10_GUESS_SHIFT
+#define G10_GUESS_SHIFT 7
+#endif
+constexpr u32 GUESS_SHIFT = G10_GUESS_SHIFT;   // first threshold of a pass: last benefit * (1 - 2^-shift)
+constexpr u64 NONE64 = ~0ull;
+constexpr u32 NONE32 = 0xffffffffu;
+
+__device__ __forceinline__ u32 w_fo(u32 d) { return 2 * d; }          // word of FOd in a slot record (OT follows)
+__device__ __forceinline__ u32 w_fi(u32 d) { return 4 + 2 * d; }      // word of FId (OT follows)
+
+struct Ctl {
+  // parameters
+  u64 gpu_cap, host_cap, bw_out[2], bw_in[2], max_iter;
+  u64 inv_out[2], inv_in[2];  // floor(2^64 / bandwidth), 0 for bandwidth 1
+  u64 C;                      // all inactive periods (live before any removal)
+  // progress
+  u32 done, status;
+  u64 n_iter, n_mig, n_drop, n_evals;
+  u64 overtime_before, overtime_after;
+  u32 thr_key;                // first threshold of the next pass (0: use the largest tile bound)
+  u32 n_live;                 // candidates that could still score at the last re-scoring
+  // statistics
+  u64 units_scored, second_rounds, jobs_run, launches;
+  u64 phase[12];              // wall-clock ticks per phase of the loop (only with G10_PHASE_TIMERS)
+};
+
+struct Cands {
+  uint4* A;                   // {L1, R, a0, b0}     a > b: no valid window for that destination
+  uint4* B;                   // {a1, b1, size lo, size hi}
+  uint2* id;                  // {index of the period in the analysis order (the tie-break), tensor}
+};
+
+struct Timelines {
+  const u64* dur;
+  u64* P;
+  u64* fre;                   // [4][Kp]
+  u64* H;
+  u64* px;                    // [K][PX]
+  u64* otc;                   // [K + 1] over-capacity time before every slot, before any eviction
+  u32 K, Kp, nch, spt, shift_ch;   // chunk = 256 * spt = 1 << shift_ch slots
+};
+
+// ---------------------------------------------------------------------------
+// 128-bit helpers and the 32-bit order-preserving upper key
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ bool gt128(u64 ahi, u64 alo, u64 bhi, u64 blo) { return ahi != bhi ? ahi > bhi : alo > blo; }
+
+// Monotone non-decreasing map of a 128-bit value to 31 bits that rounds up:
+// x <= y  =>  key(x) <= key(y), and key(x) < key(y)  =>  x < y.  Values below
+// 2^24 map to themselves; above, 24 significant bits (rounded up) and a shift.
+__device__ __forceinline__ u32 upkey(u64 hi, u64 lo) {
+  if (hi == 0 && lo < (1ull << 24)) return (u32)lo;
+  const int n = hi ? 128 - __clzll((long long)hi) : 64 - __clzll((long long)lo);
+  int sh = n - 24;                                   // >= 1
+  u64 m;
+  bool sticky;
+  if (sh >= 64) {
+    const int r = sh - 64;
+    m = hi >> r;
+    sticky = lo != 0 || (r && (hi & ((1ull << r) - 1ull)) != 0);
+  } else {
+    m = (lo >> sh) | (hi ? hi << (64 - sh) : 0ull);
+    sticky = (lo & ((1ull << sh) - 1ull)) != 0;
+  }
+  m += sticky ? 1u : 0u;
+  if (m == (1ull << 24)) { m = 1ull << 23; sh += 1; }
+  return ((u32)sh << 24) + (u32)m;
+}
+
+__device__ __forceinline__ bool carries(u64 free_ns, u64 bw, u64 bytes_x1000) {
+  // free_ns >= ceil(bytes_x1000 / bw)  <=>  free_ns * bw >= bytes_x1000
+  if (((free_ns | bw) >> 32) == 0) return (u64)(u32)free_ns * (u32)bw >= bytes_x1000;   // the usual case: one 32 x 32 multiply
+  return __umul64hi(free_ns, bw) != 0 || free_ns * bw >= bytes_x1000;
+}
+
+// ceil(s * 1000 / bw) with the reciprocal inv = floor(2^64 / bw) (bw >= 2; inv = 0 stands for
+// bw = 1): the high half of x * inv is the quotient or up to 2 below it.
+__device__ __forceinline__ u64 ceil_div_x1000(u64 s, u64 bw, u64 inv) {
+  const u64 x = s * 1000ull;              // validated: no overflow
+  if (inv == 0) return x;
+  u64 q = __umul64hi(x, inv), r = x - q * bw;
+  while (r >= bw) { r -= bw; ++q; }
+  return q + (r != 0);
+}
+
+// ---------------------------------------------------------------------------
+// score of one candidate against the current timelines
+// ---------------------------------------------------------------------------
+struct Machine { u64 bwo0, bwo1, bwi0, bwi1; };
+
+struct PrefixView {           // slot records in HBM / L2, level 1 in LDS
+  const u64* px;
+  const u64* base;            // [5][nch + 1]
+  u32 K, nch, shift_ch;
+};
+
+struct Score {
+  u64 h0, l0, h1, l1;         // benefit per destination (0 if it cannot be used now)
+  u64 fo_L, fi_R;             // of the policy's destination: free out-channel time before L1, in-channel before R
+  bool ok0, ok1;              // the destination's channels can carry the transfer now
+  bool strike0, strike1;      // the destination can never count again
+};
+
+__device__ __forceinline__ ulonglong2 ld2(const u64* p) { return *reinterpret_cast<const ulonglong2*>(p); }
+
+// Both destinations' record pairs are gathered before anything is used.  A
+// destination is struck when its channel cannot carry the transfer any more
+// (reservations only grow); host also when no over-capacity time is left in
+// its window (pressure only falls), flash then too if host is gone: while
+// host could still score, a feasible flash window keeps the policy on flash.
+__device__ __forceinline__ Score score_candidate(const PrefixView& pv, const Machine& mc, const uint4 A, const uint4 B) {
+  Score r;
+  r.h0 = r.l0 = r.h1 = r.l1 = r.fo_L = r.fi_R = 0;
+  r.ok0 = r.ok1 = r.strike0 = r.strike1 = false;
+  const bool v0 = A.z <= A.w, v1 = B.x <= B.y;
+  if (!(v0 || v1)) return r;
+  const u32 K = pv.K, nb1 = pv.nch + 1;
+  const u64 s = ((u64)B.w << 32) | B.z, x1000 = s * 1000ull;
+  const u32 L1 = A.x, R = A.y;
+  const bool sL = L1 >= K, sR = R >= K;
+  const u32 jL = sL ? L1 - K : L1, jR = sR ? R - K : R;
+  const u32 cL = jL >> pv.shift_ch, cR = jR >> pv.shift_ch;
+  const u64* bOT = pv.base + (u64)A_OT * nb1;
+  bool sa0 = false, sb0 = false, sa1 = false, sb1 = false;
+  u32 ca0 = 0, cb0 = 0, ca1 = 0, cb1 = 0;
+  ulonglong2 qa0 = {0, 0}, qb0 = {0, 0}, qL0 = {0, 0}, qR0 = {0, 0}, qa1 = {0, 0}, qb1 = {0, 0}, qL1 = {0, 0}, qR1 = {0, 0};
+  if (v0) {
+    sa0 = A.z >= K; sb0 = A.w + 1 >= K;
+    const u32 ja = sa0 ? A.z - K : A.z, jb = sb0 ? A.w + 1 - K : A.w + 1;
+    ca0 = ja >> pv.shift_ch; cb0 = jb >> pv.shift_ch;
+    qL0 = ld2(pv.px + (u64)jL * PX + 0); qR0 = ld2(pv.px + (u64)jR * PX + 4);      // {FO0, OT} {FI0, OT}
+    qa0 = ld2(pv.px + (u64)ja * PX + 0); qb0 = ld2(pv.px + (u64)jb * PX + 4);
+  }
+  if (v1) {
+    sa1 = B.x >= K; sb1 = B.y + 1 >= K;
+    const u32 ja = sa1 ? B.x - K : B.x, jb = sb1 ? B.y + 1 - K : B.y + 1;
+    ca1 = ja >> pv.shift_ch; cb1 = jb >> pv.shift_ch;
+    qL1 = ld2(pv.px + (u64)jL * PX + 2); qR1 = ld2(pv.px + (u64)jR * PX + 6);      // {FO1, OT} {FI1, OT}
+    qa1 = ld2(pv.px + (u64)ja * PX + 2); qb1 = ld2(pv.px + (u64)jb * PX + 6);
+  }
+  u64 fo0_L = 0, fi0_R = 0, fo1_L = 0, fi1_R = 0;
+  if (v0) {
+    const u64 *bFO = pv.base + (u64)(A_FO + 0) * nb1, *bFI = pv.base + (u64)(A_FI + 0) * nb1;
+    const u64 allFO = bFO[pv.nch], allFI = bFI[pv.nch], allOT = bOT[pv.nch];
+    fo0_L = (sL ? allFO : 0ull) + bFO[cL] + qL0.x; fi0_R = (sR ? allFI : 0ull) + bFI[cR] + qR0.x;
+    const u64 fo_a = (sa0 ? allFO : 0ull) + bFO[ca0] + qa0.x, fi_b = (sb0 ? allFI : 0ull) + bFI[cb0] + qb0.x;
+    r.ok0 = carries(fo_a - fo0_L, mc.bwo0, x1000) && carries(fi0_R - fi_b, mc.bwi0, x1000);
+    if (r.ok0) {
+      const u64 ot = ((sb0 ? allOT : 0ull) + bOT[cb0] + qb0.y) - ((sa0 ? allOT : 0ull) + bOT[ca0] + qa0.y);
+      r.h0 = __umul64hi(s, ot); r.l0 = s * ot;
+    }
+  }
+  if (v1) {
+    const u64 *bFO = pv.base + (u64)(A_FO + 1) * nb1, *bFI = pv.base + (u64)(A_FI + 1) * nb1;
+    const u64 allFO = bFO[pv.nch], allFI = bFI[pv.nch], allOT = bOT[pv.nch];
+    fo1_L = (sL ? allFO : 0ull) + bFO[cL] + qL1.x; fi1_R = (sR ? allFI : 0ull) + bFI[cR] + qR1.x;
+    const u64 fo_a = (sa1 ? allFO : 0ull) + bFO[ca1] + qa1.x, fi_b = (sb1 ? allFI : 0ull) + bFI[cb1] + qb1.x;
+    r.ok1 = carries(fo_a - fo1_L, mc.bwo1, x1000) && carries(fi1_R - fi_b, mc.bwi1, x1000);
+    if (r.ok1) {
+      const u64 ot = ((sb1 ? allOT : 0ull) + bOT[cb1] + qb1.y) - ((sa1 ? allOT : 0ull) + bOT[ca1] + qa1.y);
+      r.h1 = __umul64hi(s, ot); r.l1 = s * ot;
+    }
+  }
+  const bool keep1 = r.ok1 && (r.h1 | r.l1) != 0;
+  const bool keep0 = r.ok0 && (keep1 || (r.h0 | r.l0) != 0);
+  r.strike0 = v0 && !keep0;
+  r.strike1 = v1 && !keep1;
+  r.fo_L = r.ok0 ? fo0_L : fo1_L; r.fi_R = r.ok0 ? fi0_R : fi1_R;
+  return r;
+}
+
+// ---------------------------------------------------------------------------
+// the greedy loop
+// ---------------------------------------------------------------------------
+struct LoopArgs {
+  Cands cd;
+  u32 n_pad, nt, tshift;      // tile = UNIT << tshift candidates
+  Timelines tl;
+  u64 *g_tot, *g_lazyP, *g_minOver, *g_lazyH, *g_hmax, *g_base;
+  u32* g_keys;
+  Ctl* ctl;
+  g10_migration* records;
+  uint2* rec_ab;              // absent window [a, b] of every migration in doubled coordinates
+  g10_dropped* dropped;
+  u32 pass_budget;            // the launch ends after this many passes,
+  u64 tick_budget;            // or (if not 0) after this many ticks of the 100 MHz wall clock
+};
+
+struct Best {
+  u64 hi, lo;
+  u32 cand;
+};
+
+__device__ __forceinline__ bool better(u64 hi, u64 lo, u32 cand, u64 bhi, u64 blo, u32 bcand) {
+  if (hi != bhi) return hi > bhi;
+  if (lo != blo) return lo > blo;
+  return cand < bcand;
+}
+
+// covered slots of chunk c by the doubled range [x, y] (x <= y, y - x < K): the chunk's slots
+// appear at [s0, s1] and at [s0 + K, s1 + K] in doubled coordinates
+__device__ __forceinline__ u32 cover(u32 c, u32 ch, u32 K, u32 x, u32 y, u32& len) {
+  const long long s0 = (long long)c * ch, s1 = (s0 + ch - 1 < (long long)K - 1) ? s0 + ch - 1 : (long long)K - 1;
+  len = (u32)(s1 - s0 + 1);
+  const long long X = x, Y = y;
+  long long n1 = (s1 < Y ? s1 : Y) - (s0 > X ? s0 : X) + 1;
+  long long n2 = (s1 + K < Y ? s1 + K : Y) - (s0 + K > X ? s0 + K : X) + 1;
+  if (n1 < 0) n1 = 0;
+  if (n2 < 0) n2 = 0;
+  return (u32)(n1 + n2);
+}
+
+// first plain slot of [s0, s1] inside the doubled range [x, y] (y - x < K), or NONE32
+__device__ __forceinline__ u32 first_covered(u32 s0, u32 s1, u32 K, u32 x, u32 y) {
+  u32 first = NONE32;
+  if (y >= K) {                                   // the part in the second iteration: plain [max(x, K) - K, y - K]
+    const u32 x2 = x >= K ? x - K : 0u, lo = s0 > x2 ? s0 : x2, hi = s1 < y - K ? s1 : y - K;
+    if (lo <= hi) first = lo;
+  }
+  if (x < K) {                                    // the part in the first iteration: plain [x, min(y, K - 1)]
+    const u32 y1 = y < K - 1 ? y : K - 1, lo = s0 > x ? s0 : x, hi = s1 < y1 ? s1 : y1;
+    if (lo <= hi && lo < first) first = lo;
+  }
+  return first;
+}
+
+// position of plain slot j inside the doubled range [x, y] (y - x < K), or NONE32
+__device__ __forceinline__ u32 in_doubled(u32 j, u32 K, u32 x, u32 y) {
+  if (j >= x && j <= y) return j;
+  const u32 jj = j + K;
+  if (jj >= x && jj <= y) return jj;
+  return NONE32;
+}
+
+inline u32 bits_for(u64 max_value) {            // bits needed to hold values 0..max_value, at least 1
+  u32 b = 1;
+  while (b < 64 && (max_value >> b)) ++b;
+  return b;
+}
+
+}  // namespace g10
+
+struct PlanWork {
+  u32 K = 0, Kp = 0, nch = 0, spt = 1, shift_ch = 8;
+  u64 C = 0, cap_pad = 0;
+  uint4* win = nullptr;
+  u32 *keep = nullptr, *scratch32 = nullptr, *hist = nullptr, *tkeys = nullptr;
+  u64 *keys = nullptr, *keys_alt = nullptr;
+  g10::Cands cd[2] = {};
+  u64 *P = nullptr, *fre = nullptr, *H = nullptr, *px = nullptr, *otc = nullptr, *base0 = nullptr, *g_tot = nullptr,
+      *g_lazyP = nullptr, *g_minOver = nullptr, *g_lazyH = nullptr, *g_hmax = nullptr, *g_base = nullptr,
+      *pressure_after = nullptr,
+      *peak_after = nullptr;
+  g10::Ctl* ctl = nullptr;
+  g10_migration* records = nullptr;
+  uint2* rec_ab = nullptr;
+  g10_dropped* dropped = nullptr;
+  // smart prefetching
+  u64 *pf_keys = nullptr, *pf_keys_alt = nullptr, *pf_pressure = nullptr, *pf_stats = nullptr;
+  u32 *pf_order = nullptr, *pf_order_alt = nullptr, *pf_gained = nullptr, *pf_last = nullptr;
+  u32 *h_pf_order = nullptr, *h_pf_gained = nullptr, *h_pf_last = nullptr;
+  u64* h_pf_pressure = nullptr;
+  bool planned = false;         // a plan is stored in the handle
+  u64 plan_cap = 0, plan_n_mig = 0;
+  // host copies handed out through g10_result
+  g10_migration* h_records = nullptr;
+  g10_dropped* h_dropped = nullptr;
+  u64* h_pressure = nullptr;
+  hipEvent_t ev[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+  void* arena = nullptr;        // the one device allocation all pointers above point into
+  u32 max_chunks = 0;           // the chunk limit the timelines were laid out for
+};
+
+// the loop kernel (g10_loop.hip)
+size_t loop_lds_bytes(u32 nch, u32 nt);                       // dynamic LDS of one workgroup
+int loop_allow_large_lds();                                   // more than 64 KB of LDS for the kernel
+int loop_launch(const g10::LoopArgs* plans, u32 n_plans, size_t lds, hipStream_t s);
