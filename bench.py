@@ -13,6 +13,8 @@ import os
 import sys
 import time
 
+import numpy as np
+
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
@@ -167,6 +169,28 @@ def main():
                         "ms_per_plan": tb * 1e3 / nb, "passes": int(sum(x.n_iterations for x in rs)),
                         "candidates_per_s": sum(x.n_cand_evals for x in rs) / tb,
                         "speedup_over_one_by_one": (r.plan_ms * 1e-3 * nb) / tb}
+
+    # re-planning under kernel-time noise (the profiling-error study): the same batch call, every
+    # plan on durations of its own; how much of the exact plan survives is reported beside the time
+    if nb > 1:
+        hn = binding.g10_vitality(dt)
+        pcts = [0.0, 5.0, 10.0, 15.0, 20.0, 25.0]
+        durs = [torch.from_numpy(traces.noisy_durations(tr, pc, seed=1000 + int(pc)).view(np.int64)).to(dev)
+                for pc in pcts]
+        sweep = [dict(gpu_cap=cap, host_cap=hcap, bw_out=w.bw_out_Bpus, bw_in=w.bw_in_Bpus,
+                      dur=(None if pc == 0.0 else d)) for pc, d in zip(pcts, durs)]
+        hn.plan_batch(sweep)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        rn = hn.plan_batch(sweep)
+        tn = time.perf_counter() - t0
+        exact = set(zip(rn[0].records["cand"].tolist(), rn[0].records["dest"].tolist()))
+        kept = [len(exact & set(zip(x.records["cand"].tolist(), x.records["dest"].tolist()))) / max(len(exact), 1)
+                for x in rn]
+        hn.close()
+        out["noise_sweep"] = {"plans": len(pcts), "noise_percent": pcts, "ms": tn * 1e3,
+                              "migrations": [int(x.n_migrations) for x in rn],
+                              "share_of_exact_plan_kept": kept}
 
     if not a.no_cpu:
         from oracle import oracle as O

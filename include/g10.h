@@ -86,6 +86,14 @@ typedef struct {
                                 maximum 512).  Both limits only trade speed against on-chip memory; the
                                 plan does not depend on them.  Tests lower them to reach the code paths of
                                 very long traces with small ones.                                        */
+  const uint64_t *dur_ns;    /* NULL, or device [K]: kernel durations that replace the analysed trace's
+                                for this plan, each > 0 (re-planning under profiling errors, the study of
+                                the evaluation's "Impact of Profiling Errors").  Which tensors are used
+                                where does not change, so the periods and the pressure per slot are the
+                                analysed ones; slot start times, the iteration time, transfer windows,
+                                channel capacities and over-capacity times follow the new durations: the
+                                plan is the one an analysis of the trace with these durations gives.
+                                Caller-owned; read during the planning call only.                        */
 } g10_params;
 
 /* One migration, i.e. one g10_pre_evict / g10_prefetch pair of Section 4.4's
@@ -170,12 +178,13 @@ int g10_vitality_read(const g10_plan_t *handle, int which, void *dst, uint64_t b
  * channel timelines, arg-max with lowest-index tie-break, commit and range
  * updates - runs on the device.  May be called repeatedly with different
  * parameters; the analysis is never modified.  Synchronises the stream.
- * Errors: G10_EINVAL (NULL, zero bandwidth), G10_ENOMEM, G10_EDEVICE.  Not
+ * Errors: G10_EINVAL (NULL, zero bandwidth, a zero in dur_ns), G10_EOVERFLOW (sum of dur_ns
+ * >= 2^62), G10_ENOMEM, G10_EDEVICE.  Not
  * getting under capacity is not an error: status = G10_RESIDUAL. */
 int g10_plan(g10_plan_t *handle, const g10_params *params, g10_result *out);
 
-/* `count` plans on one analysed trace in one call (capacity, host-memory or bandwidth
- * sweeps): outs[i] is what g10_plan(handle, &params[i], &outs[i]) would return, bit for bit.
+/* `count` plans on one analysed trace in one call (capacity, host-memory, bandwidth or
+ * kernel-time-noise sweeps): outs[i] is what g10_plan(handle, &params[i], &outs[i]) would return, bit for bit.
  * The greedy loop of a plan is a serial chain that occupies one workgroup; a batch runs the
  * loops of all its plans side by side (one workgroup each), so up to a few hundred plans take
  * about as long as the slowest one plus their streaming passes.  Every plan keeps its own

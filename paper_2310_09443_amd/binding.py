@@ -50,7 +50,8 @@ class _Stats(C.Structure):
 class _Params(C.Structure):
     _fields_ = [("gpu_cap_bytes", C.c_uint64), ("host_cap_bytes", C.c_uint64),
                 ("bw_out_Bpus", C.c_uint64 * 2), ("bw_in_Bpus", C.c_uint64 * 2),
-                ("max_iterations", C.c_uint64), ("max_tiles", C.c_uint32), ("max_chunks", C.c_uint32)]
+                ("max_iterations", C.c_uint64), ("max_tiles", C.c_uint32), ("max_chunks", C.c_uint32),
+                ("dur_ns", C.c_void_p)]
 
 
 class _Result(C.Structure):
@@ -182,13 +183,19 @@ class Handle:
     start = property(lambda self: self.read(5))
     pressure = property(lambda self: self.read(6))
 
-    @staticmethod
-    def _fill(p, gpu_cap, host_cap, bw_out, bw_in, max_iters=0, max_tiles=0, max_chunks=0):
+    def _fill(self, p, gpu_cap, host_cap, bw_out, bw_in, max_iters=0, max_tiles=0, max_chunks=0, dur=None):
+        """dur: None, or a device tensor of K 64-bit durations (ns) that replace the trace's for this plan."""
         p.gpu_cap_bytes, p.host_cap_bytes = int(gpu_cap), int(host_cap)
         p.bw_out_Bpus[0], p.bw_out_Bpus[1] = int(bw_out[0]), int(bw_out[1])
         p.bw_in_Bpus[0], p.bw_in_Bpus[1] = int(bw_in[0]), int(bw_in[1])
         p.max_iterations = int(max_iters)
         p.max_tiles, p.max_chunks = int(max_tiles), int(max_chunks)
+        if dur is None:
+            p.dur_ns = None
+        else:
+            if not (dur.is_cuda and dur.is_contiguous() and dur.element_size() == 8 and dur.numel() == self.K):
+                raise ValueError("dur must be a contiguous device tensor of K 64-bit integers")
+            p.dur_ns = dur.data_ptr()
 
     def plan_batch(self, param_dicts):
         """g10_plan_batch: one plan per dict of plan() keyword arguments."""
@@ -204,10 +211,10 @@ class Handle:
             raise G10Error(rc, "g10_plan_batch")
         return [Result(r, self.K) for r in rs]
 
-    def plan(self, gpu_cap, host_cap, bw_out, bw_in, max_iters=0, max_tiles=0, max_chunks=0) -> Result:
+    def plan(self, gpu_cap, host_cap, bw_out, bw_in, max_iters=0, max_tiles=0, max_chunks=0, dur=None) -> Result:
         import torch
         p = _Params()
-        self._fill(p, gpu_cap, host_cap, bw_out, bw_in, max_iters, max_tiles, max_chunks)
+        self._fill(p, gpu_cap, host_cap, bw_out, bw_in, max_iters, max_tiles, max_chunks, dur)
         r = _Result()
         with torch.cuda.device(self._dev):
             rc = load().g10_plan(self._h, C.byref(p), C.byref(r))
@@ -240,8 +247,8 @@ def g10_vitality(dtrace: DeviceTrace, no_wrap: bool = False, stream=None) -> Han
     return Handle(dtrace, no_wrap, stream)
 
 
-def g10_plan(handle: Handle, gpu_cap, host_cap, bw_out, bw_in, max_iters=0, max_tiles=0, max_chunks=0) -> Result:
-    return handle.plan(gpu_cap, host_cap, bw_out, bw_in, max_iters, max_tiles, max_chunks)
+def g10_plan(handle: Handle, gpu_cap, host_cap, bw_out, bw_in, max_iters=0, max_tiles=0, max_chunks=0, dur=None) -> Result:
+    return handle.plan(gpu_cap, host_cap, bw_out, bw_in, max_iters, max_tiles, max_chunks, dur)
 
 
 def g10_plan_batch(handle: Handle, param_dicts):

@@ -209,6 +209,10 @@ struct g10_plan_s {
 };
 
 int vitality_run(g10_plan_s* h, const g10_trace* tr);
+// durations of one plan that replace the trace's (g10_vitality.hip): copy, checks, start times
+int slot_times_begin(const u64* src, u32 K, u64* dur, u64* start, u64* scratch64, void* stats_dev, void* check,
+                     hipStream_t s);
+int slot_times_end(const void* check, u64* T_out);
 int plan_run(g10_plan_s* h, const g10_params* p, g10_result* out);
 int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_result* outs);
 int prefetch_run(g10_plan_s* h, g10_prefetch_result* out);

@@ -366,6 +366,8 @@ static void work_layout(PlanWork* w, Arena& ar) {
   ar.take(&w->pf_gained, C); ar.take(&w->pf_last, C);
   ar.take(&w->pf_pressure, K);
   ar.take(&w->pf_stats, 4);
+  ar.take(&w->dur_own, K); ar.take(&w->start_own, (u64)K + 1);
+  ar.take(&w->times_scratch, scan_scratch_elems(K)); ar.take(&w->times_stats, 16);
 }
 
 static int work_alloc(g10_plan_s* h, u32 max_chunks, PlanWork** slot) {
@@ -411,6 +413,7 @@ struct Inst {
   u64 retiles = 0, launches = 0, max_launches = 0, overtime_before = 0;
   bool counted = false;        // hc.n_live holds a count of the current list
   bool timed_full = false;
+  u64 times_check[16] = {};     // the checks of the plan's own durations come back here
   u64 seen_iter = 0;           // passes done at the last re-tiling
 };
 
@@ -458,6 +461,27 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     (*slot)->planned = false;
   }
 
+  // ---- the durations every plan runs on ---------------------------------------------------
+  {
+    bool own = false;
+    for (u32 i = 0; i < count; ++i) {
+      Inst& x = I[i];
+      PlanWork* w = x.w;
+      if (x.p->dur_ns) {
+        own = true;
+        G10_TRY(slot_times_begin(x.p->dur_ns, K, w->dur_own, w->start_own, w->times_scratch, w->times_stats, x.times_check, s));
+        w->dur = w->dur_own; w->start = w->start_own;
+      } else {
+        w->dur = h->dur; w->start = h->start; w->T = h->T;
+      }
+    }
+    if (own) {
+      G10_HIP(hipStreamSynchronize(s));
+      for (u32 i = 0; i < count; ++i)
+        if (I[i].p->dur_ns) G10_TRY(slot_times_end(I[i].times_check, &I[i].w->T));
+    }
+  }
+
   // ---- timelines before any eviction, candidate windows --------------------------------
   G10_HIP(hipEventRecord(I[0].w->ev[0], s));
   for (u32 i = 0; i < count; ++i) {
@@ -476,7 +500,7 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     hc.C = C;
     G10_HIP(hipMemcpyAsync(w->ctl, &hc, sizeof hc, hipMemcpyHostToDevice, s));
     Timelines& tl = x.tl;
-    tl.dur = h->dur; tl.P = w->P; tl.fre = w->fre; tl.H = w->H; tl.px = w->px; tl.otc = w->otc;
+    tl.dur = w->dur; tl.P = w->P; tl.fre = w->fre; tl.H = w->H; tl.px = w->px; tl.otc = w->otc;
     tl.K = K; tl.Kp = w->Kp; tl.nch = w->nch; tl.spt = w->spt; tl.shift_ch = w->shift_ch;
     G10_HIP(hipMemsetAsync(w->peak_after, 0, 8, s));
     hipLaunchKernelGGL(k_init_timelines, dim3(w->nch), dim3(G10_BLOCK), 0, s, tl, (const u64*)(h->pressure_buf + 1),
@@ -485,7 +509,7 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     hipLaunchKernelGGL(k_ot_full, dim3(K / G10_BLOCK + 1), dim3(G10_BLOCK), 0, s, w->otc, (const u64*)w->base0, K, w->nch, w->shift_ch);
     G10_HIP(hipGetLastError());
     if (C) {      // windows per destination; keep the candidates with at least one valid window
-      hipLaunchKernelGGL(k_prep, dim3(gC), dim3(G10_BLOCK), 0, s, (const uint4*)h->per_by_start, (const u64*)h->per_size, h->start, K, h->T, C,
+      hipLaunchKernelGGL(k_prep, dim3(gC), dim3(G10_BLOCK), 0, s, (const uint4*)h->per_by_start, (const u64*)h->per_size, w->start, K, w->T, C,
                          (const Ctl*)w->ctl, w->win, w->keep);
       G10_HIP(hipGetLastError());
       G10_TRY(scan_excl_u32(w->keep, w->keep, C, w->scratch32, s));

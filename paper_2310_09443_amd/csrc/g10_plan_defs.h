@@ -275,6 +275,11 @@ struct PlanWork {
       *g_lazyP = nullptr, *g_minOver = nullptr, *g_lazyH = nullptr, *g_hmax = nullptr, *g_base = nullptr,
       *pressure_after = nullptr,
       *peak_after = nullptr;
+  // kernel durations, slot start times and iteration time this plan runs on: the analysed trace's, or
+  // the plan's own (dur_own, start_own) when the parameters bring durations of their own
+  const u64 *dur = nullptr, *start = nullptr;
+  u64 T = 0;
+  u64 *dur_own = nullptr, *start_own = nullptr, *times_scratch = nullptr, *times_stats = nullptr;
   g10::Ctl* ctl = nullptr;
   g10_migration* records = nullptr;
   uint2* rec_ab = nullptr;

@@ -181,9 +181,9 @@ int prefetch_run(g10_plan_s* h, g10_prefetch_result* out) {
   u32* ord = w->pf_order; u32* oalt = w->pf_order_alt;
   if (n) {
     hipLaunchKernelGGL(k_pf_keys, dim3((n + G10_BLOCK - 1) / G10_BLOCK), dim3(G10_BLOCK), 0, s, (const g10_migration*)w->records, n,
-                       (const u64*)h->start, K, h->T, keys, ord);
+                       w->start, K, w->T, keys, ord);
     G10_HIP(hipGetLastError());
-    G10_TRY(radix_sort_u64_pairs(&keys, &alt, &ord, &oalt, n, bits_for(2 * h->T), w->hist, w->scratch32, s));
+    G10_TRY(radix_sort_u64_pairs(&keys, &alt, &ord, &oalt, n, bits_for(2 * w->T), w->hist, w->scratch32, s));
   }
   const size_t lds = ((size_t)2 * w->nch * 8 + sizeof(PfShared) + (size_t)w->nch * 4 + 15) & ~(size_t)15;
   hipLaunchKernelGGL(k_eager, dim3(1), dim3(LB), lds, s, (const g10_migration*)w->records, (const uint2*)w->rec_ab,

@@ -14,6 +14,7 @@
 
 #include <stdio.h>
 #include <stdlib.h>
+#include <string.h>
 
 namespace {
 
@@ -458,6 +459,31 @@ int radix_sort_u64_pairs(u64** keys, u64** alt, u32** vals, u32** valt, u64 n, u
     u32* v = *vals; *vals = *valt; *valt = v;
   }
   G10_HIP(hipGetLastError());
+  return G10_OK;
+}
+
+// Durations given for one plan instead of the analysed trace's: own copy, the same checks as
+// the analysis makes, slot start times.  `stats_dev` is 128 bytes of device memory, `check` 128
+// bytes of host memory that slot_times_end reads once the stream has been synchronised.
+static_assert(sizeof(VitStats) <= 128, "the callers keep 128 bytes for the checks");
+int slot_times_begin(const u64* src, u32 K, u64* dur, u64* start, u64* scratch64, void* stats_dev, void* check,
+                     hipStream_t s) {
+  VitStats* st = (VitStats*)stats_dev;
+  G10_HIP(hipMemsetAsync(st, 0, sizeof(VitStats), s));
+  G10_HIP(hipMemcpyAsync(dur, src, (u64)K * 8, hipMemcpyDeviceToDevice, s));
+  hipLaunchKernelGGL(k_check_dur, dim3(grid_for(K)), dim3(G10_BLOCK), 0, s, (const u64*)dur, K, st);
+  G10_HIP(hipGetLastError());
+  G10_HIP(hipMemcpyAsync(check, st, sizeof(VitStats), hipMemcpyDeviceToHost, s));
+  return scan_excl_u64(dur, start, K, scratch64, s);
+}
+
+int slot_times_end(const void* check, u64* T_out) {
+  VitStats hs;
+  memcpy(&hs, check, sizeof hs);
+  if (hs.zero_dur) return G10_EINVAL;
+  const unsigned __int128 T = ((unsigned __int128)hs.dur_hi << 32) + hs.dur_lo;
+  if (T >> 62) return G10_EOVERFLOW;
+  *T_out = (u64)T;
   return G10_OK;
 }
 

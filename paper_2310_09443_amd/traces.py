@@ -564,6 +564,21 @@ def stress(K: int = 100_000, N: int = 1_000_000, seed: int = 0x67100005,
     return Workload(tr, cap_frac=cap_frac, meta=dict(config=5, K=K, N=N))
 
 
+def noisy_durations(tr: Trace, percent: float, seed: int) -> np.ndarray:
+    """The trace's kernel durations with a profiling error of up to +-`percent` % on each
+    (uniform, independent per kernel), rounded to >= 1 ns: the input of a re-planning
+    study under kernel-time noise."""
+    i = np.arange(tr.K, dtype=np.uint64)
+    f = 1.0 + (2.0 * rand_unit(seed, 77, i) - 1.0) * (percent / 100.0)
+    return np.maximum(np.rint(tr.dur_ns.astype(np.float64) * f), 1.0).astype(np.uint64)
+
+
+def with_durations(tr: Trace, dur_ns: np.ndarray) -> Trace:
+    """The same step with other kernel durations."""
+    return Trace(tr.name + "_dur", np.ascontiguousarray(dur_ns, np.uint64), tr.size_bytes, tr.is_global,
+                 tr.use_kernel, tr.use_tensor)
+
+
 def config(i: int) -> Workload:
     """The five workloads of the benchmark, 1-based."""
     return {1: mlp_tiny, 2: encoder12, 3: resnet152, 4: decoder48, 5: stress}[i]()

@@ -211,6 +211,61 @@ def test_plan_batch(g10):
     h.close()
 
 
+def test_plan_with_other_durations(g10):
+    """Re-planning under kernel-time noise: a plan made with durations of its own equals the
+    oracle's plan of the trace that has these durations, alone and inside a batch, and so does
+    the smart prefetching on it; the handle's own analysis stays as it was."""
+    import torch
+    for w in (traces.encoder12(), traces.stress(K=2048, N=20000, seed=2)):
+        h, v, args = run_both(g10, w)
+        base = v.plan(**args)
+        sweep, oracles = [dict(args)], [v]
+        keep = []
+        for pct in (5.0, 20.0, 25.0):
+            d = traces.noisy_durations(w.trace, pct, seed=int(pct))
+            dv = torch.from_numpy(d.view(np.int64)).to("cuda:0")
+            keep.append(dv)
+            sweep.append(dict(args, dur=dv))
+            oracles.append(O.Vitality(traces.with_durations(w.trace, d), O.PREFIX))
+            assert (oracles[-1].per_L == v.per_L).all() and (oracles[-1].pressure == v.pressure).all()
+        oargs = {k: x for k, x in args.items()}
+        # alone
+        r = h.plan(**sweep[2])
+        po = oracles[2].plan(**oargs)
+        assert_plan_equal(r, po)
+        assert_prefetch_equal(h.prefetch(), po.prefetch())
+        # in a batch, next to a plan on the analysed durations
+        rs = h.plan_batch(sweep)
+        plans = [o.plan(**oargs) for o in oracles]
+        for r, po in zip(rs, plans):
+            assert_plan_equal(r, po)
+        assert any(len(po.records) != len(base.records) or po.records.tobytes() != base.records.tobytes() for po in plans[1:])
+        # the analysis is untouched: the plain plan again
+        assert (h.start == v.start).all()
+        assert_plan_equal(h.plan(**args), base)
+        assert_prefetch_equal(h.prefetch(), base.prefetch())
+        h.close()
+
+
+def test_other_durations_errors(g10):
+    import torch
+    w = traces.random_small(3)
+    h, v, args = run_both(g10, w)
+    d = w.trace.dur_ns.copy()
+    d[1] = 0
+    with pytest.raises(g10.G10Error) as e:
+        h.plan(**dict(args, dur=torch.from_numpy(d.view(np.int64)).to("cuda:0")))
+    assert e.value.code == g10.EINVAL
+    d[1] = 2 ** 62
+    with pytest.raises(g10.G10Error) as e:
+        h.plan(**dict(args, dur=torch.from_numpy(d.view(np.int64)).to("cuda:0")))
+    assert e.value.code == g10.EOVERFLOW
+    with pytest.raises(ValueError):
+        h.plan(**dict(args, dur=torch.zeros(w.trace.K + 1, dtype=torch.int64, device="cuda:0")))
+    assert_plan_equal(h.plan(**args), v.plan(**args))          # the handle still plans
+    h.close()
+
+
 def test_iteration_limit(g10):
     w = traces.resnet152()
     h, v, args = run_both(g10, w)
