@@ -45,6 +45,21 @@
 //     capacity; equal prefetch times keep the plan's order; only the pressure
 //     curve is updated (the paper says nothing of the channels here).
 //
+// Two readings have an alternative that the text of Section 4.3 supports as
+// well; both alternatives can be switched on per plan:
+//   * area = 1 ("clipped"): the benefit is the area between the pressure curve
+//     and the capacity line that the eviction removes, i.e. per slot of the
+//     absent window  duration x min(size, pressure - capacity)  where the
+//     pressure is over the capacity; the default counts the tensor's whole
+//     band, size x duration, in such a slot.  The two agree whenever every
+//     over-capacity slot of the window exceeds the capacity by at least the
+//     tensor's size.
+//   * rank = 1 ("ratio"): periods are ranked by benefit / cost with
+//     cost = eviction time + prefetch time of the chosen destination (the
+//     benefit-cost ratio of the section's example), compared exactly as
+//     fractions; the default ranks by the benefit alone, as Algorithm 1 does.
+//     Ties go to the lowest period index either way.
+//
 // Two evaluation modes compute the same values:
 //   mode 0 ("direct"):  every sum / max / search is the literal loop of its
 //                       definition over kernel slots.  O(window) per query.
@@ -92,6 +107,8 @@ struct g10o_trace {
 struct g10o_params {
   u64 gpu_cap, host_cap;
   u64 bw_out[2], bw_in[2];  // [0] flash, [1] host; bytes per microsecond
+  u32 rank;                 // 0: by benefit; 1: by benefit / (eviction + prefetch time)
+  u32 area;                 // 0: the tensor's band over capacity; 1: clipped at the capacity line
 };
 
 struct g10o_record {  // one committed migration, in commit order
@@ -153,6 +170,17 @@ struct Oracle {
 };
 
 inline u64 ceil_div(u128 x, u64 y) { return (u64)((x + y - 1) / y); }
+
+// x * y as a 192-bit number, most significant word first
+struct U192 { u64 w[3]; };
+inline U192 mul_128_64(u128 x, u64 y) {
+  const u128 lo = (u128)(u64)x * y, hi = (u128)(u64)(x >> 64) * y + (u64)(lo >> 64);
+  return U192{{(u64)(hi >> 64), (u64)hi, (u64)lo}};
+}
+inline bool greater(const U192& p, const U192& q) {
+  for (int i = 0; i < 3; ++i) if (p.w[i] != q.w[i]) return p.w[i] > q.w[i];
+  return false;
+}
 
 // start time of slot j on the doubled timeline, j in [0, 2K]   (two
 // back-to-back iterations that follow the same plan)
@@ -341,13 +369,32 @@ struct Planner {
            free_time(d, IN, (u64)D.b + 1, (u64)x.R - 1) >= D.tau_i;
   }
 
+  // what evicting s bytes during slots [x, y] takes away from the pressure above the capacity
+  u128 benefit(u64 s, u64 x, u64 y) const {
+    if (pr.area == 0) return (u128)s * over_time(x, y);              // the tensor's band, where over capacity
+    u128 B = 0;
+    if (mode == 0) {                                                   // slot by slot: min(size, excess)
+      for (u64 j = x; j <= y; ++j) {
+        const u32 k = (u32)(j % K);
+        if (over(k)) B += (u128)o.dur[k] * std::min(s, pressure[k] - pr.gpu_cap);
+      }
+    } else {                                                           // the band minus what sticks out below the line
+      B = (u128)s * over_time(x, y);
+      for (u64 j = x; j <= y; ++j) {
+        const u32 k = (u32)(j % K);
+        if (over(k) && pressure[k] - pr.gpu_cap < s) B -= (u128)o.dur[k] * (s - (pressure[k] - pr.gpu_cap));
+      }
+    }
+    return B;
+  }
+
   // flash first; host only if flash cannot take it; benefit of that choice
   void score(const Cand& x, int& dest, u128& B) const {
     dest = -1; B = 0;
     for (int d = 0; d < 2; ++d) {
       if (!x.d[d].valid || !feasible(x, d)) continue;
       dest = d;
-      B = (u128)x.s * over_time(x.d[d].a, x.d[d].b);
+      B = benefit(x.s, x.d[d].a, x.d[d].b);
       return;
     }
   }
@@ -382,6 +429,7 @@ struct Planner {
 int plan(Oracle& o, const g10o_params& pr, int mode, u64 max_iters, g10o_summary& S) {
   std::memset(&S, 0, sizeof S);
   for (int d = 0; d < 2; ++d) if (!pr.bw_out[d] || !pr.bw_in[d]) return -1;
+  if (pr.rank > 1 || pr.area > 1) return -1;
   Planner P(o, pr, mode);
   P.prepare();
   o.records.clear();
@@ -399,11 +447,21 @@ int plan(Oracle& o, const g10o_params& pr, int mode, u64 max_iters, g10o_summary
     S.n_cand_evals += P.n_live;
     if (mode == 1) P.rebuild_prefix();
     size_t w = C; int wd = -1; u128 wB = 0;
-    for (size_t c = 0; c < C; ++c) {                                    // rank: best benefit, lowest index
+    u64 wcost = 1;
+    for (size_t c = 0; c < C; ++c) {                                    // rank: best key, lowest index
       if (!P.live[c]) continue;
       int d; u128 B;
       P.score(P.cand[c], d, B);
-      if (B > wB) { wB = B; w = c; wd = d; }
+      if (B == 0) continue;
+      bool better;
+      u64 cost = 1;
+      if (pr.rank == 0) {
+        better = B > wB;
+      } else {                                                          // B / cost > wB / wcost, as fractions
+        cost = P.cand[c].d[d].tau_o + P.cand[c].d[d].tau_i;
+        better = greater(mul_128_64(B, wcost), mul_128_64(wB, cost));
+      }
+      if (better) { wB = B; w = c; wd = d; wcost = cost; }
     }
     if (wB == 0) { S.status = 1; break; }                               // nothing beneficial is left
     const Cand& x = P.cand[w];

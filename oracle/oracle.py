@@ -13,6 +13,8 @@ import numpy as np
 from . import build as _build
 
 DIRECT, PREFIX = 0, 1
+BY_BENEFIT, BY_RATIO = 0, 1        # ranking key
+BAND, CLIPPED = 0, 1               # what counts as the benefit
 FITS, RESIDUAL, TRUNCATED = 0, 1, 2
 
 RECORD = np.dtype([("cand", "<u4"), ("tensor", "<u4"), ("evict_after", "<u4"),
@@ -30,7 +32,8 @@ class _Trace(C.Structure):
 
 class _Params(C.Structure):
     _fields_ = [("gpu_cap", C.c_uint64), ("host_cap", C.c_uint64),
-                ("bw_out", C.c_uint64 * 2), ("bw_in", C.c_uint64 * 2)]
+                ("bw_out", C.c_uint64 * 2), ("bw_in", C.c_uint64 * 2),
+                ("rank", C.c_uint32), ("area", C.c_uint32)]
 
 
 class _Summary(C.Structure):
@@ -112,8 +115,9 @@ class Vitality:
         return a
 
     @staticmethod
-    def _params(gpu_cap, host_cap, bw_out, bw_in):
+    def _params(gpu_cap, host_cap, bw_out, bw_in, rank=0, area=0):
         p = _Params()
+        p.rank, p.area = int(rank), int(area)
         p.gpu_cap, p.host_cap = int(gpu_cap), int(host_cap)
         p.bw_out[0], p.bw_out[1] = int(bw_out[0]), int(bw_out[1])
         p.bw_in[0], p.bw_in[1] = int(bw_in[0]), int(bw_in[1])
@@ -132,8 +136,8 @@ class Vitality:
             raise OracleError(rc)
         return valid, a, b, to, ti
 
-    def plan(self, gpu_cap, host_cap, bw_out, bw_in, mode=None, max_iters=2 ** 64 - 1):
-        p = self._params(gpu_cap, host_cap, bw_out, bw_in)
+    def plan(self, gpu_cap, host_cap, bw_out, bw_in, mode=None, max_iters=2 ** 64 - 1, rank=0, area=0):
+        p = self._params(gpu_cap, host_cap, bw_out, bw_in, rank, area)
         s = _Summary()
         rc = lib().g10o_plan(self._h, C.byref(p), self.mode if mode is None else mode,
                              int(max_iters), C.byref(s))

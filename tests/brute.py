@@ -7,6 +7,7 @@ by replaying those migrations from an empty channel.  Sums are loops over
 slots.  Usable only for a handful of kernels and tensors; it pins the oracle
 (Sections 4.2-4.3, Algorithm 1) on random tiny inputs.
 """
+from fractions import Fraction
 from itertools import product
 
 FLASH, HOST = 0, 1
@@ -81,7 +82,11 @@ def pressure_from_table(trace):
 
 
 class Brute:
-    def __init__(self, trace, gpu_cap, host_cap, bw_out, bw_in, no_wrap=False):
+    def __init__(self, trace, gpu_cap, host_cap, bw_out, bw_in, no_wrap=False, rank="benefit", area="band"):
+        """rank="ratio": periods are ranked by benefit / (eviction + prefetch time) instead of the
+        benefit alone; area="clipped": the benefit is the area between the pressure curve and the
+        capacity line that goes away (Section 4.3's two alternatives)."""
+        self.rank, self.area = rank, area
         self.tr = trace
         self.K = trace.K
         self.dur = [int(x) for x in trace.dur_ns]
@@ -151,9 +156,16 @@ class Brute:
             free_i = sum(self.dur[j % K] - busy[d][1][j % K] for j in range(b + 1, R))
             if free_o < tau_o or free_i < tau_i:
                 continue
+            if self.area == "clipped":
+                B = 0
+                for j in range(a, b + 1):
+                    before = max(pressure[j % K] - self.cap, 0)           # over the line with the tensor
+                    after = max(pressure[j % K] - s - self.cap, 0)        # and without it
+                    B += self.dur[j % K] * (before - after)
+                return d, B, tau_o + tau_i
             over = sum(self.dur[j % K] for j in range(a, b + 1) if pressure[j % K] > self.cap)
-            return d, s * over
-        return None, 0
+            return d, s * over, tau_o + tau_i
+        return None, 0, 1
 
     def run(self):
         """Returns (committed [(cand, dest, benefit)], dropped [(pass, cand)], status, passes)."""
@@ -166,10 +178,12 @@ class Brute:
                 return out, dropped, 0, passes
             passes += 1
             best = (0, None, None)
+            best_key = Fraction(0)
             for c in sorted(live):
-                d, B = self.score(c, pressure, busy)
-                if B > best[0]:
-                    best = (B, c, d)
+                d, B, cost = self.score(c, pressure, busy)
+                key = Fraction(B, cost) if self.rank == "ratio" else Fraction(B)
+                if key > best_key:
+                    best, best_key = (B, c, d), key
             B, c, d = best
             if B == 0:
                 return out, dropped, 1, passes

@@ -45,3 +45,7 @@ class Golden:
     def plan_args(self):
         p = self.params
         return dict(gpu_cap=p["gpu_cap"], host_cap=p["host_cap"], bw_out=p["bw_out"], bw_in=p["bw_in"])
+
+    def variant_args(self):
+        """Ranking key and benefit reading of the example (0 / absent: the default)."""
+        return dict(rank=self.params.get("rank", 0), area=self.params.get("area", 0))

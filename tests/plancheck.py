@@ -14,9 +14,12 @@ properties that must hold for any correct run at any size:
     channel reservations never exceed a slot's duration and add up to the
     committed transfer times; host memory never exceeds its capacity;
   * the recorded benefit is size x over-capacity time of the absent window in
-    the state just before the commit;
+    the state just before the commit (area="clipped": the area between the
+    pressure curve and the capacity line that the eviction removes, per slot
+    duration x min(size, pressure - capacity));
   * greedy consistency, on every pass or on a sample of passes: the chosen
-    candidate is the highest-benefit live candidate, lowest index on ties,
+    candidate is the highest-benefit live candidate (rank="ratio": the one with
+    the highest benefit / (eviction + prefetch time)), lowest index on ties,
     and a dropped candidate was the best one, bound for host, with no room;
   * the final state matches the reported status (fits <=> no slot over
     capacity; otherwise no live candidate has a positive benefit) and the
@@ -84,7 +87,9 @@ class Problem:
 
 
 class Machine:
-    def __init__(self, gpu_cap, host_cap, bw_out, bw_in):
+    def __init__(self, gpu_cap, host_cap, bw_out, bw_in, rank="benefit", area="band"):
+        assert rank in ("benefit", "ratio") and area in ("band", "clipped")
+        self.rank, self.area = rank, area
         self.gpu_cap, self.host_cap = int(gpu_cap), int(host_cap)
         self.bw_out = [int(x) for x in bw_out]
         self.bw_in = [int(x) for x in bw_in]
@@ -150,16 +155,42 @@ class Replay:
 
     def best(self):
         """(cand, dest, exact benefit) of the argmax, ties to the lowest index."""
+        from fractions import Fraction
         dest, ot = self.score_all()
         s = self.pb.per_s
-        approx = s.astype(np.float64) * ot.astype(np.float64)
+        approx = s.astype(np.float64) * ot.astype(np.float64)       # the band: also an upper bound of the clipped area
         if approx.size == 0 or approx.max() <= 0:
             return -1, -1, 0
-        near = np.flatnonzero(approx >= approx.max() * (1.0 - 1e-9))
-        exact = [int(s[i]) * int(ot[i]) for i in near]
-        mx = max(exact)
-        c = int(near[exact.index(mx)])
-        return c, int(dest[c]), mx
+        if self.m.area == "clipped":                                 # exact areas of everything that has a band at all
+            cand = np.flatnonzero(approx > 0)
+            exact_b = {int(i): self.benefit(int(i), int(dest[i])) for i in cand}
+            approx = np.zeros_like(approx)
+            for i, v in exact_b.items():
+                approx[i] = float(v)
+        else:
+            exact_b = None
+        cost = np.ones(len(s), np.float64)
+        if self.m.rank == "ratio":
+            for d in (FLASH, HOST):
+                cost = np.where(dest == d, (self.tau_o[d] + self.tau_i[d]).astype(np.float64), cost)
+        key = approx / cost
+        if key.max() <= 0:
+            return -1, -1, 0
+        near = np.flatnonzero(key >= key.max() * (1.0 - 1e-9))
+
+        def exact(i):
+            i = int(i)
+            B = exact_b[i] if exact_b is not None else int(s[i]) * int(ot[i])
+            if self.m.rank == "ratio":
+                d = int(dest[i])
+                return B, Fraction(B, int(self.tau_o[d][i]) + int(self.tau_i[d][i]))
+            return B, B
+
+        vals = [exact(i) for i in near]
+        mx = max(v[1] for v in vals)
+        j = [v[1] for v in vals].index(mx)
+        c = int(near[j])
+        return c, int(dest[c]), vals[j][0]
 
     # ---- one candidate, straight from the definitions -----------------------
     def feasible(self, c, d):
@@ -174,7 +205,11 @@ class Replay:
 
     def benefit(self, c, d):
         ab = self._slots(int(self.a[d][c]), int(self.b[d][c]))
-        return int(self.pb.per_s[c]) * int(self.pb.dur[ab][self.over()[ab]].sum())
+        size = int(self.pb.per_s[c])
+        if self.m.area == "clipped":
+            excess = np.clip(self.pressure[ab] - self.m.gpu_cap, 0, size)
+            return sum(int(x) * int(y) for x, y in zip(self.pb.dur[ab][excess > 0], excess[excess > 0]))
+        return size * int(self.pb.dur[ab][self.over()[ab]].sum())
 
     def host_room(self, c):
         pb = self.pb
