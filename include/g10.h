@@ -69,6 +69,8 @@ typedef struct {
   uint64_t iter_ns;     /* duration of the iteration                                   */
 } g10_vitality_stats;
 
+enum { G10_RANK_BENEFIT = 0, G10_RANK_RATIO = 1 };
+
 /* Inputs of Algorithm 1 beyond the periods: the GPU memory capacity, the host
  * memory that may hold evicted tensors, and the bandwidths from which eviction
  * and prefetch times are estimated (Section 4.2; Table 2 has asymmetric flash
@@ -94,6 +96,11 @@ typedef struct {
                                 channel capacities and over-capacity times follow the new durations: the
                                 plan is the one an analysis of the trace with these durations gives.
                                 Caller-owned; read during the planning call only.                        */
+  uint32_t rank;             /* G10_RANK_BENEFIT (0, Algorithm 1: by the benefit alone) or G10_RANK_RATIO:
+                                periods are ranked by benefit / (eviction time + prefetch time) of the
+                                destination the policy picks, the benefit-cost ratio of Section 4.3's
+                                example, compared exactly as fractions; ties to the lowest period index   */
+  uint32_t reserved;         /* must be 0                                                                */
 } g10_params;
 
 /* One migration, i.e. one g10_pre_evict / g10_prefetch pair of Section 4.4's
@@ -178,7 +185,7 @@ int g10_vitality_read(const g10_plan_t *handle, int which, void *dst, uint64_t b
  * channel timelines, arg-max with lowest-index tie-break, commit and range
  * updates - runs on the device.  May be called repeatedly with different
  * parameters; the analysis is never modified.  Synchronises the stream.
- * Errors: G10_EINVAL (NULL, zero bandwidth, a zero in dur_ns), G10_EOVERFLOW (sum of dur_ns
+ * Errors: G10_EINVAL (NULL, zero bandwidth, a zero in dur_ns, unknown rank, reserved != 0), G10_EOVERFLOW (sum of dur_ns
  * >= 2^62), G10_ENOMEM, G10_EDEVICE.  Not
  * getting under capacity is not an error: status = G10_RESIDUAL. */
 int g10_plan(g10_plan_t *handle, const g10_params *params, g10_result *out);

@@ -17,6 +17,7 @@ namespace {
 
 struct Winner {               // what a commit needs of the winning candidate
   u64 hi, lo;                 // benefit
+  u64 cost;                   // eviction + prefetch time (ranking by benefit / cost only)
   u64 s, fo_base, fi_end;     // size; free out-channel time before L1; free in-channel time before R
   u32 cand, tensor, pos, dest, L1, R, a, b;
 };
@@ -32,6 +33,7 @@ struct Shared {               // small per-pass state of the loop workgroup
   // progress (mirrors Ctl)
   u64 n_iter, n_mig, n_drop, n_evals, units, second, jobs;
   u32 thr_key, status, done, stop;
+  u32 gshift, pad2;
   u64 t_start;
   u64 phase[12], t_last;
 };
@@ -57,6 +59,41 @@ __device__ __forceinline__ u32 wave_best_lane(u64 hi, u64 lo, u32 cand) {
   return (u32)__builtin_ctzll(m);
 }
 
+__device__ __forceinline__ u64 read_lane64(u64 v, u32 l) {
+  const u32 lo = (u32)__builtin_amdgcn_readlane((int)(u32)v, (int)l), hi = (u32)__builtin_amdgcn_readlane((int)(u32)(v >> 32), (int)l);
+  return ((u64)hi << 32) | lo;
+}
+
+// The same for benefit / cost.  The approximate keys only narrow the field: a lane stays if
+// its upper key reaches the largest lower key.  The lanes that stay are settled exactly: take
+// the first, keep the lanes that beat it (fractions compared by cross multiplication, equal
+// ones by index), repeat with the first of those.
+__device__ __forceinline__ u32 wave_best_lane_ratio(u64 hi, u64 lo, u64 cost, u32 cand) {
+  const bool has = (hi | lo) != 0;
+  const double r = has ? ratio_approx(hi, lo, cost) : 0.0;
+  const u32 kdn_max = wave_max(has ? rkey_dn(r) : 0u);
+  u64 m = __ballot(has && rkey_up(r) >= kdn_max);
+  if (!m) return NONE32;
+  const u32 lane = lane_id();
+  u32 p = (u32)__builtin_ctzll(m);
+  while (m & (m - 1)) {
+    const u64 ph = read_lane64(hi, p), pl = read_lane64(lo, p), pc = read_lane64(cost, p);
+    const u32 pcand = (u32)__builtin_amdgcn_readlane((int)cand, (int)p);
+    const bool beats = ((m >> lane) & 1ull) && lane != p && better_ratio(hi, lo, cost, cand, ph, pl, pc, pcand);
+    m = __ballot(beats);
+    if (!m) break;
+    p = (u32)__builtin_ctzll(m);
+  }
+  return p;
+}
+
+template <bool RATIO>
+__device__ __forceinline__ u32 best_lane(u64 hi, u64 lo, u64 cost, u32 cand) {
+  if (RATIO) return wave_best_lane_ratio(hi, lo, cost, cand);
+  return wave_best_lane(hi, lo, cand);
+}
+
+template <bool RATIO>
 __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans) {
   extern __shared__ __align__(16) unsigned char smem[];
   const LoopArgs a = plans[blockIdx.x];        // one workgroup per plan
@@ -92,6 +129,7 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
     S->n_iter = ctl->n_iter; S->n_mig = ctl->n_mig; S->n_drop = ctl->n_drop; S->n_evals = ctl->n_evals;
     S->units = 0; S->second = 0; S->jobs = 0;
     S->thr_key = ctl->thr_key; S->status = ctl->status; S->done = ctl->done;
+    S->gshift = ctl->gshift ? ctl->gshift : GUESS_SHIFT;
     S->nl = 0; S->restL = NONE32; S->stale_hot = 0;
     S->stop = 0; S->t_start = wall_clock64();
     S->win.hi = 0; S->win.lo = 0;
@@ -202,9 +240,10 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
     __syncthreads();
   };
 
+  u32 pass_units = 0;           // units of 256 candidates scored in the current pass (the same in every thread)
   // this thread's best candidate of the pass
   Winner mine;
-  mine.hi = 0; mine.lo = 0; mine.cand = NONE32;
+  mine.hi = 0; mine.lo = 0; mine.cost = 1; mine.cand = NONE32;
 
   struct CandV { uint4 A, B; uint2 id; u32 p, t; };
   auto load_cand = [&](u32 u) -> CandV {
@@ -223,6 +262,7 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
     const u32 nunits = S->ntl << a.tshift;
     PrefixView pv; pv.px = tl.px; pv.base = base; pv.K = K; pv.nch = nch; pv.shift_ch = tl.shift_ch;
     Machine mc; mc.bwo0 = bwo0; mc.bwo1 = bwo1; mc.bwi0 = bwi0; mc.bwi1 = bwi1;
+    mc.ivo0 = ivo0; mc.ivo1 = ivo1; mc.ivi0 = ivi0; mc.ivi1 = ivi1;
     u32 u = tid >> 8;
     CandV cur;
     if (u < nunits) cur = load_cand(u);
@@ -241,14 +281,24 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
         if (lane == 0) { atomicAdd((unsigned long long*)&S->phase[9], (unsigned long long)nl); atomicAdd((unsigned long long*)&S->phase[10], (unsigned long long)nd); }
       }
 #endif
-      const bool one = gt128(r.h1, r.l1, r.h0, r.l0);
-      const u32 k = wave_max(upkey(one ? r.h1 : r.h0, one ? r.l1 : r.l0));
+      u64 c0 = 1, c1 = 1;
+      u32 kc;                                    // bound of the candidate: the larger of its destinations' keys
+      if (RATIO) {
+        if (r.ok0 || r.ok1) costs_of(mc, ((u64)B.w << 32) | B.z, c0, c1);
+        const u32 k0 = key_up_of<true>(r.h0, r.l0, c0), k1 = key_up_of<true>(r.h1, r.l1, c1);
+        kc = k0 > k1 ? k0 : k1;
+      } else {
+        const bool one = gt128(r.h1, r.l1, r.h0, r.l0);
+        kc = upkey(one ? r.h1 : r.h0, one ? r.l1 : r.l0);
+      }
+      const u32 k = wave_max(kc);
       if (lane == 0 && k) atomicMax(&keys[cur.t], k);
       if (r.ok0 || r.ok1) {                      // flash first; host only if flash cannot take it
         const u32 d = r.ok0 ? 0u : 1u;
-        const u64 hi = d ? r.h1 : r.h0, lo = d ? r.l1 : r.l0;
-        if ((hi | lo) != 0 && better(hi, lo, cur.id.x, mine.hi, mine.lo, mine.cand)) {
-          mine.hi = hi; mine.lo = lo; mine.cand = cur.id.x; mine.tensor = cur.id.y; mine.pos = cur.p; mine.dest = d;
+        const u64 hi = d ? r.h1 : r.h0, lo = d ? r.l1 : r.l0, cost = d ? c1 : c0;
+        if ((hi | lo) != 0 && (RATIO ? better_ratio(hi, lo, cost, cur.id.x, mine.hi, mine.lo, mine.cost, mine.cand)
+                                     : better(hi, lo, cur.id.x, mine.hi, mine.lo, mine.cand))) {
+          mine.hi = hi; mine.lo = lo; mine.cost = cost; mine.cand = cur.id.x; mine.tensor = cur.id.y; mine.pos = cur.p; mine.dest = d;
           mine.L1 = A.x; mine.R = A.y; mine.a = d ? B.x : A.z; mine.b = d ? B.y : A.w; mine.s = ((u64)B.w << 32) | B.z;
           mine.fo_base = r.fo_L; mine.fi_end = r.fi_R;
         }
@@ -257,12 +307,13 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
       cur = nxt;
     }
     if (tid == 0) S->units += nunits;
+    pass_units += nunits;
   };
 
   // block-wide arg-max of the threads' best (two barriers); refreshes the group bounds in between
   auto reduce_best = [&]() {
-    const u32 bl = wave_best_lane(mine.hi, mine.lo, mine.cand);
-    if (bl == NONE32) { if (lane == 0) { S->wave_win[wave].hi = 0; S->wave_win[wave].lo = 0; S->wave_win[wave].cand = NONE32; } }
+    const u32 bl = best_lane<RATIO>(mine.hi, mine.lo, mine.cost, mine.cand);
+    if (bl == NONE32) { if (lane == 0) { S->wave_win[wave].hi = 0; S->wave_win[wave].lo = 0; S->wave_win[wave].cost = 1; S->wave_win[wave].cand = NONE32; } }
     else if (lane == bl) S->wave_win[wave] = mine;
     __syncthreads();                               // all tile bounds and wavefront winners are in LDS
     const u32 ntl = S->ntl;
@@ -272,10 +323,10 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
       if (lane == 0) skeys[g] = k;
     }
     if (wave == 0) {
-      u64 h = 0, l = 0;
+      u64 h = 0, l = 0, cs = 1;
       u32 c = NONE32;
-      if (lane < LW) { h = S->wave_win[lane].hi; l = S->wave_win[lane].lo; c = S->wave_win[lane].cand; }
-      const u32 w = wave_best_lane(h, l, c);
+      if (lane < LW) { h = S->wave_win[lane].hi; l = S->wave_win[lane].lo; cs = S->wave_win[lane].cost; c = S->wave_win[lane].cand; }
+      const u32 w = best_lane<RATIO>(h, l, cs, c);
       if (w == NONE32) { if (lane == 0) { S->win.hi = 0; S->win.lo = 0; } }
       else {
         if (lane == 0) {
@@ -436,7 +487,8 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
     if (max_iter && S->n_iter >= max_iter) { if (tid == 0) { S->done = 1; S->status = G10_TRUNCATED; } break; }
     if (passes >= a.pass_budget || S->stop) break;
     ++passes;
-    mine.hi = 0; mine.lo = 0; mine.cand = NONE32;
+    mine.hi = 0; mine.lo = 0; mine.cost = 1; mine.cand = NONE32;
+    pass_units = 0;
     u32 thr = S->thr_key ? S->thr_key : NONE32;
     __syncthreads();                               // the loop conditions and thr are read
     for (u32 i = tid; i < ns; i += LB) smark[i] = 0;     // no tile scored in this pass yet
@@ -474,7 +526,7 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
       reduce_best();
       PHASE(2);
       ++rounds;
-      const u32 kb = upkey(S->win.hi, S->win.lo);
+      const u32 kb = key_dn_of<RATIO>(S->win.hi, S->win.lo, S->win.cost);
       const u32 need = kb ? kb : 1u;
       if (rest < need) break;                            // every tile left out is below the best found
       // a tile left out may hold an equal or better one; with nothing found yet, step down a few percent
@@ -526,12 +578,19 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
       const u32 p = S->win.pos;
       a.cd.A[p] = make_uint4(L1, R, 1u, 0u);             // the candidate leaves the live set
       a.cd.B[p] = make_uint4(1u, 0u, (u32)s, (u32)(s >> 32));
-      // first threshold of the next pass: a little under this benefit
+      // first threshold of the next pass: a little under this benefit.  How little adapts: where
+      // many candidates are nearly equal (a pass scored thousands) the margin halves, and it
+      // doubles again when a narrow margin costs second rounds with little to score
+      u32 gs = S->gshift;
+      if (pass_units > 8u && gs < GUESS_SHIFT_MAX) ++gs;
+      else if (rounds > 1u && pass_units <= 2u && gs > GUESS_SHIFT) --gs;
+      S->gshift = gs;
       u64 ghi = S->win.hi, glo = S->win.lo;
-      const u64 dlo = (glo >> GUESS_SHIFT) | (ghi << (64 - GUESS_SHIFT)), dhi = ghi >> GUESS_SHIFT;
+      const u64 dlo = (glo >> gs) | (ghi << (64 - gs)), dhi = ghi >> gs;
       const u64 nlo = glo - dlo;
       ghi = ghi - dhi - (glo < dlo ? 1ull : 0ull);
-      S->thr_key = upkey(ghi, nlo);
+      S->thr_key = RATIO ? rkey_dn(ratio_approx(S->win.hi, S->win.lo, S->win.cost) * (1.0 - 1.0 / (double)(1u << gs)))
+                         : upkey(ghi, nlo);
       if (!room) {
         g10_dropped dr; dr.iteration = S->n_iter - 1; dr.cand = S->win.cand; dr.reserved = 0;
         a.dropped[S->n_drop] = dr;
@@ -605,6 +664,7 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
   if (tid == 0) {
     ctl->n_iter = S->n_iter; ctl->n_mig = S->n_mig; ctl->n_drop = S->n_drop; ctl->n_evals = S->n_evals;
     ctl->thr_key = S->thr_key; ctl->status = S->status; ctl->done = S->done;
+    ctl->gshift = S->gshift;
     ctl->overtime_after = base[(u64)A_OT * nb1 + nch];
     for (u32 i = 0; i < 12; ++i) ctl->phase[i] += S->phase[i];
     ctl->units_scored += S->units; ctl->second_rounds += S->second; ctl->jobs_run += S->jobs; ctl->launches += 1;
@@ -623,12 +683,14 @@ size_t loop_lds_bytes(u32 nch, u32 nt) {
 }
 
 int loop_allow_large_lds() {
-  G10_HIP(hipFuncSetAttribute((const void*)k_loop, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+  G10_HIP(hipFuncSetAttribute((const void*)k_loop<false>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+  G10_HIP(hipFuncSetAttribute((const void*)k_loop<true>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
   return G10_OK;
 }
 
-int loop_launch(const LoopArgs* plans, u32 n_plans, size_t lds, hipStream_t s) {
-  hipLaunchKernelGGL(k_loop, dim3(n_plans), dim3(LB), lds, s, plans);
+int loop_launch(const LoopArgs* plans, u32 n_plans, size_t lds, u32 rank, hipStream_t s) {
+  if (rank == G10_RANK_RATIO) hipLaunchKernelGGL(k_loop<true>, dim3(n_plans), dim3(LB), lds, s, plans);
+  else hipLaunchKernelGGL(k_loop<false>, dim3(n_plans), dim3(LB), lds, s, plans);
   G10_HIP(hipGetLastError());
   return G10_OK;
 }

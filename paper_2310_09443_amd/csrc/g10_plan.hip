@@ -202,9 +202,12 @@ __device__ __forceinline__ u64 sort_key(u32 key31, u32 posbits, u32 p) {
 // the bound a sort key stands for: at least the score key it was made from, 0 only for 0
 __device__ __forceinline__ u32 bound_of_sort_key(u64 sk, u32 posbits) { return (0x7fffffu - (u32)(sk >> posbits)) << 8; }
 
+// RATIO: ranking by benefit / cost; a window inside the other may then still have the larger
+// key (its transfers can be the shorter ones), so both are looked up.
+template <bool RATIO>
 __global__ __launch_bounds__(G10_BLOCK) void k_score_full(const uint4* __restrict__ cA, const uint4* __restrict__ cB, u32 n,
                                                          const u64* __restrict__ ot, u32 K, u32 posbits,
-                                                         u64* __restrict__ sortkeys) {
+                                                         u64* __restrict__ sortkeys, const Ctl* __restrict__ ctl) {
   const u32 p = blockIdx.x * G10_BLOCK + threadIdx.x;
   if (p >= n) return;
   const uint4 A = cA[p], B = cB[p];
@@ -212,7 +215,7 @@ __global__ __launch_bounds__(G10_BLOCK) void k_score_full(const uint4* __restric
   const u64 total = ot[K];
   bool v0 = A.z <= A.w, v1 = B.x <= B.y;
   // the prefix is monotone: a window inside the other one cannot hold more over-capacity time
-  if (v0 && v1) {
+  if (!RATIO && v0 && v1) {
     if (B.x <= A.z && B.y >= A.w) v0 = false;
     else if (A.z <= B.x && A.w >= B.y) v1 = false;
   }
@@ -226,6 +229,16 @@ __global__ __launch_bounds__(G10_BLOCK) void k_score_full(const uint4* __restric
     const u32 a = B.x, b = B.y + 1;
     const u64 oa = ot[a >= K ? a - K : a], ob = ot[b >= K ? b - K : b];
     t1 = (ob + (b >= K ? total : 0ull)) - (oa + (a >= K ? total : 0ull));
+  }
+  if (RATIO) {
+    Machine mc;
+    mc.bwo0 = ctl->bw_out[0]; mc.bwo1 = ctl->bw_out[1]; mc.bwi0 = ctl->bw_in[0]; mc.bwi1 = ctl->bw_in[1];
+    mc.ivo0 = ctl->inv_out[0]; mc.ivo1 = ctl->inv_out[1]; mc.ivi0 = ctl->inv_in[0]; mc.ivi1 = ctl->inv_in[1];
+    u64 c0, c1;
+    costs_of(mc, s, c0, c1);
+    const u32 k0 = key_up_of<true>(__umul64hi(s, t0), s * t0, c0), k1 = key_up_of<true>(__umul64hi(s, t1), s * t1, c1);
+    sortkeys[p] = sort_key(k0 > k1 ? k0 : k1, posbits, p);
+    return;
   }
   const u64 t = t1 > t0 ? t1 : t0;
   sortkeys[p] = sort_key(upkey(__umul64hi(s, t), s * t), posbits, p);
@@ -257,6 +270,7 @@ __global__ __launch_bounds__(G10_BLOCK) void k_tile_gather(const u64* __restrict
 // workgroups of the chip; used between launches of the loop kernel to put the
 // candidates back into score order).  Writes the sort key;
 // strikes dead destinations; counts the candidates that can still score.
+template <bool RATIO>
 __global__ __launch_bounds__(G10_BLOCK) void k_rescore(Cands cd, u32 n, const u64* __restrict__ px, const u64* __restrict__ g_base,
                                                       u32 K, u32 nch, u32 shift_ch, const Ctl* ctl, u32 posbits,
                                                       u64* __restrict__ sortkeys, u32* __restrict__ n_live) {
@@ -265,14 +279,23 @@ __global__ __launch_bounds__(G10_BLOCK) void k_rescore(Cands cd, u32 n, const u6
   __syncthreads();
   PrefixView pv; pv.px = px; pv.base = lb; pv.K = K; pv.nch = nch; pv.shift_ch = shift_ch;
   Machine mc; mc.bwo0 = ctl->bw_out[0]; mc.bwo1 = ctl->bw_out[1]; mc.bwi0 = ctl->bw_in[0]; mc.bwi1 = ctl->bw_in[1];
+  mc.ivo0 = ctl->inv_out[0]; mc.ivo1 = ctl->inv_out[1]; mc.ivi0 = ctl->inv_in[0]; mc.ivi1 = ctl->inv_in[1];
   u32 live = 0;
   for (u32 p = blockIdx.x * G10_BLOCK + threadIdx.x; p < n; p += gridDim.x * G10_BLOCK) {
     const uint4 A = cd.A[p], B = cd.B[p];
     const Score r = score_candidate(pv, mc, A, B);
     if (r.strike0) cd.A[p] = make_uint4(A.x, A.y, 1u, 0u);
     if (r.strike1) cd.B[p] = make_uint4(1u, 0u, B.z, B.w);
-    const bool one = gt128(r.h1, r.l1, r.h0, r.l0);
-    const u32 k = upkey(one ? r.h1 : r.h0, one ? r.l1 : r.l0);
+    u32 k;
+    if (RATIO) {
+      u64 c0 = 1, c1 = 1;
+      if (r.ok0 || r.ok1) costs_of(mc, ((u64)B.w << 32) | B.z, c0, c1);
+      const u32 k0 = key_up_of<true>(r.h0, r.l0, c0), k1 = key_up_of<true>(r.h1, r.l1, c1);
+      k = k0 > k1 ? k0 : k1;
+    } else {
+      const bool one = gt128(r.h1, r.l1, r.h0, r.l0);
+      k = upkey(one ? r.h1 : r.h0, one ? r.l1 : r.l0);
+    }
     sortkeys[p] = sort_key(k, posbits, p);
     live += k != 0;
   }
@@ -497,6 +520,7 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
       hc.inv_in[d] = hc.bw_in[d] > 1 ? (u64)((((unsigned __int128)1) << 64) / hc.bw_in[d]) : 0;
     }
     hc.max_iter = p->max_iterations;
+    hc.rank = p->rank;
     hc.C = C;
     G10_HIP(hipMemcpyAsync(w->ctl, &hc, sizeof hc, hipMemcpyHostToDevice, s));
     Timelines& tl = x.tl;
@@ -531,16 +555,25 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     if (first) {
       const u32 gn = (n + G10_BLOCK - 1) / G10_BLOCK;
       // the two events take the kernel's own begin and end time stamps
-      hipExtLaunchKernelGGL(k_score_full, dim3(gn), dim3(G10_BLOCK), 0, s, w->ev[2], w->ev[3], 0, (const uint4*)w->cd[x.cur].A,
-                            (const uint4*)w->cd[x.cur].B, n, (const u64*)w->otc, K, posbits, w->keys);
+      if (x.p->rank == G10_RANK_RATIO)
+        hipExtLaunchKernelGGL(k_score_full<true>, dim3(gn), dim3(G10_BLOCK), 0, s, w->ev[2], w->ev[3], 0, (const uint4*)w->cd[x.cur].A,
+                              (const uint4*)w->cd[x.cur].B, n, (const u64*)w->otc, K, posbits, w->keys, (const Ctl*)w->ctl);
+      else
+        hipExtLaunchKernelGGL(k_score_full<false>, dim3(gn), dim3(G10_BLOCK), 0, s, w->ev[2], w->ev[3], 0, (const uint4*)w->cd[x.cur].A,
+                              (const uint4*)w->cd[x.cur].B, n, (const u64*)w->otc, K, posbits, w->keys, (const Ctl*)w->ctl);
       x.timed_full = true;
     } else {
       u32 gn = (n + G10_BLOCK - 1) / G10_BLOCK;
       if (gn > 2048) gn = 2048;
       G10_HIP(hipMemsetAsync(&w->ctl->n_live, 0, sizeof(u32), s));
-      hipLaunchKernelGGL(k_rescore, dim3(gn), dim3(G10_BLOCK), (size_t)N_ARR * (w->nch + 1) * 8, s, w->cd[x.cur], n,
-                         (const u64*)w->px, (const u64*)w->g_base, K, w->nch, w->shift_ch, (const Ctl*)w->ctl, posbits,
-                         w->keys, &w->ctl->n_live);
+      if (x.p->rank == G10_RANK_RATIO)
+        hipLaunchKernelGGL(k_rescore<true>, dim3(gn), dim3(G10_BLOCK), (size_t)N_ARR * (w->nch + 1) * 8, s, w->cd[x.cur], n,
+                           (const u64*)w->px, (const u64*)w->g_base, K, w->nch, w->shift_ch, (const Ctl*)w->ctl, posbits,
+                           w->keys, &w->ctl->n_live);
+      else
+        hipLaunchKernelGGL(k_rescore<false>, dim3(gn), dim3(G10_BLOCK), (size_t)N_ARR * (w->nch + 1) * 8, s, w->cd[x.cur], n,
+                           (const u64*)w->px, (const u64*)w->g_base, K, w->nch, w->shift_ch, (const Ctl*)w->ctl, posbits,
+                           w->keys, &w->ctl->n_live);
     }
     G10_HIP(hipGetLastError());
     u64 *keys = w->keys, *alt = w->keys_alt;
@@ -585,11 +618,13 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
   const bool timed_loop = n_active != 0;
   if (timed_loop) G10_HIP(hipEventRecord(I[0].w->ev[4], s));
   while (n_active) {
-    u32 na = 0;
+    u32 na = 0, n_by_rank[2] = {0, 0};
     size_t lds = 0;
-    for (u32 i = 0; i < count; ++i) {
+    for (u32 pass = 0; pass < 2 * count; ++pass) {         // the plans of one ranking key side by side: one kernel each
+      const u32 i = pass % count, rk = pass / count;
       Inst& x = I[i];
-      if (x.hc.done) continue;
+      if (x.hc.done || x.p->rank != rk) continue;
+      ++n_by_rank[rk];
       if (x.launches++ > x.max_launches) return G10_EDEVICE;
       PlanWork* w = x.w;
       LoopArgs& la = hargs[na++];
@@ -604,7 +639,8 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
       if (l > lds) lds = l;
     }
     G10_HIP(hipMemcpyAsync(h->loop_args, hargs, (size_t)na * sizeof(LoopArgs), hipMemcpyHostToDevice, s));
-    G10_TRY(loop_launch((const LoopArgs*)h->loop_args, na, lds, s));
+    if (n_by_rank[0]) G10_TRY(loop_launch((const LoopArgs*)h->loop_args, n_by_rank[0], lds, G10_RANK_BENEFIT, s));
+    if (n_by_rank[1]) G10_TRY(loop_launch((const LoopArgs*)h->loop_args + n_by_rank[0], n_by_rank[1], lds, G10_RANK_RATIO, s));
     for (u32 i = 0; i < count; ++i)
       if (!I[i].hc.done) G10_HIP(hipMemcpyAsync(&I[i].hc, I[i].w->ctl, sizeof(Ctl), hipMemcpyDeviceToHost, s));
     G10_HIP(hipStreamSynchronize(s));

@@ -25,7 +25,8 @@ constexpr u32 NT_MAX = 8192;           // tiles  (their bounds live in LDS)
 #ifndef G10_GUESS_SHIFT
 #define G10_GUESS_SHIFT 7
 #endif
-constexpr u32 GUESS_SHIFT = G10_GUESS_SHIFT;   // first threshold of a pass: last benefit * (1 - 2^-shift)
+constexpr u32 GUESS_SHIFT = G10_GUESS_SHIFT;   // first threshold of a pass: last benefit * (1 - 2^-shift), to begin with
+constexpr u32 GUESS_SHIFT_MAX = 24;            // the keys resolve no finer steps
 constexpr u64 NONE64 = ~0ull;
 constexpr u32 NONE32 = 0xffffffffu;
 
@@ -35,6 +36,7 @@ __device__ __forceinline__ u32 w_fi(u32 d) { return 4 + 2 * d; }      // word of
 struct Ctl {
   // parameters
   u64 gpu_cap, host_cap, bw_out[2], bw_in[2], max_iter;
+  u32 rank, pad0;             // G10_RANK_BENEFIT / G10_RANK_RATIO
   u64 inv_out[2], inv_in[2];  // floor(2^64 / bandwidth), 0 for bandwidth 1
   u64 C;                      // all inactive periods (live before any removal)
   // progress
@@ -43,6 +45,7 @@ struct Ctl {
   u64 overtime_before, overtime_after;
   u32 thr_key;                // first threshold of the next pass (0: use the largest tile bound)
   u32 n_live;                 // candidates that could still score at the last re-scoring
+  u32 gshift, pad1;           // the guess: first threshold = last best * (1 - 2^-gshift); 0 stands for GUESS_SHIFT
   // statistics
   u64 units_scored, second_rounds, jobs_run, launches;
   u64 phase[12];              // wall-clock ticks per phase of the loop (only with G10_PHASE_TIMERS)
@@ -108,9 +111,70 @@ __device__ __forceinline__ u64 ceil_div_x1000(u64 s, u64 bw, u64 inv) {
 }
 
 // ---------------------------------------------------------------------------
+// ranking by benefit / cost (the alternative key of Section 4.3): exact comparison of the
+// fractions by cross multiplication; 31-bit keys from a double approximation with a margin,
+// one that is never below the key of the true ratio and one that is never above it
+// ---------------------------------------------------------------------------
+struct U192 { u64 w2, w1, w0; };
+__device__ __forceinline__ U192 mul_128_64(u64 hi, u64 lo, u64 y) {
+  U192 r;
+  r.w0 = lo * y;
+  const u64 c0 = __umul64hi(lo, y), m = hi * y;
+  r.w1 = m + c0;
+  r.w2 = __umul64hi(hi, y) + (r.w1 < m ? 1ull : 0ull);
+  return r;
+}
+// sign of  B1 / c1 - B2 / c2  (costs > 0)
+__device__ __forceinline__ int cmp_ratio(u64 h1, u64 l1, u64 c1, u64 h2, u64 l2, u64 c2) {
+  const U192 p = mul_128_64(h1, l1, c2), q = mul_128_64(h2, l2, c1);
+  if (p.w2 != q.w2) return p.w2 > q.w2 ? 1 : -1;
+  if (p.w1 != q.w1) return p.w1 > q.w1 ? 1 : -1;
+  if (p.w0 != q.w0) return p.w0 > q.w0 ? 1 : -1;
+  return 0;
+}
+// B / cost to a relative error far below 2^-40 (five roundings of 2^-53 each)
+__device__ __forceinline__ double ratio_approx(u64 hi, u64 lo, u64 cost) {
+  return __fma_rn((double)hi, 18446744073709551616.0, (double)lo) / (double)cost;
+}
+// floor key of a positive double: 7 bits of exponent (values from 2^-20 up; 0 below), 24 bits
+// of mantissa; monotone non-decreasing
+__device__ __forceinline__ u32 rkey_floor(double r) {
+  const long long bits = __double_as_longlong(r);
+  const int e = (int)(bits >> 52) - 1023 + 21;
+  if (e < 1) return 0u;
+  if (e > 126) return (126u << 24) | 0xffffffu;
+  return ((u32)e << 24) | (u32)((bits >> 28) & 0xffffffll);
+}
+// never below the floor key of the true ratio, and at least 1: the bound side
+__device__ __forceinline__ u32 rkey_up(double r) { return rkey_floor(r * (1.0 + 0x1p-40)) + 1u; }
+// never above the floor key of the true ratio: the side of the best candidate found
+__device__ __forceinline__ u32 rkey_dn(double r) { return rkey_floor(r * (1.0 - 0x1p-40)); }
+
+// the ranking key of a benefit (and, for the ratio, the cost that divides it)
+template <bool RATIO>
+__device__ __forceinline__ u32 key_up_of(u64 hi, u64 lo, u64 cost) {
+  if (!RATIO) return upkey(hi, lo);
+  return (hi | lo) ? rkey_up(ratio_approx(hi, lo, cost)) : 0u;
+}
+template <bool RATIO>
+__device__ __forceinline__ u32 key_dn_of(u64 hi, u64 lo, u64 cost) {
+  if (!RATIO) return upkey(hi, lo);
+  return (hi | lo) ? rkey_dn(ratio_approx(hi, lo, cost)) : 0u;
+}
+
+// ---------------------------------------------------------------------------
 // score of one candidate against the current timelines
 // ---------------------------------------------------------------------------
-struct Machine { u64 bwo0, bwo1, bwi0, bwi1; };
+struct Machine {
+  u64 bwo0, bwo1, bwi0, bwi1;
+  u64 ivo0, ivo1, ivi0, ivi1;  // reciprocals (only the ratio ranking needs every candidate's transfer times)
+};
+
+// eviction + prefetch time of a tensor per destination
+__device__ __forceinline__ void costs_of(const Machine& mc, u64 s, u64& c0, u64& c1) {
+  c0 = ceil_div_x1000(s, mc.bwo0, mc.ivo0) + ceil_div_x1000(s, mc.bwi0, mc.ivi0);
+  c1 = ceil_div_x1000(s, mc.bwo1, mc.ivo1) + ceil_div_x1000(s, mc.bwi1, mc.ivi1);
+}
 
 struct PrefixView {           // slot records in HBM / L2, level 1 in LDS
   const u64* px;
@@ -220,6 +284,11 @@ __device__ __forceinline__ bool better(u64 hi, u64 lo, u32 cand, u64 bhi, u64 bl
   if (lo != blo) return lo > blo;
   return cand < bcand;
 }
+// the same for benefit / cost; "nothing yet" is benefit 0 with cost 1
+__device__ __forceinline__ bool better_ratio(u64 hi, u64 lo, u64 cost, u32 cand, u64 bhi, u64 blo, u64 bcost, u32 bcand) {
+  const int c = cmp_ratio(hi, lo, cost, bhi, blo, bcost);
+  return c ? c > 0 : cand < bcand;
+}
 
 // covered slots of chunk c by the doubled range [x, y] (x <= y, y - x < K): the chunk's slots
 // appear at [s0, s1] and at [s0 + K, s1 + K] in doubled coordinates
@@ -303,4 +372,4 @@ struct PlanWork {
 // the loop kernel (g10_loop.hip)
 size_t loop_lds_bytes(u32 nch, u32 nt);                       // dynamic LDS of one workgroup
 int loop_allow_large_lds();                                   // more than 64 KB of LDS for the kernel
-int loop_launch(const g10::LoopArgs* plans, u32 n_plans, size_t lds, hipStream_t s);
+int loop_launch(const g10::LoopArgs* plans, u32 n_plans, size_t lds, u32 rank, hipStream_t s);   // all of one ranking key

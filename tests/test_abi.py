@@ -31,7 +31,7 @@ def test_library_exports_every_declared_symbol():
 def test_struct_layouts_match_the_header():
     # sizes follow from the field lists in the header (natural alignment)
     assert ctypes.sizeof(binding._Trace) == 64
-    assert ctypes.sizeof(binding._Params) == 72
+    assert ctypes.sizeof(binding._Params) == 80
     assert ctypes.sizeof(binding._Stats) == 32
     assert ctypes.sizeof(binding._Result) == 8 + 8 * 8 + 3 * 8 + 9 * 8
     assert ctypes.sizeof(binding._PrefetchResult) == 4 * 8 + 4 * 8 + 8
