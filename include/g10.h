@@ -70,6 +70,7 @@ typedef struct {
 } g10_vitality_stats;
 
 enum { G10_RANK_BENEFIT = 0, G10_RANK_RATIO = 1 };
+enum { G10_AREA_BAND = 0, G10_AREA_CLIPPED = 1 };
 
 /* Inputs of Algorithm 1 beyond the periods: the GPU memory capacity, the host
  * memory that may hold evicted tensors, and the bandwidths from which eviction
@@ -100,7 +101,14 @@ typedef struct {
                                 periods are ranked by benefit / (eviction time + prefetch time) of the
                                 destination the policy picks, the benefit-cost ratio of Section 4.3's
                                 example, compared exactly as fractions; ties to the lowest period index   */
-  uint32_t reserved;         /* must be 0                                                                */
+  uint32_t area;             /* G10_AREA_BAND (0): the benefit is size x time over capacity inside the
+                                absent window, the tensor's whole band; G10_AREA_CLIPPED: the area between
+                                the pressure curve and the capacity line that the eviction removes, per
+                                slot duration x min(size, pressure - capacity).  The clipped area is
+                                evaluated lazily: candidates are ranked by bounds (the band, or an area
+                                computed in an earlier pass) and only the best by bound is summed exactly,
+                                so the plan is exact and the cost stays near the default's while the
+                                pressure is far above the capacity                                        */
 } g10_params;
 
 /* One migration, i.e. one g10_pre_evict / g10_prefetch pair of Section 4.4's
@@ -152,6 +160,8 @@ typedef struct {
   uint64_t loop_cands_scored;  /* candidates re-scored inside the loop (tiles * 256)   */
   uint64_t loop_second_rounds; /* passes that needed a second scoring round            */
   uint64_t loop_chunk_jobs;    /* timeline chunks rewritten slot by slot               */
+  uint64_t loop_area_evals;    /* G10_AREA_CLIPPED: clipped areas summed exactly       */
+  uint64_t loop_area_refused;  /* ... of which came out below the bound (ranked again) */
 } g10_result;
 
 typedef struct g10_plan_s g10_plan_t;   /* opaque: device copy of the analysis + workspaces */
@@ -185,7 +195,7 @@ int g10_vitality_read(const g10_plan_t *handle, int which, void *dst, uint64_t b
  * channel timelines, arg-max with lowest-index tie-break, commit and range
  * updates - runs on the device.  May be called repeatedly with different
  * parameters; the analysis is never modified.  Synchronises the stream.
- * Errors: G10_EINVAL (NULL, zero bandwidth, a zero in dur_ns, unknown rank, reserved != 0), G10_EOVERFLOW (sum of dur_ns
+ * Errors: G10_EINVAL (NULL, zero bandwidth, a zero in dur_ns, unknown rank or area), G10_EOVERFLOW (sum of dur_ns
  * >= 2^62), G10_ENOMEM, G10_EDEVICE.  Not
  * getting under capacity is not an error: status = G10_RESIDUAL. */
 int g10_plan(g10_plan_t *handle, const g10_params *params, g10_result *out);

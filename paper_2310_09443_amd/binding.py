@@ -51,7 +51,7 @@ class _Params(C.Structure):
     _fields_ = [("gpu_cap_bytes", C.c_uint64), ("host_cap_bytes", C.c_uint64),
                 ("bw_out_Bpus", C.c_uint64 * 2), ("bw_in_Bpus", C.c_uint64 * 2),
                 ("max_iterations", C.c_uint64), ("max_tiles", C.c_uint32), ("max_chunks", C.c_uint32),
-                ("dur_ns", C.c_void_p), ("rank", C.c_uint32), ("reserved", C.c_uint32)]
+                ("dur_ns", C.c_void_p), ("rank", C.c_uint32), ("area", C.c_uint32)]
 
 
 class _Result(C.Structure):
@@ -63,7 +63,8 @@ class _Result(C.Structure):
                 ("plan_ms", C.c_double), ("score_full_ms", C.c_double), ("score_full_cands", C.c_uint64),
                 ("loop_ms", C.c_double), ("loop_launches", C.c_uint64), ("loop_retiles", C.c_uint64),
                 ("loop_cands_scored", C.c_uint64),
-                ("loop_second_rounds", C.c_uint64), ("loop_chunk_jobs", C.c_uint64)]
+                ("loop_second_rounds", C.c_uint64), ("loop_chunk_jobs", C.c_uint64),
+                ("loop_area_evals", C.c_uint64), ("loop_area_refused", C.c_uint64)]
 
 
 class _PrefetchResult(C.Structure):
@@ -183,14 +184,14 @@ class Handle:
     start = property(lambda self: self.read(5))
     pressure = property(lambda self: self.read(6))
 
-    def _fill(self, p, gpu_cap, host_cap, bw_out, bw_in, max_iters=0, max_tiles=0, max_chunks=0, dur=None, rank=0):
+    def _fill(self, p, gpu_cap, host_cap, bw_out, bw_in, max_iters=0, max_tiles=0, max_chunks=0, dur=None, rank=0, area=0):
         """dur: None, or a device tensor of K 64-bit durations (ns) that replace the trace's for this plan."""
         p.gpu_cap_bytes, p.host_cap_bytes = int(gpu_cap), int(host_cap)
         p.bw_out_Bpus[0], p.bw_out_Bpus[1] = int(bw_out[0]), int(bw_out[1])
         p.bw_in_Bpus[0], p.bw_in_Bpus[1] = int(bw_in[0]), int(bw_in[1])
         p.max_iterations = int(max_iters)
         p.max_tiles, p.max_chunks = int(max_tiles), int(max_chunks)
-        p.rank, p.reserved = int(rank), 0
+        p.rank, p.area = int(rank), int(area)
         if dur is None:
             p.dur_ns = None
         else:
@@ -212,10 +213,10 @@ class Handle:
             raise G10Error(rc, "g10_plan_batch")
         return [Result(r, self.K) for r in rs]
 
-    def plan(self, gpu_cap, host_cap, bw_out, bw_in, max_iters=0, max_tiles=0, max_chunks=0, dur=None, rank=0) -> Result:
+    def plan(self, gpu_cap, host_cap, bw_out, bw_in, max_iters=0, max_tiles=0, max_chunks=0, dur=None, rank=0, area=0) -> Result:
         import torch
         p = _Params()
-        self._fill(p, gpu_cap, host_cap, bw_out, bw_in, max_iters, max_tiles, max_chunks, dur, rank)
+        self._fill(p, gpu_cap, host_cap, bw_out, bw_in, max_iters, max_tiles, max_chunks, dur, rank, area)
         r = _Result()
         with torch.cuda.device(self._dev):
             rc = load().g10_plan(self._h, C.byref(p), C.byref(r))
@@ -248,8 +249,8 @@ def g10_vitality(dtrace: DeviceTrace, no_wrap: bool = False, stream=None) -> Han
     return Handle(dtrace, no_wrap, stream)
 
 
-def g10_plan(handle: Handle, gpu_cap, host_cap, bw_out, bw_in, max_iters=0, max_tiles=0, max_chunks=0, dur=None, rank=0) -> Result:
-    return handle.plan(gpu_cap, host_cap, bw_out, bw_in, max_iters, max_tiles, max_chunks, dur, rank)
+def g10_plan(handle: Handle, gpu_cap, host_cap, bw_out, bw_in, max_iters=0, max_tiles=0, max_chunks=0, dur=None, rank=0, area=0) -> Result:
+    return handle.plan(gpu_cap, host_cap, bw_out, bw_in, max_iters, max_tiles, max_chunks, dur, rank, area)
 
 
 def g10_plan_batch(handle: Handle, param_dicts):

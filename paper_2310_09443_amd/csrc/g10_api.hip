@@ -69,7 +69,7 @@ extern "C" int g10_plan(g10_plan_t* h, const g10_params* p, g10_result* out) {
   if (!h || !p || !out) return G10_EINVAL;
   for (int d = 0; d < 2; ++d)
     if (!p->bw_out_Bpus[d] || !p->bw_in_Bpus[d]) return G10_EINVAL;
-  if (p->rank > G10_RANK_RATIO || p->reserved) return G10_EINVAL;
+  if (p->rank > G10_RANK_RATIO || p->area > G10_AREA_CLIPPED) return G10_EINVAL;
   const int rc = plan_run(h, p, out);
   if (rc) {
     (void)hipStreamSynchronize(h->stream);
@@ -84,7 +84,7 @@ extern "C" int g10_plan_batch(g10_plan_t* h, const g10_params* params, uint32_t 
   for (uint32_t i = 0; i < count; ++i) {
     for (int d = 0; d < 2; ++d)
       if (!params[i].bw_out_Bpus[d] || !params[i].bw_in_Bpus[d]) return G10_EINVAL;
-    if (params[i].rank > G10_RANK_RATIO || params[i].reserved) return G10_EINVAL;
+    if (params[i].rank > G10_RANK_RATIO || params[i].area > G10_AREA_CLIPPED) return G10_EINVAL;
   }
   const int rc = plan_batch_run(h, params, count, outs);
   if (rc) {

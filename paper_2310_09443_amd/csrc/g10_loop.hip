@@ -20,6 +20,7 @@ struct Winner {               // what a commit needs of the winning candidate
   u64 cost;                   // eviction + prefetch time (ranking by benefit / cost only)
   u64 s, fo_base, fi_end;     // size; free out-channel time before L1; free in-channel time before R
   u32 cand, tensor, pos, dest, L1, R, a, b;
+  u32 exact, pad;             // clipped-area benefit only: the value was computed in this pass (else it is a bound)
 };
 
 struct Shared {               // small per-pass state of the loop workgroup
@@ -27,6 +28,8 @@ struct Shared {               // small per-pass state of the loop workgroup
   Winner wave_win[LW];        // best of every wavefront
   u64 tau_o, tau_i;
   u64 hq;                     // host-capacity query: maximum over the period
+  u64 acc[3];                 // clipped area being summed: bits 0..31, 32..63 and 64.. of the terms, added apart
+  u64 evals, refused;         // clipped areas computed; of those, how many came out below the bound
   u32 nl, restL;              // hot list: length; bound of the tiles outside it
   u32 ntl, filt;              // current round: tiles to score; bound of the hot tiles left out
   u32 njobs, ot_changed, stale_hot, pad1;
@@ -93,7 +96,7 @@ __device__ __forceinline__ u32 best_lane(u64 hi, u64 lo, u64 cost, u32 cand) {
   return wave_best_lane(hi, lo, cand);
 }
 
-template <bool RATIO>
+template <bool RATIO, bool CLIP>
 __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans) {
   extern __shared__ __align__(16) unsigned char smem[];
   const LoopArgs a = plans[blockIdx.x];        // one workgroup per plan
@@ -127,7 +130,7 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
   for (u32 i = tid; i < ns; i += LB) smark[i] = 0;
   if (tid == 0) {
     S->n_iter = ctl->n_iter; S->n_mig = ctl->n_mig; S->n_drop = ctl->n_drop; S->n_evals = ctl->n_evals;
-    S->units = 0; S->second = 0; S->jobs = 0;
+    S->units = 0; S->second = 0; S->jobs = 0; S->evals = 0; S->refused = 0;
     S->thr_key = ctl->thr_key; S->status = ctl->status; S->done = ctl->done;
     S->gshift = ctl->gshift ? ctl->gshift : GUESS_SHIFT;
     S->nl = 0; S->restL = NONE32; S->stale_hot = 0;
@@ -243,7 +246,8 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
   u32 pass_units = 0;           // units of 256 candidates scored in the current pass (the same in every thread)
   // this thread's best candidate of the pass
   Winner mine;
-  mine.hi = 0; mine.lo = 0; mine.cost = 1; mine.cand = NONE32;
+  mine.hi = 0; mine.lo = 0; mine.cost = 1; mine.cand = NONE32; mine.exact = 0;
+  u32 cur_iter = 0;             // number of the current pass (the stamp of the values computed in it)
 
   struct CandV { uint4 A, B; uint2 id; u32 p, t; };
   auto load_cand = [&](u32 u) -> CandV {
@@ -281,26 +285,39 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
         if (lane == 0) { atomicAdd((unsigned long long*)&S->phase[9], (unsigned long long)nl); atomicAdd((unsigned long long*)&S->phase[10], (unsigned long long)nd); }
       }
 #endif
+      u32 exact = 0;
+      Score rr = r;
+      if (CLIP && (rr.ok0 || rr.ok1)) {          // the band bounds the area; a value computed earlier bounds it closer
+        const uint2 e = a.cd.ce[cur.p];
+        if (e.y & 1u) {
+          const uint4 v = a.cd.cv[cur.p];
+          const u64 vlo = ((u64)v.y << 32) | v.x, vhi = ((u64)v.w << 32) | v.z;
+          const u32 vd = (e.y >> 1) & 1u, pd = rr.ok0 ? 0u : 1u;
+          if (vd == 0u && rr.ok0 && gt128(rr.h0, rr.l0, vhi, vlo)) { rr.h0 = vhi; rr.l0 = vlo; }
+          if (vd == 1u && rr.ok1 && gt128(rr.h1, rr.l1, vhi, vlo)) { rr.h1 = vhi; rr.l1 = vlo; }
+          exact = (vd == pd && e.x == cur_iter) ? 1u : 0u;
+        }
+      }
       u64 c0 = 1, c1 = 1;
       u32 kc;                                    // bound of the candidate: the larger of its destinations' keys
       if (RATIO) {
-        if (r.ok0 || r.ok1) costs_of(mc, ((u64)B.w << 32) | B.z, c0, c1);
-        const u32 k0 = key_up_of<true>(r.h0, r.l0, c0), k1 = key_up_of<true>(r.h1, r.l1, c1);
+        if (rr.ok0 || rr.ok1) costs_of(mc, ((u64)B.w << 32) | B.z, c0, c1);
+        const u32 k0 = key_up_of<true>(rr.h0, rr.l0, c0), k1 = key_up_of<true>(rr.h1, rr.l1, c1);
         kc = k0 > k1 ? k0 : k1;
       } else {
-        const bool one = gt128(r.h1, r.l1, r.h0, r.l0);
-        kc = upkey(one ? r.h1 : r.h0, one ? r.l1 : r.l0);
+        const bool one = gt128(rr.h1, rr.l1, rr.h0, rr.l0);
+        kc = upkey(one ? rr.h1 : rr.h0, one ? rr.l1 : rr.l0);
       }
       const u32 k = wave_max(kc);
       if (lane == 0 && k) atomicMax(&keys[cur.t], k);
-      if (r.ok0 || r.ok1) {                      // flash first; host only if flash cannot take it
-        const u32 d = r.ok0 ? 0u : 1u;
-        const u64 hi = d ? r.h1 : r.h0, lo = d ? r.l1 : r.l0, cost = d ? c1 : c0;
+      if (rr.ok0 || rr.ok1) {                      // flash first; host only if flash cannot take it
+        const u32 d = rr.ok0 ? 0u : 1u;
+        const u64 hi = d ? rr.h1 : rr.h0, lo = d ? rr.l1 : rr.l0, cost = d ? c1 : c0;
         if ((hi | lo) != 0 && (RATIO ? better_ratio(hi, lo, cost, cur.id.x, mine.hi, mine.lo, mine.cost, mine.cand)
                                      : better(hi, lo, cur.id.x, mine.hi, mine.lo, mine.cand))) {
           mine.hi = hi; mine.lo = lo; mine.cost = cost; mine.cand = cur.id.x; mine.tensor = cur.id.y; mine.pos = cur.p; mine.dest = d;
           mine.L1 = A.x; mine.R = A.y; mine.a = d ? B.x : A.z; mine.b = d ? B.y : A.w; mine.s = ((u64)B.w << 32) | B.z;
-          mine.fo_base = r.fo_L; mine.fi_end = r.fi_R;
+          mine.fo_base = rr.fo_L; mine.fi_end = rr.fi_R; mine.exact = exact;
         }
       }
       u = un;
@@ -453,6 +470,33 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
           }
           if (lane == 0) { tot[(u64)A_OT * nch + c] = carry; S->ot_changed = 1; }
         }
+      } else if (type == J_CLIP) {
+        // clipped area of the winner's absent window inside this chunk: per slot over the
+        // capacity, duration x min(size, excess)
+        const u64 lz = lazyP[c];
+        u64 alo = 0, ahi = 0;
+        for (u32 st = 0; st < tl.spt; ++st) {
+          const u32 j0 = s0 + st * 256u + lane * 4u;
+#pragma unroll
+          for (u32 i = 0; i < 4; ++i) {
+            const u32 j = j0 + i;
+            if (j < K && in_doubled(j, K, wa, wb) != NONE32) {
+              const u64 act = tl.P[j] - lz;
+              if (act > cap) {
+                const u64 e = act - cap, m = e < s ? e : s, dj = tl.dur[j];
+                const u64 plo = dj * m;
+                ahi += __umul64hi(dj, m) + (alo + plo < alo ? 1ull : 0ull);
+                alo += plo;
+              }
+            }
+          }
+        }
+        const u64 p0 = wave_sum(alo & 0xffffffffull), p1 = wave_sum(alo >> 32), p2 = wave_sum(ahi);
+        if (lane == 0) {
+          atomicAdd((unsigned long long*)&S->acc[0], (unsigned long long)p0);
+          atomicAdd((unsigned long long*)&S->acc[1], (unsigned long long)p1);
+          atomicAdd((unsigned long long*)&S->acc[2], (unsigned long long)p2);
+        }
       } else {                                     // J_H: add the tensor; J_HQ: only ask for the maximum
         const u64 lz = lazyH[c];
         u64 m_all = 0, m_cov = 0;
@@ -478,6 +522,80 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
     if (tid == 0) S->jobs += nj;
   };
 
+  // Clipped-area benefit: the ranking above went by bounds (the tensor's band, or a value
+  // computed in an earlier pass: both can only be too large).  The best by bound stands only
+  // with a value computed in this pass.  Otherwise its area is computed here - whole chunks
+  // of its window in which every slot over the capacity exceeds it by the tensor's size count
+  // size x over-capacity time, the others are summed slot by slot - and if it comes out below
+  // the bound it is remembered with the candidate and the tiles scored in this pass are
+  // ranked again.  Returns true when the winner stands (or nothing is left), false when
+  // tiles left out could now hold a better one: `thr` is then the threshold to go on with.
+  auto settle = [&](u32& thr) -> bool {
+    while (true) {
+      __syncthreads();
+      if ((S->win.hi | S->win.lo) == 0 || S->win.exact) return true;
+      const u32 wa = S->win.a, wb = S->win.b;
+      const u64 s = S->win.s;
+      if (tid == 0) { S->acc[0] = 0; S->acc[1] = 0; S->acc[2] = 0; S->njobs = 0; }
+      __syncthreads();
+      if (tid < nch) {
+        u32 len = 0;
+        const u32 cv = cover(tid, CH, K, wa, wb, len);
+        if (cv) {
+          const u64 mo = minOver[tid];
+          if (cv == len && mo == NONE64) {
+            // no slot of the chunk is over the capacity
+          } else if (cv == len && mo - cap >= s) {
+            const u64 t = tot[(u64)A_OT * nch + tid], lo = s * t;
+            atomicAdd((unsigned long long*)&S->acc[0], (unsigned long long)(lo & 0xffffffffull));
+            atomicAdd((unsigned long long*)&S->acc[1], (unsigned long long)(lo >> 32));
+            atomicAdd((unsigned long long*)&S->acc[2], (unsigned long long)__umul64hi(s, t));
+          } else {
+            jobs[atomicAdd(&S->njobs, 1u)] = ((u32)J_CLIP << 16) | tid;
+          }
+        }
+      }
+      __syncthreads();
+      run_jobs();
+      __syncthreads();
+      const u64 a0 = S->acc[0], a1 = S->acc[1], a2 = S->acc[2];
+      const u64 vlo = a0 + (a1 << 32), vhi = a2 + (a1 >> 32) + (vlo < a0 ? 1ull : 0ull);
+      const bool same = vhi == S->win.hi && vlo == S->win.lo;
+      __syncthreads();                                   // everyone has read the sums and the bound
+      if (tid == 0) {
+        S->evals += 1;
+        S->njobs = 0;
+        if (same) S->win.exact = 1;
+        else {
+          S->refused += 1;
+          a.cd.cv[S->win.pos] = make_uint4((u32)vlo, (u32)(vlo >> 32), (u32)vhi, (u32)(vhi >> 32));
+          a.cd.ce[S->win.pos] = make_uint2(cur_iter, 1u | (S->win.dest << 1));
+          S->ntl = 0;
+        }
+      }
+      __syncthreads();
+      if (same) return true;
+      for (u32 g = tid; g < ns; g += LB) {               // every tile scored in this pass, once more
+        u64 m = smark[g];
+        while (m) {
+          const u32 t = g * 64 + (u32)__builtin_ctzll(m);
+          m &= m - 1;
+          alist[atomicAdd(&S->ntl, 1u)] = (unsigned short)t;
+          keys[t] = 0;
+        }
+      }
+      __syncthreads();
+      mine.hi = 0; mine.lo = 0; mine.cost = 1; mine.cand = NONE32; mine.exact = 0;
+      score_list();
+      reduce_best();
+      const u32 rest = S->restL > S->filt ? S->restL : S->filt;
+      const u32 kb = key_dn_of<RATIO>(S->win.hi, S->win.lo, S->win.cost);
+      if (rest < (kb ? kb : 1u)) continue;
+      thr = kb ? kb : (rest > (1u << 19) ? rest - (1u << 19) : 1u);
+      return false;
+    }
+  };
+
   __syncthreads();
   // ---- passes ------------------------------------------------------------------------
   u32 passes = 0;
@@ -487,7 +605,7 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
     if (max_iter && S->n_iter >= max_iter) { if (tid == 0) { S->done = 1; S->status = G10_TRUNCATED; } break; }
     if (passes >= a.pass_budget || S->stop) break;
     ++passes;
-    mine.hi = 0; mine.lo = 0; mine.cost = 1; mine.cand = NONE32;
+    mine.hi = 0; mine.lo = 0; mine.cost = 1; mine.cand = NONE32; mine.exact = 0;
     pass_units = 0;
     u32 thr = S->thr_key ? S->thr_key : NONE32;
     __syncthreads();                               // the loop conditions and thr are read
@@ -500,6 +618,7 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
       if (a.tick_budget && wall_clock64() - S->t_start > a.tick_budget) S->stop = 1;
     }
     __syncthreads();
+    cur_iter = (u32)S->n_iter;
 
     // rank: score the hot tiles whose bound reaches a threshold (first a guess a little under
     // the last benefit), lower the threshold to the best benefit found, repeat until no tile
@@ -515,7 +634,11 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
       activate(thr);
       const u32 ntl = S->ntl, rest = S->restL > S->filt ? S->restL : S->filt;
       if (ntl == 0) {
-        if ((rounds && (S->win.hi | S->win.lo) != 0) || rest == 0) break;      // nothing left that could win
+        if ((rounds && (S->win.hi | S->win.lo) != 0) || rest == 0) {           // nothing left that could win
+          if (!CLIP || settle(thr)) break;
+          __syncthreads();
+          continue;
+        }
         thr = rest;                                      // strictly lower than before: start from the largest bound left
         __syncthreads();
         continue;
@@ -528,7 +651,12 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
       ++rounds;
       const u32 kb = key_dn_of<RATIO>(S->win.hi, S->win.lo, S->win.cost);
       const u32 need = kb ? kb : 1u;
-      if (rest < need) break;                            // every tile left out is below the best found
+      if (rest < need) {                                 // every tile left out is below the best found
+        if (!CLIP || settle(thr)) break;
+        if (tid == 0) S->second += 1;
+        __syncthreads();
+        continue;
+      }
       // a tile left out may hold an equal or better one; with nothing found yet, step down a few percent
       thr = kb ? kb : (rest > (1u << 19) ? rest - (1u << 19) : 1u);
       if (tid == 0) S->second += 1;
@@ -668,6 +796,7 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
     ctl->overtime_after = base[(u64)A_OT * nb1 + nch];
     for (u32 i = 0; i < 12; ++i) ctl->phase[i] += S->phase[i];
     ctl->units_scored += S->units; ctl->second_rounds += S->second; ctl->jobs_run += S->jobs; ctl->launches += 1;
+    ctl->area_evals += S->evals; ctl->area_refused += S->refused;
   }
 }
 
@@ -682,15 +811,21 @@ size_t loop_lds_bytes(u32 nch, u32 nt) {
   return (b + 15) & ~(size_t)15;
 }
 
+typedef void (*LoopKernel)(const LoopArgs*);
+static LoopKernel loop_kernel(u32 rank, u32 area) {
+  if (area == G10_AREA_CLIPPED) return rank == G10_RANK_RATIO ? k_loop<true, true> : k_loop<false, true>;
+  return rank == G10_RANK_RATIO ? k_loop<true, false> : k_loop<false, false>;
+}
+
 int loop_allow_large_lds() {
-  G10_HIP(hipFuncSetAttribute((const void*)k_loop<false>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-  G10_HIP(hipFuncSetAttribute((const void*)k_loop<true>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+  for (u32 rank = 0; rank < 2; ++rank)
+    for (u32 area = 0; area < 2; ++area)
+      G10_HIP(hipFuncSetAttribute((const void*)loop_kernel(rank, area), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
   return G10_OK;
 }
 
-int loop_launch(const LoopArgs* plans, u32 n_plans, size_t lds, u32 rank, hipStream_t s) {
-  if (rank == G10_RANK_RATIO) hipLaunchKernelGGL(k_loop<true>, dim3(n_plans), dim3(LB), lds, s, plans);
-  else hipLaunchKernelGGL(k_loop<false>, dim3(n_plans), dim3(LB), lds, s, plans);
+int loop_launch(const LoopArgs* plans, u32 n_plans, size_t lds, u32 rank, u32 area, hipStream_t s) {
+  hipLaunchKernelGGL(loop_kernel(rank, area), dim3(n_plans), dim3(LB), lds, s, plans);
   G10_HIP(hipGetLastError());
   return G10_OK;
 }

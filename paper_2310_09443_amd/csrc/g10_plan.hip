@@ -106,6 +106,7 @@ __global__ __launch_bounds__(G10_BLOCK) void k_pack(const uint4* __restrict__ pe
   out.A[o] = make_uint4(pd.x + 1, pd.y, w.x, w.y);
   out.B[o] = make_uint4(w.z, w.w, (u32)s, (u32)(s >> 32));
   out.id[o] = make_uint2(pd.w, pd.z);
+  if (out.ce) out.ce[o] = make_uint2(0u, 0u);        // no value of the clipped area yet
 }
 
 // ---------------------------------------------------------------------------
@@ -256,11 +257,17 @@ __global__ __launch_bounds__(G10_BLOCK) void k_tile_gather(const u64* __restrict
     dst.A[r] = src.A[p];
     dst.B[r] = src.B[p];
     dst.id[r] = src.id[p];
+    if (src.ce) {
+      const uint2 e = src.ce[p];
+      dst.ce[r] = e;
+      if (e.y & 1u) dst.cv[r] = src.cv[p];
+    }
     k = bound_of_sort_key(sk, posbits);
   } else {                                       // padding of the last tile: no valid window
     dst.A[r] = make_uint4(0u, 0u, 1u, 0u);
     dst.B[r] = make_uint4(1u, 0u, 0u, 0u);
     dst.id[r] = make_uint2(NONE32, 0u);
+    if (dst.ce) dst.ce[r] = make_uint2(0u, 0u);
   }
   k = wave_max(k);
   if (lane_id() == 0 && k) atomicMax(&tkeys[r >> tile_shift], k);
@@ -370,7 +377,10 @@ static void work_layout(PlanWork* w, Arena& ar) {
   ar.take(&w->scratch32, scan_scratch_elems(he > C ? he : C));
   ar.take(&w->keys, C); ar.take(&w->keys_alt, C);
   ar.take(&w->tkeys, (u64)NT_MAX);
-  for (int i = 0; i < 2; ++i) { ar.take(&w->cd[i].A, w->cap_pad); ar.take(&w->cd[i].B, w->cap_pad); ar.take(&w->cd[i].id, w->cap_pad); }
+  for (int i = 0; i < 2; ++i) {
+    ar.take(&w->cd[i].A, w->cap_pad); ar.take(&w->cd[i].B, w->cap_pad); ar.take(&w->cd[i].id, w->cap_pad);
+    if (w->has_cache) { ar.take(&w->cd[i].cv, w->cap_pad); ar.take(&w->cd[i].ce, w->cap_pad); }
+  }
   ar.take(&w->P, K); ar.take(&w->fre, (u64)4 * w->Kp); ar.take(&w->H, K);
   ar.take(&w->px, (u64)PX * K); ar.take(&w->otc, (u64)K + 1);
   ar.take(&w->base0, (u64)w->nch + 1);
@@ -393,7 +403,7 @@ static void work_layout(PlanWork* w, Arena& ar) {
   ar.take(&w->times_scratch, scan_scratch_elems(K)); ar.take(&w->times_stats, 16);
 }
 
-static int work_alloc(g10_plan_s* h, u32 max_chunks, PlanWork** slot) {
+static int work_alloc(g10_plan_s* h, u32 max_chunks, bool cache, PlanWork** slot) {
   PlanWork* w = new (std::nothrow) PlanWork();
   if (!w) return G10_ENOMEM;
   *slot = w;
@@ -403,6 +413,7 @@ static int work_alloc(g10_plan_s* h, u32 max_chunks, PlanWork** slot) {
   w->Kp = (K + 3u) & ~3u;
   w->spt = 1; w->shift_ch = 8;
   w->max_chunks = max_chunks;
+  w->has_cache = cache;
   while ((u64)G10_BLOCK * w->spt * max_chunks < K) { w->spt *= 2; w->shift_ch += 1; }
   const u32 ch = G10_BLOCK * w->spt;
   w->nch = (K + ch - 1) / ch;
@@ -471,13 +482,16 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     const g10_params* p = params + i;
     const u32 max_chunks = clamp_limit(p->max_chunks, NCH_MAX);
     PlanWork** slot = work_slot(h, i);
-    if (*slot && (*slot)->max_chunks != max_chunks) {      // another chunk size: lay the workspaces out again
+    bool cache = p->area == G10_AREA_CLIPPED;
+    if (*slot && ((*slot)->max_chunks != max_chunks || (cache && !(*slot)->has_cache))) {
+      // another chunk size, or the first plan with clipped areas: lay the workspaces out again
+      cache = cache || (*slot)->has_cache;
       G10_HIP(hipStreamSynchronize(s));
       plan_work_free(*slot);
       *slot = nullptr;
     }
     if (!*slot) {
-      int rc = work_alloc(h, max_chunks, slot);
+      int rc = work_alloc(h, max_chunks, cache, slot);
       if (rc) { plan_work_free(*slot); *slot = nullptr; return rc; }
     }
     I[i].w = *slot; I[i].p = p; I[i].max_tiles = clamp_limit(p->max_tiles, NT_MAX);
@@ -520,7 +534,7 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
       hc.inv_in[d] = hc.bw_in[d] > 1 ? (u64)((((unsigned __int128)1) << 64) / hc.bw_in[d]) : 0;
     }
     hc.max_iter = p->max_iterations;
-    hc.rank = p->rank;
+    hc.rank = p->rank; hc.area = p->area;
     hc.C = C;
     G10_HIP(hipMemcpyAsync(w->ctl, &hc, sizeof hc, hipMemcpyHostToDevice, s));
     Timelines& tl = x.tl;
@@ -542,6 +556,13 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     G10_HIP(hipMemcpyAsync(&hc, w->ctl, sizeof hc, hipMemcpyDeviceToHost, s));
   }
   G10_HIP(hipStreamSynchronize(s));
+
+  // the candidate buffers of a plan; the value cache only where the plan reads the benefit as the clipped area
+  auto cands_of = [](const Inst& x, int which) {
+    Cands c = x.w->cd[which];
+    if (x.p->area != G10_AREA_CLIPPED) { c.cv = nullptr; c.ce = nullptr; }
+    return c;
+  };
 
   // candidates of plan x into score order, in tiles
   auto retile = [&](Inst& x, bool first) -> int {
@@ -580,7 +601,7 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     G10_TRY(radix_sort_u64(&keys, &alt, n, posbits + 23, w->hist, w->scratch32, s));
     G10_HIP(hipMemsetAsync(w->tkeys, 0, (u64)NT_MAX * 4, s));
     hipLaunchKernelGGL(k_tile_gather, dim3(x.n_pad / G10_BLOCK), dim3(G10_BLOCK), 0, s, (const u64*)keys, n, x.n_pad, posbits,
-                       w->cd[x.cur], w->cd[x.cur ^ 1], 8 + x.tsh, w->tkeys);
+                       cands_of(x, x.cur), cands_of(x, x.cur ^ 1), 8 + x.tsh, w->tkeys);
     G10_HIP(hipGetLastError());
     x.cur ^= 1;
     return G10_OK;
@@ -598,7 +619,7 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     ++n_active;
     if (x.n) {
       hipLaunchKernelGGL(k_pack, dim3(gC), dim3(G10_BLOCK), 0, s, (const uint4*)h->per_by_start, (const u64*)h->per_size, (const uint4*)x.w->win,
-                         (const u32*)x.w->keep, C, x.w->cd[x.cur]);
+                         (const u32*)x.w->keep, C, cands_of(x, x.cur));
       G10_HIP(hipGetLastError());
     }
     G10_TRY(retile(x, true));
@@ -618,13 +639,13 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
   const bool timed_loop = n_active != 0;
   if (timed_loop) G10_HIP(hipEventRecord(I[0].w->ev[4], s));
   while (n_active) {
-    u32 na = 0, n_by_rank[2] = {0, 0};
+    u32 na = 0, n_by_kind[4] = {0, 0, 0, 0};
     size_t lds = 0;
-    for (u32 pass = 0; pass < 2 * count; ++pass) {         // the plans of one ranking key side by side: one kernel each
-      const u32 i = pass % count, rk = pass / count;
+    for (u32 pass = 0; pass < 4 * count; ++pass) {         // the plans of one ranking key and benefit reading side by side: one kernel each
+      const u32 i = pass % count, kind = pass / count;
       Inst& x = I[i];
-      if (x.hc.done || x.p->rank != rk) continue;
-      ++n_by_rank[rk];
+      if (x.hc.done || 2 * x.p->area + x.p->rank != kind) continue;
+      ++n_by_kind[kind];
       if (x.launches++ > x.max_launches) return G10_EDEVICE;
       PlanWork* w = x.w;
       LoopArgs& la = hargs[na++];
@@ -632,15 +653,15 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
       la.g_tot = w->g_tot; la.g_lazyP = w->g_lazyP; la.g_minOver = w->g_minOver; la.g_lazyH = w->g_lazyH; la.g_hmax = w->g_hmax;
       la.g_base = w->g_base;
       la.g_keys = w->tkeys; la.ctl = w->ctl; la.records = w->records; la.rec_ab = w->rec_ab; la.dropped = w->dropped;
-      la.cd = w->cd[x.cur]; la.n_pad = x.n_pad; la.nt = x.nt; la.tshift = x.tsh;
+      la.cd = cands_of(x, x.cur); la.n_pad = x.n_pad; la.nt = x.nt; la.tshift = x.tsh;
       la.pass_budget = x.n > RETILE_MIN_CANDS && count == 1 ? RETILE_PASSES : PASS_BUDGET;
       la.tick_budget = count > 1 ? BATCH_LAUNCH_TICKS : 0;
       const size_t l = loop_lds_bytes(w->nch, x.nt);
       if (l > lds) lds = l;
     }
     G10_HIP(hipMemcpyAsync(h->loop_args, hargs, (size_t)na * sizeof(LoopArgs), hipMemcpyHostToDevice, s));
-    if (n_by_rank[0]) G10_TRY(loop_launch((const LoopArgs*)h->loop_args, n_by_rank[0], lds, G10_RANK_BENEFIT, s));
-    if (n_by_rank[1]) G10_TRY(loop_launch((const LoopArgs*)h->loop_args + n_by_rank[0], n_by_rank[1], lds, G10_RANK_RATIO, s));
+    for (u32 kind = 0, first = 0; kind < 4; first += n_by_kind[kind], ++kind)
+      if (n_by_kind[kind]) G10_TRY(loop_launch((const LoopArgs*)h->loop_args + first, n_by_kind[kind], lds, kind & 1u, kind >> 1, s));
     for (u32 i = 0; i < count; ++i)
       if (!I[i].hc.done) G10_HIP(hipMemcpyAsync(&I[i].hc, I[i].w->ctl, sizeof(Ctl), hipMemcpyDeviceToHost, s));
     G10_HIP(hipStreamSynchronize(s));
@@ -705,6 +726,7 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     out->score_full_ms = full_ms; out->score_full_cands = x.n_valid;
     out->loop_ms = loop_ms; out->loop_launches = hc.launches; out->loop_retiles = x.retiles;
     out->loop_cands_scored = hc.units_scored * UNIT; out->loop_second_rounds = hc.second_rounds; out->loop_chunk_jobs = hc.jobs_run;
+    out->loop_area_evals = hc.area_evals; out->loop_area_refused = hc.area_refused;
   }
   return G10_OK;
 }

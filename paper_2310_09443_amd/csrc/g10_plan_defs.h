@@ -12,7 +12,7 @@
 namespace g10 {
 
 enum { A_OT = 0, A_FO = 1, A_FI = 3, N_ARR = 5, PX = 8 };
-enum { J_FO = 0, J_FI = 1, J_P_PART = 2, J_P_FULL = 3, J_H = 4, J_HQ = 5 };
+enum { J_FO = 0, J_FI = 1, J_P_PART = 2, J_P_FULL = 3, J_H = 4, J_HQ = 5, J_CLIP = 6 };
 
 #ifndef G10_LOOP_THREADS
 #define G10_LOOP_THREADS 512
@@ -36,7 +36,7 @@ __device__ __forceinline__ u32 w_fi(u32 d) { return 4 + 2 * d; }      // word of
 struct Ctl {
   // parameters
   u64 gpu_cap, host_cap, bw_out[2], bw_in[2], max_iter;
-  u32 rank, pad0;             // G10_RANK_BENEFIT / G10_RANK_RATIO
+  u32 rank, area;             // G10_RANK_BENEFIT / G10_RANK_RATIO; G10_AREA_BAND / G10_AREA_CLIPPED
   u64 inv_out[2], inv_in[2];  // floor(2^64 / bandwidth), 0 for bandwidth 1
   u64 C;                      // all inactive periods (live before any removal)
   // progress
@@ -48,6 +48,7 @@ struct Ctl {
   u32 gshift, pad1;           // the guess: first threshold = last best * (1 - 2^-gshift); 0 stands for GUESS_SHIFT
   // statistics
   u64 units_scored, second_rounds, jobs_run, launches;
+  u64 area_evals, area_refused;   // clipped areas computed in the loop; of those, how many came out below the bound
   u64 phase[12];              // wall-clock ticks per phase of the loop (only with G10_PHASE_TIMERS)
 };
 
@@ -55,6 +56,10 @@ struct Cands {
   uint4* A;                   // {L1, R, a0, b0}     a > b: no valid window for that destination
   uint4* B;                   // {a1, b1, size lo, size hi}
   uint2* id;                  // {index of the period in the analysis order (the tie-break), tensor}
+  // Only for the clipped-area benefit (else null): the last exact value of the candidate, an
+  // upper bound of every later one since the pressure only falls.
+  uint4* cv;                  // the value, 128 bits, least significant word first
+  uint2* ce;                  // {pass in which it was computed, bit 0: there is a value, bit 1: its destination}
 };
 
 struct Timelines {
@@ -367,9 +372,10 @@ struct PlanWork {
   hipEvent_t ev[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
   void* arena = nullptr;        // the one device allocation all pointers above point into
   u32 max_chunks = 0;           // the chunk limit the timelines were laid out for
+  bool has_cache = false;       // the candidate buffers have the cv / ce arrays
 };
 
 // the loop kernel (g10_loop.hip)
 size_t loop_lds_bytes(u32 nch, u32 nt);                       // dynamic LDS of one workgroup
 int loop_allow_large_lds();                                   // more than 64 KB of LDS for the kernel
-int loop_launch(const g10::LoopArgs* plans, u32 n_plans, size_t lds, u32 rank, hipStream_t s);   // all of one ranking key
+int loop_launch(const g10::LoopArgs* plans, u32 n_plans, size_t lds, u32 rank, u32 area, hipStream_t s);   // all of one ranking key and benefit reading

@@ -154,43 +154,38 @@ class Replay:
         return dest, ot
 
     def best(self):
-        """(cand, dest, exact benefit) of the argmax, ties to the lowest index."""
+        """(cand, dest, exact benefit) of the argmax, ties to the lowest index.
+
+        The band (size x over-capacity time) is computed for every candidate at once; it equals the
+        benefit (area="band") or bounds it (area="clipped").  Candidates are then looked at in the
+        order of that bound, each evaluated exactly from the definitions, until no candidate left
+        could reach the best exact key found."""
         from fractions import Fraction
         dest, ot = self.score_all()
         s = self.pb.per_s
-        approx = s.astype(np.float64) * ot.astype(np.float64)       # the band: also an upper bound of the clipped area
-        if approx.size == 0 or approx.max() <= 0:
+        bound = s.astype(np.float64) * ot.astype(np.float64)
+        if bound.size == 0 or bound.max() <= 0:
             return -1, -1, 0
-        if self.m.area == "clipped":                                 # exact areas of everything that has a band at all
-            cand = np.flatnonzero(approx > 0)
-            exact_b = {int(i): self.benefit(int(i), int(dest[i])) for i in cand}
-            approx = np.zeros_like(approx)
-            for i, v in exact_b.items():
-                approx[i] = float(v)
-        else:
-            exact_b = None
-        cost = np.ones(len(s), np.float64)
         if self.m.rank == "ratio":
+            cost = np.ones(len(s), np.float64)
             for d in (FLASH, HOST):
                 cost = np.where(dest == d, (self.tau_o[d] + self.tau_i[d]).astype(np.float64), cost)
-        key = approx / cost
-        if key.max() <= 0:
-            return -1, -1, 0
-        near = np.flatnonzero(key >= key.max() * (1.0 - 1e-9))
-
-        def exact(i):
+            bound = bound / cost
+        best = None                                            # (key, cand, benefit)
+        for i in np.argsort(-bound, kind="stable"):
             i = int(i)
-            B = exact_b[i] if exact_b is not None else int(s[i]) * int(ot[i])
-            if self.m.rank == "ratio":
-                d = int(dest[i])
-                return B, Fraction(B, int(self.tau_o[d][i]) + int(self.tau_i[d][i]))
-            return B, B
-
-        vals = [exact(i) for i in near]
-        mx = max(v[1] for v in vals)
-        j = [v[1] for v in vals].index(mx)
-        c = int(near[j])
-        return c, int(dest[c]), vals[j][0]
+            if bound[i] <= 0:
+                break
+            if best is not None and bound[i] < float(best[0]) * (1.0 - 1e-9):
+                break
+            d = int(dest[i])
+            B = self.benefit(i, d) if self.m.area == "clipped" else int(s[i]) * int(ot[i])
+            key = Fraction(B, int(self.tau_o[d][i]) + int(self.tau_i[d][i])) if self.m.rank == "ratio" else Fraction(B)
+            if best is None or key > best[0] or (key == best[0] and i < best[1]):
+                best = (key, i, B)
+        if best is None or best[2] == 0:
+            return -1, -1, 0
+        return best[1], int(dest[best[1]]), best[2]
 
     # ---- one candidate, straight from the definitions -----------------------
     def feasible(self, c, d):

@@ -1,5 +1,6 @@
-"""Parity of the HIP library against the CPU oracle for the alternative ranking key of
-Section 4.3 (benefit / cost), through the C ABI.  Every comparison is exact."""
+"""Parity of the HIP library against the CPU oracle for the two alternative readings of
+Section 4.3 (ranking by benefit / cost; the benefit as the area removed above the capacity
+line) and their combination, through the C ABI.  Every comparison is exact."""
 import numpy as np
 import pytest
 
@@ -11,99 +12,133 @@ from test_gpu_parity import assert_plan_equal, assert_prefetch_equal, g10, run_b
 
 pytestmark = pytest.mark.gpu
 
-RATIO = dict(rank=1)
+VARIANTS = [dict(rank=1, area=0), dict(rank=0, area=1), dict(rank=1, area=1)]
+IDS = ["ratio", "clipped", "ratio+clipped"]
+var = pytest.mark.parametrize("va", VARIANTS, ids=IDS)
 
 
-def test_worked_example_ratio(g10):
-    g = Golden("hand_plan_ratio.txt")
+@pytest.mark.parametrize("name", ["hand_plan_ratio.txt", "hand_plan_clipped.txt"])
+def test_worked_examples(g10, name):
+    g = Golden(name)
+    va = g.variant_args()
     v = O.Vitality(g.trace, O.DIRECT)
     h = g10.g10_vitality(g10.DeviceTrace(g.trace))
-    r = h.plan(rank=g.params["rank"], **g.plan_args())
+    r = h.plan(**g.plan_args(), **va)
     fields = ["cand", "tensor", "evict_after", "absent_first", "absent_last", "next_use", "dest", "wraps", "size", "t_out", "t_in"]
     got = [[int(x[f]) for f in fields] + [int(x["benefit_lo"]) + (int(x["benefit_hi"]) << 64)] for x in r.records]
     assert got == g.expect["record"]                    # the values derived by hand, directly
     assert r.pressure_after.tolist() == g.expect["pressure_after"][0]
     assert (r.status, r.n_iterations, r.n_cand_evals) == (g.expect["status"][0][0], g.expect["iterations"][0][0], g.expect["evals"][0][0])
-    assert_plan_equal(r, v.plan(rank=1, **g.plan_args()))
-    assert_plan_equal(h.plan(**g.plan_args()), v.plan(**g.plan_args()))     # and the default key on the same handle
+    assert_plan_equal(r, v.plan(**g.plan_args(), **va))
+    assert_plan_equal(h.plan(**g.plan_args()), v.plan(**g.plan_args()))     # and the default reading on the same handle
     h.close()
 
 
 @pytest.mark.parametrize("seed", range(40))
-def test_random_small_ratio(g10, seed):
+def test_random_small(g10, seed):
     w = traces.random_small(7000 + seed, K=6 + seed % 20, N=4 + seed % 13, max_uses=5)
     h, v, args = run_both(g10, w, no_wrap=seed % 4 == 0)
-    for a in (args, dict(args, gpu_cap=int(args["gpu_cap"] * 1.3)), dict(args, bw_out=(1, 3), bw_in=(2, 1))):
-        p = v.plan(mode=O.DIRECT, rank=1, **a)
-        assert_plan_equal(h.plan(rank=1, **a), p)
-        assert_prefetch_equal(h.prefetch(), p.prefetch(O.DIRECT))
+    for va in VARIANTS:
+        for a in (args, dict(args, gpu_cap=int(v.peak * 0.9)), dict(args, bw_out=(1, 3), bw_in=(2, 1))):
+            p = v.plan(mode=O.DIRECT, **a, **va)
+            assert_plan_equal(h.plan(**a, **va), p)
+            assert_prefetch_equal(h.prefetch(), p.prefetch(O.DIRECT))
     h.close()
 
 
+@var
 @pytest.mark.parametrize("cfg", [1, 2, 3, 4])
-def test_configs_ratio(g10, cfg):
+def test_configs(g10, cfg, va):
     w = traces.config(cfg)
     h, v, args = run_both(g10, w)
-    p = v.plan(rank=1, **args)
-    r = h.plan(rank=1, **args)
-    assert_plan_equal(r, p)
-    assert_prefetch_equal(h.prefetch(), p.prefetch())
-    base = v.plan(**args)
-    assert_plan_equal(h.plan(**args), base)                       # the default key again on the same handle
-    assert r.records.tobytes() != base.records.tobytes()          # the key matters on these traces
+    # the oracle sums clipped areas slot by slot for every candidate in every pass: whole plans
+    # only where that takes seconds, a prefix on the two larger traces
+    limit = 0 if (va["area"] == 0 or cfg <= 2) else (150 if cfg == 3 else 12)
+    p = v.plan(max_iters=limit if limit else 2 ** 64 - 1, **args, **va)
+    r = h.plan(max_iters=limit, **args, **va)
+    if limit:
+        assert r.status == g10.TRUNCATED == p.status and r.n_iterations == limit
+        assert_plan_equal(r, p, prefix=True)
+        assert (r.pressure_after == p.pressure_after).all()
+    else:
+        assert_plan_equal(r, p)
+        assert_prefetch_equal(h.prefetch(), p.prefetch())
+        base = v.plan(**args)
+        assert_plan_equal(h.plan(**args), base)                   # the default reading again on the same handle
+        assert r.records.tobytes() != base.records.tobytes()      # the reading matters on these traces
     h.close()
 
 
+@var
 @pytest.mark.parametrize("K,N,seed", [(257, 3000, 1), (2048, 20000, 2), (5000, 60000, 3), (300, 100000, 4)])
-def test_stress_scaled_ratio(g10, K, N, seed):
+def test_stress_scaled(g10, K, N, seed, va):
     w = traces.stress(K=K, N=N, seed=seed)
     h, v, args = run_both(g10, w)
-    assert_plan_equal(h.plan(rank=1, **args), v.plan(rank=1, **args))
+    slow = va["area"] == 1 and K * N > 10 ** 7        # the oracle's slot-by-slot areas: a prefix there
+    limit = 40 if slow else 0
+    p = v.plan(max_iters=limit if limit else 2 ** 64 - 1, **args, **va)
+    r = h.plan(max_iters=limit, **args, **va)
+    assert_plan_equal(r, p, prefix=bool(limit))
+    # a capacity that can be reached: ends with FITS, and most excesses are smaller than the tensors
     args2 = dict(args, gpu_cap=int(v.peak * 0.97), host_cap=2 ** 62)
-    p2 = v.plan(rank=1, **args2)
-    assert_plan_equal(h.plan(rank=1, **args2), p2)
-    assert_prefetch_equal(h.prefetch(), p2.prefetch())
+    limit2 = 300 if (slow and va["rank"] == 1) else 0     # the ratio key makes many more (small) migrations
+    p2 = v.plan(max_iters=limit2 if limit2 else 2 ** 64 - 1, **args2, **va)
+    r2 = h.plan(max_iters=limit2, **args2, **va)
+    assert_plan_equal(r2, p2, prefix=bool(limit2))
+    if not limit2:
+        assert_prefetch_equal(h.prefetch(), p2.prefetch())
+    if va["area"] == 1:
+        assert r2.loop_area_evals >= r2.n_iterations - 1
     h.close()
 
 
+@var
 @pytest.mark.parametrize("max_tiles,max_chunks", [(1, 1), (3, 2), (16, 5)])
-def test_tile_and_chunk_limits_ratio(g10, max_tiles, max_chunks):
+def test_tile_and_chunk_limits(g10, max_tiles, max_chunks, va):
     w = traces.stress(K=2048, N=20000, seed=2)
     h, v, args = run_both(g10, w)
-    assert_plan_equal(h.plan(rank=1, max_tiles=max_tiles, max_chunks=max_chunks, **args), v.plan(rank=1, **args))
+    args = dict(args, gpu_cap=int(v.peak * 0.9))
+    assert_plan_equal(h.plan(max_tiles=max_tiles, max_chunks=max_chunks, **args, **va), v.plan(**args, **va))
     h.close()
 
 
-def test_tight_host_memory_ratio(g10):
+@var
+def test_tight_host_memory(g10, va):
     w = traces.stress(K=3000, N=30000, seed=7)
     h, v, args = run_both(g10, w)
     args = dict(args, host_cap=int(v.peak * 0.002), bw_out=(50, 25000), bw_in=(50, 25000))
-    p = v.plan(rank=1, **args)
-    r = h.plan(rank=1, **args)
-    assert_plan_equal(r, p)
-    assert r.n_dropped > 0
+    limit = 150 if va["area"] == 1 else 0              # the oracle's slot-by-slot areas take 0.1 s per pass here
+    p = v.plan(max_iters=limit if limit else 2 ** 64 - 1, **args, **va)
+    r = h.plan(max_iters=limit, **args, **va)
+    assert_plan_equal(r, p, prefix=bool(limit))
+    assert r.n_dropped > 0 or va == dict(rank=1, area=1)      # (that one drops its first candidate after pass 150)
+    if limit:
+        assert (r.n_dropped, r.n_iterations) == (p.n_null, limit) and (r.null_cands == p.null_cands).all()
     h.close()
 
 
-def test_batch_mixes_ranking_keys(g10):
+def test_batch_mixes_readings(g10):
     w = traces.stress(K=2048, N=20000, seed=2)
     h, v, args = run_both(g10, w)
     sweep = []
     for i, frac in enumerate((0.25, 0.4, 0.6, 0.8, 0.95)):
-        sweep.append(dict(args, gpu_cap=int(v.peak * frac), rank=i % 2))
-        sweep.append(dict(args, gpu_cap=int(v.peak * frac), rank=1 - i % 2))
+        sweep.append(dict(args, gpu_cap=int(v.peak * frac), rank=i % 2, area=(i // 2) % 2, max_iters=150))
+        sweep.append(dict(args, gpu_cap=int(v.peak * frac), rank=1 - i % 2, area=1 - (i // 2) % 2, max_iters=150))
     rs = h.plan_batch(sweep)
     for d, r in zip(sweep, rs):
-        assert_plan_equal(r, v.plan(**d))
+        p = v.plan(**d)
+        assert_plan_equal(r, p, prefix=p.status == O.TRUNCATED)
+        assert (r.status, r.n_iterations) == (p.status, p.n_iterations) and (r.pressure_after == p.pressure_after).all()
     h.close()
 
 
-def test_unknown_key_is_an_error(g10):
+def test_unknown_reading_is_an_error(g10):
     w = traces.mlp_tiny()
     h, v, args = run_both(g10, w)
-    with pytest.raises(g10.G10Error) as e:
-        h.plan(rank=2, **args)
-    assert e.value.code == g10.EINVAL
+    for bad in (dict(rank=2), dict(area=2)):
+        with pytest.raises(g10.G10Error) as e:
+            h.plan(**args, **bad)
+        assert e.value.code == g10.EINVAL
     h.close()
 
 
