@@ -522,78 +522,69 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
     if (tid == 0) S->jobs += nj;
   };
 
-  // Clipped-area benefit: the ranking above went by bounds (the tensor's band, or a value
-  // computed in an earlier pass: both can only be too large).  The best by bound stands only
-  // with a value computed in this pass.  Otherwise its area is computed here - whole chunks
-  // of its window in which every slot over the capacity exceeds it by the tensor's size count
-  // size x over-capacity time, the others are summed slot by slot - and if it comes out below
-  // the bound it is remembered with the candidate and the tiles scored in this pass are
-  // ranked again.  Returns true when the winner stands (or nothing is left), false when
-  // tiles left out could now hold a better one: `thr` is then the threshold to go on with.
-  auto settle = [&](u32& thr) -> bool {
-    while (true) {
-      __syncthreads();
-      if ((S->win.hi | S->win.lo) == 0 || S->win.exact) return true;
-      const u32 wa = S->win.a, wb = S->win.b;
-      const u64 s = S->win.s;
-      if (tid == 0) { S->acc[0] = 0; S->acc[1] = 0; S->acc[2] = 0; S->njobs = 0; }
-      __syncthreads();
-      if (tid < nch) {
-        u32 len = 0;
-        const u32 cv = cover(tid, CH, K, wa, wb, len);
-        if (cv) {
-          const u64 mo = minOver[tid];
-          if (cv == len && mo == NONE64) {
-            // no slot of the chunk is over the capacity
-          } else if (cv == len && mo - cap >= s) {
-            const u64 t = tot[(u64)A_OT * nch + tid], lo = s * t;
-            atomicAdd((unsigned long long*)&S->acc[0], (unsigned long long)(lo & 0xffffffffull));
-            atomicAdd((unsigned long long*)&S->acc[1], (unsigned long long)(lo >> 32));
-            atomicAdd((unsigned long long*)&S->acc[2], (unsigned long long)__umul64hi(s, t));
-          } else {
-            jobs[atomicAdd(&S->njobs, 1u)] = ((u32)J_CLIP << 16) | tid;
-          }
+  // Clipped-area benefit: the ranking went by bounds (the tensor's band, or a value computed
+  // in an earlier pass: both can only be too large).  The best by bound stands only with a
+  // value computed in this pass.  Otherwise its area is computed here - whole chunks of its
+  // window in which every slot over the capacity exceeds it by the tensor's size count
+  // size x over-capacity time, the others are summed slot by slot.  Returns true when the
+  // winner stands (or nothing is left).  If the area comes out below the bound it is
+  // remembered with the candidate and false is returned: the tiles scored in this pass are
+  // then listed again (alist) and must be ranked once more.
+  auto settle = [&]() -> bool {
+    __syncthreads();
+    if ((S->win.hi | S->win.lo) == 0 || S->win.exact) return true;
+    const u32 wa = S->win.a, wb = S->win.b;
+    const u64 s = S->win.s;
+    if (tid == 0) { S->acc[0] = 0; S->acc[1] = 0; S->acc[2] = 0; S->njobs = 0; }
+    __syncthreads();
+    if (tid < nch) {
+      u32 len = 0;
+      const u32 cv = cover(tid, CH, K, wa, wb, len);
+      if (cv) {
+        const u64 mo = minOver[tid];
+        if (cv == len && mo == NONE64) {
+          // no slot of the chunk is over the capacity
+        } else if (cv == len && mo - cap >= s) {
+          const u64 t = tot[(u64)A_OT * nch + tid], lo = s * t;
+          atomicAdd((unsigned long long*)&S->acc[0], (unsigned long long)(lo & 0xffffffffull));
+          atomicAdd((unsigned long long*)&S->acc[1], (unsigned long long)(lo >> 32));
+          atomicAdd((unsigned long long*)&S->acc[2], (unsigned long long)__umul64hi(s, t));
+        } else {
+          jobs[atomicAdd(&S->njobs, 1u)] = ((u32)J_CLIP << 16) | tid;
         }
       }
-      __syncthreads();
-      run_jobs();
-      __syncthreads();
-      const u64 a0 = S->acc[0], a1 = S->acc[1], a2 = S->acc[2];
-      const u64 vlo = a0 + (a1 << 32), vhi = a2 + (a1 >> 32) + (vlo < a0 ? 1ull : 0ull);
-      const bool same = vhi == S->win.hi && vlo == S->win.lo;
-      __syncthreads();                                   // everyone has read the sums and the bound
-      if (tid == 0) {
-        S->evals += 1;
-        S->njobs = 0;
-        if (same) S->win.exact = 1;
-        else {
-          S->refused += 1;
-          a.cd.cv[S->win.pos] = make_uint4((u32)vlo, (u32)(vlo >> 32), (u32)vhi, (u32)(vhi >> 32));
-          a.cd.ce[S->win.pos] = make_uint2(cur_iter, 1u | (S->win.dest << 1));
-          S->ntl = 0;
-        }
-      }
-      __syncthreads();
-      if (same) return true;
-      for (u32 g = tid; g < ns; g += LB) {               // every tile scored in this pass, once more
-        u64 m = smark[g];
-        while (m) {
-          const u32 t = g * 64 + (u32)__builtin_ctzll(m);
-          m &= m - 1;
-          alist[atomicAdd(&S->ntl, 1u)] = (unsigned short)t;
-          keys[t] = 0;
-        }
-      }
-      __syncthreads();
-      mine.hi = 0; mine.lo = 0; mine.cost = 1; mine.cand = NONE32; mine.exact = 0;
-      score_list();
-      reduce_best();
-      const u32 rest = S->restL > S->filt ? S->restL : S->filt;
-      const u32 kb = key_dn_of<RATIO>(S->win.hi, S->win.lo, S->win.cost);
-      if (rest < (kb ? kb : 1u)) continue;
-      thr = kb ? kb : (rest > (1u << 19) ? rest - (1u << 19) : 1u);
-      return false;
     }
+    __syncthreads();
+    run_jobs();
+    __syncthreads();
+    const u64 a0 = S->acc[0], a1 = S->acc[1], a2 = S->acc[2];
+    const u64 vlo = a0 + (a1 << 32), vhi = a2 + (a1 >> 32) + (vlo < a0 ? 1ull : 0ull);
+    const bool same = vhi == S->win.hi && vlo == S->win.lo;
+    __syncthreads();                                   // everyone has read the sums and the bound
+    if (tid == 0) {
+      S->evals += 1;
+      S->njobs = 0;
+      if (same) S->win.exact = 1;
+      else {
+        S->refused += 1;
+        a.cd.cv[S->win.pos] = make_uint4((u32)vlo, (u32)(vlo >> 32), (u32)vhi, (u32)(vhi >> 32));
+        a.cd.ce[S->win.pos] = make_uint2(cur_iter, 1u | (S->win.dest << 1));
+        S->ntl = 0;
+      }
+    }
+    __syncthreads();
+    if (same) return true;
+    for (u32 g = tid; g < ns; g += LB) {               // every tile scored in this pass, once more
+      u64 m = smark[g];
+      while (m) {
+        const u32 t = g * 64 + (u32)__builtin_ctzll(m);
+        m &= m - 1;
+        alist[atomicAdd(&S->ntl, 1u)] = (unsigned short)t;
+        keys[t] = 0;
+      }
+    }
+    __syncthreads();
+    return false;
   };
 
   __syncthreads();
@@ -624,43 +615,53 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
     // the last benefit), lower the threshold to the best benefit found, repeat until no tile
     // left out could hold an equal or better candidate
     u32 rounds = 0;
+    bool again = false;                          // CLIP: the listed tiles are the ones already scored in this pass
     while (true) {
-      if (S->restL >= thr) {                       // the hot list may miss a tile that reaches thr: build it anew,
-        const u32 low = thr == NONE32 ? thr : (thr > (1u << 19) ? thr - (1u << 19) : 1u);   // a few percent lower to last a while
-        __syncthreads();
-        build_hot(low);
-        if (rounds && tid == 0) S->stale_hot = 1;  // built without the tiles already scored: not kept for the next pass
+      u32 rest;
+      bool decided = false;                      // the best by bound is known
+      if (!again) {
+        if (S->restL >= thr) {                     // the hot list may miss a tile that reaches thr: build it anew,
+          const u32 low = thr == NONE32 ? thr : (thr > (1u << 19) ? thr - (1u << 19) : 1u);   // a few percent lower to last a while
+          __syncthreads();
+          build_hot(low);
+          if (rounds && tid == 0) S->stale_hot = 1;  // built without the tiles already scored: not kept for the next pass
+        }
+        activate(thr);
+        const u32 ntl = S->ntl;
+        rest = S->restL > S->filt ? S->restL : S->filt;
+        if (ntl == 0) {
+          if ((rounds && (S->win.hi | S->win.lo) != 0) || rest == 0) decided = true;   // nothing left that could win
+          else {
+            thr = rest;                                  // strictly lower than before: start from the largest bound left
+            __syncthreads();
+            continue;
+          }
+        }
+      } else {
+        again = false;
+        rest = S->restL > S->filt ? S->restL : S->filt;
+        mine.hi = 0; mine.lo = 0; mine.cost = 1; mine.cand = NONE32; mine.exact = 0;
       }
-      activate(thr);
-      const u32 ntl = S->ntl, rest = S->restL > S->filt ? S->restL : S->filt;
-      if (ntl == 0) {
-        if ((rounds && (S->win.hi | S->win.lo) != 0) || rest == 0) {           // nothing left that could win
-          if (!CLIP || settle(thr)) break;
+      if (!decided) {
+        PHASE(0);
+        score_list();
+        PHASE(1);
+        reduce_best();
+        PHASE(2);
+        ++rounds;
+        const u32 kb = key_dn_of<RATIO>(S->win.hi, S->win.lo, S->win.cost);
+        const u32 need = kb ? kb : 1u;
+        if (rest < need) decided = true;                 // every tile left out is below the best found
+        else {
+          // a tile left out may hold an equal or better one; with nothing found yet, step down a few percent
+          thr = kb ? kb : (rest > (1u << 19) ? rest - (1u << 19) : 1u);
+          if (tid == 0) S->second += 1;
           __syncthreads();
           continue;
         }
-        thr = rest;                                      // strictly lower than before: start from the largest bound left
-        __syncthreads();
-        continue;
       }
-      PHASE(0);
-      score_list();
-      PHASE(1);
-      reduce_best();
-      PHASE(2);
-      ++rounds;
-      const u32 kb = key_dn_of<RATIO>(S->win.hi, S->win.lo, S->win.cost);
-      const u32 need = kb ? kb : 1u;
-      if (rest < need) {                                 // every tile left out is below the best found
-        if (!CLIP || settle(thr)) break;
-        if (tid == 0) S->second += 1;
-        __syncthreads();
-        continue;
-      }
-      // a tile left out may hold an equal or better one; with nothing found yet, step down a few percent
-      thr = kb ? kb : (rest > (1u << 19) ? rest - (1u << 19) : 1u);
-      if (tid == 0) S->second += 1;
-      __syncthreads();
+      if (!CLIP || settle()) break;
+      again = true;
     }
     PHASE(3);
 

@@ -99,6 +99,23 @@ def _ceil_div(x, y):
     return (x + (y - 1)) // y
 
 
+def _dot_exact(x, y):
+    """Sum of x[i] * y[i] as a Python int, for non-negative int64 arrays below 2^60 with fewer
+    than 2^22 elements: 20-bit limbs, so no partial sum leaves the int64 range."""
+    x, y = np.asarray(x, np.int64), np.asarray(y, np.int64)
+    assert len(x) < (1 << 22)
+    mask = (1 << 20) - 1
+    total = 0
+    for i in range(3):
+        xi = (x >> (20 * i)) & mask
+        if not xi.any():
+            continue
+        for j in range(3):
+            yj = (y >> (20 * j)) & mask
+            total += int(np.dot(xi, yj)) << (20 * (i + j))
+    return total
+
+
 class Replay:
     def __init__(self, pb: Problem, m: Machine):
         self.pb, self.m = pb, m
@@ -203,7 +220,7 @@ class Replay:
         size = int(self.pb.per_s[c])
         if self.m.area == "clipped":
             excess = np.clip(self.pressure[ab] - self.m.gpu_cap, 0, size)
-            return sum(int(x) * int(y) for x, y in zip(self.pb.dur[ab][excess > 0], excess[excess > 0]))
+            return _dot_exact(self.pb.dur[ab], excess)
         return size * int(self.pb.dur[ab][self.over()[ab]].sum())
 
     def host_room(self, c):

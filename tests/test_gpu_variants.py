@@ -161,3 +161,25 @@ def test_stress_full_size_ratio(g10):
     plancheck.check_plan(tr, m, r.records, r.null_iters, r.null_cands, r.status, greedy=sample, complete=False)
     assert h.plan(rank=1, max_iters=limit, **args).records.tobytes() == r.records.tobytes()
     h.close()
+
+
+def test_stress_full_size_clipped(g10):
+    """Config 5 at full size with the clipped-area benefit, whole plan.  The oracle needs minutes
+    per pass here (it sums every candidate's window slot by slot), so the plan is judged by the
+    independent checker: every record's area from the definition in the state before its commit,
+    windows, policy and channel rules, and the arg-max property on sampled passes (the checker
+    looks at candidates in the order of their band, which bounds the area)."""
+    w = traces.config(5)
+    tr = w.trace
+    h, v, args = run_both(g10, w)
+    r = h.plan(area=1, **args)
+    m = plancheck.Machine(args["gpu_cap"], args["host_cap"], args["bw_out"], args["bw_in"], area="clipped")
+    sample = sorted(set(np.linspace(0, r.n_iterations - 1, 30).astype(int).tolist()))
+    plancheck.check_plan(tr, m, r.records, r.null_iters, r.null_cands, r.status,
+                         pressure_after=r.pressure_after, n_iterations=r.n_iterations,
+                         n_cand_evals=r.n_cand_evals, greedy=sample)
+    assert r.loop_area_evals >= r.n_iterations - 1 and r.loop_area_refused > 0
+    base = h.plan(**args)
+    assert base.records.tobytes() != r.records.tobytes()       # the reading matters on this trace
+    assert h.plan(area=1, **args).records.tobytes() == r.records.tobytes()
+    h.close()
