@@ -192,6 +192,28 @@ def main():
                               "migrations": [int(x.n_migrations) for x in rn],
                               "share_of_exact_plan_kept": kept}
 
+    # the two alternative readings of Section 4.3 on the same trace (outside the timed step):
+    # the clipped-area benefit for the whole plan, the ratio key for its first 1000 passes (that
+    # key prefers small tensors, so its plan on this trace has 20x the migrations)
+    if nb > 1:
+        hv = binding.g10_vitality(dt)
+        base_args = dict(gpu_cap=cap, host_cap=hcap, bw_out=w.bw_out_Bpus, bw_in=w.bw_in_Bpus)
+        b0 = hv.plan(**base_args)
+        out["readings"] = {}
+        for name, va in (("clipped_area", dict(area=1)), ("ratio_key_first_1000_passes", dict(rank=1, max_iters=1000))):
+            hv.plan(**base_args, **va)
+            rv = hv.plan(**base_args, **va)
+            k = min(len(b0.records), len(rv.records))
+            same = b0.records["cand"][:k] == rv.records["cand"][:k]
+            common = len(set(b0.records["cand"].tolist()) & set(rv.records["cand"].tolist()))
+            out["readings"][name] = {"ms": rv.plan_ms, "passes": int(rv.n_iterations), "migrations": int(rv.n_migrations),
+                                     "us_per_pass": 1e3 * rv.loop_ms / max(int(rv.n_iterations), 1),
+                                     "cands_rescored_per_pass": rv.loop_cands_scored / max(int(rv.n_iterations), 1),
+                                     "areas_summed": int(rv.loop_area_evals), "areas_below_bound": int(rv.loop_area_refused),
+                                     "first_record_that_differs_from_default": int((~same).argmax()) if not same.all() else k,
+                                     "migrations_shared_with_default": common}
+        hv.close()
+
     if not a.no_cpu:
         from oracle import oracle as O
         t0 = time.perf_counter()
