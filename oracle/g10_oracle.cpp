@@ -60,6 +60,11 @@
 //     fractions; the default ranks by the benefit alone, as Algorithm 1 does.
 //     Ties go to the lowest period index either way.
 //
+// Beyond the paper's planner, replay() plays a finished plan back slot by slot under given
+// kernel durations (stall time, traffic per destination): a stand-in for the breakdown the
+// paper's simulator reports; its model is stated at the function.  parity unpinned against the
+// paper (which prints no such numbers for a trace we have); pinned as defined by tests/.
+//
 // Two evaluation modes compute the same values:
 //   mode 0 ("direct"):  every sum / max / search is the literal loop of its
 //                       definition over kernel slots.  O(window) per query.
@@ -530,6 +535,82 @@ int prefetch(Oracle& o, int mode) {
   return 0;
 }
 
+// ------------------------------------------------------------ plan replay
+// Not a step of the paper's planner: a slot-level replay of a finished plan, a small stand-in
+// for the breakdown the paper's simulator reports (stall time next to compute time, traffic per
+// destination; Sections 7.2-7.3), under kernel durations that may differ from the profiled ones
+// the plan was made for (Section 7.6).  The model:
+//   * kernels run in order; instructions sit between kernels (Figure 6): the eviction of a
+//     migration is issued when kernel `evict_after` has finished, its prefetch when the last
+//     absent kernel has finished (with smart prefetching: the earlier slot it was moved to);
+//   * every (destination, direction) pair is one channel that serves its transfers one after
+//     the other in the order they were issued (same instant: plan order); a transfer takes the
+//     eviction / prefetch time of the plan; a prefetch cannot start before its eviction is done;
+//   * a kernel starts when the previous one has finished and every prefetch whose tensor it
+//     uses is done; the time it waits beyond the previous kernel's end is stall time.
+// Two iterations are replayed end to end, every migration in both (a weight evicted in the
+// first comes back in the second); what is reported is the second one, the steady state.
+struct ReplayOut {
+  u64 iter_ns, planned_ns, stall_ns, n_stalled;
+  u64 bytes[2], busy_out_ns[2], busy_in_ns[2];
+};
+
+int replay(Oracle& o, const u64* dur_in, int eager, ReplayOut& R, std::vector<u64>& late) {
+  const u32 K = o.K;
+  const size_t n = o.records.size();
+  if (eager && o.pf_gained.size() != n) return -1;
+  std::vector<u64> dur(o.dur);
+  if (dur_in) {
+    u128 tot = 0;
+    for (u32 k = 0; k < K; ++k) { if (!dur_in[k]) return -1; dur[k] = dur_in[k]; tot += dur_in[k]; }
+    if (tot >> 62) return -2;
+  }
+  std::memset(&R, 0, sizeof R);
+  late.assign(n, 0);
+  // what happens at the point before kernel j (doubled coordinates, two iterations): (copy, record)
+  struct Ev { u32 copy, rec; };
+  std::vector<std::vector<Ev>> evict_at(2 * (size_t)K), fetch_at(2 * (size_t)K), use_at(2 * (size_t)K);
+  for (u32 c = 0; c < 2; ++c)
+    for (size_t i = 0; i < n; ++i) {
+      const u64 L = o.records[i].evict_after, b = o.rec_b[i], Ruse = o.rec_R[i];
+      const u64 issue = b + 1 - (eager ? o.pf_gained[i] : 0);
+      const u64 je = L + 1 + (u64)c * K, jf = issue + (u64)c * K, ju = Ruse + (u64)c * K;
+      if (je < 2 * (u64)K) evict_at[je].push_back(Ev{c, (u32)i});
+      if (jf < 2 * (u64)K) fetch_at[jf].push_back(Ev{c, (u32)i});
+      if (ju < 2 * (u64)K) use_at[ju].push_back(Ev{c, (u32)i});
+    }
+  std::vector<u64> E[2] = {std::vector<u64>(n, 0), std::vector<u64>(n, 0)}, F[2] = {std::vector<u64>(n, 0), std::vector<u64>(n, 0)};
+  u64 chan_out[2] = {0, 0}, chan_in[2] = {0, 0};
+  u64 done_prev = 0, end_first = 0;                  // end of the previous kernel; end of the first iteration
+  for (u64 j = 0; j < 2 * (u64)K; ++j) {
+    for (const Ev& e : evict_at[j]) {
+      const g10o_record& r = o.records[e.rec];
+      const u64 t = std::max(done_prev, chan_out[r.dest]) + r.t_out;
+      E[e.copy][e.rec] = t; chan_out[r.dest] = t;
+    }
+    for (const Ev& e : fetch_at[j]) {
+      const g10o_record& r = o.records[e.rec];
+      const u64 t = std::max(std::max(done_prev, E[e.copy][e.rec]), chan_in[r.dest]) + r.t_in;
+      F[e.copy][e.rec] = t; chan_in[r.dest] = t;
+    }
+    u64 start = done_prev;
+    for (const Ev& e : use_at[j]) {
+      start = std::max(start, F[e.copy][e.rec]);
+      if (j >= K && F[e.copy][e.rec] > done_prev) late[e.rec] = F[e.copy][e.rec] - done_prev;
+    }
+    if (j >= K && start > done_prev) { R.stall_ns += start - done_prev; ++R.n_stalled; }
+    done_prev = start + dur[j % K];
+    if (j == (u64)K - 1) end_first = done_prev;
+  }
+  R.iter_ns = done_prev - end_first;
+  for (u32 k = 0; k < K; ++k) R.planned_ns += dur[k];
+  for (size_t i = 0; i < n; ++i) {
+    const g10o_record& r = o.records[i];
+    R.bytes[r.dest] += r.size; R.busy_out_ns[r.dest] += r.t_out; R.busy_in_ns[r.dest] += r.t_in;
+  }
+  return 0;
+}
+
 template <class T>
 void copy_out(const std::vector<T>& v, void* dst) { if (!v.empty()) std::memcpy(dst, v.data(), v.size() * sizeof(T)); }
 
@@ -613,6 +694,23 @@ int g10o_windows(void* h, const g10o_params* pr, int mode, int dest,
 int g10o_prefetch(void* h, int mode) {
   if (!h) return -1;
   return prefetch(*(Oracle*)h, mode);
+}
+
+// replay of the plan made last; dur: K durations or NULL (the trace's); eager: use the prefetch
+// slots of g10o_prefetch (which must have run).  out[0..9]: iteration, planned, stall, stalled
+// kernels, bytes[2], busy out[2], busy in[2]; late: per record, how long its next use in the
+// second iteration waited for it beyond the end of the previous kernel
+int g10o_replay(void* h, const u64* dur, int eager, u64* out, u64* late) {
+  if (!h || !out) return -1;
+  Oracle& o = *(Oracle*)h;
+  ReplayOut R;
+  std::vector<u64> l;
+  const int rc = replay(o, dur, eager, R, l);
+  if (rc) return rc;
+  out[0] = R.iter_ns; out[1] = R.planned_ns; out[2] = R.stall_ns; out[3] = R.n_stalled;
+  for (int d = 0; d < 2; ++d) { out[4 + d] = R.bytes[d]; out[6 + d] = R.busy_out_ns[d]; out[8 + d] = R.busy_in_ns[d]; }
+  if (late) copy_out(l, late);
+  return 0;
 }
 
 void g10o_free(void* h) { delete (Oracle*)h; }

@@ -58,6 +58,7 @@ def lib():
                                    C.POINTER(_Summary)]
         _lib.g10o_windows.argtypes = [C.c_void_p, C.POINTER(_Params), C.c_int, C.c_int] + [C.c_void_p] * 5
         _lib.g10o_prefetch.argtypes = [C.c_void_p, C.c_int]
+        _lib.g10o_replay.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
         _lib.g10o_free.argtypes = [C.c_void_p]
         _lib.g10o_free.restype = None
     return _lib
@@ -179,7 +180,30 @@ class Prefetch:
         self.peak = int(self.pressure.max()) if v.K else 0
 
 
+class Replay:
+    """Slot-level replay of a plan (see g10_oracle.cpp): steady-state iteration time, stall time,
+    stalled kernels, traffic and channel time per destination, lateness per migration."""
+
+    def __init__(self, plan: "Plan", dur=None, eager=False):
+        v = plan._v
+        out = np.zeros(10, np.uint64)
+        self.late = np.zeros(len(plan.records), np.uint64)
+        d = None if dur is None else np.ascontiguousarray(dur, np.uint64)
+        assert d is None or d.shape[0] == v.K
+        rc = lib().g10o_replay(v._h, None if d is None else _ptr(d), int(eager), _ptr(out),
+                               _ptr(self.late) if len(self.late) else None)
+        if rc:
+            raise OracleError(rc)
+        o = [int(x) for x in out]
+        self.iter_ns, self.planned_ns, self.stall_ns, self.n_stalled = o[0], o[1], o[2], o[3]
+        self.bytes, self.busy_out_ns, self.busy_in_ns = o[4:6], o[6:8], o[8:10]
+
+
 class Plan:
+    def replay(self, dur=None, eager=False) -> "Replay":
+        """Must be called before the handle plans again (eager: after prefetch())."""
+        return Replay(self, dur, eager)
+
     def prefetch(self, mode=None) -> "Prefetch":
         """Must be called before the handle plans again."""
         return Prefetch(self, self._v.mode if mode is None else mode)
