@@ -149,9 +149,22 @@ def main():
     cap, hcap = traces.resolve_caps(w, hp.peak)
     hp.plan(cap, hcap, w.bw_out_Bpus, w.bw_in_Bpus)
     pf = [hp.prefetch() for _ in range(3)][-1]
-    hp.close()
     out["smart_prefetch"] = {"kernel": "k_eager", "ms": pf.ms, "migrations": pf.n_migrations, "moved": pf.n_moved,
                              "slots_gained": pf.slots_gained, "us_per_migration": 1e3 * pf.ms / max(pf.n_migrations, 1)}
+
+    # slot-level replay of that plan (one first-in-first-out channel per destination and direction):
+    # stall time as planned and with +-20 % kernel-time noise, each with the prefetches at their latest
+    # safe time and where smart prefetching moved them
+    noisy = torch.from_numpy(traces.noisy_durations(tr, 20.0, seed=2020).view(np.int64)).to(dev)
+    out["replay"] = {}
+    for name, d, eager in (("as_planned", None, False), ("as_planned_smart_prefetch", None, True),
+                           ("noise_20_percent", noisy, False), ("noise_20_percent_smart_prefetch", noisy, True)):
+        hp.replay(d, eager)
+        rr = hp.replay(d, eager)
+        out["replay"][name] = {"ms": rr.ms, "iter_ms": rr.iter_ns / 1e6, "stall_ms": rr.stall_ns / 1e6,
+                               "stalled_kernels": rr.n_stalled, "late_migrations": int((rr.late > 0).sum()),
+                               "GB_to_flash_host": [x / 1e9 for x in rr.bytes]}
+    hp.close()
 
     # a capacity sweep planned in one call (g10_plan_batch): the loops of the plans run side by side
     nb = a.batch

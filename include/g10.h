@@ -238,6 +238,36 @@ typedef struct {
  * Errors: G10_EINVAL (NULL, no plan on the handle), G10_ENOMEM, G10_EDEVICE. */
 int g10_prefetch(g10_plan_t *handle, g10_prefetch_result *out);
 
+/* Result of g10_replay; late_ns is host memory owned by the handle, valid until the next
+ * g10_plan / g10_replay on it or g10_plan_free. */
+typedef struct {
+  uint64_t iter_ns;             /* duration of the steady-state iteration               */
+  uint64_t planned_ns;          /* sum of the replayed kernel durations (no stall)      */
+  uint64_t stall_ns;            /* iter_ns - planned_ns: time kernels waited for prefetches */
+  uint64_t n_stalled;           /* kernels that waited                                  */
+  uint64_t bytes[2];            /* evicted (= prefetched) bytes per destination and iteration */
+  uint64_t busy_out_ns[2];      /* eviction time per destination                        */
+  uint64_t busy_in_ns[2];       /* prefetch time per destination                        */
+  uint64_t n_migrations;
+  const uint64_t *late_ns;      /* [n_migrations] how long the next use of each migration's tensor
+                                   waited for its prefetch beyond the end of the kernel before it */
+  double ms;                    /* device time of the call                              */
+} g10_replay_result;
+
+/* Slot-level replay of the plan the last g10_plan made on this handle: what would the
+ * iteration take if the kernels ran `dur_ns` long (device [K], each > 0; NULL = the durations
+ * the plan was made for) and the plan's transfers went through one first-in-first-out channel
+ * per destination and direction?  A stand-in for the time and traffic breakdown of the paper's
+ * simulator (evaluation, "End-to-end Performance" and "Impact of Profiling Errors"); not a step
+ * of the planner.  The eviction of a migration is issued when kernel evict_after has finished,
+ * its prefetch when kernel absent_last has finished - with `eager` != 0 at the slot g10_prefetch
+ * moved it to (g10_prefetch must have run on this plan) - and not before the eviction is done; a
+ * kernel waits until every prefetch of a tensor it uses is done.  Two iterations are replayed
+ * end to end; the figures are those of the second.  Synchronises the stream.
+ * Errors: G10_EINVAL (NULL, no plan, eager without g10_prefetch, a zero duration),
+ * G10_EOVERFLOW (durations sum to >= 2^62), G10_ENOMEM, G10_EDEVICE. */
+int g10_replay(g10_plan_t *handle, const uint64_t *dur_ns, uint32_t eager, g10_replay_result *out);
+
 /* Frees everything the library allocated for the handle.  NULL is allowed. */
 void g10_plan_free(g10_plan_t *handle);
 

@@ -579,6 +579,11 @@ int replay(Oracle& o, const u64* dur_in, int eager, ReplayOut& R, std::vector<u6
       if (jf < 2 * (u64)K) fetch_at[jf].push_back(Ev{c, (u32)i});
       if (ju < 2 * (u64)K) use_at[ju].push_back(Ev{c, (u32)i});
     }
+  auto plan_order = [](const Ev& x, const Ev& y) { return x.rec < y.rec; };   // same instant: plan order
+  for (size_t j = 0; j < 2 * (size_t)K; ++j) {
+    std::stable_sort(evict_at[j].begin(), evict_at[j].end(), plan_order);
+    std::stable_sort(fetch_at[j].begin(), fetch_at[j].end(), plan_order);
+  }
   std::vector<u64> E[2] = {std::vector<u64>(n, 0), std::vector<u64>(n, 0)}, F[2] = {std::vector<u64>(n, 0), std::vector<u64>(n, 0)};
   u64 chan_out[2] = {0, 0}, chan_in[2] = {0, 0};
   u64 done_prev = 0, end_first = 0;                  // end of the previous kernel; end of the first iteration

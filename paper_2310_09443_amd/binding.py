@@ -20,7 +20,8 @@ FLASH, HOST = 0, 1
 FITS, RESIDUAL, TRUNCATED = 0, 1, 2
 NO_WRAP = 1
 
-EXPORTS = ["g10_vitality", "g10_vitality_info", "g10_vitality_read", "g10_plan", "g10_plan_batch", "g10_prefetch", "g10_plan_free"]
+EXPORTS = ["g10_vitality", "g10_vitality_info", "g10_vitality_read", "g10_plan", "g10_plan_batch", "g10_prefetch", "g10_replay",
+           "g10_plan_free"]
 
 MIGRATION = np.dtype([("cand", "<u4"), ("tensor", "<u4"), ("evict_after", "<u4"),
                       ("absent_first", "<u4"), ("absent_last", "<u4"), ("next_use", "<u4"),
@@ -73,6 +74,12 @@ class _PrefetchResult(C.Structure):
                 ("absent_last", C.c_void_p), ("pressure", C.c_void_p), ("ms", C.c_double)]
 
 
+class _ReplayResult(C.Structure):
+    _fields_ = [("iter_ns", C.c_uint64), ("planned_ns", C.c_uint64), ("stall_ns", C.c_uint64), ("n_stalled", C.c_uint64),
+                ("bytes", C.c_uint64 * 2), ("busy_out_ns", C.c_uint64 * 2), ("busy_in_ns", C.c_uint64 * 2),
+                ("n_migrations", C.c_uint64), ("late_ns", C.c_void_p), ("ms", C.c_double)]
+
+
 _lib = None
 
 
@@ -83,6 +90,9 @@ def load():
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2310_09443_amd.build` "
                               "(hipcc, gfx950); there is no CPU fallback")
+        # torch brings its own HIP runtime; it must be the one in the process before this library
+        # resolves its HIP symbols, or the two would not share streams and device memory
+        import torch  # noqa: F401
         lib = C.CDLL(LIB_PATH)
         lib.g10_vitality.argtypes = [C.POINTER(_Trace), C.c_void_p, C.POINTER(C.c_void_p)]
         lib.g10_vitality_info.argtypes = [C.c_void_p, C.POINTER(_Stats)]
@@ -90,6 +100,7 @@ def load():
         lib.g10_plan.argtypes = [C.c_void_p, C.POINTER(_Params), C.POINTER(_Result)]
         lib.g10_plan_batch.argtypes = [C.c_void_p, C.POINTER(_Params), C.c_uint32, C.POINTER(_Result)]
         lib.g10_prefetch.argtypes = [C.c_void_p, C.POINTER(_PrefetchResult)]
+        lib.g10_replay.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.POINTER(_ReplayResult)]
         lib.g10_plan_free.argtypes = [C.c_void_p]
         lib.g10_plan_free.restype = None
         _lib = lib
@@ -140,6 +151,14 @@ class PrefetchResult:
         self.gained = Result._copy(r.gained, n, np.dtype("<u4"))
         self.absent_last = Result._copy(r.absent_last, n, np.dtype("<u4"))
         self.pressure = Result._copy(r.pressure, K, np.dtype("<u8"))
+
+
+class ReplayResult:
+    def __init__(self, r: _ReplayResult):
+        self.iter_ns, self.planned_ns, self.stall_ns = int(r.iter_ns), int(r.planned_ns), int(r.stall_ns)
+        self.n_stalled, self.ms = int(r.n_stalled), float(r.ms)
+        self.bytes, self.busy_out_ns, self.busy_in_ns = list(r.bytes), list(r.busy_out_ns), list(r.busy_in_ns)
+        self.late = Result._copy(r.late_ns, int(r.n_migrations), np.dtype("<u8"))
 
 
 class Handle:
@@ -233,6 +252,18 @@ class Handle:
             raise G10Error(rc, "g10_prefetch")
         return PrefetchResult(r, self.K)
 
+    def replay(self, dur=None, eager=False) -> ReplayResult:
+        """dur: None, or a device tensor of K 64-bit durations (ns) to replay the plan with."""
+        import torch
+        if dur is not None and not (dur.is_cuda and dur.is_contiguous() and dur.element_size() == 8 and dur.numel() == self.K):
+            raise ValueError("dur must be a contiguous device tensor of K 64-bit integers")
+        r = _ReplayResult()
+        with torch.cuda.device(self._dev):
+            rc = load().g10_replay(self._h, None if dur is None else dur.data_ptr(), int(bool(eager)), C.byref(r))
+        if rc:
+            raise G10Error(rc, "g10_replay")
+        return ReplayResult(r)
+
     def close(self):
         if self._h:
             load().g10_plan_free(self._h)
@@ -259,6 +290,10 @@ def g10_plan_batch(handle: Handle, param_dicts):
 
 def g10_prefetch(handle: Handle) -> PrefetchResult:
     return handle.prefetch()
+
+
+def g10_replay(handle: Handle, dur=None, eager=False) -> ReplayResult:
+    return handle.replay(dur, eager)
 
 
 def g10_plan_free(handle: Handle) -> None:

@@ -105,4 +105,15 @@ extern "C" int g10_prefetch(g10_plan_t* h, g10_prefetch_result* out) {
   return rc;
 }
 
+extern "C" int g10_replay(g10_plan_t* h, const uint64_t* dur_ns, uint32_t eager, g10_replay_result* out) {
+  if (out) memset(out, 0, sizeof *out);
+  if (!h || !out) return G10_EINVAL;
+  const int rc = replay_run(h, dur_ns, eager, out);
+  if (rc) {
+    (void)hipStreamSynchronize(h->stream);
+    memset(out, 0, sizeof *out);
+  }
+  return rc;
+}
+
 extern "C" void g10_plan_free(g10_plan_t* h) { handle_free(h); }

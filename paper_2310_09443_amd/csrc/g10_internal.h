@@ -216,4 +216,5 @@ int slot_times_end(const void* check, u64* T_out);
 int plan_run(g10_plan_s* h, const g10_params* p, g10_result* out);
 int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_result* outs);
 int prefetch_run(g10_plan_s* h, g10_prefetch_result* out);
+int replay_run(g10_plan_s* h, const u64* dur_ns, u32 eager, g10_replay_result* out);
 void plan_work_free(PlanWork* w);

@@ -330,6 +330,7 @@ __global__ __launch_bounds__(G10_BLOCK) void k_finish(Timelines tl, const u64* _
 void plan_work_free(PlanWork* w) {
   if (!w) return;
   if (w->arena) (void)hipFree(w->arena);
+  replay_free(w);
   free(w->h_records);
   free(w->h_dropped);
   free(w->h_pressure);
@@ -495,7 +496,7 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
       if (rc) { plan_work_free(*slot); *slot = nullptr; return rc; }
     }
     I[i].w = *slot; I[i].p = p; I[i].max_tiles = clamp_limit(p->max_tiles, NT_MAX);
-    (*slot)->planned = false;
+    (*slot)->planned = false; (*slot)->prefetched = false;
   }
 
   // ---- the durations every plan runs on ---------------------------------------------------

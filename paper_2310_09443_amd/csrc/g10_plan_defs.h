@@ -364,16 +364,28 @@ struct PlanWork {
   u32 *h_pf_order = nullptr, *h_pf_gained = nullptr, *h_pf_last = nullptr;
   u64* h_pf_pressure = nullptr;
   bool planned = false;         // a plan is stored in the handle
+  bool prefetched = false;      // smart prefetching has run on that plan (pf_gained is valid)
   u64 plan_cap = 0, plan_n_mig = 0;
   // host copies handed out through g10_result
   g10_migration* h_records = nullptr;
   g10_dropped* h_dropped = nullptr;
   u64* h_pressure = nullptr;
   hipEvent_t ev[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+  // plan replay: a device allocation of its own, made at the first replay and sized for the plan's migrations
+  void* rp_arena = nullptr;
+  u32 rp_cap = 0;
+  u64 *rp_keys = nullptr, *rp_alt = nullptr, *rp_res = nullptr, *rp_late = nullptr, *rp_dur = nullptr, *rp_start = nullptr,
+      *rp_tscr = nullptr;
+  u32 *rp_pos = nullptr, *rp_hist = nullptr, *rp_scr = nullptr;
+  void *rp_stats = nullptr, *rp_tstats = nullptr;
+  u64* h_rp_late = nullptr;
   void* arena = nullptr;        // the one device allocation all pointers above point into
   u32 max_chunks = 0;           // the chunk limit the timelines were laid out for
   bool has_cache = false;       // the candidate buffers have the cv / ce arrays
 };
+
+// plan replay (g10_replay.hip)
+void replay_free(PlanWork* w);
 
 // the loop kernel (g10_loop.hip)
 size_t loop_lds_bytes(u32 nch, u32 nt);                       // dynamic LDS of one workgroup

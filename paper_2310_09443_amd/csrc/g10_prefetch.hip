@@ -206,5 +206,6 @@ int prefetch_run(g10_plan_s* h, g10_prefetch_result* out) {
   out->n_migrations = n; out->n_moved = st[0]; out->slots_gained = st[1]; out->peak_bytes = st[2];
   out->order = w->h_pf_order; out->gained = w->h_pf_gained; out->absent_last = w->h_pf_last; out->pressure = w->h_pf_pressure;
   out->ms = ms;
+  w->prefetched = true;
   return G10_OK;
 }
