@@ -96,51 +96,57 @@ __global__ __launch_bounds__(G10_WAVE) void k_replay(const u64* __restrict__ sor
   u64 stall = 0, n_stalled = 0;
   u32 use_pt = NONE32, stalled_pt = NONE32;
   u64 delta_pt = 0;                     // delta when the uses of the current point began
-  // one event per lane: what does not depend on earlier results (key, record fields, the point's
-  // time without stalls, where the result it waits for stands); gathered one step ahead of the walk
-  struct Ev { u64 tau, sp; u32 type, c, i, pt, dest, pp; bool valid; };
-  auto gather = [&](u32 base) -> Ev {
+  // One event per lane, gathered one step ahead of the walk: key, record fields, the point's time
+  // without stalls, and the result the event waits for.  While batch b is walked the results of
+  // the batches before b are in memory, so an older one is loaded here; one of batch b or of the
+  // batch gathered itself is noted by its lane and read from a register during the walk.
+  struct Ev { u64 tau, sp, pval; u32 type, i, pt, dest, pin, psrc; bool valid; };   // psrc 0: pval; 1: this batch; 2: the batch before
+  auto gather = [&](u32 base, u32 done) -> Ev {           // results of positions < done are in memory
     Ev v;
-    v.tau = 0; v.sp = 0; v.type = 3; v.c = 0; v.i = 0; v.pt = 0; v.dest = 0; v.pp = NONE32;
+    v.tau = 0; v.sp = 0; v.pval = 0; v.type = 3; v.i = 0; v.pt = 0; v.dest = 0; v.pin = 0; v.psrc = 0;
     const u32 p = base + lane;
     const u64 k = p < ne ? sorted[p] : NONE64;
     v.valid = k != NONE64;
     if (v.valid) {
-      v.c = (u32)(k & 1ull); v.i = (u32)((k >> 1) & ((1ull << rbits) - 1ull));
+      const u32 c = (u32)(k & 1ull);
+      v.i = (u32)((k >> 1) & ((1ull << rbits) - 1ull));
       const u64 q = k >> (rbits + 1);
       v.type = (u32)(q & 3ull); v.pt = (u32)(q >> 2);
       const g10_migration m = rec[v.i];
       v.dest = m.dest;
       v.tau = v.type == EV_EVICT ? m.t_out_ns : m.t_in_ns;
       v.sp = v.pt < K ? start[v.pt] : start[v.pt - K] + T;     // end of kernel pt - 1 without any stall
-      if (v.type != EV_EVICT) v.pp = pos_of[(u64)((v.type - 1) * 2 + v.c) * n + v.i];   // its eviction / its prefetch
+      if (v.type != EV_EVICT) {                                 // its eviction / its prefetch
+        const u32 pp = pos_of[(u64)((v.type - 1) * 2 + c) * n + v.i];
+        if (pp >= base) { v.psrc = 1; v.pin = pp - base; }
+        else if (pp >= done) { v.psrc = 2; v.pin = pp - done; }
+        else v.pval = res[pp];
+      }
     }
     return v;
   };
-  Ev nxt = gather(0);
+  Ev nxt = gather(0, 0);
+  u64 resv_prev = 0;                    // results of the batch before, one per lane
   for (u32 base = 0; base < ne; base += G10_WAVE) {
     const Ev cur = nxt;
     const u32 p = base + lane;
     const bool valid = cur.valid;
     const u32 type = cur.type, i = cur.i, pt = cur.pt, dest = cur.dest;
     const u64 tau = cur.tau, sp = cur.sp;
-    u32 prod_in = NONE32;
-    u64 prod_val = 0;
-    if (valid && type != EV_EVICT) {                            // what it waits for
-      if (cur.pp >= base) prod_in = cur.pp - base;
-      else prod_val = res[cur.pp];
-    }
-    if (base + G10_WAVE < ne) nxt = gather(base + G10_WAVE);    // in flight during the walk
+    if (base + G10_WAVE < ne) nxt = gather(base + G10_WAVE, base);   // in flight during the walk
     const u32 cnt = (u32)__popcll(__ballot(valid));             // the valid events come first
     u64 resv = 0, latev = 0;
     // ---- the walk ----------------------------------------------------------------------
     for (u32 e = 0; e < cnt; ++e) {
       const u32 ty = (u32)__builtin_amdgcn_readlane((int)type, (int)e), d = (u32)__builtin_amdgcn_readlane((int)dest, (int)e);
-      const u32 ept = (u32)__builtin_amdgcn_readlane((int)pt, (int)e), pin = (u32)__builtin_amdgcn_readlane((int)prod_in, (int)e);
+      const u32 ept = (u32)__builtin_amdgcn_readlane((int)pt, (int)e);
       const u64 esp = lane_get(sp, e), etau = lane_get(tau, e);
       if (!second && ept >= K) { second = true; delta_first = delta; }
       u64 pv = 0;
-      if (ty != EV_EVICT) pv = pin != NONE32 ? lane_get(resv, pin) : lane_get(prod_val, e);
+      if (ty != EV_EVICT) {
+        const u32 src = (u32)__builtin_amdgcn_readlane((int)cur.psrc, (int)e), pin = (u32)__builtin_amdgcn_readlane((int)cur.pin, (int)e);
+        pv = src == 1 ? lane_get(resv, pin) : (src == 2 ? lane_get(resv_prev, pin) : lane_get(cur.pval, e));
+      }
       const u64 free_at = esp + delta;                          // end of the previous kernel
       if (ty == EV_EVICT) {
         const u64 chn = d ? ch_out1 : ch_out0;
@@ -169,8 +175,9 @@ __global__ __launch_bounds__(G10_WAVE) void k_replay(const u64* __restrict__ sor
     // ---- results out ---------------------------------------------------------------------
     if (valid && type != EV_USE) res[p] = resv;
     if (valid && type == EV_USE && pt >= K) late[i] = latev;
+    resv_prev = resv;
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __builtin_amdgcn_s_waitcnt(0);                              // the next 64 may read what was just written
+    __builtin_amdgcn_s_waitcnt(0);                              // the next gather may read what was just written
     if (cnt < G10_WAVE) break;
   }
   if (!second) delta_first = delta;
