@@ -10,6 +10,7 @@ typedef uint64_t u64;
 typedef uint32_t u32;
 
 #define G10_WAVE 64
+#define G10_AUX_STREAMS 8
 #define G10_BLOCK 256               // 4 wavefronts per workgroup everywhere
 #define G10_WAVES (G10_BLOCK / G10_WAVE)
 
@@ -206,6 +207,8 @@ struct g10_plan_s {
   void* loop_args = nullptr;     // device array of per-plan arguments of the loop kernel
   u32 loop_args_cap = 0;
   bool lds_opt_in = false;       // the loop kernel was allowed more than 64 KB of LDS
+  hipStream_t aux[8] = {};       // streams for the streaming kernels of the plans of a batch (made at the first batch)
+  u32 n_aux = 0;
 };
 
 int vitality_run(g10_plan_s* h, const g10_trace* tr);

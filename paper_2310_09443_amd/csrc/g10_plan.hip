@@ -476,7 +476,15 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
   }
   Inst* I = new (std::nothrow) Inst[count];
   LoopArgs* hargs = (LoopArgs*)malloc((size_t)count * sizeof(LoopArgs));
-  struct Guard { Inst* i; LoopArgs* a; ~Guard() { delete[] i; free(a); } } guard{I, hargs};
+  // whatever way this function is left, nothing is in flight that reads or writes these host arrays
+  struct Guard {
+    g10_plan_s* h; Inst* i; LoopArgs* a;
+    ~Guard() {
+      for (u32 k = 0; k < h->n_aux; ++k) (void)hipStreamSynchronize(h->aux[k]);
+      (void)hipStreamSynchronize(h->stream);
+      delete[] i; free(a);
+    }
+  } guard{h, I, hargs};
   if (!I || !hargs) return G10_ENOMEM;
 
   for (u32 i = 0; i < count; ++i) {
@@ -520,10 +528,27 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     }
   }
 
+  // The streaming kernels of the plans of a batch are short and many (a sort alone is a dozen launches):
+  // they go to a few streams of the handle, plan by plan in turn, so that the plans' sequences overlap;
+  // the loop launches and everything of a single plan stay on the caller's stream.
+  if (count > 1 && !h->n_aux) {
+    for (u32 k = 0; k < G10_AUX_STREAMS; ++k) {
+      G10_HIP(hipStreamCreateWithFlags(&h->aux[k], hipStreamNonBlocking));
+      h->n_aux = k + 1;
+    }
+  }
+  auto stream_of = [&](u32 i) -> hipStream_t { return count == 1 ? s : h->aux[i % h->n_aux]; };
+  auto sync_all = [&]() -> int {
+    if (count > 1) for (u32 k = 0; k < h->n_aux; ++k) G10_HIP(hipStreamSynchronize(h->aux[k]));
+    G10_HIP(hipStreamSynchronize(s));
+    return G10_OK;
+  };
+
   // ---- timelines before any eviction, candidate windows --------------------------------
   G10_HIP(hipEventRecord(I[0].w->ev[0], s));
   for (u32 i = 0; i < count; ++i) {
     Inst& x = I[i];
+    hipStream_t q = stream_of(i);
     PlanWork* w = x.w;
     const g10_params* p = x.p;
     Ctl& hc = x.hc;
@@ -537,26 +562,26 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     hc.max_iter = p->max_iterations;
     hc.rank = p->rank; hc.area = p->area;
     hc.C = C;
-    G10_HIP(hipMemcpyAsync(w->ctl, &hc, sizeof hc, hipMemcpyHostToDevice, s));
+    G10_HIP(hipMemcpyAsync(w->ctl, &hc, sizeof hc, hipMemcpyHostToDevice, q));
     Timelines& tl = x.tl;
     tl.dur = w->dur; tl.P = w->P; tl.fre = w->fre; tl.H = w->H; tl.px = w->px; tl.otc = w->otc;
     tl.K = K; tl.Kp = w->Kp; tl.nch = w->nch; tl.spt = w->spt; tl.shift_ch = w->shift_ch;
-    G10_HIP(hipMemsetAsync(w->peak_after, 0, 8, s));
-    hipLaunchKernelGGL(k_init_timelines, dim3(w->nch), dim3(G10_BLOCK), 0, s, tl, (const u64*)(h->pressure_buf + 1),
+    G10_HIP(hipMemsetAsync(w->peak_after, 0, 8, q));
+    hipLaunchKernelGGL(k_init_timelines, dim3(w->nch), dim3(G10_BLOCK), 0, q, tl, (const u64*)(h->pressure_buf + 1),
                        (const Ctl*)w->ctl, w->g_tot, w->g_lazyP, w->g_minOver, w->g_lazyH, w->g_hmax);
-    hipLaunchKernelGGL(k_level1_init, dim3(1), dim3(LB), 0, s, (const u64*)w->g_tot, w->nch, w->base0, w->ctl);
-    hipLaunchKernelGGL(k_ot_full, dim3(K / G10_BLOCK + 1), dim3(G10_BLOCK), 0, s, w->otc, (const u64*)w->base0, K, w->nch, w->shift_ch);
+    hipLaunchKernelGGL(k_level1_init, dim3(1), dim3(LB), 0, q, (const u64*)w->g_tot, w->nch, w->base0, w->ctl);
+    hipLaunchKernelGGL(k_ot_full, dim3(K / G10_BLOCK + 1), dim3(G10_BLOCK), 0, q, w->otc, (const u64*)w->base0, K, w->nch, w->shift_ch);
     G10_HIP(hipGetLastError());
     if (C) {      // windows per destination; keep the candidates with at least one valid window
-      hipLaunchKernelGGL(k_prep, dim3(gC), dim3(G10_BLOCK), 0, s, (const uint4*)h->per_by_start, (const u64*)h->per_size, w->start, K, w->T, C,
+      hipLaunchKernelGGL(k_prep, dim3(gC), dim3(G10_BLOCK), 0, q, (const uint4*)h->per_by_start, (const u64*)h->per_size, w->start, K, w->T, C,
                          (const Ctl*)w->ctl, w->win, w->keep);
       G10_HIP(hipGetLastError());
-      G10_TRY(scan_excl_u32(w->keep, w->keep, C, w->scratch32, s));
-      G10_HIP(hipMemcpyAsync(&x.n, w->keep + C, sizeof(u32), hipMemcpyDeviceToHost, s));
+      G10_TRY(scan_excl_u32(w->keep, w->keep, C, w->scratch32, q));
+      G10_HIP(hipMemcpyAsync(&x.n, w->keep + C, sizeof(u32), hipMemcpyDeviceToHost, q));
     }
-    G10_HIP(hipMemcpyAsync(&hc, w->ctl, sizeof hc, hipMemcpyDeviceToHost, s));
+    G10_HIP(hipMemcpyAsync(&hc, w->ctl, sizeof hc, hipMemcpyDeviceToHost, q));
   }
-  G10_HIP(hipStreamSynchronize(s));
+  G10_TRY(sync_all());
 
   // the candidate buffers of a plan; the value cache only where the plan reads the benefit as the clipped area
   auto cands_of = [](const Inst& x, int which) {
@@ -566,7 +591,7 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
   };
 
   // candidates of plan x into score order, in tiles
-  auto retile = [&](Inst& x, bool first) -> int {
+  auto retile = [&](Inst& x, bool first, hipStream_t q) -> int {
     PlanWork* w = x.w;
     x.tsh = tile_shift_for(x.n, x.max_tiles);
     const u32 tile = UNIT << x.tsh;
@@ -578,30 +603,30 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
       const u32 gn = (n + G10_BLOCK - 1) / G10_BLOCK;
       // the two events take the kernel's own begin and end time stamps
       if (x.p->rank == G10_RANK_RATIO)
-        hipExtLaunchKernelGGL(k_score_full<true>, dim3(gn), dim3(G10_BLOCK), 0, s, w->ev[2], w->ev[3], 0, (const uint4*)w->cd[x.cur].A,
+        hipExtLaunchKernelGGL(k_score_full<true>, dim3(gn), dim3(G10_BLOCK), 0, q, w->ev[2], w->ev[3], 0, (const uint4*)w->cd[x.cur].A,
                               (const uint4*)w->cd[x.cur].B, n, (const u64*)w->otc, K, posbits, w->keys, (const Ctl*)w->ctl);
       else
-        hipExtLaunchKernelGGL(k_score_full<false>, dim3(gn), dim3(G10_BLOCK), 0, s, w->ev[2], w->ev[3], 0, (const uint4*)w->cd[x.cur].A,
+        hipExtLaunchKernelGGL(k_score_full<false>, dim3(gn), dim3(G10_BLOCK), 0, q, w->ev[2], w->ev[3], 0, (const uint4*)w->cd[x.cur].A,
                               (const uint4*)w->cd[x.cur].B, n, (const u64*)w->otc, K, posbits, w->keys, (const Ctl*)w->ctl);
       x.timed_full = true;
     } else {
       u32 gn = (n + G10_BLOCK - 1) / G10_BLOCK;
       if (gn > 2048) gn = 2048;
-      G10_HIP(hipMemsetAsync(&w->ctl->n_live, 0, sizeof(u32), s));
+      G10_HIP(hipMemsetAsync(&w->ctl->n_live, 0, sizeof(u32), q));
       if (x.p->rank == G10_RANK_RATIO)
-        hipLaunchKernelGGL(k_rescore<true>, dim3(gn), dim3(G10_BLOCK), (size_t)N_ARR * (w->nch + 1) * 8, s, w->cd[x.cur], n,
+        hipLaunchKernelGGL(k_rescore<true>, dim3(gn), dim3(G10_BLOCK), (size_t)N_ARR * (w->nch + 1) * 8, q, w->cd[x.cur], n,
                            (const u64*)w->px, (const u64*)w->g_base, K, w->nch, w->shift_ch, (const Ctl*)w->ctl, posbits,
                            w->keys, &w->ctl->n_live);
       else
-        hipLaunchKernelGGL(k_rescore<false>, dim3(gn), dim3(G10_BLOCK), (size_t)N_ARR * (w->nch + 1) * 8, s, w->cd[x.cur], n,
+        hipLaunchKernelGGL(k_rescore<false>, dim3(gn), dim3(G10_BLOCK), (size_t)N_ARR * (w->nch + 1) * 8, q, w->cd[x.cur], n,
                            (const u64*)w->px, (const u64*)w->g_base, K, w->nch, w->shift_ch, (const Ctl*)w->ctl, posbits,
                            w->keys, &w->ctl->n_live);
     }
     G10_HIP(hipGetLastError());
     u64 *keys = w->keys, *alt = w->keys_alt;
-    G10_TRY(radix_sort_u64(&keys, &alt, n, posbits + 23, w->hist, w->scratch32, s));
-    G10_HIP(hipMemsetAsync(w->tkeys, 0, (u64)NT_MAX * 4, s));
-    hipLaunchKernelGGL(k_tile_gather, dim3(x.n_pad / G10_BLOCK), dim3(G10_BLOCK), 0, s, (const u64*)keys, n, x.n_pad, posbits,
+    G10_TRY(radix_sort_u64(&keys, &alt, n, posbits + 23, w->hist, w->scratch32, q));
+    G10_HIP(hipMemsetAsync(w->tkeys, 0, (u64)NT_MAX * 4, q));
+    hipLaunchKernelGGL(k_tile_gather, dim3(x.n_pad / G10_BLOCK), dim3(G10_BLOCK), 0, q, (const u64*)keys, n, x.n_pad, posbits,
                        cands_of(x, x.cur), cands_of(x, x.cur ^ 1), 8 + x.tsh, w->tkeys);
     G10_HIP(hipGetLastError());
     x.cur ^= 1;
@@ -619,14 +644,15 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     if (x.hc.done) continue;
     ++n_active;
     if (x.n) {
-      hipLaunchKernelGGL(k_pack, dim3(gC), dim3(G10_BLOCK), 0, s, (const uint4*)h->per_by_start, (const u64*)h->per_size, (const uint4*)x.w->win,
+      hipLaunchKernelGGL(k_pack, dim3(gC), dim3(G10_BLOCK), 0, stream_of(i), (const uint4*)h->per_by_start, (const u64*)h->per_size, (const uint4*)x.w->win,
                          (const u32*)x.w->keep, C, cands_of(x, x.cur));
       G10_HIP(hipGetLastError());
     }
-    G10_TRY(retile(x, true));
+    G10_TRY(retile(x, true, stream_of(i)));
     const size_t lds = loop_lds_bytes(x.w->nch, x.nt);
     if (lds > lds_max) lds_max = lds;
   }
+  if (count > 1) G10_TRY(sync_all());
   if (!h->lds_opt_in && lds_max > 64 * 1024) {
     G10_TRY(loop_allow_large_lds());
     h->lds_opt_in = true;
@@ -637,6 +663,8 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
   // loop looks at are dense with live candidates again, and the list is cut to those that can
   // still score.  A batch ends its launches by the clock instead, so that no plan waits long for
   // the slowest one.
+  // (a batch re-tiles half as often: its loops run side by side, its re-tilings one after the other)
+  const u32 retile_every = count == 1 ? RETILE_PASSES : 2 * RETILE_PASSES;
   const bool timed_loop = n_active != 0;
   if (timed_loop) G10_HIP(hipEventRecord(I[0].w->ev[4], s));
   while (n_active) {
@@ -671,14 +699,15 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
       Inst& x = I[i];
       if (x.hc.done) continue;
       ++n_active;
-      if (x.n > RETILE_MIN_CANDS && x.hc.n_iter - x.seen_iter >= RETILE_PASSES) {
+      if (x.n > RETILE_MIN_CANDS && x.hc.n_iter - x.seen_iter >= retile_every) {
         x.seen_iter = x.hc.n_iter;
         if (x.counted && x.hc.n_live < x.n) x.n = x.hc.n_live;   // live candidates come first in the list
-        G10_TRY(retile(x, false));
+        G10_TRY(retile(x, false, stream_of(i)));
         x.counted = true;
         ++x.retiles;
       }
     }
+    if (count > 1) G10_TRY(sync_all());
   }
   if (timed_loop) G10_HIP(hipEventRecord(I[0].w->ev[5], s));
 
