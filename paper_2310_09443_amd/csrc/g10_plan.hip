@@ -17,9 +17,9 @@
 //
 // The greedy loop itself is a serial chain of small dependent steps (rank,
 // decide, range updates, prefix rebuild), bound by latency, not bandwidth.  It
-// runs in ONE persistent workgroup of 1024 threads (k_loop): no grid barrier
-// and no kernel boundary per pass, the level-1 state in LDS, the slot arrays
-// in L2.  Range updates over a period are chunked: whole chunks take a lazy
+// runs in ONE persistent workgroup of 512 threads per plan (k_loop, in
+// g10_loop.hip): no grid barrier and no kernel boundary per pass, the level-1
+// state in LDS, the slot arrays in L2.  Range updates over a period are chunked: whole chunks take a lazy
 // add in LDS (pressure, host occupancy), only chunks cut by the period ends,
 // chunks holding the transfer windows and chunks in which a slot drops under
 // the capacity are rewritten slot by slot, one wavefront per chunk.
@@ -42,6 +42,13 @@
 //                         (arrays: 0 OT, 1+d FOd, 3+d FId); a prefix up to
 //                         slot j is base[chunk(j)] + px[j].
 // Cross-iteration periods use doubled slot coordinates j in [0, 2K).
+//
+// This file: the host side of a planning call (workspaces, launches, re-tiling
+// between launches of the loop, batches of plans) and the streaming kernels
+// (candidate preparation, timelines, the full scoring pass, re-scoring, tile
+// gather).  The two alternative readings of Section 4.3 (rank by benefit /
+// cost; benefit as the area removed above the capacity line) instantiate the
+// same kernels; what they change is stated in g10_plan_defs.h and g10_loop.hip.
 
 #include "g10_plan_defs.h"
 
