@@ -12,9 +12,7 @@ static void handle_free(g10_plan_s* h) {
   free(h->more);
   if (h->loop_args) (void)hipFree(h->loop_args);
   for (u32 k = 0; k < h->n_aux; ++k) (void)hipStreamDestroy(h->aux[k]);
-  void* dev[] = {h->dur, h->size, h->glob, h->start, h->ukeys, h->use_off, h->use_k, h->per_t, h->per_L, h->per_R,
-                 h->per_by_start, h->per_size, h->pressure_buf};
-  for (void* p : dev) if (p) (void)hipFree(p);
+  if (h->arena) (void)hipFree(h->arena);        // every array of the analysis
   delete h;
 }
 

@@ -207,6 +207,7 @@ struct g10_plan_s {
   void* loop_args = nullptr;     // device array of per-plan arguments of the loop kernel
   u32 loop_args_cap = 0;
   bool lds_opt_in = false;       // the loop kernel was allowed more than 64 KB of LDS
+  void* arena = nullptr;         // the one device allocation the analysis arrays above point into
   hipStream_t aux[8] = {};       // streams for the streaming kernels of the plans of a batch (made at the first batch)
   u32 n_aux = 0;
 };

@@ -383,27 +383,29 @@ inline u32 bits_for(u64 max_value) {            // bits needed to hold values 0.
   return b;
 }
 
-struct Tmp {                                    // device temporaries released when the analysis ends
-  void* p[16] = {};
-  int n = 0;
-  ~Tmp() { for (int i = 0; i < n; ++i) (void)hipFree(p[i]); }
-  template <class T>
-  int alloc(T** out, u64 elems) {
+// One device allocation carved into arrays (every hipMalloc / hipFree costs about 0.1 ms of host
+// time, and the analysis needs twenty arrays).
+struct Pool {
+  char* base = nullptr;
+  size_t off = 0, cap = 0;
+  bool owned = false;                             // released when this object goes away (the temporaries)
+  ~Pool() { if (owned && base) (void)hipFree(base); }
+  static size_t need(u64 elems, size_t size) { return (((elems ? elems : 1) * size) + 255) & ~(size_t)255; }
+  int reserve(size_t bytes) {
     void* q = nullptr;
-    if (hipMalloc(&q, (elems ? elems : 1) * sizeof(T)) != hipSuccess) { (void)hipGetLastError(); return G10_ENOMEM; }
-    p[n++] = q;
-    *out = (T*)q;
+    if (hipMalloc(&q, bytes ? bytes : 256) != hipSuccess) { (void)hipGetLastError(); return G10_ENOMEM; }
+    base = (char*)q; cap = bytes; off = 0;
+    return G10_OK;
+  }
+  template <class T>
+  int take(T** out, u64 elems) {
+    const size_t b = need(elems, sizeof(T));
+    if (off + b > cap) return G10_ENOMEM;
+    *out = (T*)(base + off);
+    off += b;
     return G10_OK;
   }
 };
-
-template <class T>
-int dev_alloc(T** out, u64 elems) {
-  void* q = nullptr;
-  if (hipMalloc(&q, (elems ? elems : 1) * sizeof(T)) != hipSuccess) { (void)hipGetLastError(); return G10_ENOMEM; }
-  *out = (T*)q;
-  return G10_OK;
-}
 
 }  // namespace
 
@@ -492,16 +494,25 @@ int vitality_run(g10_plan_s* h, const g10_trace* tr) {
   const u32 K = h->K, N = h->N;
   const u64 P = h->P;
   if (P >= (1ull << 32)) return G10_EINVAL;      // positions and counts are 32-bit on the device
-  Tmp tmp;
+  const u64 ss_kn = scan_scratch_elems(K > N ? K : N), rh = radix_hist_elems(P), ss_p = scan_scratch_elems(rh > P ? rh : P);
+  Pool tmp, keep;                                 // temporaries of this call; what the handle keeps
+  tmp.owned = true;
+  G10_TRY(tmp.reserve(Pool::need(1, sizeof(VitStats)) + Pool::need(ss_kn, 8) + 2 * Pool::need(P, 8) + 2 * Pool::need(P + 1, 4) +
+                      Pool::need(rh, 4) + Pool::need(ss_p, 4)));
+  // (the arrays per period are sized for P entries: there are fewer periods than uses, fewer uses than pairs)
+  G10_TRY(keep.reserve(Pool::need(K, 8) + Pool::need(N, 8) + Pool::need(N, 1) + Pool::need((u64)K + 1, 8) + Pool::need(P, 8) +
+                       Pool::need(P, 4) + Pool::need((u64)N + 1, 8) + 3 * Pool::need(P, 4) + Pool::need((u64)K + 2, 8) +
+                       Pool::need(P, 16) + Pool::need(P, 8)));
+  h->arena = keep.base;                           // released with the handle
 
   VitStats* st = nullptr;
-  G10_TRY(tmp.alloc(&st, 1));
+  G10_TRY(tmp.take(&st, 1));
   G10_HIP(hipMemsetAsync(st, 0, sizeof(VitStats), s));
 
   // own copies of what planning needs later
-  G10_TRY(dev_alloc(&h->dur, K));
-  G10_TRY(dev_alloc(&h->size, N));
-  G10_TRY(dev_alloc(&h->glob, N));
+  G10_TRY(keep.take(&h->dur, K));
+  G10_TRY(keep.take(&h->size, N));
+  G10_TRY(keep.take(&h->glob, N));
   G10_HIP(hipMemcpyAsync(h->dur, tr->dur_ns, (u64)K * 8, hipMemcpyDeviceToDevice, s));
   G10_HIP(hipMemcpyAsync(h->size, tr->size_bytes, (u64)N * 8, hipMemcpyDeviceToDevice, s));
   G10_HIP(hipMemcpyAsync(h->glob, tr->is_global, (u64)N, hipMemcpyDeviceToDevice, s));
@@ -524,8 +535,8 @@ int vitality_run(g10_plan_s* h, const g10_trace* tr) {
 
   // ---- slot start times ----------------------------------------------------
   u64* scratch64 = nullptr;
-  G10_TRY(tmp.alloc(&scratch64, scan_scratch_elems(K > N ? K : N)));
-  G10_TRY(dev_alloc(&h->start, (u64)K + 1));
+  G10_TRY(tmp.take(&scratch64, scan_scratch_elems(K > N ? K : N)));
+  G10_TRY(keep.take(&h->start, (u64)K + 1));
   G10_TRY(scan_excl_u64(h->dur, h->start, K, scratch64, s));
 
   // ---- use lists -------------------------------------------------------------
@@ -533,11 +544,11 @@ int vitality_run(g10_plan_s* h, const g10_trace* tr) {
   const u32 tbits = bits_for(N - 1);
   u64 *keys = nullptr, *alt = nullptr;
   u32 *flag = nullptr, *scratch32 = nullptr, *hist = nullptr;
-  G10_TRY(tmp.alloc(&keys, P));
-  G10_TRY(tmp.alloc(&alt, P));
-  G10_TRY(tmp.alloc(&flag, P + 1));
-  G10_TRY(tmp.alloc(&hist, radix_hist_elems(P)));
-  G10_TRY(tmp.alloc(&scratch32, scan_scratch_elems(radix_hist_elems(P) > P ? radix_hist_elems(P) : P)));
+  G10_TRY(tmp.take(&keys, P));
+  G10_TRY(tmp.take(&alt, P));
+  G10_TRY(tmp.take(&flag, P + 1));
+  G10_TRY(tmp.take(&hist, radix_hist_elems(P)));
+  G10_TRY(tmp.take(&scratch32, scan_scratch_elems(radix_hist_elems(P) > P ? radix_hist_elems(P) : P)));
   if (P) {
     hipLaunchKernelGGL(k_pack, dim3(grid_for(P)), dim3(G10_BLOCK), 0, s, tr->use_kernel, tr->use_tensor, P, h->kbits, keys);
     G10_TRY(radix_sort_u64(&keys, &alt, P, h->kbits + tbits, hist, scratch32, s));
@@ -546,28 +557,28 @@ int vitality_run(g10_plan_s* h, const g10_trace* tr) {
   }
   G10_TRY(scan_excl_u32(flag, flag, P, scratch32, s));           // flag[i] = position, flag[P] = n_uses
   const u32* n_uses_p = flag + P;
-  G10_TRY(dev_alloc(&h->ukeys, P));                               // upper bounds: no host round trip here
-  G10_TRY(dev_alloc(&h->use_k, P));
-  G10_TRY(dev_alloc(&h->use_off, (u64)N + 1));
+  G10_TRY(keep.take(&h->ukeys, P));                               // upper bounds: no host round trip here
+  G10_TRY(keep.take(&h->use_k, P));
+  G10_TRY(keep.take(&h->use_off, (u64)N + 1));
   if (P) hipLaunchKernelGGL(k_compact_distinct, dim3(grid_for(P)), dim3(G10_BLOCK), 0, s, keys, P, flag, h->ukeys, h->use_k, h->kbits);
   hipLaunchKernelGGL(k_use_off, dim3(grid_for((u64)N + 1)), dim3(G10_BLOCK), 0, s, h->ukeys, n_uses_p, N, h->kbits, h->use_off);
   G10_HIP(hipGetLastError());
 
   // ---- inactive periods --------------------------------------------------------
   u32* pcnt = nullptr;
-  G10_TRY(tmp.alloc(&pcnt, P + 1));
+  G10_TRY(tmp.take(&pcnt, P + 1));
   const u32 no_wrap = (h->flags & G10_NO_WRAP) ? 1u : 0u;
   G10_HIP(hipMemsetAsync(pcnt, 0, (P + 1) * sizeof(u32), s));
   if (P) hipLaunchKernelGGL(k_period_count, dim3(grid_for(P)), dim3(G10_BLOCK), 0, s, h->ukeys, h->use_off, h->glob, n_uses_p, K, h->kbits, no_wrap, pcnt);
   G10_TRY(scan_excl_u32(pcnt, pcnt, P, scratch32, s));           // pcnt[P] = n_periods (entries past n_uses are 0)
-  G10_TRY(dev_alloc(&h->per_t, P));
-  G10_TRY(dev_alloc(&h->per_L, P));
-  G10_TRY(dev_alloc(&h->per_R, P));
+  G10_TRY(keep.take(&h->per_t, P));
+  G10_TRY(keep.take(&h->per_L, P));
+  G10_TRY(keep.take(&h->per_R, P));
   if (P) hipLaunchKernelGGL(k_period_write, dim3(grid_for(P)), dim3(G10_BLOCK), 0, s, h->ukeys, h->use_off, h->glob, n_uses_p, K, h->kbits, no_wrap, pcnt, h->per_t, h->per_L, h->per_R);
   G10_HIP(hipGetLastError());
 
   // ---- memory pressure -----------------------------------------------------------
-  G10_TRY(dev_alloc(&h->pressure_buf, (u64)K + 2));
+  G10_TRY(keep.take(&h->pressure_buf, (u64)K + 2));
   hipLaunchKernelGGL(k_fill_u64, dim3(grid_for((u64)K + 2)), dim3(G10_BLOCK), 0, s, h->pressure_buf, (u64)K + 2, 0ull);
   hipLaunchKernelGGL(k_lifetime_adds, dim3(grid_for(N)), dim3(G10_BLOCK), 0, s, h->ukeys, h->use_off, h->size, h->glob, N, K, h->kbits, h->pressure_buf, st);
   G10_HIP(hipGetLastError());
@@ -590,8 +601,8 @@ int vitality_run(g10_plan_s* h, const g10_trace* tr) {
   // Planning walks the periods with one thread each and looks up the timeline around their
   // start and end; in this order neighbouring threads look at neighbouring slots.
   const u64 C = h->n_periods;
-  G10_TRY(dev_alloc(&h->per_by_start, C));
-  G10_TRY(dev_alloc(&h->per_size, C));
+  G10_TRY(keep.take(&h->per_by_start, C));      // (C <= P)
+  G10_TRY(keep.take(&h->per_size, C));
   if (C) {
     const u32 cbits = bits_for(C - 1);
     hipLaunchKernelGGL(k_start_keys, dim3(grid_for(C)), dim3(G10_BLOCK), 0, s, h->per_L, C, cbits, keys);
