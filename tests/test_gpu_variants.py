@@ -8,6 +8,7 @@ import plancheck
 from goldenio import Golden
 from oracle import oracle as O
 from paper_2310_09443_amd import traces
+from paper_2310_09443_amd.traces import Trace
 from test_gpu_parity import assert_plan_equal, assert_prefetch_equal, g10, run_both  # noqa: F401  (g10 is a fixture)
 
 pytestmark = pytest.mark.gpu
@@ -182,4 +183,25 @@ def test_stress_full_size_clipped(g10):
     base = h.plan(**args)
     assert base.records.tobytes() != r.records.tobytes()       # the reading matters on this trace
     assert h.plan(area=1, **args).records.tobytes() == r.records.tobytes()
+    h.close()
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_huge_values(g10, seed):
+    """Sizes near 2^50 bytes and kernels near 2^44 ns: benefits need their high 64 bits, the ratio
+    comparison its third word.  Every reading, small traces, against the oracle's literal loops."""
+    w = traces.random_small(11000 + seed, K=10 + seed % 9, N=6 + seed % 7, max_uses=4)
+    tr = w.trace
+    big = Trace("huge", tr.dur_ns << np.uint64(30), tr.size_bytes << np.uint64(36), tr.is_global, tr.use_kernel, tr.use_tensor)
+    v = O.Vitality(big, O.DIRECT)
+    h = g10.g10_vitality(g10.DeviceTrace(big))
+    assert (h.start == v.start).all() and (h.pressure == v.pressure).all()
+    bw = ((1 << 19) + 12345 * seed, (1 << 21) + 777)
+    args = dict(gpu_cap=int(v.peak * (0.4 + 0.05 * (seed % 5))), host_cap=int(v.peak // 3), bw_out=bw, bw_in=(bw[0] + 99, bw[1]))
+    for va in [dict(rank=0, area=0)] + VARIANTS:
+        p = v.plan(mode=O.DIRECT, **args, **va)
+        r = h.plan(**args, **va)
+        assert_plan_equal(r, p)
+        assert len(p.records) == 0 or int(p.records["benefit_hi"].max()) > 0
+        assert_prefetch_equal(h.prefetch(), p.prefetch(O.DIRECT))
     h.close()
