@@ -204,4 +204,8 @@ def test_huge_values(g10, seed):
         assert_plan_equal(r, p)
         assert len(p.records) == 0 or int(p.records["benefit_hi"].max()) > 0
         assert_prefetch_equal(h.prefetch(), p.prefetch(O.DIRECT))
+        for eager in (False, True):                          # and the replay of that plan: times beyond 2^45 ns
+            y, yo = h.replay(eager=eager), p.replay(eager=eager)
+            assert (y.iter_ns, y.planned_ns, y.stall_ns, y.n_stalled) == (yo.iter_ns, yo.planned_ns, yo.stall_ns, yo.n_stalled)
+            assert (y.late == yo.late).all() and y.bytes == yo.bytes
     h.close()
