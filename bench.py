@@ -39,7 +39,8 @@ def counted_hbm_bytes(workload):
     fetch = c["fetch_size_kib"] * c["copy_expected_kib"] / c["copy_fetch_size_kib"]
     write = c["write_size_kib"] * c["copy_expected_kib"] / c["copy_write_size_kib"]
     return (fetch + write) * 1024.0
-BYTES_PER_CAND = 36            # full scoring pass: reads L+1, R, 2 x (a, b) as u32 + size u64, writes a 4-byte key
+BYTES_PER_CAND = 36            # what a scoring pass over a candidate moves by definition: L+1, R, 2 x (a, b) as u32 + size u64
+                               # read, a 4-byte key written (the kernel itself reads a 24-byte copy without L+1 and R)
 
 
 def main():

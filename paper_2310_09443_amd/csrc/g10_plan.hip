@@ -103,7 +103,7 @@ __global__ __launch_bounds__(G10_BLOCK) void k_prep(const uint4* __restrict__ pe
 // candidates with at least one valid window, packed in the order of their start
 __global__ __launch_bounds__(G10_BLOCK) void k_pack(const uint4* __restrict__ per, const u64* __restrict__ size,
                                                    const uint4* __restrict__ win, const u32* __restrict__ pos, u32 C,
-                                                   Cands out) {
+                                                   Cands out, uint4* __restrict__ fw, u64* __restrict__ fs) {
   const u32 c = blockIdx.x * G10_BLOCK + threadIdx.x;
   if (c >= C || pos[c + 1] == pos[c]) return;
   const uint4 pd = per[c];                  // {L, R, tensor, period index}
@@ -113,6 +113,8 @@ __global__ __launch_bounds__(G10_BLOCK) void k_pack(const uint4* __restrict__ pe
   out.A[o] = make_uint4(pd.x + 1, pd.y, w.x, w.y);
   out.B[o] = make_uint4(w.z, w.w, (u32)s, (u32)(s >> 32));
   out.id[o] = make_uint2(pd.w, pd.z);
+  fw[o] = w;                                // what the first scoring pass needs, on its own: the two windows and the size
+  fs[o] = s;
   if (out.ce) out.ce[o] = make_uint2(0u, 0u);        // no value of the clipped area yet
 }
 
@@ -198,11 +200,12 @@ __global__ __launch_bounds__(G10_BLOCK) void k_ot_full(u64* __restrict__ ot, con
 // ---------------------------------------------------------------------------
 // the streaming scoring pass over every candidate, before any eviction: all
 // channels are still free, so every valid window can be carried and
-// U = size * (largest over-capacity time of the valid windows).  Reads the 32
-// bytes of the candidate, gathers two words per window of a prefix table that
-// fits L2 (8 bytes per slot; a window inside the other one is skipped), writes
-// the 8-byte sort key: the 31-bit score key rounded up to its top 23 bits
-// (descending), then the position.
+// U = size * (largest over-capacity time of the valid windows).  The period's
+// ends are not needed for that, so the pass reads a copy of the candidates
+// made for it - the two windows and the size, 24 bytes - gathers two words per
+// window of a prefix table that fits L2 (8 bytes per slot; a window inside the
+// other one is skipped), and writes the 8-byte sort key: the 31-bit score key
+// rounded up to its top 23 bits (descending), then the position.
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ u64 sort_key(u32 key31, u32 posbits, u32 p) {
   return ((u64)(0x7fffffu - ((key31 + 255u) >> 8)) << posbits) | p;
@@ -213,28 +216,28 @@ __device__ __forceinline__ u32 bound_of_sort_key(u64 sk, u32 posbits) { return (
 // RATIO: ranking by benefit / cost; a window inside the other may then still have the larger
 // key (its transfers can be the shorter ones), so both are looked up.
 template <bool RATIO>
-__global__ __launch_bounds__(G10_BLOCK) void k_score_full(const uint4* __restrict__ cA, const uint4* __restrict__ cB, u32 n,
+__global__ __launch_bounds__(G10_BLOCK) void k_score_full(const uint4* __restrict__ fw, const u64* __restrict__ fs, u32 n,
                                                          const u64* __restrict__ ot, u32 K, u32 posbits,
                                                          u64* __restrict__ sortkeys, const Ctl* __restrict__ ctl) {
   const u32 p = blockIdx.x * G10_BLOCK + threadIdx.x;
   if (p >= n) return;
-  const uint4 A = cA[p], B = cB[p];
-  const u64 s = ((u64)B.w << 32) | B.z;
+  const uint4 W = fw[p];                      // {a0, b0, a1, b1}
+  const u64 s = fs[p];
   const u64 total = ot[K];
-  bool v0 = A.z <= A.w, v1 = B.x <= B.y;
+  bool v0 = W.x <= W.y, v1 = W.z <= W.w;
   // the prefix is monotone: a window inside the other one cannot hold more over-capacity time
   if (!RATIO && v0 && v1) {
-    if (B.x <= A.z && B.y >= A.w) v0 = false;
-    else if (A.z <= B.x && A.w >= B.y) v1 = false;
+    if (W.z <= W.x && W.w >= W.y) v0 = false;
+    else if (W.x <= W.z && W.y >= W.w) v1 = false;
   }
   u64 t0 = 0, t1 = 0;
   if (v0) {
-    const u32 a = A.z, b = A.w + 1;
+    const u32 a = W.x, b = W.y + 1;
     const u64 oa = ot[a >= K ? a - K : a], ob = ot[b >= K ? b - K : b];
     t0 = (ob + (b >= K ? total : 0ull)) - (oa + (a >= K ? total : 0ull));
   }
   if (v1) {
-    const u32 a = B.x, b = B.y + 1;
+    const u32 a = W.z, b = W.w + 1;
     const u64 oa = ot[a >= K ? a - K : a], ob = ot[b >= K ? b - K : b];
     t1 = (ob + (b >= K ? total : 0ull)) - (oa + (a >= K ? total : 0ull));
   }
@@ -385,6 +388,7 @@ static void work_layout(PlanWork* w, Arena& ar) {
   ar.take(&w->scratch32, scan_scratch_elems(he > C ? he : C));
   ar.take(&w->keys, C); ar.take(&w->keys_alt, C);
   ar.take(&w->tkeys, (u64)NT_MAX);
+  ar.take(&w->fw, C); ar.take(&w->fs, C);
   for (int i = 0; i < 2; ++i) {
     ar.take(&w->cd[i].A, w->cap_pad); ar.take(&w->cd[i].B, w->cap_pad); ar.take(&w->cd[i].id, w->cap_pad);
     if (w->has_cache) { ar.take(&w->cd[i].cv, w->cap_pad); ar.take(&w->cd[i].ce, w->cap_pad); }
@@ -610,11 +614,11 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
       const u32 gn = (n + G10_BLOCK - 1) / G10_BLOCK;
       // the two events take the kernel's own begin and end time stamps
       if (x.p->rank == G10_RANK_RATIO)
-        hipExtLaunchKernelGGL(k_score_full<true>, dim3(gn), dim3(G10_BLOCK), 0, q, w->ev[2], w->ev[3], 0, (const uint4*)w->cd[x.cur].A,
-                              (const uint4*)w->cd[x.cur].B, n, (const u64*)w->otc, K, posbits, w->keys, (const Ctl*)w->ctl);
+        hipExtLaunchKernelGGL(k_score_full<true>, dim3(gn), dim3(G10_BLOCK), 0, q, w->ev[2], w->ev[3], 0, (const uint4*)w->fw,
+                              (const u64*)w->fs, n, (const u64*)w->otc, K, posbits, w->keys, (const Ctl*)w->ctl);
       else
-        hipExtLaunchKernelGGL(k_score_full<false>, dim3(gn), dim3(G10_BLOCK), 0, q, w->ev[2], w->ev[3], 0, (const uint4*)w->cd[x.cur].A,
-                              (const uint4*)w->cd[x.cur].B, n, (const u64*)w->otc, K, posbits, w->keys, (const Ctl*)w->ctl);
+        hipExtLaunchKernelGGL(k_score_full<false>, dim3(gn), dim3(G10_BLOCK), 0, q, w->ev[2], w->ev[3], 0, (const uint4*)w->fw,
+                              (const u64*)w->fs, n, (const u64*)w->otc, K, posbits, w->keys, (const Ctl*)w->ctl);
       x.timed_full = true;
     } else {
       u32 gn = (n + G10_BLOCK - 1) / G10_BLOCK;
@@ -652,7 +656,7 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     ++n_active;
     if (x.n) {
       hipLaunchKernelGGL(k_pack, dim3(gC), dim3(G10_BLOCK), 0, stream_of(i), (const uint4*)h->per_by_start, (const u64*)h->per_size, (const uint4*)x.w->win,
-                         (const u32*)x.w->keep, C, cands_of(x, x.cur));
+                         (const u32*)x.w->keep, C, cands_of(x, x.cur), x.w->fw, x.w->fs);
       G10_HIP(hipGetLastError());
     }
     G10_TRY(retile(x, true, stream_of(i)));

@@ -342,6 +342,8 @@ struct PlanWork {
   u32 K = 0, Kp = 0, nch = 0, spt = 1, shift_ch = 8;
   u64 C = 0, cap_pad = 0;
   uint4* win = nullptr;
+  uint4* fw = nullptr;          // the kept candidates' windows {a0, b0, a1, b1} and sizes on their own, for the first scoring pass
+  u64* fs = nullptr;
   u32 *keep = nullptr, *scratch32 = nullptr, *hist = nullptr, *tkeys = nullptr;
   u64 *keys = nullptr, *keys_alt = nullptr;
   g10::Cands cd[2] = {};
