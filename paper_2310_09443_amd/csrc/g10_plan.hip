@@ -207,17 +207,16 @@ __global__ __launch_bounds__(G10_BLOCK) void k_ot_full(u64* __restrict__ ot, con
 // other one is skipped), and writes the 8-byte sort key: the 31-bit score key
 // rounded up to its top 23 bits (descending), then the position.
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ u64 sort_key(u32 key31, u32 posbits, u32 p) {
-  return ((u64)(0x7fffffu - ((key31 + 255u) >> 8)) << posbits) | p;
-}
+// (ascending sort = descending score; the sort is stable, so equal keys stay in the order of their positions)
+__device__ __forceinline__ u64 sort_key(u32 key31) { return (u64)(0x7fffffu - ((key31 + 255u) >> 8)); }
 // the bound a sort key stands for: at least the score key it was made from, 0 only for 0
-__device__ __forceinline__ u32 bound_of_sort_key(u64 sk, u32 posbits) { return (0x7fffffu - (u32)(sk >> posbits)) << 8; }
+__device__ __forceinline__ u32 bound_of_sort_key(u64 sk) { return (0x7fffffu - (u32)sk) << 8; }
 
 // RATIO: ranking by benefit / cost; a window inside the other may then still have the larger
 // key (its transfers can be the shorter ones), so both are looked up.
 template <bool RATIO>
 __global__ __launch_bounds__(G10_BLOCK) void k_score_full(const uint4* __restrict__ fw, const u64* __restrict__ fs, u32 n,
-                                                         const u64* __restrict__ ot, u32 K, u32 posbits,
+                                                         const u64* __restrict__ ot, u32 K,
                                                          u64* __restrict__ sortkeys, const Ctl* __restrict__ ctl) {
   const u32 p = blockIdx.x * G10_BLOCK + threadIdx.x;
   if (p >= n) return;
@@ -248,22 +247,22 @@ __global__ __launch_bounds__(G10_BLOCK) void k_score_full(const uint4* __restric
     u64 c0, c1;
     costs_of(mc, s, c0, c1);
     const u32 k0 = key_up_of<true>(__umul64hi(s, t0), s * t0, c0), k1 = key_up_of<true>(__umul64hi(s, t1), s * t1, c1);
-    sortkeys[p] = sort_key(k0 > k1 ? k0 : k1, posbits, p);
+    sortkeys[p] = sort_key(k0 > k1 ? k0 : k1);
     return;
   }
   const u64 t = t1 > t0 ? t1 : t0;
-  sortkeys[p] = sort_key(upkey(__umul64hi(s, t), s * t), posbits, p);
+  sortkeys[p] = sort_key(upkey(__umul64hi(s, t), s * t));
 }
 
 // candidates into score order; the tile bound is the largest bound of its members
-__global__ __launch_bounds__(G10_BLOCK) void k_tile_gather(const u64* __restrict__ sorted, u32 n, u32 n_pad, u32 posbits,
+__global__ __launch_bounds__(G10_BLOCK) void k_tile_gather(const u64* __restrict__ sorted, const u32* __restrict__ from, u32 n, u32 n_pad,
                                                           Cands src, Cands dst, u32 tile_shift, u32* __restrict__ tkeys) {
   const u32 r = blockIdx.x * G10_BLOCK + threadIdx.x;
   if (r >= n_pad) return;
   u32 k = 0;
   if (r < n) {
     const u64 sk = sorted[r];
-    const u32 p = (u32)(sk & ((1ull << posbits) - 1ull));
+    const u32 p = from[r];
     dst.A[r] = src.A[p];
     dst.B[r] = src.B[p];
     dst.id[r] = src.id[p];
@@ -272,7 +271,7 @@ __global__ __launch_bounds__(G10_BLOCK) void k_tile_gather(const u64* __restrict
       dst.ce[r] = e;
       if (e.y & 1u) dst.cv[r] = src.cv[p];
     }
-    k = bound_of_sort_key(sk, posbits);
+    k = bound_of_sort_key(sk);
   } else {                                       // padding of the last tile: no valid window
     dst.A[r] = make_uint4(0u, 0u, 1u, 0u);
     dst.B[r] = make_uint4(1u, 0u, 0u, 0u);
@@ -289,7 +288,7 @@ __global__ __launch_bounds__(G10_BLOCK) void k_tile_gather(const u64* __restrict
 // strikes dead destinations; counts the candidates that can still score.
 template <bool RATIO>
 __global__ __launch_bounds__(G10_BLOCK) void k_rescore(Cands cd, u32 n, const u64* __restrict__ px, const u64* __restrict__ g_base,
-                                                      u32 K, u32 nch, u32 shift_ch, const Ctl* ctl, u32 posbits,
+                                                      u32 K, u32 nch, u32 shift_ch, const Ctl* ctl,
                                                       u64* __restrict__ sortkeys, u32* __restrict__ n_live) {
   extern __shared__ u64 lb[];                  // [5][nch + 1]
   for (u32 i = threadIdx.x; i < N_ARR * (nch + 1); i += G10_BLOCK) lb[i] = g_base[i];
@@ -313,7 +312,7 @@ __global__ __launch_bounds__(G10_BLOCK) void k_rescore(Cands cd, u32 n, const u6
       const bool one = gt128(r.h1, r.l1, r.h0, r.l0);
       k = upkey(one ? r.h1 : r.h0, one ? r.l1 : r.l0);
     }
-    sortkeys[p] = sort_key(k, posbits, p);
+    sortkeys[p] = sort_key(k);
     live += k != 0;
   }
   __shared__ u32 tmp[G10_WAVES + 1];
@@ -387,6 +386,7 @@ static void work_layout(PlanWork* w, Arena& ar) {
   ar.take(&w->hist, he);
   ar.take(&w->scratch32, scan_scratch_elems(he > C ? he : C));
   ar.take(&w->keys, C); ar.take(&w->keys_alt, C);
+  ar.take(&w->sv, C); ar.take(&w->sv_alt, C);
   ar.take(&w->tkeys, (u64)NT_MAX);
   ar.take(&w->fw, C); ar.take(&w->fs, C);
   for (int i = 0; i < 2; ++i) {
@@ -609,16 +609,16 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     x.nt = (u32)(((u64)x.n + tile - 1) / tile);
     x.n_pad = x.nt * tile;
     if (!x.n) return G10_OK;
-    const u32 n = x.n, posbits = bits_for(n - 1);
+    const u32 n = x.n;
     if (first) {
       const u32 gn = (n + G10_BLOCK - 1) / G10_BLOCK;
       // the two events take the kernel's own begin and end time stamps
       if (x.p->rank == G10_RANK_RATIO)
         hipExtLaunchKernelGGL(k_score_full<true>, dim3(gn), dim3(G10_BLOCK), 0, q, w->ev[2], w->ev[3], 0, (const uint4*)w->fw,
-                              (const u64*)w->fs, n, (const u64*)w->otc, K, posbits, w->keys, (const Ctl*)w->ctl);
+                              (const u64*)w->fs, n, (const u64*)w->otc, K, w->keys, (const Ctl*)w->ctl);
       else
         hipExtLaunchKernelGGL(k_score_full<false>, dim3(gn), dim3(G10_BLOCK), 0, q, w->ev[2], w->ev[3], 0, (const uint4*)w->fw,
-                              (const u64*)w->fs, n, (const u64*)w->otc, K, posbits, w->keys, (const Ctl*)w->ctl);
+                              (const u64*)w->fs, n, (const u64*)w->otc, K, w->keys, (const Ctl*)w->ctl);
       x.timed_full = true;
     } else {
       u32 gn = (n + G10_BLOCK - 1) / G10_BLOCK;
@@ -626,18 +626,19 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
       G10_HIP(hipMemsetAsync(&w->ctl->n_live, 0, sizeof(u32), q));
       if (x.p->rank == G10_RANK_RATIO)
         hipLaunchKernelGGL(k_rescore<true>, dim3(gn), dim3(G10_BLOCK), (size_t)N_ARR * (w->nch + 1) * 8, q, w->cd[x.cur], n,
-                           (const u64*)w->px, (const u64*)w->g_base, K, w->nch, w->shift_ch, (const Ctl*)w->ctl, posbits,
+                           (const u64*)w->px, (const u64*)w->g_base, K, w->nch, w->shift_ch, (const Ctl*)w->ctl,
                            w->keys, &w->ctl->n_live);
       else
         hipLaunchKernelGGL(k_rescore<false>, dim3(gn), dim3(G10_BLOCK), (size_t)N_ARR * (w->nch + 1) * 8, q, w->cd[x.cur], n,
-                           (const u64*)w->px, (const u64*)w->g_base, K, w->nch, w->shift_ch, (const Ctl*)w->ctl, posbits,
+                           (const u64*)w->px, (const u64*)w->g_base, K, w->nch, w->shift_ch, (const Ctl*)w->ctl,
                            w->keys, &w->ctl->n_live);
     }
     G10_HIP(hipGetLastError());
     u64 *keys = w->keys, *alt = w->keys_alt;
-    G10_TRY(radix_sort_u64(&keys, &alt, n, posbits + 23, w->hist, w->scratch32, q));
+    u32 *from = w->sv, *from_alt = w->sv_alt;          // where every candidate of the new order stood in the old one
+    G10_TRY(radix_sort_u64_pairs(&keys, &alt, &from, &from_alt, n, 23, w->hist, w->scratch32, q, true));
     G10_HIP(hipMemsetAsync(w->tkeys, 0, (u64)NT_MAX * 4, q));
-    hipLaunchKernelGGL(k_tile_gather, dim3(x.n_pad / G10_BLOCK), dim3(G10_BLOCK), 0, q, (const u64*)keys, n, x.n_pad, posbits,
+    hipLaunchKernelGGL(k_tile_gather, dim3(x.n_pad / G10_BLOCK), dim3(G10_BLOCK), 0, q, (const u64*)keys, (const u32*)from, n, x.n_pad,
                        cands_of(x, x.cur), cands_of(x, x.cur ^ 1), 8 + x.tsh, w->tkeys);
     G10_HIP(hipGetLastError());
     x.cur ^= 1;

@@ -346,6 +346,7 @@ struct PlanWork {
   u64* fs = nullptr;
   u32 *keep = nullptr, *scratch32 = nullptr, *hist = nullptr, *tkeys = nullptr;
   u64 *keys = nullptr, *keys_alt = nullptr;
+  u32 *sv = nullptr, *sv_alt = nullptr;   // the values of the score sort: old positions
   g10::Cands cd[2] = {};
   u64 *P = nullptr, *fre = nullptr, *H = nullptr, *px = nullptr, *otc = nullptr, *base0 = nullptr, *g_tot = nullptr,
       *g_lazyP = nullptr, *g_minOver = nullptr, *g_lazyH = nullptr, *g_hmax = nullptr, *g_base = nullptr,

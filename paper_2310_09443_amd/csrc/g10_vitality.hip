@@ -176,7 +176,7 @@ __global__ __launch_bounds__(G10_BLOCK) void k_radix_scatter(const u64* __restri
     const u64 i = tile_index(r);
     const bool ok = i < P;
     key[r] = ok ? keys[i] : 0;
-    val[r] = PAIRS && ok ? vals[i] : 0u;
+    val[r] = PAIRS && ok ? (vals ? vals[i] : (u32)i) : 0u;     // no values given: the positions themselves
     const u32 dig = (u32)(key[r] >> shift) & 255u;
     u64 peers = __ballot(ok);
 #pragma unroll
@@ -448,15 +448,16 @@ int radix_sort_u64(u64** keys, u64** alt, u64 n, u32 bits, u32* hist, u32* scrat
 }
 
 // The same with a 32-bit value carried along with every key; *vals / *valt swap like the keys.
+// iota: the values are the positions 0..n-1 (the first pass makes them; *vals need not be filled).
 int radix_sort_u64_pairs(u64** keys, u64** alt, u32** vals, u32** valt, u64 n, u32 bits, u32* hist, u32* scratch,
-                         hipStream_t s) {
+                         hipStream_t s, bool iota) {
   if (n == 0) return G10_OK;
   const u32 nb = (u32)((n + TILE - 1) / TILE);
   for (u32 shift = 0; shift < bits; shift += 8) {
     hipLaunchKernelGGL(k_radix_hist, dim3(nb), dim3(G10_BLOCK), 0, s, *keys, n, shift, hist, nb);
     G10_TRY(scan_excl_u32(hist, hist, (u64)256 * nb, scratch, s));
-    hipLaunchKernelGGL(k_radix_scatter<true>, dim3(nb), dim3(G10_BLOCK), 0, s, *keys, *alt, (const u32*)*vals, *valt, n, shift,
-                       hist, nb);
+    hipLaunchKernelGGL(k_radix_scatter<true>, dim3(nb), dim3(G10_BLOCK), 0, s, *keys, *alt,
+                       iota && shift == 0 ? (const u32*)nullptr : (const u32*)*vals, *valt, n, shift, hist, nb);
     u64* t = *keys; *keys = *alt; *alt = t;
     u32* v = *vals; *vals = *valt; *valt = v;
   }
