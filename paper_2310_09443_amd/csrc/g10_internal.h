@@ -171,6 +171,8 @@ int scan_excl_u64(const u64* in, u64* out, u64 n, u64* scratch, hipStream_t s);
 // stable LSD radix sort of the low `bits` bits of 64-bit keys (see g10_vitality.hip)
 size_t radix_hist_elems(u64 n);
 int radix_sort_u64(u64** keys, u64** alt, u64 n, u32 bits, u32* hist, u32* scratch, hipStream_t s);
+int radix_sort_u32_pairs(u32** keys, u32** alt, u32** vals, u32** valt, u64 n, u32 bits, u32* hist, u32* scratch,
+                         hipStream_t s, bool iota = false);
 int radix_sort_u64_pairs(u64** keys, u64** alt, u32** vals, u32** valt, u64 n, u32 bits, u32* hist, u32* scratch,
                          hipStream_t s, bool iota = false);
 

@@ -208,16 +208,16 @@ __global__ __launch_bounds__(G10_BLOCK) void k_ot_full(u64* __restrict__ ot, con
 // rounded up to its top 23 bits (descending), then the position.
 // ---------------------------------------------------------------------------
 // (ascending sort = descending score; the sort is stable, so equal keys stay in the order of their positions)
-__device__ __forceinline__ u64 sort_key(u32 key31) { return (u64)(0x7fffffu - ((key31 + 255u) >> 8)); }
+__device__ __forceinline__ u32 sort_key(u32 key31) { return 0x7fffffu - ((key31 + 255u) >> 8); }
 // the bound a sort key stands for: at least the score key it was made from, 0 only for 0
-__device__ __forceinline__ u32 bound_of_sort_key(u64 sk) { return (0x7fffffu - (u32)sk) << 8; }
+__device__ __forceinline__ u32 bound_of_sort_key(u32 sk) { return (0x7fffffu - sk) << 8; }
 
 // RATIO: ranking by benefit / cost; a window inside the other may then still have the larger
 // key (its transfers can be the shorter ones), so both are looked up.
 template <bool RATIO>
 __global__ __launch_bounds__(G10_BLOCK) void k_score_full(const uint4* __restrict__ fw, const u64* __restrict__ fs, u32 n,
                                                          const u64* __restrict__ ot, u32 K,
-                                                         u64* __restrict__ sortkeys, const Ctl* __restrict__ ctl) {
+                                                         u32* __restrict__ sortkeys, const Ctl* __restrict__ ctl) {
   const u32 p = blockIdx.x * G10_BLOCK + threadIdx.x;
   if (p >= n) return;
   const uint4 W = fw[p];                      // {a0, b0, a1, b1}
@@ -255,13 +255,13 @@ __global__ __launch_bounds__(G10_BLOCK) void k_score_full(const uint4* __restric
 }
 
 // candidates into score order; the tile bound is the largest bound of its members
-__global__ __launch_bounds__(G10_BLOCK) void k_tile_gather(const u64* __restrict__ sorted, const u32* __restrict__ from, u32 n, u32 n_pad,
+__global__ __launch_bounds__(G10_BLOCK) void k_tile_gather(const u32* __restrict__ sorted, const u32* __restrict__ from, u32 n, u32 n_pad,
                                                           Cands src, Cands dst, u32 tile_shift, u32* __restrict__ tkeys) {
   const u32 r = blockIdx.x * G10_BLOCK + threadIdx.x;
   if (r >= n_pad) return;
   u32 k = 0;
   if (r < n) {
-    const u64 sk = sorted[r];
+    const u32 sk = sorted[r];
     const u32 p = from[r];
     dst.A[r] = src.A[p];
     dst.B[r] = src.B[p];
@@ -289,7 +289,7 @@ __global__ __launch_bounds__(G10_BLOCK) void k_tile_gather(const u64* __restrict
 template <bool RATIO>
 __global__ __launch_bounds__(G10_BLOCK) void k_rescore(Cands cd, u32 n, const u64* __restrict__ px, const u64* __restrict__ g_base,
                                                       u32 K, u32 nch, u32 shift_ch, const Ctl* ctl,
-                                                      u64* __restrict__ sortkeys, u32* __restrict__ n_live) {
+                                                      u32* __restrict__ sortkeys, u32* __restrict__ n_live) {
   extern __shared__ u64 lb[];                  // [5][nch + 1]
   for (u32 i = threadIdx.x; i < N_ARR * (nch + 1); i += G10_BLOCK) lb[i] = g_base[i];
   __syncthreads();
@@ -634,11 +634,11 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
                            w->keys, &w->ctl->n_live);
     }
     G10_HIP(hipGetLastError());
-    u64 *keys = w->keys, *alt = w->keys_alt;
+    u32 *keys = w->keys, *alt = w->keys_alt;
     u32 *from = w->sv, *from_alt = w->sv_alt;          // where every candidate of the new order stood in the old one
-    G10_TRY(radix_sort_u64_pairs(&keys, &alt, &from, &from_alt, n, 23, w->hist, w->scratch32, q, true));
+    G10_TRY(radix_sort_u32_pairs(&keys, &alt, &from, &from_alt, n, 23, w->hist, w->scratch32, q, true));
     G10_HIP(hipMemsetAsync(w->tkeys, 0, (u64)NT_MAX * 4, q));
-    hipLaunchKernelGGL(k_tile_gather, dim3(x.n_pad / G10_BLOCK), dim3(G10_BLOCK), 0, q, (const u64*)keys, (const u32*)from, n, x.n_pad,
+    hipLaunchKernelGGL(k_tile_gather, dim3(x.n_pad / G10_BLOCK), dim3(G10_BLOCK), 0, q, (const u32*)keys, (const u32*)from, n, x.n_pad,
                        cands_of(x, x.cur), cands_of(x, x.cur ^ 1), 8 + x.tsh, w->tkeys);
     G10_HIP(hipGetLastError());
     x.cur ^= 1;

@@ -345,7 +345,7 @@ struct PlanWork {
   uint4* fw = nullptr;          // the kept candidates' windows {a0, b0, a1, b1} and sizes on their own, for the first scoring pass
   u64* fs = nullptr;
   u32 *keep = nullptr, *scratch32 = nullptr, *hist = nullptr, *tkeys = nullptr;
-  u64 *keys = nullptr, *keys_alt = nullptr;
+  u32 *keys = nullptr, *keys_alt = nullptr;   // the keys of the score sort
   u32 *sv = nullptr, *sv_alt = nullptr;   // the values of the score sort: old positions
   g10::Cands cd[2] = {};
   u64 *P = nullptr, *fre = nullptr, *H = nullptr, *px = nullptr, *otc = nullptr, *base0 = nullptr, *g_tot = nullptr,

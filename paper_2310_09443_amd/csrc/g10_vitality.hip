@@ -144,7 +144,8 @@ __device__ __forceinline__ u64 tile_index(u32 r) {
   return (u64)blockIdx.x * TILE + (u64)wave_id() * (G10_WAVE * ITEMS) + (u64)r * G10_WAVE + lane_id();
 }
 
-__global__ __launch_bounds__(G10_BLOCK) void k_radix_hist(const u64* __restrict__ keys, u64 P, u32 shift,
+template <class KT>
+__global__ __launch_bounds__(G10_BLOCK) void k_radix_hist(const KT* __restrict__ keys, u64 P, u32 shift,
                                                          u32* __restrict__ hist, u32 nblocks) {
   __shared__ u32 cnt[256];
   cnt[threadIdx.x] = 0;
@@ -158,8 +159,8 @@ __global__ __launch_bounds__(G10_BLOCK) void k_radix_hist(const u64* __restrict_
   hist[(u64)threadIdx.x * nblocks + blockIdx.x] = cnt[threadIdx.x];     // digit-major
 }
 
-template <bool PAIRS>
-__global__ __launch_bounds__(G10_BLOCK) void k_radix_scatter(const u64* __restrict__ keys, u64* __restrict__ out,
+template <class KT, bool PAIRS>
+__global__ __launch_bounds__(G10_BLOCK) void k_radix_scatter(const KT* __restrict__ keys, KT* __restrict__ out,
                                                             const u32* __restrict__ vals, u32* __restrict__ vout,
                                                             u64 P, u32 shift, const u32* __restrict__ offs,
                                                             u32 nblocks) {
@@ -169,13 +170,13 @@ __global__ __launch_bounds__(G10_BLOCK) void k_radix_scatter(const u64* __restri
   __syncthreads();
   const u32 w = wave_id(), l = lane_id();
   const u64 lt = (1ull << l) - 1ull;
-  u64 key[ITEMS];
+  KT key[ITEMS];
   u32 rank[ITEMS], val[ITEMS];
 #pragma unroll
   for (u32 r = 0; r < ITEMS; ++r) {
     const u64 i = tile_index(r);
     const bool ok = i < P;
-    key[r] = ok ? keys[i] : 0;
+    key[r] = ok ? keys[i] : (KT)0;
     val[r] = PAIRS && ok ? (vals ? vals[i] : (u32)i) : 0u;     // no values given: the positions themselves
     const u32 dig = (u32)(key[r] >> shift) & 255u;
     u64 peers = __ballot(ok);
@@ -437,9 +438,9 @@ int radix_sort_u64(u64** keys, u64** alt, u64 n, u32 bits, u32* hist, u32* scrat
   if (n == 0) return G10_OK;
   const u32 nb = (u32)((n + TILE - 1) / TILE);
   for (u32 shift = 0; shift < bits; shift += 8) {
-    hipLaunchKernelGGL(k_radix_hist, dim3(nb), dim3(G10_BLOCK), 0, s, *keys, n, shift, hist, nb);
+    hipLaunchKernelGGL(k_radix_hist<u64>, dim3(nb), dim3(G10_BLOCK), 0, s, *keys, n, shift, hist, nb);
     G10_TRY(scan_excl_u32(hist, hist, (u64)256 * nb, scratch, s));
-    hipLaunchKernelGGL(k_radix_scatter<false>, dim3(nb), dim3(G10_BLOCK), 0, s, *keys, *alt, (const u32*)nullptr, (u32*)nullptr, n,
+    hipLaunchKernelGGL((k_radix_scatter<u64, false>), dim3(nb), dim3(G10_BLOCK), 0, s, *keys, *alt, (const u32*)nullptr, (u32*)nullptr, n,
                        shift, hist, nb);
     u64* t = *keys; *keys = *alt; *alt = t;
   }
@@ -454,11 +455,28 @@ int radix_sort_u64_pairs(u64** keys, u64** alt, u32** vals, u32** valt, u64 n, u
   if (n == 0) return G10_OK;
   const u32 nb = (u32)((n + TILE - 1) / TILE);
   for (u32 shift = 0; shift < bits; shift += 8) {
-    hipLaunchKernelGGL(k_radix_hist, dim3(nb), dim3(G10_BLOCK), 0, s, *keys, n, shift, hist, nb);
+    hipLaunchKernelGGL(k_radix_hist<u64>, dim3(nb), dim3(G10_BLOCK), 0, s, *keys, n, shift, hist, nb);
     G10_TRY(scan_excl_u32(hist, hist, (u64)256 * nb, scratch, s));
-    hipLaunchKernelGGL(k_radix_scatter<true>, dim3(nb), dim3(G10_BLOCK), 0, s, *keys, *alt,
+    hipLaunchKernelGGL((k_radix_scatter<u64, true>), dim3(nb), dim3(G10_BLOCK), 0, s, *keys, *alt,
                        iota && shift == 0 ? (const u32*)nullptr : (const u32*)*vals, *valt, n, shift, hist, nb);
     u64* t = *keys; *keys = *alt; *alt = t;
+    u32* v = *vals; *vals = *valt; *valt = v;
+  }
+  G10_HIP(hipGetLastError());
+  return G10_OK;
+}
+
+// 32-bit keys with a 32-bit value each (the score order of the planner's candidates).
+int radix_sort_u32_pairs(u32** keys, u32** alt, u32** vals, u32** valt, u64 n, u32 bits, u32* hist, u32* scratch,
+                         hipStream_t s, bool iota) {
+  if (n == 0) return G10_OK;
+  const u32 nb = (u32)((n + TILE - 1) / TILE);
+  for (u32 shift = 0; shift < bits; shift += 8) {
+    hipLaunchKernelGGL(k_radix_hist<u32>, dim3(nb), dim3(G10_BLOCK), 0, s, (const u32*)*keys, n, shift, hist, nb);
+    G10_TRY(scan_excl_u32(hist, hist, (u64)256 * nb, scratch, s));
+    hipLaunchKernelGGL((k_radix_scatter<u32, true>), dim3(nb), dim3(G10_BLOCK), 0, s, (const u32*)*keys, *alt,
+                       iota && shift == 0 ? (const u32*)nullptr : (const u32*)*vals, *valt, n, shift, hist, nb);
+    u32* t = *keys; *keys = *alt; *alt = t;
     u32* v = *vals; *vals = *valt; *valt = v;
   }
   G10_HIP(hipGetLastError());
