@@ -58,7 +58,7 @@ def main():
                     help="counter probe: one 256 MiB device copy (calibration), one analysis and a plan cut after 8 passes")
     a = ap.parse_args()
     if a.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (planning one trace is a serial greedy loop; "
+        sys.exit("bench.py: the planner runs on one GPU only (planning one trace is a serial greedy loop; "
                  "several GPUs would each plan their own trace independently). Use --gpus 1.")
 
     import torch
