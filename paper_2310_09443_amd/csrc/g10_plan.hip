@@ -53,6 +53,7 @@
 #include "g10_plan_defs.h"
 
 #include <hip/hip_ext.h>
+#include <chrono>
 #include <new>
 #include <stdio.h>
 #include <stdlib.h>
@@ -336,6 +337,14 @@ __global__ __launch_bounds__(G10_BLOCK) void k_finish(Timelines tl, const u64* _
 
 }  // namespace
 
+// The progress blocks of the plans of a launch, side by side, so that one copy brings them to the host.
+__global__ __launch_bounds__(G10_WAVE) void k_ctl_collect(const LoopArgs* __restrict__ args, Ctl* __restrict__ out) {
+  static_assert(sizeof(Ctl) % 8 == 0, "copied as 64-bit words");
+  const u64* src = (const u64*)args[blockIdx.x].ctl;
+  u64* dst = (u64*)(out + blockIdx.x);
+  for (u32 i = threadIdx.x; i < sizeof(Ctl) / 8; i += G10_WAVE) dst[i] = src[i];
+}
+
 void plan_work_free(PlanWork* w) {
   if (!w) return;
   if (w->arena) (void)hipFree(w->arena);
@@ -482,21 +491,32 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
   if (count > h->loop_args_cap) {
     if (h->loop_args) { G10_HIP(hipStreamSynchronize(s)); (void)hipFree(h->loop_args); h->loop_args = nullptr; h->loop_args_cap = 0; }
     void* q = nullptr;
-    if (hipMalloc(&q, (size_t)count * sizeof(LoopArgs)) != hipSuccess) { (void)hipGetLastError(); return G10_ENOMEM; }
+    if (hipMalloc(&q, (size_t)count * (sizeof(LoopArgs) + sizeof(Ctl))) != hipSuccess) { (void)hipGetLastError(); return G10_ENOMEM; }
     h->loop_args = q; h->loop_args_cap = count;
   }
+  Ctl* const ctl_side = (Ctl*)((LoopArgs*)h->loop_args + h->loop_args_cap);    // the progress blocks of a launch, collected
   Inst* I = new (std::nothrow) Inst[count];
   LoopArgs* hargs = (LoopArgs*)malloc((size_t)count * sizeof(LoopArgs));
+  Ctl* hctl = (Ctl*)malloc((size_t)count * sizeof(Ctl));
+  u32* who = (u32*)malloc((size_t)count * sizeof(u32));                       // the plan of every entry of a launch
   // whatever way this function is left, nothing is in flight that reads or writes these host arrays
   struct Guard {
-    g10_plan_s* h; Inst* i; LoopArgs* a;
+    g10_plan_s* h; Inst* i; LoopArgs* a; Ctl* c; u32* w;
     ~Guard() {
       for (u32 k = 0; k < h->n_aux; ++k) (void)hipStreamSynchronize(h->aux[k]);
       (void)hipStreamSynchronize(h->stream);
-      delete[] i; free(a);
+      delete[] i; free(a); free(c); free(w);
     }
-  } guard{h, I, hargs};
-  if (!I || !hargs) return G10_ENOMEM;
+  } guard{h, I, hargs, hctl, who};
+  if (!I || !hargs || !hctl || !who) return G10_ENOMEM;
+#ifdef G10_PHASE_TIMERS
+  double host_ms[8] = {};                                 // wall clock of the host's phases
+  auto now_ms = [] { return std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now().time_since_epoch()).count(); };
+  double t_mark = now_ms();
+#define G10_HOST_PHASE(k) do { const double t_ = now_ms(); host_ms[k] += t_ - t_mark; t_mark = t_; } while (0)
+#else
+#define G10_HOST_PHASE(k) do { } while (0)
+#endif
 
   for (u32 i = 0; i < count; ++i) {
     const g10_params* p = params + i;
@@ -593,6 +613,7 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     G10_HIP(hipMemcpyAsync(&hc, w->ctl, sizeof hc, hipMemcpyDeviceToHost, q));
   }
   G10_TRY(sync_all());
+  G10_HOST_PHASE(0);
 
   // the candidate buffers of a plan; the value cache only where the plan reads the benefit as the clipped area
   auto cands_of = [](const Inst& x, int which) {
@@ -665,6 +686,7 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     if (lds > lds_max) lds_max = lds;
   }
   if (count > 1) G10_TRY(sync_all());
+  G10_HOST_PHASE(1);
   if (!h->lds_opt_in && lds_max > 64 * 1024) {
     G10_TRY(loop_allow_large_lds());
     h->lds_opt_in = true;
@@ -680,6 +702,7 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
   const bool timed_loop = n_active != 0;
   if (timed_loop) G10_HIP(hipEventRecord(I[0].w->ev[4], s));
   while (n_active) {
+    G10_HOST_PHASE(2);
     u32 na = 0, n_by_kind[4] = {0, 0, 0, 0};
     size_t lds = 0;
     for (u32 pass = 0; pass < 4 * count; ++pass) {         // the plans of one ranking key and benefit reading side by side: one kernel each
@@ -689,6 +712,7 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
       ++n_by_kind[kind];
       if (x.launches++ > x.max_launches) return G10_EDEVICE;
       PlanWork* w = x.w;
+      who[na] = i;
       LoopArgs& la = hargs[na++];
       la.tl = x.tl;
       la.g_tot = w->g_tot; la.g_lazyP = w->g_lazyP; la.g_minOver = w->g_minOver; la.g_lazyH = w->g_lazyH; la.g_hmax = w->g_hmax;
@@ -703,9 +727,16 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     G10_HIP(hipMemcpyAsync(h->loop_args, hargs, (size_t)na * sizeof(LoopArgs), hipMemcpyHostToDevice, s));
     for (u32 kind = 0, first = 0; kind < 4; first += n_by_kind[kind], ++kind)
       if (n_by_kind[kind]) G10_TRY(loop_launch((const LoopArgs*)h->loop_args + first, n_by_kind[kind], lds, kind & 1u, kind >> 1, s));
-    for (u32 i = 0; i < count; ++i)
-      if (!I[i].hc.done) G10_HIP(hipMemcpyAsync(&I[i].hc, I[i].w->ctl, sizeof(Ctl), hipMemcpyDeviceToHost, s));
+#ifdef G10_PHASE_TIMERS
     G10_HIP(hipStreamSynchronize(s));
+    G10_HOST_PHASE(3);
+#endif
+    hipLaunchKernelGGL(k_ctl_collect, dim3(na), dim3(G10_WAVE), 0, s, (const LoopArgs*)h->loop_args, ctl_side);
+    G10_HIP(hipGetLastError());
+    G10_HIP(hipMemcpyAsync(hctl, ctl_side, (size_t)na * sizeof(Ctl), hipMemcpyDeviceToHost, s));
+    G10_HIP(hipStreamSynchronize(s));
+    for (u32 k = 0; k < na; ++k) I[who[k]].hc = hctl[k];
+    G10_HOST_PHASE(4);
     n_active = 0;
     for (u32 i = 0; i < count; ++i) {
       Inst& x = I[i];
@@ -720,6 +751,7 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
       }
     }
     if (count > 1) G10_TRY(sync_all());
+    G10_HOST_PHASE(5);
   }
   if (timed_loop) G10_HIP(hipEventRecord(I[0].w->ev[5], s));
 
@@ -739,6 +771,12 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
   }
   G10_HIP(hipEventRecord(I[0].w->ev[1], s));
   G10_HIP(hipStreamSynchronize(s));
+  G10_HOST_PHASE(6);
+#ifdef G10_PHASE_TIMERS
+  if (getenv("G10_LOG"))
+    fprintf(stderr, "g10: host phases (ms): timelines+windows %.2f, first order %.2f, loop launches %.2f, loops %.2f, progress read %.2f, "
+                    "re-tilings %.2f, results %.2f\n", host_ms[0], host_ms[1], host_ms[2], host_ms[3], host_ms[4], host_ms[5], host_ms[6]);
+#endif
   float ms = 0.f, loop_ms = 0.f;
   G10_HIP(hipEventElapsedTime(&ms, I[0].w->ev[0], I[0].w->ev[1]));
   if (timed_loop) G10_HIP(hipEventElapsedTime(&loop_ms, I[0].w->ev[4], I[0].w->ev[5]));
