@@ -153,6 +153,7 @@ typedef struct {
   /* device times (events on the stream) and work counters of this call */
   double plan_ms;              /* the whole call                                       */
   double score_full_ms;        /* the one streaming scoring pass over all candidates   */
+                               /* (not timed for the plans of a batch of several: 0)   */
   uint64_t score_full_cands;   /* candidates it streamed (those with a valid window)   */
   double loop_ms;              /* the greedy loop                                      */
   uint64_t loop_launches;      /* launches of the loop kernel                          */

@@ -124,15 +124,21 @@ class DeviceTrace:
 
 
 class Result:
-    def __init__(self, r: _Result, K: int):
+    def __init__(self, r: _Result, K: int, pool=None):
+        """pool: a _Pool that takes this result's arrays (the results of a batch share one allocation)."""
         for f, _ in _Result._fields_:
             if f not in ("migrations", "dropped", "pressure_after"):
                 setattr(self, f, getattr(r, f))
-        self.records = self._copy(r.migrations, int(r.n_migrations), MIGRATION)
-        self.dropped = self._copy(r.dropped, int(r.n_dropped), DROPPED)
-        self.pressure_after = self._copy(r.pressure_after, K, np.dtype("<u8"))
+        take = pool.take if pool is not None else self._copy
+        self.records = take(r.migrations, int(r.n_migrations), MIGRATION)
+        self.dropped = take(r.dropped, int(r.n_dropped), DROPPED)
+        self.pressure_after = take(r.pressure_after, K, np.dtype("<u8"))
         self.null_iters = self.dropped["iteration"].copy()
         self.null_cands = self.dropped["cand"].copy()
+
+    @staticmethod
+    def nbytes(r: _Result, K: int) -> int:
+        return int(r.n_migrations) * MIGRATION.itemsize + int(r.n_dropped) * DROPPED.itemsize + K * 8
 
     @staticmethod
     def _copy(ptr, n, dtype):
@@ -140,6 +146,23 @@ class Result:
             return np.zeros(0, dtype)
         buf = (C.c_char * (n * dtype.itemsize)).from_address(ptr)
         return np.frombuffer(buf, dtype=dtype, count=n).copy()
+
+
+class _Pool:
+    """One allocation for the host copies of many results: a few large pages instead of many small ones."""
+
+    def __init__(self, nbytes: int):
+        self.buf = np.empty(max(nbytes, 1), np.uint8)
+        self.at = 0
+
+    def take(self, ptr, n, dtype):
+        if not n or not ptr:
+            return np.zeros(0, dtype)
+        size = n * dtype.itemsize
+        out = self.buf[self.at:self.at + size]
+        self.at += size
+        C.memmove(out.ctypes.data, ptr, size)
+        return out.view(dtype)
 
 
 class PrefetchResult:
@@ -230,7 +253,8 @@ class Handle:
             rc = load().g10_plan_batch(self._h, ps, n, rs)
         if rc:
             raise G10Error(rc, "g10_plan_batch")
-        return [Result(r, self.K) for r in rs]
+        pool = _Pool(sum(Result.nbytes(r, self.K) for r in rs))
+        return [Result(r, self.K, pool) for r in rs]
 
     def plan(self, gpu_cap, host_cap, bw_out, bw_in, max_iters=0, max_tiles=0, max_chunks=0, dur=None, rank=0, area=0) -> Result:
         import torch

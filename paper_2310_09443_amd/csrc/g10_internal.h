@@ -173,6 +173,11 @@ size_t radix_hist_elems(u64 n);
 int radix_sort_u64(u64** keys, u64** alt, u64 n, u32 bits, u32* hist, u32* scratch, hipStream_t s);
 int radix_sort_u32_pairs(u32** keys, u32** alt, u32** vals, u32** valt, u64 n, u32 bits, u32* hist, u32* scratch,
                          hipStream_t s, bool iota = false);
+// Many such sorts in the same launches.  One job: n > 0 pairs in (keys, vals), buffers (alt, valt) of the same
+// size, hist of radix_hist_elems(n) words, nb = radix_blocks(n).
+struct SortJob { u32 *keys, *alt, *vals, *valt, *hist; u32 n, nb; };
+u32 radix_blocks(u64 n);
+int radix_sort_u32_pairs_jobs(const SortJob* jobs_dev, u32 njobs, u32 max_nb, u32 bits, bool iota, hipStream_t s);
 int radix_sort_u64_pairs(u64** keys, u64** alt, u32** vals, u32** valt, u64 n, u32 bits, u32* hist, u32* scratch,
                          hipStream_t s, bool iota = false);
 

@@ -114,8 +114,10 @@ __global__ __launch_bounds__(G10_BLOCK) void k_pack(const uint4* __restrict__ pe
   out.A[o] = make_uint4(pd.x + 1, pd.y, w.x, w.y);
   out.B[o] = make_uint4(w.z, w.w, (u32)s, (u32)(s >> 32));
   out.id[o] = make_uint2(pd.w, pd.z);
-  fw[o] = w;                                // what the first scoring pass needs, on its own: the two windows and the size
-  fs[o] = s;
+  if (fw) {                                 // what the first scoring pass needs, on its own: the two windows and the size
+    fw[o] = w;
+    fs[o] = s;
+  }
   if (out.ce) out.ce[o] = make_uint2(0u, 0u);        // no value of the clipped area yet
 }
 
@@ -256,9 +258,8 @@ __global__ __launch_bounds__(G10_BLOCK) void k_score_full(const uint4* __restric
 }
 
 // candidates into score order; the tile bound is the largest bound of its members
-__global__ __launch_bounds__(G10_BLOCK) void k_tile_gather(const u32* __restrict__ sorted, const u32* __restrict__ from, u32 n, u32 n_pad,
-                                                          Cands src, Cands dst, u32 tile_shift, u32* __restrict__ tkeys) {
-  const u32 r = blockIdx.x * G10_BLOCK + threadIdx.x;
+__device__ __forceinline__ void tile_gather_at(const u32 r, const u32* __restrict__ sorted, const u32* __restrict__ from, u32 n, u32 n_pad,
+                                               const Cands& src, const Cands& dst, u32 tile_shift, u32* __restrict__ tkeys) {
   if (r >= n_pad) return;
   u32 k = 0;
   if (r < n) {
@@ -282,16 +283,19 @@ __global__ __launch_bounds__(G10_BLOCK) void k_tile_gather(const u32* __restrict
   k = wave_max(k);
   if (lane_id() == 0 && k) atomicMax(&tkeys[r >> tile_shift], k);
 }
+__global__ __launch_bounds__(G10_BLOCK) void k_tile_gather(const u32* __restrict__ sorted, const u32* __restrict__ from, u32 n, u32 n_pad,
+                                                          Cands src, Cands dst, u32 tile_shift, u32* __restrict__ tkeys) {
+  tile_gather_at(blockIdx.x * G10_BLOCK + threadIdx.x, sorted, from, n, n_pad, src, dst, tile_shift, tkeys);
+}
 
 // Re-scores every candidate of the list against the current timelines (all
 // workgroups of the chip; used between launches of the loop kernel to put the
 // candidates back into score order).  Writes the sort key;
 // strikes dead destinations; counts the candidates that can still score.
 template <bool RATIO>
-__global__ __launch_bounds__(G10_BLOCK) void k_rescore(Cands cd, u32 n, const u64* __restrict__ px, const u64* __restrict__ g_base,
-                                                      u32 K, u32 nch, u32 shift_ch, const Ctl* ctl,
-                                                      u32* __restrict__ sortkeys, u32* __restrict__ n_live) {
-  extern __shared__ u64 lb[];                  // [5][nch + 1]
+__device__ __forceinline__ void rescore_block(const Cands& cd, u32 n, const u64* __restrict__ px, const u64* __restrict__ g_base,
+                                              u32 K, u32 nch, u32 shift_ch, const Ctl* ctl,
+                                              u32* __restrict__ sortkeys, u32* __restrict__ n_live, u64* lb, u32* tmp) {
   for (u32 i = threadIdx.x; i < N_ARR * (nch + 1); i += G10_BLOCK) lb[i] = g_base[i];
   __syncthreads();
   PrefixView pv; pv.px = px; pv.base = lb; pv.K = K; pv.nch = nch; pv.shift_ch = shift_ch;
@@ -316,9 +320,46 @@ __global__ __launch_bounds__(G10_BLOCK) void k_rescore(Cands cd, u32 n, const u6
     sortkeys[p] = sort_key(k);
     live += k != 0;
   }
-  __shared__ u32 tmp[G10_WAVES + 1];
   live = block_sum(live, tmp);
   if (threadIdx.x == 0 && live) atomicAdd(n_live, live);
+}
+template <bool RATIO>
+__global__ __launch_bounds__(G10_BLOCK) void k_rescore(Cands cd, u32 n, const u64* __restrict__ px, const u64* __restrict__ g_base,
+                                                      u32 K, u32 nch, u32 shift_ch, const Ctl* ctl,
+                                                      u32* __restrict__ sortkeys, u32* __restrict__ n_live) {
+  extern __shared__ u64 lb[];                  // [5][nch + 1]
+  __shared__ u32 tmp[G10_WAVES + 1];
+  rescore_block<RATIO>(cd, n, px, g_base, K, nch, shift_ch, ctl, sortkeys, n_live, lb, tmp);
+}
+
+// ---- the re-tilings of a round of a batch, all plans in the same launches: job = blockIdx.y ----
+struct TileJob {
+  Cands src, dst;              // the list as the loop left it; the buffer that takes the new order
+  u32 n, n_pad, tile_shift, rank;
+  u32 *sortkeys, *sorted, *from, *tkeys;     // keys out of the re-scoring; keys and old positions in the new order; tile bounds
+  const u64 *px, *g_base;
+  Ctl* ctl;
+  u32 K, nch, shift_ch, pad;
+};
+
+__global__ __launch_bounds__(G10_BLOCK) void k_retile_begin_jobs(const TileJob* __restrict__ jobs) {
+  const TileJob& j = jobs[blockIdx.y];
+  for (u32 i = threadIdx.x; i < NT_MAX; i += G10_BLOCK) j.tkeys[i] = 0u;
+  if (threadIdx.x == 0) j.ctl->n_live = 0u;
+}
+
+__global__ __launch_bounds__(G10_BLOCK) void k_rescore_jobs(const TileJob* __restrict__ jobs) {
+  extern __shared__ u64 lb[];                  // [5][nch + 1], the largest nch of the jobs
+  __shared__ u32 tmp[G10_WAVES + 1];
+  const TileJob j = jobs[blockIdx.y];
+  if (blockIdx.x * G10_BLOCK >= j.n) return;
+  if (j.rank == G10_RANK_RATIO) rescore_block<true>(j.src, j.n, j.px, j.g_base, j.K, j.nch, j.shift_ch, j.ctl, j.sortkeys, &j.ctl->n_live, lb, tmp);
+  else rescore_block<false>(j.src, j.n, j.px, j.g_base, j.K, j.nch, j.shift_ch, j.ctl, j.sortkeys, &j.ctl->n_live, lb, tmp);
+}
+
+__global__ __launch_bounds__(G10_BLOCK) void k_tile_gather_jobs(const TileJob* __restrict__ jobs) {
+  const TileJob j = jobs[blockIdx.y];
+  tile_gather_at(blockIdx.x * G10_BLOCK + threadIdx.x, j.sorted, j.from, j.n, j.n_pad, j.src, j.dst, j.tile_shift, j.tkeys);
 }
 
 // pressure after the plan (lazy adds applied) and its maximum
@@ -335,8 +376,6 @@ __global__ __launch_bounds__(G10_BLOCK) void k_finish(Timelines tl, const u64* _
   if (threadIdx.x == 0) atomicMax((unsigned long long*)peak, (unsigned long long)m);
 }
 
-}  // namespace
-
 // The progress blocks of the plans of a launch, side by side, so that one copy brings them to the host.
 __global__ __launch_bounds__(G10_WAVE) void k_ctl_collect(const LoopArgs* __restrict__ args, Ctl* __restrict__ out) {
   static_assert(sizeof(Ctl) % 8 == 0, "copied as 64-bit words");
@@ -345,18 +384,20 @@ __global__ __launch_bounds__(G10_WAVE) void k_ctl_collect(const LoopArgs* __rest
   for (u32 i = threadIdx.x; i < sizeof(Ctl) / 8; i += G10_WAVE) dst[i] = src[i];
 }
 
+}  // namespace
+
 void plan_work_free(PlanWork* w) {
   if (!w) return;
   if (w->arena) (void)hipFree(w->arena);
   replay_free(w);
-  free(w->h_records);
-  free(w->h_dropped);
-  free(w->h_pressure);
+  if (w->h_block) (void)hipHostFree(w->h_block);
   free(w->h_pf_order); free(w->h_pf_gained); free(w->h_pf_last); free(w->h_pf_pressure);
   for (hipEvent_t e : w->ev) if (e) (void)hipEventDestroy(e);
   delete w;
 }
 
+static const u32 SCORE_SORT_BITS = 23;           // significant bits of a score sort key
+static const u32 SCORE_SORT_PASSES = (SCORE_SORT_BITS + 7) / 8;
 static const u32 PASS_BUDGET = 4096;             // ranking passes per launch of the loop kernel
 #ifndef G10_RETILE_PASSES
 #define G10_RETILE_PASSES 256
@@ -448,10 +489,6 @@ static int work_alloc(g10_plan_s* h, u32 max_chunks, bool cache, PlanWork** slot
   Arena carve;
   carve.base = (char*)q;
   work_layout(w, carve);
-  w->h_records = (g10_migration*)malloc((C ? C : 1) * sizeof(g10_migration));
-  w->h_dropped = (g10_dropped*)malloc((C ? C : 1) * sizeof(g10_dropped));
-  w->h_pressure = (u64*)malloc((u64)K * sizeof(u64));
-  if (!w->h_records || !w->h_dropped || !w->h_pressure) return G10_ENOMEM;
   for (hipEvent_t& e : w->ev) G10_HIP(hipEventCreate(&e));
   return G10_OK;
 }
@@ -470,6 +507,9 @@ struct Inst {
   bool timed_full = false;
   u64 times_check[16] = {};     // the checks of the plan's own durations come back here
   u64 seen_iter = 0;           // passes done at the last re-tiling
+  u32 lead = 0;                // the plan of the batch whose candidate windows this one reads (itself, or an
+                               // earlier plan with the same bandwidths and durations: the windows depend on nothing else)
+  bool fw_done = false;        // (of such a plan) the copy of the windows for the first scoring pass is written or on its way
 };
 
 static PlanWork** work_slot(g10_plan_s* h, u32 i) { return i == 0 ? &h->work : &h->more[i - 1]; }
@@ -491,24 +531,31 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
   if (count > h->loop_args_cap) {
     if (h->loop_args) { G10_HIP(hipStreamSynchronize(s)); (void)hipFree(h->loop_args); h->loop_args = nullptr; h->loop_args_cap = 0; }
     void* q = nullptr;
-    if (hipMalloc(&q, (size_t)count * (sizeof(LoopArgs) + sizeof(Ctl))) != hipSuccess) { (void)hipGetLastError(); return G10_ENOMEM; }
+    if (hipMalloc(&q, (size_t)count * (sizeof(LoopArgs) + sizeof(Ctl) + sizeof(SortJob) + sizeof(TileJob))) != hipSuccess) {
+      (void)hipGetLastError();
+      return G10_ENOMEM;
+    }
     h->loop_args = q; h->loop_args_cap = count;
   }
   Ctl* const ctl_side = (Ctl*)((LoopArgs*)h->loop_args + h->loop_args_cap);    // the progress blocks of a launch, collected
+  SortJob* const sort_jobs = (SortJob*)(ctl_side + h->loop_args_cap);          // the re-tilings of a round of a batch
+  TileJob* const tile_jobs = (TileJob*)(sort_jobs + h->loop_args_cap);
   Inst* I = new (std::nothrow) Inst[count];
   LoopArgs* hargs = (LoopArgs*)malloc((size_t)count * sizeof(LoopArgs));
   Ctl* hctl = (Ctl*)malloc((size_t)count * sizeof(Ctl));
   u32* who = (u32*)malloc((size_t)count * sizeof(u32));                       // the plan of every entry of a launch
+  SortJob* hsj = (SortJob*)malloc((size_t)count * sizeof(SortJob));
+  TileJob* htj = (TileJob*)malloc((size_t)count * sizeof(TileJob));
   // whatever way this function is left, nothing is in flight that reads or writes these host arrays
   struct Guard {
-    g10_plan_s* h; Inst* i; LoopArgs* a; Ctl* c; u32* w;
+    g10_plan_s* h; Inst* i; LoopArgs* a; Ctl* c; u32* w; SortJob* sj; TileJob* tj;
     ~Guard() {
       for (u32 k = 0; k < h->n_aux; ++k) (void)hipStreamSynchronize(h->aux[k]);
       (void)hipStreamSynchronize(h->stream);
-      delete[] i; free(a); free(c); free(w);
+      delete[] i; free(a); free(c); free(w); free(sj); free(tj);
     }
-  } guard{h, I, hargs, hctl, who};
-  if (!I || !hargs || !hctl || !who) return G10_ENOMEM;
+  } guard{h, I, hargs, hctl, who, hsj, htj};
+  if (!I || !hargs || !hctl || !who || !hsj || !htj) return G10_ENOMEM;
 #ifdef G10_PHASE_TIMERS
   double host_ms[8] = {};                                 // wall clock of the host's phases
   auto now_ms = [] { return std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now().time_since_epoch()).count(); };
@@ -603,7 +650,13 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     hipLaunchKernelGGL(k_level1_init, dim3(1), dim3(LB), 0, q, (const u64*)w->g_tot, w->nch, w->base0, w->ctl);
     hipLaunchKernelGGL(k_ot_full, dim3(K / G10_BLOCK + 1), dim3(G10_BLOCK), 0, q, w->otc, (const u64*)w->base0, K, w->nch, w->shift_ch);
     G10_HIP(hipGetLastError());
-    if (C) {      // windows per destination; keep the candidates with at least one valid window
+    x.lead = i;
+    for (u32 j = 0; j < i; ++j) {
+      const g10_params* o = params + j;
+      if (I[j].lead == j && o->dur_ns == p->dur_ns && o->bw_out_Bpus[0] == p->bw_out_Bpus[0] && o->bw_out_Bpus[1] == p->bw_out_Bpus[1] &&
+          o->bw_in_Bpus[0] == p->bw_in_Bpus[0] && o->bw_in_Bpus[1] == p->bw_in_Bpus[1]) { x.lead = j; break; }
+    }
+    if (C && x.lead == i) {      // windows per destination; keep the candidates with at least one valid window
       hipLaunchKernelGGL(k_prep, dim3(gC), dim3(G10_BLOCK), 0, q, (const uint4*)h->per_by_start, (const u64*)h->per_size, w->start, K, w->T, C,
                          (const Ctl*)w->ctl, w->win, w->keep);
       G10_HIP(hipGetLastError());
@@ -613,6 +666,7 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     G10_HIP(hipMemcpyAsync(&hc, w->ctl, sizeof hc, hipMemcpyDeviceToHost, q));
   }
   G10_TRY(sync_all());
+  for (u32 i = 0; i < count; ++i) I[i].n = I[I[i].lead].n;
   G10_HOST_PHASE(0);
 
   // the candidate buffers of a plan; the value cache only where the plan reads the benefit as the clipped area
@@ -657,7 +711,7 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     G10_HIP(hipGetLastError());
     u32 *keys = w->keys, *alt = w->keys_alt;
     u32 *from = w->sv, *from_alt = w->sv_alt;          // where every candidate of the new order stood in the old one
-    G10_TRY(radix_sort_u32_pairs(&keys, &alt, &from, &from_alt, n, 23, w->hist, w->scratch32, q, true));
+    G10_TRY(radix_sort_u32_pairs(&keys, &alt, &from, &from_alt, n, SCORE_SORT_BITS, w->hist, w->scratch32, q, true));
     G10_HIP(hipMemsetAsync(w->tkeys, 0, (u64)NT_MAX * 4, q));
     hipLaunchKernelGGL(k_tile_gather, dim3(x.n_pad / G10_BLOCK), dim3(G10_BLOCK), 0, q, (const u32*)keys, (const u32*)from, n, x.n_pad,
                        cands_of(x, x.cur), cands_of(x, x.cur ^ 1), 8 + x.tsh, w->tkeys);
@@ -666,7 +720,42 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     return G10_OK;
   };
 
-  u32 n_active = 0;
+  // the same for many plans of a batch in the same launches: the jobs are filled plan by plan, then run on the caller's stream
+  struct JobMax { u32 nb = 0, gn = 0, pad = 0, nch = 0; };
+  auto fill_jobs = [&](Inst& x, u32 at, JobMax& m) {      // geometry (tsh, nt, n_pad) set, n > 0; the caller flips x.cur afterwards
+    PlanWork* w = x.w;
+    SortJob& sj = hsj[at];
+    sj.keys = w->keys; sj.alt = w->keys_alt; sj.vals = w->sv; sj.valt = w->sv_alt; sj.hist = w->hist;
+    sj.n = x.n; sj.nb = radix_blocks(x.n);
+    TileJob& tj = htj[at];
+    tj.src = cands_of(x, x.cur); tj.dst = cands_of(x, x.cur ^ 1);
+    tj.n = x.n; tj.n_pad = x.n_pad; tj.tile_shift = 8 + x.tsh; tj.rank = x.p->rank;
+    tj.sortkeys = w->keys; tj.tkeys = w->tkeys;
+    tj.sorted = SCORE_SORT_PASSES & 1u ? w->keys_alt : w->keys; tj.from = SCORE_SORT_PASSES & 1u ? w->sv_alt : w->sv;
+    tj.px = w->px; tj.g_base = w->g_base; tj.ctl = w->ctl; tj.K = K; tj.nch = w->nch; tj.shift_ch = w->shift_ch; tj.pad = 0;
+    const u32 gn = (x.n + G10_BLOCK - 1) / G10_BLOCK;
+    if (sj.nb > m.nb) m.nb = sj.nb;
+    if (gn > m.gn) m.gn = gn;
+    if (x.n_pad > m.pad) m.pad = x.n_pad;
+    if (w->nch > m.nch) m.nch = w->nch;
+  };
+  auto run_jobs = [&](u32 nj, const JobMax& m, bool rescore) -> int {   // rescore: the keys come from a re-scoring of the lists (else they are there)
+    if (!nj) return G10_OK;
+    G10_HIP(hipMemcpyAsync(sort_jobs, hsj, (size_t)nj * sizeof(SortJob), hipMemcpyHostToDevice, s));
+    G10_HIP(hipMemcpyAsync(tile_jobs, htj, (size_t)nj * sizeof(TileJob), hipMemcpyHostToDevice, s));
+    hipLaunchKernelGGL(k_retile_begin_jobs, dim3(1, nj), dim3(G10_BLOCK), 0, s, (const TileJob*)tile_jobs);
+    if (rescore)
+      hipLaunchKernelGGL(k_rescore_jobs, dim3(m.gn > 2048 ? 2048 : m.gn, nj), dim3(G10_BLOCK), (size_t)N_ARR * (m.nch + 1) * 8, s,
+                         (const TileJob*)tile_jobs);
+    G10_HIP(hipGetLastError());
+    G10_TRY(radix_sort_u32_pairs_jobs(sort_jobs, nj, m.nb, SCORE_SORT_BITS, true, s));
+    hipLaunchKernelGGL(k_tile_gather_jobs, dim3(m.pad / G10_BLOCK, nj), dim3(G10_BLOCK), 0, s, (const TileJob*)tile_jobs);
+    G10_HIP(hipGetLastError());
+    return G10_OK;
+  };
+
+  u32 n_active = 0, nj0 = 0;
+  JobMax max0;
   size_t lds_max = 0;
   for (u32 i = 0; i < count; ++i) {
     Inst& x = I[i];
@@ -676,16 +765,49 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     x.max_launches = count == 1 ? (u64)x.n / RETILE_PASSES + 3 : (u64)x.n + 3;   // (a launch by the clock makes a pass at least)
     if (x.hc.done) continue;
     ++n_active;
+    // the windows, and the copy of them the first scoring pass reads, may be another plan's; the first plan
+    // of such a group that gets here writes the copy
+    PlanWork* const lw = I[x.lead].w;
+    const bool writes_fw = !I[x.lead].fw_done;
     if (x.n) {
-      hipLaunchKernelGGL(k_pack, dim3(gC), dim3(G10_BLOCK), 0, stream_of(i), (const uint4*)h->per_by_start, (const u64*)h->per_size, (const uint4*)x.w->win,
-                         (const u32*)x.w->keep, C, cands_of(x, x.cur), x.w->fw, x.w->fs);
+      hipLaunchKernelGGL(k_pack, dim3(gC), dim3(G10_BLOCK), 0, stream_of(i), (const uint4*)h->per_by_start, (const u64*)h->per_size, (const uint4*)lw->win,
+                         (const u32*)lw->keep, C, cands_of(x, x.cur), writes_fw ? lw->fw : (uint4*)nullptr, writes_fw ? lw->fs : (u64*)nullptr);
       G10_HIP(hipGetLastError());
+      if (writes_fw) {
+        I[x.lead].fw_done = true;
+        if (count > 1) G10_HIP(hipEventRecord(lw->ev[2], stream_of(i)));
+      }
     }
-    G10_TRY(retile(x, true, stream_of(i)));
+    if (count == 1) G10_TRY(retile(x, true, s));
+    else {
+      // a batch: every plan's scoring pass on its stream, then the sorts and the tiles of all plans in the same launches
+      PlanWork* w = x.w;
+      x.tsh = tile_shift_for(x.n, x.max_tiles);
+      const u32 tile = UNIT << x.tsh;
+      x.nt = (u32)(((u64)x.n + tile - 1) / tile);
+      x.n_pad = x.nt * tile;
+      if (x.n) {
+        const u32 gn = (x.n + G10_BLOCK - 1) / G10_BLOCK;
+        if (!writes_fw) G10_HIP(hipStreamWaitEvent(stream_of(i), lw->ev[2], 0));         // (recorded when an earlier plan wrote the copy)
+        if (x.p->rank == G10_RANK_RATIO)
+          hipLaunchKernelGGL(k_score_full<true>, dim3(gn), dim3(G10_BLOCK), 0, stream_of(i), (const uint4*)lw->fw, (const u64*)lw->fs, x.n,
+                             (const u64*)w->otc, K, w->keys, (const Ctl*)w->ctl);
+        else
+          hipLaunchKernelGGL(k_score_full<false>, dim3(gn), dim3(G10_BLOCK), 0, stream_of(i), (const uint4*)lw->fw, (const u64*)lw->fs, x.n,
+                             (const u64*)w->otc, K, w->keys, (const Ctl*)w->ctl);
+        G10_HIP(hipGetLastError());
+        fill_jobs(x, nj0, max0);
+        ++nj0;
+        x.cur ^= 1;
+      }
+    }
     const size_t lds = loop_lds_bytes(x.w->nch, x.nt);
     if (lds > lds_max) lds_max = lds;
   }
-  if (count > 1) G10_TRY(sync_all());
+  if (count > 1) {
+    G10_TRY(sync_all());
+    G10_TRY(run_jobs(nj0, max0, false));
+  }
   G10_HOST_PHASE(1);
   if (!h->lds_opt_in && lds_max > 64 * 1024) {
     G10_TRY(loop_allow_large_lds());
@@ -738,6 +860,8 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     for (u32 k = 0; k < na; ++k) I[who[k]].hc = hctl[k];
     G10_HOST_PHASE(4);
     n_active = 0;
+    u32 nj = 0;                                               // the re-tilings of a batch: every plan's in the same launches
+    JobMax mx;
     for (u32 i = 0; i < count; ++i) {
       Inst& x = I[i];
       if (x.hc.done) continue;
@@ -745,12 +869,23 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
       if (x.n > RETILE_MIN_CANDS && x.hc.n_iter - x.seen_iter >= retile_every) {
         x.seen_iter = x.hc.n_iter;
         if (x.counted && x.hc.n_live < x.n) x.n = x.hc.n_live;   // live candidates come first in the list
-        G10_TRY(retile(x, false, stream_of(i)));
+        if (count == 1) G10_TRY(retile(x, false, s));
+        else {
+          x.tsh = tile_shift_for(x.n, x.max_tiles);
+          const u32 tile = UNIT << x.tsh;
+          x.nt = (u32)(((u64)x.n + tile - 1) / tile);
+          x.n_pad = x.nt * tile;
+          if (x.n) {
+            fill_jobs(x, nj, mx);
+            ++nj;
+            x.cur ^= 1;
+          }
+        }
         x.counted = true;
         ++x.retiles;
       }
     }
-    if (count > 1) G10_TRY(sync_all());
+    G10_TRY(run_jobs(nj, mx, true));
     G10_HOST_PHASE(5);
   }
   if (timed_loop) G10_HIP(hipEventRecord(I[0].w->ev[5], s));
@@ -765,6 +900,17 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
                        w->peak_after);
     G10_HIP(hipGetLastError());
     G10_HIP(hipMemcpyAsync(&peaks[i], w->peak_after, 8, hipMemcpyDeviceToHost, s));
+    // the host copies of a plan's results: one block of pinned memory (so the copies run as plain DMA), grown when a plan needs more
+    const size_t need = (size_t)K * 8 + hc.n_mig * sizeof(g10_migration) + hc.n_drop * sizeof(g10_dropped);
+    if (need > w->h_block_bytes) {
+      if (w->h_block) { (void)hipHostFree(w->h_block); w->h_block = nullptr; w->h_block_bytes = 0; }
+      const size_t want = need + need / 4 + 4096;
+      if (hipHostMalloc(&w->h_block, want, hipHostMallocDefault) != hipSuccess) { (void)hipGetLastError(); w->h_block = nullptr; return G10_ENOMEM; }
+      w->h_block_bytes = want;
+    }
+    w->h_pressure = (u64*)w->h_block;
+    w->h_records = (g10_migration*)(w->h_pressure + K);
+    w->h_dropped = (g10_dropped*)(w->h_records + hc.n_mig);
     if (hc.n_mig) G10_HIP(hipMemcpyAsync(w->h_records, w->records, hc.n_mig * sizeof(g10_migration), hipMemcpyDeviceToHost, s));
     if (hc.n_drop) G10_HIP(hipMemcpyAsync(w->h_dropped, w->dropped, hc.n_drop * sizeof(g10_dropped), hipMemcpyDeviceToHost, s));
     G10_HIP(hipMemcpyAsync(w->h_pressure, w->pressure_after, (u64)K * 8, hipMemcpyDeviceToHost, s));

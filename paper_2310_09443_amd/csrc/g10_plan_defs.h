@@ -370,6 +370,8 @@ struct PlanWork {
   bool prefetched = false;      // smart prefetching has run on that plan (pf_gained is valid)
   u64 plan_cap = 0, plan_n_mig = 0;
   // host copies handed out through g10_result
+  void* h_block = nullptr;     // pinned host memory of the three result arrays below
+  size_t h_block_bytes = 0;
   g10_migration* h_records = nullptr;
   g10_dropped* h_dropped = nullptr;
   u64* h_pressure = nullptr;

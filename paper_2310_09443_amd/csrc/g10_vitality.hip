@@ -144,10 +144,10 @@ __device__ __forceinline__ u64 tile_index(u32 r) {
   return (u64)blockIdx.x * TILE + (u64)wave_id() * (G10_WAVE * ITEMS) + (u64)r * G10_WAVE + lane_id();
 }
 
+// The two kernels of a sort pass; blockIdx.x is the tile (the batched forms below put the job in blockIdx.y).
 template <class KT>
-__global__ __launch_bounds__(G10_BLOCK) void k_radix_hist(const KT* __restrict__ keys, u64 P, u32 shift,
-                                                         u32* __restrict__ hist, u32 nblocks) {
-  __shared__ u32 cnt[256];
+__device__ __forceinline__ void radix_hist_tile(const KT* __restrict__ keys, u64 P, u32 shift, u32* __restrict__ hist, u32 nblocks,
+                                                u32* cnt) {
   cnt[threadIdx.x] = 0;
   __syncthreads();
 #pragma unroll
@@ -159,13 +159,18 @@ __global__ __launch_bounds__(G10_BLOCK) void k_radix_hist(const KT* __restrict__
   hist[(u64)threadIdx.x * nblocks + blockIdx.x] = cnt[threadIdx.x];     // digit-major
 }
 
+template <class KT>
+__global__ __launch_bounds__(G10_BLOCK) void k_radix_hist(const KT* __restrict__ keys, u64 P, u32 shift,
+                                                         u32* __restrict__ hist, u32 nblocks) {
+  __shared__ u32 cnt[256];
+  radix_hist_tile<KT>(keys, P, shift, hist, nblocks, cnt);
+}
+
 template <class KT, bool PAIRS>
-__global__ __launch_bounds__(G10_BLOCK) void k_radix_scatter(const KT* __restrict__ keys, KT* __restrict__ out,
-                                                            const u32* __restrict__ vals, u32* __restrict__ vout,
-                                                            u64 P, u32 shift, const u32* __restrict__ offs,
-                                                            u32 nblocks) {
-  __shared__ u32 cnt[G10_WAVES][256];        // per wavefront: running count per digit
-  __shared__ u32 gbase[256];
+__device__ __forceinline__ void radix_scatter_tile(const KT* __restrict__ keys, KT* __restrict__ out,
+                                                   const u32* __restrict__ vals, u32* __restrict__ vout,
+                                                   u64 P, u32 shift, const u32* __restrict__ offs,
+                                                   u32 nblocks, u32 (*cnt)[256], u32* gbase) {
   for (u32 i = threadIdx.x; i < G10_WAVES * 256; i += G10_BLOCK) (&cnt[0][0])[i] = 0;
   __syncthreads();
   const u32 w = wave_id(), l = lane_id();
@@ -214,6 +219,68 @@ __global__ __launch_bounds__(G10_BLOCK) void k_radix_scatter(const KT* __restric
       if (PAIRS) vout[pos] = val[r];
     }
   }
+}
+
+template <class KT, bool PAIRS>
+__global__ __launch_bounds__(G10_BLOCK) void k_radix_scatter(const KT* __restrict__ keys, KT* __restrict__ out,
+                                                            const u32* __restrict__ vals, u32* __restrict__ vout,
+                                                            u64 P, u32 shift, const u32* __restrict__ offs,
+                                                            u32 nblocks) {
+  __shared__ u32 cnt[G10_WAVES][256];        // per wavefront: running count per digit
+  __shared__ u32 gbase[256];
+  radix_scatter_tile<KT, PAIRS>(keys, out, vals, vout, P, shift, offs, nblocks, cnt, gbase);
+}
+
+// ---- many sorts of (32-bit key, 32-bit value) pairs at once: job = blockIdx.y -------------------------
+__global__ __launch_bounds__(G10_BLOCK) void k_radix_hist_jobs(const SortJob* __restrict__ jobs, u32 shift, u32 flip) {
+  __shared__ u32 cnt[256];
+  const SortJob j = jobs[blockIdx.y];
+  if (blockIdx.x >= j.nb) return;
+  radix_hist_tile<u32>(flip ? j.alt : j.keys, j.n, shift, j.hist, j.nb, cnt);
+}
+
+// exclusive scan of a job's 256 * nb counts in place, one workgroup of 1024 threads per job
+__global__ __launch_bounds__(1024) void k_radix_scan_jobs(const SortJob* __restrict__ jobs) {
+  __shared__ u32 wsum[16];
+  __shared__ u32 carry_s;
+  const SortJob j = jobs[blockIdx.y];
+  const u32 total = 256u * j.nb, w = threadIdx.x >> 6, l = threadIdx.x & 63u;
+  u32* h = j.hist;
+  u32 carry = 0;
+  for (u32 base = 0; base < total; base += 4096u) {
+    const u32 i = base + threadIdx.x * 4u;
+    u32 v[4];
+#pragma unroll
+    for (u32 q = 0; q < 4; ++q) v[q] = i + q < total ? h[i + q] : 0u;
+    const u32 mine = v[0] + v[1] + v[2] + v[3];
+    const u32 inc = wave_scan_incl(mine);
+    if (l == 63u) wsum[w] = inc;
+    __syncthreads();
+    if (w == 0) {
+      const u32 x = l < 16u ? wsum[l] : 0u;
+      const u32 xi = wave_scan_incl(x);
+      if (l < 16u) wsum[l] = xi - x;
+      if (l == 15u) carry_s = xi;
+    }
+    __syncthreads();
+    u32 run = carry + wsum[w] + inc - mine;
+#pragma unroll
+    for (u32 q = 0; q < 4; ++q) {
+      if (i + q < total) h[i + q] = run;
+      run += v[q];
+    }
+    carry += carry_s;
+    __syncthreads();                          // wsum and carry_s are read before the next round writes them
+  }
+}
+
+__global__ __launch_bounds__(G10_BLOCK) void k_radix_scatter_jobs(const SortJob* __restrict__ jobs, u32 shift, u32 flip, u32 iota) {
+  __shared__ u32 cnt[G10_WAVES][256];
+  __shared__ u32 gbase[256];
+  const SortJob j = jobs[blockIdx.y];
+  if (blockIdx.x >= j.nb) return;
+  radix_scatter_tile<u32, true>(flip ? j.alt : j.keys, flip ? j.keys : j.alt, iota ? (const u32*)nullptr : (const u32*)(flip ? j.valt : j.vals),
+                                flip ? j.vals : j.valt, j.n, shift, j.hist, j.nb, cnt, gbase);
 }
 
 __global__ __launch_bounds__(G10_BLOCK) void k_flag_distinct(const u64* __restrict__ keys, u64 P, u32* __restrict__ flag) {
@@ -478,6 +545,22 @@ int radix_sort_u32_pairs(u32** keys, u32** alt, u32** vals, u32** valt, u64 n, u
                        iota && shift == 0 ? (const u32*)nullptr : (const u32*)*vals, *valt, n, shift, hist, nb);
     u32* t = *keys; *keys = *alt; *alt = t;
     u32* v = *vals; *vals = *valt; *valt = v;
+  }
+  G10_HIP(hipGetLastError());
+  return G10_OK;
+}
+
+// `njobs` sorts of pairs in the same launches (jobs: device array; max_nb: the largest nb among them).  The
+// sorted pairs of a job end in (keys, vals) after an even number of passes, in (alt, valt) after an odd one;
+// iota: the values are the positions 0..n-1 (vals need not be filled).  Every job has n > 0.
+u32 radix_blocks(u64 n) { return (u32)((n + TILE - 1) / TILE); }
+int radix_sort_u32_pairs_jobs(const SortJob* jobs, u32 njobs, u32 max_nb, u32 bits, bool iota, hipStream_t s) {
+  if (njobs == 0 || max_nb == 0) return G10_OK;
+  u32 flip = 0;
+  for (u32 shift = 0; shift < bits; shift += 8, flip ^= 1u) {
+    hipLaunchKernelGGL(k_radix_hist_jobs, dim3(max_nb, njobs), dim3(G10_BLOCK), 0, s, jobs, shift, flip);
+    hipLaunchKernelGGL(k_radix_scan_jobs, dim3(1, njobs), dim3(1024), 0, s, jobs);
+    hipLaunchKernelGGL(k_radix_scatter_jobs, dim3(max_nb, njobs), dim3(G10_BLOCK), 0, s, jobs, shift, flip, iota && shift == 0 ? 1u : 0u);
   }
   G10_HIP(hipGetLastError());
   return G10_OK;

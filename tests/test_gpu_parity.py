@@ -211,6 +211,31 @@ def test_plan_batch(g10):
     h.close()
 
 
+def test_plan_batch_shared_windows_and_retilings(g10):
+    """Plans of a batch with equal bandwidths and durations share their candidate windows (also when the first
+    of them has nothing to do), and long lists are put back into score order for all plans at once."""
+    w = traces.stress(K=16384, N=120000, seed=5)
+    h, v, args = run_both(g10, w)
+    a, b = (6000, 25000), (3000, 25000)
+    sweep = [dict(gpu_cap=v.peak, host_cap=v.peak // 4, bw_out=a, bw_in=a),            # fits: no pass at all
+             dict(gpu_cap=int(v.peak * 0.3), host_cap=v.peak // 4, bw_out=b, bw_in=b),
+             dict(gpu_cap=int(v.peak * 0.3), host_cap=v.peak // 4, bw_out=a, bw_in=a),
+             dict(gpu_cap=int(v.peak * 0.2), host_cap=v.peak // 8, bw_out=a, bw_in=a),
+             dict(gpu_cap=int(v.peak * 0.25), host_cap=v.peak // 4, bw_out=b, bw_in=b),
+             dict(gpu_cap=int(v.peak * 0.25), host_cap=v.peak // 4, bw_out=b, bw_in=a, rank=1, max_iters=1200)]
+    rs = h.plan_batch(sweep)
+    assert rs[0].status == g10.FITS and rs[0].n_iterations == 0
+    for d, r in zip(sweep, rs):
+        assert_plan_equal(r, v.plan(**d), prefix="max_iters" in d)
+    assert all(r.loop_retiles > 0 for r in rs[1:]), [(r.n_iterations, r.score_full_cands, r.loop_retiles) for r in rs]
+    # the same plans in another order, and alone
+    rs2 = h.plan_batch(sweep[::-1])
+    for r, q in zip(rs, rs2[::-1]):
+        assert r.records.tobytes() == q.records.tobytes() and (r.pressure_after == q.pressure_after).all()
+    assert h.plan(**sweep[3]).records.tobytes() == rs[3].records.tobytes()
+    h.close()
+
+
 def test_plan_with_other_durations(g10):
     """Re-planning under kernel-time noise: a plan made with durations of its own equals the
     oracle's plan of the trace that has these durations, alone and inside a batch, and so does
