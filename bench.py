@@ -52,7 +52,7 @@ def main():
     ap.add_argument("--cpu-passes", type=int, default=0,
                     help="ranking passes of the CPU oracle to time (0 = sized to roughly 15 s)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
-    ap.add_argument("--batch", type=int, default=32,
+    ap.add_argument("--batch", type=int, default=256,
                     help="plans of the extra capacity-sweep measurement with g10_plan_batch (0 or 1: skip)")
     ap.add_argument("--probe", action="store_true",
                     help="counter probe: one 256 MiB device copy (calibration), one analysis and a plan cut after 8 passes")
@@ -178,11 +178,24 @@ def main():
         t0 = time.perf_counter()
         rs = hb.plan_batch(sweep)
         tb = time.perf_counter() - t0
-        hb.close()
         out["batch"] = {"plans": nb, "sweep": "gpu_cap 20..35 % of the peak footprint", "ms": tb * 1e3,
                         "ms_per_plan": tb * 1e3 / nb, "passes": int(sum(x.n_iterations for x in rs)),
                         "candidates_per_s": sum(x.n_cand_evals for x in rs) / tb,
                         "speedup_over_one_by_one": (r.plan_ms * 1e-3 * nb) / tb}
+        # the flash-bandwidth sweep of Section 7 (6.4 to 32 GB/s): no two plans share their candidate windows
+        sweep = []
+        for i in range(nb):
+            f = 6400 + (32000 - 6400) * i // (nb - 1)
+            sweep.append(dict(base, bw_out=(f, w.bw_out_Bpus[1]), bw_in=(f, w.bw_in_Bpus[1])))
+        hb.plan_batch(sweep)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        rs = hb.plan_batch(sweep)
+        tb = time.perf_counter() - t0
+        hb.close()
+        out["batch_bandwidth_sweep"] = {"plans": nb, "sweep": "flash bandwidth 6.4..32 GB/s", "ms": tb * 1e3,
+                                        "ms_per_plan": tb * 1e3 / nb, "passes": int(sum(x.n_iterations for x in rs)),
+                                        "candidates_per_s": sum(x.n_cand_evals for x in rs) / tb}
 
     # re-planning under kernel-time noise (the profiling-error study): the same batch call, every
     # plan on durations of its own; how much of the exact plan survives is reported beside the time
