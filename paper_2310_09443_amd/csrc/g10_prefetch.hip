@@ -6,10 +6,11 @@
 // prefetch can hold the tensor (pressure + size <= capacity); the pressure of
 // the slots gained rises by the tensor's size.  Every step depends on the
 // pressure the earlier ones left, so this is a serial chain like the eviction
-// loop and runs in one workgroup: the pressure in HBM / L2, per chunk a lazy
-// add and the chunk maximum in LDS.  The search asks the chunk maxima which
-// chunk can hold the last slot that cannot take the tensor and scans only that
-// chunk; the update adds lazily to whole chunks and slot by slot at the ends.
+// loop: one wavefront walks it (a workgroup sets the timeline up and finishes
+// it), the pressure in HBM / L2, per chunk a lazy add and the chunk maximum in
+// LDS.  The search asks the chunk maxima which chunk can hold the last slot
+// that cannot take the tensor and scans only that chunk; the update adds
+// lazily to whole chunks and slot by slot at the ends.
 
 #include "g10_plan_defs.h"
 
@@ -29,10 +30,12 @@ __global__ __launch_bounds__(G10_BLOCK) void k_pf_keys(const g10_migration* __re
   order[i] = i;
 }
 
+__device__ __forceinline__ u64 lane_value64(u64 v, u32 l) {      // lane l's v (l the same in the whole wavefront)
+  const u32 lo = (u32)__builtin_amdgcn_readlane((int)(u32)v, (int)l), hi = (u32)__builtin_amdgcn_readlane((int)(u32)(v >> 32), (int)l);
+  return ((u64)hi << 32) | lo;
+}
+
 struct PfShared {
-  unsigned long long cand;    // (upper end << 32 | lower end) of the chunk piece that may hold the last refusing slot
-  u32 found, q;               // a refusing slot was found; its doubled coordinate
-  u32 njobs, pad;
   u64 n_moved, slots;
 };
 
@@ -44,7 +47,6 @@ __global__ __launch_bounds__(LB) void k_eager(const g10_migration* __restrict__ 
   u64* cmax = (u64*)smem;                          // [nch] largest pressure of the chunk (lazy add included)
   u64* ladd = cmax + nch;                          // [nch] added to every slot of the chunk, not yet in E
   PfShared* S = (PfShared*)(ladd + nch);
-  u32* jobs = (u32*)(S + 1);                       // [nch] chunks to rewrite slot by slot
   const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6, CH = 1u << shift_ch;
 
   for (u32 c = wave; c < nch; c += LW) {           // chunk maxima
@@ -60,99 +62,124 @@ __global__ __launch_bounds__(LB) void k_eager(const g10_migration* __restrict__ 
   if (tid == 0) { S->n_moved = 0; S->slots = 0; }
   __syncthreads();
 
-  // the next record is fetched while the current one is worked on
-  u32 r_next = n ? order[0] : 0u;
-  u64 s_next = n ? rec[r_next].size_bytes : 0ull;
-  uint2 ab_next = n ? rec_ab[r_next] : make_uint2(0u, 0u);
-  for (u32 it = 0; it < n; ++it) {
-    const u32 r = r_next;
-    const u64 s = s_next;
-    const u32 a = ab_next.x, b = ab_next.y;
-    if (it + 1 < n) { r_next = order[it + 1]; s_next = rec[r_next].size_bytes; ab_next = rec_ab[r_next]; }
-    u32 p = b + 1;                                 // first slot the tensor is back in
-    // the slot just before the prefetch decides most cases: if it cannot take the tensor, nothing moves
-    const u32 bb = b >= K ? b - K : b;
-    if (s <= cap && E[bb] + ladd[bb >> shift_ch] <= cap - s) {
+  // The chain itself runs in the first wavefront alone: every step waits for the one before, and one wavefront
+  // needs no barrier between them (the others wait at the barrier below; they set up and finish the timeline).
+  // Most prefetches cannot move at all: the slot just before them cannot take the tensor.  That test reads one
+  // slot, and the pressure changes only when a prefetch does move; so 64 records are tested at once, one per
+  // lane; those before the first that passes are done - nothing gained - and only that one takes the search.
+  // (the records of the next 64 are loaded before that search: they do not depend on it)
+  if (wave == 0) {
+    const u32 ncl = (nch + 63u) / 64u;             // chunks per lane: lane, lane + 64, ...
+    u64 n_moved = 0, slots = 0;
+    u32 it = 0;
+    u32 nr = 0, na = 0, nb = 0;
+    u64 nsz = 0;
+    if (lane < n) { nr = order[lane]; nsz = rec[nr].size_bytes; const uint2 ab = rec_ab[nr]; na = ab.x; nb = ab.y; }
+    while (it < n) {
+      const u32 idx = it + lane;
+      bool pass = false;
+      if (idx < n) {
+        const u32 bb = nb >= K ? nb - K : nb;
+        pass = nsz <= cap && E[bb] + ladd[bb >> shift_ch] <= cap - nsz;
+      }
+      const u64 pm = __ballot(pass);
+      const u32 left = n - it < 64u ? n - it : 64u;
+      const u32 f = pm ? (u32)__builtin_ctzll(pm) : left;      // records it .. it + f - 1 stay where they are
+      if (lane < f) { gained[nr] = 0u; last[nr] = nb >= K ? nb - K : nb; }
+      u32 r = 0, a = 0, b = 0;
+      u64 s = 0;
+      if (pm) {
+        r = (u32)__builtin_amdgcn_readlane((int)nr, (int)f);
+        a = (u32)__builtin_amdgcn_readlane((int)na, (int)f);
+        b = (u32)__builtin_amdgcn_readlane((int)nb, (int)f);
+        s = lane_value64(nsz, f);
+      }
+      it += f + (pm ? 1u : 0u);
+      if (it + lane < n) { nr = order[it + lane]; nsz = rec[nr].size_bytes; const uint2 ab = rec_ab[nr]; na = ab.x; nb = ab.y; }
+      if (!pm) continue;
+
+      // the earliest slot from which every slot up to b can hold the tensor: one past the last slot of [a, b]
+      // that cannot.  The chunk maxima say which piece of a chunk may hold it, highest first; that piece is scanned.
       const u64 lim = cap - s;                     // a slot holds the tensor iff its pressure <= lim
       u32 upper = b;                               // the search is still open over [a, upper]
-      p = a;
+      u32 p = a;
       while (true) {
-        if (tid == 0) { S->cand = 0ull; S->found = 0; }
-        __syncthreads();
-        if (tid < nch && cmax[tid] > lim) {        // the two places of the chunk on the doubled timeline
-          const u64 s0 = (u64)tid * CH, s1 = (s0 + CH - 1 < (u64)K - 1) ? s0 + CH - 1 : (u64)K - 1;
+        unsigned long long cd = 0ull;              // (upper end + 1) << 32 | lower end of the highest such piece
+        for (u32 q = 0; q < ncl; ++q) {
+          const u32 c = q * 64u + lane;
+          if (c < nch && cmax[c] > lim) {          // the two places of the chunk on the doubled timeline
+            const u64 s0 = (u64)c * CH, s1 = (s0 + CH - 1 < (u64)K - 1) ? s0 + CH - 1 : (u64)K - 1;
 #pragma unroll
-          for (u32 rep = 0; rep < 2; ++rep) {
-            const u64 o = rep ? K : 0u;
-            const u64 plo = s0 + o > a ? s0 + o : a, phi = s1 + o < upper ? s1 + o : upper;
-            if (plo <= phi) atomicMax(&S->cand, (unsigned long long)(((phi + 1) << 32) | plo));
+            for (u32 rep = 0; rep < 2; ++rep) {
+              const u64 o = rep ? K : 0u;
+              const u64 plo = s0 + o > a ? s0 + o : a, phi = s1 + o < upper ? s1 + o : upper;
+              if (plo <= phi) { const unsigned long long v = ((phi + 1) << 32) | plo; cd = v > cd ? v : cd; }
+            }
           }
         }
-        __syncthreads();
-        const unsigned long long cd = S->cand;
+        cd = wave_max((u64)cd);
         if (cd == 0ull) break;                     // no chunk holds a refusing slot inside [a, upper]
         const u32 hi = (u32)(cd >> 32) - 1u, lo = (u32)cd;
-        if (wave == 0) {                           // the last refusing slot of the piece, if any
-          u32 best = 0;                            // doubled coordinate + 1
-          for (u32 j0 = lo; j0 <= hi; j0 += 64) {
-            const u32 j = j0 + lane;
-            if (j <= hi) {
-              const u32 jj = j >= K ? j - K : j;
-              if (E[jj] + ladd[jj >> shift_ch] > lim) best = j + 1;      // ascending: the last one stays
-            }
-          }
-          best = wave_max(best);
-          if (lane == 0 && best) { S->found = 1; S->q = best - 1; }
-        }
-        __syncthreads();
-        if (S->found) { p = S->q + 1; break; }
-        if (lo == a) break;                        // nothing refuses in [a, upper]
-        upper = lo - 1;
-        __syncthreads();
-      }
-    }
-    __syncthreads();
-    const u32 g = b + 1 - p;
-    if (tid == 0) {
-      gained[r] = g;
-      const u32 nl = b - g;                        // last absent slot left (one before a if none)
-      last[r] = nl >= K ? nl - K : nl;
-      if (g) { S->n_moved += 1; S->slots += g; }
-      S->njobs = 0;
-    }
-    __syncthreads();
-    if (g) {                                       // the slots gained take the tensor
-      if (tid < nch) {
-        u32 len;
-        const u32 cv = cover(tid, CH, K, p, b, len);
-        if (cv == len) { ladd[tid] += s; cmax[tid] += s; }
-        else if (cv) jobs[atomicAdd(&S->njobs, 1u)] = tid;
-      }
-      __syncthreads();
-      const u32 nj = S->njobs;
-      for (u32 jb = wave; jb < nj; jb += LW) {
-        const u32 c = jobs[jb];
-        const u64 lz = ladd[c];
-        u64 m = 0;
-        for (u32 st = 0; st < spt; ++st) {
-          const u32 j0 = c * CH + st * 256u + lane * 4u;
+        u32 best = 0;                              // doubled coordinate + 1 of the last refusing slot of the piece
+        for (u64 j0 = lo; j0 <= hi; j0 += 256) {   // four loads in flight per lane (64-bit counter: hi may be near 2^32)
+          u64 x[4];
 #pragma unroll
           for (u32 i = 0; i < 4; ++i) {
-            const u32 j = j0 + i;
-            if (j < K) {
-              u64 x = E[j];
-              if (in_doubled(j, K, p, b) != NONE32) { x += s; E[j] = x; }
-              x += lz;
-              m = x > m ? x : m;
+            const u64 j = j0 + i * 64u + lane;
+            const u32 jj = j >= K ? (u32)(j - K) : (u32)j;
+            x[i] = j <= hi ? E[jj] + ladd[jj >> shift_ch] : 0ull;
+          }
+#pragma unroll
+          for (u32 i = 0; i < 4; ++i)
+            if (x[i] > lim) best = (u32)j0 + i * 64u + lane + 1;         // ascending: the last one stays
+        }
+        best = wave_max(best);
+        if (best) { p = best; break; }
+        if (lo == a) break;                        // nothing refuses in [a, upper]
+        upper = lo - 1;
+      }
+      const u32 g = b + 1 - p;
+      if (lane == 0) {
+        gained[r] = g;
+        const u32 nl = b - g;                      // last absent slot left (one before a if none)
+        last[r] = nl >= K ? nl - K : nl;
+      }
+      if (g) {                                     // the slots gained take the tensor
+        n_moved += 1; slots += g;
+        for (u32 q = 0; q < ncl; ++q) {
+          const u32 c = q * 64u + lane;
+          u32 len = 0, cv = 0;
+          if (c < nch) cv = cover(c, CH, K, p, b, len);
+          if (cv && cv == len) { ladd[c] += s; cmax[c] += s; }
+          u64 part = __ballot(cv && cv != len);    // chunks the range cuts: slot by slot, the whole wavefront on each
+          while (part) {
+            const u32 cc = q * 64u + (u32)__builtin_ctzll(part);
+            part &= part - 1;
+            const u64 lz = ladd[cc];
+            u64 m = 0;
+            for (u32 st = 0; st < spt; ++st) {
+              const u32 j0 = cc * CH + st * 256u + lane * 4u;
+#pragma unroll
+              for (u32 i = 0; i < 4; ++i) {
+                const u32 j = j0 + i;
+                if (j < K) {
+                  u64 x = E[j];
+                  if (in_doubled(j, K, p, b) != NONE32) { x += s; E[j] = x; }
+                  x += lz;
+                  m = x > m ? x : m;
+                }
+              }
             }
+            m = wave_max(m);
+            if (lane == 0) cmax[cc] = m;
           }
         }
-        m = wave_max(m);
-        if (lane == 0) cmax[c] = m;
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");   // the next tests read the slots just written
       }
-      __syncthreads();
     }
+    if (lane == 0) { S->n_moved = n_moved; S->slots = slots; }
   }
+  __syncthreads();
   // the lazy adds into the slots; the peak
   u64 m = 0;
   for (u32 j = tid; j < K; j += LB) { const u64 x = E[j] + ladd[j >> shift_ch]; E[j] = x; m = x > m ? x : m; }
@@ -185,7 +212,7 @@ int prefetch_run(g10_plan_s* h, g10_prefetch_result* out) {
     G10_HIP(hipGetLastError());
     G10_TRY(radix_sort_u64_pairs(&keys, &alt, &ord, &oalt, n, bits_for(2 * w->T), w->hist, w->scratch32, s));
   }
-  const size_t lds = ((size_t)2 * w->nch * 8 + sizeof(PfShared) + (size_t)w->nch * 4 + 15) & ~(size_t)15;
+  const size_t lds = ((size_t)2 * w->nch * 8 + sizeof(PfShared) + 15) & ~(size_t)15;
   hipLaunchKernelGGL(k_eager, dim3(1), dim3(LB), lds, s, (const g10_migration*)w->records, (const uint2*)w->rec_ab,
                      (const u32*)ord, n, w->pf_pressure, K, w->nch, w->spt, w->shift_ch, w->plan_cap, w->pf_gained, w->pf_last,
                      w->pf_stats);
