@@ -192,8 +192,11 @@ def test_plan_batch(g10):
             sweep.append(dict(gpu_cap=int(v.peak * cap_frac), host_cap=int(v.peak * hfrac), bw_out=bw, bw_in=bw))
     sweep.append(dict(sweep[0], max_iters=37))
     sweep.append(dict(sweep[1], max_tiles=2, max_chunks=3))
+    first = h.plan_batch(sweep[:2])                      # a small batch first: the next one needs more workspaces
     rs = h.plan_batch(sweep)
     assert len(rs) == len(sweep)
+    assert all(x.records.tobytes() == y.records.tobytes() and (x.pressure_after == y.pressure_after).all()
+               for x, y in zip(first, rs))
     for d, r in zip(sweep, rs):
         oa = {k: x for k, x in d.items() if k not in ("max_tiles", "max_chunks")}
         p = v.plan(**oa) if "max_iters" in oa else v.plan(**oa)

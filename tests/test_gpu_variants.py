@@ -133,6 +133,25 @@ def test_batch_mixes_readings(g10):
     h.close()
 
 
+def test_batch_retilings_with_other_readings(g10):
+    """Long lists of a batch are put back into score order for all its plans in the same launches, whatever their
+    reading (the clipped area carries its cached values along); every plan must equal the one made alone, whose
+    lists go through the kernels of a single plan."""
+    w = traces.stress(K=16384, N=120000, seed=5)
+    h, v, args = run_both(g10, w)
+    sweep = [dict(args, gpu_cap=int(v.peak * 0.3), area=1), dict(args, gpu_cap=int(v.peak * 0.25), rank=1, area=1, max_iters=1500),
+             dict(args, gpu_cap=int(v.peak * 0.25)), dict(args, gpu_cap=int(v.peak * 0.2), area=1)]
+    rs = h.plan_batch(sweep)
+    assert all(r.loop_retiles > 0 for r in rs), [(r.n_iterations, r.loop_retiles) for r in rs]
+    for d, r in zip(sweep, rs):
+        q = h.plan(**d)
+        assert (r.status, r.n_iterations, r.n_dropped) == (q.status, q.n_iterations, q.n_dropped)
+        assert r.records.tobytes() == q.records.tobytes() and (r.pressure_after == q.pressure_after).all()
+    p = v.plan(**sweep[2])                                  # the default reading also against the oracle
+    assert_plan_equal(rs[2], p)
+    h.close()
+
+
 def test_unknown_reading_is_an_error(g10):
     w = traces.mlp_tiny()
     h, v, args = run_both(g10, w)
