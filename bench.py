@@ -33,14 +33,19 @@ def counted_hbm_bytes(workload):
         src = open(os.path.join(here, "csrc", "g10_plan.hip")).read()
     except OSError:
         return None
+    # the kernel and the packed form of the copy it reads
     m = re.search(r"__global__ __launch_bounds__\(G10_BLOCK\) void k_score_full\(.*?\n}\n", src, flags=re.S)
-    if not m or hashlib.sha256(m.group(0).encode()).hexdigest() != c["kernel_source_sha256"] or c["workload"] != workload:
+    f = re.search(r"constexpr u32 PACK_END_BITS.*?void unpack_windows\(.*?\n}\n", src, flags=re.S)
+    if not m or not f or c["workload"] != workload:
+        return None
+    if hashlib.sha256((f.group(0) + m.group(0)).encode()).hexdigest() != c["kernel_source_sha256"]:
         return None
     fetch = c["fetch_size_kib"] * c["copy_expected_kib"] / c["copy_fetch_size_kib"]
     write = c["write_size_kib"] * c["copy_expected_kib"] / c["copy_write_size_kib"]
     return (fetch + write) * 1024.0
 BYTES_PER_CAND = 36            # what a scoring pass over a candidate moves by definition: L+1, R, 2 x (a, b) as u32 + size u64
-                               # read, a 4-byte key written (the kernel itself reads a 24-byte copy without L+1 and R)
+                               # read, a 4-byte key written (the kernel itself reads a copy without L+1 and R: 16 bytes
+                               # where the window ends fit 21 bits and the sizes 43, else 24)
 
 
 def main():

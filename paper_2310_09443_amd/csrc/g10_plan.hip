@@ -101,10 +101,26 @@ __global__ __launch_bounds__(G10_BLOCK) void k_prep(const uint4* __restrict__ pe
   keep[c] = any;
 }
 
+// The copy of a candidate for the first scoring pass in 16 bytes instead of 24, where the trace allows it:
+// four window ends of 21 bits (2 K <= 2^21) and a size of 43 bits (no tensor of 8 TiB or more).
+constexpr u32 PACK_END_BITS = 21, PACK_SIZE_BITS = 43;
+static_assert(3 * PACK_END_BITS <= 64 && PACK_END_BITS + PACK_SIZE_BITS == 64, "three ends in one word, the fourth and the size in the other");
+__device__ __forceinline__ uint4 pack_windows(const uint4 w, const u64 s) {
+  const u64 lo = (u64)w.x | ((u64)w.y << PACK_END_BITS) | ((u64)w.z << (2 * PACK_END_BITS));
+  const u64 hi = (u64)w.w | (s << PACK_END_BITS);
+  return make_uint4((u32)lo, (u32)(lo >> 32), (u32)hi, (u32)(hi >> 32));
+}
+__device__ __forceinline__ void unpack_windows(const uint4 q, uint4& w, u64& s) {
+  const u64 lo = ((u64)q.y << 32) | q.x, hi = ((u64)q.w << 32) | q.z;
+  const u32 m = (1u << PACK_END_BITS) - 1u;
+  w = make_uint4((u32)lo & m, (u32)(lo >> PACK_END_BITS) & m, (u32)(lo >> (2 * PACK_END_BITS)) & m, (u32)hi & m);
+  s = hi >> PACK_END_BITS;
+}
+
 // candidates with at least one valid window, packed in the order of their start
 __global__ __launch_bounds__(G10_BLOCK) void k_pack(const uint4* __restrict__ per, const u64* __restrict__ size,
                                                    const uint4* __restrict__ win, const u32* __restrict__ pos, u32 C,
-                                                   Cands out, uint4* __restrict__ fw, u64* __restrict__ fs) {
+                                                   Cands out, uint4* __restrict__ fw, u64* __restrict__ fs, u32 packed) {
   const u32 c = blockIdx.x * G10_BLOCK + threadIdx.x;
   if (c >= C || pos[c + 1] == pos[c]) return;
   const uint4 pd = per[c];                  // {L, R, tensor, period index}
@@ -115,8 +131,11 @@ __global__ __launch_bounds__(G10_BLOCK) void k_pack(const uint4* __restrict__ pe
   out.B[o] = make_uint4(w.z, w.w, (u32)s, (u32)(s >> 32));
   out.id[o] = make_uint2(pd.w, pd.z);
   if (fw) {                                 // what the first scoring pass needs, on its own: the two windows and the size
-    fw[o] = w;
-    fs[o] = s;
+    if (packed) fw[o] = pack_windows(w, s);
+    else {
+      fw[o] = w;
+      fs[o] = s;
+    }
   }
   if (out.ce) out.ce[o] = make_uint2(0u, 0u);        // no value of the clipped area yet
 }
@@ -217,14 +236,17 @@ __device__ __forceinline__ u32 bound_of_sort_key(u32 sk) { return (0x7fffffu - s
 
 // RATIO: ranking by benefit / cost; a window inside the other may then still have the larger
 // key (its transfers can be the shorter ones), so both are looked up.
-template <bool RATIO>
+// PACKED: the copy is the 16-byte form (fs is not read).
+template <bool RATIO, bool PACKED>
 __global__ __launch_bounds__(G10_BLOCK) void k_score_full(const uint4* __restrict__ fw, const u64* __restrict__ fs, u32 n,
                                                          const u64* __restrict__ ot, u32 K,
                                                          u32* __restrict__ sortkeys, const Ctl* __restrict__ ctl) {
   const u32 p = blockIdx.x * G10_BLOCK + threadIdx.x;
   if (p >= n) return;
-  const uint4 W = fw[p];                      // {a0, b0, a1, b1}
-  const u64 s = fs[p];
+  uint4 W = fw[p];                            // {a0, b0, a1, b1}
+  u64 s;
+  if (PACKED) unpack_windows(W, W, s);
+  else s = fs[p];
   const u64 total = ot[K];
   bool v0 = W.x <= W.y, v1 = W.z <= W.w;
   // the prefix is monotone: a window inside the other one cannot hold more over-capacity time
@@ -517,9 +539,16 @@ static PlanWork** work_slot(g10_plan_s* h, u32 i) { return i == 0 ? &h->work : &
 // `count` plans on one analysed trace.  The streaming kernels of the plans run one after the
 // other (each fills the chip); the greedy loops run side by side, one workgroup per plan, in
 // one launch per round; between rounds the long candidate lists are put back into score order.
+typedef void (*ScoreFullKernel)(const uint4*, const u64*, u32, const u64*, u32, u32*, const Ctl*);
+static ScoreFullKernel score_full_kernel(u32 rank, bool packed) {
+  if (packed) return rank == G10_RANK_RATIO ? k_score_full<true, true> : k_score_full<false, true>;
+  return rank == G10_RANK_RATIO ? k_score_full<true, false> : k_score_full<false, false>;
+}
+
 int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_result* outs) {
   hipStream_t s = h->stream;
   const u32 K = h->K;
+  const bool packed = !h->big_size && 2ull * K <= (1ull << PACK_END_BITS);   // the first scoring pass reads 16-byte copies
   const u32 C = (u32)h->n_periods;
   const u32 gC = (C + G10_BLOCK - 1) / G10_BLOCK;
   if (count > 1 + h->n_more) {                             // more workspace slots
@@ -688,12 +717,8 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     if (first) {
       const u32 gn = (n + G10_BLOCK - 1) / G10_BLOCK;
       // the two events take the kernel's own begin and end time stamps
-      if (x.p->rank == G10_RANK_RATIO)
-        hipExtLaunchKernelGGL(k_score_full<true>, dim3(gn), dim3(G10_BLOCK), 0, q, w->ev[2], w->ev[3], 0, (const uint4*)w->fw,
-                              (const u64*)w->fs, n, (const u64*)w->otc, K, w->keys, (const Ctl*)w->ctl);
-      else
-        hipExtLaunchKernelGGL(k_score_full<false>, dim3(gn), dim3(G10_BLOCK), 0, q, w->ev[2], w->ev[3], 0, (const uint4*)w->fw,
-                              (const u64*)w->fs, n, (const u64*)w->otc, K, w->keys, (const Ctl*)w->ctl);
+      hipExtLaunchKernelGGL(score_full_kernel(x.p->rank, packed), dim3(gn), dim3(G10_BLOCK), 0, q, w->ev[2], w->ev[3], 0, (const uint4*)w->fw,
+                            (const u64*)w->fs, n, (const u64*)w->otc, K, w->keys, (const Ctl*)w->ctl);
       x.timed_full = true;
     } else {
       u32 gn = (n + G10_BLOCK - 1) / G10_BLOCK;
@@ -771,7 +796,7 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     const bool writes_fw = !I[x.lead].fw_done;
     if (x.n) {
       hipLaunchKernelGGL(k_pack, dim3(gC), dim3(G10_BLOCK), 0, stream_of(i), (const uint4*)h->per_by_start, (const u64*)h->per_size, (const uint4*)lw->win,
-                         (const u32*)lw->keep, C, cands_of(x, x.cur), writes_fw ? lw->fw : (uint4*)nullptr, writes_fw ? lw->fs : (u64*)nullptr);
+                         (const u32*)lw->keep, C, cands_of(x, x.cur), writes_fw ? lw->fw : (uint4*)nullptr, writes_fw ? lw->fs : (u64*)nullptr, packed ? 1u : 0u);
       G10_HIP(hipGetLastError());
       if (writes_fw) {
         I[x.lead].fw_done = true;
@@ -789,12 +814,8 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
       if (x.n) {
         const u32 gn = (x.n + G10_BLOCK - 1) / G10_BLOCK;
         if (!writes_fw) G10_HIP(hipStreamWaitEvent(stream_of(i), lw->ev[2], 0));         // (recorded when an earlier plan wrote the copy)
-        if (x.p->rank == G10_RANK_RATIO)
-          hipLaunchKernelGGL(k_score_full<true>, dim3(gn), dim3(G10_BLOCK), 0, stream_of(i), (const uint4*)lw->fw, (const u64*)lw->fs, x.n,
-                             (const u64*)w->otc, K, w->keys, (const Ctl*)w->ctl);
-        else
-          hipLaunchKernelGGL(k_score_full<false>, dim3(gn), dim3(G10_BLOCK), 0, stream_of(i), (const uint4*)lw->fw, (const u64*)lw->fs, x.n,
-                             (const u64*)w->otc, K, w->keys, (const Ctl*)w->ctl);
+        hipLaunchKernelGGL(score_full_kernel(x.p->rank, packed), dim3(gn), dim3(G10_BLOCK), 0, stream_of(i), (const uint4*)lw->fw, (const u64*)lw->fs, x.n,
+                           (const u64*)w->otc, K, w->keys, (const Ctl*)w->ctl);
         G10_HIP(hipGetLastError());
         fill_jobs(x, nj0, max0);
         ++nj0;

@@ -239,6 +239,29 @@ def test_plan_batch_shared_windows_and_retilings(g10):
     h.close()
 
 
+@pytest.mark.parametrize("one_beyond", [False, True])
+def test_first_scoring_pass_both_copy_forms(g10, one_beyond):
+    """The first scoring pass reads a 16-byte copy of every candidate when no tensor has 2^43 bytes or more
+    (and 2 K <= 2^21), a 24-byte one otherwise: sizes that use all 43 bits, and the same with one tensor beyond."""
+    w = traces.stress(K=2048, N=20000, seed=9)
+    tr = w.trace
+    size = tr.size_bytes << np.uint64(14)
+    assert (1 << 42) <= int(size.max()) < (1 << 43)
+    if one_beyond:
+        size[int(np.argmax(size))] = 1 << 43
+    big = Trace("sizes", tr.dur_ns, size, tr.is_global, tr.use_kernel, tr.use_tensor)
+    v = O.Vitality(big, O.PREFIX)
+    h = g10.g10_vitality(g10.DeviceTrace(big))
+    assert_vitality_equal(h, v)
+    bw = (6000 << 14, 25000 << 14)
+    args = dict(gpu_cap=int(v.peak * 0.3), host_cap=int(v.peak // 4), bw_out=bw, bw_in=bw)
+    for va in (dict(), dict(rank=1, max_iters=300)):
+        r, p = h.plan(**args, **va), v.plan(**args, **va)
+        assert_plan_equal(r, p, prefix="max_iters" in va)
+        assert "rank" in va or int((p.records["size"] >= (1 << 42)).sum()) > 0      # candidates whose size has bit 42 set
+    h.close()
+
+
 def test_plan_with_other_durations(g10):
     """Re-planning under kernel-time noise: a plan made with durations of its own equals the
     oracle's plan of the trace that has these durations, alone and inside a batch, and so does
