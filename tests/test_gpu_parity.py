@@ -430,6 +430,25 @@ def test_stress_full_size_prefix_and_properties(g10):
     o, g, pr = prefetchcheck.replay_numpy(tr.K, v.start, args["gpu_cap"], r.records, a2, b2, r.pressure_after)
     assert (f.order == o).all() and (f.gained == g).all() and (f.pressure == pr).all()
     assert (f.n_moved, f.slots_gained, f.peak) == (int((g > 0).sum()), int(g.astype(np.uint64).sum()), int(pr.max()))
+    # the sweeps the benchmark times: the same trace planned in batches (capacities that share their candidate
+    # windows; flash bandwidths that do not).  The plan at the default point must be the one above, the others
+    # the ones made alone, and one of each kind is judged by the property checker
+    caps = [int(v.peak * f) for f in (0.20, 0.25, 0.35)] + [args["gpu_cap"]]
+    sweep = [dict(args, gpu_cap=c) for c in caps]
+    for f in (6400, 32000):
+        sweep.append(dict(args, bw_out=(f, args["bw_out"][1]), bw_in=(f, args["bw_in"][1])))
+    rs = h.plan_batch(sweep)
+    assert rs[3].records.tobytes() == r.records.tobytes() and (rs[3].pressure_after == r.pressure_after).all()
+    for d, x in zip(sweep, rs):
+        alone = h.plan(**d)
+        assert (x.status, x.n_iterations, x.n_cand_evals) == (alone.status, alone.n_iterations, alone.n_cand_evals)
+        assert x.records.tobytes() == alone.records.tobytes() and (x.pressure_after == alone.pressure_after).all()
+    for i in (0, 5):
+        d, x = sweep[i], rs[i]
+        mi = plancheck.Machine(d["gpu_cap"], d["host_cap"], d["bw_out"], d["bw_in"])
+        si = sorted(set(np.linspace(0, x.n_iterations - 1, 12).astype(int).tolist()))
+        plancheck.check_plan(tr, mi, x.records, x.null_iters, x.null_cands, x.status, pressure_after=x.pressure_after,
+                             n_iterations=x.n_iterations, n_cand_evals=x.n_cand_evals, greedy=si)
     h.close()
     # the oracle's complete plan, stored as digests (tests/golden/make_config5_digest.py)
     import hashlib
