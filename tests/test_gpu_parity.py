@@ -262,6 +262,57 @@ def test_first_scoring_pass_both_copy_forms(g10, one_beyond):
     h.close()
 
 
+@pytest.mark.parametrize("block", range(4))
+def test_random_batches(g10, block):
+    """Random traces, random batches: capacities, host capacities and bandwidths drawn from small sets (so some
+    plans share their candidate windows and some do not), the readings, pass limits and lowered on-chip limits
+    mixed; every plan against the oracle, then one of them alone with its prefetch pass and its replay."""
+    import random
+    for case in range(12 * block, 12 * block + 12):
+        rnd = random.Random(424200 + case)
+        kind = rnd.choice(["small", "small", "mid", "stress"])
+        if kind == "small":
+            w = traces.random_small(70000 + case, K=rnd.randint(4, 40), N=rnd.randint(3, 30), max_uses=rnd.randint(2, 5))
+        elif kind == "mid":
+            w = traces.random_small(80000 + case, K=rnd.randint(100, 600), N=rnd.randint(50, 800), max_uses=rnd.randint(2, 4))
+        else:
+            w = traces.stress(K=rnd.choice([512, 1024, 3000]), N=rnd.choice([2000, 9000, 20000]), seed=90000 + case)
+        h, v, args = run_both(g10, w)
+        b0 = w.bw_out_Bpus
+        bws = [b0, (max(1, b0[0] // 2), b0[1]), (b0[0], max(1, b0[1] // 3))]
+        sweep = []
+        for _ in range(rnd.randint(2, 7)):
+            bw = rnd.choice(bws)
+            d = dict(gpu_cap=max(1, int(v.peak * rnd.choice([0.1, 0.25, 0.5, 0.8, 1.0, 1.2]))),
+                     host_cap=int(v.peak * rnd.choice([0.0, 0.05, 0.25, 2.0])), bw_out=bw, bw_in=rnd.choice([bw, b0]))
+            if rnd.random() < 0.3:
+                d["rank"] = 1
+            if rnd.random() < 0.3 and kind != "stress":
+                d["area"] = 1
+            if rnd.random() < 0.2:
+                d["max_iters"] = rnd.randint(1, 60)
+            if "rank" in d and kind == "stress" and "max_iters" not in d:
+                d["max_iters"] = 400
+            sweep.append(d)
+        limits = [dict(d) for d in sweep]
+        for d in limits:
+            if rnd.random() < 0.3:
+                d["max_tiles"] = rnd.randint(1, 4)
+            if rnd.random() < 0.3:
+                d["max_chunks"] = rnd.randint(1, 5)
+        for d, r in zip(sweep, h.plan_batch(limits)):
+            p = v.plan(**d)
+            assert_plan_equal(r, p, prefix=p.status == O.TRUNCATED)
+            assert (r.status, r.n_iterations) == (p.status, p.n_iterations), (case, d)
+            assert (r.pressure_after == p.pressure_after).all() and (r.null_cands == p.null_cands).all(), (case, d)
+        r, p = h.plan(**sweep[0]), v.plan(**sweep[0])
+        assert r.records.tobytes() == p.records.tobytes(), (case, sweep[0])
+        assert_prefetch_equal(h.prefetch(), p.prefetch())
+        y, yo = h.replay(eager=True), p.replay(eager=True)
+        assert (y.iter_ns, y.stall_ns, y.n_stalled) == (yo.iter_ns, yo.stall_ns, yo.n_stalled) and (y.late == yo.late).all()
+        h.close()
+
+
 def test_plan_with_other_durations(g10):
     """Re-planning under kernel-time noise: a plan made with durations of its own equals the
     oracle's plan of the trace that has these durations, alone and inside a batch, and so does
