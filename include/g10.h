@@ -209,7 +209,8 @@ int g10_plan(g10_plan_t *handle, const g10_params *params, g10_result *out);
  * workspaces in the handle (about 350 bytes per inactive period): the result arrays of all
  * `count` plans stay valid until the next planning call on the handle.  plan_ms and loop_ms of
  * every result are those of the whole batch.  g10_prefetch afterwards refers to params[0]'s plan.
- * Errors: as g10_plan; also G10_EINVAL for count = 0 or count > 4096. */
+ * Errors: as g10_plan; also G10_EINVAL for count = 0 or count > 4096.  On G10_ENOMEM the workspaces
+ * of the plans after the first are released again and the handle stays usable. */
 int g10_plan_batch(g10_plan_t *handle, const g10_params *params, uint32_t count, g10_result *outs);
 
 /* Result of g10_prefetch; the arrays are host memory owned by the handle, valid until the

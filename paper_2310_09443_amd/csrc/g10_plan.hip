@@ -608,7 +608,13 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     }
     if (!*slot) {
       int rc = work_alloc(h, max_chunks, cache, slot);
-      if (rc) { plan_work_free(*slot); *slot = nullptr; return rc; }
+      if (rc) {
+        // (out of memory, most likely: the workspaces of the other plans of the batch go too, so that a failed
+        // call does not keep the device full; the first plan's stay)
+        plan_work_free(*slot); *slot = nullptr;
+        for (u32 j = 0; j < h->n_more; ++j) { plan_work_free(h->more[j]); h->more[j] = nullptr; }
+        return rc;
+      }
     }
     I[i].w = *slot; I[i].p = p; I[i].max_tiles = clamp_limit(p->max_tiles, NT_MAX);
     (*slot)->planned = false; (*slot)->prefetched = false;
