@@ -703,7 +703,7 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
       }
     }
     PHASE(4);
-    if (tid == 0) {
+    if (tid == LB - G10_WAVE) {                            // (the last wavefront: it has no chunk to classify below)
       const u32 p = S->win.pos;
       a.cd.A[p] = make_uint4(L1, R, 1u, 0u);             // the candidate leaves the live set
       a.cd.B[p] = make_uint4(1u, 0u, (u32)s, (u32)(s >> 32));
