@@ -298,14 +298,14 @@ __device__ __forceinline__ bool better_ratio(u64 hi, u64 lo, u64 cost, u32 cand,
 // covered slots of chunk c by the doubled range [x, y] (x <= y, y - x < K): the chunk's slots
 // appear at [s0, s1] and at [s0 + K, s1 + K] in doubled coordinates
 __device__ __forceinline__ u32 cover(u32 c, u32 ch, u32 K, u32 x, u32 y, u32& len) {
-  const long long s0 = (long long)c * ch, s1 = (s0 + ch - 1 < (long long)K - 1) ? s0 + ch - 1 : (long long)K - 1;
-  len = (u32)(s1 - s0 + 1);
-  const long long X = x, Y = y;
-  long long n1 = (s1 < Y ? s1 : Y) - (s0 > X ? s0 : X) + 1;
-  long long n2 = (s1 + K < Y ? s1 + K : Y) - (s0 + K > X ? s0 + K : X) + 1;
-  if (n1 < 0) n1 = 0;
-  if (n2 < 0) n2 = 0;
-  return (u32)(n1 + n2);
+  // (all coordinates are below 2 K < 2^32, so 32-bit arithmetic does; an empty range, y = x - 1, covers nothing)
+  const u32 s0 = c * ch, s1 = s0 + ch - 1 < K - 1 ? s0 + ch - 1 : K - 1;
+  len = s1 - s0 + 1;
+  u32 lo = s0 > x ? s0 : x, hi = s1 < y ? s1 : y;
+  u32 n = hi >= lo ? hi - lo + 1 : 0u;
+  lo = s0 + K > x ? s0 + K : x; hi = s1 + K < y ? s1 + K : y;
+  n += hi >= lo ? hi - lo + 1 : 0u;
+  return n;
 }
 
 // first plain slot of [s0, s1] inside the doubled range [x, y] (y - x < K), or NONE32
