@@ -11,22 +11,43 @@ namespace {
 
 #ifdef G10_PHASE_TIMERS
 #define PHASE(i) do { if (tid == 0) { const u64 now_ = wall_clock64(); S->phase[i] += now_ - S->t_last; S->t_last = now_; } } while (0)
+#define STAT(i) do { atomicAdd((unsigned long long*)&S->phase[i], 1ull); } while (0)
 #else
 #define PHASE(i) do { } while (0)
+#define STAT(i) do { } while (0)
 #endif
 
 struct Winner {               // what a commit needs of the winning candidate
   u64 hi, lo;                 // benefit
   u64 cost;                   // eviction + prefetch time (ranking by benefit / cost only)
   u64 s, fo_base, fi_end;     // size; free out-channel time before L1; free in-channel time before R
+  u64 tau_o, tau_i;           // eviction and prefetch time to the destination
   u32 cand, tensor, pos, dest, L1, R, a, b;
-  u32 exact, pad;             // clipped-area benefit only: the value was computed in this pass (else it is a bound)
+  u32 exact;                  // clipped-area benefit only: the value was computed in this pass (else it is a bound)
+  u32 kU;                     // key of the larger of the two destinations' benefits: bounds every later benefit
+  u32 kr;                     // kU if the policy sends the candidate to flash while host could take it too (a flash
+                              // reservation in its transfer windows would move it to host, where its benefit may be
+                              // larger), else 0
+  u32 pad;
 };
 
+constexpr u32 MAXM = 8;       // migrations committed in one ranking pass at most
+#ifndef G10_MC_GSMIN
+#define G10_MC_GSMIN 5
+#endif
+constexpr u32 MC_GUESS_SHIFT_MIN = G10_MC_GSMIN;   // the widest margin of a pass's first threshold under the last benefit: 2^-this
+constexpr u32 LIST_MAX = 64;  // candidates of a pass that are looked at for the second and later migrations
+
 struct Shared {               // small per-pass state of the loop workgroup
-  Winner win;                 // winner of the pass (hi = lo = 0: none)
+  Winner mem[MAXM];           // migrations of the pass in commit order; [0] is the winner of the ranking (hi = lo = 0: none)
   Winner wave_win[LW];        // best of every wavefront
-  u64 tau_o, tau_i;
+  Winner list[LIST_MAX];      // the other candidates whose bound exceeds every bound not looked at one by one
+  u32 wave_f2[LW];            // per wavefront: largest bound among the candidates its threads scored but do not hold
+  u32 F2, Fx;                 // ... over the workgroup; largest bound of the candidates that found no room in the list
+  u32 nlist, m0, cut, need_exact;   // list length; migrations selected; how many of them may be committed; the winner's
+                              // host-capacity test needs the exact per-slot maximum
+  u32 by_floor, m;            // the selection ended because the next candidate did not clear the floor; migrations being committed
+  u32 sel[MAXM];              // list entries picked, in order
   u64 hq;                     // host-capacity query: maximum over the period
   u64 acc[3];                 // clipped area being summed: bits 0..31, 32..63 and 64.. of the terms, added apart
   u64 evals, refused;         // clipped areas computed; of those, how many came out below the bound
@@ -38,7 +59,7 @@ struct Shared {               // small per-pass state of the loop workgroup
   u32 thr_key, status, done, stop;
   u32 gshift, pad2;
   u64 t_start;
-  u64 phase[12], t_last;
+  u64 phase[32], t_last;
 };
 
 // The lane of the wavefront holding the best (benefit, lowest index), or NONE32
@@ -90,6 +111,12 @@ __device__ __forceinline__ u32 wave_best_lane_ratio(u64 hi, u64 lo, u64 cost, u3
   return p;
 }
 
+// Do the doubled slot ranges [x1, y1] and [x2, y2] (each shorter than K) share a kernel slot?
+__device__ __forceinline__ bool cyc_overlap(u32 x1, u32 y1, u32 x2, u32 y2, u32 K) {
+  const u64 p = x1, q = y1, r = x2, t = y2, k = K;
+  return (p <= t && r <= q) || (p + k <= t && r <= q + k) || (p <= t + k && r + k <= q);
+}
+
 template <bool RATIO>
 __device__ __forceinline__ u32 best_lane(u64 hi, u64 lo, u64 cost, u32 cand) {
   if (RATIO) return wave_best_lane_ratio(hi, lo, cost, cand);
@@ -98,6 +125,11 @@ __device__ __forceinline__ u32 best_lane(u64 hi, u64 lo, u64 cost, u32 cand) {
 
 template <bool RATIO, bool CLIP>
 __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans) {
+  // Several migrations per ranking pass (ranking by the benefit itself, band reading): after the
+  // winner, the next best candidates of the same pass are committed with it as long as it is
+  // certain that each would have won the pass after the one before it - see "more migrations
+  // of the same pass" below.
+  constexpr bool MC = !RATIO && !CLIP;
   extern __shared__ __align__(16) unsigned char smem[];
   const LoopArgs a = plans[blockIdx.x];        // one workgroup per plan
   const Timelines tl = a.tl;
@@ -113,8 +145,8 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
   Shared* S = (Shared*)(scr + 4 * LW);
   u32* keys = (u32*)(S + 1);                            // [nt]  bound of every tile
   u32* skeys = keys + nt;                               // [ns]  largest bound of every group of 64 tiles
-  u32* jobs = skeys + ns;                               // [4 * nch + 8]
-  unsigned short* tlist = (unsigned short*)(jobs + 4 * nch + 8);   // [nt]  the hot list
+  u32* jobs = skeys + ns;                               // [8 * nch + 8]
+  unsigned short* tlist = (unsigned short*)(jobs + 8 * nch + 8);   // [nt]  the hot list
   unsigned short* alist = tlist + nt;                            // [nt]  tiles scored in the current round
 
   const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
@@ -135,8 +167,8 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
     S->gshift = ctl->gshift ? ctl->gshift : GUESS_SHIFT;
     S->nl = 0; S->restL = NONE32; S->stale_hot = 0;
     S->stop = 0; S->t_start = wall_clock64();
-    S->win.hi = 0; S->win.lo = 0;
-    for (u32 i = 0; i < 12; ++i) S->phase[i] = 0;
+    S->mem[0].hi = 0; S->mem[0].lo = 0;
+    for (u32 i = 0; i < 32; ++i) S->phase[i] = 0;
     S->t_last = wall_clock64();
   }
   __syncthreads();
@@ -246,7 +278,8 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
   u32 pass_units = 0;           // units of 256 candidates scored in the current pass (the same in every thread)
   // this thread's best candidate of the pass
   Winner mine;
-  mine.hi = 0; mine.lo = 0; mine.cost = 1; mine.cand = NONE32; mine.exact = 0;
+  mine.hi = 0; mine.lo = 0; mine.cost = 1; mine.cand = NONE32; mine.exact = 0; mine.kU = 0; mine.kr = 0; mine.tau_o = 0; mine.tau_i = 0; mine.pad = 0;
+  u32 floor2 = 0;               // largest bound among the candidates this thread scored in the pass other than `mine`
   u32 cur_iter = 0;             // number of the current pass (the stamp of the values computed in it)
 
   struct CandV { uint4 A, B; uint2 id; u32 p, t; };
@@ -262,7 +295,7 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
   // candidate's record already in flight.  One workgroup has one texture
   // unit, about one cache line per clock: lanes whose candidate is dead load
   // nothing, and struck destinations are written back so later passes skip them.
-  auto score_list = [&]() {
+  auto score_list = [&](const u32 thr_pub) {
     const u32 nunits = S->ntl << a.tshift;
     PrefixView pv; pv.px = tl.px; pv.base = base; pv.K = K; pv.nch = nch; pv.shift_ch = tl.shift_ch;
     Machine mc; mc.bwo0 = bwo0; mc.bwo1 = bwo1; mc.bwi0 = bwi0; mc.bwi1 = bwi1;
@@ -310,15 +343,35 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
       }
       const u32 k = wave_max(kc);
       if (lane == 0 && k) atomicMax(&keys[cur.t], k);
-      if (rr.ok0 || rr.ok1) {                      // flash first; host only if flash cannot take it
-        const u32 d = rr.ok0 ? 0u : 1u;
-        const u64 hi = d ? rr.h1 : rr.h0, lo = d ? rr.l1 : rr.l0, cost = d ? c1 : c0;
-        if ((hi | lo) != 0 && (RATIO ? better_ratio(hi, lo, cost, cur.id.x, mine.hi, mine.lo, mine.cost, mine.cand)
-                                     : better(hi, lo, cur.id.x, mine.hi, mine.lo, mine.cand))) {
-          mine.hi = hi; mine.lo = lo; mine.cost = cost; mine.cand = cur.id.x; mine.tensor = cur.id.y; mine.pos = cur.p; mine.dest = d;
-          mine.L1 = A.x; mine.R = A.y; mine.a = d ? B.x : A.z; mine.b = d ? B.y : A.w; mine.s = ((u64)B.w << 32) | B.z;
-          mine.fo_base = rr.fo_L; mine.fi_end = rr.fi_R; mine.exact = exact;
+      // flash first; host only if flash cannot take it
+      const bool ok_any = rr.ok0 || rr.ok1;
+      const u32 d = rr.ok0 ? 0u : 1u;
+      const u64 hi = ok_any ? (d ? rr.h1 : rr.h0) : 0ull, lo = ok_any ? (d ? rr.l1 : rr.l0) : 0ull, cost = d ? c1 : c0;
+      if (MC) {
+        // every candidate whose bound reaches the round's threshold goes on the list of the pass
+        // with all a commit needs; the others count with their bound only (floor2)
+        const bool pub = kc >= thr_pub && kc != 0u;
+        const u64 pm = __ballot(pub);
+        u32 slot = NONE32;
+        if (pm) {
+          const u32 leader = (u32)__builtin_ctzll(pm);
+          u32 off = 0;
+          if (lane == leader) off = atomicAdd(&S->nlist, (u32)__popcll(pm));
+          off = (u32)__builtin_amdgcn_readlane((int)off, (int)leader);
+          slot = off + (u32)__popcll(pm & ((1ull << lane) - 1ull));
         }
+        if (pub && slot < LIST_MAX) {
+          Winner& e = S->list[slot];
+          e.hi = hi; e.lo = lo; e.cost = cost; e.cand = cur.id.x; e.tensor = cur.id.y; e.pos = cur.p; e.dest = d;
+          e.L1 = A.x; e.R = A.y; e.a = d ? B.x : A.z; e.b = d ? B.y : A.w; e.s = ((u64)B.w << 32) | B.z;
+          e.fo_base = rr.fo_L; e.fi_end = rr.fi_R; e.exact = 0; e.kU = kc; e.kr = (rr.ok0 && rr.ok1) ? kc : 0u;
+        } else if (kc > floor2) floor2 = kc;
+      }
+      if ((hi | lo) != 0 && (RATIO ? better_ratio(hi, lo, cost, cur.id.x, mine.hi, mine.lo, mine.cost, mine.cand)
+                                   : better(hi, lo, cur.id.x, mine.hi, mine.lo, mine.cand))) {
+        mine.hi = hi; mine.lo = lo; mine.cost = cost; mine.cand = cur.id.x; mine.tensor = cur.id.y; mine.pos = cur.p; mine.dest = d;
+        mine.L1 = A.x; mine.R = A.y; mine.a = d ? B.x : A.z; mine.b = d ? B.y : A.w; mine.s = ((u64)B.w << 32) | B.z;
+        mine.fo_base = rr.fo_L; mine.fi_end = rr.fi_R; mine.exact = exact;
       }
       u = un;
       cur = nxt;
@@ -332,6 +385,10 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
     const u32 bl = best_lane<RATIO>(mine.hi, mine.lo, mine.cost, mine.cand);
     if (bl == NONE32) { if (lane == 0) { S->wave_win[wave].hi = 0; S->wave_win[wave].lo = 0; S->wave_win[wave].cost = 1; S->wave_win[wave].cand = NONE32; } }
     else if (lane == bl) S->wave_win[wave] = mine;
+    if (MC) {
+      const u32 f2 = wave_max(floor2);
+      if (lane == 0) S->wave_f2[wave] = f2;
+    }
     __syncthreads();                               // all tile bounds and wavefront winners are in LDS
     const u32 ntl = S->ntl;
     for (u32 i = wave - 1; wave && i < ntl; i += LW - 1) {   // bounds of the groups that hold re-scored tiles
@@ -344,25 +401,31 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
       u32 c = NONE32;
       if (lane < LW) { h = S->wave_win[lane].hi; l = S->wave_win[lane].lo; cs = S->wave_win[lane].cost; c = S->wave_win[lane].cand; }
       const u32 w = best_lane<RATIO>(h, l, cs, c);
-      if (w == NONE32) { if (lane == 0) { S->win.hi = 0; S->win.lo = 0; } }
+      if (MC) {
+        const u32 f2 = wave_max(lane < LW ? S->wave_f2[lane] : 0u);
+        if (lane == 0) S->F2 = f2;
+      }
+      if (w == NONE32) { if (lane == 0) { S->mem[0].hi = 0; S->mem[0].lo = 0; } }
       else {
         if (lane == 0) {
-          S->win = S->wave_win[w];
-          S->tau_o = ceil_div_x1000(S->wave_win[w].s, S->wave_win[w].dest ? bwo1 : bwo0, S->wave_win[w].dest ? ivo1 : ivo0);
+          S->mem[0] = S->wave_win[w];
+          S->mem[0].tau_o = ceil_div_x1000(S->wave_win[w].s, S->wave_win[w].dest ? bwo1 : bwo0, S->wave_win[w].dest ? ivo1 : ivo0);
         }
-        if (lane == 1) S->tau_i = ceil_div_x1000(S->wave_win[w].s, S->wave_win[w].dest ? bwi1 : bwi0, S->wave_win[w].dest ? ivi1 : ivi0);
+        if (lane == 1) S->mem[0].tau_i = ceil_div_x1000(S->wave_win[w].s, S->wave_win[w].dest ? bwi1 : bwi0, S->wave_win[w].dest ? ivi1 : ivi0);
       }
     }
     __syncthreads();
   };
 
   // ---- chunk jobs: one wavefront rewrites one chunk of one array ------------------------
+  // (a job word: migration of the pass << 20 | kind << 16 | chunk)
   auto run_jobs = [&]() {
     const u32 nj = S->njobs;
-    const u32 d = S->win.dest, L1 = S->win.L1, R = S->win.R, wa = S->win.a, wb = S->win.b;
-    const u64 s = S->win.s, tau_o = S->tau_o, tau_i = S->tau_i, fo_base = S->win.fo_base, fi_end = S->win.fi_end;
     for (u32 jb = wave; jb < nj; jb += LW) {
-      const u32 type = jobs[jb] >> 16, c = jobs[jb] & 0xffffu;
+      const u32 type = (jobs[jb] >> 16) & 15u, c = jobs[jb] & 0xffffu;
+      const Winner& M = S->mem[jobs[jb] >> 20];
+      const u32 d = M.dest, L1 = M.L1, R = M.R, wa = M.a, wb = M.b;
+      const u64 s = M.s, tau_o = M.tau_o, tau_i = M.tau_i, fo_base = M.fo_base, fi_end = M.fi_end;
       const u32 s0 = c * CH;
       if (type == J_FO || type == J_FI) {
         // channel time of the window is taken from this chunk's slots; the free-time prefix
@@ -416,9 +479,21 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
         }
         if (lane == 0) tot[(u64)arr * nch + c] = carry;
       } else if (type == J_P_PART || type == J_P_FULL) {
-        // pressure of the chunk's slots; where a slot drops under the capacity the
-        // over-capacity prefix after it is rewritten
+        // pressure of the chunk's slots, for all migrations of the pass at once: the ones whose
+        // absent window cuts the chunk are taken off slot by slot (the ones that cover it whole
+        // went into the lazy add); where a slot drops under the capacity the over-capacity prefix
+        // after it is rewritten
+        const u32 mm = S->m;
         const u64 lz = lazyP[c];
+        u64 lz_full = 0;
+        u32 part = 0;                                    // migrations whose window cuts the chunk
+        for (u32 q = 0; q < mm; ++q) {
+          u32 len = 0;
+          const u32 cv = cover(c, CH, K, S->mem[q].a, S->mem[q].b, len);
+          if (cv == len) lz_full += S->mem[q].s;
+          else if (cv) part |= 1u << q;
+        }
+        const u64 lz0 = lz - lz_full;                    // the lazy add before this pass
         u64 mn = NONE64;
         u32 first = NONE32;                              // first slot that dropped under the capacity
         for (u32 st = 0; st < tl.spt; ++st) {
@@ -429,9 +504,13 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
             const u32 j = j0 + i;
             if (j < K) {
               u64 p = tl.P[j];
-              const bool hit = type == J_P_PART && in_doubled(j, K, wa, wb) != NONE32;
-              const u64 before = p - lz + (type == J_P_FULL ? s : 0ull);     // pressure before this eviction
-              if (hit) { p -= s; tl.P[j] = p; }
+              const u64 before = p - lz0;                // pressure before this pass
+              u64 sub = 0;
+              for (u32 pb = part; pb; pb &= pb - 1) {
+                const Winner& W = S->mem[__builtin_ctz(pb)];
+                if (in_doubled(j, K, W.a, W.b) != NONE32) sub += W.s;
+              }
+              if (sub) { p -= sub; tl.P[j] = p; }
               const u64 act = p - lz;
               if (act > cap) mn = act < mn ? act : mn;
               else if (before > cap && myfirst == NONE32) myfirst = j;
@@ -532,9 +611,9 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
   // then listed again (alist) and must be ranked once more.
   auto settle = [&]() -> bool {
     __syncthreads();
-    if ((S->win.hi | S->win.lo) == 0 || S->win.exact) return true;
-    const u32 wa = S->win.a, wb = S->win.b;
-    const u64 s = S->win.s;
+    if ((S->mem[0].hi | S->mem[0].lo) == 0 || S->mem[0].exact) return true;
+    const u32 wa = S->mem[0].a, wb = S->mem[0].b;
+    const u64 s = S->mem[0].s;
     if (tid == 0) { S->acc[0] = 0; S->acc[1] = 0; S->acc[2] = 0; S->njobs = 0; }
     __syncthreads();
     if (tid < nch) {
@@ -559,16 +638,16 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
     __syncthreads();
     const u64 a0 = S->acc[0], a1 = S->acc[1], a2 = S->acc[2];
     const u64 vlo = a0 + (a1 << 32), vhi = a2 + (a1 >> 32) + (vlo < a0 ? 1ull : 0ull);
-    const bool same = vhi == S->win.hi && vlo == S->win.lo;
+    const bool same = vhi == S->mem[0].hi && vlo == S->mem[0].lo;
     __syncthreads();                                   // everyone has read the sums and the bound
     if (tid == 0) {
       S->evals += 1;
       S->njobs = 0;
-      if (same) S->win.exact = 1;
+      if (same) S->mem[0].exact = 1;
       else {
         S->refused += 1;
-        a.cd.cv[S->win.pos] = make_uint4((u32)vlo, (u32)(vlo >> 32), (u32)vhi, (u32)(vhi >> 32));
-        a.cd.ce[S->win.pos] = make_uint2(cur_iter, 1u | (S->win.dest << 1));
+        a.cd.cv[S->mem[0].pos] = make_uint4((u32)vlo, (u32)(vlo >> 32), (u32)vhi, (u32)(vhi >> 32));
+        a.cd.ce[S->mem[0].pos] = make_uint2(cur_iter, 1u | (S->mem[0].dest << 1));
         S->ntl = 0;
       }
     }
@@ -596,7 +675,11 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
     if (max_iter && S->n_iter >= max_iter) { if (tid == 0) { S->done = 1; S->status = G10_TRUNCATED; } break; }
     if (passes >= a.pass_budget || S->stop) break;
     ++passes;
-    mine.hi = 0; mine.lo = 0; mine.cost = 1; mine.cand = NONE32; mine.exact = 0;
+#ifdef G10_PHASE_TIMERS
+    if (tid == 0) S->phase[11] += 1;
+#endif
+    mine.hi = 0; mine.lo = 0; mine.cost = 1; mine.cand = NONE32; mine.exact = 0; mine.kU = 0; mine.kr = 0;
+    floor2 = 0;
     pass_units = 0;
     u32 thr = S->thr_key ? S->thr_key : NONE32;
     __syncthreads();                               // the loop conditions and thr are read
@@ -604,7 +687,8 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
     if (tid == 0) {
       S->n_iter += 1; S->n_evals += C - S->n_mig - S->n_drop;
       S->hq = 0; S->njobs = 0; S->ot_changed = 0;
-      S->win.hi = 0; S->win.lo = 0;
+      S->mem[0].hi = 0; S->mem[0].lo = 0;
+      S->nlist = 0; S->Fx = 0; S->F2 = 0; S->cut = MAXM; S->need_exact = 0; S->m0 = 1; S->by_floor = 0; S->m = 1;
       if (S->stale_hot) { S->restL = NONE32; S->stale_hot = 0; }
       if (a.tick_budget && wall_clock64() - S->t_start > a.tick_budget) S->stop = 1;
     }
@@ -614,7 +698,7 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
     // rank: score the hot tiles whose bound reaches a threshold (first a guess a little under
     // the last benefit), lower the threshold to the best benefit found, repeat until no tile
     // left out could hold an equal or better candidate
-    u32 rounds = 0;
+    u32 rounds = 0, rest_final = 0;
     bool again = false;                          // CLIP: the listed tiles are the ones already scored in this pass
     while (true) {
       u32 rest;
@@ -630,7 +714,7 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
         const u32 ntl = S->ntl;
         rest = S->restL > S->filt ? S->restL : S->filt;
         if (ntl == 0) {
-          if ((rounds && (S->win.hi | S->win.lo) != 0) || rest == 0) decided = true;   // nothing left that could win
+          if ((rounds && (S->mem[0].hi | S->mem[0].lo) != 0) || rest == 0) decided = true;   // nothing left that could win
           else {
             thr = rest;                                  // strictly lower than before: start from the largest bound left
             __syncthreads();
@@ -644,12 +728,12 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
       }
       if (!decided) {
         PHASE(0);
-        score_list();
+        score_list(thr);
         PHASE(1);
         reduce_best();
         PHASE(2);
         ++rounds;
-        const u32 kb = key_dn_of<RATIO>(S->win.hi, S->win.lo, S->win.cost);
+        const u32 kb = key_dn_of<RATIO>(S->mem[0].hi, S->mem[0].lo, S->mem[0].cost);
         const u32 need = kb ? kb : 1u;
         if (rest < need) decided = true;                 // every tile left out is below the best found
         else {
@@ -660,15 +744,262 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
           continue;
         }
       }
+      rest_final = rest;
       if (!CLIP || settle()) break;
       again = true;
     }
     PHASE(3);
 
-    const bool none = (S->win.hi | S->win.lo) == 0;
-    const u32 d = S->win.dest, L1 = S->win.L1, R = S->win.R, wa = S->win.a, wb = S->win.b;
-    const u64 s = S->win.s;
+    const bool none = (S->mem[0].hi | S->mem[0].lo) == 0;
+    const u32 d = S->mem[0].dest, L1 = S->mem[0].L1, R = S->mem[0].R, wa = S->mem[0].a, wb = S->mem[0].b;
+    const u64 s = S->mem[0].s;
     if (none) { __syncthreads(); if (tid == 0) { S->done = 1; S->status = G10_RESIDUAL; } break; }
+
+    if constexpr (MC) {
+      // ---- more migrations of the same pass -------------------------------------------------
+      // The ranking also tells which candidate comes second, third, ...: candidate w_j wins the
+      // pass after w_1 .. w_(j-1) were committed if (1) nothing those commits change enters its
+      // own score - no slot drops under the capacity, and no two of them reserve channel time or
+      // rewrite slots in the same chunk of the same timeline - and (2) no other candidate can
+      // have risen above it.  Pressure only falls and reservations only grow, so a benefit rises
+      // in one case only: a candidate the policy sends to flash, with a host window as well,
+      // loses its flash window to a reservation and moves to host.  Such a candidate is at risk
+      // once a committed flash migration's transfer windows meet its own; it then counts with the
+      // bound of its host benefit.  Every candidate not looked at one by one (tiles left out, a
+      // thread's second best, the overflow of the list) counts with its bound, the floor F.
+      if (wave == LW - 1) {                            // one wavefront picks them in order, a list entry per lane
+        const u32 nl_ = S->nlist, n = nl_ < LIST_MAX ? nl_ : LIST_MAX;
+        const u32 F = rest_final > S->F2 ? rest_final : S->F2;
+        const bool have = lane < n;
+        Winner e;
+        if (have) e = S->list[lane];
+        else { e.hi = 0; e.lo = 0; e.cand = NONE32; e.dest = 1; e.kr = 0; e.L1 = 0; e.R = 0; e.a = 0; e.b = 0; e.s = 0; }
+        bool picked = have && e.cand == S->mem[0].cand;  // a migration of this pass already
+        u32 kB = (have && !picked) ? upkey(e.hi, e.lo) : 0u;     // (0: cannot be picked)
+        bool risky = false;                              // a committed flash migration's transfer windows meet this entry's
+        auto risk = [&](u32 wL1, u32 wa, u32 wb, u32 wR) {
+          if (have && !picked && e.dest == 0u && e.kr != 0u && !risky)
+            risky = cyc_overlap(e.L1, e.a - 1, wL1, wa - 1, K) || cyc_overlap(e.b + 1, e.R - 1, wb + 1, wR - 1, K);
+        };
+        if (S->mem[0].dest == 0u) risk(S->mem[0].L1, S->mem[0].a, S->mem[0].b, S->mem[0].R);
+        u32 mmax = MAXM;
+        if (max_iter && max_iter - S->n_iter + 1 < mmax) mmax = (u32)(max_iter - S->n_iter + 1);   // (n_iter counts this pass already)
+        u32 m = 1, by_floor = 0;
+        while (m < mmax) {
+          const u32 kmax = wave_max(kB);
+          if (kmax <= F) { by_floor = 1; if (lane == 0) STAT(kmax ? 13 : 12); break; }   // (F >= 0: also when nothing is left)
+          u64 mk = __ballot(kB == kmax);
+          if (mk & (mk - 1)) {                           // equal keys: high word, low word, lowest index
+            const bool in1 = kB == kmax;
+            const u64 hmax = wave_max(in1 ? e.hi : 0ull);
+            const bool in2 = in1 && e.hi == hmax;
+            const u64 lmax = wave_max(in2 ? e.lo : 0ull);
+            const bool in3 = in2 && e.lo == lmax;
+            const u32 cmin = wave_min(in3 ? e.cand : NONE32);
+            mk = __ballot(in3 && e.cand == cmin);
+          }
+          const u32 bl = (u32)__builtin_ctzll(mk);
+          if (__ballot(risky)) {
+            if (__ballot(risky && lane == bl)) { if (lane == 0) STAT(15); break; }      // its own flash window may be gone
+            const u32 rm = wave_max(risky ? e.kr : 0u);
+            if (rm >= kmax) { if (lane == 0) STAT(14); break; }                        // a candidate at risk might rise above it
+          }
+          if (lane == 0) S->sel[m] = bl;
+          if (lane == bl) { kB = 0u; picked = true; }
+          if (__builtin_amdgcn_readlane((int)e.dest, (int)bl) == 0)
+            risk((u32)__builtin_amdgcn_readlane((int)e.L1, (int)bl), (u32)__builtin_amdgcn_readlane((int)e.a, (int)bl),
+                 (u32)__builtin_amdgcn_readlane((int)e.b, (int)bl), (u32)__builtin_amdgcn_readlane((int)e.R, (int)bl));
+          ++m;
+        }
+        if (lane >= 1 && lane < m) {                       // the picked entries become migrations 1 .. m - 1
+          Winner x = S->list[S->sel[lane]];
+          x.tau_o = ceil_div_x1000(x.s, x.dest ? bwo1 : bwo0, x.dest ? ivo1 : ivo0);
+          x.tau_i = ceil_div_x1000(x.s, x.dest ? bwi1 : bwi0, x.dest ? ivi1 : ivi0);
+          S->mem[lane] = x;
+        }
+        if (lane == 0) { S->m0 = m; S->by_floor = by_floor; }
+      }
+      __syncthreads();
+      PHASE(3);
+      // Per chunk, the selected migrations in order: how many of them can go together.  The first
+      // that might let a slot drop under the capacity, that needs a chunk of a timeline an earlier
+      // one rewrites, or that host memory might not hold on top of the earlier ones, ends the set
+      // (it is ranked again in the next pass).  For the winner itself the two tests only decide
+      // how it is committed: alone, and with the exact host-capacity test.
+      const u32 m0 = S->m0;
+      if (tid < ((nch + 63u) & ~63u)) {
+        u32 cut = MAXM;
+        bool ex0 = false;
+        if (tid < nch) {
+          const u64 mo = minOver[tid], hm = hmax[tid];
+          u64 runP = 0, runH = 0;
+          u32 usedFO = 0, usedFI = 0, usedH = 0;
+          for (u32 i = 0; i < m0; ++i) {
+            const Winner& M = S->mem[i];
+            const u32 mL1 = M.L1, mR = M.R, ma = M.a, mb = M.b, md = M.dest;
+            const u64 ms = M.s;
+            u32 len = 0;
+            const u32 cE = cover(tid, CH, K, mL1, ma - 1, len), cW = cover(tid, CH, K, mb + 1, mR - 1, len), cA = cover(tid, CH, K, ma, mb, len);
+            const u32 cP = cE + cA + cW;
+            const u32 lim = i ? i : 1u;
+            if (cA) {
+              runP += ms;
+              if (mo != NONE64 && mo - cap <= runP && lim < cut) { cut = lim; STAT(16); }
+            }
+            if (cE) { if (((usedFO >> md) & 1u) && i < cut) { cut = i; STAT(18); } usedFO |= 1u << md; }
+            if (cW) { if (((usedFI >> md) & 1u) && i < cut) { cut = i; STAT(18); } usedFI |= 1u << md; }
+            if (md == G10_HOST && cP) {
+              if (ms > host_cap || hm + runH > host_cap - ms) { if (i == 0) ex0 = true; else if (i < cut) { cut = i; STAT(19); } }
+              runH += ms;
+              if (cP != len) { if (usedH && i < cut) cut = i; usedH = 1; }
+            }
+          }
+        }
+        cut = wave_min(cut);
+        if (lane == 0 && cut < MAXM) atomicMin(&S->cut, cut);
+        if (ex0) S->need_exact = 1;
+      }
+      __syncthreads();
+      u32 m = m0 < S->cut ? m0 : S->cut;
+      if (tid == 0) { STAT(20 + m0); STAT(20 + m); }      // histograms of selected (doubled at equal) and committed
+      bool room = true;
+      if (S->need_exact) {                               // the winner alone; host memory slot by slot where its period cuts a chunk
+        m = 1;
+        u32 cvP = 0, len = 0;
+        if (tid < nch) cvP = cover(tid, CH, K, L1, R - 1, len);
+        __syncthreads();
+        if (tid == 0) S->hq = 0;
+        __syncthreads();
+        if (cvP == len && cvP) atomicMax((unsigned long long*)&S->hq, (unsigned long long)hmax[tid]);
+        else if (cvP) jobs[atomicAdd(&S->njobs, 1u)] = ((u32)J_HQ << 16) | tid;
+        __syncthreads();
+        run_jobs();
+        __syncthreads();
+        room = s <= host_cap && S->hq <= host_cap - s;
+        __syncthreads();
+        if (tid == 0) S->njobs = 0;
+        __syncthreads();
+      }
+      PHASE(4);
+      if (wave == LW - 1) {                              // the records, the counters, the next pass's first threshold
+        const u64 nm = S->n_mig, nd = S->n_drop;
+        if (lane < m) {
+          const Winner& M = S->mem[lane];
+          const u32 mL1 = M.L1, mR = M.R, ma = M.a, mb = M.b;
+          const u64 ms = M.s;
+          a.cd.A[M.pos] = make_uint4(mL1, mR, 1u, 0u);     // the candidate leaves the live set
+          a.cd.B[M.pos] = make_uint4(1u, 0u, (u32)ms, (u32)(ms >> 32));
+          if (!room) {
+            g10_dropped dr; dr.iteration = S->n_iter - 1; dr.cand = M.cand; dr.reserved = 0;
+            a.dropped[nd] = dr;
+          } else {
+            g10_migration mg;
+            mg.cand = M.cand; mg.tensor = M.tensor;
+            mg.evict_after = mL1 - 1; mg.absent_first = ma >= K ? ma - K : ma; mg.absent_last = mb >= K ? mb - K : mb;
+            mg.next_use = mR >= K ? mR - K : mR;
+            mg.dest = M.dest; mg.wraps = mR >= K ? 1u : 0u;
+            mg.size_bytes = ms; mg.t_out_ns = M.tau_o; mg.t_in_ns = M.tau_i; mg.benefit_lo = M.lo; mg.benefit_hi = M.hi;
+            a.records[nm + lane] = mg;
+            a.rec_ab[nm + lane] = make_uint2(ma, mb);
+          }
+        }
+        if (lane == 0) {
+          // first threshold of the next pass: a little under the last benefit.  How little adapts: where
+          // many candidates are nearly equal (a pass scored thousands) the margin halves; it doubles
+          // when the pass ran out of candidates above the floor with little scored
+          u32 gs = S->gshift;
+          if (pass_units > 8u && gs < GUESS_SHIFT_MAX) ++gs;
+          else if ((S->by_floor || rounds > 1u) && pass_units <= 4u && gs > MC_GUESS_SHIFT_MIN) --gs;
+          S->gshift = gs;
+          u64 ghi = S->mem[m - 1].hi, glo = S->mem[m - 1].lo;
+          const u64 dlo = (glo >> gs) | (ghi << (64 - gs)), dhi = ghi >> gs;
+          const u64 nlo = glo - dlo;
+          ghi = ghi - dhi - (glo < dlo ? 1ull : 0ull);
+          S->thr_key = upkey(ghi, nlo);
+          if (!room) S->n_drop = nd + 1;
+          else {
+            const u64 x = m - 1;                          // the passes of Algorithm 1 this one stands for beyond the first
+            S->n_mig = nm + m; S->n_iter += x;
+            S->n_evals += x * (C - nm - nd) - x * (x + 1) / 2;
+          }
+        }
+      }
+      if (!room) { __syncthreads(); continue; }
+      if (tid == 0) S->m = m;
+
+      // commit: whole chunks take a lazy add, the others a job
+      if (tid < nch) {
+        const u32 c = tid;
+        u64 lzP = lazyP[c], mo = minOver[c], lzH = lazyH[c], hm = hmax[c];
+        bool chP = false, chH = false, slots = false;    // slots: the chunk's pressures are gone through one by one
+        for (u32 i = 0; i < m; ++i) {
+          const Winner& M = S->mem[i];
+          const u32 mL1 = M.L1, mR = M.R, ma = M.a, mb = M.b, md = M.dest;
+          const u64 ms = M.s;
+          u32 len = 0;
+          const u32 cE = cover(c, CH, K, mL1, ma - 1, len), cW = cover(c, CH, K, mb + 1, mR - 1, len), cA = cover(c, CH, K, ma, mb, len);
+          const u32 cP = cE + cA + cW;
+          if (cE) jobs[atomicAdd(&S->njobs, 1u)] = (i << 20) | ((u32)J_FO << 16) | c;
+          if (cW) jobs[atomicAdd(&S->njobs, 1u)] = (i << 20) | ((u32)J_FI << 16) | c;
+          if (cA == len) {                                 // the whole chunk loses the tensor
+            lzP += ms; chP = true;
+            if (mo != NONE64) {
+              mo -= ms;
+              if (mo <= cap) slots = true;                 // a slot drops under the capacity
+            }
+          } else if (cA) slots = true;
+          if (md == G10_HOST) {
+            if (cP == len) { lzH += ms; hm += ms; chH = true; }
+            else if (cP) jobs[atomicAdd(&S->njobs, 1u)] = (i << 20) | ((u32)J_H << 16) | c;
+          }
+        }
+        if (chP) { lazyP[c] = lzP; minOver[c] = mo; }
+        if (chH) { lazyH[c] = lzH; hmax[c] = hm; }
+        if (slots) jobs[atomicAdd(&S->njobs, 1u)] = ((u32)J_P_PART << 16) | c;
+      }
+      __syncthreads();
+      PHASE(6);
+      run_jobs();
+      __syncthreads();
+      PHASE(7);
+      // level 1: a transfer window inside one chunk lowers every later chunk's base by the
+      // transfer time; otherwise (and for the over-capacity time, if it changed) scan again
+      {
+        bool simple = S->ot_changed == 0;
+        for (u32 i = 0; i < m && simple; ++i) {
+          const Winner& M = S->mem[i];
+          const u32 mL1 = M.L1, mR = M.R, ma = M.a, mb = M.b;
+          const u32 eA = (mL1 >= K ? mL1 - K : mL1) >> tl.shift_ch, eB = (ma - 1 >= K ? ma - 1 - K : ma - 1) >> tl.shift_ch;
+          const u32 pA = (mb + 1 >= K ? mb + 1 - K : mb + 1) >> tl.shift_ch, pB = (mR - 1 >= K ? mR - 1 - K : mR - 1) >> tl.shift_ch;
+          simple = eA == eB && !(mL1 < K && ma - 1 >= K) && pA == pB && !(mb + 1 < K && mR - 1 >= K);
+        }
+        if (simple) {
+          for (u32 t = tid; t <= nch; t += LB) {           // (index nch: the totals)
+            u64 dFO[2] = {0, 0}, dFI[2] = {0, 0};
+            for (u32 i = 0; i < m; ++i) {
+              const Winner& M = S->mem[i];
+              const u32 mL1 = M.L1, mb = M.b, md = M.dest;
+              const u32 eA = (mL1 >= K ? mL1 - K : mL1) >> tl.shift_ch, pA = (mb + 1 >= K ? mb + 1 - K : mb + 1) >> tl.shift_ch;
+              if (t > eA) dFO[md] += M.tau_o;
+              if (t > pA) dFI[md] += M.tau_i;
+            }
+            for (u32 q = 0; q < 2; ++q) {
+              if (dFO[q]) base[(u64)(A_FO + q) * nb1 + t] -= dFO[q];
+              if (dFI[q]) base[(u64)(A_FI + q) * nb1 + t] -= dFI[q];
+            }
+          }
+          __syncthreads();
+        } else if (m == 1) {
+          if (S->ot_changed) scan_bases(A_OT, A_FO + d, A_FI + d, 3);
+          else scan_bases(A_FO + d, A_FI + d, 0, 2);
+        } else {
+          scan_bases(A_FO, A_FO + 1, A_FI, 3);
+          scan_bases(A_FI + 1, A_OT, 0, S->ot_changed ? 2 : 1);
+        }
+      }
+      PHASE(8);
+      continue;
+    }
 
     // which chunks the period, its absent window and its transfer windows cover
     u32 cvE = 0, cvW = 0, cvA = 0, cvP = 0, len = 0;
@@ -704,7 +1035,7 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
     }
     PHASE(4);
     if (tid == LB - G10_WAVE) {                            // (the last wavefront: it has no chunk to classify below)
-      const u32 p = S->win.pos;
+      const u32 p = S->mem[0].pos;
       a.cd.A[p] = make_uint4(L1, R, 1u, 0u);             // the candidate leaves the live set
       a.cd.B[p] = make_uint4(1u, 0u, (u32)s, (u32)(s >> 32));
       // first threshold of the next pass: a little under this benefit.  How little adapts: where
@@ -714,23 +1045,23 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
       if (pass_units > 8u && gs < GUESS_SHIFT_MAX) ++gs;
       else if (rounds > 1u && pass_units <= 2u && gs > GUESS_SHIFT) --gs;
       S->gshift = gs;
-      u64 ghi = S->win.hi, glo = S->win.lo;
+      u64 ghi = S->mem[0].hi, glo = S->mem[0].lo;
       const u64 dlo = (glo >> gs) | (ghi << (64 - gs)), dhi = ghi >> gs;
       const u64 nlo = glo - dlo;
       ghi = ghi - dhi - (glo < dlo ? 1ull : 0ull);
-      S->thr_key = RATIO ? rkey_dn(ratio_approx(S->win.hi, S->win.lo, S->win.cost) * (1.0 - 1.0 / (double)(1u << gs)))
+      S->thr_key = RATIO ? rkey_dn(ratio_approx(S->mem[0].hi, S->mem[0].lo, S->mem[0].cost) * (1.0 - 1.0 / (double)(1u << gs)))
                          : upkey(ghi, nlo);
       if (!room) {
-        g10_dropped dr; dr.iteration = S->n_iter - 1; dr.cand = S->win.cand; dr.reserved = 0;
+        g10_dropped dr; dr.iteration = S->n_iter - 1; dr.cand = S->mem[0].cand; dr.reserved = 0;
         a.dropped[S->n_drop] = dr;
         S->n_drop += 1;
       } else {
         g10_migration mg;
-        mg.cand = S->win.cand; mg.tensor = S->win.tensor;
+        mg.cand = S->mem[0].cand; mg.tensor = S->mem[0].tensor;
         mg.evict_after = L1 - 1; mg.absent_first = wa >= K ? wa - K : wa; mg.absent_last = wb >= K ? wb - K : wb;
         mg.next_use = R >= K ? R - K : R;
         mg.dest = d; mg.wraps = R >= K ? 1u : 0u;
-        mg.size_bytes = s; mg.t_out_ns = S->tau_o; mg.t_in_ns = S->tau_i; mg.benefit_lo = S->win.lo; mg.benefit_hi = S->win.hi;
+        mg.size_bytes = s; mg.t_out_ns = S->mem[0].tau_o; mg.t_in_ns = S->mem[0].tau_i; mg.benefit_lo = S->mem[0].lo; mg.benefit_hi = S->mem[0].hi;
         a.records[S->n_mig] = mg;
         a.rec_ab[S->n_mig] = make_uint2(wa, wb);
         S->n_mig += 1;
@@ -773,10 +1104,10 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
       const bool ot = S->ot_changed != 0;
       if (oneE && oneP && !ot) {
         if (tid < nch) {
-          if (tid > eA) base[(u64)(A_FO + d) * nb1 + tid] -= S->tau_o;
-          if (tid > pA) base[(u64)(A_FI + d) * nb1 + tid] -= S->tau_i;
+          if (tid > eA) base[(u64)(A_FO + d) * nb1 + tid] -= S->mem[0].tau_o;
+          if (tid > pA) base[(u64)(A_FI + d) * nb1 + tid] -= S->mem[0].tau_i;
         }
-        if (tid == 0) { base[(u64)(A_FO + d) * nb1 + nch] -= S->tau_o; base[(u64)(A_FI + d) * nb1 + nch] -= S->tau_i; }
+        if (tid == 0) { base[(u64)(A_FO + d) * nb1 + nch] -= S->mem[0].tau_o; base[(u64)(A_FI + d) * nb1 + nch] -= S->mem[0].tau_i; }
         __syncthreads();
       } else if (ot) scan_bases(A_OT, A_FO + d, A_FI + d, 3);
       else scan_bases(A_FO + d, A_FI + d, 0, 2);
@@ -795,7 +1126,7 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
     ctl->thr_key = S->thr_key; ctl->status = S->status; ctl->done = S->done;
     ctl->gshift = S->gshift;
     ctl->overtime_after = base[(u64)A_OT * nb1 + nch];
-    for (u32 i = 0; i < 12; ++i) ctl->phase[i] += S->phase[i];
+    for (u32 i = 0; i < 32; ++i) ctl->phase[i] += S->phase[i];
     ctl->units_scored += S->units; ctl->second_rounds += S->second; ctl->jobs_run += S->jobs; ctl->launches += 1;
     ctl->area_evals += S->evals; ctl->area_refused += S->refused;
   }
@@ -808,7 +1139,7 @@ size_t loop_lds_bytes(u32 nch, u32 nt) {
   size_t b = 0;
   b += ((size_t)N_ARR * (nch + 1) + (size_t)N_ARR * nch + (size_t)4 * nch + ns + (size_t)4 * LW) * 8;
   b += sizeof(Shared);
-  b += ((size_t)nt + ns + (size_t)4 * nch + 8) * 4 + (size_t)nt * 4;
+  b += ((size_t)nt + ns + (size_t)8 * nch + 8) * 4 + (size_t)nt * 4;
   return (b + 15) & ~(size_t)15;
 }
 

@@ -964,7 +964,10 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     if (getenv("G10_LOG")) {
       fprintf(stderr, "g10: loop phases (us per pass):");
       for (int q = 0; q < 9; ++q) fprintf(stderr, " %d:%.2f", q, hc.phase[q] / 100.0 / (double)(hc.n_iter ? hc.n_iter : 1));
-      fprintf(stderr, "  live/pass %.1f dests/pass %.1f\n", hc.phase[9] / (double)(hc.n_iter ? hc.n_iter : 1), hc.phase[10] / (double)(hc.n_iter ? hc.n_iter : 1));
+      fprintf(stderr, "  live/pass %.1f dests/pass %.1f real passes %llu\n", hc.phase[9] / (double)(hc.n_iter ? hc.n_iter : 1), hc.phase[10] / (double)(hc.n_iter ? hc.n_iter : 1), (unsigned long long)hc.phase[11]);
+      fprintf(stderr, "g10: stats:");
+      for (int q = 12; q < 32; ++q) fprintf(stderr, " %d:%llu", q, (unsigned long long)hc.phase[q]);
+      fprintf(stderr, "\n");
     }
 #endif
     w->planned = true; w->plan_cap = x.p->gpu_cap_bytes; w->plan_n_mig = hc.n_mig;

@@ -49,7 +49,7 @@ struct Ctl {
   // statistics
   u64 units_scored, second_rounds, jobs_run, launches;
   u64 area_evals, area_refused;   // clipped areas computed in the loop; of those, how many came out below the bound
-  u64 phase[12];              // wall-clock ticks per phase of the loop (only with G10_PHASE_TIMERS)
+  u64 phase[32];              // wall-clock ticks per phase of the loop (only with G10_PHASE_TIMERS)
 };
 
 struct Cands {
