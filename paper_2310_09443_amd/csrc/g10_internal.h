@@ -211,6 +211,7 @@ struct g10_plan_s {
   PlanWork* work = nullptr;      // workspaces of the first plan of a batch (the only one of g10_plan)
   PlanWork** more = nullptr;     // ... of the further plans of a batch
   u32 n_more = 0;
+  u64 max_size = 0;              // the largest tensor
   bool big_size = false;         // some tensor has 2^43 bytes or more (the planner's 16-byte candidate copies hold 43 bits)
   void* loop_args = nullptr;     // device array of per-plan arguments of the loop kernel
   u32 loop_args_cap = 0;

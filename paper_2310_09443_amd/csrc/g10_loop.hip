@@ -12,7 +12,9 @@ namespace {
 #ifdef G10_PHASE_TIMERS
 #define PHASE(i) do { if (tid == 0) { const u64 now_ = wall_clock64(); S->phase[i] += now_ - S->t_last; S->t_last = now_; } } while (0)
 #define STAT(i) do { atomicAdd((unsigned long long*)&S->phase[i], 1ull); } while (0)
+#define SUBT(i) do { if (lane == 0) { const u64 now_ = wall_clock64(); S->phase[i] += now_ - sub_last; sub_last = now_; } } while (0)
 #else
+#define SUBT(i) do { } while (0)
 #define PHASE(i) do { } while (0)
 #define STAT(i) do { } while (0)
 #endif
@@ -32,6 +34,7 @@ struct Winner {               // what a commit needs of the winning candidate
 };
 
 constexpr u32 MAXM = 8;       // migrations committed in one ranking pass at most
+
 #ifndef G10_MC_GSMIN
 #define G10_MC_GSMIN 5
 #endif
@@ -48,6 +51,7 @@ struct Shared {               // small per-pass state of the loop workgroup
                               // host-capacity test needs the exact per-slot maximum
   u32 by_floor, m;            // the selection ended because the next candidate did not clear the floor; migrations being committed
   u32 sel[MAXM];              // list entries picked, in order
+  u32 touched, pad3;          // timelines (a bit per array of level 1) whose chunk totals change in this pass
   u64 hq;                     // host-capacity query: maximum over the period
   u64 acc[3];                 // clipped area being summed: bits 0..31, 32..63 and 64.. of the terms, added apart
   u64 evals, refused;         // clipped areas computed; of those, how many came out below the bound
@@ -117,6 +121,20 @@ __device__ __forceinline__ bool cyc_overlap(u32 x1, u32 y1, u32 x2, u32 y2, u32 
   return (p <= t && r <= q) || (p + k <= t && r <= q + k) || (p <= t + k && r + k <= q);
 }
 
+// The plain slots of a doubled slot range [x, y] (x <= y, y - x < K) as one or two runs [p, q]
+__device__ __forceinline__ u32 plain_runs(u32 x, u32 y, u32 K, u32 (&p)[2], u32 (&q)[2]) {
+  p[1] = 0; q[1] = 0;
+  if (x >= K) { p[0] = x - K; q[0] = y - K; return 1u; }
+  if (y < K) { p[0] = x; q[0] = y; return 1u; }
+  p[0] = x; q[0] = K - 1; q[1] = y - K;
+  return 2u;
+}
+
+// Do the doubled slot ranges [x1, y1] and [x2, y2] (each shorter than K) share a kernel slot?  (K < 2^30)
+__device__ __forceinline__ bool cyc_overlap32(u32 x1, u32 y1, u32 x2, u32 y2, u32 K) {
+  return (x1 <= y2 && x2 <= y1) || (x1 + K <= y2 && x2 <= y1 + K) || (x1 <= y2 + K && x2 + K <= y1);
+}
+
 template <bool RATIO>
 __device__ __forceinline__ u32 best_lane(u64 hi, u64 lo, u64 cost, u32 cand) {
   if (RATIO) return wave_best_lane_ratio(hi, lo, cost, cand);
@@ -142,11 +160,11 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
   u64* hmax = lazyH + nch;
   u64* smark = hmax + nch;                              // [ns] tiles of a group of 64 scored in this pass
   u64* scr = smark + ns;                                // [4 * LW]
-  Shared* S = (Shared*)(scr + 4 * LW);
+  u64* jobs = scr + 4 * LW;                             // [8 * nch + 8]  chunk << 0 | kind << 16 | migrations << 24 | migrations << 32
+  Shared* S = (Shared*)(jobs + 8 * nch + 8);
   u32* keys = (u32*)(S + 1);                            // [nt]  bound of every tile
   u32* skeys = keys + nt;                               // [ns]  largest bound of every group of 64 tiles
-  u32* jobs = skeys + ns;                               // [8 * nch + 8]
-  unsigned short* tlist = (unsigned short*)(jobs + 8 * nch + 8);   // [nt]  the hot list
+  unsigned short* tlist = (unsigned short*)(skeys + ns);   // [nt]  the hot list
   unsigned short* alist = tlist + nt;                            // [nt]  tiles scored in the current round
 
   const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
@@ -207,6 +225,7 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
   };
   scan_bases(0, 1, 2, 3);
   scan_bases(3, 4, 0, 2);
+
 
   // The hot list: every tile not scored in this pass whose bound reaches `thr`; restL bounds
   // the tiles left out.  Bounds only fall and only scored tiles change, so the list stays
@@ -417,35 +436,46 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
     __syncthreads();
   };
 
-  // ---- chunk jobs: one wavefront rewrites one chunk of one array ------------------------
-  // (a job word: migration of the pass << 20 | kind << 16 | chunk)
-  auto run_jobs = [&]() {
+  // ---- chunk jobs: one wavefront rewrites one chunk of one timeline, for all migrations of the
+  // pass at once (a job word: kind << 16 | chunk) -------------------------------------------
+  auto run_jobs = [&](const u32 mm) {
     const u32 nj = S->njobs;
     for (u32 jb = wave; jb < nj; jb += LW) {
-      const u32 type = (jobs[jb] >> 16) & 15u, c = jobs[jb] & 0xffffu;
-      const Winner& M = S->mem[jobs[jb] >> 20];
-      const u32 d = M.dest, L1 = M.L1, R = M.R, wa = M.a, wb = M.b;
-      const u64 s = M.s, tau_o = M.tau_o, tau_i = M.tau_i, fo_base = M.fo_base, fi_end = M.fi_end;
-      const u32 s0 = c * CH;
-      if (type == J_FO || type == J_FI) {
-        // channel time of the window is taken from this chunk's slots; the free-time prefix
-        // of the slots after the first window slot is rewritten from a scan of the new values
-        const bool out = type == J_FO;
+      const u64 jw = jobs[jb];
+      const u32 type = (u32)(jw >> 16) & 0xffu, c = (u32)jw & 0xffffu, ma_ = (u32)(jw >> 24) & 0xffu, mb_ = (u32)(jw >> 32) & 0xffu;
+      const u32 s0 = c * CH, s1 = (s0 + CH - 1 < K - 1) ? s0 + CH - 1 : K - 1;
+      if (type >= J_FO0 && type <= J_FI1) {
+        // channel time of the transfer windows of this destination that meet the chunk is taken
+        // from its slots (the windows of one pass are disjoint); the free-time prefix of the
+        // slots after the first window slot is rewritten from a scan of the new values
+        const bool out = type < J_FI0;
+        const u32 d = (type - J_FO0) & 1u;
         const u32 arr = (out ? A_FO : A_FI) + d, w = out ? w_fo(d) : w_fi(d);
         u64* fr = tl.fre + (u64)((out ? 0u : 2u) + d) * tl.Kp;
         const u64 bc = base[(u64)arr * nb1 + c], ball = base[(u64)arr * nb1 + nch];
-        const u32 x = out ? L1 : wb + 1, y = out ? wa - 1 : R - 1;
-        const u32 first = first_covered(s0, (s0 + CH - 1 < K - 1) ? s0 + CH - 1 : K - 1, K, x, y);
+        const u32 mask = ma_;                            // the migrations of this destination whose window meets the chunk
+        u32 first = NONE32;
+        for (u32 pb = mask; pb; pb &= pb - 1) {
+          const Winner& W = S->mem[__builtin_ctz(pb)];
+          const u32 f = first_covered(s0, s1, K, out ? W.L1 : W.b + 1, out ? W.a - 1 : W.R - 1);
+          first = f < first ? f : first;
+        }
         u64 carry = 0;
         for (u32 st = 0; st < tl.spt; ++st) {
           const u32 j0 = s0 + st * 256u + lane * 4u;
-          u64 f[4], old[4];
+          u64 f[4], old[4], tau[4], ref[4];
           u32 jj[4];
 #pragma unroll
           for (u32 i = 0; i < 4; ++i) {
             const u32 j = j0 + i;
             f[i] = j < K ? fr[j] : 0ull;
-            jj[i] = j < K ? in_doubled(j, K, x, y) : NONE32;
+            jj[i] = NONE32; tau[i] = 0; ref[i] = 0;
+            if (j < K)
+              for (u32 pb = mask; pb; pb &= pb - 1) {
+                const Winner& W = S->mem[__builtin_ctz(pb)];
+                const u32 p = in_doubled(j, K, out ? W.L1 : W.b + 1, out ? W.a - 1 : W.R - 1);
+                if (p != NONE32) { jj[i] = p; tau[i] = out ? W.tau_o : W.tau_i; ref[i] = out ? W.fo_base : W.fi_end; }
+              }
             old[i] = jj[i] != NONE32 ? tl.px[(u64)j * PX + w] : 0ull;       // free time of the chunk before the slot
           }
           u64 lsum = 0;
@@ -455,13 +485,13 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
               const u64 before_slot = (jj[i] >= K ? ball : 0ull) + bc + old[i];  // free time before slot jj
               u64 take;
               if (out) {                           // eviction: earliest free time of the window first
-                const u64 before = before_slot - fo_base;
-                const u64 used = before < tau_o ? before : tau_o;
-                take = f[i] < tau_o - used ? f[i] : tau_o - used;
+                const u64 before = before_slot - ref[i];
+                const u64 used = before < tau[i] ? before : tau[i];
+                take = f[i] < tau[i] - used ? f[i] : tau[i] - used;
               } else {                             // prefetch: latest free time first
-                const u64 after = fi_end - (before_slot + f[i]);
-                const u64 used = after < tau_i ? after : tau_i;
-                take = f[i] < tau_i - used ? f[i] : tau_i - used;
+                const u64 after = ref[i] - (before_slot + f[i]);
+                const u64 used = after < tau[i] ? after : tau[i];
+                take = f[i] < tau[i] - used ? f[i] : tau[i] - used;
               }
               if (take) { f[i] -= take; fr[j0 + i] = f[i]; }
             }
@@ -478,22 +508,16 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
           carry += wave_last(inc);
         }
         if (lane == 0) tot[(u64)arr * nch + c] = carry;
-      } else if (type == J_P_PART || type == J_P_FULL) {
-        // pressure of the chunk's slots, for all migrations of the pass at once: the ones whose
-        // absent window cuts the chunk are taken off slot by slot (the ones that cover it whole
-        // went into the lazy add); where a slot drops under the capacity the over-capacity prefix
-        // after it is rewritten
-        const u32 mm = S->m;
-        const u64 lz = lazyP[c];
+      } else if (type == J_P) {
+        // pressure of the chunk's slots: the migrations whose absent window cuts the chunk are
+        // taken off slot by slot, the ones that cover it whole go into the chunk's lazy add
+        // (here, not by the chunk's thread); where a slot drops under the capacity the
+        // over-capacity prefix after it is rewritten
+        const u64 lz0 = lazyP[c];                        // the lazy add before this pass
         u64 lz_full = 0;
-        u32 part = 0;                                    // migrations whose window cuts the chunk
-        for (u32 q = 0; q < mm; ++q) {
-          u32 len = 0;
-          const u32 cv = cover(c, CH, K, S->mem[q].a, S->mem[q].b, len);
-          if (cv == len) lz_full += S->mem[q].s;
-          else if (cv) part |= 1u << q;
-        }
-        const u64 lz0 = lz - lz_full;                    // the lazy add before this pass
+        const u32 part = ma_;                            // migrations whose window cuts the chunk; mb_: those that cover it whole
+        for (u32 pb = mb_; pb; pb &= pb - 1) lz_full += S->mem[__builtin_ctz(pb)].s;
+        const u64 lz = lz0 + lz_full;
         u64 mn = NONE64;
         u32 first = NONE32;                              // first slot that dropped under the capacity
         for (u32 st = 0; st < tl.spt; ++st) {
@@ -520,7 +544,7 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
           if (first == NONE32) first = stfirst;
         }
         mn = wave_min(mn);
-        if (lane == 0) minOver[c] = mn;
+        if (lane == 0) { minOver[c] = mn; lazyP[c] = lz; }
         if (first != NONE32) {                           // rewrite the prefix of the slots after it
           u64 carry = 0;
           for (u32 st = 0; st < tl.spt; ++st) {
@@ -552,6 +576,8 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
       } else if (type == J_CLIP) {
         // clipped area of the winner's absent window inside this chunk: per slot over the
         // capacity, duration x min(size, excess)
+        const u32 wa = S->mem[0].a, wb = S->mem[0].b;
+        const u64 s = S->mem[0].s;
         const u64 lz = lazyP[c];
         u64 alo = 0, ahi = 0;
         for (u32 st = 0; st < tl.spt; ++st) {
@@ -576,26 +602,51 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
           atomicAdd((unsigned long long*)&S->acc[1], (unsigned long long)p1);
           atomicAdd((unsigned long long*)&S->acc[2], (unsigned long long)p2);
         }
-      } else {                                     // J_H: add the tensor; J_HQ: only ask for the maximum
-        const u64 lz = lazyH[c];
-        u64 m_all = 0, m_cov = 0;
+      } else if (type == J_H) {
+        // host bytes of the chunk's slots: the host migrations whose period cuts the chunk are
+        // added slot by slot, the ones that cover it whole go into the chunk's lazy add
+        const u64 lz0 = lazyH[c];
+        u64 lz_full = 0;
+        const u32 part = ma_;
+        for (u32 pb = mb_; pb; pb &= pb - 1) lz_full += S->mem[__builtin_ctz(pb)].s;
+        const u64 lz = lz0 + lz_full;
+        u64 m_all = 0;
         for (u32 st = 0; st < tl.spt; ++st) {
           const u32 j0 = s0 + st * 256u + lane * 4u;
 #pragma unroll
           for (u32 i = 0; i < 4; ++i) {
             const u32 j = j0 + i;
             if (j < K) {
-              u64 h = tl.H[j];
-              const bool cov = in_doubled(j, K, L1, R - 1) != NONE32;
-              if (type == J_H && cov) { h += s; tl.H[j] = h; }
+              u64 h = tl.H[j], add = 0;
+              for (u32 pb = part; pb; pb &= pb - 1) {
+                const Winner& W = S->mem[__builtin_ctz(pb)];
+                if (in_doubled(j, K, W.L1, W.R - 1) != NONE32) add += W.s;
+              }
+              if (add) { h += add; tl.H[j] = h; }
               const u64 act = h + lz;
               m_all = act > m_all ? act : m_all;
-              if (cov) m_cov = act > m_cov ? act : m_cov;
             }
           }
         }
-        if (type == J_H) { m_all = wave_max(m_all); if (lane == 0) hmax[c] = m_all; }
-        else { m_cov = wave_max(m_cov); if (lane == 0) atomicMax((unsigned long long*)&S->hq, (unsigned long long)m_cov); }
+        m_all = wave_max(m_all);
+        if (lane == 0) { hmax[c] = m_all; lazyH[c] = lz; }
+      } else {                                     // J_HQ: the largest host occupancy over the winner's period inside the chunk
+        const u32 L1 = S->mem[0].L1, R = S->mem[0].R;
+        const u64 lz = lazyH[c];
+        u64 m_cov = 0;
+        for (u32 st = 0; st < tl.spt; ++st) {
+          const u32 j0 = s0 + st * 256u + lane * 4u;
+#pragma unroll
+          for (u32 i = 0; i < 4; ++i) {
+            const u32 j = j0 + i;
+            if (j < K && in_doubled(j, K, L1, R - 1) != NONE32) {
+              const u64 act = tl.H[j] + lz;
+              m_cov = act > m_cov ? act : m_cov;
+            }
+          }
+        }
+        m_cov = wave_max(m_cov);
+        if (lane == 0) atomicMax((unsigned long long*)&S->hq, (unsigned long long)m_cov);
       }
     }
     if (tid == 0) S->jobs += nj;
@@ -629,12 +680,12 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
           atomicAdd((unsigned long long*)&S->acc[1], (unsigned long long)(lo >> 32));
           atomicAdd((unsigned long long*)&S->acc[2], (unsigned long long)__umul64hi(s, t));
         } else {
-          jobs[atomicAdd(&S->njobs, 1u)] = ((u32)J_CLIP << 16) | tid;
+          jobs[atomicAdd(&S->njobs, 1u)] = ((u64)J_CLIP << 16) | tid;
         }
       }
     }
     __syncthreads();
-    run_jobs();
+    run_jobs(1u);
     __syncthreads();
     const u64 a0 = S->acc[0], a1 = S->acc[1], a2 = S->acc[2];
     const u64 vlo = a0 + (a1 << 32), vhi = a2 + (a1 >> 32) + (vlo < a0 ? 1ull : 0ull);
@@ -688,7 +739,7 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
       S->n_iter += 1; S->n_evals += C - S->n_mig - S->n_drop;
       S->hq = 0; S->njobs = 0; S->ot_changed = 0;
       S->mem[0].hi = 0; S->mem[0].lo = 0;
-      S->nlist = 0; S->Fx = 0; S->F2 = 0; S->cut = MAXM; S->need_exact = 0; S->m0 = 1; S->by_floor = 0; S->m = 1;
+      S->nlist = 0; S->Fx = 0; S->F2 = 0; S->cut = MAXM; S->need_exact = 0; S->m0 = 1; S->by_floor = 0; S->m = 1; S->touched = 0;
       if (S->stale_hot) { S->restL = NONE32; S->stale_hot = 0; }
       if (a.tick_budget && wall_clock64() - S->t_start > a.tick_budget) S->stop = 1;
     }
@@ -751,368 +802,251 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
     PHASE(3);
 
     const bool none = (S->mem[0].hi | S->mem[0].lo) == 0;
-    const u32 d = S->mem[0].dest, L1 = S->mem[0].L1, R = S->mem[0].R, wa = S->mem[0].a, wb = S->mem[0].b;
-    const u64 s = S->mem[0].s;
     if (none) { __syncthreads(); if (tid == 0) { S->done = 1; S->status = G10_RESIDUAL; } break; }
 
-    if constexpr (MC) {
-      // ---- more migrations of the same pass -------------------------------------------------
-      // The ranking also tells which candidate comes second, third, ...: candidate w_j wins the
-      // pass after w_1 .. w_(j-1) were committed if (1) nothing those commits change enters its
-      // own score - no slot drops under the capacity, and no two of them reserve channel time or
-      // rewrite slots in the same chunk of the same timeline - and (2) no other candidate can
-      // have risen above it.  Pressure only falls and reservations only grow, so a benefit rises
-      // in one case only: a candidate the policy sends to flash, with a host window as well,
-      // loses its flash window to a reservation and moves to host.  Such a candidate is at risk
-      // once a committed flash migration's transfer windows meet its own; it then counts with the
-      // bound of its host benefit.  Every candidate not looked at one by one (tiles left out, a
-      // thread's second best, the overflow of the list) counts with its bound, the floor F.
-      if (wave == LW - 1) {                            // one wavefront picks them in order, a list entry per lane
-        const u32 nl_ = S->nlist, n = nl_ < LIST_MAX ? nl_ : LIST_MAX;
-        const u32 F = rest_final > S->F2 ? rest_final : S->F2;
-        const bool have = lane < n;
-        Winner e;
-        if (have) e = S->list[lane];
-        else { e.hi = 0; e.lo = 0; e.cand = NONE32; e.dest = 1; e.kr = 0; e.L1 = 0; e.R = 0; e.a = 0; e.b = 0; e.s = 0; }
-        bool picked = have && e.cand == S->mem[0].cand;  // a migration of this pass already
-        u32 kB = (have && !picked) ? upkey(e.hi, e.lo) : 0u;     // (0: cannot be picked)
-        bool risky = false;                              // a committed flash migration's transfer windows meet this entry's
-        auto risk = [&](u32 wL1, u32 wa, u32 wb, u32 wR) {
-          if (have && !picked && e.dest == 0u && e.kr != 0u && !risky)
-            risky = cyc_overlap(e.L1, e.a - 1, wL1, wa - 1, K) || cyc_overlap(e.b + 1, e.R - 1, wb + 1, wR - 1, K);
-        };
-        if (S->mem[0].dest == 0u) risk(S->mem[0].L1, S->mem[0].a, S->mem[0].b, S->mem[0].R);
-        u32 mmax = MAXM;
-        if (max_iter && max_iter - S->n_iter + 1 < mmax) mmax = (u32)(max_iter - S->n_iter + 1);   // (n_iter counts this pass already)
-        u32 m = 1, by_floor = 0;
-        while (m < mmax) {
-          const u32 kmax = wave_max(kB);
-          if (kmax <= F) { by_floor = 1; if (lane == 0) STAT(kmax ? 13 : 12); break; }   // (F >= 0: also when nothing is left)
-          u64 mk = __ballot(kB == kmax);
-          if (mk & (mk - 1)) {                           // equal keys: high word, low word, lowest index
-            const bool in1 = kB == kmax;
-            const u64 hmax = wave_max(in1 ? e.hi : 0ull);
-            const bool in2 = in1 && e.hi == hmax;
-            const u64 lmax = wave_max(in2 ? e.lo : 0ull);
-            const bool in3 = in2 && e.lo == lmax;
-            const u32 cmin = wave_min(in3 ? e.cand : NONE32);
-            mk = __ballot(in3 && e.cand == cmin);
-          }
-          const u32 bl = (u32)__builtin_ctzll(mk);
-          if (__ballot(risky)) {
-            if (__ballot(risky && lane == bl)) { if (lane == 0) STAT(15); break; }      // its own flash window may be gone
-            const u32 rm = wave_max(risky ? e.kr : 0u);
-            if (rm >= kmax) { if (lane == 0) STAT(14); break; }                        // a candidate at risk might rise above it
-          }
-          if (lane == 0) S->sel[m] = bl;
-          if (lane == bl) { kB = 0u; picked = true; }
-          if (__builtin_amdgcn_readlane((int)e.dest, (int)bl) == 0)
-            risk((u32)__builtin_amdgcn_readlane((int)e.L1, (int)bl), (u32)__builtin_amdgcn_readlane((int)e.a, (int)bl),
-                 (u32)__builtin_amdgcn_readlane((int)e.b, (int)bl), (u32)__builtin_amdgcn_readlane((int)e.R, (int)bl));
-          ++m;
+    // ---- decide and commit -------------------------------------------------------------------
+    // More migrations of the same pass (MC): the ranking also tells which candidate comes second,
+    // third, ...  Candidate w_j wins the pass after w_1 .. w_(j-1) were committed if (1) nothing
+    // those commits change enters its own score - no slot of its absent window can drop under the
+    // capacity, and its transfer windows meet none of theirs on the same channel - and (2) no
+    // other candidate can have risen above it.  Pressure only falls and reservations only grow,
+    // so a benefit rises in one case only: a candidate the policy sends to flash, with a host
+    // window as well, loses its flash window to a reservation and moves to host.  Such a
+    // candidate is at risk once a committed flash migration's transfer windows meet its own; it
+    // then counts with the bound of its host benefit.  Every candidate not on the list of the
+    // pass (tiles left out, candidates under the round's threshold, the overflow of the list)
+    // counts with its bound: the floor F.
+    //
+    // Step 1 (the last wavefront, a list entry per lane): the candidates in the order of their
+    // benefit, as far as (2) and the transfer windows allow.
+    if (MC && wave == LW - 1 && S->nlist > 1u && K < (1u << 30)) {
+      const Winner& W1 = S->mem[0];
+      const u32 nl_ = S->nlist, n = nl_ < LIST_MAX ? nl_ : LIST_MAX;
+      const bool have = lane < n;
+      Winner e;
+      if (have) e = S->list[lane];
+      else { e.hi = 0; e.lo = 0; e.cand = NONE32; e.dest = 1; e.kr = 0; e.L1 = 0; e.R = 0; e.a = 1; e.b = 0; e.s = 0; }
+      bool picked = have && e.cand == W1.cand;         // a migration of this pass already
+      u32 kB = (have && !picked) ? upkey(e.hi, e.lo) : 0u;       // (0: cannot be picked)
+      const u32 eE0 = e.L1, eE1 = e.a - 1, eW0 = e.b + 1, eW1 = e.R - 1, ed = e.dest;
+      const u32 kr = ed == 0u ? e.kr : 0u;
+      bool ov = false;                                 // a transfer window meets one of a committed migration on the same channel
+      auto meet = [&](u32 wd, u32 wL1, u32 wa, u32 wb, u32 wR) {
+        const bool hit = cyc_overlap32(eE0, eE1, wL1, wa - 1, K) || cyc_overlap32(eW0, eW1, wb + 1, wR - 1, K);
+        ov = ov || (hit && ed == wd && !picked);
+      };
+      meet(W1.dest, W1.L1, W1.a, W1.b, W1.R);
+      const u32 F = rest_final > S->F2 ? rest_final : S->F2;
+      u32 mmax = MAXM;
+      if (max_iter && max_iter - S->n_iter + 1 < mmax) mmax = (u32)(max_iter - S->n_iter + 1);   // (n_iter counts this pass already)
+      u32 m = 1, by_floor = 0;
+      while (m < mmax) {
+        const u32 kmax = wave_max(kB);
+        if (kmax <= F) { by_floor = 1; break; }        // (also when nothing is left)
+        u64 mk = __ballot(kB == kmax);
+        if (mk & (mk - 1)) {                           // equal keys: high word, low word, lowest index
+          const bool in1 = kB == kmax;
+          const u64 hmx = wave_max(in1 ? e.hi : 0ull);
+          const bool in2 = in1 && e.hi == hmx;
+          const u64 lmx = wave_max(in2 ? e.lo : 0ull);
+          const bool in3 = in2 && e.lo == lmx;
+          const u32 cmin = wave_min(in3 ? e.cand : NONE32);
+          mk = __ballot(in3 && e.cand == cmin);
         }
-        if (lane >= 1 && lane < m) {                       // the picked entries become migrations 1 .. m - 1
-          Winner x = S->list[S->sel[lane]];
-          x.tau_o = ceil_div_x1000(x.s, x.dest ? bwo1 : bwo0, x.dest ? ivo1 : ivo0);
-          x.tau_i = ceil_div_x1000(x.s, x.dest ? bwi1 : bwi0, x.dest ? ivi1 : ivi0);
-          S->mem[lane] = x;
-        }
-        if (lane == 0) { S->m0 = m; S->by_floor = by_floor; }
+        const u32 bl = (u32)__builtin_ctzll(mk);
+        const u64 ovm = __ballot(ov);
+        if ((ovm >> bl) & 1ull) break;                 // its own windows are not what they were
+        if (ovm && wave_max(ov ? kr : 0u) >= kmax) break;     // a candidate at risk might rise above it
+        if (lane == 0) S->sel[m] = bl;
+        if (lane == bl) { kB = 0u; picked = true; ov = false; }
+        meet((u32)__builtin_amdgcn_readlane((int)ed, (int)bl), (u32)__builtin_amdgcn_readlane((int)e.L1, (int)bl),
+             (u32)__builtin_amdgcn_readlane((int)e.a, (int)bl), (u32)__builtin_amdgcn_readlane((int)e.b, (int)bl),
+             (u32)__builtin_amdgcn_readlane((int)e.R, (int)bl));
+        ++m;
       }
-      __syncthreads();
-      PHASE(3);
-      // Per chunk, the selected migrations in order: how many of them can go together.  The first
-      // that might let a slot drop under the capacity, that needs a chunk of a timeline an earlier
-      // one rewrites, or that host memory might not hold on top of the earlier ones, ends the set
-      // (it is ranked again in the next pass).  For the winner itself the two tests only decide
-      // how it is committed: alone, and with the exact host-capacity test.
-      const u32 m0 = S->m0;
-      if (tid < ((nch + 63u) & ~63u)) {
-        u32 cut = MAXM;
-        bool ex0 = false;
-        if (tid < nch) {
-          const u64 mo = minOver[tid], hm = hmax[tid];
-          u64 runP = 0, runH = 0;
-          u32 usedFO = 0, usedFI = 0, usedH = 0;
-          for (u32 i = 0; i < m0; ++i) {
-            const Winner& M = S->mem[i];
-            const u32 mL1 = M.L1, mR = M.R, ma = M.a, mb = M.b, md = M.dest;
-            const u64 ms = M.s;
-            u32 len = 0;
-            const u32 cE = cover(tid, CH, K, mL1, ma - 1, len), cW = cover(tid, CH, K, mb + 1, mR - 1, len), cA = cover(tid, CH, K, ma, mb, len);
-            const u32 cP = cE + cA + cW;
-            const u32 lim = i ? i : 1u;
-            if (cA) {
-              runP += ms;
-              if (mo != NONE64 && mo - cap <= runP && lim < cut) { cut = lim; STAT(16); }
-            }
-            if (cE) { if (((usedFO >> md) & 1u) && i < cut) { cut = i; STAT(18); } usedFO |= 1u << md; }
-            if (cW) { if (((usedFI >> md) & 1u) && i < cut) { cut = i; STAT(18); } usedFI |= 1u << md; }
-            if (md == G10_HOST && cP) {
-              if (ms > host_cap || hm + runH > host_cap - ms) { if (i == 0) ex0 = true; else if (i < cut) { cut = i; STAT(19); } }
-              runH += ms;
-              if (cP != len) { if (usedH && i < cut) cut = i; usedH = 1; }
-            }
-          }
-        }
-        cut = wave_min(cut);
-        if (lane == 0 && cut < MAXM) atomicMin(&S->cut, cut);
-        if (ex0) S->need_exact = 1;
+      if (lane >= 1 && lane < m) {                     // the picked entries become migrations 1 .. m - 1
+        Winner x = S->list[S->sel[lane]];
+        x.tau_o = ceil_div_x1000(x.s, x.dest ? bwo1 : bwo0, x.dest ? ivo1 : ivo0);
+        x.tau_i = ceil_div_x1000(x.s, x.dest ? bwi1 : bwi0, x.dest ? ivi1 : ivi0);
+        S->mem[lane] = x;
       }
-      __syncthreads();
-      u32 m = m0 < S->cut ? m0 : S->cut;
-      if (tid == 0) { STAT(20 + m0); STAT(20 + m); }      // histograms of selected (doubled at equal) and committed
-      bool room = true;
-      if (S->need_exact) {                               // the winner alone; host memory slot by slot where its period cuts a chunk
-        m = 1;
-        u32 cvP = 0, len = 0;
-        if (tid < nch) cvP = cover(tid, CH, K, L1, R - 1, len);
-        __syncthreads();
-        if (tid == 0) S->hq = 0;
-        __syncthreads();
-        if (cvP == len && cvP) atomicMax((unsigned long long*)&S->hq, (unsigned long long)hmax[tid]);
-        else if (cvP) jobs[atomicAdd(&S->njobs, 1u)] = ((u32)J_HQ << 16) | tid;
-        __syncthreads();
-        run_jobs();
-        __syncthreads();
-        room = s <= host_cap && S->hq <= host_cap - s;
-        __syncthreads();
-        if (tid == 0) S->njobs = 0;
-        __syncthreads();
-      }
-      PHASE(4);
-      if (wave == LW - 1) {                              // the records, the counters, the next pass's first threshold
-        const u64 nm = S->n_mig, nd = S->n_drop;
-        if (lane < m) {
-          const Winner& M = S->mem[lane];
-          const u32 mL1 = M.L1, mR = M.R, ma = M.a, mb = M.b;
-          const u64 ms = M.s;
-          a.cd.A[M.pos] = make_uint4(mL1, mR, 1u, 0u);     // the candidate leaves the live set
-          a.cd.B[M.pos] = make_uint4(1u, 0u, (u32)ms, (u32)(ms >> 32));
-          if (!room) {
-            g10_dropped dr; dr.iteration = S->n_iter - 1; dr.cand = M.cand; dr.reserved = 0;
-            a.dropped[nd] = dr;
-          } else {
-            g10_migration mg;
-            mg.cand = M.cand; mg.tensor = M.tensor;
-            mg.evict_after = mL1 - 1; mg.absent_first = ma >= K ? ma - K : ma; mg.absent_last = mb >= K ? mb - K : mb;
-            mg.next_use = mR >= K ? mR - K : mR;
-            mg.dest = M.dest; mg.wraps = mR >= K ? 1u : 0u;
-            mg.size_bytes = ms; mg.t_out_ns = M.tau_o; mg.t_in_ns = M.tau_i; mg.benefit_lo = M.lo; mg.benefit_hi = M.hi;
-            a.records[nm + lane] = mg;
-            a.rec_ab[nm + lane] = make_uint2(ma, mb);
-          }
-        }
-        if (lane == 0) {
-          // first threshold of the next pass: a little under the last benefit.  How little adapts: where
-          // many candidates are nearly equal (a pass scored thousands) the margin halves; it doubles
-          // when the pass ran out of candidates above the floor with little scored
-          u32 gs = S->gshift;
-          if (pass_units > 8u && gs < GUESS_SHIFT_MAX) ++gs;
-          else if ((S->by_floor || rounds > 1u) && pass_units <= 4u && gs > MC_GUESS_SHIFT_MIN) --gs;
-          S->gshift = gs;
-          u64 ghi = S->mem[m - 1].hi, glo = S->mem[m - 1].lo;
-          const u64 dlo = (glo >> gs) | (ghi << (64 - gs)), dhi = ghi >> gs;
-          const u64 nlo = glo - dlo;
-          ghi = ghi - dhi - (glo < dlo ? 1ull : 0ull);
-          S->thr_key = upkey(ghi, nlo);
-          if (!room) S->n_drop = nd + 1;
-          else {
-            const u64 x = m - 1;                          // the passes of Algorithm 1 this one stands for beyond the first
-            S->n_mig = nm + m; S->n_iter += x;
-            S->n_evals += x * (C - nm - nd) - x * (x + 1) / 2;
-          }
-        }
-      }
-      if (!room) { __syncthreads(); continue; }
-      if (tid == 0) S->m = m;
+      if (lane == 0) { S->m0 = m; S->by_floor = by_floor; }
+    } else if (MC && wave == LW - 1 && lane == 0) S->by_floor = 1;     // (nothing else on the list)
+    __syncthreads();
+    PHASE(3);
 
-      // commit: whole chunks take a lazy add, the others a job
+    // Step 2, chunk by chunk: what every picked migration does to the chunk (kept in `fl`, six bits
+    // each), and how many of them can go together: the first that might let a slot drop under the
+    // capacity, or that host memory might not hold on top of the earlier ones, ends the set (it
+    // is ranked again in the next pass).  For the winner itself the two tests only decide how it
+    // is committed: alone, and with the exact host-capacity test.
+    enum { F_E = 1, F_W = 2, F_ACUT = 4, F_AALL = 8, F_PCUT = 16, F_PALL = 32 };
+    const u32 m0 = S->m0;
+    u64 fl = 0;
+    if (tid < ((nch + 63u) & ~63u)) {
+      u32 cut = MAXM;
+      bool ex0 = false;
       if (tid < nch) {
-        const u32 c = tid;
-        u64 lzP = lazyP[c], mo = minOver[c], lzH = lazyH[c], hm = hmax[c];
-        bool chP = false, chH = false, slots = false;    // slots: the chunk's pressures are gone through one by one
-        for (u32 i = 0; i < m; ++i) {
+        const u64 mo = minOver[tid], hm = hmax[tid];
+        u64 runP = 0, runH = 0;
+        for (u32 i = 0; i < m0; ++i) {
           const Winner& M = S->mem[i];
           const u32 mL1 = M.L1, mR = M.R, ma = M.a, mb = M.b, md = M.dest;
           const u64 ms = M.s;
           u32 len = 0;
-          const u32 cE = cover(c, CH, K, mL1, ma - 1, len), cW = cover(c, CH, K, mb + 1, mR - 1, len), cA = cover(c, CH, K, ma, mb, len);
+          const u32 cE = cover(tid, CH, K, mL1, ma - 1, len), cW = cover(tid, CH, K, mb + 1, mR - 1, len), cA = cover(tid, CH, K, ma, mb, len);
           const u32 cP = cE + cA + cW;
-          if (cE) jobs[atomicAdd(&S->njobs, 1u)] = (i << 20) | ((u32)J_FO << 16) | c;
-          if (cW) jobs[atomicAdd(&S->njobs, 1u)] = (i << 20) | ((u32)J_FI << 16) | c;
-          if (cA == len) {                                 // the whole chunk loses the tensor
-            lzP += ms; chP = true;
-            if (mo != NONE64) {
-              mo -= ms;
-              if (mo <= cap) slots = true;                 // a slot drops under the capacity
-            }
-          } else if (cA) slots = true;
-          if (md == G10_HOST) {
-            if (cP == len) { lzH += ms; hm += ms; chH = true; }
-            else if (cP) jobs[atomicAdd(&S->njobs, 1u)] = (i << 20) | ((u32)J_H << 16) | c;
+          u32 f = (cE ? F_E : 0u) | (cW ? F_W : 0u) | (cA == len ? F_AALL : cA ? F_ACUT : 0u);
+          if (cA) {
+            runP += ms;
+            if (mo != NONE64 && mo - cap <= runP) { const u32 lim = i ? i : 1u; cut = lim < cut ? lim : cut; }
           }
-        }
-        if (chP) { lazyP[c] = lzP; minOver[c] = mo; }
-        if (chH) { lazyH[c] = lzH; hmax[c] = hm; }
-        if (slots) jobs[atomicAdd(&S->njobs, 1u)] = ((u32)J_P_PART << 16) | c;
-      }
-      __syncthreads();
-      PHASE(6);
-      run_jobs();
-      __syncthreads();
-      PHASE(7);
-      // level 1: a transfer window inside one chunk lowers every later chunk's base by the
-      // transfer time; otherwise (and for the over-capacity time, if it changed) scan again
-      {
-        bool simple = S->ot_changed == 0;
-        for (u32 i = 0; i < m && simple; ++i) {
-          const Winner& M = S->mem[i];
-          const u32 mL1 = M.L1, mR = M.R, ma = M.a, mb = M.b;
-          const u32 eA = (mL1 >= K ? mL1 - K : mL1) >> tl.shift_ch, eB = (ma - 1 >= K ? ma - 1 - K : ma - 1) >> tl.shift_ch;
-          const u32 pA = (mb + 1 >= K ? mb + 1 - K : mb + 1) >> tl.shift_ch, pB = (mR - 1 >= K ? mR - 1 - K : mR - 1) >> tl.shift_ch;
-          simple = eA == eB && !(mL1 < K && ma - 1 >= K) && pA == pB && !(mb + 1 < K && mR - 1 >= K);
-        }
-        if (simple) {
-          for (u32 t = tid; t <= nch; t += LB) {           // (index nch: the totals)
-            u64 dFO[2] = {0, 0}, dFI[2] = {0, 0};
-            for (u32 i = 0; i < m; ++i) {
-              const Winner& M = S->mem[i];
-              const u32 mL1 = M.L1, mb = M.b, md = M.dest;
-              const u32 eA = (mL1 >= K ? mL1 - K : mL1) >> tl.shift_ch, pA = (mb + 1 >= K ? mb + 1 - K : mb + 1) >> tl.shift_ch;
-              if (t > eA) dFO[md] += M.tau_o;
-              if (t > pA) dFI[md] += M.tau_i;
-            }
-            for (u32 q = 0; q < 2; ++q) {
-              if (dFO[q]) base[(u64)(A_FO + q) * nb1 + t] -= dFO[q];
-              if (dFI[q]) base[(u64)(A_FI + q) * nb1 + t] -= dFI[q];
-            }
+          if (md == G10_HOST && cP) {
+            f |= cP == len ? F_PALL : F_PCUT;
+            if (ms > host_cap || hm + runH > host_cap - ms) { if (i == 0) ex0 = true; else cut = i < cut ? i : cut; }
+            runH += ms;
           }
-          __syncthreads();
-        } else if (m == 1) {
-          if (S->ot_changed) scan_bases(A_OT, A_FO + d, A_FI + d, 3);
-          else scan_bases(A_FO + d, A_FI + d, 0, 2);
-        } else {
-          scan_bases(A_FO, A_FO + 1, A_FI, 3);
-          scan_bases(A_FI + 1, A_OT, 0, S->ot_changed ? 2 : 1);
+          fl |= (u64)f << (8 * i);
         }
       }
-      PHASE(8);
-      continue;
+      cut = wave_min(cut);
+      if (lane == 0 && cut < MAXM) atomicMin(&S->cut, cut);
+      if (ex0) S->need_exact = 1;
     }
-
-    // which chunks the period, its absent window and its transfer windows cover
-    u32 cvE = 0, cvW = 0, cvA = 0, cvP = 0, len = 0;
-    if (tid < nch) {
-      cvE = cover(tid, CH, K, L1, wa - 1, len);
-      cvW = cover(tid, CH, K, wb + 1, R - 1, len);
-      cvA = cover(tid, CH, K, wa, wb, len);
-      cvP = cvE + cvA + cvW;                             // the period interior [L1, R - 1]
-    }
-    // host memory must hold the tensor during the whole period
+    __syncthreads();
+    u32 m = m0 < S->cut ? m0 : S->cut;
     bool room = true;
-    if (d == G10_HOST) {
-      if (tid < ((nch + 63u) & ~63u)) {                  // bound: the maxima of all chunks the period touches
-        const u64 m = wave_max(cvP ? hmax[tid] : 0ull);
-        if (lane == 0 && m) atomicMax((unsigned long long*)&S->hq, (unsigned long long)m);
-      }
+    if (S->need_exact) {                                 // the winner alone; host memory slot by slot where its period cuts a chunk
+      m = 1;
+      const u64 s = S->mem[0].s;
+      const u32 f0 = (u32)fl & 0xffu;
+      if (tid == 0) S->hq = 0;
+      __syncthreads();
+      if (f0 & F_PALL) atomicMax((unsigned long long*)&S->hq, (unsigned long long)hmax[tid]);
+      else if (f0 & F_PCUT) jobs[atomicAdd(&S->njobs, 1u)] = ((u64)J_HQ << 16) | tid;
+      __syncthreads();
+      run_jobs(1u);
       __syncthreads();
       room = s <= host_cap && S->hq <= host_cap - s;
-      if (!room) {                                       // exact: chunks cut by the period ends slot by slot
-        __syncthreads();
-        if (tid == 0) S->hq = 0;
-        __syncthreads();
-        if (cvP == len && cvP) atomicMax((unsigned long long*)&S->hq, (unsigned long long)hmax[tid]);
-        else if (cvP) jobs[atomicAdd(&S->njobs, 1u)] = ((u32)J_HQ << 16) | tid;
-        __syncthreads();
-        run_jobs();
-        __syncthreads();
-        room = s <= host_cap && S->hq <= host_cap - s;
-        __syncthreads();
-        if (tid == 0) S->njobs = 0;
-        __syncthreads();
-      }
+      __syncthreads();
+      if (tid == 0) S->njobs = 0;
+      __syncthreads();
     }
     PHASE(4);
-    if (tid == LB - G10_WAVE) {                            // (the last wavefront: it has no chunk to classify below)
-      const u32 p = S->mem[0].pos;
-      a.cd.A[p] = make_uint4(L1, R, 1u, 0u);             // the candidate leaves the live set
-      a.cd.B[p] = make_uint4(1u, 0u, (u32)s, (u32)(s >> 32));
-      // first threshold of the next pass: a little under this benefit.  How little adapts: where
-      // many candidates are nearly equal (a pass scored thousands) the margin halves, and it
-      // doubles again when a narrow margin costs second rounds with little to score
-      u32 gs = S->gshift;
-      if (pass_units > 8u && gs < GUESS_SHIFT_MAX) ++gs;
-      else if (rounds > 1u && pass_units <= 2u && gs > GUESS_SHIFT) --gs;
-      S->gshift = gs;
-      u64 ghi = S->mem[0].hi, glo = S->mem[0].lo;
-      const u64 dlo = (glo >> gs) | (ghi << (64 - gs)), dhi = ghi >> gs;
-      const u64 nlo = glo - dlo;
-      ghi = ghi - dhi - (glo < dlo ? 1ull : 0ull);
-      S->thr_key = RATIO ? rkey_dn(ratio_approx(S->mem[0].hi, S->mem[0].lo, S->mem[0].cost) * (1.0 - 1.0 / (double)(1u << gs)))
-                         : upkey(ghi, nlo);
-      if (!room) {
-        g10_dropped dr; dr.iteration = S->n_iter - 1; dr.cand = S->mem[0].cand; dr.reserved = 0;
-        a.dropped[S->n_drop] = dr;
-        S->n_drop += 1;
-      } else {
-        g10_migration mg;
-        mg.cand = S->mem[0].cand; mg.tensor = S->mem[0].tensor;
-        mg.evict_after = L1 - 1; mg.absent_first = wa >= K ? wa - K : wa; mg.absent_last = wb >= K ? wb - K : wb;
-        mg.next_use = R >= K ? R - K : R;
-        mg.dest = d; mg.wraps = R >= K ? 1u : 0u;
-        mg.size_bytes = s; mg.t_out_ns = S->mem[0].tau_o; mg.t_in_ns = S->mem[0].tau_i; mg.benefit_lo = S->mem[0].lo; mg.benefit_hi = S->mem[0].hi;
-        a.records[S->n_mig] = mg;
-        a.rec_ab[S->n_mig] = make_uint2(wa, wb);
-        S->n_mig += 1;
+
+    // Step 3: the plan records, the counters and the next pass's first threshold (the last
+    // wavefront, lane i takes migration i) beside the commit chunk by chunk: a chunk a migration
+    // covers whole takes a lazy add; a chunk that is cut, that holds a transfer window, or in
+    // which a slot drops under the capacity gets a job (with the migrations it is about)
+    if (wave == LW - 1) {
+      const u64 nm = S->n_mig, nd = S->n_drop;
+      if (lane < m) {
+        const Winner& M = S->mem[lane];
+        const u32 mL1 = M.L1, mR = M.R, ma = M.a, mb = M.b;
+        const u64 ms = M.s;
+        a.cd.A[M.pos] = make_uint4(mL1, mR, 1u, 0u);       // the candidate leaves the live set
+        a.cd.B[M.pos] = make_uint4(1u, 0u, (u32)ms, (u32)(ms >> 32));
+        if (!room) {
+          g10_dropped dr; dr.iteration = S->n_iter - 1; dr.cand = M.cand; dr.reserved = 0;
+          a.dropped[nd] = dr;
+        } else {
+          g10_migration mg;
+          mg.cand = M.cand; mg.tensor = M.tensor;
+          mg.evict_after = mL1 - 1; mg.absent_first = ma >= K ? ma - K : ma; mg.absent_last = mb >= K ? mb - K : mb;
+          mg.next_use = mR >= K ? mR - K : mR;
+          mg.dest = M.dest; mg.wraps = mR >= K ? 1u : 0u;
+          mg.size_bytes = ms; mg.t_out_ns = M.tau_o; mg.t_in_ns = M.tau_i; mg.benefit_lo = M.lo; mg.benefit_hi = M.hi;
+          a.records[nm + lane] = mg;
+          a.rec_ab[nm + lane] = make_uint2(ma, mb);
+          atomicOr(&S->touched, (1u << (A_FO + M.dest)) | (1u << (A_FI + M.dest)));
+        }
+      }
+      if (lane == 0) {
+        // first threshold of the next pass: a little under the last benefit.  How little adapts:
+        // where many candidates are nearly equal (a pass scored thousands) the margin halves; it
+        // doubles when a pass ran out of candidates above the floor with little scored
+        u32 gs = S->gshift;
+        if (pass_units > 8u && gs < GUESS_SHIFT_MAX) ++gs;
+        else if (MC) { if ((S->by_floor || rounds > 1u) && pass_units <= 4u && gs > MC_GUESS_SHIFT_MIN) --gs; }
+        else if (rounds > 1u && pass_units <= 2u && gs > GUESS_SHIFT) --gs;
+        S->gshift = gs;
+        const Winner& Z = S->mem[m - 1];
+        u64 ghi = Z.hi, glo = Z.lo;
+        const u64 dlo = (glo >> gs) | (ghi << (64 - gs)), dhi = ghi >> gs;
+        const u64 nlo = glo - dlo;
+        ghi = ghi - dhi - (glo < dlo ? 1ull : 0ull);
+        S->thr_key = RATIO ? rkey_dn(ratio_approx(Z.hi, Z.lo, Z.cost) * (1.0 - 1.0 / (double)(1u << gs))) : upkey(ghi, nlo);
+        if (!room) S->n_drop = nd + 1;
+        else {
+          const u64 x = m - 1;                            // the passes of Algorithm 1 this one stands for beyond the first
+          S->n_mig = nm + m; S->n_iter += x;
+          S->n_evals += x * (C - nm - nd) - x * (x + 1) / 2;
+        }
       }
     }
     if (!room) { __syncthreads(); continue; }
-
-    // commit: whole chunks take a lazy add, the others a job
     if (tid < nch) {
       const u32 c = tid;
-      if (cvE) jobs[atomicAdd(&S->njobs, 1u)] = ((u32)J_FO << 16) | c;
-      if (cvW) jobs[atomicAdd(&S->njobs, 1u)] = ((u32)J_FI << 16) | c;
-      if (cvA == len) {                                  // the whole chunk loses the tensor
-        lazyP[c] += s;
-        u64 mo = minOver[c];
-        if (mo != NONE64) {
-          mo -= s;
-          minOver[c] = mo;
-          if (mo <= cap) jobs[atomicAdd(&S->njobs, 1u)] = ((u32)J_P_FULL << 16) | c;   // a slot drops under the capacity
-        }
-      } else if (cvA) {
-        jobs[atomicAdd(&S->njobs, 1u)] = ((u32)J_P_PART << 16) | c;
+      u64 lzP = 0, lzH = 0;
+      u32 cutP = 0, allP = 0, cutH = 0, allH = 0, fo[2] = {0, 0}, fi[2] = {0, 0};
+      for (u32 i = 0; i < m; ++i) {
+        const u32 f = (u32)(fl >> (8 * i)) & 0xffu;
+        if (!f) continue;
+        const u64 ms = S->mem[i].s;
+        const u32 md = S->mem[i].dest;
+        if (f & F_AALL) { lzP += ms; allP |= 1u << i; }
+        if (f & F_ACUT) cutP |= 1u << i;
+        if (f & F_PALL) { lzH += ms; allH |= 1u << i; }
+        if (f & F_PCUT) cutH |= 1u << i;
+        if (f & F_E) fo[md] |= 1u << i;
+        if (f & F_W) fi[md] |= 1u << i;
       }
-      if (d == G10_HOST) {
-        if (cvP == len) { lazyH[c] += s; hmax[c] += s; }
-        else if (cvP) jobs[atomicAdd(&S->njobs, 1u)] = ((u32)J_H << 16) | c;
+      bool jobP = cutP != 0;
+      if (lzP) {
+        const u64 mo = minOver[c];
+        if (mo != NONE64 && mo - cap <= lzP) jobP = true;       // a slot drops under the capacity
+        if (!jobP) { lazyP[c] += lzP; if (mo != NONE64) minOver[c] = mo - lzP; }
       }
+      if (lzH && !cutH) { lazyH[c] += lzH; hmax[c] += lzH; }
+      // (a job adds the sizes of the migrations that cover its chunk whole itself)
+      if (jobP) jobs[atomicAdd(&S->njobs, 1u)] = ((u64)allP << 32) | ((u64)cutP << 24) | ((u64)J_P << 16) | c;
+      if (cutH) jobs[atomicAdd(&S->njobs, 1u)] = ((u64)allH << 32) | ((u64)cutH << 24) | ((u64)J_H << 16) | c;
+      if (fo[0]) jobs[atomicAdd(&S->njobs, 1u)] = ((u64)fo[0] << 24) | ((u64)J_FO0 << 16) | c;
+      if (fo[1]) jobs[atomicAdd(&S->njobs, 1u)] = ((u64)fo[1] << 24) | ((u64)J_FO1 << 16) | c;
+      if (fi[0]) jobs[atomicAdd(&S->njobs, 1u)] = ((u64)fi[0] << 24) | ((u64)J_FI0 << 16) | c;
+      if (fi[1]) jobs[atomicAdd(&S->njobs, 1u)] = ((u64)fi[1] << 24) | ((u64)J_FI1 << 16) | c;
     }
     __syncthreads();
     PHASE(6);
-    run_jobs();
+    run_jobs(m);
     __syncthreads();
     PHASE(7);
-    // level 1: a transfer window inside one chunk lowers every later chunk's base by the
-    // transfer time; otherwise (and for the over-capacity time, if it changed) scan again
+    // level 1: the bases of the timelines whose chunk totals changed, one wavefront per timeline
     {
-      const u32 eA = (L1 >= K ? L1 - K : L1) >> tl.shift_ch, eB = (wa - 1 >= K ? wa - 1 - K : wa - 1) >> tl.shift_ch;
-      const u32 pA = (wb + 1 >= K ? wb + 1 - K : wb + 1) >> tl.shift_ch, pB = (R - 1 >= K ? R - 1 - K : R - 1) >> tl.shift_ch;
-      const bool oneE = eA == eB && !(L1 < K && wa - 1 >= K), oneP = pA == pB && !(wb + 1 < K && R - 1 >= K);
-      const bool ot = S->ot_changed != 0;
-      if (oneE && oneP && !ot) {
-        if (tid < nch) {
-          if (tid > eA) base[(u64)(A_FO + d) * nb1 + tid] -= S->mem[0].tau_o;
-          if (tid > pA) base[(u64)(A_FI + d) * nb1 + tid] -= S->mem[0].tau_i;
+      const u32 touched = S->touched | (S->ot_changed ? 1u : 0u);
+      if (wave < N_ARR && ((touched >> wave) & 1u)) {
+        const u32 arr = wave;
+        constexpr u32 PER = (NCH_MAX + G10_WAVE - 1) / G10_WAVE;
+        u64 v[PER], sum = 0;
+#pragma unroll
+        for (u32 k = 0; k < PER; ++k) {
+          const u32 c = lane * PER + k;
+          v[k] = c < nch ? tot[(u64)arr * nch + c] : 0ull;
+          sum += v[k];
         }
-        if (tid == 0) { base[(u64)(A_FO + d) * nb1 + nch] -= S->mem[0].tau_o; base[(u64)(A_FI + d) * nb1 + nch] -= S->mem[0].tau_i; }
-        __syncthreads();
-      } else if (ot) scan_bases(A_OT, A_FO + d, A_FI + d, 3);
-      else scan_bases(A_FO + d, A_FI + d, 0, 2);
+        const u64 inc = wave_scan_incl(sum);
+        u64 run = inc - sum;
+#pragma unroll
+        for (u32 k = 0; k < PER; ++k) {
+          const u32 c = lane * PER + k;
+          if (c < nch) base[(u64)arr * nb1 + c] = run;
+          run += v[k];
+        }
+        if (lane == G10_WAVE - 1) base[(u64)arr * nb1 + nch] = inc;
+      }
+      __syncthreads();
+      PHASE(8);
     }
-    PHASE(8);
   }
   __syncthreads();
 
@@ -1137,9 +1071,9 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
 size_t loop_lds_bytes(u32 nch, u32 nt) {
   const size_t ns = (nt + 63) / 64;
   size_t b = 0;
-  b += ((size_t)N_ARR * (nch + 1) + (size_t)N_ARR * nch + (size_t)4 * nch + ns + (size_t)4 * LW) * 8;
+  b += ((size_t)N_ARR * (nch + 1) + (size_t)N_ARR * nch + (size_t)4 * nch + ns + (size_t)4 * LW + (size_t)8 * nch + 8) * 8;
   b += sizeof(Shared);
-  b += ((size_t)nt + ns + (size_t)8 * nch + 8) * 4 + (size_t)nt * 4;
+  b += ((size_t)nt + ns) * 4 + (size_t)nt * 4;
   return (b + 15) & ~(size_t)15;
 }
 

@@ -675,6 +675,7 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     hc.max_iter = p->max_iterations;
     hc.rank = p->rank; hc.area = p->area;
     hc.C = C;
+    hc.smax = h->max_size;
     G10_HIP(hipMemcpyAsync(w->ctl, &hc, sizeof hc, hipMemcpyHostToDevice, q));
     Timelines& tl = x.tl;
     tl.dur = w->dur; tl.P = w->P; tl.fre = w->fre; tl.H = w->H; tl.px = w->px; tl.otc = w->otc;
@@ -965,6 +966,7 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
       fprintf(stderr, "g10: loop phases (us per pass):");
       for (int q = 0; q < 9; ++q) fprintf(stderr, " %d:%.2f", q, hc.phase[q] / 100.0 / (double)(hc.n_iter ? hc.n_iter : 1));
       fprintf(stderr, "  live/pass %.1f dests/pass %.1f real passes %llu\n", hc.phase[9] / (double)(hc.n_iter ? hc.n_iter : 1), hc.phase[10] / (double)(hc.n_iter ? hc.n_iter : 1), (unsigned long long)hc.phase[11]);
+      fprintf(stderr, "g10: last wavefront (us per real pass): scan %.2f host %.2f select %.2f finalize %.2f\n", hc.phase[29] / 100.0 / (double)hc.phase[11], hc.phase[30] / 100.0 / (double)hc.phase[11], hc.phase[31] / 100.0 / (double)hc.phase[11], hc.phase[17] / 100.0 / (double)hc.phase[11]);
       fprintf(stderr, "g10: stats:");
       for (int q = 12; q < 32; ++q) fprintf(stderr, " %d:%llu", q, (unsigned long long)hc.phase[q]);
       fprintf(stderr, "\n");

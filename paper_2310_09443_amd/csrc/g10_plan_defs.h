@@ -12,7 +12,7 @@
 namespace g10 {
 
 enum { A_OT = 0, A_FO = 1, A_FI = 3, N_ARR = 5, PX = 8 };
-enum { J_FO = 0, J_FI = 1, J_P_PART = 2, J_P_FULL = 3, J_H = 4, J_HQ = 5, J_CLIP = 6 };
+enum { J_P = 0, J_H = 1, J_FO0 = 2, J_FO1 = 3, J_FI0 = 4, J_FI1 = 5, J_HQ = 6, J_CLIP = 7 };   // kinds of chunk jobs
 
 #ifndef G10_LOOP_THREADS
 #define G10_LOOP_THREADS 512
@@ -39,6 +39,7 @@ struct Ctl {
   u32 rank, area;             // G10_RANK_BENEFIT / G10_RANK_RATIO; G10_AREA_BAND / G10_AREA_CLIPPED
   u64 inv_out[2], inv_in[2];  // floor(2^64 / bandwidth), 0 for bandwidth 1
   u64 C;                      // all inactive periods (live before any removal)
+  u64 smax;                   // the largest tensor of the trace
   // progress
   u32 done, status;
   u64 n_iter, n_mig, n_drop, n_evals;

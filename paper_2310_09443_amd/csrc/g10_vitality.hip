@@ -85,6 +85,7 @@ int scan_excl(const T* in, T* out, u64 n, T* scratch, hipStream_t s) {
 struct VitStats {
   u32 bad_index, zero_dur, zero_size, size_overflow;
   u32 big_size, pad;         // a tensor of 2^43 bytes or more
+  u64 max_size;              // the largest tensor
   u64 dur_lo, dur_hi;        // sum of low / high 32-bit halves of the durations
   u64 used_lo, used_hi;      // same for the sizes of used tensors
   u64 n_uses, n_periods, peak;
@@ -119,8 +120,10 @@ __global__ __launch_bounds__(G10_BLOCK) void k_check_dur(const u64* __restrict__
 
 __global__ __launch_bounds__(G10_BLOCK) void k_check_size(const u64* __restrict__ size, u32 N, VitStats* st) {
   u32 zero = 0, ovf = 0, big = 0;
+  u64 mx = 0;
   for (u64 i = (u64)blockIdx.x * G10_BLOCK + threadIdx.x; i < N; i += (u64)gridDim.x * G10_BLOCK) {
     u64 s = size[i];
+    mx = s > mx ? s : mx;
     zero |= s == 0;
     ovf |= s > 0xffffffffffffffffull / 1000ull;
     big |= (s >> 43) != 0;
@@ -128,6 +131,8 @@ __global__ __launch_bounds__(G10_BLOCK) void k_check_size(const u64* __restrict_
   if (__any(zero) && lane_id() == 0) atomicOr(&st->zero_size, 1u);
   if (__any(ovf) && lane_id() == 0) atomicOr(&st->size_overflow, 1u);
   if (__any(big) && lane_id() == 0) atomicOr(&st->big_size, 1u);
+  mx = wave_max(mx);
+  if (lane_id() == 0) atomicMax((unsigned long long*)&st->max_size, (unsigned long long)mx);
 }
 
 // ===========================================================================
@@ -699,6 +704,7 @@ int vitality_run(g10_plan_s* h, const g10_trace* tr) {
     if (used >> 64) return G10_EOVERFLOW;
   }
   h->big_size = hs.big_size != 0;
+  h->max_size = hs.max_size;
   h->n_uses = hs.n_uses;
   h->n_periods = hs.n_periods;
   h->peak = hs.peak;
