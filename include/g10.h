@@ -36,7 +36,9 @@ enum {
   G10_EOVERFLOW = -2, /* sum of durations >= 2^62, sum of used sizes >= 2^64,
                          or a size * 1000 >= 2^64                                      */
   G10_ENOMEM = -3,    /* host or device allocation failed                              */
-  G10_EDEVICE = -4    /* a HIP call failed                                             */
+  G10_EDEVICE = -4,   /* a HIP call failed                                             */
+  G10_ELIMIT = -5     /* g10_vitality_static only: the trace is larger than the fixed
+                         device memory of that call can take                           */
 };
 
 enum { G10_FLASH = 0, G10_HOST = 1 };          /* migration destinations               */
@@ -190,6 +192,39 @@ int g10_vitality_info(const g10_plan_t *handle, g10_vitality_stats *out);
  *   5 start    u64[K+1]  start time of every kernel slot
  *   6 pressure u64[K] */
 int g10_vitality_read(const g10_plan_t *handle, int which, void *dst, uint64_t bytes);
+
+/* Device buffers for the results of g10_vitality_static, owned by the caller. */
+typedef struct {
+  uint64_t *use_off;     /* device [N+1]  CSR offsets into use_k                              */
+  uint32_t *use_k;       /* device [P]    the first n_uses entries are written                */
+  uint32_t *per_tensor;  /* device [P]    the first n_periods entries of these three are      */
+  uint32_t *per_L;       /* device [P]    written (L = last use before the period, R = next   */
+  uint32_t *per_R;       /* device [P]    use; R >= K for the cross-iteration period)         */
+  uint64_t *start;       /* device [K+1]  start time of every kernel slot                     */
+  uint64_t *pressure;    /* device [K]    bytes resident per kernel slot                      */
+} g10_vitality_buffers;
+
+#define G10_STATIC_MAX_K 131072u            /* limits of g10_vitality_static ...              */
+#define G10_STATIC_MAX_N 262144u
+#define G10_STATIC_MAX_P 262144u
+#define G10_STATIC_SCRATCH_BYTES (24u << 20) /* ... and the device memory it works in, per GPU */
+
+/* g10_vitality for callers that cannot allocate: code under HIP graph capture or between
+ * captures, tight serving loops, harnesses that forbid hipMalloc.  The same analysis, the same
+ * results bit for bit, but no handle: the results are written into the caller's device buffers
+ * (`out`, sized as listed above) and the counts into `stats` (host).  The call allocates
+ * nothing, on the device or through any library: every intermediate lives in one fixed array
+ * of G10_STATIC_SCRATCH_BYTES bytes that the library holds on each GPU it runs on until the
+ * process ends.  The trace's arrays are read in place during the call.  Traces beyond
+ * G10_STATIC_MAX_K kernels, G10_STATIC_MAX_N tensors or G10_STATIC_MAX_P pairs (or whose
+ * intermediates would not fit the array) are refused with G10_ELIMIT before any work.  All calls
+ * on one GPU share that array, which keeps the last call's contents (the call clears what it
+ * needs cleared): calls that overlap in time on one GPU race and must be serialised by the
+ * caller.  Enqueues on `hip_stream` and synchronises it before returning.  No planning can follow
+ * (use g10_vitality for that).
+ * Errors: G10_EINVAL / G10_EOVERFLOW as g10_vitality, G10_ELIMIT, G10_EDEVICE. */
+int g10_vitality_static(const g10_trace *trace, void *hip_stream, const g10_vitality_buffers *out,
+                        g10_vitality_stats *stats);
 
 /* Smart tensor eviction (Algorithm 1, Section 4.3) on an analysed trace: the
  * whole greedy loop - scoring of the live candidates against the pressure and

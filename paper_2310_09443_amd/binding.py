@@ -15,13 +15,14 @@ import numpy as np
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libg10.so")
 
-OK, EINVAL, EOVERFLOW, ENOMEM, EDEVICE = 0, -1, -2, -3, -4
+OK, EINVAL, EOVERFLOW, ENOMEM, EDEVICE, ELIMIT = 0, -1, -2, -3, -4, -5
 FLASH, HOST = 0, 1
 FITS, RESIDUAL, TRUNCATED = 0, 1, 2
 NO_WRAP = 1
 
-EXPORTS = ["g10_vitality", "g10_vitality_info", "g10_vitality_read", "g10_plan", "g10_plan_batch", "g10_prefetch", "g10_replay",
-           "g10_plan_free"]
+EXPORTS = ["g10_vitality", "g10_vitality_info", "g10_vitality_read", "g10_vitality_static", "g10_plan", "g10_plan_batch",
+           "g10_prefetch", "g10_replay", "g10_plan_free"]
+STATIC_MAX_K, STATIC_MAX_N, STATIC_MAX_P = 131072, 262144, 262144
 
 MIGRATION = np.dtype([("cand", "<u4"), ("tensor", "<u4"), ("evict_after", "<u4"),
                       ("absent_first", "<u4"), ("absent_last", "<u4"), ("next_use", "<u4"),
@@ -46,6 +47,11 @@ class _Trace(C.Structure):
 class _Stats(C.Structure):
     _fields_ = [("n_uses", C.c_uint64), ("n_periods", C.c_uint64), ("peak_bytes", C.c_uint64),
                 ("iter_ns", C.c_uint64)]
+
+
+class _VitalityBuffers(C.Structure):
+    _fields_ = [("use_off", C.c_void_p), ("use_k", C.c_void_p), ("per_tensor", C.c_void_p), ("per_L", C.c_void_p),
+                ("per_R", C.c_void_p), ("start", C.c_void_p), ("pressure", C.c_void_p)]
 
 
 class _Params(C.Structure):
@@ -97,6 +103,7 @@ def load():
         lib.g10_vitality.argtypes = [C.POINTER(_Trace), C.c_void_p, C.POINTER(C.c_void_p)]
         lib.g10_vitality_info.argtypes = [C.c_void_p, C.POINTER(_Stats)]
         lib.g10_vitality_read.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_uint64]
+        lib.g10_vitality_static.argtypes = [C.POINTER(_Trace), C.c_void_p, C.POINTER(_VitalityBuffers), C.POINTER(_Stats)]
         lib.g10_plan.argtypes = [C.c_void_p, C.POINTER(_Params), C.POINTER(_Result)]
         lib.g10_plan_batch.argtypes = [C.c_void_p, C.POINTER(_Params), C.c_uint32, C.POINTER(_Result)]
         lib.g10_prefetch.argtypes = [C.c_void_p, C.POINTER(_PrefetchResult)]
@@ -302,6 +309,53 @@ class Handle:
 
 def g10_vitality(dtrace: DeviceTrace, no_wrap: bool = False, stream=None) -> Handle:
     return Handle(dtrace, no_wrap, stream)
+
+
+class StaticVitality:
+    """Results of g10_vitality_static: the caller's device buffers (torch tensors made here, before
+    the call) and the counts.  The arrays come back as numpy copies through the properties."""
+
+    def __init__(self, dtrace: DeviceTrace, no_wrap: bool = False, stream=None, buffers=None):
+        import torch
+        lib = load()
+        dev = dtrace.device
+        K, N, P = dtrace.K, dtrace.N, dtrace.P
+        if buffers is None:                         # (a caller may bring tensors it already holds)
+            buffers = dict(use_off=torch.empty(N + 1, dtype=torch.int64, device=dev),
+                           use_k=torch.empty(max(P, 1), dtype=torch.int32, device=dev),
+                           per_tensor=torch.empty(max(P, 1), dtype=torch.int32, device=dev),
+                           per_L=torch.empty(max(P, 1), dtype=torch.int32, device=dev),
+                           per_R=torch.empty(max(P, 1), dtype=torch.int32, device=dev),
+                           start=torch.empty(K + 1, dtype=torch.int64, device=dev),
+                           pressure=torch.empty(K, dtype=torch.int64, device=dev))
+        self.buffers = buffers
+        b = _VitalityBuffers(*(buffers[f].data_ptr() for f, _ in _VitalityBuffers._fields_))
+        if stream is None:
+            stream = torch.cuda.current_stream(dev).cuda_stream
+        t = _Trace(K, N, P, dtrace.dur.data_ptr(), dtrace.size.data_ptr(), dtrace.glob.data_ptr(),
+                   dtrace.uk.data_ptr() if P else None, dtrace.ut.data_ptr() if P else None, NO_WRAP if no_wrap else 0)
+        s = _Stats()
+        with torch.cuda.device(dev):
+            rc = lib.g10_vitality_static(C.byref(t), C.c_void_p(stream), C.byref(b), C.byref(s))
+        if rc:
+            raise G10Error(rc, "g10_vitality_static")
+        self.K, self.N = K, N
+        self.n_uses, self.C, self.peak, self.T = int(s.n_uses), int(s.n_periods), int(s.peak_bytes), int(s.iter_ns)
+
+    def _get(self, name, n, dtype):
+        return self.buffers[name][:n].cpu().numpy().view(dtype).copy()
+
+    use_off = property(lambda self: self._get("use_off", self.N + 1, np.uint64))
+    use_k = property(lambda self: self._get("use_k", self.n_uses, np.uint32))
+    per_tensor = property(lambda self: self._get("per_tensor", self.C, np.uint32))
+    per_L = property(lambda self: self._get("per_L", self.C, np.uint32))
+    per_R = property(lambda self: self._get("per_R", self.C, np.uint32))
+    start = property(lambda self: self._get("start", self.K + 1, np.uint64))
+    pressure = property(lambda self: self._get("pressure", self.K, np.uint64))
+
+
+def g10_vitality_static(dtrace: DeviceTrace, no_wrap: bool = False, stream=None, buffers=None) -> StaticVitality:
+    return StaticVitality(dtrace, no_wrap, stream, buffers)
 
 
 def g10_plan(handle: Handle, gpu_cap, host_cap, bw_out, bw_in, max_iters=0, max_tiles=0, max_chunks=0, dur=None, rank=0, area=0) -> Result:

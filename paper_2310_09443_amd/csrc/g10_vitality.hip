@@ -401,6 +401,9 @@ __global__ __launch_bounds__(G10_BLOCK) void k_gather_periods(const u64* __restr
 __global__ __launch_bounds__(G10_BLOCK) void k_fill_u64(u64* p, u64 n, u64 v) {
   for (u64 i = (u64)blockIdx.x * G10_BLOCK + threadIdx.x; i < n; i += (u64)gridDim.x * G10_BLOCK) p[i] = v;
 }
+__global__ __launch_bounds__(G10_BLOCK) void k_fill_u32(u32* p, u64 n, u32 v) {
+  for (u64 i = (u64)blockIdx.x * G10_BLOCK + threadIdx.x; i < n; i += (u64)gridDim.x * G10_BLOCK) p[i] = v;
+}
 
 __global__ __launch_bounds__(G10_BLOCK) void k_lifetime_adds(const u64* __restrict__ ukeys, const u64* __restrict__ use_off,
                                                             const u64* __restrict__ size, const uint8_t* __restrict__ glob,
@@ -599,33 +602,47 @@ int slot_times_end(const void* check, u64* T_out) {
   return G10_OK;
 }
 
-int vitality_run(g10_plan_s* h, const g10_trace* tr) {
+// Device memory an analysis of K kernels, N tensors and P pairs takes: the temporaries of the call,
+// and what outlives it (`planning`: with own copies of the trace's arrays and the periods in the
+// order of their start, which only planning needs).
+static size_t vit_tmp_bytes(u32 K, u32 N, u64 P) {
+  const u64 ss_kn = scan_scratch_elems(K > N ? K : N), rh = radix_hist_elems(P), ss_p = scan_scratch_elems(rh > P ? rh : P);
+  return Pool::need(1, sizeof(VitStats)) + Pool::need(ss_kn, 8) + 2 * Pool::need(P, 8) + 2 * Pool::need(P + 1, 4) +
+         Pool::need(rh, 4) + Pool::need(ss_p, 4);
+}
+static size_t vit_keep_bytes(u32 K, u32 N, u64 P, bool planning) {
+  // (the arrays per period are sized for P entries: there are fewer periods than uses, fewer uses than pairs)
+  size_t b = Pool::need((u64)K + 1, 8) + Pool::need(P, 8) + Pool::need(P, 4) + Pool::need((u64)N + 1, 8) + 3 * Pool::need(P, 4) +
+             Pool::need((u64)K + 2, 8);
+  if (planning) b += Pool::need(K, 8) + Pool::need(N, 8) + Pool::need(N, 1) + Pool::need(P, 16) + Pool::need(P, 8);
+  return b;
+}
+
+// The analysis proper, in memory the caller of this function provides (two pools of at least
+// vit_tmp_bytes / vit_keep_bytes).
+static int vitality_core(g10_plan_s* h, const g10_trace* tr, Pool& tmp, Pool& keep, const bool planning) {
   hipStream_t s = h->stream;
   const u32 K = h->K, N = h->N;
   const u64 P = h->P;
-  if (P >= (1ull << 32)) return G10_EINVAL;      // positions and counts are 32-bit on the device
-  const u64 ss_kn = scan_scratch_elems(K > N ? K : N), rh = radix_hist_elems(P), ss_p = scan_scratch_elems(rh > P ? rh : P);
-  Pool tmp, keep;                                 // temporaries of this call; what the handle keeps
-  tmp.owned = true;
-  G10_TRY(tmp.reserve(Pool::need(1, sizeof(VitStats)) + Pool::need(ss_kn, 8) + 2 * Pool::need(P, 8) + 2 * Pool::need(P + 1, 4) +
-                      Pool::need(rh, 4) + Pool::need(ss_p, 4)));
-  // (the arrays per period are sized for P entries: there are fewer periods than uses, fewer uses than pairs)
-  G10_TRY(keep.reserve(Pool::need(K, 8) + Pool::need(N, 8) + Pool::need(N, 1) + Pool::need((u64)K + 1, 8) + Pool::need(P, 8) +
-                       Pool::need(P, 4) + Pool::need((u64)N + 1, 8) + 3 * Pool::need(P, 4) + Pool::need((u64)K + 2, 8) +
-                       Pool::need(P, 16) + Pool::need(P, 8)));
-  h->arena = keep.base;                           // released with the handle
 
   VitStats* st = nullptr;
   G10_TRY(tmp.take(&st, 1));
-  G10_HIP(hipMemsetAsync(st, 0, sizeof(VitStats), s));
+  static_assert(sizeof(VitStats) % 8 == 0, "cleared as 64-bit words");
+  hipLaunchKernelGGL(k_fill_u64, dim3(1), dim3(G10_BLOCK), 0, s, (u64*)st, (u64)(sizeof(VitStats) / 8), 0ull);
+  G10_HIP(hipGetLastError());
 
-  // own copies of what planning needs later
-  G10_TRY(keep.take(&h->dur, K));
-  G10_TRY(keep.take(&h->size, N));
-  G10_TRY(keep.take(&h->glob, N));
-  G10_HIP(hipMemcpyAsync(h->dur, tr->dur_ns, (u64)K * 8, hipMemcpyDeviceToDevice, s));
-  G10_HIP(hipMemcpyAsync(h->size, tr->size_bytes, (u64)N * 8, hipMemcpyDeviceToDevice, s));
-  G10_HIP(hipMemcpyAsync(h->glob, tr->is_global, (u64)N, hipMemcpyDeviceToDevice, s));
+  if (planning) {                                 // own copies of what planning needs later
+    G10_TRY(keep.take(&h->dur, K));
+    G10_TRY(keep.take(&h->size, N));
+    G10_TRY(keep.take(&h->glob, N));
+    G10_HIP(hipMemcpyAsync(h->dur, tr->dur_ns, (u64)K * 8, hipMemcpyDeviceToDevice, s));
+    G10_HIP(hipMemcpyAsync(h->size, tr->size_bytes, (u64)N * 8, hipMemcpyDeviceToDevice, s));
+    G10_HIP(hipMemcpyAsync(h->glob, tr->is_global, (u64)N, hipMemcpyDeviceToDevice, s));
+  } else {                                        // the caller's arrays are read in place, during the call only
+    h->dur = const_cast<u64*>(tr->dur_ns);
+    h->size = const_cast<u64*>(tr->size_bytes);
+    h->glob = const_cast<uint8_t*>(tr->is_global);
+  }
 
   // ---- validation --------------------------------------------------------
   if (P) hipLaunchKernelGGL(k_check_pairs, dim3(grid_for(P)), dim3(G10_BLOCK), 0, s, tr->use_kernel, tr->use_tensor, P, K, N, st);
@@ -678,7 +695,7 @@ int vitality_run(g10_plan_s* h, const g10_trace* tr) {
   u32* pcnt = nullptr;
   G10_TRY(tmp.take(&pcnt, P + 1));
   const u32 no_wrap = (h->flags & G10_NO_WRAP) ? 1u : 0u;
-  G10_HIP(hipMemsetAsync(pcnt, 0, (P + 1) * sizeof(u32), s));
+  hipLaunchKernelGGL(k_fill_u32, dim3(grid_for(P + 1)), dim3(G10_BLOCK), 0, s, pcnt, P + 1, 0u);
   if (P) hipLaunchKernelGGL(k_period_count, dim3(grid_for(P)), dim3(G10_BLOCK), 0, s, h->ukeys, h->use_off, h->glob, n_uses_p, K, h->kbits, no_wrap, pcnt);
   G10_TRY(scan_excl_u32(pcnt, pcnt, P, scratch32, s));           // pcnt[P] = n_periods (entries past n_uses are 0)
   G10_TRY(keep.take(&h->per_t, P));
@@ -709,6 +726,8 @@ int vitality_run(g10_plan_s* h, const g10_trace* tr) {
   h->n_periods = hs.n_periods;
   h->peak = hs.peak;
 
+  if (!planning) return G10_OK;
+
   // ---- the periods once more, ordered by their start --------------------------------------
   // Planning walks the periods with one thread each and looks up the timeline around their
   // start and end; in this order neighbouring threads look at neighbouring slots.
@@ -724,5 +743,74 @@ int vitality_run(g10_plan_s* h, const g10_trace* tr) {
     G10_HIP(hipGetLastError());
     G10_HIP(hipStreamSynchronize(s));               // the temporaries go away with this function
   }
+  return G10_OK;
+}
+
+int vitality_run(g10_plan_s* h, const g10_trace* tr) {
+  if (h->P >= (1ull << 32)) return G10_EINVAL;    // positions and counts are 32-bit on the device
+  Pool tmp, keep;                                 // temporaries of this call; what the handle keeps
+  tmp.owned = true;
+  G10_TRY(tmp.reserve(vit_tmp_bytes(h->K, h->N, h->P)));
+  G10_TRY(keep.reserve(vit_keep_bytes(h->K, h->N, h->P, true)));
+  h->arena = keep.base;                           // released with the handle
+  return vitality_core(h, tr, tmp, keep, true);
+}
+
+// ===========================================================================
+// The analysis for callers that cannot allocate: all device memory beyond the caller's inputs
+// and outputs is this array, one copy per GPU, held until the process ends.  Its address on the
+// current device is asked for once per device (the array's name itself is only a host-side
+// stand-in and is never passed to a kernel or a copy).
+// ===========================================================================
+static __device__ __align__(256) unsigned char scratch[G10_STATIC_SCRATCH_BYTES];
+
+enum { G10_MAX_DEVICES = 64 };
+static unsigned char* scratch_on_device[G10_MAX_DEVICES] = {};
+
+extern "C" int g10_vitality_static(const g10_trace* tr, void* hip_stream, const g10_vitality_buffers* out,
+                                   g10_vitality_stats* stats) {
+  if (stats) memset(stats, 0, sizeof *stats);
+  if (!tr || !out || !stats) return G10_EINVAL;
+  if (!tr->K || !tr->N) return G10_EINVAL;
+  if (!tr->dur_ns || !tr->size_bytes || !tr->is_global) return G10_EINVAL;
+  if (tr->P && (!tr->use_kernel || !tr->use_tensor)) return G10_EINVAL;
+  if (!out->use_off || !out->start || !out->pressure) return G10_EINVAL;
+  if (tr->P && (!out->use_k || !out->per_tensor || !out->per_L || !out->per_R)) return G10_EINVAL;
+  if (tr->K > G10_STATIC_MAX_K || tr->N > G10_STATIC_MAX_N || tr->P > G10_STATIC_MAX_P) return G10_ELIMIT;
+  const size_t need_tmp = vit_tmp_bytes(tr->K, tr->N, tr->P), need_keep = vit_keep_bytes(tr->K, tr->N, tr->P, false);
+  if (need_tmp + need_keep > (size_t)G10_STATIC_SCRATCH_BYTES) return G10_ELIMIT;
+  int dev = 0;
+  G10_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= G10_MAX_DEVICES) return G10_EDEVICE;
+  if (!scratch_on_device[dev]) {
+    void* q = nullptr;
+    G10_HIP(hipGetSymbolAddress(&q, HIP_SYMBOL(scratch)));
+    if (!q) return G10_EDEVICE;
+    scratch_on_device[dev] = (unsigned char*)q;
+  }
+  unsigned char* const mem = scratch_on_device[dev];
+
+  g10_plan_s h;                                   // (lives on the stack for the call; nothing of it is handed out)
+  h.device = dev;
+  h.stream = (hipStream_t)hip_stream;
+  h.K = tr->K; h.N = tr->N; h.P = tr->P; h.flags = tr->flags;
+  Pool tmp, keep;                                 // both inside the array; neither owns it
+  tmp.base = (char*)mem; tmp.cap = need_tmp;
+  keep.base = (char*)mem + need_tmp; keep.cap = need_keep;
+  hipStream_t s = h.stream;
+  int rc = vitality_core(&h, tr, tmp, keep, false);
+  if (rc) { (void)hipStreamSynchronize(s); return rc; }
+  // the results go into the caller's buffers
+  G10_HIP(hipMemcpyAsync(out->use_off, h.use_off, ((u64)h.N + 1) * 8, hipMemcpyDeviceToDevice, s));
+  G10_HIP(hipMemcpyAsync(out->start, h.start, ((u64)h.K + 1) * 8, hipMemcpyDeviceToDevice, s));
+  G10_HIP(hipMemcpyAsync(out->pressure, h.pressure_buf + 1, (u64)h.K * 8, hipMemcpyDeviceToDevice, s));
+  if (h.n_uses) G10_HIP(hipMemcpyAsync(out->use_k, h.use_k, h.n_uses * 4, hipMemcpyDeviceToDevice, s));
+  if (h.n_periods) {
+    G10_HIP(hipMemcpyAsync(out->per_tensor, h.per_t, h.n_periods * 4, hipMemcpyDeviceToDevice, s));
+    G10_HIP(hipMemcpyAsync(out->per_L, h.per_L, h.n_periods * 4, hipMemcpyDeviceToDevice, s));
+    G10_HIP(hipMemcpyAsync(out->per_R, h.per_R, h.n_periods * 4, hipMemcpyDeviceToDevice, s));
+  }
+  G10_HIP(hipStreamSynchronize(s));
+  stats->n_uses = h.n_uses; stats->n_periods = h.n_periods; stats->peak_bytes = h.peak; stats->iter_ns = h.T;
   return G10_OK;
 }
