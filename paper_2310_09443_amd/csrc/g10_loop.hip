@@ -33,10 +33,14 @@ struct Winner {               // what a commit needs of the winning candidate
   u32 pad;
 };
 
-constexpr u32 MAXM = 8;       // migrations committed in one ranking pass at most
+#ifndef G10_MAXM
+#define G10_MAXM 16
+#endif
+constexpr u32 MAXM = G10_MAXM; // migrations committed in one ranking pass at most (a multiple of 8, at most 16: the job words hold two sets of 16)
+static_assert(MAXM % 8 == 0 && MAXM <= 16, "job words and chunk flags are laid out for 8 or 16");
 
 #ifndef G10_MC_GSMIN
-#define G10_MC_GSMIN 5
+#define G10_MC_GSMIN 4
 #endif
 constexpr u32 MC_GUESS_SHIFT_MIN = G10_MC_GSMIN;   // the widest margin of a pass's first threshold under the last benefit: 2^-this
 constexpr u32 LIST_MAX = 64;  // candidates of a pass that are looked at for the second and later migrations
@@ -442,7 +446,7 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
     const u32 nj = S->njobs;
     for (u32 jb = wave; jb < nj; jb += LW) {
       const u64 jw = jobs[jb];
-      const u32 type = (u32)(jw >> 16) & 0xffu, c = (u32)jw & 0xffffu, ma_ = (u32)(jw >> 24) & 0xffu, mb_ = (u32)(jw >> 32) & 0xffu;
+      const u32 type = (u32)(jw >> 16) & 0xffu, c = (u32)jw & 0xffffu, ma_ = (u32)(jw >> 24) & 0xffffu, mb_ = (u32)(jw >> 40) & 0xffffu;
       const u32 s0 = c * CH, s1 = (s0 + CH - 1 < K - 1) ? s0 + CH - 1 : K - 1;
       if (type >= J_FO0 && type <= J_FI1) {
         // channel time of the transfer windows of this destination that meet the chunk is taken
@@ -882,7 +886,7 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
     // is committed: alone, and with the exact host-capacity test.
     enum { F_E = 1, F_W = 2, F_ACUT = 4, F_AALL = 8, F_PCUT = 16, F_PALL = 32 };
     const u32 m0 = S->m0;
-    u64 fl = 0;
+    u64 fl[MAXM / 8] = {};
     if (tid < ((nch + 63u) & ~63u)) {
       u32 cut = MAXM;
       bool ex0 = false;
@@ -906,7 +910,7 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
             if (ms > host_cap || hm + runH > host_cap - ms) { if (i == 0) ex0 = true; else cut = i < cut ? i : cut; }
             runH += ms;
           }
-          fl |= (u64)f << (8 * i);
+          fl[i >> 3] |= (u64)f << (8 * (i & 7u));
         }
       }
       cut = wave_min(cut);
@@ -919,7 +923,7 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
     if (S->need_exact) {                                 // the winner alone; host memory slot by slot where its period cuts a chunk
       m = 1;
       const u64 s = S->mem[0].s;
-      const u32 f0 = (u32)fl & 0xffu;
+      const u32 f0 = (u32)fl[0] & 0xffu;
       if (tid == 0) S->hq = 0;
       __syncthreads();
       if (f0 & F_PALL) atomicMax((unsigned long long*)&S->hq, (unsigned long long)hmax[tid]);
@@ -990,7 +994,7 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
       u64 lzP = 0, lzH = 0;
       u32 cutP = 0, allP = 0, cutH = 0, allH = 0, fo[2] = {0, 0}, fi[2] = {0, 0};
       for (u32 i = 0; i < m; ++i) {
-        const u32 f = (u32)(fl >> (8 * i)) & 0xffu;
+        const u32 f = (u32)(fl[i >> 3] >> (8 * (i & 7u))) & 0xffu;
         if (!f) continue;
         const u64 ms = S->mem[i].s;
         const u32 md = S->mem[i].dest;
@@ -1009,8 +1013,8 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
       }
       if (lzH && !cutH) { lazyH[c] += lzH; hmax[c] += lzH; }
       // (a job adds the sizes of the migrations that cover its chunk whole itself)
-      if (jobP) jobs[atomicAdd(&S->njobs, 1u)] = ((u64)allP << 32) | ((u64)cutP << 24) | ((u64)J_P << 16) | c;
-      if (cutH) jobs[atomicAdd(&S->njobs, 1u)] = ((u64)allH << 32) | ((u64)cutH << 24) | ((u64)J_H << 16) | c;
+      if (jobP) jobs[atomicAdd(&S->njobs, 1u)] = ((u64)allP << 40) | ((u64)cutP << 24) | ((u64)J_P << 16) | c;
+      if (cutH) jobs[atomicAdd(&S->njobs, 1u)] = ((u64)allH << 40) | ((u64)cutH << 24) | ((u64)J_H << 16) | c;
       if (fo[0]) jobs[atomicAdd(&S->njobs, 1u)] = ((u64)fo[0] << 24) | ((u64)J_FO0 << 16) | c;
       if (fo[1]) jobs[atomicAdd(&S->njobs, 1u)] = ((u64)fo[1] << 24) | ((u64)J_FO1 << 16) | c;
       if (fi[0]) jobs[atomicAdd(&S->njobs, 1u)] = ((u64)fi[0] << 24) | ((u64)J_FI0 << 16) | c;

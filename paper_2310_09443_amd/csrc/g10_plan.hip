@@ -422,7 +422,7 @@ static const u32 SCORE_SORT_BITS = 23;           // significant bits of a score 
 static const u32 SCORE_SORT_PASSES = (SCORE_SORT_BITS + 7) / 8;
 static const u32 PASS_BUDGET = 4096;             // ranking passes per launch of the loop kernel
 #ifndef G10_RETILE_PASSES
-#define G10_RETILE_PASSES 256
+#define G10_RETILE_PASSES 128
 #endif
 static const u32 RETILE_PASSES = G10_RETILE_PASSES;   // ... between two re-tilings of a long candidate list
 static const u32 RETILE_MIN_CANDS = 8192;        // shorter lists are never re-tiled

@@ -140,7 +140,15 @@ class _Graph:
     what the planner consumes (who touches which tensor, in which order).
     """
 
-    def __init__(self):
+    def __init__(self, tmp_seed: int = 0, fwd_tmps: int = 0, bwd_tmps: int = 0, opt_tmps: int = 0,
+                 tmp_log2: tuple = (16, 23)):
+        # Single-use temporaries (the pattern of Figure 6's tensor2914: allocated for one kernel, never
+        # used again): every forward / backward / optimizer kernel gets this many, sized log-uniformly
+        # between 2^tmp_log2[0] and 2^tmp_log2[1] bytes from a counter-based stream of their own.
+        self.tmp_seed, self.tmp_log2 = tmp_seed, tmp_log2
+        self.tmps = dict(fwd=fwd_tmps, bwd=bwd_tmps, opt=opt_tmps)
+        self.phase = "fwd"
+        self.n_tmp = 0
         self.sizes: list = []
         self.glob: list = []
         self.kernels: list = []          # list of list of tensor ids
@@ -167,7 +175,13 @@ class _Graph:
 
     # kernels -------------------------------------------------------------
     def kernel(self, uses) -> int:
-        self.kernels.append([int(u) for u in uses])
+        uses = [int(u) for u in uses]
+        for _ in range(self.tmps[self.phase]):
+            lo, hi = self.tmp_log2
+            e = lo + (hi - lo) * float(rand_unit(self.tmp_seed, 7, np.array([self.n_tmp]))[0])
+            uses.append(self.tensor(max(4096, int(2.0 ** e)) & ~255))
+            self.n_tmp += 1
+        self.kernels.append(uses)
         return len(self.kernels) - 1
 
     def op(self, ins, ws, outs, saved=None, ws_bytes: int = 0, extra=()):
@@ -185,6 +199,7 @@ class _Graph:
 
     def backward(self, split_weight_grads: bool = True):
         """Emit backward kernels in reverse order of the recorded forward."""
+        self.phase = "bwd"
         for rec in reversed(self.fwd):
             douts = [self.grad_of(o) for o in rec["outs"]]
             if rec["ins"]:
@@ -202,14 +217,26 @@ class _Graph:
                     self.kernel(uses)
         self.fwd = []
 
-    def optimizer(self, n_state: int, n_kernels: int, half_copy: bool = False):
+    def optimizer(self, n_state: int, n_kernels: int, half_copy: bool = False, fp32_grad: bool = False,
+                  pre_kernels: int = 0):
         """Per weight: `n_state` fp32 state tensors (momentum / Adam moments),
         an update split over `n_kernels` elementwise kernels, optionally a
-        half-precision working copy refreshed by a cast kernel."""
+        half-precision working copy refreshed by a cast kernel.  `fp32_grad`:
+        the half-precision gradient is first accumulated into an fp32 buffer
+        that lives across iterations (one more kernel and tensor per weight).
+        `pre_kernels`: elementwise kernels on the gradient alone before the
+        update (unscale / average over replicas / clip)."""
+        self.phase = "opt"
         for w in self.weights:
             if w not in self.grad:
                 continue
             g = self.grad[w]
+            for _ in range(pre_kernels):
+                self.kernel([g])
+            if fp32_grad:
+                acc = self.tensor(self.sizes[w] * 2, True)
+                self.kernel([g, acc])
+                g = acc
             states = [self.tensor(self.sizes[w], True) for _ in range(n_state)]
             for j in range(n_kernels):
                 s = states[j % n_state] if n_state else None
@@ -293,7 +320,7 @@ def encoder12(seed: int = 0x67100002) -> Workload:
     Bt, S, H, NH, L, FF, V = 32, 512, 768, 12, 12, 3072, 30522
     esz, wsz = 2, 4
     rows = Bt * S
-    g = _Graph()
+    g = _Graph(tmp_seed=seed, fwd_tmps=1, bwd_tmps=2)             # every kernel with scratch of its own, single use
     ids = g.tensor(rows * 8)
     emb = g.weight(V * H * wsz)
     pos = g.weight(S * H * wsz)
@@ -344,7 +371,7 @@ def encoder12(seed: int = 0x67100002) -> Workload:
     loss = g.tensor(4)
     g.op([logits], [], [loss], saved=[logits], extra=[labels])
     g.backward(split_weight_grads=True)
-    g.optimizer(n_state=2, n_kernels=2, half_copy=True)          # AdamW + cast
+    g.optimizer(n_state=2, n_kernels=2, half_copy=True, fp32_grad=True)   # fp32 gradient accumulation, AdamW, cast
     K = len(g.kernels)
     dur = rand_lognormal_ns(seed, 1, K, 80_000.0, 1.0)
     return Workload(g.finish("encoder12", dur), cap_frac=0.50,
@@ -360,14 +387,21 @@ def _conv_bn(g: _Graph, x: int, n: int, cin: int, cout: int, hw: int, ksz: int, 
     out_b = n * cout * hw * hw * esz
     col = g.tensor(max(4096, min(out_b, 256 << 20)))             # transform / im2col scratch
     g.op([x], [], [col], saved=[])
-    y = g.tensor(out_b)
-    g.op([col], [w], [y], saved=[x], ws_bytes=64 << 20)
+    wt = g.tensor(cin * cout * ksz * ksz * esz)                  # filter in the layout the convolution kernel wants
+    g.op([], [w], [wt])
+    yt = g.tensor(out_b)
+    g.op([col, wt], [], [yt], saved=[x, wt], ws_bytes=64 << 20)
+    y = g.tensor(out_b)                                           # output back in the activation layout
+    g.op([yt], [], [y], saved=[])
     gam, bet = g.weight(cout * esz), g.weight(cout * esz)
     rm, rv = g.tensor(cout * esz, True), g.tensor(cout * esz, True)
     mean, var = g.tensor(cout * esz), g.tensor(cout * esz)
-    g.op([y], [], [mean, var], saved=[], extra=[rm, rv])          # batch statistics
+    g.op([y], [], [mean, var], saved=[])                           # batch statistics
+    g.kernel([mean, var, rm, rv])                                  # running statistics (no backward)
+    yn = g.tensor(out_b)                                          # normalised, kept for the backward of the affine part
+    g.op([y], [], [yn], saved=[y, mean, var], extra=[mean, var])
     z = g.tensor(out_b)
-    g.op([y], [gam, bet], [z], saved=[y, mean, var], extra=[mean, var])
+    g.op([yn], [gam, bet], [z], saved=[yn])
     if relu:
         r = g.tensor(out_b)
         g.op([z], [], [r], saved=[r])
@@ -377,7 +411,7 @@ def _conv_bn(g: _Graph, x: int, n: int, cin: int, cout: int, hw: int, ksz: int, 
 
 def resnet152(seed: int = 0x67100003) -> Workload:
     n, esz = 256, 4
-    g = _Graph()
+    g = _Graph(tmp_seed=seed, fwd_tmps=1, bwd_tmps=2, opt_tmps=2)
     img = g.tensor(n * 3 * 224 * 224 * esz)
     x = _conv_bn(g, img, n, 3, 64, 112, 7, True)
     p = g.tensor(n * 64 * 56 * 56 * esz)
@@ -406,7 +440,7 @@ def resnet152(seed: int = 0x67100003) -> Workload:
     loss = g.tensor(4)
     g.op([logits], [], [loss], saved=[logits], extra=[labels])
     g.backward(split_weight_grads=True)
-    g.optimizer(n_state=1, n_kernels=3)                           # decay, momentum, update
+    g.optimizer(n_state=1, n_kernels=4, pre_kernels=2)            # average over replicas, clip; decay, momentum, update, statistics
     K = len(g.kernels)
     dur = rand_lognormal_ns(seed, 1, K, 80_000.0, 1.0)
     return Workload(g.finish("resnet152", dur), cap_frac=0.40,
@@ -422,7 +456,7 @@ def decoder48(seed: int = 0x67100004) -> Workload:
     HG = 16                                   # attention runs per group of NH/HG heads
     esz, wsz = 2, 2
     rows = Bt * S
-    g = _Graph()
+    g = _Graph(tmp_seed=seed, fwd_tmps=2, bwd_tmps=2, opt_tmps=2)
     ids = g.tensor(rows * 8)
     emb = g.weight(V * H * wsz)
     x = g.tensor(rows * H * esz)
