@@ -31,6 +31,29 @@ def test_hand_worked_replay():
     assert r.bytes + r.busy_out_ns + r.busy_in_ns == e["traffic"][0]
 
 
+def test_hand_worked_replay_two_iteration_copies_at_one_point():
+    """A cross-iteration period's prefetch (first copy) and the second copy's prefetch of a
+    migration ranked before it are issued at the same point on the same channel:
+    they queue in plan order, whichever copy they belong to.  The other order would stall 8000 ns."""
+    g = Golden("hand_replay_two_copies.txt")
+    v = O.Vitality(g.trace)
+    p = v.plan(**g.plan_args(), **g.variant_args())
+    fields = ["cand", "tensor", "evict_after", "absent_first", "absent_last", "next_use", "dest", "wraps", "size", "t_out", "t_in"]
+    assert [[int(r[f]) for f in fields] + [int(r["benefit_lo"])] for r in p.records] == g.expect["record"]
+    e = g.expect
+    r = p.replay()
+    assert [r.iter_ns, r.planned_ns, r.stall_ns, r.n_stalled] == e["replay_planned"][0] and r.late.tolist() == e["late_planned"][0]
+    assert r.bytes + r.busy_out_ns + r.busy_in_ns == e["traffic"][0]
+    # the differently formulated solver agrees, and a queue in the other order is what it would cost
+    recs = [{k: int(x[k]) for k in ("evict_after", "dest", "t_out", "t_in")} for x in p.records]
+    K = g.trace.K
+    b2 = [int(x["absent_last"]) + (K if int(x["absent_last"]) < int(x["evict_after"]) else 0) for x in p.records]
+    R2 = [int(x["next_use"]) + (K if x["wraps"] else 0) for x in p.records]
+    assert replaycheck.solve(K, g.trace.dur_ns, recs, b2, R2)[:4] == (100000, 100000, 0, 0)
+    swapped = replaycheck.solve(K, g.trace.dur_ns, recs[::-1], b2[::-1], R2[::-1])
+    assert swapped[:4] == (108000, 100000, 8000, 1) and swapped[4] == [0, 8000]
+
+
 def test_no_migration_no_stall():
     w = traces.encoder12()
     v = O.Vitality(w.trace, O.PREFIX)
