@@ -21,31 +21,76 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 
 
-def counted_hbm_bytes(workload):
-    """HBM bytes of one launch of the scoring pass from stored rocprofv3 counters (FETCH_SIZE and
-    WRITE_SIZE, each scaled by a copy of known size), or None if the kernel's source text has
-    changed since they were taken or they belong to another workload."""
-    import hashlib
-    import re
-    here = os.path.join(ROOT, "paper_2310_09443_amd")
-    try:
-        c = json.load(open(os.path.join(here, "hbm_counters.json")))
-        src = open(os.path.join(here, "csrc", "g10_plan.hip")).read()
-    except OSError:
-        return None
-    # the kernel and the packed form of the copy it reads
-    m = re.search(r"__global__ __launch_bounds__\(G10_BLOCK\) void k_score_full\(.*?\n}\n", src, flags=re.S)
-    f = re.search(r"constexpr u32 PACK_END_BITS.*?void unpack_windows\(.*?\n}\n", src, flags=re.S)
-    if not m or not f or c["workload"] != workload:
-        return None
-    if hashlib.sha256((f.group(0) + m.group(0)).encode()).hexdigest() != c["kernel_source_sha256"]:
-        return None
-    fetch = c["fetch_size_kib"] * c["copy_expected_kib"] / c["copy_fetch_size_kib"]
-    write = c["write_size_kib"] * c["copy_expected_kib"] / c["copy_write_size_kib"]
-    return (fetch + write) * 1024.0
 BYTES_PER_CAND = 36            # what a scoring pass over a candidate moves by definition: L+1, R, 2 x (a, b) as u32 + size u64
-                               # read, a 4-byte key written (the kernel itself reads a copy without L+1 and R: 16 bytes
-                               # where the window ends fit 21 bits and the sizes 43, else 24)
+                               # read, a 4-byte key written
+BYTES_PER_CAND_READ_ONLY = 32  # the same without the key (the arg-max fused into the pass: nothing written)
+BYTES_PER_CAND_MOVED = 20      # what k_score_full itself streams per candidate: a 16-byte packed copy (four window
+                               # ends of 21 bits, 43 bits of size; 24 bytes where a trace exceeds that) + the 4-byte key;
+                               # its gathers (two 8-byte words per window) hit a table that stays in L2
+
+
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def oracle_pinned(fn):
+    """Runs fn() with this process pinned to one core (the oracle is single-threaded); returns (result, core or None)."""
+    try:
+        allowed = sorted(os.sched_getaffinity(0))
+        os.sched_setaffinity(0, {allowed[-1]})
+    except (AttributeError, OSError):
+        return fn(), None
+    try:
+        return fn(), allowed[-1]
+    finally:
+        os.sched_setaffinity(0, set(allowed))
+
+
+def one_config(binding, traces, cfg, dev, steps, with_oracle):
+    """One of the smaller workloads: the step (analysis + plan) on the GPU, and the oracle's whole plan on one core."""
+    import torch
+    w = traces.config(cfg)
+    tr = w.trace
+    dt = binding.DeviceTrace(tr, dev)
+
+    def step():
+        h = binding.g10_vitality(dt)
+        cap, hcap = traces.resolve_caps(w, h.peak)
+        r = h.plan(cap, hcap, w.bw_out_Bpus, w.bw_in_Bpus)
+        C = h.C
+        h.close()
+        return r, C
+    step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        r, C = step()
+    torch.cuda.synchronize()
+    dt_s = (time.perf_counter() - t0) / steps
+    row = {"config": cfg, "workload": tr.name, "K": tr.K, "N": tr.N, "P": tr.P, "periods": C,
+           "passes": int(r.n_iterations), "migrations": int(r.n_migrations), "status": int(r.status),
+           "ms_per_step": dt_s * 1e3, "plan_ms": r.plan_ms, "loop_ms": r.loop_ms,
+           "loop_kernel_passes": int(r.loop_passes), "candidates_per_s": r.n_cand_evals / dt_s}
+    if with_oracle:
+        from oracle import oracle as O
+
+        def run():
+            t0 = time.perf_counter()
+            v = O.Vitality(tr, O.PREFIX)
+            cap, hcap = traces.resolve_caps(w, v.peak)
+            p = v.plan(cap, hcap, w.bw_out_Bpus, w.bw_in_Bpus)
+            return p, time.perf_counter() - t0
+        (p, t), _ = oracle_pinned(run)
+        row["oracle_ms"] = t * 1e3
+        row["oracle_candidates_per_s"] = p.n_cand_evals / t
+        row["oracle_matches"] = bool(p.records.tobytes() == r.records.tobytes())
+    return row
 
 
 def main():
@@ -59,6 +104,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--batch", type=int, default=256,
                     help="plans of the extra capacity-sweep measurement with g10_plan_batch (0 or 1: skip)")
+    ap.add_argument("--no-configs", dest="configs", action="store_false",
+                    help="skip the per-workload rows for configs 1-4")
     ap.add_argument("--probe", action="store_true",
                     help="counter probe: one 256 MiB device copy (calibration), one analysis and a plan cut after 8 passes")
     a = ap.parse_args()
@@ -108,19 +155,34 @@ def main():
     dt_s = (time.perf_counter() - t0) / a.steps
     assert all(x.records.tobytes() == r.records.tobytes() for x in runs)
 
-    # roofline of the streaming scoring pass (k_score_full: every candidate with a valid window, once per
-    # plan), timed by the library with HIP events on the planner's stream around each of its launches
+    # Two kernels are reported.  k_loop takes the time (the greedy loop, one persistent workgroup): its
+    # roofline entry counts the bytes it really moves, from its own counters, which is far under any
+    # bandwidth roof - it is bound by the latency of a serial chain of dependent steps.  k_score_full is
+    # the one pass that streams every candidate (once per plan): timed by the library with HIP events
+    # bound to the kernel's begin and end on the planner's stream.
     launches = len(runs)
     avg_ms = sum(x.score_full_ms for x in runs) / launches
     cands_per_launch = float(r.score_full_cands)
-    achieved = cands_per_launch * BYTES_PER_CAND / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else 0.0
+    def rate(bytes_per_cand):
+        return cands_per_launch * bytes_per_cand / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else 0.0
     loop_ms = sum(x.loop_ms for x in runs) / launches
     passes = max(int(r.n_iterations), 1)
+    kpasses = max(int(r.loop_passes), 1)
+    # bytes the loop kernel moves per plan: 40-byte candidate records re-scored (+ 8 gathers of 16 bytes for the
+    # live ones, here counted for all), chunk jobs of 256 slots (two 8-byte timelines read, one written, prefix words)
+    loop_bytes = r.loop_cands_scored * (40.0 + 8 * 16.0) + r.loop_chunk_jobs * 256 * 32.0
+    loop_gbps = loop_bytes / (loop_ms * 1e-3) / 1e9 if loop_ms > 0 else 0.0
+    listing_bytes = 32.0 * r.n_cand_evals + 72.0 * tr.K * passes       # what Algorithm 1 as listed would stream
+    scored = float(r.score_full_cands + r.loop_cands_scored + r.retile_cands)
 
     out = {
         "metric": "migration candidates scored/sec (whole step: vitality analysis + eviction plan)",
         "value": r.n_cand_evals / dt_s,
         "unit": "candidates/s",
+        "value_definition": "Algorithm 1's count: the sum over its ranking passes of the candidates live in the pass "
+                            "(what the listing ranks and the CPU oracle does rank), divided by the step time.  The GPU "
+                            "planner reaches the same decisions looking at far fewer: see candidates_actually_scored_per_s",
+        "candidates_actually_scored_per_s": scored / dt_s,
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": dt_s * 1e3,
         "plan_ms": sum(x.plan_ms for x in runs) / launches,
@@ -130,24 +192,35 @@ def main():
                    "periods": h.C, "passes": int(r.n_iterations), "migrations": int(r.n_migrations),
                    "dropped": int(r.n_dropped), "status": int(r.status), "cap_frac": w.cap_frac,
                    "bw_out_Bpus": list(w.bw_out_Bpus), "bw_in_Bpus": list(w.bw_in_Bpus)},
-        "roofline": {"bound": "hbm", "kernel": "k_score_full", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": counted_hbm_bytes(f"config {a.config}: {tr.name}"),
-                     "launches": launches, "avg_launch_us": avg_ms * 1e3,
-                     "cands_per_launch": cands_per_launch, "bytes_per_cand": BYTES_PER_CAND,
-                     "algorithmic_bytes_per_launch": cands_per_launch * BYTES_PER_CAND,
-                     "note": "the one pass that streams every candidate (traffic = HBM bytes per launch from "
-                             "stored counters). It is not the kernel that takes the time: see dominant_kernel"},
-        # the greedy loop: one persistent workgroup, a serial chain of dependent small steps per pass,
-        # bound by instruction and memory latency; its traffic is far below any bandwidth roof
-        "dominant_kernel": {"kernel": "k_loop", "bound": "latency (serial dependency chain, one workgroup)",
-                            "ms": loop_ms, "share_of_step": loop_ms / (dt_s * 1e3), "us_per_pass": 1e3 * loop_ms / passes,
-                            "launches": int(r.loop_launches), "retiles": int(r.loop_retiles),
-                            "cands_rescored_per_pass": r.loop_cands_scored / passes,
-                            "second_rounds": int(r.loop_second_rounds),
-                            "chunk_jobs_per_pass": r.loop_chunk_jobs / passes,
-                            "achieved_GBps": (r.loop_cands_scored * 40.0 + r.loop_chunk_jobs * 256 * 24.0)
-                            / (loop_ms * 1e-3) / 1e9 if loop_ms > 0 else 0.0},
+        "roofline": {"bound": "hbm", "kernel": "k_loop", "achieved": loop_gbps, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": loop_gbps / HBM_PEAK_GBS, "traffic": None, "traffic_source": "none (no counter run inside bench.py)",
+                     "ms": loop_ms, "share_of_step": loop_ms / (dt_s * 1e3), "launches": int(r.loop_launches),
+                     "bytes_per_plan": loop_bytes,
+                     "listing_equivalent_GBps": listing_bytes / (loop_ms * 1e-3) / 1e9 if loop_ms > 0 else 0.0,
+                     "us_per_algorithm_pass": 1e3 * loop_ms / passes, "kernel_passes": int(r.loop_passes),
+                     "migrations_per_kernel_pass": passes / kpasses, "us_per_kernel_pass": 1e3 * loop_ms / kpasses,
+                     "retiles": int(r.loop_retiles), "cands_rescored_per_kernel_pass": r.loop_cands_scored / kpasses,
+                     "second_rounds": int(r.loop_second_rounds), "chunk_jobs_per_kernel_pass": r.loop_chunk_jobs / kpasses,
+                     "note": "the dominant kernel: one persistent workgroup, a serial chain of dependent small steps per "
+                             "pass, bound by instruction and memory latency, not by bandwidth: achieved = the bytes it "
+                             "really reads and writes (its own counters) / its time.  listing_equivalent_GBps is what "
+                             "Algorithm 1 as listed would have to stream to do the same passes: not a bandwidth this "
+                             "kernel reaches, only a measure of the work it avoids.  There is no streaming "
+                             "timeline-update kernel to put on the roofline: updates touch a few chunks per migration"},
+        "roofline_scoring_pass": {"bound": "hbm", "kernel": "k_score_full", "achieved": rate(BYTES_PER_CAND), "peak": HBM_PEAK_GBS,
+                                  "unit": "GB/s", "frac": rate(BYTES_PER_CAND) / HBM_PEAK_GBS,
+                                  "frac_at_32B": rate(BYTES_PER_CAND_READ_ONLY) / HBM_PEAK_GBS,
+                                  "frac_moved_20B": rate(BYTES_PER_CAND_MOVED) / HBM_PEAK_GBS,
+                                  "traffic": None, "traffic_source": "none in this run; counters of an earlier build: "
+                                  "profiles/score_full_stress_hbm_counters.md",
+                                  "launches": launches, "avg_launch_us": avg_ms * 1e3,
+                                  "share_of_step": avg_ms / (dt_s * 1e3),
+                                  "cands_per_launch": cands_per_launch, "bytes_per_cand": BYTES_PER_CAND,
+                                  "algorithmic_bytes_per_launch": cands_per_launch * BYTES_PER_CAND,
+                                  "note": "the one pass that streams every candidate, once per plan.  frac: 36 B per "
+                                          "candidate (32 B read + the 4-byte key it writes); frac_at_32B: the read side "
+                                          "alone; frac_moved_20B: the bytes the kernel itself streams (16-byte packed "
+                                          "copy + key), its gathers staying in L2"},
     }
 
     # smart prefetching (Section 4.4) on the finished plan: a further row of the path, timed on its own
@@ -246,22 +319,30 @@ def main():
                                      "migrations_shared_with_default": common}
         hv.close()
 
+    # the other workloads (milliseconds each): the step on the GPU beside the oracle's complete plan on one core
+    if a.config == 5 and a.configs:
+        out["configs"] = [one_config(binding, traces, c, dev, max(a.steps, 3), not a.no_cpu) for c in (1, 2, 3, 4)]
+
     if not a.no_cpu:
         from oracle import oracle as O
-        t0 = time.perf_counter()
-        v = O.Vitality(tr, O.PREFIX)
-        t_vit = time.perf_counter() - t0
-        cap, hcap = traces.resolve_caps(w, v.peak)
-        passes = a.cpu_passes
-        if passes <= 0:                         # ~15 s of single-thread work at ~10 ns per evaluation
-            passes = max(1, min(int(r.n_iterations), int(1.5e9 / max(v.C, 1))))
-        t0 = time.perf_counter()
-        p = v.plan(cap, hcap, w.bw_out_Bpus, w.bw_in_Bpus, max_iters=passes)
-        t_plan = time.perf_counter() - t0
+
+        def run():
+            t0 = time.perf_counter()
+            v = O.Vitality(tr, O.PREFIX)
+            t_vit = time.perf_counter() - t0
+            cap, hcap = traces.resolve_caps(w, v.peak)
+            passes = a.cpu_passes
+            if passes <= 0:                         # ~15 s of single-thread work at ~10 ns per evaluation
+                passes = max(1, min(int(r.n_iterations), int(1.5e9 / max(v.C, 1))))
+            t0 = time.perf_counter()
+            p = v.plan(cap, hcap, w.bw_out_Bpus, w.bw_in_Bpus, max_iters=passes)
+            return p, t_vit, time.perf_counter() - t0
+        (p, t_vit, t_plan), core = oracle_pinned(run)
         n = len(p.records)
         same = all((r.records[f][:n] == p.records[f]).all() for f in p.records.dtype.names)
         out["cpu_baseline"] = {"value": p.n_cand_evals / (t_vit + t_plan), "unit": "candidates/s", "cores": 1,
-                               "kind": "oracle",
+                               "kind": "oracle", "threads_used": 1, "nproc": os.cpu_count(),
+                               "cpu_model": cpu_model(), "pinned_to_core": core,
                                "sample": f"vitality analysis + the first {p.n_iterations} of {int(r.n_iterations)} "
                                          f"ranking passes of the same trace ({t_vit + t_plan:.1f} s)",
                                "matches_gpu_prefix": bool(same)}

@@ -83,14 +83,8 @@ typedef struct {
   uint64_t host_cap_bytes;
   uint64_t bw_out_Bpus[2];   /* GPU -> [G10_FLASH, G10_HOST], bytes per microsecond    */
   uint64_t bw_in_Bpus[2];    /* [G10_FLASH, G10_HOST] -> GPU                           */
-  uint64_t max_iterations;   /* stop after this many ranking passes; 0 = no limit      */
-  uint32_t max_tiles;        /* 0 = library default.  Candidates are ranked in tiles of 256 << k, k the
-                                smallest with at most this many tiles (default and maximum 8192)        */
-  uint32_t max_chunks;       /* 0 = library default.  The kernel timeline is split into chunks of
-                                256 << k slots, k the smallest with at most this many chunks (default and
-                                maximum 512).  Both limits only trade speed against on-chip memory; the
-                                plan does not depend on them.  Tests lower them to reach the code paths of
-                                very long traces with small ones.                                        */
+  uint64_t max_iterations;   /* stop after this many ranking passes (of Algorithm 1: one migration or
+                                one dropped candidate each); 0 = no limit                              */
   const uint64_t *dur_ns;    /* NULL, or device [K]: kernel durations that replace the analysed trace's
                                 for this plan, each > 0 (re-planning under profiling errors, the study of
                                 the evaluation's "Impact of Profiling Errors").  Which tensors are used
@@ -152,20 +146,28 @@ typedef struct {
   const g10_migration *migrations;           /* host [n_migrations], commit order      */
   const g10_dropped *dropped;                /* host [n_dropped]                       */
   const uint64_t *pressure_after;            /* host [K]                               */
-  /* device times (events on the stream) and work counters of this call */
-  double plan_ms;              /* the whole call                                       */
+  double plan_ms;         /* device time of the whole call (events on the stream); for the
+                             plans of a batch, of the whole batch                      */
+} g10_result;
+
+/* How the last planning call on a handle did its work: device times and work counters of one
+ * of its plans (g10_plan_counters).  For measurements and tests; no part of the plan. */
+typedef struct {
   double score_full_ms;        /* the one streaming scoring pass over all candidates   */
                                /* (not timed for the plans of a batch of several: 0)   */
   uint64_t score_full_cands;   /* candidates it streamed (those with a valid window)   */
-  double loop_ms;              /* the greedy loop                                      */
+  double loop_ms;              /* the greedy loop (of a batch: all loops)              */
   uint64_t loop_launches;      /* launches of the loop kernel                          */
+  uint64_t loop_passes;        /* ranking passes the kernel made: a pass commits one migration or,
+                                  where that is provably what Algorithm 1 would do next, several  */
   uint64_t loop_retiles;       /* times the candidate list was put back into score order */
+  uint64_t retile_cands;       /* candidates scored again by those re-orderings        */
   uint64_t loop_cands_scored;  /* candidates re-scored inside the loop (tiles * 256)   */
   uint64_t loop_second_rounds; /* passes that needed a second scoring round            */
   uint64_t loop_chunk_jobs;    /* timeline chunks rewritten slot by slot               */
   uint64_t loop_area_evals;    /* G10_AREA_CLIPPED: clipped areas summed exactly       */
   uint64_t loop_area_refused;  /* ... of which came out below the bound (ranked again) */
-} g10_result;
+} g10_counters;
 
 typedef struct g10_plan_s g10_plan_t;   /* opaque: device copy of the analysis + workspaces */
 
@@ -179,11 +181,13 @@ typedef struct g10_plan_s g10_plan_t;   /* opaque: device copy of the analysis +
  * validated on the device before any other work), G10_ENOMEM, G10_EDEVICE. */
 int g10_vitality(const g10_trace *trace, void *hip_stream, g10_plan_t **out_handle);
 
-/* Counts and peak of a finished analysis. */
+/* Counts and peak of a finished analysis (Section 4.2: the uses, the inactive periods that are
+ * Algorithm 1's input, the peak of the memory-pressure curve of Section 4.3). */
 int g10_vitality_info(const g10_plan_t *handle, g10_vitality_stats *out);
 
-/* Copies one analysis array to HOST memory `dst` of `bytes` bytes (must match
- * the array's size exactly, else G10_EINVAL).  `which`:
+/* Read-back of the analysis of Section 4.2 (with g10_vitality_info: what the planner works on),
+ * for tests and tools: copies one analysis array to HOST memory `dst` of `bytes` bytes (must
+ * match the array's size exactly, else G10_EINVAL).  `which`:
  *   0 use_off  u64[N+1]   CSR offsets into use_k
  *   1 use_k    u32[n_uses]
  *   2 per_tensor u32[n_periods]   3 per_L u32[n_periods]   4 per_R u32[n_periods]
@@ -236,14 +240,29 @@ int g10_vitality_static(const g10_trace *trace, void *hip_stream, const g10_vita
  * getting under capacity is not an error: status = G10_RESIDUAL. */
 int g10_plan(g10_plan_t *handle, const g10_params *params, g10_result *out);
 
-/* `count` plans on one analysed trace in one call (capacity, host-memory, bandwidth or
- * kernel-time-noise sweeps): outs[i] is what g10_plan(handle, &params[i], &outs[i]) would return, bit for bit.
+/* Counters of plan `plan_index` (0 for g10_plan; 0 .. count-1 after g10_plan_batch) of the last
+ * planning call on the handle.  Errors: G10_EINVAL (NULL, no such plan). */
+int g10_plan_counters(const g10_plan_t *handle, uint32_t plan_index, g10_counters *out);
+
+/* Bounds of the two on-chip structures of the greedy loop for the planning calls that follow on
+ * this handle; 0 = the library's default, which is also the maximum.  max_tiles: candidates are
+ * ranked in tiles of 256 << k, k the smallest with at most this many tiles (8192).  max_chunks:
+ * the kernel timeline is split into chunks of 256 << k slots, k the smallest with at most this
+ * many chunks (512).  Both only trade speed against on-chip memory; no plan depends on them.
+ * They exist so that tests reach the code paths of very long traces with small ones.
+ * Errors: G10_EINVAL (NULL). */
+int g10_plan_limits(g10_plan_t *handle, uint32_t max_tiles, uint32_t max_chunks);
+
+/* `count` plans on one analysed trace in one call.  The sensitivity studies of the paper's
+ * evaluation (Section 7: host memory capacity, SSD bandwidth, profiling errors) plan one trace
+ * many times with other capacities, bandwidths or kernel times; this is that sweep as one call:
+ * outs[i] is what g10_plan(handle, &params[i], &outs[i]) would return, bit for bit.
  * The greedy loop of a plan is a serial chain that occupies one workgroup; a batch runs the
  * loops of all its plans side by side (one workgroup each), so up to a few hundred plans take
  * about as long as the slowest one plus their streaming passes.  Every plan keeps its own
  * workspaces in the handle (about 350 bytes per inactive period): the result arrays of all
- * `count` plans stay valid until the next planning call on the handle.  plan_ms and loop_ms of
- * every result are those of the whole batch.  g10_prefetch afterwards refers to params[0]'s plan.
+ * `count` plans stay valid until the next planning call on the handle.  plan_ms of every
+ * result is that of the whole batch.  g10_prefetch afterwards refers to params[0]'s plan.
  * Errors: as g10_plan; also G10_EINVAL for count = 0 or count > 4096.  On G10_ENOMEM the workspaces
  * of the plans after the first are released again and the handle stays usable. */
 int g10_plan_batch(g10_plan_t *handle, const g10_params *params, uint32_t count, g10_result *outs);
@@ -305,7 +324,8 @@ typedef struct {
  * G10_EOVERFLOW (durations sum to >= 2^62), G10_ENOMEM, G10_EDEVICE. */
 int g10_replay(g10_plan_t *handle, const uint64_t *dur_ns, uint32_t eager, g10_replay_result *out);
 
-/* Frees everything the library allocated for the handle.  NULL is allowed. */
+/* Frees everything the library allocated for the handle (the analysis of g10_vitality and the
+ * workspaces of the planning calls).  NULL is allowed. */
 void g10_plan_free(g10_plan_t *handle);
 
 #ifdef __cplusplus

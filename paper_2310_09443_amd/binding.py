@@ -21,7 +21,7 @@ FITS, RESIDUAL, TRUNCATED = 0, 1, 2
 NO_WRAP = 1
 
 EXPORTS = ["g10_vitality", "g10_vitality_info", "g10_vitality_read", "g10_vitality_static", "g10_plan", "g10_plan_batch",
-           "g10_prefetch", "g10_replay", "g10_plan_free"]
+           "g10_plan_counters", "g10_plan_limits", "g10_prefetch", "g10_replay", "g10_plan_free"]
 STATIC_MAX_K, STATIC_MAX_N, STATIC_MAX_P = 131072, 262144, 262144
 
 MIGRATION = np.dtype([("cand", "<u4"), ("tensor", "<u4"), ("evict_after", "<u4"),
@@ -57,7 +57,7 @@ class _VitalityBuffers(C.Structure):
 class _Params(C.Structure):
     _fields_ = [("gpu_cap_bytes", C.c_uint64), ("host_cap_bytes", C.c_uint64),
                 ("bw_out_Bpus", C.c_uint64 * 2), ("bw_in_Bpus", C.c_uint64 * 2),
-                ("max_iterations", C.c_uint64), ("max_tiles", C.c_uint32), ("max_chunks", C.c_uint32),
+                ("max_iterations", C.c_uint64),
                 ("dur_ns", C.c_void_p), ("rank", C.c_uint32), ("area", C.c_uint32)]
 
 
@@ -67,9 +67,13 @@ class _Result(C.Structure):
                 ("n_cand_evals", C.c_uint64), ("peak_before", C.c_uint64), ("peak_after", C.c_uint64),
                 ("overtime_before_ns", C.c_uint64), ("overtime_after_ns", C.c_uint64),
                 ("migrations", C.c_void_p), ("dropped", C.c_void_p), ("pressure_after", C.c_void_p),
-                ("plan_ms", C.c_double), ("score_full_ms", C.c_double), ("score_full_cands", C.c_uint64),
-                ("loop_ms", C.c_double), ("loop_launches", C.c_uint64), ("loop_retiles", C.c_uint64),
-                ("loop_cands_scored", C.c_uint64),
+                ("plan_ms", C.c_double)]
+
+
+class _Counters(C.Structure):
+    _fields_ = [("score_full_ms", C.c_double), ("score_full_cands", C.c_uint64),
+                ("loop_ms", C.c_double), ("loop_launches", C.c_uint64), ("loop_passes", C.c_uint64),
+                ("loop_retiles", C.c_uint64), ("retile_cands", C.c_uint64), ("loop_cands_scored", C.c_uint64),
                 ("loop_second_rounds", C.c_uint64), ("loop_chunk_jobs", C.c_uint64),
                 ("loop_area_evals", C.c_uint64), ("loop_area_refused", C.c_uint64)]
 
@@ -106,6 +110,8 @@ def load():
         lib.g10_vitality_static.argtypes = [C.POINTER(_Trace), C.c_void_p, C.POINTER(_VitalityBuffers), C.POINTER(_Stats)]
         lib.g10_plan.argtypes = [C.c_void_p, C.POINTER(_Params), C.POINTER(_Result)]
         lib.g10_plan_batch.argtypes = [C.c_void_p, C.POINTER(_Params), C.c_uint32, C.POINTER(_Result)]
+        lib.g10_plan_counters.argtypes = [C.c_void_p, C.c_uint32, C.POINTER(_Counters)]
+        lib.g10_plan_limits.argtypes = [C.c_void_p, C.c_uint32, C.c_uint32]
         lib.g10_prefetch.argtypes = [C.c_void_p, C.POINTER(_PrefetchResult)]
         lib.g10_replay.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.POINTER(_ReplayResult)]
         lib.g10_plan_free.argtypes = [C.c_void_p]
@@ -131,11 +137,15 @@ class DeviceTrace:
 
 
 class Result:
-    def __init__(self, r: _Result, K: int, pool=None):
-        """pool: a _Pool that takes this result's arrays (the results of a batch share one allocation)."""
+    def __init__(self, r: _Result, K: int, pool=None, counters: _Counters = None):
+        """pool: a _Pool that takes this result's arrays (the results of a batch share one allocation).
+        counters: what g10_plan_counters says of this plan; kept as attributes of the same names."""
         for f, _ in _Result._fields_:
             if f not in ("migrations", "dropped", "pressure_after"):
                 setattr(self, f, getattr(r, f))
+        if counters is not None:
+            for f, _ in _Counters._fields_:
+                setattr(self, f, getattr(counters, f))
         take = pool.take if pool is not None else self._copy
         self.records = take(r.migrations, int(r.n_migrations), MIGRATION)
         self.dropped = take(r.dropped, int(r.n_dropped), DROPPED)
@@ -233,13 +243,25 @@ class Handle:
     start = property(lambda self: self.read(5))
     pressure = property(lambda self: self.read(6))
 
-    def _fill(self, p, gpu_cap, host_cap, bw_out, bw_in, max_iters=0, max_tiles=0, max_chunks=0, dur=None, rank=0, area=0):
+    def limits(self, max_tiles=0, max_chunks=0):
+        """g10_plan_limits: bounds of the loop's on-chip structures for the planning calls that follow (0 = default)."""
+        rc = load().g10_plan_limits(self._h, int(max_tiles), int(max_chunks))
+        if rc:
+            raise G10Error(rc, "g10_plan_limits")
+
+    def _counters(self, i):
+        c = _Counters()
+        rc = load().g10_plan_counters(self._h, i, C.byref(c))
+        if rc:
+            raise G10Error(rc, "g10_plan_counters")
+        return c
+
+    def _fill(self, p, gpu_cap, host_cap, bw_out, bw_in, max_iters=0, dur=None, rank=0, area=0):
         """dur: None, or a device tensor of K 64-bit durations (ns) that replace the trace's for this plan."""
         p.gpu_cap_bytes, p.host_cap_bytes = int(gpu_cap), int(host_cap)
         p.bw_out_Bpus[0], p.bw_out_Bpus[1] = int(bw_out[0]), int(bw_out[1])
         p.bw_in_Bpus[0], p.bw_in_Bpus[1] = int(bw_in[0]), int(bw_in[1])
         p.max_iterations = int(max_iters)
-        p.max_tiles, p.max_chunks = int(max_tiles), int(max_chunks)
         p.rank, p.area = int(rank), int(area)
         if dur is None:
             p.dur_ns = None
@@ -248,11 +270,17 @@ class Handle:
                 raise ValueError("dur must be a contiguous device tensor of K 64-bit integers")
             p.dur_ns = dur.data_ptr()
 
-    def plan_batch(self, param_dicts):
-        """g10_plan_batch: one plan per dict of plan() keyword arguments."""
+    def plan_batch(self, param_dicts, max_tiles=0, max_chunks=0):
+        """g10_plan_batch: one plan per dict of plan() keyword arguments (max_tiles / max_chunks, which
+        belong to the handle, may also come in the first dict)."""
         import torch
         n = len(param_dicts)
         ps = (_Params * n)()
+        param_dicts = [dict(d) for d in param_dicts]
+        for d in param_dicts:
+            max_tiles = d.pop("max_tiles", max_tiles) or max_tiles
+            max_chunks = d.pop("max_chunks", max_chunks) or max_chunks
+        self.limits(max_tiles, max_chunks)
         for p, d in zip(ps, param_dicts):
             self._fill(p, **d)
         rs = (_Result * n)()
@@ -261,18 +289,19 @@ class Handle:
         if rc:
             raise G10Error(rc, "g10_plan_batch")
         pool = _Pool(sum(Result.nbytes(r, self.K) for r in rs))
-        return [Result(r, self.K, pool) for r in rs]
+        return [Result(r, self.K, pool, self._counters(i)) for i, r in enumerate(rs)]
 
     def plan(self, gpu_cap, host_cap, bw_out, bw_in, max_iters=0, max_tiles=0, max_chunks=0, dur=None, rank=0, area=0) -> Result:
         import torch
         p = _Params()
-        self._fill(p, gpu_cap, host_cap, bw_out, bw_in, max_iters, max_tiles, max_chunks, dur, rank, area)
+        self._fill(p, gpu_cap, host_cap, bw_out, bw_in, max_iters, dur, rank, area)
+        self.limits(max_tiles, max_chunks)
         r = _Result()
         with torch.cuda.device(self._dev):
             rc = load().g10_plan(self._h, C.byref(p), C.byref(r))
         if rc:
             raise G10Error(rc, "g10_plan")
-        return Result(r, self.K)
+        return Result(r, self.K, None, self._counters(0))
 
     def prefetch(self) -> PrefetchResult:
         import torch

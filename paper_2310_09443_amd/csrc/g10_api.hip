@@ -10,6 +10,7 @@ static void handle_free(g10_plan_s* h) {
   plan_work_free(h->work);
   for (u32 i = 0; i < h->n_more; ++i) plan_work_free(h->more[i]);
   free(h->more);
+  free(h->counters);
   if (h->loop_args) (void)hipFree(h->loop_args);
   for (u32 k = 0; k < h->n_aux; ++k) (void)hipStreamDestroy(h->aux[k]);
   if (h->arena) (void)hipFree(h->arena);        // every array of the analysis
@@ -75,6 +76,18 @@ extern "C" int g10_plan(g10_plan_t* h, const g10_params* p, g10_result* out) {
     memset(out, 0, sizeof *out);
   }
   return rc;
+}
+
+extern "C" int g10_plan_counters(const g10_plan_t* h, uint32_t plan_index, g10_counters* out) {
+  if (!h || !out || plan_index >= h->n_counters) return G10_EINVAL;
+  *out = h->counters[plan_index];
+  return G10_OK;
+}
+
+extern "C" int g10_plan_limits(g10_plan_t* h, uint32_t max_tiles, uint32_t max_chunks) {
+  if (!h) return G10_EINVAL;
+  h->max_tiles = max_tiles; h->max_chunks = max_chunks;
+  return G10_OK;
 }
 
 extern "C" int g10_plan_batch(g10_plan_t* h, const g10_params* params, uint32_t count, g10_result* outs) {

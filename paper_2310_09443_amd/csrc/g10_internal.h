@@ -212,6 +212,9 @@ struct g10_plan_s {
   PlanWork** more = nullptr;     // ... of the further plans of a batch
   u32 n_more = 0;
   u64 max_size = 0;              // the largest tensor
+  u32 max_tiles = 0, max_chunks = 0;   // g10_plan_limits (0 = the defaults)
+  g10_counters* counters = nullptr;    // of the plans of the last planning call
+  u32 n_counters = 0;
   bool big_size = false;         // some tensor has 2^43 bytes or more (the planner's 16-byte candidate copies hold 43 bits)
   void* loop_args = nullptr;     // device array of per-plan arguments of the loop kernel
   u32 loop_args_cap = 0;

@@ -1066,6 +1066,7 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
     ctl->overtime_after = base[(u64)A_OT * nb1 + nch];
     for (u32 i = 0; i < 32; ++i) ctl->phase[i] += S->phase[i];
     ctl->units_scored += S->units; ctl->second_rounds += S->second; ctl->jobs_run += S->jobs; ctl->launches += 1;
+    ctl->passes += passes;
     ctl->area_evals += S->evals; ctl->area_refused += S->refused;
   }
 }

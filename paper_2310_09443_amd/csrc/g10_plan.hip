@@ -524,7 +524,7 @@ struct Inst {
   u32 n = 0, n_valid = 0, max_tiles = 0;
   u32 tsh = 0, nt = 0, n_pad = 0;
   int cur = 0;                 // the candidate buffer the loop reads
-  u64 retiles = 0, launches = 0, max_launches = 0, overtime_before = 0;
+  u64 retiles = 0, retile_cands = 0, launches = 0, max_launches = 0, overtime_before = 0;
   bool counted = false;        // hc.n_live holds a count of the current list
   bool timed_full = false;
   u64 times_check[16] = {};     // the checks of the plan's own durations come back here
@@ -569,6 +569,13 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
   Ctl* const ctl_side = (Ctl*)((LoopArgs*)h->loop_args + h->loop_args_cap);    // the progress blocks of a launch, collected
   SortJob* const sort_jobs = (SortJob*)(ctl_side + h->loop_args_cap);          // the re-tilings of a round of a batch
   TileJob* const tile_jobs = (TileJob*)(sort_jobs + h->loop_args_cap);
+  h->n_counters = 0;
+  {
+    g10_counters* q = (g10_counters*)realloc(h->counters, (size_t)count * sizeof(g10_counters));
+    if (!q) return G10_ENOMEM;
+    h->counters = q;
+    memset(q, 0, (size_t)count * sizeof(g10_counters));
+  }
   Inst* I = new (std::nothrow) Inst[count];
   LoopArgs* hargs = (LoopArgs*)malloc((size_t)count * sizeof(LoopArgs));
   Ctl* hctl = (Ctl*)malloc((size_t)count * sizeof(Ctl));
@@ -596,7 +603,7 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
 
   for (u32 i = 0; i < count; ++i) {
     const g10_params* p = params + i;
-    const u32 max_chunks = clamp_limit(p->max_chunks, NCH_MAX);
+    const u32 max_chunks = clamp_limit(h->max_chunks, NCH_MAX);
     PlanWork** slot = work_slot(h, i);
     bool cache = p->area == G10_AREA_CLIPPED;
     if (*slot && ((*slot)->max_chunks != max_chunks || (cache && !(*slot)->has_cache))) {
@@ -616,7 +623,7 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
         return rc;
       }
     }
-    I[i].w = *slot; I[i].p = p; I[i].max_tiles = clamp_limit(p->max_tiles, NT_MAX);
+    I[i].w = *slot; I[i].p = p; I[i].max_tiles = clamp_limit(h->max_tiles, NT_MAX);
     (*slot)->planned = false; (*slot)->prefetched = false;
   }
 
@@ -897,6 +904,7 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
       if (x.n > RETILE_MIN_CANDS && x.hc.n_iter - x.seen_iter >= retile_every) {
         x.seen_iter = x.hc.n_iter;
         if (x.counted && x.hc.n_live < x.n) x.n = x.hc.n_live;   // live candidates come first in the list
+        x.retile_cands += x.n;
         if (count == 1) G10_TRY(retile(x, false, s));
         else {
           x.tsh = tile_shift_for(x.n, x.max_tiles);
@@ -981,11 +989,14 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     out->overtime_before_ns = x.overtime_before; out->overtime_after_ns = hc.overtime_after;
     out->migrations = w->h_records; out->dropped = w->h_dropped; out->pressure_after = w->h_pressure;
     out->plan_ms = ms;
-    out->score_full_ms = full_ms; out->score_full_cands = x.n_valid;
-    out->loop_ms = loop_ms; out->loop_launches = hc.launches; out->loop_retiles = x.retiles;
-    out->loop_cands_scored = hc.units_scored * UNIT; out->loop_second_rounds = hc.second_rounds; out->loop_chunk_jobs = hc.jobs_run;
-    out->loop_area_evals = hc.area_evals; out->loop_area_refused = hc.area_refused;
+    g10_counters& ct = h->counters[i];
+    ct.score_full_ms = full_ms; ct.score_full_cands = x.n_valid;
+    ct.loop_ms = loop_ms; ct.loop_launches = hc.launches; ct.loop_passes = hc.passes; ct.loop_retiles = x.retiles;
+    ct.retile_cands = x.retile_cands;
+    ct.loop_cands_scored = hc.units_scored * UNIT; ct.loop_second_rounds = hc.second_rounds; ct.loop_chunk_jobs = hc.jobs_run;
+    ct.loop_area_evals = hc.area_evals; ct.loop_area_refused = hc.area_refused;
   }
+  h->n_counters = count;
   return G10_OK;
 }
 

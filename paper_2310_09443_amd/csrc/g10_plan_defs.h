@@ -48,7 +48,7 @@ struct Ctl {
   u32 n_live;                 // candidates that could still score at the last re-scoring
   u32 gshift, pad1;           // the guess: first threshold = last best * (1 - 2^-gshift); 0 stands for GUESS_SHIFT
   // statistics
-  u64 units_scored, second_rounds, jobs_run, launches;
+  u64 units_scored, second_rounds, jobs_run, launches, passes;
   u64 area_evals, area_refused;   // clipped areas computed in the loop; of those, how many came out below the bound
   u64 phase[32];              // wall-clock ticks per phase of the loop (only with G10_PHASE_TIMERS)
 };

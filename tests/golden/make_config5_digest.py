@@ -1,8 +1,11 @@
 """Writes tests/golden/config5_plan_digest.txt: digests of the oracle's complete
-plan for the stress workload (config 5).  Calls only the trace generator and
-oracle/.  Takes about five minutes of one CPU core.
+plan for the stress workload (config 5), and tests/golden/config5_ratio_digest.txt:
+digests of the first 4000 ranking passes of the oracle's plan with the benefit /
+cost ranking key on the same workload (that key's complete plan has some 200 000
+migrations).  Calls only the trace generator and oracle/.  Takes about ten
+minutes of one CPU core.
 
-    python tests/golden/make_config5_digest.py
+    python tests/golden/make_config5_digest.py [default|ratio]
 """
 import hashlib
 import os
@@ -34,10 +37,30 @@ def records_digest(rec):
     return h.hexdigest()
 
 
+RATIO_PASSES = 4000
+
+
 def main():
+    which = sys.argv[1] if len(sys.argv) > 1 else "both"
     w = traces.config(5)
     v = O.Vitality(w.trace, O.PREFIX)
     cap, hcap = traces.resolve_caps(w, v.peak)
+    if which in ("ratio", "both"):
+        p = v.plan(cap, hcap, w.bw_out_Bpus, w.bw_in_Bpus, max_iters=RATIO_PASSES, rank=O.BY_RATIO)
+        with open(os.path.join(HERE, "config5_ratio_digest.txt"), "w") as f:
+            f.write("# First 4000 ranking passes of the CPU oracle's plan for the stress workload (config 5) with the\n")
+            f.write("# benefit / cost ranking key, as digests.  Written by tests/golden/make_config5_digest.py, which\n")
+            f.write("# calls only oracle/.  The digest per hundred records lets a test say where a plan first differs.\n")
+            f.write(f"trace_sha256 {trace_digest(w.trace)}\n")
+            f.write(f"records_sha256 {records_digest(p.records)}\n")
+            f.write(f"pressure_after_sha256 {hashlib.sha256(p.pressure_after.astype('<u8').tobytes()).hexdigest()}\n")
+            f.write(f"status {p.status}\npasses {p.n_iterations}\nmigrations {p.n_migrations}\n"
+                    f"dropped {p.n_null}\ncand_evals {p.n_cand_evals}\n")
+            for k in range(0, len(p.records), 100):
+                f.write(f"records_{k}_sha256 {records_digest(p.records[k:k + 100])}\n")
+        print("ratio written")
+        if which == "ratio":
+            return
     p = v.plan(cap, hcap, w.bw_out_Bpus, w.bw_in_Bpus)
     with open(os.path.join(HERE, "config5_plan_digest.txt"), "w") as f:
         f.write("# Complete plan of the CPU oracle for the stress workload (config 5), as digests.\n")

@@ -31,9 +31,11 @@ def test_library_exports_every_declared_symbol():
 def test_struct_layouts_match_the_header():
     # sizes follow from the field lists in the header (natural alignment)
     assert ctypes.sizeof(binding._Trace) == 64
-    assert ctypes.sizeof(binding._Params) == 80
+    assert ctypes.sizeof(binding._Params) == 72
     assert ctypes.sizeof(binding._Stats) == 32
-    assert ctypes.sizeof(binding._Result) == 8 + 8 * 8 + 3 * 8 + 11 * 8
+    assert ctypes.sizeof(binding._Result) == 8 + 8 * 8 + 3 * 8 + 8
+    assert ctypes.sizeof(binding._Counters) == 12 * 8
+    assert ctypes.sizeof(binding._VitalityBuffers) == 7 * 8
     assert ctypes.sizeof(binding._PrefetchResult) == 4 * 8 + 4 * 8 + 8
     assert ctypes.sizeof(binding._ReplayResult) == 4 * 8 + 6 * 8 + 3 * 8
     assert binding.MIGRATION.itemsize == 72 and binding.DROPPED.itemsize == 16
@@ -45,6 +47,9 @@ def test_null_arguments_are_rejected_without_a_gpu():
     assert lib.g10_plan(None, None, None) == binding.EINVAL
     assert lib.g10_vitality_info(None, None) == binding.EINVAL
     assert lib.g10_prefetch(None, None) == binding.EINVAL
+    assert lib.g10_plan_counters(None, 0, None) == binding.EINVAL
+    assert lib.g10_plan_limits(None, 0, 0) == binding.EINVAL
+    assert lib.g10_vitality_static(None, None, None, None) == binding.EINVAL
     lib.g10_plan_free(None)
     t = binding._Trace()                        # K = 0
     h = ctypes.c_void_p()

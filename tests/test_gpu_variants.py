@@ -165,8 +165,9 @@ def test_unknown_reading_is_an_error(g10):
 def test_stress_full_size_ratio(g10):
     """Config 5 at full size with the ratio key.  This key prefers small tensors with long
     windows, so the plan has far more (and smaller) migrations than the default; the test
-    looks at its first 4000 passes: the first 100 against the oracle, all of them against the
-    property checker with the arg-max property on sampled passes."""
+    looks at its first 4000 passes: the first 100 against the oracle run here, all 4000 against the
+    stored digests of the oracle's records (tests/golden/make_config5_digest.py, per hundred records
+    and as a whole), and against the property checker with the arg-max property on sampled passes."""
     w = traces.config(5)
     tr = w.trace
     h, v, args = run_both(g10, w)
@@ -181,6 +182,21 @@ def test_stress_full_size_ratio(g10):
     plancheck.check_plan(tr, m, r.records, r.null_iters, r.null_cands, r.status, greedy=sample, complete=False)
     assert h.plan(rank=1, max_iters=limit, **args).records.tobytes() == r.records.tobytes()
     h.close()
+    import hashlib
+    import os
+    import sys
+    sys.path.insert(0, os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden"))
+    import make_config5_digest as gd
+    gold = dict(line.split() for line in open(os.path.join(gd.HERE, "config5_ratio_digest.txt")) if not line.startswith("#"))
+    if gd.trace_digest(tr) != gold["trace_sha256"]:
+        pytest.skip("this machine's numpy generates a different stress trace than the stored digests were made from")
+    assert limit == gd.RATIO_PASSES == int(gold["passes"])
+    for k in range(0, len(r.records), 100):
+        assert gd.records_digest(r.records[k:k + 100]) == gold[f"records_{k}_sha256"], f"records {k}..{k + 99} differ from the oracle's"
+    assert gd.records_digest(r.records) == gold["records_sha256"]
+    assert hashlib.sha256(r.pressure_after.astype("<u8").tobytes()).hexdigest() == gold["pressure_after_sha256"]
+    assert (int(r.status), int(r.n_iterations), int(r.n_migrations), int(r.n_dropped), int(r.n_cand_evals)) == \
+           (int(gold["status"]), int(gold["passes"]), int(gold["migrations"]), int(gold["dropped"]), int(gold["cand_evals"]))
 
 
 def test_stress_full_size_clipped(g10):
