@@ -108,6 +108,8 @@ def main():
                     help="skip the per-workload rows for configs 1-4")
     ap.add_argument("--probe", action="store_true",
                     help="counter probe: one 256 MiB device copy (calibration), one analysis and a plan cut after 8 passes")
+    ap.add_argument("--peak-check", action="store_true",
+                    help="what the HBM peak of the roofline is checked against: device properties and measured copy / read rates")
     a = ap.parse_args()
     if a.gpus != 1:
         sys.exit("bench.py: the planner runs on one GPU only (planning one trace is a serial greedy loop; "
@@ -118,6 +120,34 @@ def main():
     binding.load()
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     dev = "cuda:0"
+
+    if a.peak_check:
+        p = torch.cuda.get_device_properties(0)
+        clk_khz, bus = getattr(p, "memory_clock_rate", None), getattr(p, "memory_bus_width", None)
+        out = {"peak_check": True, "device": p.name, "compute_units": p.multi_processor_count,
+               "memory_clock_khz": clk_khz, "memory_bus_bits": bus, "published_GBps": HBM_PEAK_GBS,
+               # HBM3E moves four bits per pin per reported clock
+               "clock_x_bus_x4_GBps": (clk_khz * 1e3 * bus / 8 * 4 / 1e9) if clk_khz and bus else None,
+               "copy": [], "read": []}
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for mb in (64, 256, 1024, 4096):
+            n = mb << 20
+            x = torch.empty(n, dtype=torch.uint8, device=dev)
+            y = torch.empty_like(x)
+            x.fill_(1)
+            y.copy_(x)
+            v = x.view(torch.int64)
+            best_c = best_r = 1e9
+            for _ in range(10):
+                e0.record(); y.copy_(x); e1.record(); torch.cuda.synchronize()
+                best_c = min(best_c, e0.elapsed_time(e1))
+                e0.record(); v.sum(); e1.record(); torch.cuda.synchronize()
+                best_r = min(best_r, e0.elapsed_time(e1))
+            out["copy"].append({"MiB": mb, "ms": best_c, "GBps_read_plus_write": 2 * n / best_c / 1e6})
+            out["read"].append({"MiB": mb, "ms": best_r, "GBps": n / best_r / 1e6})
+            del x, y, v
+        print(json.dumps(out))
+        return
 
     w = traces.config(a.config)
     tr = w.trace

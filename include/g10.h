@@ -31,8 +31,8 @@ extern "C" {
 
 enum {
   G10_OK = 0,
-  G10_EINVAL = -1,    /* NULL argument, K = 0, N = 0, K >= 2^31, an index out of range,
-                         a zero duration / size / bandwidth                            */
+  G10_EINVAL = -1,    /* NULL argument, K = 0, N = 0, K >= 2^31, P >= 2^32, an index out of
+                         range, a zero duration / size / bandwidth                     */
   G10_EOVERFLOW = -2, /* sum of durations >= 2^62, sum of used sizes >= 2^64,
                          or a size * 1000 >= 2^64                                      */
   G10_ENOMEM = -3,    /* host or device allocation failed                              */
@@ -55,7 +55,7 @@ enum { G10_FITS = 0, G10_RESIDUAL = 1, G10_TRUNCATED = 2 };
  * passes one tensor twice to a kernel) and collapse. */
 typedef struct {
   uint32_t K, N;               /* kernels, tensors                                     */
-  uint64_t P;                  /* use pairs (may be 0)                                 */
+  uint64_t P;                  /* use pairs (may be 0; fewer than 2^32)                */
   const uint64_t *dur_ns;      /* device [K], each > 0                                 */
   const uint64_t *size_bytes;  /* device [N], each > 0                                 */
   const uint8_t *is_global;    /* device [N], 1 = global                               */

@@ -9,16 +9,6 @@ using namespace g10;
 
 namespace {
 
-#ifdef G10_PHASE_TIMERS
-#define PHASE(i) do { if (tid == 0) { const u64 now_ = wall_clock64(); S->phase[i] += now_ - S->t_last; S->t_last = now_; } } while (0)
-#define STAT(i) do { atomicAdd((unsigned long long*)&S->phase[i], 1ull); } while (0)
-#define SUBT(i) do { if (lane == 0) { const u64 now_ = wall_clock64(); S->phase[i] += now_ - sub_last; sub_last = now_; } } while (0)
-#else
-#define SUBT(i) do { } while (0)
-#define PHASE(i) do { } while (0)
-#define STAT(i) do { } while (0)
-#endif
-
 struct Winner {               // what a commit needs of the winning candidate
   u64 hi, lo;                 // benefit
   u64 cost;                   // eviction + prefetch time (ranking by benefit / cost only)
@@ -33,16 +23,10 @@ struct Winner {               // what a commit needs of the winning candidate
   u32 pad;
 };
 
-#ifndef G10_MAXM
-#define G10_MAXM 16
-#endif
-constexpr u32 MAXM = G10_MAXM; // migrations committed in one ranking pass at most (a multiple of 8, at most 16: the job words hold two sets of 16)
+constexpr u32 MAXM = 16;      // migrations committed in one ranking pass at most (a multiple of 8, at most 16: the job words hold two sets of 16)
 static_assert(MAXM % 8 == 0 && MAXM <= 16, "job words and chunk flags are laid out for 8 or 16");
 
-#ifndef G10_MC_GSMIN
-#define G10_MC_GSMIN 4
-#endif
-constexpr u32 MC_GUESS_SHIFT_MIN = G10_MC_GSMIN;   // the widest margin of a pass's first threshold under the last benefit: 2^-this
+constexpr u32 MC_GUESS_SHIFT_MIN = 4;   // the widest margin of a pass's first threshold under the last benefit: 2^-this
 constexpr u32 LIST_MAX = 64;  // candidates of a pass that are looked at for the second and later migrations
 
 struct Shared {               // small per-pass state of the loop workgroup
@@ -50,12 +34,12 @@ struct Shared {               // small per-pass state of the loop workgroup
   Winner wave_win[LW];        // best of every wavefront
   Winner list[LIST_MAX];      // the other candidates whose bound exceeds every bound not looked at one by one
   u32 wave_f2[LW];            // per wavefront: largest bound among the candidates its threads scored but do not hold
-  u32 F2, Fx;                 // ... over the workgroup; largest bound of the candidates that found no room in the list
+  u32 F2, pad0;               // ... over the workgroup
   u32 nlist, m0, cut, need_exact;   // list length; migrations selected; how many of them may be committed; the winner's
                               // host-capacity test needs the exact per-slot maximum
-  u32 by_floor, m;            // the selection ended because the next candidate did not clear the floor; migrations being committed
+  u32 by_floor, touched;      // the selection ended because the next candidate did not clear the floor; timelines (a bit
+                              // per array of level 1) whose chunk totals change in this pass
   u32 sel[MAXM];              // list entries picked, in order
-  u32 touched, pad3;          // timelines (a bit per array of level 1) whose chunk totals change in this pass
   u64 hq;                     // host-capacity query: maximum over the period
   u64 acc[3];                 // clipped area being summed: bits 0..31, 32..63 and 64.. of the terms, added apart
   u64 evals, refused;         // clipped areas computed; of those, how many came out below the bound
@@ -67,7 +51,6 @@ struct Shared {               // small per-pass state of the loop workgroup
   u32 thr_key, status, done, stop;
   u32 gshift, pad2;
   u64 t_start;
-  u64 phase[32], t_last;
 };
 
 // The lane of the wavefront holding the best (benefit, lowest index), or NONE32
@@ -119,21 +102,6 @@ __device__ __forceinline__ u32 wave_best_lane_ratio(u64 hi, u64 lo, u64 cost, u3
   return p;
 }
 
-// Do the doubled slot ranges [x1, y1] and [x2, y2] (each shorter than K) share a kernel slot?
-__device__ __forceinline__ bool cyc_overlap(u32 x1, u32 y1, u32 x2, u32 y2, u32 K) {
-  const u64 p = x1, q = y1, r = x2, t = y2, k = K;
-  return (p <= t && r <= q) || (p + k <= t && r <= q + k) || (p <= t + k && r + k <= q);
-}
-
-// The plain slots of a doubled slot range [x, y] (x <= y, y - x < K) as one or two runs [p, q]
-__device__ __forceinline__ u32 plain_runs(u32 x, u32 y, u32 K, u32 (&p)[2], u32 (&q)[2]) {
-  p[1] = 0; q[1] = 0;
-  if (x >= K) { p[0] = x - K; q[0] = y - K; return 1u; }
-  if (y < K) { p[0] = x; q[0] = y; return 1u; }
-  p[0] = x; q[0] = K - 1; q[1] = y - K;
-  return 2u;
-}
-
 // Do the doubled slot ranges [x1, y1] and [x2, y2] (each shorter than K) share a kernel slot?  (K < 2^30)
 __device__ __forceinline__ bool cyc_overlap32(u32 x1, u32 y1, u32 x2, u32 y2, u32 K) {
   return (x1 <= y2 && x2 <= y1) || (x1 + K <= y2 && x2 <= y1 + K) || (x1 <= y2 + K && x2 + K <= y1);
@@ -164,7 +132,7 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
   u64* hmax = lazyH + nch;
   u64* smark = hmax + nch;                              // [ns] tiles of a group of 64 scored in this pass
   u64* scr = smark + ns;                                // [4 * LW]
-  u64* jobs = scr + 4 * LW;                             // [8 * nch + 8]  chunk << 0 | kind << 16 | migrations << 24 | migrations << 32
+  u64* jobs = scr + 4 * LW;                             // [8 * nch + 8]  chunk | kind << 16 | a set of the pass's migrations << 24 | another << 40
   Shared* S = (Shared*)(jobs + 8 * nch + 8);
   u32* keys = (u32*)(S + 1);                            // [nt]  bound of every tile
   u32* skeys = keys + nt;                               // [ns]  largest bound of every group of 64 tiles
@@ -190,8 +158,6 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
     S->nl = 0; S->restL = NONE32; S->stale_hot = 0;
     S->stop = 0; S->t_start = wall_clock64();
     S->mem[0].hi = 0; S->mem[0].lo = 0;
-    for (u32 i = 0; i < 32; ++i) S->phase[i] = 0;
-    S->t_last = wall_clock64();
   }
   __syncthreads();
   for (u32 g = wave; g < ns; g += LW) {                 // group bounds
@@ -334,13 +300,6 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
       const Score r = score_candidate(pv, mc, A, B);
       if (r.strike0) a.cd.A[cur.p] = make_uint4(A.x, A.y, 1u, 0u);
       if (r.strike1) a.cd.B[cur.p] = make_uint4(1u, 0u, B.z, B.w);
-#ifdef G10_PHASE_TIMERS
-      {                                          // live candidates and destinations looked at
-        const bool v0 = A.z <= A.w, v1 = B.x <= B.y;
-        const u32 nl = (u32)__popcll(__ballot(v0 || v1)), nd = (u32)(__popcll(__ballot(v0)) + __popcll(__ballot(v1)));
-        if (lane == 0) { atomicAdd((unsigned long long*)&S->phase[9], (unsigned long long)nl); atomicAdd((unsigned long long*)&S->phase[10], (unsigned long long)nd); }
-      }
-#endif
       u32 exact = 0;
       Score rr = r;
       if (CLIP && (rr.ok0 || rr.ok1)) {          // the band bounds the area; a value computed earlier bounds it closer
@@ -441,8 +400,11 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
   };
 
   // ---- chunk jobs: one wavefront rewrites one chunk of one timeline, for all migrations of the
-  // pass at once (a job word: kind << 16 | chunk) -------------------------------------------
-  auto run_jobs = [&](const u32 mm) {
+  // pass at once.  A job word: chunk | kind << 16 | set A << 24 | set B << 40, the sets being
+  // bits over the pass's migrations: for a transfer-window job, A = the migrations of that
+  // destination whose window meets the chunk; for a pressure or host job, A = those whose range
+  // cuts the chunk, B = those that cover it whole -------------------------------------------
+  auto run_jobs = [&]() {
     const u32 nj = S->njobs;
     for (u32 jb = wave; jb < nj; jb += LW) {
       const u64 jw = jobs[jb];
@@ -689,7 +651,7 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
       }
     }
     __syncthreads();
-    run_jobs(1u);
+    run_jobs();
     __syncthreads();
     const u64 a0 = S->acc[0], a1 = S->acc[1], a2 = S->acc[2];
     const u64 vlo = a0 + (a1 << 32), vhi = a2 + (a1 >> 32) + (vlo < a0 ? 1ull : 0ull);
@@ -730,9 +692,6 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
     if (max_iter && S->n_iter >= max_iter) { if (tid == 0) { S->done = 1; S->status = G10_TRUNCATED; } break; }
     if (passes >= a.pass_budget || S->stop) break;
     ++passes;
-#ifdef G10_PHASE_TIMERS
-    if (tid == 0) S->phase[11] += 1;
-#endif
     mine.hi = 0; mine.lo = 0; mine.cost = 1; mine.cand = NONE32; mine.exact = 0; mine.kU = 0; mine.kr = 0;
     floor2 = 0;
     pass_units = 0;
@@ -743,7 +702,7 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
       S->n_iter += 1; S->n_evals += C - S->n_mig - S->n_drop;
       S->hq = 0; S->njobs = 0; S->ot_changed = 0;
       S->mem[0].hi = 0; S->mem[0].lo = 0;
-      S->nlist = 0; S->Fx = 0; S->F2 = 0; S->cut = MAXM; S->need_exact = 0; S->m0 = 1; S->by_floor = 0; S->m = 1; S->touched = 0;
+      S->nlist = 0; S->F2 = 0; S->cut = MAXM; S->need_exact = 0; S->m0 = 1; S->by_floor = 0; S->touched = 0;
       if (S->stale_hot) { S->restL = NONE32; S->stale_hot = 0; }
       if (a.tick_budget && wall_clock64() - S->t_start > a.tick_budget) S->stop = 1;
     }
@@ -782,11 +741,8 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
         mine.hi = 0; mine.lo = 0; mine.cost = 1; mine.cand = NONE32; mine.exact = 0;
       }
       if (!decided) {
-        PHASE(0);
         score_list(thr);
-        PHASE(1);
         reduce_best();
-        PHASE(2);
         ++rounds;
         const u32 kb = key_dn_of<RATIO>(S->mem[0].hi, S->mem[0].lo, S->mem[0].cost);
         const u32 need = kb ? kb : 1u;
@@ -803,7 +759,6 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
       if (!CLIP || settle()) break;
       again = true;
     }
-    PHASE(3);
 
     const bool none = (S->mem[0].hi | S->mem[0].lo) == 0;
     if (none) { __syncthreads(); if (tid == 0) { S->done = 1; S->status = G10_RESIDUAL; } break; }
@@ -877,7 +832,6 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
       if (lane == 0) { S->m0 = m; S->by_floor = by_floor; }
     } else if (MC && wave == LW - 1 && lane == 0) S->by_floor = 1;     // (nothing else on the list)
     __syncthreads();
-    PHASE(3);
 
     // Step 2, chunk by chunk: what every picked migration does to the chunk (kept in `fl`, six bits
     // each), and how many of them can go together: the first that might let a slot drop under the
@@ -929,14 +883,13 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
       if (f0 & F_PALL) atomicMax((unsigned long long*)&S->hq, (unsigned long long)hmax[tid]);
       else if (f0 & F_PCUT) jobs[atomicAdd(&S->njobs, 1u)] = ((u64)J_HQ << 16) | tid;
       __syncthreads();
-      run_jobs(1u);
+      run_jobs();
       __syncthreads();
       room = s <= host_cap && S->hq <= host_cap - s;
       __syncthreads();
       if (tid == 0) S->njobs = 0;
       __syncthreads();
     }
-    PHASE(4);
 
     // Step 3: the plan records, the counters and the next pass's first threshold (the last
     // wavefront, lane i takes migration i) beside the commit chunk by chunk: a chunk a migration
@@ -1021,10 +974,8 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
       if (fi[1]) jobs[atomicAdd(&S->njobs, 1u)] = ((u64)fi[1] << 24) | ((u64)J_FI1 << 16) | c;
     }
     __syncthreads();
-    PHASE(6);
-    run_jobs(m);
+    run_jobs();
     __syncthreads();
-    PHASE(7);
     // level 1: the bases of the timelines whose chunk totals changed, one wavefront per timeline
     {
       const u32 touched = S->touched | (S->ot_changed ? 1u : 0u);
@@ -1049,7 +1000,6 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
         if (lane == G10_WAVE - 1) base[(u64)arr * nb1 + nch] = inc;
       }
       __syncthreads();
-      PHASE(8);
     }
   }
   __syncthreads();
@@ -1064,7 +1014,6 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
     ctl->thr_key = S->thr_key; ctl->status = S->status; ctl->done = S->done;
     ctl->gshift = S->gshift;
     ctl->overtime_after = base[(u64)A_OT * nb1 + nch];
-    for (u32 i = 0; i < 32; ++i) ctl->phase[i] += S->phase[i];
     ctl->units_scored += S->units; ctl->second_rounds += S->second; ctl->jobs_run += S->jobs; ctl->launches += 1;
     ctl->passes += passes;
     ctl->area_evals += S->evals; ctl->area_refused += S->refused;
@@ -1088,10 +1037,15 @@ static LoopKernel loop_kernel(u32 rank, u32 area) {
   return rank == G10_RANK_RATIO ? k_loop<true, false> : k_loop<false, false>;
 }
 
-int loop_allow_large_lds() {
+int loop_allow_large_lds() {                     // (once per device: the attribute belongs to the kernel, not to a handle)
+  static bool done[64] = {};
+  int dev = 0;
+  G10_HIP(hipGetDevice(&dev));
+  if (dev >= 0 && dev < 64 && done[dev]) return G10_OK;
   for (u32 rank = 0; rank < 2; ++rank)
     for (u32 area = 0; area < 2; ++area)
       G10_HIP(hipFuncSetAttribute((const void*)loop_kernel(rank, area), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+  if (dev >= 0 && dev < 64) done[dev] = true;
   return G10_OK;
 }
 

@@ -53,7 +53,6 @@
 #include "g10_plan_defs.h"
 
 #include <hip/hip_ext.h>
-#include <chrono>
 #include <new>
 #include <stdio.h>
 #include <stdlib.h>
@@ -421,10 +420,7 @@ void plan_work_free(PlanWork* w) {
 static const u32 SCORE_SORT_BITS = 23;           // significant bits of a score sort key
 static const u32 SCORE_SORT_PASSES = (SCORE_SORT_BITS + 7) / 8;
 static const u32 PASS_BUDGET = 4096;             // ranking passes per launch of the loop kernel
-#ifndef G10_RETILE_PASSES
-#define G10_RETILE_PASSES 128
-#endif
-static const u32 RETILE_PASSES = G10_RETILE_PASSES;   // ... between two re-tilings of a long candidate list
+static const u32 RETILE_PASSES = 128;   // ... between two re-tilings of a long candidate list
 static const u32 RETILE_MIN_CANDS = 8192;        // shorter lists are never re-tiled
 static const u64 BATCH_LAUNCH_TICKS = 250000;    // a launch of a batch ends after 2.5 ms (100 MHz clock)
 
@@ -592,14 +588,6 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     }
   } guard{h, I, hargs, hctl, who, hsj, htj};
   if (!I || !hargs || !hctl || !who || !hsj || !htj) return G10_ENOMEM;
-#ifdef G10_PHASE_TIMERS
-  double host_ms[8] = {};                                 // wall clock of the host's phases
-  auto now_ms = [] { return std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now().time_since_epoch()).count(); };
-  double t_mark = now_ms();
-#define G10_HOST_PHASE(k) do { const double t_ = now_ms(); host_ms[k] += t_ - t_mark; t_mark = t_; } while (0)
-#else
-#define G10_HOST_PHASE(k) do { } while (0)
-#endif
 
   for (u32 i = 0; i < count; ++i) {
     const g10_params* p = params + i;
@@ -710,7 +698,6 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
   }
   G10_TRY(sync_all());
   for (u32 i = 0; i < count; ++i) I[i].n = I[I[i].lead].n;
-  G10_HOST_PHASE(0);
 
   // the candidate buffers of a plan; the value cache only where the plan reads the benefit as the clipped area
   auto cands_of = [](const Inst& x, int which) {
@@ -843,7 +830,6 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     G10_TRY(sync_all());
     G10_TRY(run_jobs(nj0, max0, false));
   }
-  G10_HOST_PHASE(1);
   if (!h->lds_opt_in && lds_max > 64 * 1024) {
     G10_TRY(loop_allow_large_lds());
     h->lds_opt_in = true;
@@ -859,7 +845,6 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
   const bool timed_loop = n_active != 0;
   if (timed_loop) G10_HIP(hipEventRecord(I[0].w->ev[4], s));
   while (n_active) {
-    G10_HOST_PHASE(2);
     u32 na = 0, n_by_kind[4] = {0, 0, 0, 0};
     size_t lds = 0;
     for (u32 pass = 0; pass < 4 * count; ++pass) {         // the plans of one ranking key and benefit reading side by side: one kernel each
@@ -884,16 +869,11 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     G10_HIP(hipMemcpyAsync(h->loop_args, hargs, (size_t)na * sizeof(LoopArgs), hipMemcpyHostToDevice, s));
     for (u32 kind = 0, first = 0; kind < 4; first += n_by_kind[kind], ++kind)
       if (n_by_kind[kind]) G10_TRY(loop_launch((const LoopArgs*)h->loop_args + first, n_by_kind[kind], lds, kind & 1u, kind >> 1, s));
-#ifdef G10_PHASE_TIMERS
-    G10_HIP(hipStreamSynchronize(s));
-    G10_HOST_PHASE(3);
-#endif
     hipLaunchKernelGGL(k_ctl_collect, dim3(na), dim3(G10_WAVE), 0, s, (const LoopArgs*)h->loop_args, ctl_side);
     G10_HIP(hipGetLastError());
     G10_HIP(hipMemcpyAsync(hctl, ctl_side, (size_t)na * sizeof(Ctl), hipMemcpyDeviceToHost, s));
     G10_HIP(hipStreamSynchronize(s));
     for (u32 k = 0; k < na; ++k) I[who[k]].hc = hctl[k];
-    G10_HOST_PHASE(4);
     n_active = 0;
     u32 nj = 0;                                               // the re-tilings of a batch: every plan's in the same launches
     JobMax mx;
@@ -922,7 +902,6 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
       }
     }
     G10_TRY(run_jobs(nj, mx, true));
-    G10_HOST_PHASE(5);
   }
   if (timed_loop) G10_HIP(hipEventRecord(I[0].w->ev[5], s));
 
@@ -953,12 +932,6 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
   }
   G10_HIP(hipEventRecord(I[0].w->ev[1], s));
   G10_HIP(hipStreamSynchronize(s));
-  G10_HOST_PHASE(6);
-#ifdef G10_PHASE_TIMERS
-  if (getenv("G10_LOG"))
-    fprintf(stderr, "g10: host phases (ms): timelines+windows %.2f, first order %.2f, loop launches %.2f, loops %.2f, progress read %.2f, "
-                    "re-tilings %.2f, results %.2f\n", host_ms[0], host_ms[1], host_ms[2], host_ms[3], host_ms[4], host_ms[5], host_ms[6]);
-#endif
   float ms = 0.f, loop_ms = 0.f;
   G10_HIP(hipEventElapsedTime(&ms, I[0].w->ev[0], I[0].w->ev[1]));
   if (timed_loop) G10_HIP(hipEventElapsedTime(&loop_ms, I[0].w->ev[4], I[0].w->ev[5]));
@@ -969,17 +942,6 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     const Ctl& hc = x.hc;
     float full_ms = 0.f;
     if (x.timed_full) G10_HIP(hipEventElapsedTime(&full_ms, w->ev[2], w->ev[3]));
-#ifdef G10_PHASE_TIMERS
-    if (getenv("G10_LOG")) {
-      fprintf(stderr, "g10: loop phases (us per pass):");
-      for (int q = 0; q < 9; ++q) fprintf(stderr, " %d:%.2f", q, hc.phase[q] / 100.0 / (double)(hc.n_iter ? hc.n_iter : 1));
-      fprintf(stderr, "  live/pass %.1f dests/pass %.1f real passes %llu\n", hc.phase[9] / (double)(hc.n_iter ? hc.n_iter : 1), hc.phase[10] / (double)(hc.n_iter ? hc.n_iter : 1), (unsigned long long)hc.phase[11]);
-      fprintf(stderr, "g10: last wavefront (us per real pass): scan %.2f host %.2f select %.2f finalize %.2f\n", hc.phase[29] / 100.0 / (double)hc.phase[11], hc.phase[30] / 100.0 / (double)hc.phase[11], hc.phase[31] / 100.0 / (double)hc.phase[11], hc.phase[17] / 100.0 / (double)hc.phase[11]);
-      fprintf(stderr, "g10: stats:");
-      for (int q = 12; q < 32; ++q) fprintf(stderr, " %d:%llu", q, (unsigned long long)hc.phase[q]);
-      fprintf(stderr, "\n");
-    }
-#endif
     w->planned = true; w->plan_cap = x.p->gpu_cap_bytes; w->plan_n_mig = hc.n_mig;
     g10_result* out = outs + i;
     memset(out, 0, sizeof *out);

@@ -14,18 +14,12 @@ namespace g10 {
 enum { A_OT = 0, A_FO = 1, A_FI = 3, N_ARR = 5, PX = 8 };
 enum { J_P = 0, J_H = 1, J_FO0 = 2, J_FO1 = 3, J_FI0 = 4, J_FI1 = 5, J_HQ = 6, J_CLIP = 7 };   // kinds of chunk jobs
 
-#ifndef G10_LOOP_THREADS
-#define G10_LOOP_THREADS 512
-#endif
-constexpr u32 LB = G10_LOOP_THREADS;   // threads of the loop workgroup (at least NCH_MAX)
+constexpr u32 LB = 512;                // threads of the loop workgroup (at least NCH_MAX)
 constexpr u32 LW = LB / G10_WAVE;      // its wavefronts
 constexpr u32 UNIT = 256;              // candidates scored by four wavefronts at a time
 constexpr u32 NCH_MAX = 512;           // chunks (level-1 arrays live in LDS)
 constexpr u32 NT_MAX = 8192;           // tiles  (their bounds live in LDS)
-#ifndef G10_GUESS_SHIFT
-#define G10_GUESS_SHIFT 7
-#endif
-constexpr u32 GUESS_SHIFT = G10_GUESS_SHIFT;   // first threshold of a pass: last benefit * (1 - 2^-shift), to begin with
+constexpr u32 GUESS_SHIFT = 7;                 // first threshold of a pass: last benefit * (1 - 2^-shift), to begin with
 constexpr u32 GUESS_SHIFT_MAX = 24;            // the keys resolve no finer steps
 constexpr u64 NONE64 = ~0ull;
 constexpr u32 NONE32 = 0xffffffffu;
@@ -50,7 +44,6 @@ struct Ctl {
   // statistics
   u64 units_scored, second_rounds, jobs_run, launches, passes;
   u64 area_evals, area_refused;   // clipped areas computed in the loop; of those, how many came out below the bound
-  u64 phase[32];              // wall-clock ticks per phase of the loop (only with G10_PHASE_TIMERS)
 };
 
 struct Cands {

@@ -199,7 +199,12 @@ int prefetch_run(g10_plan_s* h, g10_prefetch_result* out) {
     const u64 C = w->C ? w->C : 1;
     w->h_pf_order = (u32*)malloc(C * 4); w->h_pf_gained = (u32*)malloc(C * 4); w->h_pf_last = (u32*)malloc(C * 4);
     w->h_pf_pressure = (u64*)malloc((u64)K * 8);
-    if (!w->h_pf_order || !w->h_pf_gained || !w->h_pf_last || !w->h_pf_pressure) return G10_ENOMEM;
+    if (!w->h_pf_order || !w->h_pf_gained || !w->h_pf_last || !w->h_pf_pressure) {
+      // all four or none: the next call must find the same state as the first
+      free(w->h_pf_order); free(w->h_pf_gained); free(w->h_pf_last); free(w->h_pf_pressure);
+      w->h_pf_order = nullptr; w->h_pf_gained = nullptr; w->h_pf_last = nullptr; w->h_pf_pressure = nullptr;
+      return G10_ENOMEM;
+    }
   }
   G10_HIP(hipEventRecord(w->ev[0], s));
   G10_HIP(hipMemcpyAsync(w->pf_pressure, w->pressure_after, (u64)K * 8, hipMemcpyDeviceToDevice, s));
