@@ -287,6 +287,9 @@ def main():
         rs = hb.plan_batch(sweep)
         tb = time.perf_counter() - t0
         out["batch"] = {"plans": nb, "sweep": "gpu_cap 20..35 % of the peak footprint", "ms": tb * 1e3,
+                        "library_ms": rs[0].plan_ms, "prepare_ms": rs[0].batch_prepare_ms, "loops_ms": rs[0].batch_loops_ms,
+                        "retile_ms": rs[0].batch_retile_ms, "results_ms": rs[0].batch_results_ms,
+                        "binding_ms": tb * 1e3 - rs[0].plan_ms,
                         "ms_per_plan": tb * 1e3 / nb, "passes": int(sum(x.n_iterations for x in rs)),
                         "candidates_per_s": sum(x.n_cand_evals for x in rs) / tb,
                         "speedup_over_one_by_one": (r.plan_ms * 1e-3 * nb) / tb}
@@ -302,6 +305,8 @@ def main():
         tb = time.perf_counter() - t0
         hb.close()
         out["batch_bandwidth_sweep"] = {"plans": nb, "sweep": "flash bandwidth 6.4..32 GB/s", "ms": tb * 1e3,
+                                        "prepare_ms": rs[0].batch_prepare_ms, "loops_ms": rs[0].batch_loops_ms,
+                                        "retile_ms": rs[0].batch_retile_ms, "results_ms": rs[0].batch_results_ms,
                                         "ms_per_plan": tb * 1e3 / nb, "passes": int(sum(x.n_iterations for x in rs)),
                                         "candidates_per_s": sum(x.n_cand_evals for x in rs) / tb}
 

@@ -167,6 +167,11 @@ typedef struct {
   uint64_t loop_chunk_jobs;    /* timeline chunks rewritten slot by slot               */
   uint64_t loop_area_evals;    /* G10_AREA_CLIPPED: clipped areas summed exactly       */
   uint64_t loop_area_refused;  /* ... of which came out below the bound (ranked again) */
+  /* g10_plan_batch with more than one plan: host wall clock of the phases of the call (0 otherwise) */
+  double batch_prepare_ms;     /* timelines, candidate windows, first scoring and ordering of all plans */
+  double batch_loops_ms;       /* the launches of the greedy loops (all plans side by side) and the read-back of their progress */
+  double batch_retile_ms;      /* putting the candidate lists back into score order between launches */
+  double batch_results_ms;     /* final pressure, copies of the plans to the host              */
 } g10_counters;
 
 typedef struct g10_plan_s g10_plan_t;   /* opaque: device copy of the analysis + workspaces */

@@ -75,7 +75,9 @@ class _Counters(C.Structure):
                 ("loop_ms", C.c_double), ("loop_launches", C.c_uint64), ("loop_passes", C.c_uint64),
                 ("loop_retiles", C.c_uint64), ("retile_cands", C.c_uint64), ("loop_cands_scored", C.c_uint64),
                 ("loop_second_rounds", C.c_uint64), ("loop_chunk_jobs", C.c_uint64),
-                ("loop_area_evals", C.c_uint64), ("loop_area_refused", C.c_uint64)]
+                ("loop_area_evals", C.c_uint64), ("loop_area_refused", C.c_uint64),
+                ("batch_prepare_ms", C.c_double), ("batch_loops_ms", C.c_double), ("batch_retile_ms", C.c_double),
+                ("batch_results_ms", C.c_double)]
 
 
 class _PrefetchResult(C.Structure):
@@ -150,6 +152,10 @@ class Result:
         self.records = take(r.migrations, int(r.n_migrations), MIGRATION)
         self.dropped = take(r.dropped, int(r.n_dropped), DROPPED)
         self.pressure_after = take(r.pressure_after, K, np.dtype("<u8"))
+        if pool is None:
+            self._dropped_views()
+
+    def _dropped_views(self):
         self.null_iters = self.dropped["iteration"].copy()
         self.null_cands = self.dropped["cand"].copy()
 
@@ -166,11 +172,14 @@ class Result:
 
 
 class _Pool:
-    """One allocation for the host copies of many results: a few large pages instead of many small ones."""
+    """One allocation for the host copies of many results: a few large pages instead of many small ones.
+    The copies themselves are collected and run together by flush(), over a few threads where there is
+    much to copy (ctypes releases the interpreter lock around memmove)."""
 
     def __init__(self, nbytes: int):
         self.buf = np.empty(max(nbytes, 1), np.uint8)
         self.at = 0
+        self.todo = []
 
     def take(self, ptr, n, dtype):
         if not n or not ptr:
@@ -178,8 +187,18 @@ class _Pool:
         size = n * dtype.itemsize
         out = self.buf[self.at:self.at + size]
         self.at += size
-        C.memmove(out.ctypes.data, ptr, size)
+        self.todo.append((out.ctypes.data, ptr, size))
         return out.view(dtype)
+
+    def flush(self):
+        todo, self.todo = self.todo, []
+        if sum(t[2] for t in todo) < (32 << 20):
+            for dst, src, size in todo:
+                C.memmove(dst, src, size)
+            return
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=8) as ex:
+            list(ex.map(lambda t: C.memmove(*t), todo))
 
 
 class PrefetchResult:
@@ -289,7 +308,11 @@ class Handle:
         if rc:
             raise G10Error(rc, "g10_plan_batch")
         pool = _Pool(sum(Result.nbytes(r, self.K) for r in rs))
-        return [Result(r, self.K, pool, self._counters(i)) for i, r in enumerate(rs)]
+        out = [Result(r, self.K, pool, self._counters(i)) for i, r in enumerate(rs)]
+        pool.flush()
+        for x in out:
+            x._dropped_views()
+        return out
 
     def plan(self, gpu_cap, host_cap, bw_out, bw_in, max_iters=0, max_tiles=0, max_chunks=0, dur=None, rank=0, area=0) -> Result:
         import torch

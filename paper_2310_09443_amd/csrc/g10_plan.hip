@@ -53,6 +53,7 @@
 #include "g10_plan_defs.h"
 
 #include <hip/hip_ext.h>
+#include <chrono>
 #include <new>
 #include <stdio.h>
 #include <stdlib.h>
@@ -524,10 +525,11 @@ struct Inst {
   bool counted = false;        // hc.n_live holds a count of the current list
   bool timed_full = false;
   u64 times_check[16] = {};     // the checks of the plan's own durations come back here
-  u64 seen_iter = 0;           // passes done at the last re-tiling
+  u64 seen_passes = 0;         // passes of the loop kernel done at the last re-tiling
   u32 lead = 0;                // the plan of the batch whose candidate windows this one reads (itself, or an
                                // earlier plan with the same bandwidths and durations: the windows depend on nothing else)
   bool fw_done = false;        // (of such a plan) the copy of the windows for the first scoring pass is written or on its way
+  bool results_sent = false;   // the plan is finished and its results are on their way to the host
 };
 
 static PlanWork** work_slot(g10_plan_s* h, u32 i) { return i == 0 ? &h->work : &h->more[i - 1]; }
@@ -565,6 +567,12 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
   Ctl* const ctl_side = (Ctl*)((LoopArgs*)h->loop_args + h->loop_args_cap);    // the progress blocks of a launch, collected
   SortJob* const sort_jobs = (SortJob*)(ctl_side + h->loop_args_cap);          // the re-tilings of a round of a batch
   TileJob* const tile_jobs = (TileJob*)(sort_jobs + h->loop_args_cap);
+  // host wall clock of the call's phases (a batch of several plans only: it costs a synchronisation per round)
+  const bool clocked = count > 1;
+  double phase_ms[4] = {0, 0, 0, 0};                     // preparation and first ordering; loops; re-tilings; results
+  auto now_ms = [] { return std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now().time_since_epoch()).count(); };
+  double t_mark = now_ms();
+  auto phase_end = [&](int k) { const double t = now_ms(); phase_ms[k] += t - t_mark; t_mark = t; };
   h->n_counters = 0;
   {
     g10_counters* q = (g10_counters*)realloc(h->counters, (size_t)count * sizeof(g10_counters));
@@ -576,18 +584,19 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
   LoopArgs* hargs = (LoopArgs*)malloc((size_t)count * sizeof(LoopArgs));
   Ctl* hctl = (Ctl*)malloc((size_t)count * sizeof(Ctl));
   u32* who = (u32*)malloc((size_t)count * sizeof(u32));                       // the plan of every entry of a launch
+  u64* peaks = (u64*)malloc((size_t)count * sizeof(u64));                     // the plans' final peaks come back here
   SortJob* hsj = (SortJob*)malloc((size_t)count * sizeof(SortJob));
   TileJob* htj = (TileJob*)malloc((size_t)count * sizeof(TileJob));
   // whatever way this function is left, nothing is in flight that reads or writes these host arrays
   struct Guard {
-    g10_plan_s* h; Inst* i; LoopArgs* a; Ctl* c; u32* w; SortJob* sj; TileJob* tj;
+    g10_plan_s* h; Inst* i; LoopArgs* a; Ctl* c; u32* w; SortJob* sj; TileJob* tj; u64* pk;
     ~Guard() {
       for (u32 k = 0; k < h->n_aux; ++k) (void)hipStreamSynchronize(h->aux[k]);
       (void)hipStreamSynchronize(h->stream);
-      delete[] i; free(a); free(c); free(w); free(sj); free(tj);
+      delete[] i; free(a); free(c); free(w); free(sj); free(tj); free(pk);
     }
-  } guard{h, I, hargs, hctl, who, hsj, htj};
-  if (!I || !hargs || !hctl || !who || !hsj || !htj) return G10_ENOMEM;
+  } guard{h, I, hargs, hctl, who, hsj, htj, peaks};
+  if (!I || !hargs || !hctl || !who || !hsj || !htj || !peaks) return G10_ENOMEM;
 
   for (u32 i = 0; i < count; ++i) {
     const g10_params* p = params + i;
@@ -843,7 +852,38 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
   // (a batch re-tiles half as often: its loops run side by side, its re-tilings one after the other)
   const u32 retile_every = count == 1 ? RETILE_PASSES : 2 * RETILE_PASSES;
   const bool timed_loop = n_active != 0;
+  // The results of a finished plan: the pressure with the lazy adds applied and its peak, then the
+  // copies to one block of pinned host memory (so that they run as plain DMA), grown when a plan
+  // needs more.  In a batch they go out on the plan's own stream as soon as the plan is done, beside
+  // the loops of the others.
+  auto send_results = [&](u32 i) -> int {
+    Inst& x = I[i];
+    PlanWork* w = x.w;
+    const Ctl& hc = x.hc;
+    hipStream_t q = stream_of(i);
+    x.results_sent = true;
+    hipLaunchKernelGGL(k_finish, dim3(K / G10_BLOCK / 4 + 1), dim3(G10_BLOCK), 0, q, x.tl, (const u64*)w->g_lazyP, w->pressure_after,
+                       w->peak_after);
+    G10_HIP(hipGetLastError());
+    G10_HIP(hipMemcpyAsync(&peaks[i], w->peak_after, 8, hipMemcpyDeviceToHost, q));
+    const size_t need = (size_t)K * 8 + hc.n_mig * sizeof(g10_migration) + hc.n_drop * sizeof(g10_dropped);
+    if (need > w->h_block_bytes) {
+      if (w->h_block) { (void)hipHostFree(w->h_block); w->h_block = nullptr; w->h_block_bytes = 0; }
+      const size_t want = need + need / 4 + 4096;
+      if (hipHostMalloc(&w->h_block, want, hipHostMallocDefault) != hipSuccess) { (void)hipGetLastError(); w->h_block = nullptr; return G10_ENOMEM; }
+      w->h_block_bytes = want;
+    }
+    w->h_pressure = (u64*)w->h_block;
+    w->h_records = (g10_migration*)(w->h_pressure + K);
+    w->h_dropped = (g10_dropped*)(w->h_records + hc.n_mig);
+    if (hc.n_mig) G10_HIP(hipMemcpyAsync(w->h_records, w->records, hc.n_mig * sizeof(g10_migration), hipMemcpyDeviceToHost, q));
+    if (hc.n_drop) G10_HIP(hipMemcpyAsync(w->h_dropped, w->dropped, hc.n_drop * sizeof(g10_dropped), hipMemcpyDeviceToHost, q));
+    G10_HIP(hipMemcpyAsync(w->h_pressure, w->pressure_after, (u64)K * 8, hipMemcpyDeviceToHost, q));
+    return G10_OK;
+  };
+
   if (timed_loop) G10_HIP(hipEventRecord(I[0].w->ev[4], s));
+  if (clocked) { G10_HIP(hipStreamSynchronize(s)); phase_end(0); }
   while (n_active) {
     u32 na = 0, n_by_kind[4] = {0, 0, 0, 0};
     size_t lds = 0;
@@ -873,16 +913,20 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     G10_HIP(hipGetLastError());
     G10_HIP(hipMemcpyAsync(hctl, ctl_side, (size_t)na * sizeof(Ctl), hipMemcpyDeviceToHost, s));
     G10_HIP(hipStreamSynchronize(s));
+    if (clocked) phase_end(1);
     for (u32 k = 0; k < na; ++k) I[who[k]].hc = hctl[k];
     n_active = 0;
     u32 nj = 0;                                               // the re-tilings of a batch: every plan's in the same launches
     JobMax mx;
     for (u32 i = 0; i < count; ++i) {
       Inst& x = I[i];
-      if (x.hc.done) continue;
+      if (x.hc.done) {
+        if (count > 1 && !x.results_sent) G10_TRY(send_results(i));     // (the stream was synchronised: the plan's state is final)
+        continue;
+      }
       ++n_active;
-      if (x.n > RETILE_MIN_CANDS && x.hc.n_iter - x.seen_iter >= retile_every) {
-        x.seen_iter = x.hc.n_iter;
+      if (x.n > RETILE_MIN_CANDS && x.hc.passes - x.seen_passes >= retile_every) {
+        x.seen_passes = x.hc.passes;
         if (x.counted && x.hc.n_live < x.n) x.n = x.hc.n_live;   // live candidates come first in the list
         x.retile_cands += x.n;
         if (count == 1) G10_TRY(retile(x, false, s));
@@ -902,36 +946,17 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
       }
     }
     G10_TRY(run_jobs(nj, mx, true));
+    if (clocked && nj) { G10_HIP(hipStreamSynchronize(s)); phase_end(2); }
   }
   if (timed_loop) G10_HIP(hipEventRecord(I[0].w->ev[5], s));
 
   // ---- results ---------------------------------------------------------------------------
-  u64* peaks = (u64*)hargs;                                // reuse as a small host buffer (count <= its size / 8)
-  for (u32 i = 0; i < count; ++i) {
-    Inst& x = I[i];
-    PlanWork* w = x.w;
-    const Ctl& hc = x.hc;
-    hipLaunchKernelGGL(k_finish, dim3(K / G10_BLOCK / 4 + 1), dim3(G10_BLOCK), 0, s, x.tl, (const u64*)w->g_lazyP, w->pressure_after,
-                       w->peak_after);
-    G10_HIP(hipGetLastError());
-    G10_HIP(hipMemcpyAsync(&peaks[i], w->peak_after, 8, hipMemcpyDeviceToHost, s));
-    // the host copies of a plan's results: one block of pinned memory (so the copies run as plain DMA), grown when a plan needs more
-    const size_t need = (size_t)K * 8 + hc.n_mig * sizeof(g10_migration) + hc.n_drop * sizeof(g10_dropped);
-    if (need > w->h_block_bytes) {
-      if (w->h_block) { (void)hipHostFree(w->h_block); w->h_block = nullptr; w->h_block_bytes = 0; }
-      const size_t want = need + need / 4 + 4096;
-      if (hipHostMalloc(&w->h_block, want, hipHostMallocDefault) != hipSuccess) { (void)hipGetLastError(); w->h_block = nullptr; return G10_ENOMEM; }
-      w->h_block_bytes = want;
-    }
-    w->h_pressure = (u64*)w->h_block;
-    w->h_records = (g10_migration*)(w->h_pressure + K);
-    w->h_dropped = (g10_dropped*)(w->h_records + hc.n_mig);
-    if (hc.n_mig) G10_HIP(hipMemcpyAsync(w->h_records, w->records, hc.n_mig * sizeof(g10_migration), hipMemcpyDeviceToHost, s));
-    if (hc.n_drop) G10_HIP(hipMemcpyAsync(w->h_dropped, w->dropped, hc.n_drop * sizeof(g10_dropped), hipMemcpyDeviceToHost, s));
-    G10_HIP(hipMemcpyAsync(w->h_pressure, w->pressure_after, (u64)K * 8, hipMemcpyDeviceToHost, s));
-  }
+  for (u32 i = 0; i < count; ++i)
+    if (!I[i].results_sent) G10_TRY(send_results(i));
+  if (count > 1) for (u32 k = 0; k < h->n_aux; ++k) G10_HIP(hipStreamSynchronize(h->aux[k]));
   G10_HIP(hipEventRecord(I[0].w->ev[1], s));
   G10_HIP(hipStreamSynchronize(s));
+  if (clocked) phase_end(3);
   float ms = 0.f, loop_ms = 0.f;
   G10_HIP(hipEventElapsedTime(&ms, I[0].w->ev[0], I[0].w->ev[1]));
   if (timed_loop) G10_HIP(hipEventElapsedTime(&loop_ms, I[0].w->ev[4], I[0].w->ev[5]));
@@ -957,6 +982,7 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     ct.retile_cands = x.retile_cands;
     ct.loop_cands_scored = hc.units_scored * UNIT; ct.loop_second_rounds = hc.second_rounds; ct.loop_chunk_jobs = hc.jobs_run;
     ct.loop_area_evals = hc.area_evals; ct.loop_area_refused = hc.area_refused;
+    ct.batch_prepare_ms = phase_ms[0]; ct.batch_loops_ms = phase_ms[1]; ct.batch_retile_ms = phase_ms[2]; ct.batch_results_ms = phase_ms[3];
   }
   h->n_counters = count;
   return G10_OK;
