@@ -9,7 +9,9 @@
  * bytes per microsecond (6 GB/s = 6000).
  *
  * Conventions
- *   - plain C, no exceptions, no global state; every call returns an int:
+ *   - plain C, no exceptions; the only state outside the handles is the cache
+ *     of released memory (g10_trim) and the array of g10_vitality_static;
+ *     every call but g10_plan_free and g10_trim returns an int:
  *     G10_OK or a negative error.  On error output arguments are left
  *     untouched (handles) or zeroed (result structs).
  *   - pointers inside g10_trace are DEVICE pointers owned by the caller; the
@@ -329,9 +331,19 @@ typedef struct {
  * G10_EOVERFLOW (durations sum to >= 2^62), G10_ENOMEM, G10_EDEVICE. */
 int g10_replay(g10_plan_t *handle, const uint64_t *dur_ns, uint32_t eager, g10_replay_result *out);
 
-/* Frees everything the library allocated for the handle (the analysis of g10_vitality and the
- * workspaces of the planning calls).  NULL is allowed. */
+/* Releases everything the library allocated for the handle (the analysis of g10_vitality and the
+ * workspaces of the planning calls), after waiting for the handle's stream.  NULL is allowed.
+ * The profiling -> analysis -> plan cycle of Section 4.1 repeats with every new trace, and
+ * allocating and freeing device memory costs about as much host time as the analysis' kernels
+ * take: the blocks (device memory, pinned host memory, events) go to a cache inside the library,
+ * at most 4 GiB and 96 blocks per process, oldest out first, and the next g10_vitality / g10_plan
+ * takes a block of a fitting size from there before it asks the driver.  When the driver has no
+ * memory left the cache is emptied and the request made once more. */
 void g10_plan_free(g10_plan_t *handle);
+
+/* Hands every block of that cache back to the driver (for a caller that is done with the library
+ * for a while, or needs the memory).  Handles in use are not affected. */
+void g10_trim(void);
 
 #ifdef __cplusplus
 }

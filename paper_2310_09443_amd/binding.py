@@ -21,7 +21,7 @@ FITS, RESIDUAL, TRUNCATED = 0, 1, 2
 NO_WRAP = 1
 
 EXPORTS = ["g10_vitality", "g10_vitality_info", "g10_vitality_read", "g10_vitality_static", "g10_plan", "g10_plan_batch",
-           "g10_plan_counters", "g10_plan_limits", "g10_prefetch", "g10_replay", "g10_plan_free"]
+           "g10_plan_counters", "g10_plan_limits", "g10_prefetch", "g10_replay", "g10_plan_free", "g10_trim"]
 STATIC_MAX_K, STATIC_MAX_N, STATIC_MAX_P = 131072, 262144, 262144
 
 MIGRATION = np.dtype([("cand", "<u4"), ("tensor", "<u4"), ("evict_after", "<u4"),
@@ -118,6 +118,8 @@ def load():
         lib.g10_replay.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.POINTER(_ReplayResult)]
         lib.g10_plan_free.argtypes = [C.c_void_p]
         lib.g10_plan_free.restype = None
+        lib.g10_trim.argtypes = []
+        lib.g10_trim.restype = None
         _lib = lib
     return _lib
 
@@ -428,3 +430,7 @@ def g10_replay(handle: Handle, dur=None, eager=False) -> ReplayResult:
 
 def g10_plan_free(handle: Handle) -> None:
     handle.close()
+
+
+def g10_trim() -> None:
+    load().g10_trim()

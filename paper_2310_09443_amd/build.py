@@ -5,7 +5,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SRC = [os.path.join(HERE, "csrc", f) for f in ("g10_api.hip", "g10_vitality.hip", "g10_plan.hip", "g10_loop.hip", "g10_prefetch.hip", "g10_replay.hip")]
+SRC = [os.path.join(HERE, "csrc", f) for f in ("g10_api.hip", "g10_mem.hip", "g10_vitality.hip", "g10_plan.hip", "g10_loop.hip", "g10_prefetch.hip", "g10_replay.hip")]
 DEPS = SRC + [os.path.join(HERE, "csrc", "g10_internal.h"), os.path.join(HERE, "csrc", "g10_plan_defs.h"),
               os.path.join(ROOT, "include", "g10.h")]
 LIB = os.path.join(HERE, "libg10.so")

@@ -5,15 +5,26 @@
 #include <stdlib.h>
 #include <string.h>
 
+// The analysis' temporaries, once the handle's stream has been waited for after the analysis.
+static void release_tmp(g10_plan_s* h) {
+  mem_dev_free(h->tmp_arena);
+  h->tmp_arena = nullptr;
+}
+
 static void handle_free(g10_plan_s* h) {
   if (!h) return;
+  // what is released below is kept for the next call, not handed to the driver (which would wait
+  // for the device by itself): nothing of this handle may still be running
+  (void)hipStreamSynchronize(h->stream);
+  for (u32 k = 0; k < h->n_aux; ++k) (void)hipStreamSynchronize(h->aux[k]);
   plan_work_free(h->work);
   for (u32 i = 0; i < h->n_more; ++i) plan_work_free(h->more[i]);
   free(h->more);
   free(h->counters);
-  if (h->loop_args) (void)hipFree(h->loop_args);
+  mem_dev_free(h->loop_args);
   for (u32 k = 0; k < h->n_aux; ++k) (void)hipStreamDestroy(h->aux[k]);
-  if (h->arena) (void)hipFree(h->arena);        // every array of the analysis
+  mem_dev_free(h->arena);                      // every array of the analysis
+  release_tmp(h);
   delete h;
 }
 
@@ -75,6 +86,7 @@ extern "C" int g10_plan(g10_plan_t* h, const g10_params* p, g10_result* out) {
     (void)hipStreamSynchronize(h->stream);
     memset(out, 0, sizeof *out);
   }
+  release_tmp(h);                                 // (the results have been waited for, or the line above has)
   return rc;
 }
 
@@ -103,6 +115,7 @@ extern "C" int g10_plan_batch(g10_plan_t* h, const g10_params* params, uint32_t 
     (void)hipStreamSynchronize(h->stream);
     memset(outs, 0, sizeof(g10_result) * (size_t)count);
   }
+  release_tmp(h);
   return rc;
 }
 

@@ -21,6 +21,19 @@ typedef uint32_t u32;
   } while (0)
 
 int g10_hip_fail(hipError_t e, const char* file, int line);
+#define G10_TRY(x) do { int rc_ = (x); if (rc_) return rc_; } while (0)
+
+// Device memory, pinned host memory and events that outlive the call that released them (kept up
+// to a limit and handed to the next request of a fitting size; g10_trim gives them back to the
+// driver).  A block is released only after the work that used it has been waited for.
+#define G10_MEM_MAX_DEVICES 64
+int mem_dev_alloc(void** out, size_t bytes);      // on the current device
+void mem_dev_free(void* p);
+int mem_host_alloc(void** out, size_t bytes);     // pinned
+void mem_host_free(void* p);
+int mem_event_get(hipEvent_t* out);               // of the current device
+void mem_event_put(hipEvent_t e, int device);
+void mem_trim();
 
 // ---------------------------------------------------------------------------
 // wavefront / workgroup primitives (64-wide)
@@ -220,6 +233,7 @@ struct g10_plan_s {
   u32 loop_args_cap = 0;
   bool lds_opt_in = false;       // the loop kernel was allowed more than 64 KB of LDS
   void* arena = nullptr;         // the one device allocation the analysis arrays above point into
+  void* tmp_arena = nullptr;     // the analysis' temporaries, until the stream has next been waited for
   hipStream_t aux[8] = {};       // streams for the streaming kernels of the plans of a batch (made at the first batch)
   u32 n_aux = 0;
 };

@@ -410,11 +410,11 @@ __global__ __launch_bounds__(G10_WAVE) void k_ctl_collect(const LoopArgs* __rest
 
 void plan_work_free(PlanWork* w) {
   if (!w) return;
-  if (w->arena) (void)hipFree(w->arena);
+  mem_dev_free(w->arena);
   replay_free(w);
-  if (w->h_block) (void)hipHostFree(w->h_block);
+  mem_host_free(w->h_block);
   free(w->h_pf_order); free(w->h_pf_gained); free(w->h_pf_last); free(w->h_pf_pressure);
-  for (hipEvent_t e : w->ev) if (e) (void)hipEventDestroy(e);
+  for (hipEvent_t e : w->ev) mem_event_put(e, w->device);
   delete w;
 }
 
@@ -491,6 +491,7 @@ static int work_alloc(g10_plan_s* h, u32 max_chunks, bool cache, PlanWork** slot
   const u32 K = h->K;
   const u64 C = h->n_periods;
   w->K = K; w->C = C;
+  w->device = h->device;
   w->Kp = (K + 3u) & ~3u;
   w->spt = 1; w->shift_ch = 8;
   w->max_chunks = max_chunks;
@@ -503,12 +504,12 @@ static int work_alloc(g10_plan_s* h, u32 max_chunks, bool cache, PlanWork** slot
   Arena measure;
   work_layout(w, measure);
   void* q = nullptr;
-  if (hipMalloc(&q, measure.off + 256) != hipSuccess) { (void)hipGetLastError(); return G10_ENOMEM; }
+  G10_TRY(mem_dev_alloc(&q, measure.off + 256));
   w->arena = q;
   Arena carve;
   carve.base = (char*)q;
   work_layout(w, carve);
-  for (hipEvent_t& e : w->ev) G10_HIP(hipEventCreate(&e));
+  for (hipEvent_t& e : w->ev) G10_TRY(mem_event_get(&e));
   return G10_OK;
 }
 
@@ -556,12 +557,9 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     h->more = m; h->n_more = count - 1;
   }
   if (count > h->loop_args_cap) {
-    if (h->loop_args) { G10_HIP(hipStreamSynchronize(s)); (void)hipFree(h->loop_args); h->loop_args = nullptr; h->loop_args_cap = 0; }
+    if (h->loop_args) { G10_HIP(hipStreamSynchronize(s)); mem_dev_free(h->loop_args); h->loop_args = nullptr; h->loop_args_cap = 0; }
     void* q = nullptr;
-    if (hipMalloc(&q, (size_t)count * (sizeof(LoopArgs) + sizeof(Ctl) + sizeof(SortJob) + sizeof(TileJob))) != hipSuccess) {
-      (void)hipGetLastError();
-      return G10_ENOMEM;
-    }
+    G10_TRY(mem_dev_alloc(&q, (size_t)count * (sizeof(LoopArgs) + sizeof(Ctl) + sizeof(SortJob) + sizeof(TileJob))));
     h->loop_args = q; h->loop_args_cap = count;
   }
   Ctl* const ctl_side = (Ctl*)((LoopArgs*)h->loop_args + h->loop_args_cap);    // the progress blocks of a launch, collected
@@ -868,9 +866,9 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     G10_HIP(hipMemcpyAsync(&peaks[i], w->peak_after, 8, hipMemcpyDeviceToHost, q));
     const size_t need = (size_t)K * 8 + hc.n_mig * sizeof(g10_migration) + hc.n_drop * sizeof(g10_dropped);
     if (need > w->h_block_bytes) {
-      if (w->h_block) { (void)hipHostFree(w->h_block); w->h_block = nullptr; w->h_block_bytes = 0; }
+      if (w->h_block) { mem_host_free(w->h_block); w->h_block = nullptr; w->h_block_bytes = 0; }
       const size_t want = need + need / 4 + 4096;
-      if (hipHostMalloc(&w->h_block, want, hipHostMallocDefault) != hipSuccess) { (void)hipGetLastError(); w->h_block = nullptr; return G10_ENOMEM; }
+      if (mem_host_alloc(&w->h_block, want) != G10_OK) { w->h_block = nullptr; return G10_ENOMEM; }
       w->h_block_bytes = want;
     }
     w->h_pressure = (u64*)w->h_block;

@@ -7,7 +7,6 @@
 
 #include <hip/hip_runtime.h>
 
-#define G10_TRY(x) do { int rc_ = (x); if (rc_) return rc_; } while (0)
 
 namespace g10 {
 
@@ -364,6 +363,7 @@ struct PlanWork {
   bool prefetched = false;      // smart prefetching has run on that plan (pf_gained is valid)
   u64 plan_cap = 0, plan_n_mig = 0;
   // host copies handed out through g10_result
+  int device = 0;              // the GPU the workspaces and events belong to
   void* h_block = nullptr;     // pinned host memory of the three result arrays below
   size_t h_block_bytes = 0;
   g10_migration* h_records = nullptr;

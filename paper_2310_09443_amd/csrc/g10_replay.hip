@@ -191,7 +191,7 @@ __global__ __launch_bounds__(G10_WAVE) void k_replay(const u64* __restrict__ sor
 }  // namespace
 
 void replay_free(PlanWork* w) {
-  if (w->rp_arena) (void)hipFree(w->rp_arena);
+  mem_dev_free(w->rp_arena);
   w->rp_arena = nullptr; w->rp_cap = 0;
   free(w->h_rp_late); w->h_rp_late = nullptr;
 }
@@ -216,7 +216,7 @@ int replay_run(g10_plan_s* h, const u64* dur_ns, u32 eager, g10_replay_result* o
                  o_hist = take(he * 4), o_scr = take(se * 4), o_st = take(sizeof(ReplayStats)), o_dur = take((u64)K * 8),
                  o_start = take(((u64)K + 1) * 8), o_ts = take(scan_scratch_elems(K) * 8), o_tst = take(128);
     void* q = nullptr;
-    if (hipMalloc(&q, off) != hipSuccess) { (void)hipGetLastError(); return G10_ENOMEM; }
+    G10_TRY(mem_dev_alloc(&q, off));
     char* b = (char*)q;
     w->rp_arena = q; w->rp_cap = (u32)cap;
     w->rp_keys = (u64*)(b + o_keys); w->rp_alt = (u64*)(b + o_alt); w->rp_res = (u64*)(b + o_res); w->rp_late = (u64*)(b + o_late);

@@ -91,14 +91,6 @@ struct VitStats {
   u64 n_uses, n_periods, peak;
 };
 
-__global__ __launch_bounds__(G10_BLOCK) void k_check_pairs(const u32* __restrict__ uk, const u32* __restrict__ ut,
-                                                          u64 P, u32 K, u32 N, VitStats* st) {
-  u32 bad = 0;
-  for (u64 i = (u64)blockIdx.x * G10_BLOCK + threadIdx.x; i < P; i += (u64)gridDim.x * G10_BLOCK)
-    bad |= (uk[i] >= K) | (ut[i] >= N);
-  if (__any(bad) && lane_id() == 0) atomicOr(&st->bad_index, 1u);
-}
-
 __global__ __launch_bounds__(G10_BLOCK) void k_check_dur(const u64* __restrict__ dur, u32 K, VitStats* st) {
   __shared__ u64 tmp[G10_WAVES + 1];
   u64 lo = 0, hi = 0;
@@ -132,16 +124,25 @@ __global__ __launch_bounds__(G10_BLOCK) void k_check_size(const u64* __restrict_
   if (__any(ovf) && lane_id() == 0) atomicOr(&st->size_overflow, 1u);
   if (__any(big) && lane_id() == 0) atomicOr(&st->big_size, 1u);
   mx = wave_max(mx);
-  if (lane_id() == 0) atomicMax((unsigned long long*)&st->max_size, (unsigned long long)mx);
+  // (atomics on one address queue up behind each other: only a wavefront that can still raise the maximum sends one)
+  if (lane_id() == 0 && mx > *(volatile u64*)&st->max_size) atomicMax((unsigned long long*)&st->max_size, (unsigned long long)mx);
 }
 
 // ===========================================================================
 // use lists: key pack, radix sort, distinct
 // ===========================================================================
+// Sort keys (tensor, kernel) of the pairs.  A pair that names no kernel or no tensor of the trace is
+// reported and stands in as (0, 0): every later kernel then indexes inside its arrays, and the host
+// rejects the trace when it reads the report at the end of the analysis.
 __global__ __launch_bounds__(G10_BLOCK) void k_pack(const u32* __restrict__ uk, const u32* __restrict__ ut, u64 P,
-                                                   u32 kbits, u64* __restrict__ keys) {
-  for (u64 i = (u64)blockIdx.x * G10_BLOCK + threadIdx.x; i < P; i += (u64)gridDim.x * G10_BLOCK)
-    keys[i] = ((u64)ut[i] << kbits) | uk[i];
+                                                   u32 K, u32 N, u32 kbits, u64* __restrict__ keys, VitStats* st) {
+  u32 bad = 0;
+  for (u64 i = (u64)blockIdx.x * G10_BLOCK + threadIdx.x; i < P; i += (u64)gridDim.x * G10_BLOCK) {
+    u32 k = uk[i], t = ut[i];
+    if (k >= K || t >= N) { bad = 1; k = 0; t = 0; }
+    keys[i] = ((u64)t << kbits) | k;
+  }
+  if (__any(bad) && lane_id() == 0) atomicOr(&st->bad_index, 1u);
 }
 
 // Tile layout of the sort kernels: wavefront w of a workgroup owns the
@@ -377,18 +378,13 @@ __global__ __launch_bounds__(G10_BLOCK) void k_period_write(const u64* __restric
   }
 }
 
-// sort keys (period start, period index) and the periods gathered in that order as {L, R, tensor, index}
-__global__ __launch_bounds__(G10_BLOCK) void k_start_keys(const u32* __restrict__ per_L, u64 C, u32 cbits, u64* __restrict__ keys) {
-  for (u64 c = (u64)blockIdx.x * G10_BLOCK + threadIdx.x; c < C; c += (u64)gridDim.x * G10_BLOCK)
-    keys[c] = ((u64)per_L[c] << cbits) | c;
-}
-
-__global__ __launch_bounds__(G10_BLOCK) void k_gather_periods(const u64* __restrict__ keys, u64 C, u32 cbits,
+// the periods gathered in the order of their start (order[i]: index of the i-th) as {L, R, tensor, index}
+__global__ __launch_bounds__(G10_BLOCK) void k_gather_periods(const u32* __restrict__ order, u64 C,
                                                              const u32* __restrict__ per_t, const u32* __restrict__ per_L,
                                                              const u32* __restrict__ per_R, const u64* __restrict__ size,
                                                              uint4* __restrict__ out, u64* __restrict__ out_size) {
   for (u64 i = (u64)blockIdx.x * G10_BLOCK + threadIdx.x; i < C; i += (u64)gridDim.x * G10_BLOCK) {
-    const u32 c = (u32)(keys[i] & ((1ull << cbits) - 1ull));
+    const u32 c = order[i];
     const u32 t = per_t[c];
     out[i] = make_uint4(per_L[c], per_R[c], t, c);
     out_size[i] = size[t];
@@ -468,11 +464,11 @@ struct Pool {
   char* base = nullptr;
   size_t off = 0, cap = 0;
   bool owned = false;                             // released when this object goes away (the temporaries)
-  ~Pool() { if (owned && base) (void)hipFree(base); }
+  ~Pool() { if (owned) mem_dev_free(base); }
   static size_t need(u64 elems, size_t size) { return (((elems ? elems : 1) * size) + 255) & ~(size_t)255; }
   int reserve(size_t bytes) {
     void* q = nullptr;
-    if (hipMalloc(&q, bytes ? bytes : 256) != hipSuccess) { (void)hipGetLastError(); return G10_ENOMEM; }
+    G10_TRY(mem_dev_alloc(&q, bytes));
     base = (char*)q; cap = bytes; off = 0;
     return G10_OK;
   }
@@ -505,7 +501,6 @@ int g10_hip_fail(hipError_t e, const char* file, int line) {
   return e == hipErrorOutOfMemory ? G10_ENOMEM : G10_EDEVICE;
 }
 
-#define G10_TRY(x) do { int rc_ = (x); if (rc_) return rc_; } while (0)
 
 size_t radix_hist_elems(u64 n) { return (size_t)256 * ((n + TILE - 1) / TILE ? (n + TILE - 1) / TILE : 1) + 1; }
 
@@ -644,21 +639,11 @@ static int vitality_core(g10_plan_s* h, const g10_trace* tr, Pool& tmp, Pool& ke
     h->glob = const_cast<uint8_t*>(tr->is_global);
   }
 
-  // ---- validation --------------------------------------------------------
-  if (P) hipLaunchKernelGGL(k_check_pairs, dim3(grid_for(P)), dim3(G10_BLOCK), 0, s, tr->use_kernel, tr->use_tensor, P, K, N, st);
+  // ---- validation (read by the host with the counts, at the one synchronisation below: nothing
+  // a kernel does with a zero duration, a zero or huge size or a wrapped sum leaves its arrays) ---
   hipLaunchKernelGGL(k_check_dur, dim3(grid_for(K)), dim3(G10_BLOCK), 0, s, h->dur, K, st);
-  hipLaunchKernelGGL(k_check_size, dim3(grid_for(N)), dim3(G10_BLOCK), 0, s, h->size, N, st);
+  hipLaunchKernelGGL(k_check_size, dim3(grid_for(N, 1024)), dim3(G10_BLOCK), 0, s, h->size, N, st);
   G10_HIP(hipGetLastError());
-  VitStats hs;
-  G10_HIP(hipMemcpyAsync(&hs, st, sizeof hs, hipMemcpyDeviceToHost, s));
-  G10_HIP(hipStreamSynchronize(s));
-  if (hs.bad_index || hs.zero_dur || hs.zero_size) return G10_EINVAL;
-  if (hs.size_overflow) return G10_EOVERFLOW;
-  {
-    unsigned __int128 T = ((unsigned __int128)hs.dur_hi << 32) + hs.dur_lo;
-    if (T >> 62) return G10_EOVERFLOW;
-    h->T = (u64)T;
-  }
 
   // ---- slot start times ----------------------------------------------------
   u64* scratch64 = nullptr;
@@ -677,7 +662,7 @@ static int vitality_core(g10_plan_s* h, const g10_trace* tr, Pool& tmp, Pool& ke
   G10_TRY(tmp.take(&hist, radix_hist_elems(P)));
   G10_TRY(tmp.take(&scratch32, scan_scratch_elems(radix_hist_elems(P) > P ? radix_hist_elems(P) : P)));
   if (P) {
-    hipLaunchKernelGGL(k_pack, dim3(grid_for(P)), dim3(G10_BLOCK), 0, s, tr->use_kernel, tr->use_tensor, P, h->kbits, keys);
+    hipLaunchKernelGGL(k_pack, dim3(grid_for(P)), dim3(G10_BLOCK), 0, s, tr->use_kernel, tr->use_tensor, P, K, N, h->kbits, keys, st);
     G10_TRY(radix_sort_u64(&keys, &alt, P, h->kbits + tbits, hist, scratch32, s));
     hipLaunchKernelGGL(k_flag_distinct, dim3(grid_for(P)), dim3(G10_BLOCK), 0, s, keys, P, flag);
     G10_HIP(hipGetLastError());
@@ -714,9 +699,15 @@ static int vitality_core(g10_plan_s* h, const g10_trace* tr, Pool& tmp, Pool& ke
   hipLaunchKernelGGL(k_max_u64, dim3(grid_for(K, 1024)), dim3(G10_BLOCK), 0, s, h->pressure_buf + 1, (u64)K, &st->peak);
   hipLaunchKernelGGL(k_store_counts, dim3(1), dim3(1), 0, s, n_uses_p, pcnt + P, st);
   G10_HIP(hipGetLastError());
+  VitStats hs;
   G10_HIP(hipMemcpyAsync(&hs, st, sizeof hs, hipMemcpyDeviceToHost, s));
   G10_HIP(hipStreamSynchronize(s));
+  if (hs.bad_index || hs.zero_dur || hs.zero_size) return G10_EINVAL;
+  if (hs.size_overflow) return G10_EOVERFLOW;
   {
+    unsigned __int128 T = ((unsigned __int128)hs.dur_hi << 32) + hs.dur_lo;
+    if (T >> 62) return G10_EOVERFLOW;
+    h->T = (u64)T;
     unsigned __int128 used = ((unsigned __int128)hs.used_hi << 32) + hs.used_lo;
     if (used >> 64) return G10_EOVERFLOW;
   }
@@ -735,24 +726,28 @@ static int vitality_core(g10_plan_s* h, const g10_trace* tr, Pool& tmp, Pool& ke
   G10_TRY(keep.take(&h->per_by_start, C));      // (C <= P)
   G10_TRY(keep.take(&h->per_size, C));
   if (C) {
-    const u32 cbits = bits_for(C - 1);
-    hipLaunchKernelGGL(k_start_keys, dim3(grid_for(C)), dim3(G10_BLOCK), 0, s, h->per_L, C, cbits, keys);
-    G10_TRY(radix_sort_u64(&keys, &alt, C, cbits + h->kbits, hist, scratch32, s));
-    hipLaunchKernelGGL(k_gather_periods, dim3(grid_for(C)), dim3(G10_BLOCK), 0, s, keys, C, cbits, h->per_t, h->per_L, h->per_R,
+    // (a stable sort of the starts alone, the position carried along: equal starts keep the order of the periods)
+    u32 *k32 = (u32*)keys, *k32_alt = k32 + C, *ord = (u32*)alt, *ord_alt = ord + C;      // (C <= P: two arrays of C words in one of P keys)
+    G10_HIP(hipMemcpyAsync(k32, h->per_L, C * 4, hipMemcpyDeviceToDevice, s));
+    G10_TRY(radix_sort_u32_pairs(&k32, &k32_alt, &ord, &ord_alt, C, h->kbits, hist, scratch32, s, true));
+    hipLaunchKernelGGL(k_gather_periods, dim3(grid_for(C)), dim3(G10_BLOCK), 0, s, (const u32*)ord, C, h->per_t, h->per_L, h->per_R,
                        h->size, h->per_by_start, h->per_size);
-    G10_HIP(hipGetLastError());
-    G10_HIP(hipStreamSynchronize(s));               // the temporaries go away with this function
+    G10_HIP(hipGetLastError());                     // (still running when this function returns: see vitality_run)
   }
   return G10_OK;
 }
 
 int vitality_run(g10_plan_s* h, const g10_trace* tr) {
   if (h->P >= (1ull << 32)) return G10_EINVAL;    // positions and counts are 32-bit on the device
-  Pool tmp, keep;                                 // temporaries of this call; what the handle keeps
-  tmp.owned = true;
+  // The temporaries of the call and what the handle keeps.  The last kernels of the analysis
+  // still read the temporaries when the call returns (planning follows on the same stream and
+  // need not wait for them): they are released at the next point where the stream has been
+  // waited for, at the latest with the handle.
+  Pool tmp, keep;
   G10_TRY(tmp.reserve(vit_tmp_bytes(h->K, h->N, h->P)));
+  h->tmp_arena = tmp.base;
   G10_TRY(keep.reserve(vit_keep_bytes(h->K, h->N, h->P, true)));
-  h->arena = keep.base;                           // released with the handle
+  h->arena = keep.base;
   return vitality_core(h, tr, tmp, keep, true);
 }
 

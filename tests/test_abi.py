@@ -51,6 +51,7 @@ def test_null_arguments_are_rejected_without_a_gpu():
     assert lib.g10_plan_limits(None, 0, 0) == binding.EINVAL
     assert lib.g10_vitality_static(None, None, None, None) == binding.EINVAL
     lib.g10_plan_free(None)
+    lib.g10_trim()                              # (nothing is kept yet: touches no device)
     t = binding._Trace()                        # K = 0
     h = ctypes.c_void_p()
     assert lib.g10_vitality(ctypes.byref(t), None, ctypes.byref(h)) == binding.EINVAL

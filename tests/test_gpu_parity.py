@@ -515,3 +515,34 @@ def test_stress_full_size_prefix_and_properties(g10):
     assert hashlib.sha256(r.pressure_after.astype("<u8").tobytes()).hexdigest() == gold["pressure_after_sha256"]
     assert (r.status, r.n_iterations, r.n_migrations, r.n_dropped, r.n_cand_evals) == \
         tuple(int(gold[k]) for k in ("status", "passes", "migrations", "dropped", "cand_evals"))
+
+
+def test_released_memory_is_reused_and_trim_returns_it(g10):
+    """What g10_plan_free releases stays in the library's cache and serves the next handle (same
+    results from memory that holds the last call's contents); g10_trim hands it back to the driver."""
+    import torch
+    w = traces.config(3)
+    dt = g10.DeviceTrace(w.trace)
+    v = O.Vitality(w.trace, O.PREFIX)
+    cap, hcap = traces.resolve_caps(w, v.peak)
+    p = v.plan(cap, hcap, w.bw_out_Bpus, w.bw_in_Bpus)
+    g10.g10_trim()
+    torch.cuda.synchronize()
+    free_start = torch.cuda.mem_get_info()[0]
+    for _ in range(3):                              # the second and third run in released blocks
+        h = g10.g10_vitality(dt)
+        assert_vitality_equal(h, v)
+        r = h.plan(cap, hcap, w.bw_out_Bpus, w.bw_in_Bpus)
+        assert_plan_equal(r, p)
+        in_use = torch.cuda.mem_get_info()[0]
+        h.close()
+    kept = torch.cuda.mem_get_info()[0]
+    assert kept <= in_use + (1 << 20)               # nothing went back to the driver with the handle
+    # a different, smaller trace afterwards: blocks that do not fit are not handed out
+    w2 = traces.config(1)
+    h2, v2, args2 = run_both(g10, w2)
+    assert_plan_equal(h2.plan(**args2), v2.plan(args2["gpu_cap"], args2["host_cap"], w2.bw_out_Bpus, w2.bw_in_Bpus))
+    h2.close()
+    g10.g10_trim()
+    assert torch.cuda.mem_get_info()[0] >= free_start - (8 << 20)
+    assert torch.cuda.mem_get_info()[0] > kept
