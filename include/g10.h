@@ -169,6 +169,8 @@ typedef struct {
   uint64_t loop_chunk_jobs;    /* timeline chunks rewritten slot by slot               */
   uint64_t loop_area_evals;    /* G10_AREA_CLIPPED: clipped areas summed exactly       */
   uint64_t loop_area_refused;  /* ... of which came out below the bound (ranked again) */
+  uint64_t loop_wide_rounds;   /* G10_RANK_RATIO, one plan: scoring rounds of a pass left to the scoring
+                                  kernel on all compute units (their candidates count in loop_cands_scored) */
   /* g10_plan_batch with more than one plan: host wall clock of the phases of the call (0 otherwise) */
   double batch_prepare_ms;     /* timelines, candidate windows, first scoring and ordering of all plans */
   double batch_loops_ms;       /* the launches of the greedy loops (all plans side by side) and the read-back of their progress */

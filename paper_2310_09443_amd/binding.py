@@ -75,7 +75,7 @@ class _Counters(C.Structure):
                 ("loop_ms", C.c_double), ("loop_launches", C.c_uint64), ("loop_passes", C.c_uint64),
                 ("loop_retiles", C.c_uint64), ("retile_cands", C.c_uint64), ("loop_cands_scored", C.c_uint64),
                 ("loop_second_rounds", C.c_uint64), ("loop_chunk_jobs", C.c_uint64),
-                ("loop_area_evals", C.c_uint64), ("loop_area_refused", C.c_uint64),
+                ("loop_area_evals", C.c_uint64), ("loop_area_refused", C.c_uint64), ("loop_wide_rounds", C.c_uint64),
                 ("batch_prepare_ms", C.c_double), ("batch_loops_ms", C.c_double), ("batch_retile_ms", C.c_double),
                 ("batch_results_ms", C.c_double)]
 

@@ -23,6 +23,39 @@ struct Winner {               // what a commit needs of the winning candidate
   u32 pad;
 };
 
+// Ranking by benefit / cost keeps a bound per candidate that holds whichever destination the
+// policy ends up with: most of a long list then reaches the threshold of every pass and has to
+// be scored again.  Such a round is left to all compute units: the loop kernel writes the list
+// of tiles to score, ends in the middle of its pass, a scoring kernel takes the list (the tile
+// bounds go into the array of tile bounds in device memory, every workgroup's best candidate
+// into `win`), and the next launch of the loop kernel takes the pass up again with those.
+constexpr u32 WIDE_WG = LB - 1;   // workgroups of the scoring kernel that take part at most: one winner per thread of the loop
+                                  // kernel, whose last thread takes the best of the pass's earlier rounds
+struct WideCtx {
+  u32 pending;                // the loop kernel has left a list and waits for it to be scored
+  u32 nwg, done_wgs;          // workgroups of the scoring kernel that take part; that have finished
+  u32 ntl, thr, rest;         // of the round left open: tiles on the list, its threshold, bound of the tiles not on it
+  u32 rounds, pass_units;     // of the pass left open: rounds finished, units scored in them
+  u32 seq, pad[3];            // launches of the loop kernel on this plan so far
+};
+struct WideView {
+  WideCtx* ctx;
+  Winner* win;                // [WIDE_WG], then the best of the earlier rounds
+  u64* smark;                 // [NT_MAX / 64]  tiles scored in the pass left open
+  unsigned short* alist;      // [NT_MAX]       the list
+};
+constexpr size_t WIDE_BYTES = sizeof(WideCtx) + (WIDE_WG + 1) * sizeof(Winner) + (NT_MAX / 64) * 8 + (size_t)NT_MAX * 2;
+__host__ __device__ __forceinline__ WideView wide_view(void* blob) {
+  WideView v;
+  char* q = (char*)blob;
+  v.ctx = (WideCtx*)q; q += sizeof(WideCtx);
+  v.win = (Winner*)q; q += (WIDE_WG + 1) * sizeof(Winner);
+  v.smark = (u64*)q; q += (NT_MAX / 64) * 8;
+  v.alist = (unsigned short*)q;
+  return v;
+}
+static_assert(sizeof(WideCtx) % 16 == 0 && sizeof(Winner) % 8 == 0, "the arrays of the scoring kernel's block stay aligned");
+
 constexpr u32 MAXM = 16;      // migrations committed in one ranking pass at most (a multiple of 8, at most 16: the job words hold two sets of 16)
 static_assert(MAXM % 8 == 0 && MAXM <= 16, "job words and chunk flags are laid out for 8 or 16");
 
@@ -45,7 +78,8 @@ struct Shared {               // small per-pass state of the loop workgroup
   u64 evals, refused;         // clipped areas computed; of those, how many came out below the bound
   u32 nl, restL;              // hot list: length; bound of the tiles outside it
   u32 ntl, filt;              // current round: tiles to score; bound of the hot tiles left out
-  u32 njobs, ot_changed, stale_hot, pad1;
+  u32 njobs, ot_changed, stale_hot;
+  u32 no_wide;                // this launch may not leave a round to the scoring kernel (none is queued behind it)
   // progress (mirrors Ctl)
   u64 n_iter, n_mig, n_drop, n_evals, units, second, jobs;
   u32 thr_key, status, done, stop;
@@ -120,6 +154,7 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
   // certain that each would have won the pass after the one before it - see "more migrations
   // of the same pass" below.
   constexpr bool MC = !RATIO && !CLIP;
+  constexpr bool WIDE = RATIO && !CLIP;        // long scoring rounds may be left to the scoring kernel (see WideCtx)
   extern __shared__ __align__(16) unsigned char smem[];
   const LoopArgs a = plans[blockIdx.x];        // one workgroup per plan
   const Timelines tl = a.tl;
@@ -141,6 +176,23 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
 
   const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
   Ctl* ctl = a.ctl;
+  // A pass left open by the last launch: its list has been scored by the scoring kernel (1), or
+  // has not (2: it is scored here).  Launches are queued ahead of what is known of the plan's
+  // progress; one that finds nothing to do ends at once.
+  WideView wv = {};
+  u32 resume = 0;
+  if (tid == 0) S->no_wide = 0;
+  if (WIDE && a.wide) {
+    wv = wide_view(a.wide);
+    if (wv.ctx->pending) resume = (wv.ctx->nwg && wv.ctx->done_wgs == wv.ctx->nwg) ? 1u : 2u;
+    if (tid == 0) {                                  // (read by everyone after the barrier that ends "state in")
+      const u32 seq = wv.ctx->seq + 1;
+      wv.ctx->seq = seq;
+      S->no_wide = seq == a.wide_last_seq ? 1u : 0u;
+    }
+    if (!resume && (ctl->done || (a.pass_stop && ctl->passes >= a.pass_stop))) return;
+  }
+  const u64 passes_before = ctl->passes;
   const u64 cap = ctl->gpu_cap, host_cap = ctl->host_cap, max_iter = ctl->max_iter, C = ctl->C;
   const u64 bwo0 = ctl->bw_out[0], bwo1 = ctl->bw_out[1], bwi0 = ctl->bw_in[0], bwi1 = ctl->bw_in[1];
   const u64 ivo0 = ctl->inv_out[0], ivo1 = ctl->inv_out[1], ivi0 = ctl->inv_in[0], ivi1 = ctl->inv_in[1];
@@ -686,20 +738,31 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
   __syncthreads();
   // ---- passes ------------------------------------------------------------------------
   u32 passes = 0;
+  bool wide_exit = false;
   while (true) {
-    if (S->done) break;
-    if (base[(u64)A_OT * nb1 + nch] == 0) { if (tid == 0) { S->done = 1; S->status = G10_FITS; } break; }
-    if (max_iter && S->n_iter >= max_iter) { if (tid == 0) { S->done = 1; S->status = G10_TRUNCATED; } break; }
-    if (passes >= a.pass_budget || S->stop) break;
-    ++passes;
+    if (!resume) {                                   // (a pass taken up again has passed these tests)
+      if (S->done) break;
+      if (base[(u64)A_OT * nb1 + nch] == 0) { if (tid == 0) { S->done = 1; S->status = G10_FITS; } break; }
+      if (max_iter && S->n_iter >= max_iter) { if (tid == 0) { S->done = 1; S->status = G10_TRUNCATED; } break; }
+      if (passes >= a.pass_budget || S->stop || (a.pass_stop && passes_before + passes >= a.pass_stop)) break;
+      if (WIDE && S->no_wide) break;               // (the last launch of a round only ends the pass left open)
+      ++passes;
+    }
     mine.hi = 0; mine.lo = 0; mine.cost = 1; mine.cand = NONE32; mine.exact = 0; mine.kU = 0; mine.kr = 0;
     floor2 = 0;
     pass_units = 0;
     u32 thr = S->thr_key ? S->thr_key : NONE32;
+    if (WIDE && resume) thr = wv.ctx->thr;
     __syncthreads();                               // the loop conditions and thr are read
-    for (u32 i = tid; i < ns; i += LB) smark[i] = 0;     // no tile scored in this pass yet
+    if (WIDE && resume) {                          // the tiles the open pass has scored, and the list of its open round
+      for (u32 i = tid; i < ns; i += LB) smark[i] = wv.smark[i];
+      for (u32 i = tid; i < wv.ctx->ntl; i += LB) alist[i] = wv.alist[i];
+    } else {
+      for (u32 i = tid; i < ns; i += LB) smark[i] = 0;   // no tile scored in this pass yet
+    }
     if (tid == 0) {
-      S->n_iter += 1; S->n_evals += C - S->n_mig - S->n_drop;
+      if (WIDE && resume) { S->ntl = wv.ctx->ntl; S->filt = 0; S->nl = 0; S->restL = NONE32; S->stale_hot = 0; }
+      else { S->n_iter += 1; S->n_evals += C - S->n_mig - S->n_drop; }
       S->hq = 0; S->njobs = 0; S->ot_changed = 0;
       S->mem[0].hi = 0; S->mem[0].lo = 0;
       S->nlist = 0; S->F2 = 0; S->cut = MAXM; S->need_exact = 0; S->m0 = 1; S->by_floor = 0; S->touched = 0;
@@ -717,7 +780,12 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
     while (true) {
       u32 rest;
       bool decided = false;                      // the best by bound is known
-      if (!again) {
+      if (WIDE && resume) {
+        rest = wv.ctx->rest;
+        rounds = wv.ctx->rounds;
+        pass_units = wv.ctx->pass_units;
+        if (tid == LB - 1 && rounds) mine = wv.win[WIDE_WG];    // the best of the rounds before
+      } else if (!again) {
         if (S->restL >= thr) {                     // the hot list may miss a tile that reaches thr: build it anew,
           const u32 low = thr == NONE32 ? thr : (thr > (1u << 19) ? thr - (1u << 19) : 1u);   // a few percent lower to last a while
           __syncthreads();
@@ -741,7 +809,33 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
         mine.hi = 0; mine.lo = 0; mine.cost = 1; mine.cand = NONE32; mine.exact = 0;
       }
       if (!decided) {
-        score_list(thr);
+        if (WIDE && a.wide_min && !resume && !S->no_wide && (S->ntl << a.tshift) >= a.wide_min) {
+          // a long round: the list, the tiles marked and what the pass needs to go on (with the
+          // best of its earlier rounds) are left for the scoring kernel and the next launch
+          const u32 ntl = S->ntl, nu = ntl << a.tshift;
+          for (u32 i = tid; i < ns; i += LB) wv.smark[i] = smark[i];
+          for (u32 i = tid; i < ntl; i += LB) wv.alist[i] = alist[i];
+          if (tid == 0) {
+            wv.win[WIDE_WG] = S->mem[0];         // (hi = lo = 0: none yet)
+            wv.ctx->rounds = rounds; wv.ctx->pass_units = pass_units;
+            wv.ctx->ntl = ntl; wv.ctx->thr = thr; wv.ctx->rest = rest;
+            wv.ctx->nwg = nu < WIDE_WG ? nu : WIDE_WG; wv.ctx->done_wgs = 0;
+            wv.ctx->pending = 1;
+            ctl->wide_rounds += 1;
+          }
+          wide_exit = true;
+          break;
+        }
+        if (WIDE && resume == 1) {                // the scoring kernel's winners, one per thread
+          if (tid < wv.ctx->nwg) mine = wv.win[tid];
+          const u32 nu = S->ntl << a.tshift;
+          if (tid == 0) S->units += nu;
+          pass_units += nu;
+        } else score_list(thr);
+        if (WIDE && resume) {
+          resume = 0;
+          if (tid == 0) wv.ctx->pending = 0;
+        }
         reduce_best();
         ++rounds;
         const u32 kb = key_dn_of<RATIO>(S->mem[0].hi, S->mem[0].lo, S->mem[0].cost);
@@ -759,6 +853,7 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
       if (!CLIP || settle()) break;
       again = true;
     }
+    if (WIDE && wide_exit) break;
 
     const bool none = (S->mem[0].hi | S->mem[0].lo) == 0;
     if (none) { __syncthreads(); if (tid == 0) { S->done = 1; S->status = G10_RESIDUAL; } break; }
@@ -1020,7 +1115,80 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
   }
 }
 
+// The scoring kernel of WideCtx: workgroup b scores the units b, b + nwg, ... of the list the
+// loop kernel left (256 candidates each, scored as the loop kernel's own rounds score them),
+// raises the bounds of their tiles in device memory and leaves its best candidate in win[b].
+__global__ __launch_bounds__(UNIT) void k_wide_score(const LoopArgs* __restrict__ plans) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const LoopArgs a = plans[0];
+  if (!a.wide) return;
+  const WideView wv = wide_view(a.wide);
+  const u32 nwg = wv.ctx->nwg;
+  if (!wv.ctx->pending || blockIdx.x >= nwg) return;
+  const Timelines tl = a.tl;
+  const u32 nch = tl.nch, nb1 = nch + 1, K = tl.K;
+  const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+  u64* base = (u64*)smem;                               // [5][nch + 1]
+  Winner* wwin = (Winner*)(base + (u64)N_ARR * nb1);    // [UNIT / 64]
+  for (u32 i = tid; i < N_ARR * nb1; i += UNIT) base[i] = a.g_base[i];
+  __syncthreads();
+  const Ctl* ctl = a.ctl;
+  PrefixView pv; pv.px = tl.px; pv.base = base; pv.K = K; pv.nch = nch; pv.shift_ch = tl.shift_ch;
+  Machine mc; mc.bwo0 = ctl->bw_out[0]; mc.bwo1 = ctl->bw_out[1]; mc.bwi0 = ctl->bw_in[0]; mc.bwi1 = ctl->bw_in[1];
+  mc.ivo0 = ctl->inv_out[0]; mc.ivo1 = ctl->inv_out[1]; mc.ivi0 = ctl->inv_in[0]; mc.ivi1 = ctl->inv_in[1];
+  Winner mine;
+  mine.hi = 0; mine.lo = 0; mine.cost = 1; mine.cand = NONE32; mine.exact = 0; mine.kU = 0; mine.kr = 0; mine.tau_o = 0; mine.tau_i = 0; mine.pad = 0;
+  mine.s = 0; mine.fo_base = 0; mine.fi_end = 0; mine.tensor = 0; mine.pos = 0; mine.dest = 0; mine.L1 = 0; mine.R = 0; mine.a = 1; mine.b = 0;
+  const u32 nunits = wv.ctx->ntl << a.tshift;
+  for (u32 u = blockIdx.x; u < nunits; u += nwg) {
+    const u32 t = wv.alist[u >> a.tshift];
+    const u32 p = (((t << a.tshift) + (u & ((1u << a.tshift) - 1u))) << 8) + tid;
+    const uint4 A = a.cd.A[p], B = a.cd.B[p];
+    const uint2 id = a.cd.id[p];
+    const Score r = score_candidate(pv, mc, A, B);
+    if (r.strike0) a.cd.A[p] = make_uint4(A.x, A.y, 1u, 0u);
+    if (r.strike1) a.cd.B[p] = make_uint4(1u, 0u, B.z, B.w);
+    u64 c0 = 1, c1 = 1;
+    if (r.ok0 || r.ok1) costs_of(mc, ((u64)B.w << 32) | B.z, c0, c1);
+    const u32 k0 = key_up_of<true>(r.h0, r.l0, c0), k1 = key_up_of<true>(r.h1, r.l1, c1);
+    const u32 k = wave_max(k0 > k1 ? k0 : k1);         // the tile's bound holds for either destination
+    if (lane == 0 && k) atomicMax(&a.g_keys[t], k);
+    const bool ok_any = r.ok0 || r.ok1;                // flash first; host only if flash cannot take it
+    const u32 d = r.ok0 ? 0u : 1u;
+    const u64 hi = ok_any ? (d ? r.h1 : r.h0) : 0ull, lo = ok_any ? (d ? r.l1 : r.l0) : 0ull, cost = d ? c1 : c0;
+    if ((hi | lo) != 0 && better_ratio(hi, lo, cost, id.x, mine.hi, mine.lo, mine.cost, mine.cand)) {
+      mine.hi = hi; mine.lo = lo; mine.cost = cost; mine.cand = id.x; mine.tensor = id.y; mine.pos = p; mine.dest = d;
+      mine.L1 = A.x; mine.R = A.y; mine.a = d ? B.x : A.z; mine.b = d ? B.y : A.w; mine.s = ((u64)B.w << 32) | B.z;
+      mine.fo_base = r.fo_L; mine.fi_end = r.fi_R;
+    }
+  }
+  const u32 bl = wave_best_lane_ratio(mine.hi, mine.lo, mine.cost, mine.cand);
+  if (bl == NONE32) { if (lane == 0) { mine.hi = 0; mine.lo = 0; mine.cost = 1; mine.cand = NONE32; wwin[wave] = mine; } }
+  else if (lane == bl) wwin[wave] = mine;
+  __syncthreads();
+  if (wave == 0) {
+    u64 h = 0, l = 0, cs = 1;
+    u32 c = NONE32;
+    if (lane < UNIT / 64) { h = wwin[lane].hi; l = wwin[lane].lo; cs = wwin[lane].cost; c = wwin[lane].cand; }
+    const u32 w = wave_best_lane_ratio(h, l, cs, c);
+    if (lane == 0) {
+      wv.win[blockIdx.x] = wwin[w == NONE32 ? 0u : w];  // (none: any of the four, all empty)
+      __threadfence();
+      atomicAdd(&wv.ctx->done_wgs, 1u);
+    }
+  }
+}
+
 }  // namespace
+
+size_t loop_wide_bytes() { return WIDE_BYTES; }
+
+int loop_wide_launch(const LoopArgs* plans, u32 nch, hipStream_t s) {
+  const size_t lds = (size_t)N_ARR * (nch + 1) * 8 + (UNIT / 64) * sizeof(Winner);
+  hipLaunchKernelGGL(k_wide_score, dim3(WIDE_WG), dim3(UNIT), lds, s, plans);
+  G10_HIP(hipGetLastError());
+  return G10_OK;
+}
 
 size_t loop_lds_bytes(u32 nch, u32 nt) {
   const size_t ns = (nt + 63) / 64;

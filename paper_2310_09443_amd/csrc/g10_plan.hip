@@ -424,6 +424,12 @@ static const u32 PASS_BUDGET = 4096;             // ranking passes per launch of
 static const u32 RETILE_PASSES = 128;   // ... between two re-tilings of a long candidate list
 static const u32 RETILE_MIN_CANDS = 8192;        // shorter lists are never re-tiled
 static const u64 BATCH_LAUNCH_TICKS = 250000;    // a launch of a batch ends after 2.5 ms (100 MHz clock)
+// Ranking by benefit / cost on a long list (one plan, band reading): a scoring round of WIDE_MIN_UNITS
+// x 256 candidates or more is left to a kernel on all compute units.  The loop kernel then ends in
+// the middle of its pass and takes it up in its next launch, so such launches are queued in pairs,
+// a round of them ahead of what the host knows.
+static const u32 WIDE_MIN_UNITS = 32;
+static const u64 WIDE_MIN_CANDS = 65536;
 
 static u32 tile_shift_for(u64 n, u32 max_tiles) { // smallest tile (256 << shift) with at most max_tiles tiles
   u32 sh = 0;
@@ -482,6 +488,7 @@ static void work_layout(PlanWork* w, Arena& ar) {
   ar.take(&w->pf_stats, 4);
   ar.take(&w->dur_own, K); ar.take(&w->start_own, (u64)K + 1);
   ar.take(&w->times_scratch, scan_scratch_elems(K)); ar.take(&w->times_stats, 16);
+  ar.take(&w->wide, loop_wide_bytes());
 }
 
 static int work_alloc(g10_plan_s* h, u32 max_chunks, bool cache, PlanWork** slot) {
@@ -527,6 +534,9 @@ struct Inst {
   bool timed_full = false;
   u64 times_check[16] = {};     // the checks of the plan's own durations come back here
   u64 seen_passes = 0;         // passes of the loop kernel done at the last re-tiling
+  u64 seen_units = 0, seen_passes_w = 0;   // units scored and passes done when the last round of launches began
+  bool wide = false;           // long scoring rounds are left to the scoring kernel in the current round of launches
+  u32 loop_seq = 0;            // launches of the loop kernel queued so far (with a block for the scoring kernel)
   u32 lead = 0;                // the plan of the batch whose candidate windows this one reads (itself, or an
                                // earlier plan with the same bandwidths and durations: the windows depend on nothing else)
   bool fw_done = false;        // (of such a plan) the copy of the windows for the first scoring pass is written or on its way
@@ -683,6 +693,7 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     tl.dur = w->dur; tl.P = w->P; tl.fre = w->fre; tl.H = w->H; tl.px = w->px; tl.otc = w->otc;
     tl.K = K; tl.Kp = w->Kp; tl.nch = w->nch; tl.spt = w->spt; tl.shift_ch = w->shift_ch;
     G10_HIP(hipMemsetAsync(w->peak_after, 0, 8, q));
+    G10_HIP(hipMemsetAsync(w->wide, 0, 64, q));           // (no pass left open)
     hipLaunchKernelGGL(k_init_timelines, dim3(w->nch), dim3(G10_BLOCK), 0, q, tl, (const u64*)(h->pressure_buf + 1),
                        (const Ctl*)w->ctl, w->g_tot, w->g_lazyP, w->g_minOver, w->g_lazyH, w->g_hmax);
     hipLaunchKernelGGL(k_level1_init, dim3(1), dim3(LB), 0, q, (const u64*)w->g_tot, w->nch, w->base0, w->ctl);
@@ -901,10 +912,36 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
       la.cd = cands_of(x, x.cur); la.n_pad = x.n_pad; la.nt = x.nt; la.tshift = x.tsh;
       la.pass_budget = x.n > RETILE_MIN_CANDS && count == 1 ? RETILE_PASSES : PASS_BUDGET;
       la.tick_budget = count > 1 ? BATCH_LAUNCH_TICKS : 0;
+      // one plan ranked by benefit / cost: with the scoring kernel where the list is long and the
+      // last round of launches scored much of it per pass (or none has run yet)
+      la.wide = nullptr; la.wide_min = 0; la.pass_stop = 0; la.wide_last_seq = 0;
+      x.wide = false;
+      if (count == 1 && x.p->rank == G10_RANK_RATIO && x.p->area == G10_AREA_BAND && x.n >= WIDE_MIN_CANDS) {
+        const u64 dp = x.hc.passes - x.seen_passes_w, du = x.hc.units_scored - x.seen_units;
+        la.wide = w->wide;                       // (always there for this kind of plan: a pass may have been left open)
+        if (x.launches == 1 || du >= (u64)WIDE_MIN_UNITS * dp) {
+          x.wide = true;
+          la.wide_min = WIDE_MIN_UNITS;
+          la.pass_stop = x.hc.passes + la.pass_budget;
+          la.wide_last_seq = x.loop_seq + la.pass_budget + 1;
+        }
+        x.loop_seq += x.wide ? la.pass_budget + 1 : 1;
+        x.seen_passes_w = x.hc.passes; x.seen_units = x.hc.units_scored;
+      }
       const size_t l = loop_lds_bytes(w->nch, x.nt);
       if (l > lds) lds = l;
     }
     G10_HIP(hipMemcpyAsync(h->loop_args, hargs, (size_t)na * sizeof(LoopArgs), hipMemcpyHostToDevice, s));
+    if (count == 1 && I[0].wide) {
+      // pairs of loop and scoring kernel: every launch of the loop kernel starts a pass at least (or
+      // finds nothing left to do), so this many reach the round's last pass; one more launch ends
+      // the pass the last pair may have left open
+      for (u32 g = 0; g < hargs[0].pass_budget; ++g) {
+        G10_TRY(loop_launch((const LoopArgs*)h->loop_args, 1, lds, 1u, 0u, s));
+        G10_TRY(loop_wide_launch((const LoopArgs*)h->loop_args, I[0].w->nch, s));
+      }
+      G10_TRY(loop_launch((const LoopArgs*)h->loop_args, 1, lds, 1u, 0u, s));
+    } else
     for (u32 kind = 0, first = 0; kind < 4; first += n_by_kind[kind], ++kind)
       if (n_by_kind[kind]) G10_TRY(loop_launch((const LoopArgs*)h->loop_args + first, n_by_kind[kind], lds, kind & 1u, kind >> 1, s));
     hipLaunchKernelGGL(k_ctl_collect, dim3(na), dim3(G10_WAVE), 0, s, (const LoopArgs*)h->loop_args, ctl_side);
@@ -980,6 +1017,7 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     ct.retile_cands = x.retile_cands;
     ct.loop_cands_scored = hc.units_scored * UNIT; ct.loop_second_rounds = hc.second_rounds; ct.loop_chunk_jobs = hc.jobs_run;
     ct.loop_area_evals = hc.area_evals; ct.loop_area_refused = hc.area_refused;
+    ct.loop_wide_rounds = hc.wide_rounds;
     ct.batch_prepare_ms = phase_ms[0]; ct.batch_loops_ms = phase_ms[1]; ct.batch_retile_ms = phase_ms[2]; ct.batch_results_ms = phase_ms[3];
   }
   h->n_counters = count;

@@ -43,6 +43,7 @@ struct Ctl {
   // statistics
   u64 units_scored, second_rounds, jobs_run, launches, passes;
   u64 area_evals, area_refused;   // clipped areas computed in the loop; of those, how many came out below the bound
+  u64 wide_rounds;                // scoring rounds left to the scoring kernel
 };
 
 struct Cands {
@@ -269,7 +270,14 @@ struct LoopArgs {
   uint2* rec_ab;              // absent window [a, b] of every migration in doubled coordinates
   g10_dropped* dropped;
   u32 pass_budget;            // the launch ends after this many passes,
-  u64 tick_budget;            // or (if not 0) after this many ticks of the 100 MHz wall clock
+  u64 tick_budget;            // or (if not 0) after this many ticks of the 100 MHz wall clock,
+  u64 pass_stop;              // or (if not 0) once the plan has made this many passes over all its launches
+  // Scoring rounds left to all compute units (ranking by benefit / cost, band reading; else null):
+  // the block of loop_wide_bytes() bytes the loop kernel and the scoring kernel talk through, and
+  // the length of a round's list, in units of 256 candidates, from which it is left to that kernel
+  void* wide;
+  u32 wide_min;
+  u32 wide_last_seq;          // the launch of the loop kernel (counted from 1 over the plan) behind which no scoring kernel is queued
 };
 
 struct Best {
@@ -350,6 +358,7 @@ struct PlanWork {
   const u64 *dur = nullptr, *start = nullptr;
   u64 T = 0;
   u64 *dur_own = nullptr, *start_own = nullptr, *times_scratch = nullptr, *times_stats = nullptr;
+  char* wide = nullptr;        // what the loop kernel and the scoring kernel talk through (loop_wide_bytes())
   g10::Ctl* ctl = nullptr;
   g10_migration* records = nullptr;
   uint2* rec_ab = nullptr;
@@ -389,4 +398,6 @@ void replay_free(PlanWork* w);
 // the loop kernel (g10_loop.hip)
 size_t loop_lds_bytes(u32 nch, u32 nt);                       // dynamic LDS of one workgroup
 int loop_allow_large_lds();                                   // more than 64 KB of LDS for the kernel
+size_t loop_wide_bytes();                                     // device memory a plan's loop and the scoring kernel talk through
+int loop_wide_launch(const g10::LoopArgs* plans, u32 nch, hipStream_t s);   // the scoring kernel for plans[0]
 int loop_launch(const g10::LoopArgs* plans, u32 n_plans, size_t lds, u32 rank, u32 area, hipStream_t s);   // all of one ranking key and benefit reading

@@ -174,6 +174,7 @@ def test_stress_full_size_ratio(g10):
     limit = 4000
     r = h.plan(rank=1, max_iters=limit, **args)
     assert r.status == g10.TRUNCATED and r.n_iterations == limit
+    assert r.loop_wide_rounds > limit // 2         # (the long scoring rounds ran on all compute units)
     n = 100
     p = v.plan(max_iters=n, rank=1, **args)
     assert_plan_equal(r, p, prefix=True)
@@ -197,6 +198,21 @@ def test_stress_full_size_ratio(g10):
     assert hashlib.sha256(r.pressure_after.astype("<u8").tobytes()).hexdigest() == gold["pressure_after_sha256"]
     assert (int(r.status), int(r.n_iterations), int(r.n_migrations), int(r.n_dropped), int(r.n_cand_evals)) == \
            (int(gold["status"]), int(gold["passes"]), int(gold["migrations"]), int(gold["dropped"]), int(gold["cand_evals"]))
+
+
+def test_ratio_key_long_list_against_the_oracle(g10):
+    """Ranking by benefit / cost on a list long enough that the scoring rounds are left to the
+    scoring kernel (the loop kernel ends in the middle of a pass and takes it up in its next
+    launch): a stress trace of a tenth of config 5's size, the first 3000 passes record by record
+    against the oracle, and a second run with a limit that falls between two re-tilings."""
+    w = traces.stress(K=8000, N=80000, seed=0x67100015)
+    h, v, args = run_both(g10, w)
+    for limit in (3000, 333):
+        r = h.plan(rank=1, max_iters=limit, **args)
+        p = v.plan(max_iters=limit, rank=1, **args)
+        assert r.loop_wide_rounds > 0
+        assert_plan_equal(r, p)
+    h.close()
 
 
 def test_stress_full_size_clipped(g10):
