@@ -29,8 +29,8 @@ struct Winner {               // what a commit needs of the winning candidate
 // of tiles to score, ends in the middle of its pass, a scoring kernel takes the list (the tile
 // bounds go into the array of tile bounds in device memory, every workgroup's best candidate
 // into `win`), and the next launch of the loop kernel takes the pass up again with those.
-constexpr u32 WIDE_WG = LB - 1;   // workgroups of the scoring kernel that take part at most: one winner per thread of the loop
-                                  // kernel, whose last thread takes the best of the pass's earlier rounds
+constexpr u32 WIDE_WG = 2 * (LB - 1);   // workgroups of the scoring kernel that take part at most: two winners per thread of the
+                                        // loop kernel, whose last thread takes the best of the pass's earlier rounds
 struct WideCtx {
   u32 pending;                // the loop kernel has left a list and waits for it to be scored
   u32 nwg, done_wgs;          // workgroups of the scoring kernel that take part; that have finished
@@ -826,8 +826,13 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
           wide_exit = true;
           break;
         }
-        if (WIDE && resume == 1) {                // the scoring kernel's winners, one per thread
-          if (tid < wv.ctx->nwg) mine = wv.win[tid];
+        if (WIDE && resume == 1) {                // the scoring kernel's winners, two per thread
+          const u32 nw = wv.ctx->nwg;
+          if (tid < LB - 1 && tid < nw) mine = wv.win[tid];
+          if (tid < LB - 1 && tid + (LB - 1) < nw) {
+            const Winner o = wv.win[tid + (LB - 1)];
+            if ((o.hi | o.lo) != 0 && better_ratio(o.hi, o.lo, o.cost, o.cand, mine.hi, mine.lo, mine.cost, mine.cand)) mine = o;
+          }
           const u32 nu = S->ntl << a.tshift;
           if (tid == 0) S->units += nu;
           pass_units += nu;
@@ -1018,7 +1023,12 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
         // where many candidates are nearly equal (a pass scored thousands) the margin halves; it
         // doubles when a pass ran out of candidates above the floor with little scored
         u32 gs = S->gshift;
-        if (pass_units > 8u && gs < GUESS_SHIFT_MAX) ++gs;
+        if (WIDE && a.wide_min) {
+          // with the scoring kernel a longer list costs little and a second round a pair of launches:
+          // the margin doubles whenever a pass needed one, and narrows only now and then
+          if (rounds > 1u) { if (gs > 2u) --gs; }
+          else if ((S->n_iter & 31u) == 0u && gs < GUESS_SHIFT) ++gs;
+        } else if (pass_units > 8u && gs < GUESS_SHIFT_MAX) ++gs;
         else if (MC) { if ((S->by_floor || rounds > 1u) && pass_units <= 4u && gs > MC_GUESS_SHIFT_MIN) --gs; }
         else if (rounds > 1u && pass_units <= 2u && gs > GUESS_SHIFT) --gs;
         S->gshift = gs;
@@ -1126,14 +1136,12 @@ __global__ __launch_bounds__(UNIT) void k_wide_score(const LoopArgs* __restrict_
   const u32 nwg = wv.ctx->nwg;
   if (!wv.ctx->pending || blockIdx.x >= nwg) return;
   const Timelines tl = a.tl;
-  const u32 nch = tl.nch, nb1 = nch + 1, K = tl.K;
+  const u32 nch = tl.nch, K = tl.K;
   const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
-  u64* base = (u64*)smem;                               // [5][nch + 1]
-  Winner* wwin = (Winner*)(base + (u64)N_ARR * nb1);    // [UNIT / 64]
-  for (u32 i = tid; i < N_ARR * nb1; i += UNIT) base[i] = a.g_base[i];
-  __syncthreads();
+  Winner* wwin = (Winner*)smem;                         // [UNIT / 64]
   const Ctl* ctl = a.ctl;
-  PrefixView pv; pv.px = tl.px; pv.base = base; pv.K = K; pv.nch = nch; pv.shift_ch = tl.shift_ch;
+  PrefixView pv; pv.px = tl.px; pv.K = K; pv.nch = nch; pv.shift_ch = tl.shift_ch;
+  pv.base = a.g_base;                                   // (a few entries per candidate, read where they lie)
   Machine mc; mc.bwo0 = ctl->bw_out[0]; mc.bwo1 = ctl->bw_out[1]; mc.bwi0 = ctl->bw_in[0]; mc.bwi1 = ctl->bw_in[1];
   mc.ivo0 = ctl->inv_out[0]; mc.ivo1 = ctl->inv_out[1]; mc.ivi0 = ctl->inv_in[0]; mc.ivi1 = ctl->inv_in[1];
   Winner mine;
@@ -1184,7 +1192,8 @@ __global__ __launch_bounds__(UNIT) void k_wide_score(const LoopArgs* __restrict_
 size_t loop_wide_bytes() { return WIDE_BYTES; }
 
 int loop_wide_launch(const LoopArgs* plans, u32 nch, hipStream_t s) {
-  const size_t lds = (size_t)N_ARR * (nch + 1) * 8 + (UNIT / 64) * sizeof(Winner);
+  (void)nch;
+  const size_t lds = (UNIT / 64) * sizeof(Winner);
   hipLaunchKernelGGL(k_wide_score, dim3(WIDE_WG), dim3(UNIT), lds, s, plans);
   G10_HIP(hipGetLastError());
   return G10_OK;
