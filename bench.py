@@ -350,6 +350,7 @@ def main():
                                      "us_per_pass": 1e3 * rv.loop_ms / max(int(rv.n_iterations), 1),
                                      "cands_rescored_per_pass": rv.loop_cands_scored / max(int(rv.n_iterations), 1),
                                      "areas_summed": int(rv.loop_area_evals), "areas_below_bound": int(rv.loop_area_refused),
+                                     "rounds_scored_by_k_wide_score": int(rv.loop_wide_rounds),
                                      "first_record_that_differs_from_default": int((~same).argmax()) if not same.all() else k,
                                      "migrations_shared_with_default": common}
         hv.close()

@@ -123,9 +123,10 @@ __global__ __launch_bounds__(G10_BLOCK) void k_check_size(const u64* __restrict_
   if (__any(zero) && lane_id() == 0) atomicOr(&st->zero_size, 1u);
   if (__any(ovf) && lane_id() == 0) atomicOr(&st->size_overflow, 1u);
   if (__any(big) && lane_id() == 0) atomicOr(&st->big_size, 1u);
-  mx = wave_max(mx);
-  // (atomics on one address queue up behind each other: only a wavefront that can still raise the maximum sends one)
-  if (lane_id() == 0 && mx > *(volatile u64*)&st->max_size) atomicMax((unsigned long long*)&st->max_size, (unsigned long long)mx);
+  // (atomics on one address queue up behind each other: one per workgroup, and only where it can still raise the maximum)
+  __shared__ u64 tmp[G10_WAVES + 1];
+  mx = block_max(mx, tmp);
+  if (threadIdx.x == 0 && mx > *(volatile u64*)&st->max_size) atomicMax((unsigned long long*)&st->max_size, (unsigned long long)mx);
 }
 
 // ===========================================================================
@@ -642,7 +643,7 @@ static int vitality_core(g10_plan_s* h, const g10_trace* tr, Pool& tmp, Pool& ke
   // ---- validation (read by the host with the counts, at the one synchronisation below: nothing
   // a kernel does with a zero duration, a zero or huge size or a wrapped sum leaves its arrays) ---
   hipLaunchKernelGGL(k_check_dur, dim3(grid_for(K)), dim3(G10_BLOCK), 0, s, h->dur, K, st);
-  hipLaunchKernelGGL(k_check_size, dim3(grid_for(N, 1024)), dim3(G10_BLOCK), 0, s, h->size, N, st);
+  hipLaunchKernelGGL(k_check_size, dim3(grid_for(N, 512)), dim3(G10_BLOCK), 0, s, h->size, N, st);
   G10_HIP(hipGetLastError());
 
   // ---- slot start times ----------------------------------------------------
