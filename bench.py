@@ -228,6 +228,8 @@ def main():
                      "bytes_per_plan": loop_bytes,
                      "listing_equivalent_GBps": listing_bytes / (loop_ms * 1e-3) / 1e9 if loop_ms > 0 else 0.0,
                      "us_per_algorithm_pass": 1e3 * loop_ms / passes, "kernel_passes": int(r.loop_passes),
+                     "more_commit_rounds_from_the_same_list": int(r.loop_more_rounds),
+                     "us_per_commit_round": 1e3 * loop_ms / max(int(r.loop_passes + r.loop_more_rounds), 1),
                      "migrations_per_kernel_pass": passes / kpasses, "us_per_kernel_pass": 1e3 * loop_ms / kpasses,
                      "retiles": int(r.loop_retiles), "cands_rescored_per_kernel_pass": r.loop_cands_scored / kpasses,
                      "second_rounds": int(r.loop_second_rounds), "chunk_jobs_per_kernel_pass": r.loop_chunk_jobs / kpasses,

@@ -162,9 +162,12 @@ typedef struct {
   uint64_t loop_launches;      /* launches of the loop kernel                          */
   uint64_t loop_passes;        /* ranking passes the kernel made: a pass commits one migration or,
                                   where that is provably what Algorithm 1 would do next, several  */
+  uint64_t loop_more_rounds;   /* further rounds of commits made from the list of a ranking pass
+                                  (its entries scored again) instead of a new ranking pass        */
   uint64_t loop_retiles;       /* times the candidate list was put back into score order */
   uint64_t retile_cands;       /* candidates scored again by those re-orderings        */
-  uint64_t loop_cands_scored;  /* candidates re-scored inside the loop (tiles * 256)   */
+  uint64_t loop_cands_scored;  /* candidates re-scored inside the loop (tiles * 256, and the list
+                                  entries scored again for loop_more_rounds)              */
   uint64_t loop_second_rounds; /* passes that needed a second scoring round            */
   uint64_t loop_chunk_jobs;    /* timeline chunks rewritten slot by slot               */
   uint64_t loop_area_evals;    /* G10_AREA_CLIPPED: clipped areas summed exactly       */

@@ -72,7 +72,7 @@ class _Result(C.Structure):
 
 class _Counters(C.Structure):
     _fields_ = [("score_full_ms", C.c_double), ("score_full_cands", C.c_uint64),
-                ("loop_ms", C.c_double), ("loop_launches", C.c_uint64), ("loop_passes", C.c_uint64),
+                ("loop_ms", C.c_double), ("loop_launches", C.c_uint64), ("loop_passes", C.c_uint64), ("loop_more_rounds", C.c_uint64),
                 ("loop_retiles", C.c_uint64), ("retile_cands", C.c_uint64), ("loop_cands_scored", C.c_uint64),
                 ("loop_second_rounds", C.c_uint64), ("loop_chunk_jobs", C.c_uint64),
                 ("loop_area_evals", C.c_uint64), ("loop_area_refused", C.c_uint64), ("loop_wide_rounds", C.c_uint64),

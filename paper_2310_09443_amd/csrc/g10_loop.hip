@@ -72,6 +72,8 @@ struct Shared {               // small per-pass state of the loop workgroup
                               // host-capacity test needs the exact per-slot maximum
   u32 by_floor, touched;      // the selection ended because the next candidate did not clear the floor; timelines (a bit
                               // per array of level 1) whose chunk totals change in this pass
+  u32 Fkeep, more;            // the floor of the pass; another round of commits follows from the same list
+  u64 more_rounds, list_rescored;   // such rounds made; list entries scored again for them (statistics)
   u32 sel[MAXM];              // list entries picked, in order
   u64 hq;                     // host-capacity query: maximum over the period
   u64 acc[3];                 // clipped area being summed: bits 0..31, 32..63 and 64.. of the terms, added apart
@@ -204,7 +206,7 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
   for (u32 i = tid; i < ns; i += LB) smark[i] = 0;
   if (tid == 0) {
     S->n_iter = ctl->n_iter; S->n_mig = ctl->n_mig; S->n_drop = ctl->n_drop; S->n_evals = ctl->n_evals;
-    S->units = 0; S->second = 0; S->jobs = 0; S->evals = 0; S->refused = 0;
+    S->units = 0; S->second = 0; S->jobs = 0; S->evals = 0; S->refused = 0; S->more_rounds = 0; S->more = 0; S->list_rescored = 0;
     S->thr_key = ctl->thr_key; S->status = ctl->status; S->done = ctl->done;
     S->gshift = ctl->gshift ? ctl->gshift : GUESS_SHIFT;
     S->nl = 0; S->restL = NONE32; S->stale_hot = 0;
@@ -737,16 +739,16 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
 
   __syncthreads();
   // ---- passes ------------------------------------------------------------------------
-  u32 passes = 0;
+  u32 passes = 0, used = 0;                          // ranking passes of this launch; with the further rounds of commits: what the budget counts
   bool wide_exit = false;
   while (true) {
     if (!resume) {                                   // (a pass taken up again has passed these tests)
       if (S->done) break;
       if (base[(u64)A_OT * nb1 + nch] == 0) { if (tid == 0) { S->done = 1; S->status = G10_FITS; } break; }
       if (max_iter && S->n_iter >= max_iter) { if (tid == 0) { S->done = 1; S->status = G10_TRUNCATED; } break; }
-      if (passes >= a.pass_budget || S->stop || (a.pass_stop && passes_before + passes >= a.pass_stop)) break;
+      if (used >= a.pass_budget || S->stop || (a.pass_stop && passes_before + passes >= a.pass_stop)) break;
       if (WIDE && S->no_wide) break;               // (the last launch of a round only ends the pass left open)
-      ++passes;
+      ++passes; ++used;
     }
     mine.hi = 0; mine.lo = 0; mine.cost = 1; mine.cand = NONE32; mine.exact = 0; mine.kU = 0; mine.kr = 0;
     floor2 = 0;
@@ -877,57 +879,100 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
     // counts with its bound: the floor F.
     //
     // Step 1 (the last wavefront, a list entry per lane): the candidates in the order of their
-    // benefit, as far as (2) and the transfer windows allow.
+    // benefit, as far as (2) and the transfer windows allow.  Where a round of commits ends with
+    // entries still on the list that might clear the floor, the steps are taken again from here
+    // (cround > 0) instead of from a new ranking.
+    for (u32 cround = 0;; ++cround) {
     if (MC && wave == LW - 1 && S->nlist > 1u && K < (1u << 30)) {
-      const Winner& W1 = S->mem[0];
       const u32 nl_ = S->nlist, n = nl_ < LIST_MAX ? nl_ : LIST_MAX;
       const bool have = lane < n;
       Winner e;
       if (have) e = S->list[lane];
-      else { e.hi = 0; e.lo = 0; e.cand = NONE32; e.dest = 1; e.kr = 0; e.L1 = 0; e.R = 0; e.a = 1; e.b = 0; e.s = 0; }
-      bool picked = have && e.cand == W1.cand;         // a migration of this pass already
-      u32 kB = (have && !picked) ? upkey(e.hi, e.lo) : 0u;       // (0: cannot be picked)
-      const u32 eE0 = e.L1, eE1 = e.a - 1, eW0 = e.b + 1, eW1 = e.R - 1, ed = e.dest;
-      const u32 kr = ed == 0u ? e.kr : 0u;
-      bool ov = false;                                 // a transfer window meets one of a committed migration on the same channel
-      auto meet = [&](u32 wd, u32 wL1, u32 wa, u32 wb, u32 wR) {
-        const bool hit = cyc_overlap32(eE0, eE1, wL1, wa - 1, K) || cyc_overlap32(eW0, eW1, wb + 1, wR - 1, K);
-        ov = ov || (hit && ed == wd && !picked);
-      };
-      meet(W1.dest, W1.L1, W1.a, W1.b, W1.R);
-      const u32 F = rest_final > S->F2 ? rest_final : S->F2;
-      u32 mmax = MAXM;
-      if (max_iter && max_iter - S->n_iter + 1 < mmax) mmax = (u32)(max_iter - S->n_iter + 1);   // (n_iter counts this pass already)
-      u32 m = 1, by_floor = 0;
-      while (m < mmax) {
-        const u32 kmax = wave_max(kB);
-        if (kmax <= F) { by_floor = 1; break; }        // (also when nothing is left)
-        u64 mk = __ballot(kB == kmax);
-        if (mk & (mk - 1)) {                           // equal keys: high word, low word, lowest index
-          const bool in1 = kB == kmax;
-          const u64 hmx = wave_max(in1 ? e.hi : 0ull);
-          const bool in2 = in1 && e.hi == hmx;
-          const u64 lmx = wave_max(in2 ? e.lo : 0ull);
-          const bool in3 = in2 && e.lo == lmx;
-          const u32 cmin = wave_min(in3 ? e.cand : NONE32);
-          mk = __ballot(in3 && e.cand == cmin);
+      else { e.hi = 0; e.lo = 0; e.cand = NONE32; e.dest = 1; e.kr = 0; e.L1 = 0; e.R = 0; e.a = 1; e.b = 0; e.s = 0; e.pos = 0; }
+      u32 F = rest_final > S->F2 ? rest_final : S->F2;
+      u32 allowed = MAXM;                              // passes of Algorithm 1 this round may stand for
+      bool picked;
+      if (cround == 0u) {
+        picked = have && e.cand == S->mem[0].cand;     // a migration of this pass already
+        if (max_iter && max_iter - S->n_iter + 1 < allowed) allowed = (u32)(max_iter - S->n_iter + 1);   // (n_iter counts this pass already)
+        if (lane == 0) S->Fkeep = F;
+      } else {
+        // Another round from the same list: its entries are scored again against the timelines as
+        // the earlier rounds left them (a committed candidate has no window any more and scores
+        // nothing), and the best of them wins the next pass of Algorithm 1 if its key clears the
+        // floor - every candidate not on the list is still bounded by it, since bounds only fall.
+        F = S->Fkeep;
+        if (max_iter && max_iter - S->n_iter < allowed) allowed = (u32)(max_iter - S->n_iter);
+        if (lane == 0) { S->njobs = 0; S->cut = MAXM; S->need_exact = 0; S->touched = 0; S->ot_changed = 0; S->hq = 0; S->list_rescored += n; }
+        PrefixView pv; pv.px = tl.px; pv.base = base; pv.K = K; pv.nch = nch; pv.shift_ch = tl.shift_ch;
+        Machine mc; mc.bwo0 = bwo0; mc.bwo1 = bwo1; mc.bwi0 = bwi0; mc.bwi1 = bwi1;
+        mc.ivo0 = ivo0; mc.ivo1 = ivo1; mc.ivi0 = ivi0; mc.ivi1 = ivi1;
+        if (have) {
+          const uint4 A = a.cd.A[e.pos], B = a.cd.B[e.pos];
+          const Score r = score_candidate(pv, mc, A, B);
+          const bool ok_any = r.ok0 || r.ok1;
+          const u32 d = r.ok0 ? 0u : 1u;
+          const bool one = gt128(r.h1, r.l1, r.h0, r.l0);
+          const u32 kc = upkey(one ? r.h1 : r.h0, one ? r.l1 : r.l0);
+          e.hi = ok_any ? (d ? r.h1 : r.h0) : 0ull; e.lo = ok_any ? (d ? r.l1 : r.l0) : 0ull;
+          e.dest = d; e.a = d ? B.x : A.z; e.b = d ? B.y : A.w;
+          e.fo_base = r.fo_L; e.fi_end = r.fi_R; e.kU = kc; e.kr = (r.ok0 && r.ok1) ? kc : 0u;
+          S->list[lane] = e;
         }
-        const u32 bl = (u32)__builtin_ctzll(mk);
-        const u64 ovm = __ballot(ov);
-        if ((ovm >> bl) & 1ull) break;                 // its own windows are not what they were
-        if (ovm && wave_max(ov ? kr : 0u) >= kmax) break;     // a candidate at risk might rise above it
-        if (lane == 0) S->sel[m] = bl;
-        if (lane == bl) { kB = 0u; picked = true; ov = false; }
-        meet((u32)__builtin_amdgcn_readlane((int)ed, (int)bl), (u32)__builtin_amdgcn_readlane((int)e.L1, (int)bl),
-             (u32)__builtin_amdgcn_readlane((int)e.a, (int)bl), (u32)__builtin_amdgcn_readlane((int)e.b, (int)bl),
-             (u32)__builtin_amdgcn_readlane((int)e.R, (int)bl));
-        ++m;
+        const u32 b1 = wave_best_lane(e.hi, e.lo, e.cand);
+        const u32 k1 = b1 == NONE32 ? 0u : upkey(read_lane64(e.hi, b1), read_lane64(e.lo, b1));
+        if (allowed == 0u || k1 <= F) allowed = 0u;    // nothing on the list clears the floor: the pass is over
+        else if (lane == b1) {
+          e.tau_o = ceil_div_x1000(e.s, e.dest ? bwo1 : bwo0, e.dest ? ivo1 : ivo0);
+          e.tau_i = ceil_div_x1000(e.s, e.dest ? bwi1 : bwi0, e.dest ? ivi1 : ivi0);
+          S->mem[0] = e;
+        }
+        picked = allowed != 0u && lane == b1;
       }
-      if (lane >= 1 && lane < m) {                     // the picked entries become migrations 1 .. m - 1
-        Winner x = S->list[S->sel[lane]];
-        x.tau_o = ceil_div_x1000(x.s, x.dest ? bwo1 : bwo0, x.dest ? ivo1 : ivo0);
-        x.tau_i = ceil_div_x1000(x.s, x.dest ? bwi1 : bwi0, x.dest ? ivi1 : ivi0);
-        S->mem[lane] = x;
+      u32 m = 0, by_floor = 0;
+      if (allowed) {
+        const Winner& W1 = S->mem[0];
+        u32 kB = (have && !picked) ? upkey(e.hi, e.lo) : 0u;       // (0: cannot be picked)
+        const u32 eE0 = e.L1, eE1 = e.a - 1, eW0 = e.b + 1, eW1 = e.R - 1, ed = e.dest;
+        const u32 kr = ed == 0u ? e.kr : 0u;
+        bool ov = false;                               // a transfer window meets one of a committed migration on the same channel
+        auto meet = [&](u32 wd, u32 wL1, u32 wa, u32 wb, u32 wR) {
+          const bool hit = cyc_overlap32(eE0, eE1, wL1, wa - 1, K) || cyc_overlap32(eW0, eW1, wb + 1, wR - 1, K);
+          ov = ov || (hit && ed == wd && !picked);
+        };
+        meet(W1.dest, W1.L1, W1.a, W1.b, W1.R);
+        const u32 mmax = allowed;
+        m = 1;
+        while (m < mmax) {
+          const u32 kmax = wave_max(kB);
+          if (kmax <= F) { by_floor = 1; break; }      // (also when nothing is left)
+          u64 mk = __ballot(kB == kmax);
+          if (mk & (mk - 1)) {                         // equal keys: high word, low word, lowest index
+            const bool in1 = kB == kmax;
+            const u64 hmx = wave_max(in1 ? e.hi : 0ull);
+            const bool in2 = in1 && e.hi == hmx;
+            const u64 lmx = wave_max(in2 ? e.lo : 0ull);
+            const bool in3 = in2 && e.lo == lmx;
+            const u32 cmin = wave_min(in3 ? e.cand : NONE32);
+            mk = __ballot(in3 && e.cand == cmin);
+          }
+          const u32 bl = (u32)__builtin_ctzll(mk);
+          const u64 ovm = __ballot(ov);
+          if ((ovm >> bl) & 1ull) break;               // its own windows are not what they were
+          if (ovm && wave_max(ov ? kr : 0u) >= kmax) break;   // a candidate at risk might rise above it
+          if (lane == 0) S->sel[m] = bl;
+          if (lane == bl) { kB = 0u; picked = true; ov = false; }
+          meet((u32)__builtin_amdgcn_readlane((int)ed, (int)bl), (u32)__builtin_amdgcn_readlane((int)e.L1, (int)bl),
+               (u32)__builtin_amdgcn_readlane((int)e.a, (int)bl), (u32)__builtin_amdgcn_readlane((int)e.b, (int)bl),
+               (u32)__builtin_amdgcn_readlane((int)e.R, (int)bl));
+          ++m;
+        }
+        if (lane >= 1 && lane < m) {                   // the picked entries become migrations 1 .. m - 1
+          Winner x = S->list[S->sel[lane]];
+          x.tau_o = ceil_div_x1000(x.s, x.dest ? bwo1 : bwo0, x.dest ? ivo1 : ivo0);
+          x.tau_i = ceil_div_x1000(x.s, x.dest ? bwi1 : bwi0, x.dest ? ivi1 : ivi0);
+          S->mem[lane] = x;
+        }
       }
       if (lane == 0) { S->m0 = m; S->by_floor = by_floor; }
     } else if (MC && wave == LW - 1 && lane == 0) S->by_floor = 1;     // (nothing else on the list)
@@ -940,6 +985,7 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
     // is committed: alone, and with the exact host-capacity test.
     enum { F_E = 1, F_W = 2, F_ACUT = 4, F_AALL = 8, F_PCUT = 16, F_PALL = 32 };
     const u32 m0 = S->m0;
+    if (MC && m0 == 0u) break;                           // (a later round found nothing above the floor)
     u64 fl[MAXM / 8] = {};
     if (tid < ((nch + 63u) & ~63u)) {
       u32 cut = MAXM;
@@ -974,6 +1020,7 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
     __syncthreads();
     u32 m = m0 < S->cut ? m0 : S->cut;
     bool room = true;
+    if (MC && cround && S->need_exact) break;            // (the exact host-memory test is left to the next ranking pass)
     if (S->need_exact) {                                 // the winner alone; host memory slot by slot where its period cuts a chunk
       m = 1;
       const u64 s = S->mem[0].s;
@@ -1023,7 +1070,9 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
         // where many candidates are nearly equal (a pass scored thousands) the margin halves; it
         // doubles when a pass ran out of candidates above the floor with little scored
         u32 gs = S->gshift;
-        if (WIDE && a.wide_min) {
+        if (cround) {
+          // (the margin adapts once per ranking pass)
+        } else if (WIDE && a.wide_min) {
           // with the scoring kernel a longer list costs little and a second round a pair of launches:
           // the margin doubles whenever a pass needed one, and narrows only now and then
           if (rounds > 1u) { if (gs > 2u) --gs; }
@@ -1038,15 +1087,22 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
         const u64 nlo = glo - dlo;
         ghi = ghi - dhi - (glo < dlo ? 1ull : 0ull);
         S->thr_key = RATIO ? rkey_dn(ratio_approx(Z.hi, Z.lo, Z.cost) * (1.0 - 1.0 / (double)(1u << gs))) : upkey(ghi, nlo);
-        if (!room) S->n_drop = nd + 1;
+        if (!room) { S->n_drop = nd + 1; S->more = 0; }
         else {
-          const u64 x = m - 1;                            // the passes of Algorithm 1 this one stands for beyond the first
+          // the passes of Algorithm 1 this round stands for beyond the one the ranking pass counted
+          // at its top (a later round: all of its own), each with one live candidate fewer to rank
+          const u64 x = cround ? m : m - 1, live = C - nm - nd;
           S->n_mig = nm + m; S->n_iter += x;
-          S->n_evals += x * (C - nm - nd) - x * (x + 1) / 2;
+          S->n_evals += cround ? x * live - x * (x - 1) / 2 : x * live - x * (x + 1) / 2;
+          // another round of commits from the same list: unless the picking ran out of entries above
+          // the floor and every one it picked was committed
+          const bool more = MC && S->nlist > 1u && K < (1u << 30) && (!S->by_floor || m < m0) && !(max_iter && S->n_iter >= max_iter);
+          S->more = more ? 1u : 0u;
+          if (cround) S->more_rounds += 1;
         }
       }
     }
-    if (!room) { __syncthreads(); continue; }
+    if (!room) { __syncthreads(); break; }
     if (tid < nch) {
       const u32 c = tid;
       u64 lzP = 0, lzH = 0;
@@ -1106,6 +1162,9 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
       }
       __syncthreads();
     }
+    if (!MC || !S->more) break;
+    ++used;
+    }                                                    // (rounds of commits of one ranking pass)
   }
   __syncthreads();
 
@@ -1122,6 +1181,7 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
     ctl->units_scored += S->units; ctl->second_rounds += S->second; ctl->jobs_run += S->jobs; ctl->launches += 1;
     ctl->passes += passes;
     ctl->area_evals += S->evals; ctl->area_refused += S->refused;
+    ctl->more_rounds += S->more_rounds; ctl->list_rescored += S->list_rescored;
   }
 }
 

@@ -960,8 +960,9 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
         continue;
       }
       ++n_active;
-      if (x.n > RETILE_MIN_CANDS && x.hc.passes - x.seen_passes >= retile_every) {
-        x.seen_passes = x.hc.passes;
+      // (the cadence counts the rounds of commits: ranking passes and the further rounds made from their lists)
+      if (x.n > RETILE_MIN_CANDS && x.hc.passes + x.hc.more_rounds - x.seen_passes >= retile_every) {
+        x.seen_passes = x.hc.passes + x.hc.more_rounds;
         if (x.counted && x.hc.n_live < x.n) x.n = x.hc.n_live;   // live candidates come first in the list
         x.retile_cands += x.n;
         if (count == 1) G10_TRY(retile(x, false, s));
@@ -1015,9 +1016,10 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     ct.score_full_ms = full_ms; ct.score_full_cands = x.n_valid;
     ct.loop_ms = loop_ms; ct.loop_launches = hc.launches; ct.loop_passes = hc.passes; ct.loop_retiles = x.retiles;
     ct.retile_cands = x.retile_cands;
-    ct.loop_cands_scored = hc.units_scored * UNIT; ct.loop_second_rounds = hc.second_rounds; ct.loop_chunk_jobs = hc.jobs_run;
+    ct.loop_cands_scored = hc.units_scored * UNIT + hc.list_rescored; ct.loop_second_rounds = hc.second_rounds; ct.loop_chunk_jobs = hc.jobs_run;
     ct.loop_area_evals = hc.area_evals; ct.loop_area_refused = hc.area_refused;
     ct.loop_wide_rounds = hc.wide_rounds;
+    ct.loop_more_rounds = hc.more_rounds;
     ct.batch_prepare_ms = phase_ms[0]; ct.batch_loops_ms = phase_ms[1]; ct.batch_retile_ms = phase_ms[2]; ct.batch_results_ms = phase_ms[3];
   }
   h->n_counters = count;

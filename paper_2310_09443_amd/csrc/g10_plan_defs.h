@@ -44,6 +44,8 @@ struct Ctl {
   u64 units_scored, second_rounds, jobs_run, launches, passes;
   u64 area_evals, area_refused;   // clipped areas computed in the loop; of those, how many came out below the bound
   u64 wide_rounds;                // scoring rounds left to the scoring kernel
+  u64 more_rounds;                // rounds of commits after the first of their ranking pass
+  u64 list_rescored;              // list entries scored again for those rounds
 };
 
 struct Cands {

@@ -464,8 +464,6 @@ inline u32 bits_for(u64 max_value) {            // bits needed to hold values 0.
 struct Pool {
   char* base = nullptr;
   size_t off = 0, cap = 0;
-  bool owned = false;                             // released when this object goes away (the temporaries)
-  ~Pool() { if (owned) mem_dev_free(base); }
   static size_t need(u64 elems, size_t size) { return (((elems ? elems : 1) * size) + 255) & ~(size_t)255; }
   int reserve(size_t bytes) {
     void* q = nullptr;
@@ -790,7 +788,7 @@ extern "C" int g10_vitality_static(const g10_trace* tr, void* hip_stream, const 
   h.device = dev;
   h.stream = (hipStream_t)hip_stream;
   h.K = tr->K; h.N = tr->N; h.P = tr->P; h.flags = tr->flags;
-  Pool tmp, keep;                                 // both inside the array; neither owns it
+  Pool tmp, keep;                                 // both inside the array
   tmp.base = (char*)mem; tmp.cap = need_tmp;
   keep.base = (char*)mem + need_tmp; keep.cap = need_keep;
   hipStream_t s = h.stream;

@@ -34,7 +34,7 @@ def test_struct_layouts_match_the_header():
     assert ctypes.sizeof(binding._Params) == 72
     assert ctypes.sizeof(binding._Stats) == 32
     assert ctypes.sizeof(binding._Result) == 8 + 8 * 8 + 3 * 8 + 8
-    assert ctypes.sizeof(binding._Counters) == 17 * 8
+    assert ctypes.sizeof(binding._Counters) == 18 * 8
     assert ctypes.sizeof(binding._VitalityBuffers) == 7 * 8
     assert ctypes.sizeof(binding._PrefetchResult) == 4 * 8 + 4 * 8 + 8
     assert ctypes.sizeof(binding._ReplayResult) == 4 * 8 + 6 * 8 + 3 * 8
