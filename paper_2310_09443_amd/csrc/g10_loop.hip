@@ -998,8 +998,9 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
           const u32 mL1 = M.L1, mR = M.R, ma = M.a, mb = M.b, md = M.dest;
           const u64 ms = M.s;
           u32 len = 0;
-          const u32 cE = cover(tid, CH, K, mL1, ma - 1, len), cW = cover(tid, CH, K, mb + 1, mR - 1, len), cA = cover(tid, CH, K, ma, mb, len);
-          const u32 cP = cE + cA + cW;
+          const u32 cP = cover(tid, CH, K, mL1, mR - 1, len);       // the period: eviction window, absent window, prefetch window
+          if (!cP) continue;                                        // (most migrations do not touch most chunks)
+          const u32 cE = cover(tid, CH, K, mL1, ma - 1, len), cA = cover(tid, CH, K, ma, mb, len), cW = cP - cE - cA;
           u32 f = (cE ? F_E : 0u) | (cW ? F_W : 0u) | (cA == len ? F_AALL : cA ? F_ACUT : 0u);
           if (cA) {
             runP += ms;
