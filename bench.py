@@ -29,6 +29,30 @@ BYTES_PER_CAND_MOVED = 20      # what k_score_full itself streams per candidate:
                                # its gathers (two 8-byte words per window) hit a table that stays in L2
 
 
+# HBM traffic of the loop kernel on config 5 from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, scaled by what the
+# same counters read for a 256 MiB copy): profiles/loop_stress_hbm_counters.md has the commands and the sums.  The
+# figures hold for the kernel they were taken on: reported only while the kernel's sources hash to what they did then.
+LOOP_TRAFFIC = {"sha256": {"g10_loop.hip": "d238a32d251669219b9ab3f03de13d8d9aca2d482d726a7b508ea7a7afbc0978",
+                           "g10_plan_defs.h": "b6d87b0b9979a35ed8dcd7288be0c97e0dbfe86f23e6dfd14b3d60b4e51cbea8"},
+                "workload": "config 5", "fetch_bytes_per_plan": 71.4e6, "write_bytes_per_plan": 93.9e6, "launches_per_plan": 11}
+
+
+def loop_traffic_per_launch(config):
+    """Bytes per launch of k_loop by the stored counters, or None where they do not apply (another workload, or the
+    kernel has changed since they were taken)."""
+    import hashlib
+    if config != 5:
+        return None
+    for name, want in LOOP_TRAFFIC["sha256"].items():
+        try:
+            got = hashlib.sha256(open(os.path.join(ROOT, "paper_2310_09443_amd", "csrc", name), "rb").read()).hexdigest()
+        except OSError:
+            return None
+        if got != want:
+            return None
+    return (LOOP_TRAFFIC["fetch_bytes_per_plan"] + LOOP_TRAFFIC["write_bytes_per_plan"]) / LOOP_TRAFFIC["launches_per_plan"]
+
+
 def cpu_model():
     try:
         for line in open("/proc/cpuinfo"):
@@ -223,7 +247,11 @@ def main():
                    "dropped": int(r.n_dropped), "status": int(r.status), "cap_frac": w.cap_frac,
                    "bw_out_Bpus": list(w.bw_out_Bpus), "bw_in_Bpus": list(w.bw_in_Bpus)},
         "roofline": {"bound": "hbm", "kernel": "k_loop", "achieved": loop_gbps, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": loop_gbps / HBM_PEAK_GBS, "traffic": None, "traffic_source": "none (no counter run inside bench.py)",
+                     "frac": loop_gbps / HBM_PEAK_GBS, "traffic": loop_traffic_per_launch(a.config),
+                     "traffic_unit": "bytes per launch",
+                     "traffic_source": "stored: two rocprofv3 --pmc runs on this kernel (profiles/loop_stress_hbm_counters.md); "
+                                       "null when the kernel's sources have changed since, or for another workload",
+                     "achieved_bytes_per_launch": loop_bytes / max(int(r.loop_launches), 1),
                      "ms": loop_ms, "share_of_step": loop_ms / (dt_s * 1e3), "launches": int(r.loop_launches),
                      "bytes_per_plan": loop_bytes,
                      "listing_equivalent_GBps": listing_bytes / (loop_ms * 1e-3) / 1e9 if loop_ms > 0 else 0.0,
