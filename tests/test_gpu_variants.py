@@ -220,7 +220,8 @@ def test_stress_full_size_clipped(g10):
     per pass here (it sums every candidate's window slot by slot), so the plan is judged by the
     independent checker: every record's area from the definition in the state before its commit,
     windows, policy and channel rules, and the arg-max property on sampled passes (the checker
-    looks at candidates in the order of their band, which bounds the area)."""
+    looks at candidates in the order of their band, which bounds the area); its first three
+    records also against the oracle's (stored digests)."""
     w = traces.config(5)
     tr = w.trace
     h, v, args = run_both(g10, w)
@@ -235,6 +236,16 @@ def test_stress_full_size_clipped(g10):
     assert base.records.tobytes() != r.records.tobytes()       # the reading matters on this trace
     assert h.plan(area=1, **args).records.tobytes() == r.records.tobytes()
     h.close()
+    # the first passes against the oracle's own records (stored as digests: tests/golden/make_config5_digest.py clipped)
+    import os
+    import sys
+    sys.path.insert(0, os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden"))
+    import make_config5_digest as gd
+    gold = dict(line.split() for line in open(os.path.join(gd.HERE, "config5_clipped_digest.txt")) if not line.startswith("#"))
+    if gd.trace_digest(tr) != gold["trace_sha256"]:
+        pytest.skip("this machine's numpy generates a different stress trace than the stored digests were made from")
+    n = int(gold["migrations"])
+    assert n == gd.CLIPPED_PASSES and gd.records_digest(r.records[:n]) == gold["records_sha256"]
 
 
 @pytest.mark.parametrize("seed", range(12))
