@@ -271,3 +271,29 @@ def test_huge_values(g10, seed):
             assert (y.iter_ns, y.planned_ns, y.stall_ns, y.n_stalled) == (yo.iter_ns, yo.planned_ns, yo.stall_ns, yo.n_stalled)
             assert (y.late == yo.late).all() and y.bytes == yo.bytes
     h.close()
+
+
+@pytest.mark.parametrize("rank", [0, 1])
+def test_random_stress_traces_and_machines(g10, rank):
+    """Stress traces of random size with random capacities and bandwidths, whole plans (ranking by
+    benefit) or their first passes (ranking by benefit / cost, lists long enough for the scoring
+    kernel among them), record by record against the oracle."""
+    rng = np.random.default_rng(5150 + rank)
+    wide = 0
+    for _ in range(8 if rank == 0 else 5):
+        K = int(rng.integers(300, 6000))
+        N = int(rng.integers(2000, 60000)) if rank == 0 else int(rng.integers(55000, 90000))
+        w = traces.stress(K=K, N=N, seed=int(rng.integers(1, 1 << 30)))
+        v = O.Vitality(w.trace, O.PREFIX)
+        h = g10.g10_vitality(g10.DeviceTrace(w.trace))
+        bo = (int(rng.integers(1000, 40000)), int(rng.integers(1000, 80000)))
+        bi = (int(rng.integers(1000, 40000)), int(rng.integers(1000, 80000)))
+        args = dict(gpu_cap=int(v.peak * float(rng.uniform(0.15, 0.95))), host_cap=int(v.peak * float(rng.choice([0.05, 0.25, 1.0]))),
+                    bw_out=bo, bw_in=bi)
+        lim = 0 if rank == 0 else int(rng.integers(200, 1200))
+        p = v.plan(max_iters=lim if lim else 2 ** 64 - 1, rank=rank, **args)
+        r = h.plan(max_iters=lim, rank=rank, **args)
+        assert_plan_equal(r, p)
+        wide += int(r.loop_wide_rounds > 0)
+        h.close()
+    assert rank == 0 or wide > 0
