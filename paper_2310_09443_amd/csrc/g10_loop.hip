@@ -173,7 +173,9 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
   Shared* S = (Shared*)(jobs + 8 * nch + 8);
   u32* keys = (u32*)(S + 1);                            // [nt]  bound of every tile
   u32* skeys = keys + nt;                               // [ns]  largest bound of every group of 64 tiles
-  unsigned short* tlist = (unsigned short*)(skeys + ns);   // [nt]  the hot list
+  u32* hmat = skeys + ns;                               // [nch] host occupancy: migrations (by index) already added to the chunk's slots
+  u32* hpend = hmat + nch;                              // [nch] ... and whether a later one that cuts the chunk is still missing
+  unsigned short* tlist = (unsigned short*)(hpend + nch);  // [nt]  the hot list
   unsigned short* alist = tlist + nt;                            // [nt]  tiles scored in the current round
 
   const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
@@ -201,7 +203,7 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
 
   // ---- state in ----------------------------------------------------------------------
   for (u32 i = tid; i < N_ARR * nch; i += LB) tot[i] = a.g_tot[i];
-  for (u32 i = tid; i < nch; i += LB) { lazyP[i] = a.g_lazyP[i]; minOver[i] = a.g_minOver[i]; lazyH[i] = a.g_lazyH[i]; hmax[i] = a.g_hmax[i]; }
+  for (u32 i = tid; i < nch; i += LB) { lazyP[i] = a.g_lazyP[i]; minOver[i] = a.g_minOver[i]; lazyH[i] = a.g_lazyH[i]; hmax[i] = a.g_hmax[i]; hmat[i] = a.g_hmat[i]; hpend[i] = a.g_hpend[i]; }
   for (u32 i = tid; i < nt; i += LB) keys[i] = a.g_keys[i];
   for (u32 i = tid; i < ns; i += LB) smark[i] = 0;
   if (tid == 0) {
@@ -456,8 +458,8 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
   // ---- chunk jobs: one wavefront rewrites one chunk of one timeline, for all migrations of the
   // pass at once.  A job word: chunk | kind << 16 | set A << 24 | set B << 40, the sets being
   // bits over the pass's migrations: for a transfer-window job, A = the migrations of that
-  // destination whose window meets the chunk; for a pressure or host job, A = those whose range
-  // cuts the chunk, B = those that cover it whole -------------------------------------------
+  // destination whose window meets the chunk; for a pressure job, A = those whose absent window
+  // cuts the chunk, B = those that cover it whole.  (Host occupancy has no such job: see J_HQ.) --
   auto run_jobs = [&]() {
     const u32 nj = S->njobs;
     for (u32 jb = wave; jb < nj; jb += LW) {
@@ -622,50 +624,59 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
           atomicAdd((unsigned long long*)&S->acc[1], (unsigned long long)p1);
           atomicAdd((unsigned long long*)&S->acc[2], (unsigned long long)p2);
         }
-      } else if (type == J_H) {
-        // host bytes of the chunk's slots: the host migrations whose period cuts the chunk are
-        // added slot by slot, the ones that cover it whole go into the chunk's lazy add
-        const u64 lz0 = lazyH[c];
-        u64 lz_full = 0;
-        const u32 part = ma_;
-        for (u32 pb = mb_; pb; pb &= pb - 1) lz_full += S->mem[__builtin_ctz(pb)].s;
-        const u64 lz = lz0 + lz_full;
-        u64 m_all = 0;
+      } else {
+        // J_HQ: the largest host occupancy over the winner's period inside the chunk.  The slots'
+        // host bytes are kept up to date on demand only: a migration to host that covers a chunk
+        // whole goes into the chunk's lazy add when it is committed, one that cuts it is only
+        // counted into the chunk's bound then (hmax, hpend); here the migrations committed since
+        // the chunk was last brought up to date (hmat) are looked through, 64 at a time, and those
+        // that cut the chunk are added to its slots, after which the bound is exact again.
+        const u32 L1 = S->mem[0].L1, R = S->mem[0].R;
+        const u64 lz = lazyH[c];
+        const bool bring = hpend[c] != 0u;
+        const u32 from = hmat[c], to = (u32)S->n_mig;
+        u64 m_cov = 0, m_all = 0;
         for (u32 st = 0; st < tl.spt; ++st) {
           const u32 j0 = s0 + st * 256u + lane * 4u;
+          u64 h[4];
+#pragma unroll
+          for (u32 i = 0; i < 4; ++i) h[i] = j0 + i < K ? tl.H[j0 + i] : 0ull;
+          if (bring) {
+            for (u32 r0 = from; r0 < to; r0 += 64u) {
+              const u32 r = r0 + lane;
+              const uint4 q = r < to ? a.rec_h[r] : make_uint4(0u, 1u, 0u, 0u);
+              const u64 qs = ((u64)q.w << 32) | q.z;
+              u32 len = 0;
+              const u32 cv = qs ? cover(c, CH, K, q.x, q.y - 1, len) : 0u;
+              u64 rel = __ballot(qs != 0ull && cv != 0u && cv != len);
+              while (rel) {
+                const u32 l = (u32)__builtin_ctzll(rel);
+                rel &= rel - 1;
+                const u32 x = (u32)__builtin_amdgcn_readlane((int)q.x, (int)l), y = (u32)__builtin_amdgcn_readlane((int)q.y, (int)l);
+                const u64 sz = read_lane64(qs, l);
+#pragma unroll
+                for (u32 i = 0; i < 4; ++i)
+                  if (j0 + i < K && in_doubled(j0 + i, K, x, y - 1) != NONE32) h[i] += sz;
+              }
+            }
+#pragma unroll
+            for (u32 i = 0; i < 4; ++i) if (j0 + i < K) tl.H[j0 + i] = h[i];
+          }
 #pragma unroll
           for (u32 i = 0; i < 4; ++i) {
             const u32 j = j0 + i;
             if (j < K) {
-              u64 h = tl.H[j], add = 0;
-              for (u32 pb = part; pb; pb &= pb - 1) {
-                const Winner& W = S->mem[__builtin_ctz(pb)];
-                if (in_doubled(j, K, W.L1, W.R - 1) != NONE32) add += W.s;
-              }
-              if (add) { h += add; tl.H[j] = h; }
-              const u64 act = h + lz;
+              const u64 act = h[i] + lz;
               m_all = act > m_all ? act : m_all;
-            }
-          }
-        }
-        m_all = wave_max(m_all);
-        if (lane == 0) { hmax[c] = m_all; lazyH[c] = lz; }
-      } else {                                     // J_HQ: the largest host occupancy over the winner's period inside the chunk
-        const u32 L1 = S->mem[0].L1, R = S->mem[0].R;
-        const u64 lz = lazyH[c];
-        u64 m_cov = 0;
-        for (u32 st = 0; st < tl.spt; ++st) {
-          const u32 j0 = s0 + st * 256u + lane * 4u;
-#pragma unroll
-          for (u32 i = 0; i < 4; ++i) {
-            const u32 j = j0 + i;
-            if (j < K && in_doubled(j, K, L1, R - 1) != NONE32) {
-              const u64 act = tl.H[j] + lz;
-              m_cov = act > m_cov ? act : m_cov;
+              if (in_doubled(j, K, L1, R - 1) != NONE32) m_cov = act > m_cov ? act : m_cov;
             }
           }
         }
         m_cov = wave_max(m_cov);
+        if (bring) {
+          m_all = wave_max(m_all);
+          if (lane == 0) { hmax[c] = m_all; hmat[c] = to; hpend[c] = 0u; }
+        }
         if (lane == 0) atomicMax((unsigned long long*)&S->hq, (unsigned long long)m_cov);
       }
     }
@@ -1028,8 +1039,8 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
       const u32 f0 = (u32)fl[0] & 0xffu;
       if (tid == 0) S->hq = 0;
       __syncthreads();
-      if (f0 & F_PALL) atomicMax((unsigned long long*)&S->hq, (unsigned long long)hmax[tid]);
-      else if (f0 & F_PCUT) jobs[atomicAdd(&S->njobs, 1u)] = ((u64)J_HQ << 16) | tid;
+      if ((f0 & F_PCUT) || ((f0 & F_PALL) && hpend[tid])) jobs[atomicAdd(&S->njobs, 1u)] = ((u64)J_HQ << 16) | tid;
+      else if (f0 & F_PALL) atomicMax((unsigned long long*)&S->hq, (unsigned long long)hmax[tid]);   // (exact: nothing is missing there)
       __syncthreads();
       run_jobs();
       __syncthreads();
@@ -1063,6 +1074,7 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
           mg.size_bytes = ms; mg.t_out_ns = M.tau_o; mg.t_in_ns = M.tau_i; mg.benefit_lo = M.lo; mg.benefit_hi = M.hi;
           a.records[nm + lane] = mg;
           a.rec_ab[nm + lane] = make_uint2(ma, mb);
+          a.rec_h[nm + lane] = M.dest == G10_HOST ? make_uint4(mL1, mR, (u32)ms, (u32)(ms >> 32)) : make_uint4(mL1, mR, 0u, 0u);
           atomicOr(&S->touched, (1u << (A_FO + M.dest)) | (1u << (A_FI + M.dest)));
         }
       }
@@ -1106,8 +1118,8 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
     if (!room) { __syncthreads(); break; }
     if (tid < nch) {
       const u32 c = tid;
-      u64 lzP = 0, lzH = 0;
-      u32 cutP = 0, allP = 0, cutH = 0, allH = 0, fo[2] = {0, 0}, fi[2] = {0, 0};
+      u64 lzP = 0, lzH = 0, cutHs = 0;
+      u32 cutP = 0, allP = 0, cutH = 0, fo[2] = {0, 0}, fi[2] = {0, 0};
       for (u32 i = 0; i < m; ++i) {
         const u32 f = (u32)(fl[i >> 3] >> (8 * (i & 7u))) & 0xffu;
         if (!f) continue;
@@ -1115,8 +1127,8 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
         const u32 md = S->mem[i].dest;
         if (f & F_AALL) { lzP += ms; allP |= 1u << i; }
         if (f & F_ACUT) cutP |= 1u << i;
-        if (f & F_PALL) { lzH += ms; allH |= 1u << i; }
-        if (f & F_PCUT) cutH |= 1u << i;
+        if (f & F_PALL) lzH += ms;
+        if (f & F_PCUT) { cutH |= 1u << i; cutHs += ms; }
         if (f & F_E) fo[md] |= 1u << i;
         if (f & F_W) fi[md] |= 1u << i;
       }
@@ -1126,10 +1138,11 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
         if (mo != NONE64 && mo - cap <= lzP) jobP = true;       // a slot drops under the capacity
         if (!jobP) { lazyP[c] += lzP; if (mo != NONE64) minOver[c] = mo - lzP; }
       }
-      if (lzH && !cutH) { lazyH[c] += lzH; hmax[c] += lzH; }
+      // host occupancy: whole covers into the lazy add; cuts only into the chunk's bound, the slots follow on demand (J_HQ)
+      if (lzH | cutHs) { lazyH[c] += lzH; hmax[c] += lzH + cutHs; }
+      if (cutH) hpend[c] = 1u;
       // (a job adds the sizes of the migrations that cover its chunk whole itself)
       if (jobP) jobs[atomicAdd(&S->njobs, 1u)] = ((u64)allP << 40) | ((u64)cutP << 24) | ((u64)J_P << 16) | c;
-      if (cutH) jobs[atomicAdd(&S->njobs, 1u)] = ((u64)allH << 40) | ((u64)cutH << 24) | ((u64)J_H << 16) | c;
       if (fo[0]) jobs[atomicAdd(&S->njobs, 1u)] = ((u64)fo[0] << 24) | ((u64)J_FO0 << 16) | c;
       if (fo[1]) jobs[atomicAdd(&S->njobs, 1u)] = ((u64)fo[1] << 24) | ((u64)J_FO1 << 16) | c;
       if (fi[0]) jobs[atomicAdd(&S->njobs, 1u)] = ((u64)fi[0] << 24) | ((u64)J_FI0 << 16) | c;
@@ -1171,7 +1184,7 @@ __global__ __launch_bounds__(LB) void k_loop(const LoopArgs* __restrict__ plans)
 
   // ---- state out ---------------------------------------------------------------------
   for (u32 i = tid; i < N_ARR * nch; i += LB) a.g_tot[i] = tot[i];
-  for (u32 i = tid; i < nch; i += LB) { a.g_lazyP[i] = lazyP[i]; a.g_minOver[i] = minOver[i]; a.g_lazyH[i] = lazyH[i]; a.g_hmax[i] = hmax[i]; }
+  for (u32 i = tid; i < nch; i += LB) { a.g_lazyP[i] = lazyP[i]; a.g_minOver[i] = minOver[i]; a.g_lazyH[i] = lazyH[i]; a.g_hmax[i] = hmax[i]; a.g_hmat[i] = hmat[i]; a.g_hpend[i] = hpend[i]; }
   for (u32 i = tid; i < nt; i += LB) a.g_keys[i] = keys[i];
   for (u32 i = tid; i < N_ARR * nb1; i += LB) a.g_base[i] = base[i];
   if (tid == 0) {
@@ -1265,7 +1278,7 @@ size_t loop_lds_bytes(u32 nch, u32 nt) {
   size_t b = 0;
   b += ((size_t)N_ARR * (nch + 1) + (size_t)N_ARR * nch + (size_t)4 * nch + ns + (size_t)4 * LW + (size_t)8 * nch + 8) * 8;
   b += sizeof(Shared);
-  b += ((size_t)nt + ns) * 4 + (size_t)nt * 4;
+  b += ((size_t)nt + ns + 2 * (size_t)nch) * 4 + (size_t)nt * 4;
   return (b + 15) & ~(size_t)15;
 }
 

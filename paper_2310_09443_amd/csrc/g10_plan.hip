@@ -146,7 +146,8 @@ __global__ __launch_bounds__(G10_BLOCK) void k_pack(const uint4* __restrict__ pe
 __global__ __launch_bounds__(G10_BLOCK) void k_init_timelines(Timelines tl, const u64* __restrict__ pressure0, const Ctl* ctl,
                                                              u64* __restrict__ g_tot, u64* __restrict__ g_lazyP,
                                                              u64* __restrict__ g_minOver, u64* __restrict__ g_lazyH,
-                                                             u64* __restrict__ g_hmax) {
+                                                             u64* __restrict__ g_hmax, u32* __restrict__ g_hmat,
+                                                             u32* __restrict__ g_hpend) {
   __shared__ u64 tmp[2 * G10_WAVES];
   __shared__ u64 mins[G10_WAVES];
   const u64 cap = ctl->gpu_cap;
@@ -186,7 +187,7 @@ __global__ __launch_bounds__(G10_BLOCK) void k_init_timelines(Timelines tl, cons
     for (u32 w = 1; w < G10_WAVES; ++w) m = mins[w] < m ? mins[w] : m;
     g_tot[(u64)A_OT * tl.nch + chunk] = total[1];
     for (u32 c = 0; c < 4; ++c) g_tot[(u64)(A_FO + c) * tl.nch + chunk] = total[0];
-    g_lazyP[chunk] = 0; g_minOver[chunk] = m; g_lazyH[chunk] = 0; g_hmax[chunk] = 0;
+    g_lazyP[chunk] = 0; g_minOver[chunk] = m; g_lazyH[chunk] = 0; g_hmax[chunk] = 0; g_hmat[chunk] = 0; g_hpend[chunk] = 0;
   }
 }
 
@@ -480,6 +481,8 @@ static void work_layout(PlanWork* w, Arena& ar) {
   ar.take(&w->ctl, 1);
   ar.take(&w->records, C);
   ar.take(&w->rec_ab, C);
+  ar.take(&w->rec_h, C);
+  ar.take(&w->g_hmat, w->nch); ar.take(&w->g_hpend, w->nch);
   ar.take(&w->dropped, C);
   ar.take(&w->pf_keys, C); ar.take(&w->pf_keys_alt, C);
   ar.take(&w->pf_order, C); ar.take(&w->pf_order_alt, C);
@@ -695,7 +698,7 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     G10_HIP(hipMemsetAsync(w->peak_after, 0, 8, q));
     G10_HIP(hipMemsetAsync(w->wide, 0, 64, q));           // (no pass left open)
     hipLaunchKernelGGL(k_init_timelines, dim3(w->nch), dim3(G10_BLOCK), 0, q, tl, (const u64*)(h->pressure_buf + 1),
-                       (const Ctl*)w->ctl, w->g_tot, w->g_lazyP, w->g_minOver, w->g_lazyH, w->g_hmax);
+                       (const Ctl*)w->ctl, w->g_tot, w->g_lazyP, w->g_minOver, w->g_lazyH, w->g_hmax, w->g_hmat, w->g_hpend);
     hipLaunchKernelGGL(k_level1_init, dim3(1), dim3(LB), 0, q, (const u64*)w->g_tot, w->nch, w->base0, w->ctl);
     hipLaunchKernelGGL(k_ot_full, dim3(K / G10_BLOCK + 1), dim3(G10_BLOCK), 0, q, w->otc, (const u64*)w->base0, K, w->nch, w->shift_ch);
     G10_HIP(hipGetLastError());
@@ -909,6 +912,7 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
       la.g_tot = w->g_tot; la.g_lazyP = w->g_lazyP; la.g_minOver = w->g_minOver; la.g_lazyH = w->g_lazyH; la.g_hmax = w->g_hmax;
       la.g_base = w->g_base;
       la.g_keys = w->tkeys; la.ctl = w->ctl; la.records = w->records; la.rec_ab = w->rec_ab; la.dropped = w->dropped;
+      la.rec_h = w->rec_h; la.g_hmat = w->g_hmat; la.g_hpend = w->g_hpend;
       la.cd = cands_of(x, x.cur); la.n_pad = x.n_pad; la.nt = x.nt; la.tshift = x.tsh;
       la.pass_budget = x.n > RETILE_MIN_CANDS && count == 1 ? RETILE_PASSES : PASS_BUDGET;
       la.tick_budget = count > 1 ? BATCH_LAUNCH_TICKS : 0;

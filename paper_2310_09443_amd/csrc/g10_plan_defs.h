@@ -11,7 +11,7 @@
 namespace g10 {
 
 enum { A_OT = 0, A_FO = 1, A_FI = 3, N_ARR = 5, PX = 8 };
-enum { J_P = 0, J_H = 1, J_FO0 = 2, J_FO1 = 3, J_FI0 = 4, J_FI1 = 5, J_HQ = 6, J_CLIP = 7 };   // kinds of chunk jobs
+enum { J_P = 0, J_FO0 = 2, J_FO1 = 3, J_FI0 = 4, J_FI1 = 5, J_HQ = 6, J_CLIP = 7 };   // kinds of chunk jobs
 
 constexpr u32 LB = 512;                // threads of the loop workgroup (at least NCH_MAX)
 constexpr u32 LW = LB / G10_WAVE;      // its wavefronts
@@ -266,10 +266,12 @@ struct LoopArgs {
   u32 n_pad, nt, tshift;      // tile = UNIT << tshift candidates
   Timelines tl;
   u64 *g_tot, *g_lazyP, *g_minOver, *g_lazyH, *g_hmax, *g_base;
+  u32 *g_hmat, *g_hpend;      // host occupancy is brought up to date chunk by chunk, on demand: records applied so far; some may be missing
   u32* g_keys;
   Ctl* ctl;
   g10_migration* records;
   uint2* rec_ab;              // absent window [a, b] of every migration in doubled coordinates
+  uint4* rec_h;               // {L + 1, R, size} of every migration to host in doubled coordinates (size 0: to flash)
   g10_dropped* dropped;
   u32 pass_budget;            // the launch ends after this many passes,
   u64 tick_budget;            // or (if not 0) after this many ticks of the 100 MHz wall clock,
@@ -364,6 +366,8 @@ struct PlanWork {
   g10::Ctl* ctl = nullptr;
   g10_migration* records = nullptr;
   uint2* rec_ab = nullptr;
+  uint4* rec_h = nullptr;      // {L + 1, R, size} of every migration to host (size 0: to flash)
+  u32 *g_hmat = nullptr, *g_hpend = nullptr;   // per chunk: records applied to the host occupancy; some may be missing
   g10_dropped* dropped = nullptr;
   // smart prefetching
   u64 *pf_keys = nullptr, *pf_keys_alt = nullptr, *pf_pressure = nullptr, *pf_stats = nullptr;
