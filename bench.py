@@ -32,9 +32,9 @@ BYTES_PER_CAND_MOVED = 20      # what k_score_full itself streams per candidate:
 # HBM traffic of the loop kernel on config 5 from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, scaled by what the
 # same counters read for a 256 MiB copy): profiles/loop_stress_hbm_counters.md has the commands and the sums.  The
 # figures hold for the kernel they were taken on: reported only while the kernel's sources hash to what they did then.
-LOOP_TRAFFIC = {"sha256": {"g10_loop.hip": "d238a32d251669219b9ab3f03de13d8d9aca2d482d726a7b508ea7a7afbc0978",
-                           "g10_plan_defs.h": "b6d87b0b9979a35ed8dcd7288be0c97e0dbfe86f23e6dfd14b3d60b4e51cbea8"},
-                "workload": "config 5", "fetch_bytes_per_plan": 71.4e6, "write_bytes_per_plan": 93.9e6, "launches_per_plan": 11}
+LOOP_TRAFFIC = {"sha256": {"g10_loop.hip": "3c6f01f2fb00ae43315726b03d712aece9ec43d892a9cca014e32bd24dc844ee",
+                           "g10_plan_defs.h": "29da48963f0aaf9bd88314d48c4f2f465f7d1896872937d584d8bbcd3c7fc7d0"},
+                "workload": "config 5", "fetch_bytes_per_plan": 57.8e6, "write_bytes_per_plan": 81.7e6, "launches_per_plan": 11}
 
 
 def loop_traffic_per_launch(config):
