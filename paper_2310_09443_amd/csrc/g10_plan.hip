@@ -295,7 +295,7 @@ __device__ __forceinline__ void tile_gather_at(const u32 r, const u32* __restric
       const uint2 e = src.ce[p];
       dst.ce[r] = e;
       if (e.y & 1u) dst.cv[r] = src.cv[p];
-    }
+    } else if (dst.ce) dst.ce[r] = make_uint2(0u, 0u);     // (gathered from another plan's fresh list: no value yet)
     k = bound_of_sort_key(sk);
   } else {                                       // padding of the last tile: no valid window
     dst.A[r] = make_uint4(0u, 0u, 1u, 0u);
@@ -543,6 +543,9 @@ struct Inst {
   u32 lead = 0;                // the plan of the batch whose candidate windows this one reads (itself, or an
                                // earlier plan with the same bandwidths and durations: the windows depend on nothing else)
   bool fw_done = false;        // (of such a plan) the copy of the windows for the first scoring pass is written or on its way
+  Cands pack_src = {};         // (of such a plan) the candidates in the order of their start, as the first plan of the group packed
+                               // them: the other plans of the group gather their first order from there
+  bool own_pack = true;        // this plan's first order is gathered from its own packed list
   bool results_sent = false;   // the plan is finished and its results are on their way to the host
 };
 
@@ -775,7 +778,8 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     sj.keys = w->keys; sj.alt = w->keys_alt; sj.vals = w->sv; sj.valt = w->sv_alt; sj.hist = w->hist;
     sj.n = x.n; sj.nb = radix_blocks(x.n);
     TileJob& tj = htj[at];
-    tj.src = cands_of(x, x.cur); tj.dst = cands_of(x, x.cur ^ 1);
+    tj.src = x.own_pack ? cands_of(x, x.cur) : I[x.lead].pack_src; tj.dst = cands_of(x, x.cur ^ 1);
+    x.own_pack = true;                                    // (every later order comes from the plan's own list)
     tj.n = x.n; tj.n_pad = x.n_pad; tj.tile_shift = 8 + x.tsh; tj.rank = x.p->rank;
     tj.sortkeys = w->keys; tj.tkeys = w->tkeys;
     tj.sorted = SCORE_SORT_PASSES & 1u ? w->keys_alt : w->keys; tj.from = SCORE_SORT_PASSES & 1u ? w->sv_alt : w->sv;
@@ -816,15 +820,19 @@ int plan_batch_run(g10_plan_s* h, const g10_params* params, u32 count, g10_resul
     // of such a group that gets here writes the copy
     PlanWork* const lw = I[x.lead].w;
     const bool writes_fw = !I[x.lead].fw_done;
-    if (x.n) {
+    if (x.n && (writes_fw || count == 1)) {
+      // (the packed list depends on the windows only: in a batch the first plan of a group packs it, the
+      // others gather their first order straight from that list, which nobody writes before they have)
       hipLaunchKernelGGL(k_pack, dim3(gC), dim3(G10_BLOCK), 0, stream_of(i), (const uint4*)h->per_by_start, (const u64*)h->per_size, (const uint4*)lw->win,
                          (const u32*)lw->keep, C, cands_of(x, x.cur), writes_fw ? lw->fw : (uint4*)nullptr, writes_fw ? lw->fs : (u64*)nullptr, packed ? 1u : 0u);
       G10_HIP(hipGetLastError());
       if (writes_fw) {
         I[x.lead].fw_done = true;
+        I[x.lead].pack_src = x.w->cd[x.cur];
+        I[x.lead].pack_src.cv = nullptr; I[x.lead].pack_src.ce = nullptr;
         if (count > 1) G10_HIP(hipEventRecord(lw->ev[2], stream_of(i)));
       }
-    }
+    } else if (x.n) x.own_pack = false;
     if (count == 1) G10_TRY(retile(x, true, s));
     else {
       // a batch: every plan's scoring pass on its stream, then the sorts and the tiles of all plans in the same launches
